@@ -1,0 +1,172 @@
+"""float64 CPU oracle for causal polynomial-sketch attention (ctypes over psf_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Importers: tests/, __graft_entry__.smoke() and the
+cpu_baseline leg of bench.py.  The GPU library never imports this package and this
+package never imports the GPU library; they share no arithmetic.
+
+All arrays are numpy float64, row-major.  A "unit" is one (batch, head) slice.
+Sketch matrices travel as one flat vector per set: the p/2 matrices of shape d x r
+first, then the p/2 - 2 matrices of shape r x r, each list in the order Algorithm 1
+reaches its sampling line (left subtree, right subtree, node).
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+FEAT_SKETCH, FEAT_EXACT = 0, 1
+LOCAL_EXACT, LOCAL_SKETCH = 0, 1
+
+_lib = None
+_dp = ctypes.POINTER(ctypes.c_double)
+_lp = ctypes.POINTER(ctypes.c_long)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if (not os.path.exists(path)
+                or os.path.getmtime(path) < os.path.getmtime(_build.SRC)):
+            _build.build()
+        L = ctypes.CDLL(path)
+        L.psf_oracle_num_g_first.restype = ctypes.c_long
+        L.psf_oracle_num_g_first.argtypes = [ctypes.c_long]
+        L.psf_oracle_num_g_inner.restype = ctypes.c_long
+        L.psf_oracle_num_g_inner.argtypes = [ctypes.c_long]
+        L.psf_oracle_sketch.restype = ctypes.c_int
+        L.psf_oracle_sketch.argtypes = [_dp] + [ctypes.c_long] * 4 + [_dp, _dp]
+        L.psf_oracle_self_tensor.restype = None
+        L.psf_oracle_self_tensor.argtypes = [_dp, ctypes.c_long, ctypes.c_long, _dp]
+        L.psf_oracle_power_tensor.restype = ctypes.c_int
+        L.psf_oracle_power_tensor.argtypes = [_dp] + [ctypes.c_long] * 3 + [_dp]
+        L.psf_oracle_attn_def.restype = ctypes.c_int
+        L.psf_oracle_attn_def.argtypes = ([_dp] * 5 + [ctypes.c_long] * 6 + [ctypes.c_int] * 3
+                                          + [_lp, ctypes.c_long, _dp, _dp])
+        L.psf_oracle_attn_block.restype = ctypes.c_int
+        L.psf_oracle_attn_block.argtypes = ([_dp] * 5 + [ctypes.c_long] * 6
+                                            + [ctypes.c_int, _dp])
+        L.psf_oracle_attn_def_batch.restype = ctypes.c_int
+        L.psf_oracle_attn_def_batch.argtypes = ([_dp] * 4 + [ctypes.c_long] * 9
+                                                + [ctypes.c_int] * 2
+                                                + [_lp, ctypes.c_long, _dp, ctypes.c_int])
+        _lib = L
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _ptr(a):
+    return a.ctypes.data_as(_dp) if a is not None else None
+
+
+def g_len(d, r, p):
+    L = lib()
+    return L.psf_oracle_num_g_first(p) * d * r + L.psf_oracle_num_g_inner(p) * r * r
+
+
+def sketch(X, G, r, p):
+    """m(x) = PolySketchWithNegativity(x, r, p/2) for every row of X (Algorithm 1)."""
+    X = _f64(X)
+    k, d = X.shape
+    G = _f64(G).reshape(-1) if p > 2 else np.zeros(1)
+    if p > 2 and G.size != g_len(d, r, p):
+        raise ValueError("G has %d entries, expected %d" % (G.size, g_len(d, r, p)))
+    M = np.empty((k, d if p == 2 else r))
+    rc = lib().psf_oracle_sketch(_ptr(X), k, d, r, p, _ptr(G), _ptr(M))
+    if rc:
+        raise ValueError("psf_oracle_sketch failed: %d" % rc)
+    return M
+
+
+def self_tensor(M):
+    """phi'(x) = m (x) m, index a*r + b (Algorithm 1, PolySketchNonNegative)."""
+    M = _f64(M)
+    k, m = M.shape
+    Phi = np.empty((k, m * m))
+    lib().psf_oracle_self_tensor(_ptr(M), k, m, _ptr(Phi))
+    return Phi
+
+
+def power_tensor(X, p):
+    """x^{(x)p} (Section 2.2), d^p columns."""
+    X = _f64(X)
+    k, d = X.shape
+    Phi = np.empty((k, d ** p))
+    rc = lib().psf_oracle_power_tensor(_ptr(X), k, d, p, _ptr(Phi))
+    if rc:
+        raise MemoryError("psf_oracle_power_tensor failed: %d" % rc)
+    return Phi
+
+
+def attn_def(Q, K, V, G, p, r, b, feat=FEAT_SKETCH, local=LOCAL_EXACT, rows=None,
+             explicit_features=False, return_weights=False):
+    """Rows of causal Polysketch attention straight from its definition (Section 3,
+    with Section 3.2's exact in-block weights when local == LOCAL_EXACT)."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    n, d = Q.shape
+    dv = V.shape[1]
+    MQ = MK = None
+    mcols = d if p == 2 else r
+    if feat == FEAT_SKETCH:
+        MQ, MK = sketch(Q, G, r, p), sketch(K, G, r, p)
+    rows_a = None if rows is None else np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    nrows = n if rows_a is None else rows_a.size
+    O = np.empty((nrows, dv))
+    W = np.empty((nrows, n)) if return_weights else None
+    rc = lib().psf_oracle_attn_def(
+        _ptr(Q), _ptr(K), _ptr(V), _ptr(MQ), _ptr(MK), n, d, dv, mcols, p, b,
+        feat, local, int(bool(explicit_features)),
+        rows_a.ctypes.data_as(_lp) if rows_a is not None else None, nrows, _ptr(O), _ptr(W))
+    if rc:
+        raise ValueError("psf_oracle_attn_def failed: %d" % rc)
+    return (O, W) if return_weights else O
+
+
+def attn_block(Q, K, V, G, p, r, b, feat=FEAT_SKETCH, local=LOCAL_EXACT):
+    """The paper's block lower-triangular algorithm with explicit features
+    (Section 3.1; Section 3.2 for the in-block term when local == LOCAL_EXACT)."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    n, d = Q.shape
+    dv = V.shape[1]
+    if feat == FEAT_EXACT:
+        PhiQ, PhiK = power_tensor(Q, p), power_tensor(K, p)
+    else:
+        PhiQ, PhiK = self_tensor(sketch(Q, G, r, p)), self_tensor(sketch(K, G, r, p))
+    F = PhiQ.shape[1]
+    O = np.empty((n, dv))
+    local_exact = int(local == LOCAL_EXACT and feat == FEAT_SKETCH)
+    rc = lib().psf_oracle_attn_block(_ptr(Q), _ptr(K), _ptr(V), _ptr(PhiQ), _ptr(PhiK),
+                                     n, d, dv, F, p, b, local_exact, _ptr(O))
+    if rc:
+        raise ValueError("psf_oracle_attn_block failed: %d" % rc)
+    return O
+
+
+def attn_def_batch(Q, K, V, G, p, r, b, feat=FEAT_SKETCH, local=LOCAL_EXACT, rows=None,
+                   max_threads=0):
+    """attn_def over [batch, heads, n, *] inputs; G is [1 or heads, g_len].
+    Returns (O [batch, heads, nrows, dv], threads_used).  OpenMP over units only."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    B, H, n, d = Q.shape
+    dv = V.shape[-1]
+    if feat == FEAT_SKETCH and p > 2:
+        G = _f64(G).reshape(-1, g_len(d, r, p))
+        if G.shape[0] not in (1, H):
+            raise ValueError("G must have 1 or `heads` sets")
+    else:
+        G = np.zeros((1, 1))
+    rows_a = None if rows is None else np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    nrows = n if rows_a is None else rows_a.size
+    O = np.empty((B, H, nrows, dv))
+    rc = lib().psf_oracle_attn_def_batch(
+        _ptr(Q), _ptr(K), _ptr(V), _ptr(G), G.shape[0], H, B * H, n, d, dv, p, r, b,
+        feat, local, rows_a.ctypes.data_as(_lp) if rows_a is not None else None, nrows,
+        _ptr(O), int(max_threads))
+    if rc < 0:
+        raise ValueError("psf_oracle_attn_def_batch failed: %d" % rc)
+    return O, rc

@@ -1,0 +1,320 @@
+/*
+ * psf_oracle.c -- float64 CPU oracle for causal polynomial-sketch attention.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the
+ * GPU library is compared against.  It shares no code, header, table or
+ * helper with the HIP path and must never be called from the product path;
+ * only tests, the smoke check and the bench's cpu_baseline leg use it.
+ *
+ * Everything is float64, row-major, plain loops (no BLAS, no blocking beyond
+ * what the paper's block algorithm itself states).  One call handles one
+ * (batch, head) unit; the *_batch drivers at the bottom only loop over units
+ * (OpenMP over units, nothing inside a unit is parallel).
+ *
+ * What each function follows in the paper (PolySketchFormer, arXiv 2310.01655):
+ *   oracle_pswn              Algorithm 1, PolySketchWithNegativity (literal recursion)
+ *   psf_oracle_sketch        Algorithm 1, the M = PolySketchWithNegativity(A, r, p/2)
+ *                            step of PolySketchNonNegative
+ *   psf_oracle_self_tensor   Algorithm 1, M^{(x)2}; Kronecker index order of Section 1.2
+ *   psf_oracle_power_tensor  Section 2.2, exact feature map x^{(x)p}
+ *   psf_oracle_attn_def      Section 3 (causal Polysketch attention, 1 + sum in the
+ *                            denominator), Section 3.2 (exact weights inside a block),
+ *                            Section 2.2 (<x,y>^p = <x^{(x)p}, y^{(x)p}>)
+ *   psf_oracle_attn_block    Section 3.1 block lower-triangular multiplication
+ *                            (H_l, Z_l, P_l, row = p + a_i^T Z_l), Section 3.2 for P_l
+ *
+ * Pins (tests/test_oracle_*.py): brute-force masked polynomial attention written
+ * in numpy, block-size invariance, definition == block algorithm, p = 2 base
+ * case, closed forms for row 0 and V == 1, Monte-Carlo moments of the sketch,
+ * non-negativity and the convex-hull bound.  No function here is unpinned.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { FEAT_SKETCH = 0, FEAT_EXACT = 1 };
+enum { LOCAL_EXACT = 0, LOCAL_SKETCH = 1 };
+
+static int is_pow2(long v) { return v > 0 && (v & (v - 1)) == 0; }
+
+static double ipow(double x, long p)
+{
+    double y = 1.0;
+    for (long e = 0; e < p; ++e) y *= x;
+    return y;
+}
+
+static double dot(const double *x, const double *y, long m)
+{
+    double s = 0.0;
+    for (long c = 0; c < m; ++c) s += x[c] * y[c];
+    return s;
+}
+
+/* ---- Algorithm 1: PolySketchWithNegativity(A in R^{k x m}, r, deg) ----------------
+ * Returns a freshly malloc'ed k x cols matrix, cols = m when deg == 1, else r.
+ * The Gaussian matrices are not sampled here: they are inputs.  Those with m rows
+ * are taken from g_first, those with r rows from g_inner, each list consumed in the
+ * order the recursion reaches its "sample G1, G2" line: left subtree, right subtree,
+ * then the node itself. */
+static double *oracle_pswn(const double *A, long k, long m, long r, long deg,
+                           const double **g_first, const double **g_inner)
+{
+    if (deg == 1) {
+        double *out = (double *)malloc(sizeof(double) * (size_t)k * (size_t)m);
+        if (out) memcpy(out, A, sizeof(double) * (size_t)k * (size_t)m);
+        return out;
+    }
+    double *M1 = oracle_pswn(A, k, m, r, deg / 2, g_first, g_inner);
+    double *M2 = oracle_pswn(A, k, m, r, deg / 2, g_first, g_inner);
+    long rows = (deg / 2 == 1) ? m : r;          /* columns of M1 and M2 */
+    const double *G1, *G2;
+    if (deg / 2 == 1) {             /* M1 = M2 = A: matrices with m rows */
+        G1 = *g_first;  G2 = G1 + rows * r;  *g_first = G2 + rows * r;
+    } else {
+        G1 = *g_inner;  G2 = G1 + rows * r;  *g_inner = G2 + rows * r;
+    }
+    double *out = (double *)malloc(sizeof(double) * (size_t)k * (size_t)r);
+    if (!M1 || !M2 || !out) { free(M1); free(M2); free(out); return NULL; }
+    double scale = sqrt(1.0 / (double)r);
+    for (long i = 0; i < k; ++i) {
+        for (long c = 0; c < r; ++c) {
+            double u = 0.0, v = 0.0;
+            for (long e = 0; e < rows; ++e) {
+                u += M1[i * rows + e] * G1[e * r + c];
+                v += M2[i * rows + e] * G2[e * r + c];
+            }
+            out[i * r + c] = scale * (u * v);
+        }
+    }
+    free(M1);
+    free(M2);
+    return out;
+}
+
+/* Number of Gaussian matrices the degree-p feature map uses (Theorem 1.1, item 3). */
+long psf_oracle_num_g_first(long p) { return p / 2 >= 2 ? p / 2 : 0; }
+long psf_oracle_num_g_inner(long p) { return p / 2 >= 4 ? p / 2 - 2 : 0; }
+
+/* M = PolySketchWithNegativity(X, r, p/2); X is k x d.  G holds the d x r matrices
+ * first, then the r x r ones.  M_out is k x r, or k x d when p == 2 (base case). */
+int psf_oracle_sketch(const double *X, long k, long d, long r, long p,
+                      const double *G, double *M_out)
+{
+    if (!is_pow2(p) || p < 2 || k < 0 || d <= 0 || r <= 0) return 1;
+    const double *gf = G;
+    const double *gi = G ? G + psf_oracle_num_g_first(p) * d * r : NULL;
+    double *M = oracle_pswn(X, k, d, r, p / 2, &gf, &gi);
+    if (!M) return 2;
+    long cols = (p == 2) ? d : r;
+    memcpy(M_out, M, sizeof(double) * (size_t)k * (size_t)cols);
+    free(M);
+    return 0;
+}
+
+/* Phi[i, a*m + b] = M[i,a] * M[i,b]  (a (x) b lists a_1 b_1, a_1 b_2, ...). */
+void psf_oracle_self_tensor(const double *M, long k, long m, double *Phi)
+{
+    for (long i = 0; i < k; ++i)
+        for (long a = 0; a < m; ++a)
+            for (long b = 0; b < m; ++b)
+                Phi[(i * m + a) * m + b] = M[i * m + a] * M[i * m + b];
+}
+
+/* Phi = X^{(x)p}: x^{(x)p} = x (x) x^{(x)(p-1)}, x^{(x)1} = x.  Phi is k x d^p. */
+int psf_oracle_power_tensor(const double *X, long k, long d, long p, double *Phi)
+{
+    long F = 1;
+    for (long e = 0; e < p; ++e) F *= d;
+    double *prev = (double *)malloc(sizeof(double) * (size_t)F);
+    if (!prev) return 2;
+    for (long i = 0; i < k; ++i) {
+        const double *x = X + i * d;
+        double *out = Phi + i * F;
+        long len = d;
+        memcpy(out, x, sizeof(double) * (size_t)d);
+        for (long e = 2; e <= p; ++e) {
+            memcpy(prev, out, sizeof(double) * (size_t)len);
+            for (long a = 0; a < d; ++a)
+                for (long t = 0; t < len; ++t) out[a * len + t] = x[a] * prev[t];
+            len *= d;
+        }
+    }
+    free(prev);
+    return 0;
+}
+
+/* ---- the definition: rows of causal Polysketch attention -------------------------
+ * For the listed rows i (0-based; rows == NULL means all n rows):
+ *   o_i = sum_{j<=i} w_ij v_j / (1 + sum_{j<=i} w_ij)
+ *   w_ij = <q_i,k_j>^p                    if feat == EXACT, or (local == EXACT and
+ *                                         i, j fall in the same block of b rows)
+ *        = <phi'(q_i), phi'(k_j)>         otherwise, phi'(x) = m(x) (x) m(x)
+ * MQ, MK are the n x mcols sketches m(q_i), m(k_j) (unused when feat == EXACT).
+ * explicit_features != 0 evaluates <phi',phi'> as the r^2-term sum; otherwise as
+ * <m,m>^2, which Section 3.1 states is the same number.  W_out (nrows x n, may be
+ * NULL) receives the weights, zero above the diagonal. */
+int psf_oracle_attn_def(const double *Q, const double *K, const double *V,
+                        const double *MQ, const double *MK,
+                        long n, long d, long dv, long mcols, long p, long b,
+                        int feat, int local, int explicit_features,
+                        const long *rows, long nrows, double *O_out, double *W_out)
+{
+    if (n <= 0 || b <= 0 || n % b != 0) return 1;
+    if (!rows) nrows = n;
+    double *acc = (double *)malloc(sizeof(double) * (size_t)dv);
+    if (!acc) return 2;
+    for (long t = 0; t < nrows; ++t) {
+        long i = rows ? rows[t] : t;
+        if (i < 0 || i >= n) { free(acc); return 1; }
+        double den = 1.0;
+        for (long c = 0; c < dv; ++c) acc[c] = 0.0;
+        if (W_out) for (long j = 0; j < n; ++j) W_out[t * n + j] = 0.0;
+        for (long j = 0; j <= i; ++j) {
+            double w;
+            int same_block = (i / b) == (j / b);
+            if (feat == FEAT_EXACT || (local == LOCAL_EXACT && same_block)) {
+                w = ipow(dot(Q + i * d, K + j * d, d), p);
+            } else if (explicit_features) {
+                w = 0.0;
+                for (long a = 0; a < mcols; ++a)
+                    for (long e = 0; e < mcols; ++e)
+                        w += (MQ[i * mcols + a] * MQ[i * mcols + e]) *
+                             (MK[j * mcols + a] * MK[j * mcols + e]);
+            } else {
+                double s = dot(MQ + i * mcols, MK + j * mcols, mcols);
+                w = s * s;
+            }
+            den += w;
+            for (long c = 0; c < dv; ++c) acc[c] += w * V[j * dv + c];
+            if (W_out) W_out[t * n + j] = w;
+        }
+        for (long c = 0; c < dv; ++c) O_out[t * dv + c] = acc[c] / den;
+    }
+    free(acc);
+    return 0;
+}
+
+/* ---- the paper's block algorithm, step by step -----------------------------------
+ * A = PhiQ, B = PhiK (n x F explicit features), C = [V | 1] (n x (dv+1)).
+ *   H_l = sum_{i in B_l} b_i c_i^T          Z_l = sum_{j<l} H_j   (sequential)
+ *   P_l = lt(A_l B_l^T) C_l                 or lt((Q_l K_l^T)^p) C_l   (local exact)
+ *   row i of lt(A B^T) C = row i' of P_l + a_i^T Z_l
+ * then the last column is the denominator: o_i = row[0:dv] / (1 + row[dv]). */
+int psf_oracle_attn_block(const double *Q, const double *K, const double *V,
+                          const double *PhiQ, const double *PhiK,
+                          long n, long d, long dv, long F, long p, long b,
+                          int local_exact, double *O_out)
+{
+    if (n <= 0 || b <= 0 || n % b != 0) return 1;
+    long t = n / b, kc = dv + 1;
+    double *C = (double *)malloc(sizeof(double) * (size_t)n * (size_t)kc);
+    double *Z = (double *)calloc((size_t)F * (size_t)kc, sizeof(double));
+    double *H = (double *)malloc(sizeof(double) * (size_t)F * (size_t)kc);
+    double *P = (double *)malloc(sizeof(double) * (size_t)b * (size_t)kc);
+    double *S = (double *)malloc(sizeof(double) * (size_t)b * (size_t)b);
+    if (!C || !Z || !H || !P || !S) { free(C); free(Z); free(H); free(P); free(S); return 2; }
+    for (long i = 0; i < n; ++i) {
+        for (long c = 0; c < dv; ++c) C[i * kc + c] = V[i * dv + c];
+        C[i * kc + dv] = 1.0;
+    }
+    for (long l = 0; l < t; ++l) {
+        long r0 = l * b;
+        /* S = lt(A_l B_l^T), or lt((Q_l K_l^T)^p) when exact weights are used locally */
+        for (long x = 0; x < b; ++x)
+            for (long y = 0; y < b; ++y) {
+                double s = 0.0;
+                if (y <= x) {
+                    if (local_exact) s = ipow(dot(Q + (r0 + x) * d, K + (r0 + y) * d, d), p);
+                    else s = dot(PhiQ + (r0 + x) * F, PhiK + (r0 + y) * F, F);
+                }
+                S[x * b + y] = s;
+            }
+        /* P_l = S C_l */
+        for (long x = 0; x < b; ++x)
+            for (long c = 0; c < kc; ++c) {
+                double s = 0.0;
+                for (long y = 0; y < b; ++y) s += S[x * b + y] * C[(r0 + y) * kc + c];
+                P[x * kc + c] = s;
+            }
+        /* rows of this block: P_l + A_l Z_l   (Z holds Z_l = sum_{j<l} H_j here) */
+        for (long x = 0; x < b; ++x) {
+            const double *a = PhiQ + (r0 + x) * F;
+            double den = 1.0 + P[x * kc + dv];
+            for (long f = 0; f < F; ++f) den += a[f] * Z[f * kc + dv];
+            for (long c = 0; c < dv; ++c) {
+                double num = P[x * kc + c];
+                for (long f = 0; f < F; ++f) num += a[f] * Z[f * kc + c];
+                O_out[(r0 + x) * dv + c] = num / den;
+            }
+        }
+        /* H_l = B_l^T C_l, then Z_{l+1} = Z_l + H_l */
+        for (long f = 0; f < F; ++f)
+            for (long c = 0; c < kc; ++c) H[f * kc + c] = 0.0;
+        for (long x = 0; x < b; ++x) {
+            const double *bf = PhiK + (r0 + x) * F;
+            for (long f = 0; f < F; ++f)
+                for (long c = 0; c < kc; ++c) H[f * kc + c] += bf[f] * C[(r0 + x) * kc + c];
+        }
+        for (long f = 0; f < F; ++f)
+            for (long c = 0; c < kc; ++c) Z[f * kc + c] += H[f * kc + c];
+    }
+    free(C); free(Z); free(H); free(P); free(S);
+    return 0;
+}
+
+/* ---- drivers over (batch, head) units ---------------------------------------------
+ * Q, K, V are [units, n, d|dv]; G is [g_sets, g_len] with unit u using set
+ * (u % heads) when g_sets == heads, set 0 when g_sets == 1.  Rows are shared by all
+ * units.  OpenMP splits the unit loop only.  Returns the number of threads used,
+ * or a negative error code. */
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+int psf_oracle_attn_def_batch(const double *Q, const double *K, const double *V,
+                              const double *G, long g_sets, long heads,
+                              long units, long n, long d, long dv, long p, long r, long b,
+                              int feat, int local,
+                              const long *rows, long nrows, double *O_out, int max_threads)
+{
+    if (!is_pow2(p) || p < 2) return -1;
+    long mcols = (p == 2) ? d : r;
+    long g_len = psf_oracle_num_g_first(p) * d * r + psf_oracle_num_g_inner(p) * r * r;
+    long orows = rows ? nrows : n;
+    int err = 0, used = 1;
+#ifdef _OPENMP
+    if (max_threads > 0) omp_set_num_threads(max_threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (long u = 0; u < units; ++u) {
+        const double *q = Q + u * n * d, *k = K + u * n * d, *v = V + u * n * dv;
+        double *mq = NULL, *mk = NULL;
+        int e = 0;
+        if (feat == FEAT_SKETCH) {
+            const double *g = G + ((g_sets == 1) ? 0 : (u % heads)) * g_len;
+            mq = (double *)malloc(sizeof(double) * (size_t)n * (size_t)mcols);
+            mk = (double *)malloc(sizeof(double) * (size_t)n * (size_t)mcols);
+            if (!mq || !mk) e = 2;
+            if (!e) e = psf_oracle_sketch(q, n, d, r, p, g, mq);
+            if (!e) e = psf_oracle_sketch(k, n, d, r, p, g, mk);
+        }
+        if (!e)
+            e = psf_oracle_attn_def(q, k, v, mq, mk, n, d, dv, mcols, p, b, feat, local, 0,
+                                    rows, nrows, O_out + u * orows * dv, NULL);
+        free(mq);
+        free(mk);
+        if (e) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+            err = e;
+        }
+    }
+    return err ? -err : used;
+}
