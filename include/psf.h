@@ -1,0 +1,131 @@
+/*
+ * psf.h -- C ABI of libpsf: causal polynomial-sketch attention (forward) on AMD CDNA4.
+ *
+ * Method: PolySketchFormer (arXiv 2310.01655).  Every query/key row x is mapped to
+ *   m(x)    = PolySketchWithNegativity(x, r, p/2)            (Algorithm 1)
+ *   phi'(x) = m(x) (x) m(x)  in R^{r^2}, index a*r + b       (Algorithm 1, PolySketchNonNegative)
+ * and the causal, normalised attention of Section 3
+ *   o_i = sum_{j<=i} w_ij v_j / (1 + sum_{j<=i} w_ij),   w_ij = <phi'(q_i), phi'(k_j)>
+ * is evaluated with the block lower-triangular algorithm of Section 3.1 (per-block states
+ * H_l = phi'(K_l)^T [V_l | 1], exclusive prefix Z_l over blocks, in-block term P_l) and, by
+ * default, exact weights <q_i,k_j>^p for pairs inside one block (Section 3.2).
+ *
+ * Conventions
+ *   - Every data pointer is DEVICE memory owned by the caller.  The library never allocates,
+ *     frees or synchronises; all work is enqueued on `hip_stream` (a hipStream_t, NULL = the
+ *     default stream).  Calls are re-entrant as long as workspaces do not overlap.
+ *   - Tensors are dense row-major: Q, K, M [batch, heads, n, d|r]; V, O [batch, heads, n, dv].
+ *   - The library neither normalises Q/K (the paper applies layer normalisation before the
+ *     kernel, Section 2.1) nor applies a 1/sqrt(d) scale (the final definition has none).
+ *   - Sketch matrices G are data, not drawn here: [sets, g_len] with sets = heads when
+ *     sketch_per_head != 0, else 1 (the paper shares one phi' per layer, Section 4), and inside
+ *     a set the p/2 matrices of shape d x r followed by the p/2 - 2 matrices of shape r x r
+ *     (counts: Theorem 1.1 item 3), each list in the order Algorithm 1 reaches its sampling
+ *     line (left subtree, right subtree, node).  For p = 8: G1,G2 -> M1; G3,G4 -> M2; then the
+ *     r x r pair applied to M1 and M2.  Same storage dtype as Q.
+ *   - Errors are reported by return code only; arguments are validated on the host before
+ *     anything is launched.  On error the contents of outputs and workspace are unspecified.
+ */
+#ifndef PSF_H
+#define PSF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PSF_OK = 0,
+    PSF_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+    PSF_ERR_SHAPE = 2,       /* non-positive size, or n not a multiple of b                 */
+    PSF_ERR_UNSUPPORTED = 3, /* p not in {2,4,8,16}, feature count above PSF_MAX_FEATURES,
+                                unknown enum value, sizes beyond the stated limits          */
+    PSF_ERR_WORKSPACE = 4,   /* workspace smaller than psf_workspace_bytes()                */
+    PSF_ERR_HIP = 5          /* a HIP call or kernel launch failed                          */
+} psf_status;
+
+typedef enum { PSF_F32 = 0, PSF_BF16 = 1 } psf_dtype;   /* storage type of Q, K, V, G, M, Phi, O */
+typedef enum { PSF_FEAT_SKETCH = 0,                     /* phi' of Algorithm 1                   */
+               PSF_FEAT_EXACT = 1 } psf_feat;           /* phi(x) = x^{(x)p} (Section 2.2), needs
+                                                           d^p <= PSF_MAX_FEATURES               */
+typedef enum { PSF_LOCAL_EXACT = 0,                     /* in-block weights <q,k>^p (Section 3.2) */
+               PSF_LOCAL_SKETCH = 1 } psf_local;        /* in-block weights <phi',phi'> = <m,m>^2
+                                                           (Section 3.1, the (L R^T)^2 shortcut)  */
+
+#define PSF_MAX_FEATURES 65536   /* largest explicit feature count (r^2, d^2 for p = 2, or d^p) */
+#define PSF_MAX_DIM 256          /* largest d, dv and r                                         */
+
+/* Problem descriptor (plain data, passed by pointer, read on the host only). */
+typedef struct {
+    int32_t batch, heads;    /* units = batch * heads independent attention problems           */
+    int32_t n;               /* context length                                                 */
+    int32_t d, dv;           /* row length of Q/K and of V/O                                   */
+    int32_t p;               /* polynomial degree: 2, 4, 8 or 16 (Algorithm 1 halves it)       */
+    int32_t r;               /* sketch size; r^2 features.  Ignored for p = 2 and FEAT_EXACT   */
+    int32_t b;               /* block size of the lower-triangular algorithm; n % b == 0       */
+    int32_t dtype;           /* psf_dtype                                                      */
+    int32_t feat;            /* psf_feat                                                       */
+    int32_t local;           /* psf_local (ignored with FEAT_EXACT: all weights are exact)     */
+    int32_t sketch_per_head; /* 0: one set of G for all heads, 1: G has a leading [heads] axis */
+} psf_desc;
+
+/* Host-only check of a descriptor; what the other entry points run first. */
+psf_status psf_check_desc(const psf_desc *desc);
+
+/* Which kernels the descriptor selects: 1 = bf16 MFMA path (FEAT_SKETCH, LOCAL_EXACT, bf16,
+ * p in {4,8}, r in {32,64}, d = dv in {64,128}, b % 128 == 0), 0 = general fp32 path
+ * (everything else the descriptor check admits), -1 = invalid descriptor. */
+int psf_kernel_path(const psf_desc *desc);
+
+/* Bytes of device workspace psf_causal_attn_fwd needs for this descriptor (0 if invalid).
+ * Holds the sketches m(Q), m(K), the block prefix states Z_l (Section 3.1) and staging. */
+size_t psf_workspace_bytes(const psf_desc *desc);
+
+/* Number of entries of one set of sketch matrices for (d, r, p). */
+size_t psf_g_len(int32_t d, int32_t r, int32_t p);
+
+/*
+ * psf_sketch -- Algorithm 1 applied to every row of X [batch, heads, n, d] (device).
+ *   M_out   [batch, heads, n, r]    m(x) = PolySketchWithNegativity(x, r, p/2); r -> d when p = 2
+ *   Phi_out [batch, heads, n, r*r]  phi'(x) = m(x) (x) m(x), or NULL to skip it.  With
+ *                                   FEAT_EXACT: [.., n, d^p] = x^{(x)p} and M_out may be NULL.
+ * G as described above (device; may be NULL when p = 2 or FEAT_EXACT).  Outputs are written
+ * once, in desc->dtype (bf16 rounds to nearest even).  At least one output must be given.
+ */
+psf_status psf_sketch(const psf_desc *desc, const void *X, const void *G,
+                      void *M_out, void *Phi_out, void *hip_stream);
+
+/*
+ * psf_causal_attn_fwd -- Section 3 causal Polysketch attention through the block algorithm of
+ * Sections 3.1/3.2 with block size desc->b.
+ *   Q, K [batch, heads, n, d], V [batch, heads, n, dv], G: device inputs (never written)
+ *   O    [batch, heads, n, dv]: device output in desc->dtype
+ *   workspace: device scratch of at least psf_workspace_bytes(desc) bytes, 256-byte aligned;
+ *              contents on entry are irrelevant, contents on return unspecified.
+ * Accumulation is fp32 throughout; on the MFMA path the operands of the contractions
+ * (m(x), phi', Z_l, in-block weights) are rounded to bf16.
+ */
+psf_status psf_causal_attn_fwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                               const void *G, void *O,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Same call, but brackets each kernel with HIP events on `hip_stream`, waits for the stream
+ * and reports per-stage milliseconds: stage_ms[i], stage names via psf_stage_name(path, i).
+ * n_stages is the capacity of stage_ms; returns the stage count in *n_written.  Creates and
+ * destroys HIP events; intended for benchmarking only.
+ */
+psf_status psf_causal_attn_fwd_timed(const psf_desc *desc, const void *Q, const void *K,
+                                     const void *V, const void *G, void *O,
+                                     void *workspace, size_t workspace_bytes, void *hip_stream,
+                                     float *stage_ms, int32_t n_stages, int32_t *n_written);
+const char *psf_stage_name(int path, int32_t stage);
+
+const char *psf_status_string(psf_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSF_H */

@@ -1,0 +1,201 @@
+"""ctypes binding of libpsf (include/psf.h): argument marshalling only.
+
+torch supplies device memory and the stream; every step of the path runs inside the
+library's HIP kernels.  There is no CPU fallback: a missing library or a CPU tensor
+raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpsf.so")
+
+PSF_OK = 0
+F32, BF16 = 0, 1
+FEAT_SKETCH, FEAT_EXACT = 0, 1
+LOCAL_EXACT, LOCAL_SKETCH = 0, 1
+
+EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_len", "psf_sketch",
+           "psf_causal_attn_fwd", "psf_causal_attn_fwd_timed", "psf_stage_name",
+           "psf_status_string")
+
+
+class PsfDesc(ctypes.Structure):
+    _fields_ = [(name, ctypes.c_int32) for name in
+                ("batch", "heads", "n", "d", "dv", "p", "r", "b", "dtype", "feat", "local",
+                 "sketch_per_head")]
+
+
+class PsfError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = int(code)
+        super().__init__("%s: %s (status %d)" % (where, status_string(code), code))
+
+
+_lib = None
+
+
+def lib():
+    """Load libpsf.so (built in-tree by build.py).  Raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s not found: build it first (python -m paper_2310_01655_amd.build or "
+                "__graft_entry__.build())" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        dp = ctypes.POINTER(PsfDesc)
+        vp = ctypes.c_void_p
+        L.psf_check_desc.restype = ctypes.c_int
+        L.psf_check_desc.argtypes = [dp]
+        L.psf_kernel_path.restype = ctypes.c_int
+        L.psf_kernel_path.argtypes = [dp]
+        L.psf_workspace_bytes.restype = ctypes.c_size_t
+        L.psf_workspace_bytes.argtypes = [dp]
+        L.psf_g_len.restype = ctypes.c_size_t
+        L.psf_g_len.argtypes = [ctypes.c_int32] * 3
+        L.psf_sketch.restype = ctypes.c_int
+        L.psf_sketch.argtypes = [dp, vp, vp, vp, vp, vp]
+        L.psf_causal_attn_fwd.restype = ctypes.c_int
+        L.psf_causal_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.psf_causal_attn_fwd_timed.restype = ctypes.c_int
+        L.psf_causal_attn_fwd_timed.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp,
+                                                ctypes.POINTER(ctypes.c_float), ctypes.c_int32,
+                                                ctypes.POINTER(ctypes.c_int32)]
+        L.psf_stage_name.restype = ctypes.c_char_p
+        L.psf_stage_name.argtypes = [ctypes.c_int, ctypes.c_int32]
+        L.psf_status_string.restype = ctypes.c_char_p
+        L.psf_status_string.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def status_string(code):
+    return lib().psf_status_string(int(code)).decode()
+
+
+def make_desc(batch, heads, n, d, p, r, b, dtype="bf16", dv=None, feat=FEAT_SKETCH,
+              local=LOCAL_EXACT, per_head=False):
+    code = {"f32": F32, "bf16": BF16}[dtype] if isinstance(dtype, str) else int(dtype)
+    return PsfDesc(batch, heads, n, d, d if dv is None else dv, p, r, b, code, int(feat),
+                   int(local), int(bool(per_head)))
+
+
+def check_desc(desc):
+    return lib().psf_check_desc(ctypes.byref(desc))
+
+
+def kernel_path(desc):
+    return lib().psf_kernel_path(ctypes.byref(desc))
+
+
+def workspace_bytes(desc):
+    return lib().psf_workspace_bytes(ctypes.byref(desc))
+
+
+def g_len(d, r, p):
+    return lib().psf_g_len(d, r, p)
+
+
+def _torch_dtype(desc):
+    return torch.bfloat16 if desc.dtype == BF16 else torch.float32
+
+
+def _dev_ptr(t, desc, shape, name):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must live on the GPU (no CPU path exists)" % name)
+    if t.dtype != _torch_dtype(desc):
+        raise ValueError("%s has dtype %s, descriptor says %s" % (name, t.dtype, _torch_dtype(desc)))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s has shape %s, expected %s" % (name, tuple(t.shape), tuple(shape)))
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _g_shape(desc):
+    if desc.feat == FEAT_EXACT or desc.p == 2:
+        return None
+    return (desc.heads if desc.sketch_per_head else 1, g_len(desc.d, desc.r, desc.p))
+
+
+def alloc_workspace(desc, device="cuda"):
+    nbytes = workspace_bytes(desc)
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def psf_sketch(desc, X, G, want_m=True, want_phi=False, stream=None):
+    """Algorithm 1 on every row of X.  Returns (M or None, Phi or None)."""
+    st = check_desc(desc)
+    if st != PSF_OK:
+        raise PsfError(st, "psf_sketch")
+    B, H, n, d = desc.batch, desc.heads, desc.n, desc.d
+    exact = desc.feat == FEAT_EXACT
+    mcols = d if desc.p == 2 else desc.r
+    F = d ** desc.p if exact else mcols * mcols
+    x_ptr = _dev_ptr(X, desc, (B, H, n, d), "X")
+    g_ptr = _dev_ptr(G, desc, _g_shape(desc), "G") if _g_shape(desc) else None
+    M = torch.empty(B, H, n, mcols, dtype=X.dtype, device=X.device) if (want_m and not exact) else None
+    Phi = torch.empty(B, H, n, F, dtype=X.dtype, device=X.device) if want_phi else None
+    st = lib().psf_sketch(ctypes.byref(desc), x_ptr, g_ptr,
+                          ctypes.c_void_p(M.data_ptr()) if M is not None else None,
+                          ctypes.c_void_p(Phi.data_ptr()) if Phi is not None else None,
+                          _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_sketch")
+    return M, Phi
+
+
+def _attn_args(desc, Q, K, V, G, O, workspace):
+    B, H, n, d, dv = desc.batch, desc.heads, desc.n, desc.d, desc.dv
+    if O is None:
+        O = torch.empty(B, H, n, dv, dtype=Q.dtype, device=Q.device)
+    if workspace is None:
+        workspace = alloc_workspace(desc, Q.device)
+    if not workspace.is_cuda or workspace.dtype != torch.uint8:
+        raise ValueError("workspace must be a uint8 GPU tensor")
+    gs = _g_shape(desc)
+    ptrs = [_dev_ptr(Q, desc, (B, H, n, d), "Q"), _dev_ptr(K, desc, (B, H, n, d), "K"),
+            _dev_ptr(V, desc, (B, H, n, dv), "V"),
+            _dev_ptr(G, desc, gs, "G") if gs else None,
+            _dev_ptr(O, desc, (B, H, n, dv), "O"),
+            ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel())]
+    return O, workspace, ptrs
+
+
+def psf_causal_attn_fwd(desc, Q, K, V, G, O=None, workspace=None, stream=None):
+    """Causal Polysketch attention forward; returns O [batch, heads, n, dv] (device)."""
+    st = check_desc(desc)
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_fwd")
+    O, workspace, ptrs = _attn_args(desc, Q, K, V, G, O, workspace)
+    st = lib().psf_causal_attn_fwd(ctypes.byref(desc), *ptrs, _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_fwd")
+    return O
+
+
+def psf_causal_attn_fwd_timed(desc, Q, K, V, G, O=None, workspace=None, stream=None):
+    """Same call with per-kernel HIP-event timing; returns (O, {stage_name: ms})."""
+    st = check_desc(desc)
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_fwd_timed")
+    O, workspace, ptrs = _attn_args(desc, Q, K, V, G, O, workspace)
+    ms = (ctypes.c_float * 16)()
+    written = ctypes.c_int32(0)
+    st = lib().psf_causal_attn_fwd_timed(ctypes.byref(desc), *ptrs, _stream_ptr(stream), ms, 16,
+                                         ctypes.byref(written))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_fwd_timed")
+    path = kernel_path(desc)
+    names = [lib().psf_stage_name(path, i).decode() for i in range(written.value)]
+    return O, {nm: float(ms[i]) for i, nm in enumerate(names)}

@@ -1,0 +1,212 @@
+// libpsf entry points: descriptor validation, path selection, workspace sizing, dispatch.
+// The operations themselves are defined in include/psf.h (with their citations of
+// PolySketchFormer, arXiv 2310.01655); nothing here computes.
+#include "psf_internal.h"
+
+namespace psf {
+
+psf_status make_problem(const psf_desc *desc, Problem *out)
+{
+    if (!desc) return PSF_ERR_NULL;
+    if (desc->batch <= 0 || desc->heads <= 0 || desc->n <= 0 || desc->d <= 0 || desc->dv <= 0 ||
+        desc->b <= 0)
+        return PSF_ERR_SHAPE;
+    if (desc->n % desc->b != 0) return PSF_ERR_SHAPE;        // t = n/b blocks (Section 3.1)
+    if (desc->p != 2 && desc->p != 4 && desc->p != 8 && desc->p != 16) return PSF_ERR_UNSUPPORTED;
+    if (desc->dtype != PSF_F32 && desc->dtype != PSF_BF16) return PSF_ERR_UNSUPPORTED;
+    if (desc->feat != PSF_FEAT_SKETCH && desc->feat != PSF_FEAT_EXACT) return PSF_ERR_UNSUPPORTED;
+    if (desc->local != PSF_LOCAL_EXACT && desc->local != PSF_LOCAL_SKETCH) return PSF_ERR_UNSUPPORTED;
+    const bool needs_r = desc->feat == PSF_FEAT_SKETCH && desc->p > 2;
+    if (needs_r && desc->r <= 0) return PSF_ERR_SHAPE;
+    if (desc->d > PSF_MAX_DIM || desc->dv > PSF_MAX_DIM || (needs_r && desc->r > PSF_MAX_DIM))
+        return PSF_ERR_UNSUPPORTED;
+    // units and blocks index grid dimensions y/z (limit 65535); n stays well inside 32 bits
+    if ((long long)desc->batch * desc->heads > 65535 || desc->n > (1 << 24) ||
+        desc->n / desc->b > 65535)
+        return PSF_ERR_UNSUPPORTED;
+
+    Problem pb;
+    pb.batch = desc->batch; pb.heads = desc->heads; pb.units = desc->batch * desc->heads;
+    pb.n = desc->n; pb.d = desc->d; pb.dv = desc->dv; pb.p = desc->p;
+    pb.r = needs_r ? desc->r : desc->d;
+    pb.b = desc->b; pb.t = desc->n / desc->b;
+    pb.bf16 = desc->dtype == PSF_BF16;
+    pb.exact_feat = desc->feat == PSF_FEAT_EXACT;
+    pb.local_exact = pb.exact_feat || desc->local == PSF_LOCAL_EXACT;
+    pb.per_head = desc->sketch_per_head != 0;
+    pb.mcols = (desc->p == 2) ? desc->d : pb.r;
+    if (pb.exact_feat) {
+        long long F = 1;
+        for (int e = 0; e < desc->p; ++e) {
+            F *= desc->d;
+            if (F > PSF_MAX_FEATURES) return PSF_ERR_UNSUPPORTED;
+        }
+        pb.F = F;
+    } else {
+        pb.F = (long long)pb.mcols * pb.mcols;
+        if (pb.F > PSF_MAX_FEATURES) return PSF_ERR_UNSUPPORTED;
+    }
+    pb.g_len = (pb.exact_feat || desc->p == 2) ? 0 : psf_g_len(desc->d, pb.r, desc->p);
+    *out = pb;
+    return PSF_OK;
+}
+
+int select_path(const Problem &pb)
+{
+    const bool shapes = (pb.r == 32 || pb.r == 64) && pb.d == pb.dv && (pb.d == 64 || pb.d == 128) &&
+                        (pb.p == 4 || pb.p == 8) && pb.b % 128 == 0;
+    return (pb.bf16 && !pb.exact_feat && pb.local_exact && shapes) ? 1 : 0;
+}
+
+psf_status StageTimer::begin(hipStream_t s)
+{
+    on = true; stream = s; count = 0;
+    for (int i = 0; i <= kMax; ++i) PSF_HIP_TRY(hipEventCreate(&ev[i]));
+    PSF_HIP_TRY(hipEventRecord(ev[0], stream));
+    return PSF_OK;
+}
+
+void StageTimer::mark()
+{
+    if (!on || count >= kMax) return;
+    ++count;
+    (void)hipEventRecord(ev[count], stream);
+}
+
+psf_status StageTimer::finish(float *ms, int cap, int *written)
+{
+    psf_status st = PSF_OK;
+    if (hipStreamSynchronize(stream) != hipSuccess) st = PSF_ERR_HIP;
+    int w = 0;
+    for (int i = 0; i < count && i < cap && st == PSF_OK; ++i) {
+        if (hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]) != hipSuccess) st = PSF_ERR_HIP;
+        ++w;
+    }
+    for (int i = 0; i <= kMax; ++i) (void)hipEventDestroy(ev[i]);
+    if (written) *written = w;
+    on = false;
+    return st;
+}
+
+static psf_status run_attn(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                           const void *G, void *O, void *ws, size_t ws_bytes, void *stream,
+                           StageTimer *tm)
+{
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);
+    if (st != PSF_OK) return st;
+    if (!Q || !K || !V || !O) return PSF_ERR_NULL;
+    if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
+    const size_t need = psf_workspace_bytes(desc);
+    if (need > 0 && !ws) return PSF_ERR_NULL;
+    if (ws_bytes < need) return PSF_ERR_WORKSPACE;
+    if (((uintptr_t)ws & 255u) != 0) return PSF_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    return select_path(pb) == 1 ? mfma_attn(pb, Q, K, V, G, O, ws, s, tm)
+                                : general_attn(pb, Q, K, V, G, O, ws, s, tm);
+}
+
+}  // namespace psf
+
+using namespace psf;
+
+extern "C" {
+
+psf_status psf_check_desc(const psf_desc *desc)
+{
+    Problem pb;
+    return make_problem(desc, &pb);
+}
+
+int psf_kernel_path(const psf_desc *desc)
+{
+    Problem pb;
+    if (make_problem(desc, &pb) != PSF_OK) return -1;
+    return select_path(pb);
+}
+
+size_t psf_g_len(int32_t d, int32_t r, int32_t p)
+{
+    if (d <= 0 || r <= 0 || p < 4) return 0;
+    const size_t half = (size_t)p / 2;
+    const size_t n_first = half >= 2 ? half : 0;          // d x r matrices (Theorem 1.1 item 3)
+    const size_t n_inner = half >= 4 ? half - 2 : 0;      // r x r matrices
+    return n_first * (size_t)d * (size_t)r + n_inner * (size_t)r * (size_t)r;
+}
+
+size_t psf_workspace_bytes(const psf_desc *desc)
+{
+    Problem pb;
+    if (make_problem(desc, &pb) != PSF_OK) return 0;
+    return select_path(pb) == 1 ? mfma_workspace_bytes(pb) : general_workspace_bytes(pb);
+}
+
+psf_status psf_sketch(const psf_desc *desc, const void *X, const void *G, void *M_out,
+                      void *Phi_out, void *hip_stream)
+{
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);
+    if (st != PSF_OK) return st;
+    if (!X) return PSF_ERR_NULL;
+    if (!M_out && !Phi_out) return PSF_ERR_NULL;
+    if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
+    hipStream_t s = (hipStream_t)hip_stream;
+    // The MFMA sketch kernel covers the same shapes as the MFMA attention path; explicit
+    // features (Phi_out) are always written by the general kernel.
+    if (select_path(pb) == 1 && !Phi_out) return mfma_sketch(pb, X, G, M_out, Phi_out, s);
+    return general_sketch(pb, X, G, M_out, Phi_out, s);
+}
+
+psf_status psf_causal_attn_fwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                               const void *G, void *O, void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
+{
+    return run_attn(desc, Q, K, V, G, O, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+psf_status psf_causal_attn_fwd_timed(const psf_desc *desc, const void *Q, const void *K,
+                                     const void *V, const void *G, void *O, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream, float *stage_ms,
+                                     int32_t n_stages, int32_t *n_written)
+{
+    if (!stage_ms || n_stages <= 0) return PSF_ERR_NULL;
+    if (n_written) *n_written = 0;
+    // validate before creating any event
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);
+    if (st != PSF_OK) return st;
+    StageTimer tm;
+    st = tm.begin((hipStream_t)hip_stream);
+    if (st != PSF_OK) return st;
+    st = run_attn(desc, Q, K, V, G, O, workspace, workspace_bytes, hip_stream, &tm);
+    int w = 0;
+    psf_status st2 = tm.finish(stage_ms, n_stages, &w);
+    if (n_written) *n_written = w;
+    return st != PSF_OK ? st : st2;
+}
+
+const char *psf_stage_name(int path, int32_t stage)
+{
+    static const char *general[] = {"sketch_q", "sketch_k", "block_states", "exclusive_scan",
+                                    "output"};
+    static const char *mfma[] = {"sketch_and_layouts", "denominator_states", "block_states_scan",
+                                 "output"};
+    if (path == 0 && stage >= 0 && stage < 5) return general[stage];
+    if (path == 1 && stage >= 0 && stage < 4) return mfma[stage];
+    return "";
+}
+
+const char *psf_status_string(psf_status status)
+{
+    switch (status) {
+    case PSF_OK: return "ok";
+    case PSF_ERR_NULL: return "required pointer is NULL";
+    case PSF_ERR_SHAPE: return "invalid shape (non-positive size or n not a multiple of b)";
+    case PSF_ERR_UNSUPPORTED: return "unsupported parameter";
+    case PSF_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case PSF_ERR_HIP: return "HIP call or kernel launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,369 @@
+// General fp32 path of libpsf: every descriptor the check admits (any d, dv, r <= 256,
+// p in {2,4,8,16}, exact features x^{(x)p}, either in-block rule, fp32 or bf16 storage).
+// Plain LDS-staged VALU kernels that follow the block algorithm of PolySketchFormer
+// (arXiv 2310.01655, Sections 3.1 and 3.2) step by step; the tuned bf16 MFMA kernels for
+// the large shapes live in psf_mfma.hip.
+#include "psf_internal.h"
+
+namespace psf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kStateFeat = 8;     // features per workgroup in the block-state kernel
+constexpr int kStateChunk = 64;   // tokens staged per step in the block-state kernel
+constexpr int kOutRows = 8;       // rows per workgroup in the output kernel (at most)
+constexpr int kOutChunk = 512;    // features / keys staged per step in the output kernel
+
+__device__ __forceinline__ float pow_pow2(float x, int p)
+{
+    for (int e = 1; e < p; e <<= 1) x *= x;      // p is a power of two: repeated squaring
+    return x;
+}
+
+// phi(x)[f] for exact features: f = (a_1 ... a_p) in base d, most significant first
+// (x^{(x)p} = x (x) x^{(x)(p-1)}, Section 1.2), value prod_e x[a_e].
+template <typename T>
+__device__ __forceinline__ float exact_feature(const T *x, long long f, int d, int p)
+{
+    float v = 1.f;
+    for (int e = 0; e < p; ++e) {
+        v *= load_f(x, (size_t)(f % d));
+        f /= d;
+    }
+    return v;
+}
+
+// ---- Algorithm 1 for one row per loop iteration; intermediates live in LDS ----------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gen_sketch_kernel(
+    const T *__restrict__ X, const T *__restrict__ G, long long rows, int n, int heads,
+    int per_head, int d, int r, int p, int exact, long long F, size_t g_len,
+    float *__restrict__ M_f32, T *__restrict__ M_st, T *__restrict__ Phi)
+{
+    __shared__ float xs[PSF_MAX_DIM];
+    __shared__ float lev[2][4][PSF_MAX_DIM];
+    const int tid = threadIdx.x;
+    const int mcols = (p == 2) ? d : r;
+    for (long long row = blockIdx.x; row < rows; row += gridDim.x) {
+        const T *x = X + (size_t)row * d;
+        __syncthreads();
+        if (tid < d) xs[tid] = load_f(x, tid);
+        __syncthreads();
+        const float *fin = xs;
+        if (!exact && p > 2) {
+            const int head = (int)((row / n) % heads);
+            const T *g_first = G + (per_head ? (size_t)head * g_len : 0);
+            const T *g_inner = g_first + (size_t)(p / 2) * d * r;
+            const float sc = sqrtf(1.0f / (float)r);
+            int cur = 0, count = p / 4;                       // degree-2 sketches of x
+            if (tid < r) {
+                for (int j = 0; j < count; ++j) {
+                    const T *ga = g_first + (size_t)(2 * j) * d * r;
+                    const T *gb = ga + (size_t)d * r;
+                    float u = 0.f, v = 0.f;
+                    for (int e = 0; e < d; ++e) {
+                        u += xs[e] * load_f(ga, (size_t)e * r + tid);
+                        v += xs[e] * load_f(gb, (size_t)e * r + tid);
+                    }
+                    lev[cur][j][tid] = sc * (u * v);
+                }
+            }
+            __syncthreads();
+            size_t inner_at = 0;                              // r x r matrices, level by level
+            while (count > 1) {
+                const int next = count / 2;
+                if (tid < r) {
+                    for (int j = 0; j < next; ++j) {
+                        const T *ga = g_inner + (inner_at + 2 * j) * (size_t)r * r;
+                        const T *gb = ga + (size_t)r * r;
+                        const float *m1 = lev[cur][2 * j], *m2 = lev[cur][2 * j + 1];
+                        float u = 0.f, v = 0.f;
+                        for (int e = 0; e < r; ++e) {
+                            u += m1[e] * load_f(ga, (size_t)e * r + tid);
+                            v += m2[e] * load_f(gb, (size_t)e * r + tid);
+                        }
+                        lev[cur ^ 1][j][tid] = sc * (u * v);
+                    }
+                }
+                __syncthreads();
+                inner_at += 2 * (size_t)next;
+                count = next;
+                cur ^= 1;
+            }
+            fin = lev[cur][0];
+        }
+        if (!exact) {
+            if (tid < mcols) {
+                if (M_f32) M_f32[(size_t)row * mcols + tid] = fin[tid];
+                if (M_st) store_f(M_st, (size_t)row * mcols + tid, fin[tid]);
+            }
+            if (Phi)
+                for (int idx = tid; idx < mcols * mcols; idx += kThreads)
+                    store_f(Phi, (size_t)row * F + idx, fin[idx / mcols] * fin[idx % mcols]);
+        } else if (Phi) {
+            for (long long f = tid; f < F; f += kThreads) {
+                long long g = f;                 // the product does not depend on digit order
+                float v = 1.f;
+                for (int e = 0; e < p; ++e) { v *= xs[g % d]; g /= d; }
+                store_f(Phi, (size_t)row * F + f, v);
+            }
+        }
+    }
+}
+
+// ---- H_l = phi(K_l)^T [V_l | 1]  (Section 3.1), one block l per blockIdx.y ----------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gen_state_kernel(
+    const float *__restrict__ MK, const T *__restrict__ K, const T *__restrict__ V,
+    float *__restrict__ Z, int n, int d, int dv, int p, int b, int t, int mcols, long long F,
+    int exact)
+{
+    __shared__ float phi[kStateChunk][kStateFeat];
+    const int tid = threadIdx.x, l = blockIdx.y, u = blockIdx.z;
+    const long long f0 = (long long)blockIdx.x * kStateFeat;
+    const int kc = dv + 1;
+    float acc[kStateFeat][2];
+    for (int ff = 0; ff < kStateFeat; ++ff) acc[ff][0] = acc[ff][1] = 0.f;
+    const size_t row0 = (size_t)u * n + (size_t)l * b;
+    for (int j0 = 0; j0 < b; j0 += kStateChunk) {
+        __syncthreads();
+        for (int idx = tid; idx < kStateChunk * kStateFeat; idx += kThreads) {
+            const int jj = idx / kStateFeat, ff = idx % kStateFeat;
+            float v = 0.f;
+            if (j0 + jj < b && f0 + ff < F) {
+                const size_t row = row0 + j0 + jj;
+                const long long f = f0 + ff;
+                v = exact ? exact_feature(K + row * d, f, d, p)
+                          : MK[row * mcols + f / mcols] * MK[row * mcols + f % mcols];
+            }
+            phi[jj][ff] = v;
+        }
+        __syncthreads();
+        const int lim = min(kStateChunk, b - j0);
+        for (int ci = 0; ci < 2; ++ci) {
+            const int c = tid + ci * kThreads;
+            if (c >= kc) break;
+            for (int jj = 0; jj < lim; ++jj) {
+                const float v = (c < dv) ? load_f(V, (row0 + j0 + jj) * dv + c) : 1.f;
+                for (int ff = 0; ff < kStateFeat; ++ff) acc[ff][ci] += phi[jj][ff] * v;
+            }
+        }
+    }
+    float *z = Z + (((size_t)u * t + l) * (size_t)F) * kc;
+    for (int ci = 0; ci < 2; ++ci) {
+        const int c = tid + ci * kThreads;
+        if (c >= kc) break;
+        for (int ff = 0; ff < kStateFeat; ++ff)
+            if (f0 + ff < F) z[(size_t)(f0 + ff) * kc + c] = acc[ff][ci];
+    }
+}
+
+// ---- Z_l = sum_{j<l} H_j, sequential over blocks as in the paper; in place --------------
+__global__ __launch_bounds__(kThreads) void gen_scan_kernel(float *__restrict__ Z, int units, int t,
+                                                            size_t per_block)
+{
+    const size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= (size_t)units * per_block) return;
+    const size_t u = idx / per_block, e = idx % per_block;
+    float *z = Z + u * (size_t)t * per_block + e;
+    float run = 0.f;
+    for (int l = 0; l < t; ++l) {
+        const float h = (l < t - 1) ? z[(size_t)l * per_block] : 0.f;   // H_t is never needed
+        z[(size_t)l * per_block] = run;
+        run += h;
+    }
+}
+
+// ---- rows of the output: P_l row + phi(q_i)^T Z_l, then divide by 1 + last column ---------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gen_out_kernel(
+    const float *__restrict__ MQ, const float *__restrict__ MK, const T *__restrict__ Q,
+    const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ Z,
+    T *__restrict__ O, int n, int d, int dv, int p, int b, int t, int mcols, long long F,
+    int exact_feat, int local_exact, int rows_per_wg)
+{
+    __shared__ float stage[kOutRows][kOutChunk];
+    __shared__ float den_s[kOutRows];
+    const int tid = threadIdx.x, u = blockIdx.y;
+    const int i0 = blockIdx.x * rows_per_wg;            // first row of this workgroup
+    const int l = i0 / b;                               // all its rows lie in block l
+    const int kc = dv + 1, RT = rows_per_wg;
+    float acc[kOutRows][2];
+    for (int rt = 0; rt < kOutRows; ++rt) acc[rt][0] = acc[rt][1] = 0.f;
+    const size_t urow = (size_t)u * n;
+
+    if (l > 0) {                                        // a_i^T Z_l
+        const float *z = Z + (((size_t)u * t + l) * (size_t)F) * kc;
+        for (long long f0 = 0; f0 < F; f0 += kOutChunk) {
+            __syncthreads();
+            for (int idx = tid; idx < RT * kOutChunk; idx += kThreads) {
+                const int rt = idx / kOutChunk, ff = idx % kOutChunk;
+                const long long f = f0 + ff;
+                float v = 0.f;
+                if (f < F) {
+                    const size_t row = urow + i0 + rt;
+                    v = exact_feat ? exact_feature(Q + row * d, f, d, p)
+                                   : MQ[row * mcols + f / mcols] * MQ[row * mcols + f % mcols];
+                }
+                stage[rt][ff] = v;
+            }
+            __syncthreads();
+            const int lim = (int)min((long long)kOutChunk, F - f0);
+            for (int ci = 0; ci < 2; ++ci) {
+                const int c = tid + ci * kThreads;
+                if (c >= kc) break;
+                for (int ff = 0; ff < lim; ++ff) {
+                    const float zv = z[(size_t)(f0 + ff) * kc + c];
+                    for (int rt = 0; rt < kOutRows; ++rt)
+                        if (rt < RT) acc[rt][ci] += stage[rt][ff] * zv;
+                }
+            }
+        }
+    }
+
+    const int jbeg = l * b, jend = i0 + RT;             // keys jbeg .. i0+RT-1 (row rt keeps j <= i0+rt)
+    for (int j0 = jbeg; j0 < jend; j0 += kOutChunk) {   // row of P_l = lt(.) [V_l | 1]
+        __syncthreads();
+        for (int idx = tid; idx < RT * kOutChunk; idx += kThreads) {
+            const int rt = idx / kOutChunk, jj = idx % kOutChunk;
+            const int j = j0 + jj, i = i0 + rt;
+            float w = 0.f;
+            if (j <= i) {
+                if (local_exact) {
+                    const T *q = Q + (urow + i) * d, *k = K + (urow + j) * d;
+                    float s = 0.f;
+                    for (int e = 0; e < d; ++e) s += load_f(q, e) * load_f(k, e);
+                    w = pow_pow2(s, p);
+                } else {
+                    const float *q = MQ + (urow + i) * mcols, *k = MK + (urow + j) * mcols;
+                    float s = 0.f;
+                    for (int e = 0; e < mcols; ++e) s += q[e] * k[e];
+                    w = s * s;
+                }
+            }
+            stage[rt][jj] = w;
+        }
+        __syncthreads();
+        const int lim = min(kOutChunk, jend - j0);
+        for (int ci = 0; ci < 2; ++ci) {
+            const int c = tid + ci * kThreads;
+            if (c >= kc) break;
+            for (int jj = 0; jj < lim; ++jj) {
+                const float v = (c < dv) ? load_f(V, (urow + j0 + jj) * dv + c) : 1.f;
+                for (int rt = 0; rt < kOutRows; ++rt)
+                    if (rt < RT) acc[rt][ci] += stage[rt][jj] * v;
+            }
+        }
+    }
+
+    __syncthreads();
+    if (tid == dv % kThreads)
+        for (int rt = 0; rt < kOutRows; ++rt)
+            if (rt < RT) den_s[rt] = 1.f + acc[rt][dv / kThreads];
+    __syncthreads();
+    for (int ci = 0; ci < 2; ++ci) {
+        const int c = tid + ci * kThreads;
+        if (c >= dv) break;
+        for (int rt = 0; rt < kOutRows; ++rt)
+            if (rt < RT) store_f(O, (urow + i0 + rt) * dv + c, acc[rt][ci] / den_s[rt]);
+    }
+}
+
+struct GeneralWs {
+    float *MQ, *MK, *Z;
+    size_t total;
+};
+
+GeneralWs carve(const Problem &pb, void *ws)
+{
+    GeneralWs w;
+    const size_t m_bytes = pb.exact_feat ? 0 : align_up((size_t)pb.units * pb.n * pb.mcols * 4, 256);
+    const size_t z_bytes = align_up((size_t)pb.units * pb.t * (size_t)pb.F * (pb.dv + 1) * 4, 256);
+    char *base = (char *)ws;
+    w.MQ = (float *)base;
+    w.MK = (float *)(base + m_bytes);
+    w.Z = (float *)(base + 2 * m_bytes);
+    w.total = 2 * m_bytes + z_bytes;
+    return w;
+}
+
+template <typename T>
+psf_status sketch_launch(const Problem &pb, const void *X, const void *G, float *M_f32, void *M_out,
+                         void *Phi_out, hipStream_t s)
+{
+    const long long rows = (long long)pb.units * pb.n;
+    const int grid = (int)(rows < 65536 ? rows : 65536);
+    hipLaunchKernelGGL(gen_sketch_kernel<T>, dim3(grid), dim3(kThreads), 0, s, (const T *)X,
+                       (const T *)G, rows, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.d, pb.r, pb.p,
+                       pb.exact_feat ? 1 : 0, pb.F, pb.g_len, M_f32, (T *)M_out, (T *)Phi_out);
+    PSF_LAUNCH_CHECK();
+    return PSF_OK;
+}
+
+template <typename T>
+psf_status attn_launch(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+                       void *O, void *ws, hipStream_t s, StageTimer *tm)
+{
+    GeneralWs w = carve(pb, ws);
+    psf_status st;
+    if (!pb.exact_feat) {
+        st = sketch_launch<T>(pb, Q, G, w.MQ, nullptr, nullptr, s);
+        if (st != PSF_OK) return st;
+    }
+    if (tm) tm->mark();
+    if (!pb.exact_feat) {
+        st = sketch_launch<T>(pb, K, G, w.MK, nullptr, nullptr, s);
+        if (st != PSF_OK) return st;
+    }
+    if (tm) tm->mark();
+    if (pb.t > 1) {
+        dim3 grid((unsigned)((pb.F + kStateFeat - 1) / kStateFeat), (unsigned)(pb.t - 1),
+                  (unsigned)pb.units);
+        hipLaunchKernelGGL(gen_state_kernel<T>, grid, dim3(kThreads), 0, s, w.MK, (const T *)K,
+                           (const T *)V, w.Z, pb.n, pb.d, pb.dv, pb.p, pb.b, pb.t, pb.mcols, pb.F,
+                           pb.exact_feat ? 1 : 0);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    if (pb.t > 1) {
+        const size_t per_block = (size_t)pb.F * (pb.dv + 1);
+        const size_t total = (size_t)pb.units * per_block;
+        hipLaunchKernelGGL(gen_scan_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)),
+                           dim3(kThreads), 0, s, w.Z, pb.units, pb.t, per_block);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    int rows_per_wg = kOutRows;
+    while (pb.b % rows_per_wg != 0) rows_per_wg /= 2;
+    dim3 grid((unsigned)(pb.n / rows_per_wg), (unsigned)pb.units);
+    hipLaunchKernelGGL(gen_out_kernel<T>, grid, dim3(kThreads), 0, s, w.MQ, w.MK, (const T *)Q,
+                       (const T *)K, (const T *)V, w.Z, (T *)O, pb.n, pb.d, pb.dv, pb.p, pb.b, pb.t,
+                       pb.mcols, pb.F, pb.exact_feat ? 1 : 0, pb.local_exact ? 1 : 0, rows_per_wg);
+    PSF_LAUNCH_CHECK();
+    if (tm) tm->mark();
+    return PSF_OK;
+}
+
+}  // namespace
+
+size_t general_workspace_bytes(const Problem &pb)
+{
+    return carve(pb, nullptr).total;
+}
+
+psf_status general_sketch(const Problem &pb, const void *X, const void *G, void *M_out, void *Phi_out,
+                          hipStream_t s)
+{
+    if (pb.exact_feat && !Phi_out) return PSF_ERR_NULL;   // exact features have no m(x)
+    return pb.bf16 ? sketch_launch<bf16_t>(pb, X, G, nullptr, M_out, Phi_out, s)
+                   : sketch_launch<float>(pb, X, G, nullptr, M_out, Phi_out, s);
+}
+
+psf_status general_attn(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+                        void *O, void *ws, hipStream_t s, StageTimer *tm)
+{
+    return pb.bf16 ? attn_launch<bf16_t>(pb, Q, K, V, G, O, ws, s, tm)
+                   : attn_launch<float>(pb, Q, K, V, G, O, ws, s, tm);
+}
+
+}  // namespace psf

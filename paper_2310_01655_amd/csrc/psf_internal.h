@@ -1,0 +1,85 @@
+// Internal declarations shared by the translation units of libpsf (not part of the ABI).
+#ifndef PSF_INTERNAL_H
+#define PSF_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "psf.h"
+
+namespace psf {
+
+// Host-side view of a validated descriptor.
+struct Problem {
+    int batch, heads, units;
+    int n, d, dv, p, r, b, t;
+    int mcols;        // columns of m(x): r, or d when p == 2 (Algorithm 1 base case)
+    long long F;      // explicit feature count: mcols^2, or d^p with exact features
+    bool bf16, exact_feat, local_exact, per_head;
+    size_t g_len;     // entries of one set of sketch matrices
+};
+
+psf_status make_problem(const psf_desc *desc, Problem *out);
+int select_path(const Problem &pb);
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Event recorder used by the timed entry point; inert when `on` is false.
+struct StageTimer {
+    bool on = false;
+    hipStream_t stream = nullptr;
+    static const int kMax = 12;
+    hipEvent_t ev[kMax + 1];
+    int count = 0;
+    psf_status begin(hipStream_t s);
+    void mark();                       // closes the current stage
+    psf_status finish(float *ms, int cap, int *written);
+};
+
+// General fp32 path (any descriptor the check admits).
+size_t general_workspace_bytes(const Problem &pb);
+psf_status general_sketch(const Problem &pb, const void *X, const void *G, void *M_out,
+                          void *Phi_out, hipStream_t s);
+psf_status general_attn(const Problem &pb, const void *Q, const void *K, const void *V,
+                        const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);
+
+// bf16 MFMA path.
+size_t mfma_workspace_bytes(const Problem &pb);
+psf_status mfma_sketch(const Problem &pb, const void *X, const void *G, void *M_out,
+                       void *Phi_out, hipStream_t s);
+psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void *V,
+                     const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);
+
+#define PSF_HIP_TRY(expr)                                   \
+    do {                                                    \
+        hipError_t e__ = (expr);                            \
+        if (e__ != hipSuccess) return PSF_ERR_HIP;          \
+    } while (0)
+
+#define PSF_LAUNCH_CHECK()                                  \
+    do {                                                    \
+        if (hipGetLastError() != hipSuccess) return PSF_ERR_HIP; \
+    } while (0)
+
+// ---- storage helpers (device) ------------------------------------------------------
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_f(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_f(const bf16_t *p, size_t i) { return bf16_to_f32(p[i]); }
+__device__ __forceinline__ void store_f(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_f(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
+
+}  // namespace psf
+#endif

@@ -1,0 +1,54 @@
+"""Helpers for the GPU-vs-oracle parity tests (test infrastructure)."""
+import numpy as np
+import torch
+
+import oracle
+from paper_2310_01655_amd import binding as psf
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}     # max-abs and relative-Frobenius bound, per storage dtype
+
+
+def errors(got, want):
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    max_abs = float(np.abs(got - want).max()) if got.size else 0.0
+    denom = float(np.linalg.norm(want))
+    rel = float(np.linalg.norm(got - want) / denom) if denom > 0 else max_abs
+    return max_abs, rel
+
+
+def assert_close(got, want, dtype, what=""):
+    max_abs, rel = errors(got, want)
+    tol = TOL[dtype]
+    assert np.isfinite(np.asarray(got, dtype=np.float64)).all(), what
+    assert max_abs <= tol and rel <= tol, "%s: max_abs %.3e rel_fro %.3e (tol %.0e)" % (
+        what, max_abs, rel, tol)
+    return max_abs, rel
+
+
+def as_f64(t):
+    return t.to(torch.float64).numpy()
+
+
+def gpu_attn(cfg, q, k, v, G, feat=psf.FEAT_SKETCH, local=psf.LOCAL_EXACT, b=None, timed=False):
+    desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"],
+                         cfg["b"] if b is None else b, cfg["dtype"], feat=feat, local=local,
+                         per_head=cfg.get("per_head", False))
+    dev = torch.device("cuda:0")
+    args = [x.to(dev) if x is not None else None for x in (q, k, v, G)]
+    if timed:
+        O, stages = psf.psf_causal_attn_fwd_timed(desc, *args)
+    else:
+        O, stages = psf.psf_causal_attn_fwd(desc, *args), None
+    torch.cuda.synchronize()
+    out = O.float().cpu()
+    return (out, stages, desc) if timed else (out, desc)
+
+
+def oracle_attn(cfg, q, k, v, G, feat=oracle.FEAT_SKETCH, local=oracle.LOCAL_EXACT, b=None,
+                rows=None):
+    O, _ = oracle.attn_def_batch(as_f64(q), as_f64(k), as_f64(v),
+                                 as_f64(G) if G is not None else None,
+                                 cfg["p"], cfg["r"], cfg["b"] if b is None else b,
+                                 feat=feat, local=local, rows=rows)
+    return O

@@ -1,0 +1,92 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and validates descriptors and pointers before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2310_01655_amd import binding as psf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "psf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(psf_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = psf.lib()
+    names = header_symbols()
+    assert set(names) == set(psf.EXPORTS), names
+    for nm in names:
+        assert getattr(L, nm) is not None
+
+
+def good():
+    return psf.make_desc(2, 12, 32768, 64, 4, 64, 1024, "bf16")
+
+
+def test_descriptor_validation_codes():
+    assert psf.check_desc(good()) == 0
+    assert psf.lib().psf_check_desc(None) == 1
+    for field, val, code in [("n", 0, 2), ("batch", -1, 2), ("b", 1000, 2), ("r", 0, 2),
+                             ("p", 6, 3), ("p", 32, 3), ("dtype", 7, 3), ("feat", 2, 3),
+                             ("local", -1, 3), ("d", 512, 3), ("r", 300, 3)]:
+        d = good()
+        setattr(d, field, val)
+        assert psf.check_desc(d) == code, (field, val)
+        assert psf.workspace_bytes(d) == 0 and psf.kernel_path(d) == -1
+    # exact features: d^p must stay within the stated cap
+    assert psf.check_desc(psf.make_desc(1, 1, 64, 8, 4, 1, 8, "f32", feat=psf.FEAT_EXACT)) == 0
+    assert psf.check_desc(psf.make_desc(1, 1, 64, 16, 4, 1, 8, "f32", feat=psf.FEAT_EXACT)) == 0
+    assert psf.check_desc(psf.make_desc(1, 1, 64, 64, 4, 1, 8, "f32", feat=psf.FEAT_EXACT)) == 3
+    # r is ignored for p = 2 (Algorithm 1's base case returns the input)
+    assert psf.check_desc(psf.make_desc(1, 1, 64, 64, 2, 0, 8, "f32")) == 0
+
+
+def test_path_selection_and_workspace():
+    assert psf.kernel_path(psf.make_desc(1, 1, 1024, 64, 4, 16, 128, "f32")) == 0
+    assert psf.kernel_path(psf.make_desc(1, 1, 1024, 64, 4, 64, 128, "f32")) == 0
+    d1 = psf.make_desc(1, 1, 1024, 64, 4, 16, 128, "f32")
+    # general path: m(Q), m(K) in fp32 and t states of r^2 x (dv+1) fp32
+    assert psf.workspace_bytes(d1) >= 2 * 1024 * 16 * 4 + 8 * 256 * 65 * 4
+    assert psf.g_len(64, 64, 4) == 2 * 64 * 64
+    assert psf.g_len(128, 64, 8) == 4 * 128 * 64 + 2 * 64 * 64
+    assert psf.g_len(64, 8, 16) == 8 * 64 * 8 + 6 * 8 * 8
+    assert psf.g_len(64, 8, 2) == 0
+
+
+def test_null_pointers_are_rejected_before_any_launch():
+    L = psf.lib()
+    d = psf.make_desc(1, 1, 1024, 64, 4, 16, 128, "f32")
+    ref = ctypes.byref(d)
+    one = ctypes.c_void_p(256)   # never dereferenced: the calls must fail on the NULL first
+    assert L.psf_sketch(ref, None, one, one, None, None) == 1
+    assert L.psf_sketch(ref, one, None, one, None, None) == 1
+    assert L.psf_sketch(ref, one, one, None, None, None) == 1
+    assert L.psf_causal_attn_fwd(ref, None, one, one, one, one, one, 1 << 40, None) == 1
+    assert L.psf_causal_attn_fwd(ref, one, one, one, one, None, one, 1 << 40, None) == 1
+    assert L.psf_causal_attn_fwd(ref, one, one, one, None, one, one, 1 << 40, None) == 1
+    assert L.psf_causal_attn_fwd(ref, one, one, one, one, one, one, 16, None) == 4
+    assert L.psf_causal_attn_fwd(ref, one, one, one, one, one, ctypes.c_void_p(264), 1 << 40, None) == 4
+    d.p = 5
+    assert L.psf_causal_attn_fwd(ref, one, one, one, one, one, one, 1 << 40, None) == 3
+    assert L.psf_causal_attn_fwd_timed(ref, one, one, one, one, one, one, 1 << 40, None, None, 0, None) == 1
+
+
+def test_status_strings_and_stage_names():
+    assert psf.status_string(0) == "ok"
+    assert all(psf.status_string(c) for c in range(6))
+    assert psf.lib().psf_stage_name(0, 0) == b"sketch_q"
+    assert psf.lib().psf_stage_name(1, 3) == b"output"
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    d = psf.make_desc(1, 1, 64, 8, 4, 4, 8, "f32")
+    x = torch.zeros(1, 1, 64, 8)
+    with pytest.raises(ValueError):
+        psf.psf_sketch(d, x, torch.zeros(1, 64), want_m=True)
