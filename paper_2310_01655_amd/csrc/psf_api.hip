@@ -54,7 +54,7 @@ psf_status make_problem(const psf_desc *desc, Problem *out)
 int select_path(const Problem &pb)
 {
     const bool shapes = (pb.r == 32 || pb.r == 64) && pb.d == pb.dv && (pb.d == 64 || pb.d == 128) &&
-                        (pb.p == 4 || pb.p == 8) && pb.b % 128 == 0;
+                        (pb.p == 4 || pb.p == 8) && pb.b % 256 == 0;
     return (pb.bf16 && !pb.exact_feat && pb.local_exact && shapes) ? 1 : 0;
 }
 

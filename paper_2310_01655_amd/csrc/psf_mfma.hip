@@ -1,7 +1,826 @@
-// bf16 MFMA path of libpsf (placeholder until the kernels land).
+// bf16 MFMA path of libpsf for gfx950 (MI355X): causal polynomial-sketch attention with the
+// block lower-triangular algorithm of PolySketchFormer (arXiv 2310.01655, Sections 3.1, 3.2).
+//
+// Kernels (R = sketch size r, D = head size d = dv, b = block size, t = n/b):
+//   k_sketch       Algorithm 1 on bf16 MFMA.  m(Q) is stored row-major bf16 and transposed
+//                  fp32; m(K) is stored as fp32 "token octets" [n/8][R][8] so that the state
+//                  kernel can stage it into LDS with straight copies.
+//   k_v_octets     V -> [n/8][D][8] bf16 (same octet layout).
+//   k_den_partial  per block: S_l = m(K_l)^T m(K_l) (R x R).  This is the "ones" column of
+//                  H_l = phi'(K_l)^T [V_l | 1] because phi' = m (x) m (Algorithm 1).
+//   k_den_scan     exclusive prefix of S_l over blocks, stored as bf16 hi + lo MFMA operands.
+//   k_state        running prefix state Z = sum phi'(k_j) v_j^T kept in MFMA accumulators while
+//                  one workgroup walks the blocks in order; phi'(k_j) = m_j (x) m_j is expanded
+//                  in registers (one operand broadcast across lanes with DPP) and never
+//                  written to memory.  A bf16 snapshot Z_{l+1} is stored after each block, so
+//                  the exclusive scan over blocks (Section 3.1) costs nothing extra.
+//   k_out          per 256-token tile: exact in-block weights lt((Q_l K_l^T)^p) [V_l | 1]
+//                  (Section 3.2) kept in registers, plus phi'(Q_l) Z_l evaluated as
+//                  sum_a m_i[a] * (Z_l[a,:,:]^T m_i) so that no phi' operand is ever formed,
+//                  then the division by 1 + denominator (Section 3).
+//
+// MFMA v_mfma_f32_32x32x16_bf16 operand layout used throughout (lane = 32*h + x, x < 32):
+//   A[i][k]: lane x = i, half h supplies k = 8h..8h+7 (8 bf16 per lane)
+//   B[k][j]: lane x = j, half h supplies k = 8h..8h+7
+//   D[i][j]: lane x = j, register v holds row i = 8*(v/4) + 4*h + (v%4)
 #include "psf_internal.h"
+
 namespace psf {
-size_t mfma_workspace_bytes(const Problem &) { return 0; }
-psf_status mfma_sketch(const Problem &, const void *, const void *, void *, void *, hipStream_t) { return PSF_ERR_UNSUPPORTED; }
-psf_status mfma_attn(const Problem &, const void *, const void *, const void *, const void *, void *, void *, hipStream_t, StageTimer *) { return PSF_ERR_UNSUPPORTED; }
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWg = 256;          // 4 wavefronts
+constexpr int kTokWg = 256;       // tokens per workgroup in k_out (4 waves x 2 tiles of 32)
+constexpr int kStateChunk = 64;   // tokens staged per step in k_state
+constexpr int kKeyTile = 64;      // keys staged per step in the in-block phase of k_out
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
+
+__device__ __forceinline__ bf16x8 cvt8(f32x8 v) { return __builtin_convertvector(v, bf16x8); }
+__device__ __forceinline__ bf16x4 cvt4(f32x4 v) { return __builtin_convertvector(v, bf16x4); }
+
+__device__ __forceinline__ bf16x8 cvt8_from16(const f32x16 &v, int first)
+{
+    f32x8 t;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t[e] = v[first + e];
+    return cvt8(t);
+}
+
+template <int LANE>
+__device__ __forceinline__ float row_bcast(float v)
+{
+    // value of lane LANE of each row of 16 lanes, delivered to all lanes of that row
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v),
+                                                                  0x150 + LANE, 0xf, 0xf, false));
+}
+
+__device__ __forceinline__ float pow_p(float x, int p)
+{
+    x *= x;                 // p is 4 or 8 here
+    x *= x;
+    if (p == 8) x *= x;
+    return x;
+}
+
+// ------------------------------------------------------------------------------------
+// Algorithm 1 on MFMA.  One wave sketches 32 tokens at a time; a workgroup walks
+// `tiles_per_wg` consecutive 128-token tiles of one unit so that the transposed sketch
+// matrices staged in LDS are reused.
+//   QSIDE: results in D^T orientation (lane = token): writes M_rm [rows][R] bf16 and
+//          MT [U][R][n] fp32.
+//   !QSIDE: results in D orientation (lane = sketch column): writes M8 [U][n/8][R][8] fp32
+//          (and M_rm if given).
+// ------------------------------------------------------------------------------------
+template <int D, int R>
+struct SketchLds {
+    static constexpr int kPitch = (D > R ? D : R) + 8;     // bf16 elements per transposed row
+    bf16_t gt[2][R * kPitch];
+};
+
+template <int D, int R, int ROWS>
+__device__ __forceinline__ void stage_gt(bf16_t *dst, const bf16_t *g)
+{
+    // g is [ROWS][R] row-major; dst[c][e] = g[e][c]
+    constexpr int PITCH = SketchLds<D, R>::kPitch;
+    for (int idx = threadIdx.x; idx < ROWS * R; idx += kWg) {
+        const int e = idx / R, c = idx % R;
+        dst[c * PITCH + e] = g[idx];
+    }
+}
+
+// acc[ct] (+)= G^T X^T restricted to 32 tokens; xfr are the B-operand fragments of X.
+template <int D, int R, int KSTEPS, bool TOKEN_LANES>
+__device__ __forceinline__ void project(const bf16_t *gt, const bf16x8 *xfr, f32x16 *acc, int x,
+                                        int h)
+{
+    constexpr int PITCH = SketchLds<D, R>::kPitch;
+#pragma unroll
+    for (int ct = 0; ct < R / 32; ++ct) {
+        f32x16 c = {0};
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            const bf16x8 g = *(const bf16x8 *)&gt[(32 * ct + x) * PITCH + 16 * s + 8 * h];
+            c = TOKEN_LANES ? mfma32(g, xfr[s], c) : mfma32(xfr[s], g, c);
+        }
+        acc[ct] = c;
+    }
+}
+
+// Second-level projection: operand fragments of M (from accumulators, k index permuted as
+// 16s + 8*(e/4) + 4h + e%4) against G (R x R), same permutation on the G side.
+template <int D, int R, bool TOKEN_LANES>
+__device__ __forceinline__ void project_inner(const bf16_t *gt, const bf16x8 *mfr, f32x16 *acc,
+                                              int x, int h)
+{
+    constexpr int PITCH = SketchLds<D, R>::kPitch;
+#pragma unroll
+    for (int ct = 0; ct < R / 32; ++ct) {
+        f32x16 c = {0};
+#pragma unroll
+        for (int s = 0; s < R / 16; ++s) {
+            const bf16x4 lo = *(const bf16x4 *)&gt[(32 * ct + x) * PITCH + 16 * s + 4 * h];
+            const bf16x4 hi = *(const bf16x4 *)&gt[(32 * ct + x) * PITCH + 16 * s + 8 + 4 * h];
+            bf16x8 g;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { g[e] = lo[e]; g[4 + e] = hi[e]; }
+            c = TOKEN_LANES ? mfma32(g, mfr[s], c) : mfma32(mfr[s], g, c);
+        }
+        acc[ct] = c;
+    }
+}
+
+template <int D, int R, int P, bool QSIDE>
+__global__ __launch_bounds__(kWg) void k_sketch(const bf16_t *__restrict__ X,
+                                                const bf16_t *__restrict__ G, int n, int heads,
+                                                int per_head, size_t g_len, int tiles_per_wg,
+                                                bf16_t *__restrict__ M_rm, float *__restrict__ MT,
+                                                float *__restrict__ M8)
+{
+    __shared__ SketchLds<D, R> lds;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int x = lane & 31, h = lane >> 5;
+    const size_t tok_wg0 = (size_t)blockIdx.x * tiles_per_wg * 128;   // global token (row) index
+    const int u = (int)(tok_wg0 / n);
+    const bf16_t *g = G + (per_head ? (size_t)(u % heads) * g_len : 0);
+    const float scale = sqrtf(1.0f / (float)R);
+    constexpr int KS = D / 16;
+
+    for (int tile = 0; tile < tiles_per_wg; ++tile) {
+        const size_t row0 = tok_wg0 + (size_t)tile * 128 + wave * 32;   // this wave's 32 tokens
+        bf16x8 xfr[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            xfr[s] = *(const bf16x8 *)&X[(row0 + x) * D + 16 * s + 8 * h];
+
+        f32x16 m[R / 32];
+        if (P == 4) {
+            if (tile == 0) {
+                stage_gt<D, R, D>(lds.gt[0], g);
+                stage_gt<D, R, D>(lds.gt[1], g + (size_t)D * R);
+                __syncthreads();
+            }
+            f32x16 a0[R / 32], a1[R / 32];
+            project<D, R, KS, QSIDE>(lds.gt[0], xfr, a0, x, h);
+            project<D, R, KS, QSIDE>(lds.gt[1], xfr, a1, x, h);
+#pragma unroll
+            for (int ct = 0; ct < R / 32; ++ct) m[ct] = scale * (a0[ct] * a1[ct]);
+        } else {
+            // degree 4 = p/2: two independent degree-2 sketches, then one more level
+            bf16x8 m1fr[R / 16], m2fr[R / 16];
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                __syncthreads();
+                stage_gt<D, R, D>(lds.gt[0], g + (size_t)(2 * half) * D * R);
+                stage_gt<D, R, D>(lds.gt[1], g + (size_t)(2 * half + 1) * D * R);
+                __syncthreads();
+                f32x16 a0[R / 32], a1[R / 32];
+                project<D, R, KS, true>(lds.gt[0], xfr, a0, x, h);
+                project<D, R, KS, true>(lds.gt[1], xfr, a1, x, h);
+#pragma unroll
+                for (int ct = 0; ct < R / 32; ++ct) {
+                    const f32x16 mm = scale * (a0[ct] * a1[ct]);
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        if (half == 0) m1fr[2 * ct + q] = cvt8_from16(mm, 8 * q);
+                        else m2fr[2 * ct + q] = cvt8_from16(mm, 8 * q);
+                    }
+                }
+            }
+            __syncthreads();
+            const bf16_t *gi = g + (size_t)4 * D * R;
+            stage_gt<D, R, R>(lds.gt[0], gi);
+            stage_gt<D, R, R>(lds.gt[1], gi + (size_t)R * R);
+            __syncthreads();
+            f32x16 a0[R / 32], a1[R / 32];
+            project_inner<D, R, QSIDE>(lds.gt[0], m1fr, a0, x, h);
+            project_inner<D, R, QSIDE>(lds.gt[1], m2fr, a1, x, h);
+#pragma unroll
+            for (int ct = 0; ct < R / 32; ++ct) m[ct] = scale * (a0[ct] * a1[ct]);
+        }
+
+        const size_t tok_in_unit = row0 - (size_t)u * n;
+        if (QSIDE) {
+            // lane = token x, register v = sketch column 32ct + 8(v/4) + 4h + v%4
+#pragma unroll
+            for (int ct = 0; ct < R / 32; ++ct)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int c0 = 32 * ct + 8 * gq + 4 * h;
+                    f32x4 q4 = {m[ct][4 * gq], m[ct][4 * gq + 1], m[ct][4 * gq + 2], m[ct][4 * gq + 3]};
+                    if (M_rm) *(bf16x4 *)&M_rm[(row0 + x) * R + c0] = cvt4(q4);
+                    if (MT)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            MT[((size_t)u * R + c0 + j) * n + tok_in_unit + x] = q4[j];
+                }
+        } else {
+            // lane = sketch column 32ct + x, register v = token 8(v/4) + 4h + v%4
+#pragma unroll
+            for (int ct = 0; ct < R / 32; ++ct)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int c = 32 * ct + x;
+                    f32x4 q4 = {m[ct][4 * gq], m[ct][4 * gq + 1], m[ct][4 * gq + 2], m[ct][4 * gq + 3]};
+                    if (M8) {
+                        const size_t oct = (row0 >> 3) + gq;
+                        *(f32x4 *)&M8[(oct * R + c) * 8 + 4 * h] = q4;
+                    }
+                    if (M_rm)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            M_rm[(row0 + 8 * gq + 4 * h + j) * R + c] = f32_to_bf16(q4[j]);
+                }
+        }
+    }
+}
+
+// V [rows][D] -> V8 [rows/8][D][8] (bf16 bits moved, not converted)
+template <int D>
+__global__ __launch_bounds__(kWg) void k_v_octets(const bf16_t *__restrict__ V,
+                                                  bf16_t *__restrict__ V8, size_t octets)
+{
+    const size_t idx = (size_t)blockIdx.x * kWg + threadIdx.x;
+    if (idx >= octets * D) return;
+    const size_t oct = idx / D;
+    const int c = (int)(idx % D);
+    uint16_t tmp[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) tmp[j] = V[(oct * 8 + j) * D + c];
+    uint4 pk;
+    pk.x = tmp[0] | ((uint32_t)tmp[1] << 16);
+    pk.y = tmp[2] | ((uint32_t)tmp[3] << 16);
+    pk.z = tmp[4] | ((uint32_t)tmp[5] << 16);
+    pk.w = tmp[6] | ((uint32_t)tmp[7] << 16);
+    *(uint4 *)&V8[idx * 8] = pk;
+}
+
+// ------------------------------------------------------------------------------------
+// Denominator column of the block states: S_l = sum_{j in block l} m_j m_j^T.
+// grid (t-1, U); the four waves split the block's tokens and reduce through LDS.
+// ------------------------------------------------------------------------------------
+template <int R>
+__global__ __launch_bounds__(kWg) void k_den_partial(const float *__restrict__ M8,
+                                                     float *__restrict__ Spart, int n, int b, int t)
+{
+    __shared__ float red[4][32][33];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int x = lane & 31, h = lane >> 5;
+    const int l = blockIdx.x, u = blockIdx.y;
+    constexpr int NT = R / 32;
+    f32x16 acc[NT][NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) acc[i][j] = f32x16{0};
+    const int tok_per_wave = b / 4;
+    const size_t oct0 = ((size_t)u * n + (size_t)l * b + (size_t)wave * tok_per_wave) >> 3;
+    for (int s = 0; s < tok_per_wave / 16; ++s) {
+        bf16x8 fr[NT];
+#pragma unroll
+        for (int i = 0; i < NT; ++i) {
+            const float *p = &M8[((oct0 + 2 * s + h) * R + 32 * i + x) * 8];
+            f32x8 v;
+            const f32x4 lo = *(const f32x4 *)p, hi = *(const f32x4 *)(p + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
+            fr[i] = cvt8(v);
+        }
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) acc[i][j] = mfma32(fr[i], fr[j], acc[i][j]);
+    }
+    float *out = Spart + ((size_t)u * (t - 1) + l) * R * R;
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[wave][8 * (v / 4) + 4 * h + (v % 4)][x] = acc[i][j][v];
+            __syncthreads();
+            for (int idx = threadIdx.x; idx < 32 * 32; idx += kWg) {
+                const int a = idx / 32, c = idx % 32;
+                out[(size_t)(32 * i + a) * R + 32 * j + c] =
+                    red[0][a][c] + red[1][a][c] + red[2][a][c] + red[3][a][c];
+            }
+        }
+}
+
+// Exclusive prefix over blocks of S_l, written as MFMA A-operands [R/8][R][8] bf16, split
+// into hi + lo so that the denominator keeps ~16 mantissa bits.  Slot l holds sum_{j<=l} S_j,
+// which is what block l+1 needs.
+template <int R>
+__global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spart,
+                                                  bf16_t *__restrict__ Shi, bf16_t *__restrict__ Slo,
+                                                  int t)
+{
+    const int u = blockIdx.x;
+    for (int e = threadIdx.x; e < R * R; e += kWg) {
+        const int a = e / R, bq = e % R;
+        const size_t dst = ((size_t)(bq / 8) * R + a) * 8 + (bq % 8);
+        float run = 0.f;
+        for (int l = 0; l < t - 1; ++l) {
+            const size_t base = ((size_t)u * (t - 1) + l) * R * R;
+            run += Spart[base + e];
+            const bf16_t hi = f32_to_bf16(run);
+            Shi[base + dst] = hi;
+            Slo[base + dst] = f32_to_bf16(run - bf16_to_f32(hi));
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Running prefix state.  Workgroup = (unit, group of AG = NA * 4 / NB sketch rows a); wave =
+// (NA rows a) x (32 columns b') x (all D value columns).  Accumulator tile (a, ct):
+// rows b' (A operand = phi'(k)^T generated in registers), columns c (B operand = V).
+// ------------------------------------------------------------------------------------
+template <int NA, int AI>
+struct GenFrag {
+    // products m_j[a] * m_j[b'] for the 8 tokens of this lane's half; a is broadcast with DPP
+    // from lane 8*(e/4) + AI of each row, which holds tokens 4*(e/4)..+3 of row a0 + AI.
+    static __device__ __forceinline__ bf16x8 run(const f32x4 &af, const f32x8 &bfv)
+    {
+        f32x8 p;
+        p[0] = row_bcast<AI>(af[0]) * bfv[0];
+        p[1] = row_bcast<AI>(af[1]) * bfv[1];
+        p[2] = row_bcast<AI>(af[2]) * bfv[2];
+        p[3] = row_bcast<AI>(af[3]) * bfv[3];
+        p[4] = row_bcast<8 + AI>(af[0]) * bfv[4];
+        p[5] = row_bcast<8 + AI>(af[1]) * bfv[5];
+        p[6] = row_bcast<8 + AI>(af[2]) * bfv[6];
+        p[7] = row_bcast<8 + AI>(af[3]) * bfv[7];
+        return cvt8(p);
+    }
+};
+
+template <int NA, int CT, int AI>
+struct StateStep {
+    static __device__ __forceinline__ void run(const f32x4 &af, const f32x8 &bfv, const bf16x8 *vf,
+                                               f32x16 (*acc)[CT])
+    {
+        const bf16x8 frag = GenFrag<NA, AI>::run(af, bfv);
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) acc[AI][ct] = mfma32(frag, vf[ct], acc[AI][ct]);
+        if constexpr (AI + 1 < NA) StateStep<NA, CT, AI + 1>::run(af, bfv, vf, acc);
+    }
+};
+
+template <int R, int D, int NA>
+__global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
+                                               const bf16_t *__restrict__ V8,
+                                               bf16_t *__restrict__ Zg, int n, int b, int t,
+                                               int units)
+{
+    constexpr int NB = R / 32;                 // 32-wide b' ranges
+    constexpr int AG = NA * 4 / NB;            // sketch rows a per workgroup
+    constexpr int CT = D / 32;
+    constexpr int TC = kStateChunk;
+    constexpr int M_F4 = TC * R / 4;           // float4 units per staged m(K) chunk
+    constexpr int V_U4 = TC * D / 8;           // 16-byte units per staged V chunk
+    static_assert(NA <= 8, "DPP source lanes");
+    __shared__ __attribute__((aligned(16))) float lds_m[2][TC * R];
+    __shared__ __attribute__((aligned(16))) bf16_t lds_v[2][TC * D];
+
+    // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
+    // contiguous range of (unit, group) pairs; the groups of one unit then share one L2.
+    int wg = blockIdx.x;
+    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    constexpr int GROUPS = R / AG;
+    const int u = wg / GROUPS, grp = wg % GROUPS;
+    if (u >= units) return;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int x = lane & 31, h = lane >> 5, n16 = lane & 15;
+    const int bh = wave % NB, ag = wave / NB;
+    const int a0 = grp * AG + ag * NA;
+    const int a_src = a0 + ((n16 & 7) < NA ? (n16 & 7) : NA - 1);
+    const int q_src = n16 >> 3;
+
+    f32x16 acc[NA][CT];
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+        for (int j = 0; j < CT; ++j) acc[i][j] = f32x16{0};
+
+    const f32x4 *gm = (const f32x4 *)(M8 + (size_t)u * n * R);
+    const uint4 *gv = (const uint4 *)(V8 + (size_t)u * n * D);
+    const int chunks = (t - 1) * (b / TC), chunks_per_block = b / TC;
+
+    f32x4 pm[M_F4 / kWg];
+    uint4 pv[V_U4 / kWg];
+    auto fetch = [&](int chunk) {
+#pragma unroll
+        for (int i = 0; i < M_F4 / kWg; ++i) pm[i] = gm[(size_t)chunk * M_F4 + i * kWg + threadIdx.x];
+#pragma unroll
+        for (int i = 0; i < V_U4 / kWg; ++i) pv[i] = gv[(size_t)chunk * V_U4 + i * kWg + threadIdx.x];
+    };
+    auto commit = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < M_F4 / kWg; ++i) ((f32x4 *)lds_m[buf])[i * kWg + threadIdx.x] = pm[i];
+#pragma unroll
+        for (int i = 0; i < V_U4 / kWg; ++i) ((uint4 *)lds_v[buf])[i * kWg + threadIdx.x] = pv[i];
+    };
+
+    if (chunks > 0) { fetch(0); commit(0); }
+    __syncthreads();
+    for (int chunk = 0; chunk < chunks; ++chunk) {
+        const int buf = chunk & 1;
+        if (chunk + 1 < chunks) fetch(chunk + 1);
+        const float *lm = lds_m[buf];
+        const bf16_t *lv = lds_v[buf];
+#pragma unroll
+        for (int s = 0; s < TC / 16; ++s) {
+            const int oct = 2 * s + h;
+            const float *pb = &lm[(oct * R + 32 * bh + x) * 8];
+            const f32x4 b_lo = *(const f32x4 *)pb, b_hi = *(const f32x4 *)(pb + 4);
+            f32x8 bfv;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { bfv[e] = b_lo[e]; bfv[4 + e] = b_hi[e]; }
+            const f32x4 af = *(const f32x4 *)&lm[(oct * R + a_src) * 8 + 4 * q_src];
+            bf16x8 vf[CT];
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) vf[ct] = *(const bf16x8 *)&lv[(oct * D + 32 * ct + x) * 8];
+            StateStep<NA, CT, 0>::run(af, bfv, vf, acc);
+        }
+        if (chunk + 1 < chunks) commit(buf ^ 1);
+        if ((chunk + 1) % chunks_per_block == 0) {
+            // snapshot: Z_{l+1} = sum over blocks 0..l, stored [a][b'/8][c][8] bf16
+            const int l = chunk / chunks_per_block;
+            bf16_t *z = Zg + ((size_t)u * (t - 1) + l) * R * R * D;
+#pragma unroll
+            for (int i = 0; i < NA; ++i)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                    for (int gq = 0; gq < 4; ++gq) {
+                        f32x4 q4 = {acc[i][ct][4 * gq], acc[i][ct][4 * gq + 1], acc[i][ct][4 * gq + 2],
+                                    acc[i][ct][4 * gq + 3]};
+                        const size_t o = 4 * bh + gq;
+                        *(bf16x4 *)&z[(((size_t)(a0 + i) * (R / 8) + o) * D + 32 * ct + x) * 8 + 4 * h] =
+                            cvt4(q4);
+                    }
+        }
+        __syncthreads();
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Output kernel.  Workgroup = 256 consecutive tokens of one block; wave = 64 tokens = TT 32-token
+// tiles.  All accumulators are D^T-oriented: lane = token, registers = value columns.
+// ------------------------------------------------------------------------------------
+template <int R, int D, int P, int TT>
+__global__ __launch_bounds__(kWg) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                             const bf16_t *__restrict__ V8,
+                                             const bf16_t *__restrict__ MQ, const float *__restrict__ MT,
+                                             const bf16_t *__restrict__ Zg,
+                                             const bf16_t *__restrict__ Shi,
+                                             const bf16_t *__restrict__ Slo, bf16_t *__restrict__ O,
+                                             int n, int b, int t)
+{
+    constexpr int CT = D / 32, KS = D / 16, RS = R / 16, AT = R / 32;
+    constexpr int TOK_WAVE = 32 * TT, TOK_WG = 4 * TOK_WAVE;
+    constexpr int KP = D + 8;                             // pitch of staged K rows (bf16)
+    constexpr int ZA = 16384 / (R * D);                   // sketch rows a per staged Z chunk (32 KB)
+    constexpr int Z_PER_A = R * D;                        // bf16 elements of Z for one a
+    constexpr int STAGE_ELEMS = ZA * Z_PER_A > kKeyTile * KP + kKeyTile * D ? ZA * Z_PER_A
+                                                                             : kKeyTile * KP + kKeyTile * D;
+    __shared__ __attribute__((aligned(16))) bf16_t stage[2][STAGE_ELEMS];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int x = lane & 31, h = lane >> 5;
+    const int tiles_per_unit = n / TOK_WG;
+    const int u = blockIdx.x / tiles_per_unit;
+    // late tiles of a block have the most in-block work: hand them out first
+    const int tile = tiles_per_unit - 1 - (blockIdx.x % tiles_per_unit);
+    const int i0 = tile * TOK_WG;                         // first token of the workgroup (in unit)
+    const int l = i0 / b, jb = l * b;
+    const size_t urow = (size_t)u * n;
+    const int tok_w0 = i0 + wave * TOK_WAVE;              // first token of this wave
+
+    f32x16 out[TT][CT];
+    float den[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        den[tt] = 0.f;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) out[tt][ct] = f32x16{0};
+    }
+
+    // ---------------- in-block exact weights (Section 3.2) ----------------
+    {
+        bf16x8 qfr[TT][KS];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                qfr[tt][s] = *(const bf16x8 *)&Q[(urow + tok_w0 + 32 * tt + x) * D + 16 * s + 8 * h];
+
+        bf16_t *ks = stage[0];                            // [kKeyTile][KP]
+        bf16_t *vs = stage[0] + kKeyTile * KP;            // [kKeyTile/8][D][8]
+        for (int j0 = jb; j0 < i0 + TOK_WG; j0 += kKeyTile) {
+            __syncthreads();
+            for (int idx = threadIdx.x; idx < kKeyTile * D / 8; idx += kWg) {
+                const int row = idx / (D / 8), part = idx % (D / 8);
+                *(uint4 *)&ks[row * KP + part * 8] = *(const uint4 *)&K[(urow + j0 + row) * D + part * 8];
+                ((uint4 *)vs)[idx] = ((const uint4 *)(V8 + (urow + j0) * D))[idx];
+            }
+            __syncthreads();
+            if (j0 > tok_w0 + TOK_WAVE - 1) continue;     // every key of this tile is masked
+#pragma unroll
+            for (int sub = 0; sub < kKeyTile / 32; ++sub) {
+                const int key0 = j0 + 32 * sub;
+                bf16x8 kfr[KS];
+#pragma unroll
+                for (int s = 0; s < KS; ++s)
+                    kfr[s] = *(const bf16x8 *)&ks[(32 * sub + x) * KP + 16 * s + 8 * h];
+                // A operand of P V: V^T, k index = key 16s' + 8*(e/4) + 4h + e%4 (matches the
+                // register order of the score tile)
+                bf16x8 vfr[2][CT];
+#pragma unroll
+                for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const int oct = 4 * sub + 2 * sp;
+                        const bf16x4 lo = *(const bf16x4 *)&vs[((oct)*D + 32 * ct + x) * 8 + 4 * h];
+                        const bf16x4 hi = *(const bf16x4 *)&vs[((oct + 1) * D + 32 * ct + x) * 8 + 4 * h];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) { vfr[sp][ct][e] = lo[e]; vfr[sp][ct][4 + e] = hi[e]; }
+                    }
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    const int tok0 = tok_w0 + 32 * tt;
+                    if (key0 > tok0 + 31) continue;       // tile entirely above the diagonal
+                    f32x16 sc = {0};                      // S^T[key][token]
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) sc = mfma32(kfr[s], qfr[tt][s], sc);
+                    const bool diag = key0 + 31 > tok0;
+                    float dsum = 0.f;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        float w = pow_p(sc[v], P);
+                        if (diag) {
+                            const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
+                            w = key <= tok0 + x ? w : 0.f;
+                        }
+                        sc[v] = w;
+                        dsum += w;
+                    }
+                    den[tt] += dsum;
+                    const bf16x8 p0 = cvt8_from16(sc, 0), p1 = cvt8_from16(sc, 8);
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        out[tt][ct] = mfma32(vfr[0][ct], p0, out[tt][ct]);
+                        out[tt][ct] = mfma32(vfr[1][ct], p1, out[tt][ct]);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---------------- cross-block term phi'(Q_l) Z_l (Section 3.1) ----------------
+    if (l > 0) {
+        bf16x8 mfr[TT][RS];                               // B operands: m(q_i), k index = b'
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int s = 0; s < RS; ++s)
+                mfr[tt][s] = *(const bf16x8 *)&MQ[(urow + tok_w0 + 32 * tt + x) * R + 16 * s + 8 * h];
+        const float *mt = MT + (size_t)u * R * n;         // [R][n] fp32
+
+        // denominator: m_i^T S m_i with S = prefix of m_j m_j^T, hi + lo operands
+        {
+            const size_t sbase = ((size_t)u * (t - 1) + (l - 1)) * R * R;
+#pragma unroll
+            for (int at = 0; at < AT; ++at) {
+                f32x16 td[TT];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) td[tt] = f32x16{0};
+#pragma unroll
+                for (int s = 0; s < RS; ++s) {
+                    const size_t off = sbase + ((size_t)(2 * s + h) * R + 32 * at + x) * 8;
+                    const bf16x8 s_hi = *(const bf16x8 *)&Shi[off], s_lo = *(const bf16x8 *)&Slo[off];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        td[tt] = mfma32(s_hi, mfr[tt][s], td[tt]);
+                        td[tt] = mfma32(s_lo, mfr[tt][s], td[tt]);
+                    }
+                }
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int a = 32 * at + 8 * (v / 4) + 4 * h + (v % 4);
+                        den[tt] += mt[(size_t)a * n + tok_w0 + 32 * tt + x] * td[tt][v];
+                    }
+            }
+        }
+
+        // numerator: for every a, T_a = Z_l[a]^T m_i (D x tokens), out += m_i[a] * T_a
+        const uint4 *zsrc = (const uint4 *)(Zg + ((size_t)u * (t - 1) + (l - 1)) * R * R * D);
+        constexpr int CHUNK_U4 = ZA * Z_PER_A / 8;        // 16-byte units per staged chunk
+        constexpr int NCHUNK = R / ZA;
+        uint4 pre[CHUNK_U4 / kWg];
+        auto fetch = [&](int chunk) {
+#pragma unroll
+            for (int i = 0; i < CHUNK_U4 / kWg; ++i) pre[i] = zsrc[(size_t)chunk * CHUNK_U4 + i * kWg + threadIdx.x];
+        };
+        auto commit = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < CHUNK_U4 / kWg; ++i) ((uint4 *)stage[buf])[i * kWg + threadIdx.x] = pre[i];
+        };
+        __syncthreads();                                  // in-block staging is done with stage[0]
+        fetch(0);
+        commit(0);
+        __syncthreads();
+        for (int chunk = 0; chunk < NCHUNK; ++chunk) {
+            const int buf = chunk & 1;
+            if (chunk + 1 < NCHUNK) fetch(chunk + 1);
+#pragma unroll
+            for (int ai = 0; ai < ZA; ++ai) {
+                const int a = chunk * ZA + ai;
+                const bf16_t *za = stage[buf] + ai * Z_PER_A;      // [R/8][D][8]
+                float mq[TT];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) mq[tt] = mt[(size_t)a * n + tok_w0 + 32 * tt + x];
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    bf16x8 zf[RS];
+#pragma unroll
+                    for (int s = 0; s < RS; ++s)
+                        zf[s] = *(const bf16x8 *)&za[((2 * s + h) * D + 32 * ct + x) * 8];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        f32x16 tacc = {0};
+#pragma unroll
+                        for (int s = 0; s < RS; ++s) tacc = mfma32(zf[s], mfr[tt][s], tacc);
+                        out[tt][ct] += mq[tt] * tacc;
+                    }
+                }
+            }
+            if (chunk + 1 < NCHUNK) commit(buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // ---------------- normalise and store (Section 3: divide by 1 + sum of weights) ----------------
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const float total = den[tt] + __shfl_xor(den[tt], 32);   // the two halves hold different keys / rows
+        const float inv = 1.0f / (1.0f + total);
+        const size_t row = urow + tok_w0 + 32 * tt + x;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                f32x4 q4 = {out[tt][ct][4 * gq] * inv, out[tt][ct][4 * gq + 1] * inv,
+                            out[tt][ct][4 * gq + 2] * inv, out[tt][ct][4 * gq + 3] * inv};
+                *(bf16x4 *)&O[row * D + 32 * ct + 8 * gq + 4 * h] = cvt4(q4);
+            }
+    }
+}
+
+struct MfmaWs {
+    bf16_t *MQ; float *MT; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
+    size_t total;
+};
+
+MfmaWs carve(const Problem &pb, void *ws)
+{
+    MfmaWs w;
+    const size_t rows = (size_t)pb.units * pb.n, R = pb.r, D = pb.d, tb = pb.t > 1 ? pb.t - 1 : 0;
+    size_t off = 0;
+    char *base = (char *)ws;
+    auto take = [&](size_t bytes) { char *p = base + off; off += align_up(bytes, 256); return p; };
+    w.MQ = (bf16_t *)take(rows * R * 2);
+    w.MT = (float *)take(rows * R * 4);
+    w.MK8 = (float *)take(rows * R * 4);
+    w.V8 = (bf16_t *)take(rows * D * 2);
+    w.Zg = (bf16_t *)take((size_t)pb.units * tb * R * R * D * 2);
+    w.Spart = (float *)take((size_t)pb.units * tb * R * R * 4);
+    w.Shi = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
+    w.Slo = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
+    w.total = off;
+    return w;
+}
+
+int sketch_tiles_per_wg(int n)
+{
+    int tiles = 8;
+    while (n % (tiles * 128) != 0) tiles /= 2;
+    return tiles;
+}
+
+template <int D, int R, int P>
+psf_status launch_sketch(const Problem &pb, const void *X, const void *G, bool qside, bf16_t *M_rm,
+                         float *MT, float *M8, hipStream_t s)
+{
+    const int tiles = sketch_tiles_per_wg(pb.n);
+    const unsigned grid = (unsigned)((size_t)pb.units * pb.n / (128 * (size_t)tiles));
+    if (qside)
+        hipLaunchKernelGGL((k_sketch<D, R, P, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)X,
+                           (const bf16_t *)G, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles,
+                           M_rm, MT, M8);
+    else
+        hipLaunchKernelGGL((k_sketch<D, R, P, false>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)X,
+                           (const bf16_t *)G, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles,
+                           M_rm, MT, M8);
+    PSF_LAUNCH_CHECK();
+    return PSF_OK;
+}
+
+template <int D, int R, int P>
+psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+                     void *O, void *ws, hipStream_t s, StageTimer *tm)
+{
+    MfmaWs w = carve(pb, ws);
+    psf_status st = launch_sketch<D, R, P>(pb, Q, G, true, w.MQ, w.MT, nullptr, s);
+    if (st != PSF_OK) return st;
+    st = launch_sketch<D, R, P>(pb, K, G, false, nullptr, nullptr, w.MK8, s);
+    if (st != PSF_OK) return st;
+    {
+        const size_t octets = (size_t)pb.units * pb.n / 8;
+        hipLaunchKernelGGL((k_v_octets<D>), dim3((unsigned)((octets * D + kWg - 1) / kWg)), dim3(kWg), 0,
+                           s, (const bf16_t *)V, w.V8, octets);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    if (pb.t > 1) {
+        hipLaunchKernelGGL((k_den_partial<R>), dim3(pb.t - 1, pb.units), dim3(kWg), 0, s, w.MK8, w.Spart,
+                           pb.n, pb.b, pb.t);
+        PSF_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_den_scan<R>), dim3(pb.units), dim3(kWg), 0, s, w.Spart, w.Shi, w.Slo, pb.t);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    if (pb.t > 1) {
+        constexpr int NA = (D == 64) ? 4 : 2;
+        constexpr int AG = NA * 4 / (R / 32);
+        const unsigned grid = (unsigned)(pb.units * (R / AG));
+        hipLaunchKernelGGL((k_state<R, D, NA>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg, pb.n, pb.b,
+                           pb.t, pb.units);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    {
+        constexpr int TT = 2;
+        const unsigned grid = (unsigned)((size_t)pb.units * (pb.n / kTokWg));
+        hipLaunchKernelGGL((k_out<R, D, P, TT>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
+                           (const bf16_t *)K, w.V8, w.MQ, w.MT, w.Zg, w.Shi, w.Slo, (bf16_t *)O, pb.n, pb.b,
+                           pb.t);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    return PSF_OK;
+}
+
+template <int D, int R, int P>
+psf_status sketch_impl(const Problem &pb, const void *X, const void *G, void *M_out, hipStream_t s)
+{
+    return launch_sketch<D, R, P>(pb, X, G, true, (bf16_t *)M_out, nullptr, nullptr, s);
+}
+
+}  // namespace
+
+size_t mfma_workspace_bytes(const Problem &pb) { return carve(pb, nullptr).total; }
+
+#define PSF_DISPATCH(CALL)                                                   \
+    do {                                                                     \
+        if (pb.d == 64 && pb.r == 64 && pb.p == 4) return CALL(64, 64, 4);   \
+        if (pb.d == 64 && pb.r == 32 && pb.p == 4) return CALL(64, 32, 4);   \
+        if (pb.d == 64 && pb.r == 64 && pb.p == 8) return CALL(64, 64, 8);   \
+        if (pb.d == 64 && pb.r == 32 && pb.p == 8) return CALL(64, 32, 8);   \
+        if (pb.d == 128 && pb.r == 64 && pb.p == 4) return CALL(128, 64, 4); \
+        if (pb.d == 128 && pb.r == 32 && pb.p == 4) return CALL(128, 32, 4); \
+        if (pb.d == 128 && pb.r == 64 && pb.p == 8) return CALL(128, 64, 8); \
+        if (pb.d == 128 && pb.r == 32 && pb.p == 8) return CALL(128, 32, 8); \
+        return PSF_ERR_UNSUPPORTED;                                          \
+    } while (0)
+
+psf_status mfma_sketch(const Problem &pb, const void *X, const void *G, void *M_out, void *Phi_out,
+                       hipStream_t s)
+{
+    if (Phi_out || !M_out) return PSF_ERR_UNSUPPORTED;
+#define PSF_SK(D_, R_, P_) (sketch_impl<D_, R_, P_>(pb, X, G, M_out, s))
+    PSF_DISPATCH(PSF_SK);
+#undef PSF_SK
+}
+
+psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+                     void *O, void *ws, hipStream_t s, StageTimer *tm)
+{
+#define PSF_AT(D_, R_, P_) (attn_impl<D_, R_, P_>(pb, Q, K, V, G, O, ws, s, tm))
+    PSF_DISPATCH(PSF_AT);
+#undef PSF_AT
+}
+
+}  // namespace psf

@@ -52,3 +52,25 @@ def oracle_attn(cfg, q, k, v, G, feat=oracle.FEAT_SKETCH, local=oracle.LOCAL_EXA
                                  cfg["p"], cfg["r"], cfg["b"] if b is None else b,
                                  feat=feat, local=local, rows=rows)
     return O
+
+
+def oracle_units_rows(cfg, q, k, v, G, units, rows, local=oracle.LOCAL_EXACT, b=None):
+    """Oracle rows `rows` of the listed (batch, head) units -> {(bi, h): [len(rows), dv]}."""
+    out = {}
+    for bi, h in units:
+        g = G[h if G.shape[0] > 1 else 0]
+        out[(bi, h)] = oracle.attn_def(as_f64(q[bi, h]), as_f64(k[bi, h]), as_f64(v[bi, h]), as_f64(g),
+                                       cfg["p"], cfg["r"], cfg["b"] if b is None else b,
+                                       local=local, rows=rows)
+    return out
+
+
+def probe_rows(n, b, extra=24, seed=0):
+    """Rows that exercise every regime: first/last of the sequence and of blocks, tile edges,
+    plus a seeded random sample."""
+    rng = np.random.default_rng(seed)
+    fixed = {0, 1, 31, 32, 63, 64, 255, 256, b - 1, n - 1, n - b, n - b - 1, n // 2, n // 2 - 1}
+    if n > b:
+        fixed |= {b, b + 1, 2 * b - 1}
+    fixed |= set(int(x) for x in rng.integers(0, n, size=extra))
+    return sorted(x for x in fixed if 0 <= x < n)

@@ -1,0 +1,113 @@
+"""GPU parity of the bf16 MFMA path against the float64 oracle (through the C ABI).
+The oracle consumes the same bf16-rounded inputs upcast to float64; tolerance 2e-2 on both
+max-abs and relative Frobenius error."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2310_01655_amd import binding as psf
+from paper_2310_01655_amd import inputs
+from parity import as_f64, assert_close, errors, gpu_attn, oracle_attn, oracle_units_rows, probe_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def mk(batch, heads, n, d, p, r, b, per_head=False, dist="normal"):
+    return dict(batch=batch, heads=heads, n=n, d=d, p=p, r=r, b=b, dtype="bf16", per_head=per_head,
+                dist=dist)
+
+
+def draw(cfg, seed=17):
+    q, k, v = inputs.make_qkv(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], seed=seed,
+                              dist=cfg["dist"], dtype="bf16")
+    G = inputs.make_sketch_matrices(cfg["heads"], cfg["d"], cfg["r"], cfg["p"],
+                                    per_head=cfg["per_head"], seed=0, dtype="bf16")
+    return q, k, v, G
+
+
+@pytest.mark.parametrize("d,p,r,b", [(64, 4, 64, 256), (64, 4, 32, 256), (64, 4, 64, 512),
+                                     (128, 8, 64, 256), (128, 4, 32, 256), (64, 8, 32, 512)])
+def test_small_full_parity(d, p, r, b):
+    cfg = mk(1, 2, 1024, d, p, r, b, per_head=True)
+    q, k, v, G = draw(cfg)
+    got, desc = gpu_attn(cfg, q, k, v, G)
+    assert psf.kernel_path(desc) == 1
+    want = oracle_attn(cfg, q, k, v, G)
+    print("small", (d, p, r, b), assert_close(got.numpy(), want, "bf16", "d=%d p=%d r=%d b=%d" % (d, p, r, b)))
+
+
+@pytest.mark.parametrize("d,p,r", [(64, 4, 64), (64, 4, 32), (128, 8, 64), (64, 8, 64)])
+def test_sketch_entry_point(d, p, r):
+    cfg = mk(2, 3, 512, d, p, r, 256, per_head=True)
+    q, _, _, G = draw(cfg)
+    desc = psf.make_desc(2, 3, 512, d, p, r, 256, "bf16", per_head=True)
+    M, _ = psf.psf_sketch(desc, q.cuda(), G.cuda())
+    torch.cuda.synchronize()
+    for bi in range(2):
+        for h in range(3):
+            want = oracle.sketch(as_f64(q[bi, h]), as_f64(G[h]), r, p)
+            assert_close(M[bi, h].float().cpu().numpy(), want, "bf16", "sketch d=%d p=%d r=%d" % (d, p, r))
+
+
+def test_single_block_fast_path_is_exact_polynomial_attention():
+    cfg = mk(1, 1, 512, 64, 4, 64, 512)
+    q, k, v, G = draw(cfg)
+    got, desc = gpu_attn(cfg, q, k, v, G)
+    assert psf.kernel_path(desc) == 1
+    Q, K, V = as_f64(q)[0, 0], as_f64(k)[0, 0], as_f64(v)[0, 0]
+    W = np.tril((Q @ K.T) ** 4)
+    assert_close(got.numpy()[0, 0], (W @ V) / (1.0 + W.sum(1, keepdims=True)), "bf16", "b = n")
+
+
+def sampled_parity(cfg, q, k, v, G, units, what):
+    got, desc = gpu_attn(cfg, q, k, v, G)
+    assert psf.kernel_path(desc) == 1
+    rows = probe_rows(cfg["n"], cfg["b"])
+    want = oracle_units_rows(cfg, q, k, v, G, units, rows)
+    g = np.stack([got[bi, h].numpy()[rows] for bi, h in units])
+    w = np.stack([want[u] for u in units])
+    res = assert_close(g, w, "bf16", what)
+    # properties that hold at any size: finite, convex-hull bound (weights are non-negative)
+    gn = got.numpy()
+    assert np.isfinite(gn).all()
+    vmax = np.maximum.accumulate(np.abs(v.float().numpy()).max(-1), axis=-1)
+    assert (np.abs(gn).max(-1) <= vmax * 1.01 + 1e-3).all()
+    print(what, res)
+    return got
+
+
+def test_config2_sampled_rows_all_heads():
+    cfg, q, k, v, G = inputs.make_config(2)
+    units = [(bi, h) for bi in (0, 7) for h in range(cfg["heads"])]
+    sampled_parity(cfg, q, k, v, G, units, "config 2")
+
+
+def test_config3_headline_sampled_rows():
+    cfg, q, k, v, G = inputs.make_config(3)
+    units = [(0, h) for h in range(0, cfg["heads"], 3)] + [(1, 11)]
+    sampled_parity(cfg, q, k, v, G, units, "config 3")
+
+
+@pytest.mark.parametrize("variant", [None, "heavy"])
+def test_config5_sampled_rows(variant):
+    cfg, q, k, v, G = inputs.make_config(5, variant=variant)
+    units = [(0, 0), (0, 7), (0, 15)]
+    sampled_parity(cfg, q, k, v, G, units, "config 5 %s" % variant)
+
+
+@pytest.mark.parametrize("n,r,b", [(8192, 32, 256), (16384, 64, 512), (65536, 64, 1024), (65536, 32, 256)])
+def test_config4_sweep_points_reduced_batch(n, r, b):
+    # sweep shapes at 2 batch entries instead of 2^20/n (units are independent; the full batch
+    # is what bench.py --workload sweep times)
+    cfg = mk(2, 12, n, 64, 4, r, b)
+    q, k, v, G = draw(cfg, seed=1004)
+    sampled_parity(cfg, q, k, v, G, [(0, 0), (1, 11)], "config 4 n=%d r=%d b=%d" % (n, r, b))
+
+
+def test_deterministic_across_runs():
+    cfg = mk(1, 2, 2048, 64, 4, 64, 512)
+    q, k, v, G = draw(cfg)
+    a, _ = gpu_attn(cfg, q, k, v, G)
+    b2, _ = gpu_attn(cfg, q, k, v, G)
+    assert torch.equal(a, b2)
