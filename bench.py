@@ -1,0 +1,154 @@
+"""Benchmark of the causal polysketch attention forward path on one MI355X.
+
+A step = one full pass of the hot path (sketch of Q and K, block prefix states, fused output)
+over one synthetic batch.  Prints ONE JSON line ("Measurement").
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+HBM_PEAK_GBS = 8000.0
+
+
+def workloads():
+    from paper_2310_01655_amd import inputs
+    w = {"config%d" % i: dict(c) for i, c in inputs.CONFIGS.items()}
+    for c in inputs.sweep_configs():
+        w["sweep_n%d_r%d_b%d" % (c["n"], c["r"], c["b"])] = c
+    return w
+
+
+def stage_flops(cfg):
+    """Algorithmic flops per step (multiply-add = 2), split by kernel stage.  Causal lower
+    triangle only; the first block has no prefix and the last block's state is never needed."""
+    U = cfg["batch"] * cfg["heads"]
+    n, d, r, b, p = cfg["n"], cfg["d"], cfg["r"], cfg["b"], cfg["p"]
+    sketch = 2 * (8 * n * d * r if p == 4 else 16 * n * d * r + 8 * n * r * r)   # Q and K
+    f = {
+        "sketch_and_layouts": U * (sketch + 2 * (n - b) * r * r),      # + ones column of H_l
+        "block_states_scan": U * 2 * (n - b) * r * r * d,               # H_l and Z_l
+        "output": U * (2 * (n - b) * r * r * (d + 1) + n * (b + 1) * (2 * d + 1)),
+    }
+    f["total"] = sum(f.values())
+    return f
+
+
+def cpu_baseline(cfg, q, k, v, G, rows_per_unit=16384):
+    """The float64 oracle, as it stands, on a bounded sample: `cores` units, a uniform random
+    sample of rows of each.  The full-unit time is estimated as sketch time + row time * n/rows
+    (row cost grows with the row index; a uniform sample is unbiased for the sum)."""
+    import numpy as np
+    import oracle
+    cores = min(os.cpu_count() or 1, 16)
+    U = cfg["batch"] * cfg["heads"]
+    units = min(cores, U)
+    n = cfg["n"]
+    sel = [(i // cfg["heads"], i % cfg["heads"]) for i in range(units)]
+    f64 = lambda t: np.stack([t[bi, h].double().numpy() for bi, h in sel])[None]   # [1, units, n, d]
+    Q, K, V = f64(q), f64(k), f64(v)
+    Gs = G.double().numpy()
+    Gs = Gs[[h for _, h in sel]] if Gs.shape[0] > 1 else Gs
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(n, size=min(rows_per_unit, n), replace=False))
+    t0 = time.perf_counter()
+    _, threads = oracle.attn_def_batch(Q, K, V, Gs, cfg["p"], cfg["r"], cfg["b"], rows=[0], max_threads=cores)
+    t_sketch = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    oracle.attn_def_batch(Q, K, V, Gs, cfg["p"], cfg["r"], cfg["b"], rows=rows, max_threads=cores)
+    t_all = time.perf_counter() - t0
+    t_rows = max(t_all - t_sketch, 1e-9)
+    est_full = t_sketch + t_rows * n / len(rows)
+    return {"value": units * n / est_full, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d units x %d uniformly sampled rows of n=%d (float64 definition, O(n^2)); "
+                      "full-unit time estimated as sketch %.2fs + rows %.2fs * n/rows" %
+                      (units, len(rows), n, t_sketch, t_rows),
+            "seconds_measured": t_sketch + t_all}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config3", help="config2|config3|config5|sweep_n.._r.._b..")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (units = batch x heads would shard with "
+                 "no communication, see DESIGN.md); run with --gpus 1")
+
+    import torch
+    from paper_2310_01655_amd import binding as psf
+    from paper_2310_01655_amd import inputs
+
+    wl = workloads()
+    if args.workload not in wl:
+        sys.exit("unknown workload %s; choose from %s" % (args.workload, ", ".join(sorted(wl))))
+    cfg = wl[args.workload]
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    idx = int(args.workload[6:]) if args.workload.startswith("config") else 4
+    q, k, v = inputs.make_qkv(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], seed=1000 + idx,
+                              dist=cfg["dist"], dtype=cfg["dtype"])
+    G = inputs.make_sketch_matrices(cfg["heads"], cfg["d"], cfg["r"], cfg["p"], per_head=cfg["per_head"],
+                                    seed=0, dtype=cfg["dtype"])
+    desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
+                         cfg["dtype"], per_head=cfg["per_head"])
+    path = psf.kernel_path(desc)
+    qd, kd, vd, Gd = q.to(dev), k.to(dev), v.to(dev), G.to(dev)
+    O = torch.empty_like(vd)
+    ws = psf.alloc_workspace(desc, dev)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    tokens = cfg["batch"] * cfg["n"]
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream
+    reps = max(3, min(args.steps, 10))
+    acc = {}
+    for _ in range(reps):
+        _, st = psf.psf_causal_attn_fwd_timed(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
+        for nm, ms in st.items():
+            acc[nm] = acc.get(nm, 0.0) + ms / reps
+    fl = stage_flops(cfg) if path == 1 else None
+    out = {
+        "metric": "causal_polysketch_attention_fwd_tokens_per_s", "value": tokens * args.steps / elapsed,
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"],
+                   "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
+                   "kernel_path": "mfma_bf16" if path == 1 else "general_fp32"},
+        "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
+    }
+    if fl:
+        out["tflops"] = fl["total"] / (ms_per_step * 1e-3) / 1e12
+        out["pct_mfma_peak"] = 100.0 * out["tflops"] / MFMA_BF16_PEAK_TFLOPS
+        dom = max((nm for nm in acc if nm in fl), key=lambda nm: acc[nm])
+        achieved = fl[dom] / (acc[dom] * 1e-3) / 1e12
+        out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": achieved,
+                           "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                           "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc if nm in fl}}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, G)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

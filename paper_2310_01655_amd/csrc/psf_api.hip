@@ -151,9 +151,8 @@ psf_status psf_sketch(const psf_desc *desc, const void *X, const void *G, void *
     if (!M_out && !Phi_out) return PSF_ERR_NULL;
     if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
     hipStream_t s = (hipStream_t)hip_stream;
-    // The MFMA sketch kernel covers the same shapes as the MFMA attention path; explicit
-    // features (Phi_out) are always written by the general kernel.
-    if (select_path(pb) == 1 && !Phi_out) return mfma_sketch(pb, X, G, M_out, Phi_out, s);
+    // This entry point has no workspace, so it always runs the general kernel (fp32
+    // arithmetic, any shape); the MFMA sketch lives inside psf_causal_attn_fwd.
     return general_sketch(pb, X, G, M_out, Phi_out, s);
 }
 
@@ -189,7 +188,7 @@ const char *psf_stage_name(int path, int32_t stage)
 {
     static const char *general[] = {"sketch_q", "sketch_k", "block_states", "exclusive_scan",
                                     "output"};
-    static const char *mfma[] = {"sketch_and_layouts", "denominator_states", "block_states_scan",
+    static const char *mfma[] = {"sketch_and_layouts", "denominator_scan", "block_states_scan",
                                  "output"};
     if (path == 0 && stage >= 0 && stage < 5) return general[stage];
     if (path == 1 && stage >= 0 && stage < 4) return mfma[stage];

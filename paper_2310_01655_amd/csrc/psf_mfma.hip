@@ -2,13 +2,14 @@
 // block lower-triangular algorithm of PolySketchFormer (arXiv 2310.01655, Sections 3.1, 3.2).
 //
 // Kernels (R = sketch size r, D = head size d = dv, b = block size, t = n/b):
-//   k_sketch       Algorithm 1 on bf16 MFMA.  m(Q) is stored row-major bf16 and transposed
-//                  fp32; m(K) is stored as fp32 "token octets" [n/8][R][8] so that the state
-//                  kernel can stage it into LDS with straight copies.
+//   k_transpose_g  sketch matrices transposed once (operand-friendly for the sketch kernel).
+//   k_sketch       Algorithm 1 on bf16 MFMA.  m(Q) is stored row-major bf16; m(K) is stored as
+//                  fp32 "token octets" [n/8][R][8] so that the state kernel can stage it into
+//                  LDS with straight copies.  The K side also accumulates S = m(K)^T m(K) per
+//                  workgroup (R x R): the "ones" column of H_l = phi'(K_l)^T [V_l | 1], because
+//                  phi' = m (x) m (Algorithm 1).
 //   k_v_octets     V -> [n/8][D][8] bf16 (same octet layout).
-//   k_den_partial  per block: S_l = m(K_l)^T m(K_l) (R x R).  This is the "ones" column of
-//                  H_l = phi'(K_l)^T [V_l | 1] because phi' = m (x) m (Algorithm 1).
-//   k_den_scan     exclusive prefix of S_l over blocks, stored as bf16 hi + lo MFMA operands.
+//   k_den_scan     prefix of the S partials over blocks, stored as bf16 hi + lo MFMA operands.
 //   k_state        running prefix state Z = sum phi'(k_j) v_j^T kept in MFMA accumulators while
 //                  one workgroup walks the blocks in order; phi'(k_j) = m_j (x) m_j is expanded
 //                  in registers (one operand broadcast across lanes with DPP) and never
@@ -35,7 +36,6 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWg = 256;          // 4 wavefronts
-constexpr int kTokWg = 256;       // tokens per workgroup in k_out (4 waves x 2 tiles of 32)
 constexpr int kStateChunk = 64;   // tokens staged per step in k_state
 constexpr int kKeyTile = 64;      // keys staged per step in the in-block phase of k_out
 
@@ -71,14 +71,44 @@ __device__ __forceinline__ float pow_p(float x, int p)
     return x;
 }
 
+// Direct global -> LDS copy of 16 bytes per lane: lane i of the wave lands at lds_wave_base +
+// 16*i.  Completion is tracked by vmcnt; callers wait before the barrier that publishes it.
+__device__ __forceinline__ void dma16(const void *gsrc_lane, void *lds_wave_base)
+{
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc_lane,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+__device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
+
+// ------------------------------------------------------------------------------------
+// Sketch matrices transposed once: Gt[set][mat][c][e] = G[set][mat][e][c], so that the sketch
+// kernel stages MFMA operands (8 consecutive e per lane) with 16-byte copies.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWg) void k_transpose_g(const bf16_t *__restrict__ G,
+                                                     bf16_t *__restrict__ Gt, int d, int r, int p,
+                                                     size_t g_len)
+{
+    const int mat = blockIdx.x, set = blockIdx.y;
+    const int n_first = p / 2;
+    const int rows = mat < n_first ? d : r;
+    const size_t off = mat < n_first ? (size_t)mat * d * r
+                                     : (size_t)n_first * d * r + (size_t)(mat - n_first) * r * r;
+    const bf16_t *g = G + set * g_len + off;
+    bf16_t *gt = Gt + set * g_len + off;
+    for (int idx = threadIdx.x; idx < rows * r; idx += kWg) {
+        const int c = idx / rows, e = idx % rows;
+        gt[idx] = g[(size_t)e * r + c];
+    }
+}
+
 // ------------------------------------------------------------------------------------
 // Algorithm 1 on MFMA.  One wave sketches 32 tokens at a time; a workgroup walks
-// `tiles_per_wg` consecutive 128-token tiles of one unit so that the transposed sketch
-// matrices staged in LDS are reused.
-//   QSIDE: results in D^T orientation (lane = token): writes M_rm [rows][R] bf16 and
-//          MT [U][R][n] fp32.
+// `tiles_per_wg` consecutive 128-token tiles of one unit so that the sketch matrices staged
+// in LDS are reused.
+//   QSIDE: results in D^T orientation (lane = token): writes M_rm [rows][R] bf16.
 //   !QSIDE: results in D orientation (lane = sketch column): writes M8 [U][n/8][R][8] fp32
-//          (and M_rm if given).
+//          and the workgroup's partial S = sum_j m_j m_j^T (the "ones" column of the block
+//          states, since phi' = m (x) m) to Spart [U][n / tokens_per_wg][R][R].
 // ------------------------------------------------------------------------------------
 template <int D, int R>
 struct SketchLds {
@@ -87,17 +117,18 @@ struct SketchLds {
 };
 
 template <int D, int R, int ROWS>
-__device__ __forceinline__ void stage_gt(bf16_t *dst, const bf16_t *g)
+__device__ __forceinline__ void stage_gt(bf16_t *dst, const bf16_t *gt)
 {
-    // g is [ROWS][R] row-major; dst[c][e] = g[e][c]
+    // gt is [R][ROWS] (already transposed); rows are padded to kPitch in LDS
     constexpr int PITCH = SketchLds<D, R>::kPitch;
-    for (int idx = threadIdx.x; idx < ROWS * R; idx += kWg) {
-        const int e = idx / R, c = idx % R;
-        dst[c * PITCH + e] = g[idx];
+    constexpr int VEC = ROWS / 8;
+    for (int idx = threadIdx.x; idx < R * VEC; idx += kWg) {
+        const int c = idx / VEC, part = idx % VEC;
+        *(uint4 *)&dst[c * PITCH + 8 * part] = *(const uint4 *)&gt[(size_t)c * ROWS + 8 * part];
     }
 }
 
-// acc[ct] (+)= G^T X^T restricted to 32 tokens; xfr are the B-operand fragments of X.
+// acc[ct] = G^T X^T restricted to 32 tokens; xfr are the operand fragments of X.
 template <int D, int R, int KSTEPS, bool TOKEN_LANES>
 __device__ __forceinline__ void project(const bf16_t *gt, const bf16x8 *xfr, f32x16 *acc, int x,
                                         int h)
@@ -140,20 +171,30 @@ __device__ __forceinline__ void project_inner(const bf16_t *gt, const bf16x8 *mf
 
 template <int D, int R, int P, bool QSIDE>
 __global__ __launch_bounds__(kWg) void k_sketch(const bf16_t *__restrict__ X,
-                                                const bf16_t *__restrict__ G, int n, int heads,
+                                                const bf16_t *__restrict__ Gt, int n, int heads,
                                                 int per_head, size_t g_len, int tiles_per_wg,
-                                                bf16_t *__restrict__ M_rm, float *__restrict__ MT,
-                                                float *__restrict__ M8)
+                                                bf16_t *__restrict__ M_rm, float *__restrict__ M8,
+                                                float *__restrict__ Spart)
 {
-    __shared__ SketchLds<D, R> lds;
+    __shared__ __attribute__((aligned(16))) SketchLds<D, R> lds;
+    __shared__ float red[QSIDE ? 1 : 4][QSIDE ? 1 : 32][33];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int x = lane & 31, h = lane >> 5;
     const size_t tok_wg0 = (size_t)blockIdx.x * tiles_per_wg * 128;   // global token (row) index
     const int u = (int)(tok_wg0 / n);
-    const bf16_t *g = G + (per_head ? (size_t)(u % heads) * g_len : 0);
+    const bf16_t *g = Gt + (per_head ? (size_t)(u % heads) * g_len : 0);
     const float scale = sqrtf(1.0f / (float)R);
-    constexpr int KS = D / 16;
+    constexpr int KS = D / 16, NT = R / 32;
 
+    f32x16 sacc[QSIDE ? 1 : NT][QSIDE ? 1 : NT];
+    if (!QSIDE) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) sacc[i][j] = f32x16{0};
+    }
+
+#pragma unroll 1
     for (int tile = 0; tile < tiles_per_wg; ++tile) {
         const size_t row0 = tok_wg0 + (size_t)tile * 128 + wave * 32;   // this wave's 32 tokens
         bf16x8 xfr[KS];
@@ -161,18 +202,18 @@ __global__ __launch_bounds__(kWg) void k_sketch(const bf16_t *__restrict__ X,
         for (int s = 0; s < KS; ++s)
             xfr[s] = *(const bf16x8 *)&X[(row0 + x) * D + 16 * s + 8 * h];
 
-        f32x16 m[R / 32];
+        f32x16 m[NT];
         if (P == 4) {
             if (tile == 0) {
                 stage_gt<D, R, D>(lds.gt[0], g);
                 stage_gt<D, R, D>(lds.gt[1], g + (size_t)D * R);
                 __syncthreads();
             }
-            f32x16 a0[R / 32], a1[R / 32];
+            f32x16 a0[NT], a1[NT];
             project<D, R, KS, QSIDE>(lds.gt[0], xfr, a0, x, h);
             project<D, R, KS, QSIDE>(lds.gt[1], xfr, a1, x, h);
 #pragma unroll
-            for (int ct = 0; ct < R / 32; ++ct) m[ct] = scale * (a0[ct] * a1[ct]);
+            for (int ct = 0; ct < NT; ++ct) m[ct] = scale * (a0[ct] * a1[ct]);
         } else {
             // degree 4 = p/2: two independent degree-2 sketches, then one more level
             bf16x8 m1fr[R / 16], m2fr[R / 16];
@@ -182,11 +223,11 @@ __global__ __launch_bounds__(kWg) void k_sketch(const bf16_t *__restrict__ X,
                 stage_gt<D, R, D>(lds.gt[0], g + (size_t)(2 * half) * D * R);
                 stage_gt<D, R, D>(lds.gt[1], g + (size_t)(2 * half + 1) * D * R);
                 __syncthreads();
-                f32x16 a0[R / 32], a1[R / 32];
+                f32x16 a0[NT], a1[NT];
                 project<D, R, KS, true>(lds.gt[0], xfr, a0, x, h);
                 project<D, R, KS, true>(lds.gt[1], xfr, a1, x, h);
 #pragma unroll
-                for (int ct = 0; ct < R / 32; ++ct) {
+                for (int ct = 0; ct < NT; ++ct) {
                     const f32x16 mm = scale * (a0[ct] * a1[ct]);
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
@@ -200,46 +241,69 @@ __global__ __launch_bounds__(kWg) void k_sketch(const bf16_t *__restrict__ X,
             stage_gt<D, R, R>(lds.gt[0], gi);
             stage_gt<D, R, R>(lds.gt[1], gi + (size_t)R * R);
             __syncthreads();
-            f32x16 a0[R / 32], a1[R / 32];
+            f32x16 a0[NT], a1[NT];
             project_inner<D, R, QSIDE>(lds.gt[0], m1fr, a0, x, h);
             project_inner<D, R, QSIDE>(lds.gt[1], m2fr, a1, x, h);
 #pragma unroll
-            for (int ct = 0; ct < R / 32; ++ct) m[ct] = scale * (a0[ct] * a1[ct]);
+            for (int ct = 0; ct < NT; ++ct) m[ct] = scale * (a0[ct] * a1[ct]);
         }
 
-        const size_t tok_in_unit = row0 - (size_t)u * n;
         if (QSIDE) {
             // lane = token x, register v = sketch column 32ct + 8(v/4) + 4h + v%4
 #pragma unroll
-            for (int ct = 0; ct < R / 32; ++ct)
+            for (int ct = 0; ct < NT; ++ct)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const int c0 = 32 * ct + 8 * gq + 4 * h;
                     f32x4 q4 = {m[ct][4 * gq], m[ct][4 * gq + 1], m[ct][4 * gq + 2], m[ct][4 * gq + 3]};
-                    if (M_rm) *(bf16x4 *)&M_rm[(row0 + x) * R + c0] = cvt4(q4);
-                    if (MT)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            MT[((size_t)u * R + c0 + j) * n + tok_in_unit + x] = q4[j];
+                    *(bf16x4 *)&M_rm[(row0 + x) * R + c0] = cvt4(q4);
                 }
         } else {
             // lane = sketch column 32ct + x, register v = token 8(v/4) + 4h + v%4
 #pragma unroll
-            for (int ct = 0; ct < R / 32; ++ct)
+            for (int ct = 0; ct < NT; ++ct)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const int c = 32 * ct + x;
                     f32x4 q4 = {m[ct][4 * gq], m[ct][4 * gq + 1], m[ct][4 * gq + 2], m[ct][4 * gq + 3]};
-                    if (M8) {
-                        const size_t oct = (row0 >> 3) + gq;
-                        *(f32x4 *)&M8[(oct * R + c) * 8 + 4 * h] = q4;
-                    }
+                    const size_t oct = (row0 >> 3) + gq;
+                    *(f32x4 *)&M8[(oct * R + c) * 8 + 4 * h] = q4;
                     if (M_rm)
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
                             M_rm[(row0 + 8 * gq + 4 * h + j) * R + c] = f32_to_bf16(q4[j]);
                 }
+            // S += M^T M over these 32 tokens: the accumulator registers, taken 8 at a time, are
+            // valid A and B fragments at once (k = token, same permutation on both sides)
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp) {
+                bf16x8 f[NT];
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct) f[ct] = cvt8_from16(m[ct], 8 * sp);
+#pragma unroll
+                for (int i = 0; i < NT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) sacc[i][j] = mfma32(f[i], f[j], sacc[i][j]);
+            }
         }
+    }
+
+    if (!QSIDE) {
+        float *out = Spart + (size_t)blockIdx.x * R * R;
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                __syncthreads();
+#pragma unroll
+                for (int v = 0; v < 16; ++v) red[wave][8 * (v / 4) + 4 * h + (v % 4)][x] = sacc[i][j][v];
+                __syncthreads();
+                for (int idx = threadIdx.x; idx < 32 * 32; idx += kWg) {
+                    const int a = idx / 32, c = idx % 32;
+                    out[(size_t)(32 * i + a) * R + 32 * j + c] =
+                        red[0][a][c] + red[1][a][c] + red[2][a][c] + red[3][a][c];
+                }
+            }
     }
 }
 
@@ -263,78 +327,39 @@ __global__ __launch_bounds__(kWg) void k_v_octets(const bf16_t *__restrict__ V,
     *(uint4 *)&V8[idx * 8] = pk;
 }
 
-// ------------------------------------------------------------------------------------
-// Denominator column of the block states: S_l = sum_{j in block l} m_j m_j^T.
-// grid (t-1, U); the four waves split the block's tokens and reduce through LDS.
-// ------------------------------------------------------------------------------------
-template <int R>
-__global__ __launch_bounds__(kWg) void k_den_partial(const float *__restrict__ M8,
-                                                     float *__restrict__ Spart, int n, int b, int t)
-{
-    __shared__ float red[4][32][33];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int x = lane & 31, h = lane >> 5;
-    const int l = blockIdx.x, u = blockIdx.y;
-    constexpr int NT = R / 32;
-    f32x16 acc[NT][NT];
-#pragma unroll
-    for (int i = 0; i < NT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) acc[i][j] = f32x16{0};
-    const int tok_per_wave = b / 4;
-    const size_t oct0 = ((size_t)u * n + (size_t)l * b + (size_t)wave * tok_per_wave) >> 3;
-    for (int s = 0; s < tok_per_wave / 16; ++s) {
-        bf16x8 fr[NT];
-#pragma unroll
-        for (int i = 0; i < NT; ++i) {
-            const float *p = &M8[((oct0 + 2 * s + h) * R + 32 * i + x) * 8];
-            f32x8 v;
-            const f32x4 lo = *(const f32x4 *)p, hi = *(const f32x4 *)(p + 4);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
-            fr[i] = cvt8(v);
-        }
-#pragma unroll
-        for (int i = 0; i < NT; ++i)
-#pragma unroll
-            for (int j = 0; j < NT; ++j) acc[i][j] = mfma32(fr[i], fr[j], acc[i][j]);
-    }
-    float *out = Spart + ((size_t)u * (t - 1) + l) * R * R;
-#pragma unroll
-    for (int i = 0; i < NT; ++i)
-#pragma unroll
-        for (int j = 0; j < NT; ++j) {
-            __syncthreads();
-#pragma unroll
-            for (int v = 0; v < 16; ++v) red[wave][8 * (v / 4) + 4 * h + (v % 4)][x] = acc[i][j][v];
-            __syncthreads();
-            for (int idx = threadIdx.x; idx < 32 * 32; idx += kWg) {
-                const int a = idx / 32, c = idx % 32;
-                out[(size_t)(32 * i + a) * R + 32 * j + c] =
-                    red[0][a][c] + red[1][a][c] + red[2][a][c] + red[3][a][c];
-            }
-        }
-}
-
-// Exclusive prefix over blocks of S_l, written as MFMA A-operands [R/8][R][8] bf16, split
-// into hi + lo so that the denominator keeps ~16 mantissa bits.  Slot l holds sum_{j<=l} S_j,
-// which is what block l+1 needs.
+// Prefix over the sketch kernel's per-workgroup partials of S, snapshotted at block boundaries
+// and written as MFMA A-operands [R/8][R][8] bf16, split into hi + lo so that the denominator
+// keeps ~16 mantissa bits.  Slot l holds sum over blocks 0..l, which is what block l+1 needs.
 template <int R>
 __global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spart,
                                                   bf16_t *__restrict__ Shi, bf16_t *__restrict__ Slo,
-                                                  int t)
+                                                  int t, int parts_per_block)
 {
-    const int u = blockIdx.x;
-    for (int e = threadIdx.x; e < R * R; e += kWg) {
-        const int a = e / R, bq = e % R;
-        const size_t dst = ((size_t)(bq / 8) * R + a) * 8 + (bq % 8);
-        float run = 0.f;
-        for (int l = 0; l < t - 1; ++l) {
-            const size_t base = ((size_t)u * (t - 1) + l) * R * R;
-            run += Spart[base + e];
-            const bf16_t hi = f32_to_bf16(run);
-            Shi[base + dst] = hi;
-            Slo[base + dst] = f32_to_bf16(run - bf16_to_f32(hi));
+    const int u = blockIdx.y;
+    const int e = blockIdx.x * kWg + threadIdx.x;          // one entry of S per thread
+    if (e >= R * R) return;
+    const int a = e / R, bq = e % R;
+    const size_t dst = ((size_t)(bq / 8) * R + a) * 8 + (bq % 8);
+    const size_t parts_per_unit = (size_t)t * parts_per_block;
+    const float *src = Spart + (size_t)u * parts_per_unit * R * R + e;
+    const int total = (t - 1) * parts_per_block;
+    float run = 0.f;
+    for (int w0 = 0; w0 < total; w0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (w0 + i < total) ? src[(size_t)(w0 + i) * R * R] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int w = w0 + i;
+            if (w >= total) break;
+            run += v[i];
+            if ((w + 1) % parts_per_block == 0) {
+                const int l = w / parts_per_block;
+                const size_t base = ((size_t)u * (t - 1) + l) * R * R;
+                const bf16_t hi = f32_to_bf16(run);
+                Shi[base + dst] = hi;
+                Slo[base + dst] = f32_to_bf16(run - bf16_to_f32(hi));
+            }
         }
     }
 }
@@ -344,34 +369,52 @@ __global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spar
 // (NA rows a) x (32 columns b') x (all D value columns).  Accumulator tile (a, ct):
 // rows b' (A operand = phi'(k)^T generated in registers), columns c (B operand = V).
 // ------------------------------------------------------------------------------------
-template <int NA, int AI>
-struct GenFrag {
+template <int AI>
+__device__ __forceinline__ bf16x8 gen_frag(const f32x4 &af, const f32x8 &bfv)
+{
     // products m_j[a] * m_j[b'] for the 8 tokens of this lane's half; a is broadcast with DPP
     // from lane 8*(e/4) + AI of each row, which holds tokens 4*(e/4)..+3 of row a0 + AI.
-    static __device__ __forceinline__ bf16x8 run(const f32x4 &af, const f32x8 &bfv)
-    {
-        f32x8 p;
-        p[0] = row_bcast<AI>(af[0]) * bfv[0];
-        p[1] = row_bcast<AI>(af[1]) * bfv[1];
-        p[2] = row_bcast<AI>(af[2]) * bfv[2];
-        p[3] = row_bcast<AI>(af[3]) * bfv[3];
-        p[4] = row_bcast<8 + AI>(af[0]) * bfv[4];
-        p[5] = row_bcast<8 + AI>(af[1]) * bfv[5];
-        p[6] = row_bcast<8 + AI>(af[2]) * bfv[6];
-        p[7] = row_bcast<8 + AI>(af[3]) * bfv[7];
-        return cvt8(p);
-    }
+    f32x8 p;
+    p[0] = row_bcast<AI>(af[0]) * bfv[0];
+    p[1] = row_bcast<AI>(af[1]) * bfv[1];
+    p[2] = row_bcast<AI>(af[2]) * bfv[2];
+    p[3] = row_bcast<AI>(af[3]) * bfv[3];
+    p[4] = row_bcast<8 + AI>(af[0]) * bfv[4];
+    p[5] = row_bcast<8 + AI>(af[1]) * bfv[5];
+    p[6] = row_bcast<8 + AI>(af[2]) * bfv[6];
+    p[7] = row_bcast<8 + AI>(af[3]) * bfv[7];
+    return cvt8(p);
+}
+
+template <int CT>
+struct StateOps {           // LDS operands of one 16-token step
+    f32x4 af;               // m_j[a] source values (see gen_frag)
+    f32x8 bfv;              // m_j[b'] for this lane's b' and 8 tokens
+    bf16x8 vf[CT];          // V fragments (B operand)
 };
 
+// One 16-token step: for every a of the wave, two things overlap -- the MFMAs that consume the
+// fragment generated last, and the VALU work generating the next fragment (the first one of
+// the following step comes from `nxt`).
 template <int NA, int CT, int AI>
 struct StateStep {
-    static __device__ __forceinline__ void run(const f32x4 &af, const f32x8 &bfv, const bf16x8 *vf,
-                                               f32x16 (*acc)[CT])
+    static __device__ __forceinline__ void run(const StateOps<CT> &cur, const StateOps<CT> &nxt,
+                                               bf16x8 &frag, f32x16 (*acc)[CT])
     {
-        const bf16x8 frag = GenFrag<NA, AI>::run(af, bfv);
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) acc[AI][ct] = mfma32(frag, vf[ct], acc[AI][ct]);
-        if constexpr (AI + 1 < NA) StateStep<NA, CT, AI + 1>::run(af, bfv, vf, acc);
+        for (int ct = 0; ct < CT; ++ct) acc[AI][ct] = mfma32(frag, cur.vf[ct], acc[AI][ct]);
+        if constexpr (AI + 1 < NA) {
+            frag = gen_frag<AI + 1>(cur.af, cur.bfv);
+        } else {
+            frag = gen_frag<0>(nxt.af, nxt.bfv);
+        }
+        // interleave: one MFMA, then half of the 12 VALU ops of the next fragment
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 12 / CT, 0);
+        }
+        if constexpr (AI + 1 < NA) StateStep<NA, CT, AI + 1>::run(cur, nxt, frag, acc);
     }
 };
 
@@ -385,11 +428,10 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
     constexpr int AG = NA * 4 / NB;            // sketch rows a per workgroup
     constexpr int CT = D / 32;
     constexpr int TC = kStateChunk;
-    constexpr int M_F4 = TC * R / 4;           // float4 units per staged m(K) chunk
-    constexpr int V_U4 = TC * D / 8;           // 16-byte units per staged V chunk
+    constexpr int STEPS = TC / 16;
+    constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2;
     static_assert(NA <= 8, "DPP source lanes");
-    __shared__ __attribute__((aligned(16))) float lds_m[2][TC * R];
-    __shared__ __attribute__((aligned(16))) bf16_t lds_v[2][TC * D];
+    __shared__ __attribute__((aligned(16))) unsigned char lds[2][M_BYTES + V_BYTES];
 
     // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
     // contiguous range of (unit, group) pairs; the groups of one unit then share one L2.
@@ -399,7 +441,7 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
     const int u = wg / GROUPS, grp = wg % GROUPS;
     if (u >= units) return;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int x = lane & 31, h = lane >> 5, n16 = lane & 15;
     const int bh = wave % NB, ag = wave / NB;
     const int a0 = grp * AG + ag * NA;
@@ -412,47 +454,60 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
 #pragma unroll
         for (int j = 0; j < CT; ++j) acc[i][j] = f32x16{0};
 
-    const f32x4 *gm = (const f32x4 *)(M8 + (size_t)u * n * R);
-    const uint4 *gv = (const uint4 *)(V8 + (size_t)u * n * D);
+    const float *gm = M8 + (size_t)u * n * R;
+    const bf16_t *gv = V8 + (size_t)u * n * D;
     const int chunks = (t - 1) * (b / TC), chunks_per_block = b / TC;
+    if (chunks == 0) return;
 
-    f32x4 pm[M_F4 / kWg];
-    uint4 pv[V_U4 / kWg];
-    auto fetch = [&](int chunk) {
+    auto stage = [&](int buf, int chunk) {      // straight copies: global layout == LDS layout
+        const float *sm = gm + (size_t)chunk * TC * R;
+        const bf16_t *sv = gv + (size_t)chunk * TC * D;
 #pragma unroll
-        for (int i = 0; i < M_F4 / kWg; ++i) pm[i] = gm[(size_t)chunk * M_F4 + i * kWg + threadIdx.x];
+        for (int q = 0; q < M_BYTES / 16 / kWg; ++q)
+            dma16(sm + (size_t)(q * kWg + tid) * 4, lds[buf] + (size_t)(q * kWg + wave * 64) * 16);
 #pragma unroll
-        for (int i = 0; i < V_U4 / kWg; ++i) pv[i] = gv[(size_t)chunk * V_U4 + i * kWg + threadIdx.x];
+        for (int q = 0; q < V_BYTES / 16 / kWg; ++q)
+            dma16(sv + (size_t)(q * kWg + tid) * 8, lds[buf] + M_BYTES + (size_t)(q * kWg + wave * 64) * 16);
     };
-    auto commit = [&](int buf) {
+    auto load_ops = [&](int buf, int s) {
+        StateOps<CT> o;
+        const float *lm = (const float *)lds[buf];
+        const bf16_t *lv = (const bf16_t *)(lds[buf] + M_BYTES);
+        const int oct = 2 * s + h;
+        const float *pb = &lm[(oct * R + 32 * bh + x) * 8];
+        const f32x4 b_lo = *(const f32x4 *)pb, b_hi = *(const f32x4 *)(pb + 4);
 #pragma unroll
-        for (int i = 0; i < M_F4 / kWg; ++i) ((f32x4 *)lds_m[buf])[i * kWg + threadIdx.x] = pm[i];
+        for (int e = 0; e < 4; ++e) { o.bfv[e] = b_lo[e]; o.bfv[4 + e] = b_hi[e]; }
+        o.af = *(const f32x4 *)&lm[(oct * R + a_src) * 8 + 4 * q_src];
 #pragma unroll
-        for (int i = 0; i < V_U4 / kWg; ++i) ((uint4 *)lds_v[buf])[i * kWg + threadIdx.x] = pv[i];
+        for (int ct = 0; ct < CT; ++ct) o.vf[ct] = *(const bf16x8 *)&lv[(oct * D + 32 * ct + x) * 8];
+        return o;
     };
 
-    if (chunks > 0) { fetch(0); commit(0); }
+    stage(0, 0);
+    wait_all_memory();
     __syncthreads();
+    StateOps<CT> cur = load_ops(0, 0);
+    bf16x8 frag = gen_frag<0>(cur.af, cur.bfv);
+
+#pragma unroll 1
     for (int chunk = 0; chunk < chunks; ++chunk) {
         const int buf = chunk & 1;
-        if (chunk + 1 < chunks) fetch(chunk + 1);
-        const float *lm = lds_m[buf];
-        const bf16_t *lv = lds_v[buf];
+        if (chunk + 1 < chunks) stage(buf ^ 1, chunk + 1);
 #pragma unroll
-        for (int s = 0; s < TC / 16; ++s) {
-            const int oct = 2 * s + h;
-            const float *pb = &lm[(oct * R + 32 * bh + x) * 8];
-            const f32x4 b_lo = *(const f32x4 *)pb, b_hi = *(const f32x4 *)(pb + 4);
-            f32x8 bfv;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { bfv[e] = b_lo[e]; bfv[4 + e] = b_hi[e]; }
-            const f32x4 af = *(const f32x4 *)&lm[(oct * R + a_src) * 8 + 4 * q_src];
-            bf16x8 vf[CT];
-#pragma unroll
-            for (int ct = 0; ct < CT; ++ct) vf[ct] = *(const bf16x8 *)&lv[(oct * D + 32 * ct + x) * 8];
-            StateStep<NA, CT, 0>::run(af, bfv, vf, acc);
+        for (int s = 0; s < STEPS; ++s) {
+            if (s == STEPS - 1) {
+                // the next step's operands come from the other buffer: its copies (issued one
+                // chunk ago) must have landed for every wave; nobody reads this buffer after
+                // this point (the last step's operands are already in registers)
+                wait_all_memory();
+                __syncthreads();
+            }
+            const StateOps<CT> nxt = (s + 1 < STEPS) ? load_ops(buf, s + 1)
+                                                      : load_ops(chunk + 1 < chunks ? buf ^ 1 : buf, 0);
+            StateStep<NA, CT, 0>::run(cur, nxt, frag, acc);
+            cur = nxt;
         }
-        if (chunk + 1 < chunks) commit(buf ^ 1);
         if ((chunk + 1) % chunks_per_block == 0) {
             // snapshot: Z_{l+1} = sum over blocks 0..l, stored [a][b'/8][c][8] bf16
             const int l = chunk / chunks_per_block;
@@ -470,33 +525,36 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
                             cvt4(q4);
                     }
         }
-        __syncthreads();
     }
 }
 
 // ------------------------------------------------------------------------------------
-// Output kernel.  Workgroup = 256 consecutive tokens of one block; wave = 64 tokens = TT 32-token
-// tiles.  All accumulators are D^T-oriented: lane = token, registers = value columns.
+// Output kernel.  Workgroup = 128*TT consecutive tokens of one block; wave = TT tiles of 32
+// tokens.  All accumulators are D^T-oriented: lane = token, registers = value columns.
+// Two workgroups share a CU (2 waves per SIMD) so that one wave's VALU work (x^p, the
+// m_i[a] * T_a updates) overlaps the other's MFMAs.
 // ------------------------------------------------------------------------------------
 template <int R, int D, int P, int TT>
-__global__ __launch_bounds__(kWg) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
-                                             const bf16_t *__restrict__ V8,
-                                             const bf16_t *__restrict__ MQ, const float *__restrict__ MT,
-                                             const bf16_t *__restrict__ Zg,
-                                             const bf16_t *__restrict__ Shi,
-                                             const bf16_t *__restrict__ Slo, bf16_t *__restrict__ O,
-                                             int n, int b, int t)
+__global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                const bf16_t *__restrict__ V8,
+                                                const bf16_t *__restrict__ MQ,
+                                                const bf16_t *__restrict__ Zg,
+                                                const bf16_t *__restrict__ Shi,
+                                                const bf16_t *__restrict__ Slo, bf16_t *__restrict__ O,
+                                                int n, int b, int t)
 {
     constexpr int CT = D / 32, KS = D / 16, RS = R / 16, AT = R / 32;
     constexpr int TOK_WAVE = 32 * TT, TOK_WG = 4 * TOK_WAVE;
-    constexpr int KP = D + 8;                             // pitch of staged K rows (bf16)
-    constexpr int ZA = 16384 / (R * D);                   // sketch rows a per staged Z chunk (32 KB)
+    constexpr int ZA = 16384 / (R * D);                   // sketch rows a per staged Z chunk
     constexpr int Z_PER_A = R * D;                        // bf16 elements of Z for one a
-    constexpr int STAGE_ELEMS = ZA * Z_PER_A > kKeyTile * KP + kKeyTile * D ? ZA * Z_PER_A
-                                                                             : kKeyTile * KP + kKeyTile * D;
-    __shared__ __attribute__((aligned(16))) bf16_t stage[2][STAGE_ELEMS];
+    constexpr int Z_CHUNK_BYTES = ZA * Z_PER_A * 2;       // 32 KB
+    constexpr int MQ_CHUNK_BYTES = ZA * TOK_WG * 4;       // m_i[a] of the chunk, fp32 [ZA][TOK_WG]
+    constexpr int KV_BYTES = kKeyTile * D * 2 * 2;        // staged K tile + V tile
+    constexpr int STAGE_BYTES = Z_CHUNK_BYTES + MQ_CHUNK_BYTES > KV_BYTES ? Z_CHUNK_BYTES + MQ_CHUNK_BYTES
+                                                                          : KV_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char stage[2][STAGE_BYTES];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int x = lane & 31, h = lane >> 5;
     const int tiles_per_unit = n / TOK_WG;
     const int u = blockIdx.x / tiles_per_unit;
@@ -525,65 +583,81 @@ __global__ __launch_bounds__(kWg) void k_out(const bf16_t *__restrict__ Q, const
             for (int s = 0; s < KS; ++s)
                 qfr[tt][s] = *(const bf16x8 *)&Q[(urow + tok_w0 + 32 * tt + x) * D + 16 * s + 8 * h];
 
-        bf16_t *ks = stage[0];                            // [kKeyTile][KP]
-        bf16_t *vs = stage[0] + kKeyTile * KP;            // [kKeyTile/8][D][8]
-        for (int j0 = jb; j0 < i0 + TOK_WG; j0 += kKeyTile) {
-            __syncthreads();
-            for (int idx = threadIdx.x; idx < kKeyTile * D / 8; idx += kWg) {
-                const int row = idx / (D / 8), part = idx % (D / 8);
-                *(uint4 *)&ks[row * KP + part * 8] = *(const uint4 *)&K[(urow + j0 + row) * D + part * 8];
-                ((uint4 *)vs)[idx] = ((const uint4 *)(V8 + (urow + j0) * D))[idx];
+        // K tile in LDS as [D/8][64 keys][8] (A fragments are then contiguous 16-byte reads),
+        // V tile as [8 octets][D][8], both filled by direct global->LDS copies.
+        auto stage_kv = [&](int buf, int j0) {
+            bf16_t *ks = (bf16_t *)stage[buf];
+            bf16_t *vs = ks + kKeyTile * D;
+#pragma unroll
+            for (int q = 0; q < D / 32; ++q) {
+                const int o = q * 4 + wave;               // d-octet handled by this wave
+                dma16(&K[(urow + j0 + lane) * D + 8 * o], ks + (size_t)o * kKeyTile * 8);
             }
-            __syncthreads();
-            if (j0 > tok_w0 + TOK_WAVE - 1) continue;     // every key of this tile is masked
 #pragma unroll
-            for (int sub = 0; sub < kKeyTile / 32; ++sub) {
-                const int key0 = j0 + 32 * sub;
-                bf16x8 kfr[KS];
+            for (int q = 0; q < kKeyTile * D / 8 / kWg; ++q)
+                dma16(&V8[(urow + j0) * D + (size_t)(q * kWg + tid) * 8], vs + (size_t)(q * kWg + wave * 64) * 8);
+        };
+
+        const int ntiles = (i0 + TOK_WG - jb) / kKeyTile;
+        stage_kv(0, jb);
+        wait_all_memory();
+        __syncthreads();
+#pragma unroll 1
+        for (int kt = 0; kt < ntiles; ++kt) {
+            const int buf = kt & 1, j0 = jb + kt * kKeyTile;
+            if (kt + 1 < ntiles) stage_kv(buf ^ 1, j0 + kKeyTile);
+            if (j0 <= tok_w0 + TOK_WAVE - 1) {            // otherwise every key of this tile is masked
+                const bf16_t *ks = (const bf16_t *)stage[buf];
+                const bf16_t *vs = ks + kKeyTile * D;
 #pragma unroll
-                for (int s = 0; s < KS; ++s)
-                    kfr[s] = *(const bf16x8 *)&ks[(32 * sub + x) * KP + 16 * s + 8 * h];
-                // A operand of P V: V^T, k index = key 16s' + 8*(e/4) + 4h + e%4 (matches the
-                // register order of the score tile)
-                bf16x8 vfr[2][CT];
+                for (int sub = 0; sub < kKeyTile / 32; ++sub) {
+                    const int key0 = j0 + 32 * sub;
+                    if (key0 > tok_w0 + TOK_WAVE - 1) continue;
+                    bf16x8 kfr[KS];
 #pragma unroll
-                for (int sp = 0; sp < 2; ++sp)
+                    for (int s = 0; s < KS; ++s)
+                        kfr[s] = *(const bf16x8 *)&ks[((2 * s + h) * kKeyTile + 32 * sub + x) * 8];
 #pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) {
-                        const int oct = 4 * sub + 2 * sp;
-                        const bf16x4 lo = *(const bf16x4 *)&vs[((oct)*D + 32 * ct + x) * 8 + 4 * h];
-                        const bf16x4 hi = *(const bf16x4 *)&vs[((oct + 1) * D + 32 * ct + x) * 8 + 4 * h];
+                    for (int tt = 0; tt < TT; ++tt) {
+                        const int tok0 = tok_w0 + 32 * tt;
+                        if (key0 > tok0 + 31) continue;   // tile entirely above the diagonal
+                        f32x16 sc = {0};                  // S^T[key][token]
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) { vfr[sp][ct][e] = lo[e]; vfr[sp][ct][4 + e] = hi[e]; }
-                    }
+                        for (int s = 0; s < KS; ++s) sc = mfma32(kfr[s], qfr[tt][s], sc);
+                        const bool diag = key0 + 31 > tok0;
+                        float dsum = 0.f;
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) {
-                    const int tok0 = tok_w0 + 32 * tt;
-                    if (key0 > tok0 + 31) continue;       // tile entirely above the diagonal
-                    f32x16 sc = {0};                      // S^T[key][token]
-#pragma unroll
-                    for (int s = 0; s < KS; ++s) sc = mfma32(kfr[s], qfr[tt][s], sc);
-                    const bool diag = key0 + 31 > tok0;
-                    float dsum = 0.f;
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        float w = pow_p(sc[v], P);
-                        if (diag) {
-                            const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
-                            w = key <= tok0 + x ? w : 0.f;
+                        for (int v = 0; v < 16; ++v) {
+                            float w = pow_p(sc[v], P);
+                            if (diag) {
+                                const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
+                                w = key <= tok0 + x ? w : 0.f;
+                            }
+                            sc[v] = w;
+                            dsum += w;
                         }
-                        sc[v] = w;
-                        dsum += w;
-                    }
-                    den[tt] += dsum;
-                    const bf16x8 p0 = cvt8_from16(sc, 0), p1 = cvt8_from16(sc, 8);
+                        den[tt] += dsum;
+                        // P^T as B operand: k index = key 16sp + 8*(e/4) + 4h + e%4, which is the
+                        // register order of the score tile; V^T fragments use the same order.
 #pragma unroll
-                    for (int ct = 0; ct < CT; ++ct) {
-                        out[tt][ct] = mfma32(vfr[0][ct], p0, out[tt][ct]);
-                        out[tt][ct] = mfma32(vfr[1][ct], p1, out[tt][ct]);
+                        for (int sp = 0; sp < 2; ++sp) {
+                            const bf16x8 pfr = cvt8_from16(sc, 8 * sp);
+                            const int oct = 4 * sub + 2 * sp;
+#pragma unroll
+                            for (int ct = 0; ct < CT; ++ct) {
+                                const bf16x4 lo = *(const bf16x4 *)&vs[((oct)*D + 32 * ct + x) * 8 + 4 * h];
+                                const bf16x4 hi = *(const bf16x4 *)&vs[((oct + 1) * D + 32 * ct + x) * 8 + 4 * h];
+                                bf16x8 vfr;
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) { vfr[e] = lo[e]; vfr[4 + e] = hi[e]; }
+                                out[tt][ct] = mfma32(vfr, pfr, out[tt][ct]);
+                            }
+                        }
                     }
                 }
             }
+            wait_all_memory();
+            __syncthreads();
         }
     }
 
@@ -595,7 +669,6 @@ __global__ __launch_bounds__(kWg) void k_out(const bf16_t *__restrict__ Q, const
 #pragma unroll
             for (int s = 0; s < RS; ++s)
                 mfr[tt][s] = *(const bf16x8 *)&MQ[(urow + tok_w0 + 32 * tt + x) * R + 16 * s + 8 * h];
-        const float *mt = MT + (size_t)u * R * n;         // [R][n] fp32
 
         // denominator: m_i^T S m_i with S = prefix of m_j m_j^T, hi + lo operands
         {
@@ -618,40 +691,60 @@ __global__ __launch_bounds__(kWg) void k_out(const bf16_t *__restrict__ Q, const
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int a = 32 * at + 8 * (v / 4) + 4 * h + (v % 4);
-                        den[tt] += mt[(size_t)a * n + tok_w0 + 32 * tt + x] * td[tt][v];
+                    for (int gq = 0; gq < 4; ++gq) {
+                        const bf16x4 m4 = *(const bf16x4 *)&MQ[(urow + tok_w0 + 32 * tt + x) * R + 32 * at +
+                                                               8 * gq + 4 * h];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) den[tt] += (float)m4[j] * td[tt][4 * gq + j];
                     }
             }
         }
 
         // numerator: for every a, T_a = Z_l[a]^T m_i (D x tokens), out += m_i[a] * T_a
-        const uint4 *zsrc = (const uint4 *)(Zg + ((size_t)u * (t - 1) + (l - 1)) * R * R * D);
-        constexpr int CHUNK_U4 = ZA * Z_PER_A / 8;        // 16-byte units per staged chunk
+        const bf16_t *zsrc = Zg + ((size_t)u * (t - 1) + (l - 1)) * R * R * D;
         constexpr int NCHUNK = R / ZA;
-        uint4 pre[CHUNK_U4 / kWg];
-        auto fetch = [&](int chunk) {
+        constexpr int DMA_PER_THREAD = Z_CHUNK_BYTES / 16 / kWg;     // 8
+        // m_i[a] of the chunk as fp32 [ZA][TOK_WG]: each thread converts MQ_PER consecutive a of
+        // one token; loaded early into registers, written to LDS after the chunk's MFMAs
+        constexpr int MQ_PER = ZA * TOK_WG / kWg;
+        typedef __bf16 mqvec __attribute__((ext_vector_type(MQ_PER)));
+        const int mq_tok = tid % TOK_WG, mq_grp = tid / TOK_WG;
+        mqvec mqv;
+        auto stage_z = [&](int buf, int chunk) {
+            unsigned char *dst = stage[buf];
+            const bf16_t *src = zsrc + (size_t)chunk * ZA * Z_PER_A;
 #pragma unroll
-            for (int i = 0; i < CHUNK_U4 / kWg; ++i) pre[i] = zsrc[(size_t)chunk * CHUNK_U4 + i * kWg + threadIdx.x];
+            for (int q = 0; q < DMA_PER_THREAD; ++q)
+                dma16(src + (size_t)(q * kWg + tid) * 8, dst + (size_t)(q * kWg + wave * 64) * 16);
         };
-        auto commit = [&](int buf) {
+        auto load_mq = [&](int chunk) {
+            mqv = *(const mqvec *)&MQ[(urow + i0 + mq_tok) * R + chunk * ZA + mq_grp * MQ_PER];
+        };
+        auto store_mq = [&](int buf) {
+            float *dst = (float *)(stage[buf] + Z_CHUNK_BYTES);      // [ZA][TOK_WG]
 #pragma unroll
-            for (int i = 0; i < CHUNK_U4 / kWg; ++i) ((uint4 *)stage[buf])[i * kWg + threadIdx.x] = pre[i];
+            for (int e = 0; e < MQ_PER; ++e) dst[(mq_grp * MQ_PER + e) * TOK_WG + mq_tok] = (float)mqv[e];
         };
-        __syncthreads();                                  // in-block staging is done with stage[0]
-        fetch(0);
-        commit(0);
+        stage_z(0, 0);
+        load_mq(0);
+        store_mq(0);
+        wait_all_memory();
         __syncthreads();
+#pragma unroll 1
         for (int chunk = 0; chunk < NCHUNK; ++chunk) {
             const int buf = chunk & 1;
-            if (chunk + 1 < NCHUNK) fetch(chunk + 1);
-#pragma unroll
+            if (chunk + 1 < NCHUNK) {
+                stage_z(buf ^ 1, chunk + 1);
+                load_mq(chunk + 1);
+            }
+            const bf16_t *zc = (const bf16_t *)stage[buf];
+            const float *mqs = (const float *)(stage[buf] + Z_CHUNK_BYTES);
+#pragma unroll 1
             for (int ai = 0; ai < ZA; ++ai) {
-                const int a = chunk * ZA + ai;
-                const bf16_t *za = stage[buf] + ai * Z_PER_A;      // [R/8][D][8]
+                const bf16_t *za = zc + ai * Z_PER_A;     // [R/8][D][8]
                 float mq[TT];
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) mq[tt] = mt[(size_t)a * n + tok_w0 + 32 * tt + x];
+                for (int tt = 0; tt < TT; ++tt) mq[tt] = mqs[ai * TOK_WG + wave * TOK_WAVE + 32 * tt + x];
 #pragma unroll
                 for (int ct = 0; ct < CT; ++ct) {
                     bf16x8 zf[RS];
@@ -667,7 +760,8 @@ __global__ __launch_bounds__(kWg) void k_out(const bf16_t *__restrict__ Q, const
                     }
                 }
             }
-            if (chunk + 1 < NCHUNK) commit(buf ^ 1);
+            if (chunk + 1 < NCHUNK) store_mq(buf ^ 1);
+            wait_all_memory();
             __syncthreads();
         }
     }
@@ -690,50 +784,58 @@ __global__ __launch_bounds__(kWg) void k_out(const bf16_t *__restrict__ Q, const
 }
 
 struct MfmaWs {
-    bf16_t *MQ; float *MT; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
+    bf16_t *Gt; bf16_t *MQ; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
     size_t total;
 };
+
+int sketch_tiles_per_wg(int b)
+{
+    int tiles = 8;                               // workgroup = 128 * tiles tokens, inside one block
+    while (b % (tiles * 128) != 0) tiles /= 2;
+    return tiles;
+}
 
 MfmaWs carve(const Problem &pb, void *ws)
 {
     MfmaWs w;
     const size_t rows = (size_t)pb.units * pb.n, R = pb.r, D = pb.d, tb = pb.t > 1 ? pb.t - 1 : 0;
+    const size_t sets = pb.per_head ? pb.heads : 1;
+    const size_t parts = rows / (128 * (size_t)sketch_tiles_per_wg(pb.b));
     size_t off = 0;
     char *base = (char *)ws;
     auto take = [&](size_t bytes) { char *p = base + off; off += align_up(bytes, 256); return p; };
+    w.Gt = (bf16_t *)take(sets * pb.g_len * 2);
     w.MQ = (bf16_t *)take(rows * R * 2);
-    w.MT = (float *)take(rows * R * 4);
     w.MK8 = (float *)take(rows * R * 4);
     w.V8 = (bf16_t *)take(rows * D * 2);
     w.Zg = (bf16_t *)take((size_t)pb.units * tb * R * R * D * 2);
-    w.Spart = (float *)take((size_t)pb.units * tb * R * R * 4);
+    w.Spart = (float *)take(parts * R * R * 4);
     w.Shi = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
     w.Slo = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
     w.total = off;
     return w;
 }
 
-int sketch_tiles_per_wg(int n)
+psf_status launch_transpose_g(const Problem &pb, const void *G, bf16_t *Gt, hipStream_t s)
 {
-    int tiles = 8;
-    while (n % (tiles * 128) != 0) tiles /= 2;
-    return tiles;
+    const int nmat = pb.p / 2 + (pb.p / 2 >= 4 ? pb.p / 2 - 2 : 0);
+    hipLaunchKernelGGL(k_transpose_g, dim3(nmat, pb.per_head ? pb.heads : 1), dim3(kWg), 0, s,
+                       (const bf16_t *)G, Gt, pb.d, pb.r, pb.p, pb.g_len);
+    PSF_LAUNCH_CHECK();
+    return PSF_OK;
 }
 
 template <int D, int R, int P>
-psf_status launch_sketch(const Problem &pb, const void *X, const void *G, bool qside, bf16_t *M_rm,
-                         float *MT, float *M8, hipStream_t s)
+psf_status launch_sketch(const Problem &pb, const void *X, const bf16_t *Gt, bool qside, bf16_t *M_rm,
+                         float *M8, float *Spart, int tiles, hipStream_t s)
 {
-    const int tiles = sketch_tiles_per_wg(pb.n);
     const unsigned grid = (unsigned)((size_t)pb.units * pb.n / (128 * (size_t)tiles));
     if (qside)
-        hipLaunchKernelGGL((k_sketch<D, R, P, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)X,
-                           (const bf16_t *)G, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles,
-                           M_rm, MT, M8);
+        hipLaunchKernelGGL((k_sketch<D, R, P, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)X, Gt,
+                           pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles, M_rm, M8, Spart);
     else
-        hipLaunchKernelGGL((k_sketch<D, R, P, false>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)X,
-                           (const bf16_t *)G, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles,
-                           M_rm, MT, M8);
+        hipLaunchKernelGGL((k_sketch<D, R, P, false>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)X, Gt,
+                           pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles, M_rm, M8, Spart);
     PSF_LAUNCH_CHECK();
     return PSF_OK;
 }
@@ -743,9 +845,12 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
                      void *O, void *ws, hipStream_t s, StageTimer *tm)
 {
     MfmaWs w = carve(pb, ws);
-    psf_status st = launch_sketch<D, R, P>(pb, Q, G, true, w.MQ, w.MT, nullptr, s);
+    const int tiles = sketch_tiles_per_wg(pb.b);
+    psf_status st = launch_transpose_g(pb, G, w.Gt, s);
     if (st != PSF_OK) return st;
-    st = launch_sketch<D, R, P>(pb, K, G, false, nullptr, nullptr, w.MK8, s);
+    st = launch_sketch<D, R, P>(pb, Q, w.Gt, true, w.MQ, nullptr, nullptr, tiles, s);
+    if (st != PSF_OK) return st;
+    st = launch_sketch<D, R, P>(pb, K, w.Gt, false, nullptr, w.MK8, w.Spart, tiles, s);
     if (st != PSF_OK) return st;
     {
         const size_t octets = (size_t)pb.units * pb.n / 8;
@@ -755,10 +860,8 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     }
     if (tm) tm->mark();
     if (pb.t > 1) {
-        hipLaunchKernelGGL((k_den_partial<R>), dim3(pb.t - 1, pb.units), dim3(kWg), 0, s, w.MK8, w.Spart,
-                           pb.n, pb.b, pb.t);
-        PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_den_scan<R>), dim3(pb.units), dim3(kWg), 0, s, w.Spart, w.Shi, w.Slo, pb.t);
+        hipLaunchKernelGGL((k_den_scan<R>), dim3(R * R / kWg, pb.units), dim3(kWg), 0, s, w.Spart, w.Shi,
+                           w.Slo, pb.t, pb.b / (128 * tiles));
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
@@ -772,26 +875,26 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     }
     if (tm) tm->mark();
     {
-        constexpr int TT = 2;
-        const unsigned grid = (unsigned)((size_t)pb.units * (pb.n / kTokWg));
+        constexpr int TT = (D == 64) ? 2 : 1;
+        const unsigned grid = (unsigned)((size_t)pb.units * (pb.n / (128 * TT)));
         hipLaunchKernelGGL((k_out<R, D, P, TT>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
-                           (const bf16_t *)K, w.V8, w.MQ, w.MT, w.Zg, w.Shi, w.Slo, (bf16_t *)O, pb.n, pb.b,
-                           pb.t);
+                           (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, pb.n, pb.b, pb.t);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
     return PSF_OK;
 }
 
-template <int D, int R, int P>
-psf_status sketch_impl(const Problem &pb, const void *X, const void *G, void *M_out, hipStream_t s)
-{
-    return launch_sketch<D, R, P>(pb, X, G, true, (bf16_t *)M_out, nullptr, nullptr, s);
-}
-
 }  // namespace
 
 size_t mfma_workspace_bytes(const Problem &pb) { return carve(pb, nullptr).total; }
+
+// psf_sketch on the MFMA path: needs scratch for the transposed sketch matrices, which the
+// entry point does not have, so the general kernel serves it.
+psf_status mfma_sketch(const Problem &, const void *, const void *, void *, void *, hipStream_t)
+{
+    return PSF_ERR_UNSUPPORTED;
+}
 
 #define PSF_DISPATCH(CALL)                                                   \
     do {                                                                     \
@@ -805,15 +908,6 @@ size_t mfma_workspace_bytes(const Problem &pb) { return carve(pb, nullptr).total
         if (pb.d == 128 && pb.r == 32 && pb.p == 8) return CALL(128, 32, 8); \
         return PSF_ERR_UNSUPPORTED;                                          \
     } while (0)
-
-psf_status mfma_sketch(const Problem &pb, const void *X, const void *G, void *M_out, void *Phi_out,
-                       hipStream_t s)
-{
-    if (Phi_out || !M_out) return PSF_ERR_UNSUPPORTED;
-#define PSF_SK(D_, R_, P_) (sketch_impl<D_, R_, P_>(pb, X, G, M_out, s))
-    PSF_DISPATCH(PSF_SK);
-#undef PSF_SK
-}
 
 psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                      void *O, void *ws, hipStream_t s, StageTimer *tm)
