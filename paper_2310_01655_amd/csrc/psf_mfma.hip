@@ -4,7 +4,7 @@
 // Kernels (R = sketch size r, D = head size d = dv, b = block size, t = n/b):
 //   k_transpose_g  sketch matrices transposed once (operand-friendly for the sketch kernel).
 //   k_sketch       Algorithm 1 on bf16 MFMA.  m(Q) is stored row-major bf16; m(K) is stored as
-//                  fp32 "token octets" [n/8][R][8] so that the state kernel can stage it into
+//                  fp32 "token octets" [n/8][2][R][4] so that the state kernel can stage it into
 //                  LDS with straight copies.  The K side also accumulates S = m(K)^T m(K) per
 //                  workgroup (R x R): the "ones" column of H_l = phi'(K_l)^T [V_l | 1], because
 //                  phi' = m (x) m (Algorithm 1).
@@ -24,6 +24,8 @@
 //   A[i][k]: lane x = i, half h supplies k = 8h..8h+7 (8 bf16 per lane)
 //   B[k][j]: lane x = j, half h supplies k = 8h..8h+7
 //   D[i][j]: lane x = j, register v holds row i = 8*(v/4) + 4*h + (v%4)
+#include <type_traits>
+
 #include "psf_internal.h"
 
 namespace psf {
@@ -79,6 +81,14 @@ __device__ __forceinline__ void dma16(const void *gsrc_lane, void *lds_wave_base
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
+// Wait until at most N vector-memory operations of this wave are outstanding (they complete in
+// order, so everything older has landed); LDS/scalar counters are left alone.
+template <int N>
+__device__ __forceinline__ void wait_vmem_le()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is 6 bits");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+}
 
 // ------------------------------------------------------------------------------------
 // Sketch matrices transposed once: Gt[set][mat][c][e] = G[set][mat][e][c], so that the sketch
@@ -106,7 +116,8 @@ __global__ __launch_bounds__(kWg) void k_transpose_g(const bf16_t *__restrict__ 
 // `tiles_per_wg` consecutive 128-token tiles of one unit so that the sketch matrices staged
 // in LDS are reused.
 //   QSIDE: results in D^T orientation (lane = token): writes M_rm [rows][R] bf16.
-//   !QSIDE: results in D orientation (lane = sketch column): writes M8 [U][n/8][R][8] fp32
+//   !QSIDE: results in D orientation (lane = sketch column): writes M8 [U][n/8][2][R][4] fp32
+//          (token octet, half of the octet, sketch column, 4 tokens: conflict-free LDS reads)
 //          and the workgroup's partial S = sum_j m_j m_j^T (the "ones" column of the block
 //          states, since phi' = m (x) m) to Spart [U][n / tokens_per_wg][R][R].
 // ------------------------------------------------------------------------------------
@@ -267,7 +278,7 @@ __global__ __launch_bounds__(kWg) void k_sketch(const bf16_t *__restrict__ X,
                     const int c = 32 * ct + x;
                     f32x4 q4 = {m[ct][4 * gq], m[ct][4 * gq + 1], m[ct][4 * gq + 2], m[ct][4 * gq + 3]};
                     const size_t oct = (row0 >> 3) + gq;
-                    *(f32x4 *)&M8[(oct * R + c) * 8 + 4 * h] = q4;
+                    *(f32x4 *)&M8[((oct * 2 + h) * R + c) * 4] = q4;
                     if (M_rm)
 #pragma unroll
                         for (int j = 0; j < 4; ++j)
@@ -431,7 +442,9 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
     constexpr int STEPS = TC / 16;
     constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2;
     static_assert(NA <= 8, "DPP source lanes");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][M_BYTES + V_BYTES];
+    constexpr int NBUF = 4;                    // staged chunks in flight: covers HBM latency
+    constexpr int DMA_PER_CHUNK = (M_BYTES + V_BYTES) / 16 / kWg;
+    __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF][M_BYTES + V_BYTES];
 
     // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
     // contiguous range of (unit, group) pairs; the groups of one unit then share one L2.
@@ -474,57 +487,70 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
         const float *lm = (const float *)lds[buf];
         const bf16_t *lv = (const bf16_t *)(lds[buf] + M_BYTES);
         const int oct = 2 * s + h;
-        const float *pb = &lm[(oct * R + 32 * bh + x) * 8];
-        const f32x4 b_lo = *(const f32x4 *)pb, b_hi = *(const f32x4 *)(pb + 4);
+        const f32x4 b_lo = *(const f32x4 *)&lm[((oct * 2 + 0) * R + 32 * bh + x) * 4];
+        const f32x4 b_hi = *(const f32x4 *)&lm[((oct * 2 + 1) * R + 32 * bh + x) * 4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) { o.bfv[e] = b_lo[e]; o.bfv[4 + e] = b_hi[e]; }
-        o.af = *(const f32x4 *)&lm[(oct * R + a_src) * 8 + 4 * q_src];
+        o.af = *(const f32x4 *)&lm[((oct * 2 + q_src) * R + a_src) * 4];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) o.vf[ct] = *(const bf16x8 *)&lv[(oct * D + 32 * ct + x) * 8];
         return o;
     };
 
-    stage(0, 0);
-    wait_all_memory();
-    __syncthreads();
-    StateOps<CT> cur = load_ops(0, 0);
-    bf16x8 frag = gen_frag<0>(cur.af, cur.bfv);
+    auto snapshot = [&](int l) {
+        // Z_{l+1} = sum over blocks 0..l, stored [a][b'/8][c][8] bf16
+        bf16_t *z = Zg + ((size_t)u * (t - 1) + l) * R * R * D;
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    f32x4 q4 = {acc[i][ct][4 * gq], acc[i][ct][4 * gq + 1], acc[i][ct][4 * gq + 2],
+                                acc[i][ct][4 * gq + 3]};
+                    const size_t o = 4 * bh + gq;
+                    *(bf16x4 *)&z[(((size_t)(a0 + i) * (R / 8) + o) * D + 32 * ct + x) * 8 + 4 * h] = cvt4(q4);
+                }
+    };
 
+    // Prologue: NBUF-1 chunks in flight, the first one landed.  Chunk indices past the end are
+    // clamped: the copies are redundant but keep the in-flight count, and with it the wait
+    // below, the same in every iteration.
+#pragma unroll
+    for (int c = 0; c < NBUF - 1; ++c) stage(c, min(c, chunks - 1));
+    wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
+    __syncthreads();
+    StateOps<CT> ops[2];
+    ops[0] = load_ops(0, 0);
+    bf16x8 frag = gen_frag<0>(ops[0].af, ops[0].bfv);
+    static_assert(STEPS % 2 == 0, "operand ping-pong");
+
+    // One chunk = STEPS steps.  Operands of step s+1 are read from LDS at the start of step s.
+    // Before the last step the next chunk must have landed for every wave (wait + barrier);
+    // after that barrier nobody reads this chunk's buffer again, so the next iteration may
+    // refill it.
+    int chunk = 0;
 #pragma unroll 1
-    for (int chunk = 0; chunk < chunks; ++chunk) {
-        const int buf = chunk & 1;
-        if (chunk + 1 < chunks) stage(buf ^ 1, chunk + 1);
+    for (int l = 0; l < t - 1; ++l) {
+#pragma unroll 1
+        for (int cb = 0; cb < chunks_per_block; ++cb, ++chunk) {
+            const int buf = chunk % NBUF, nbuf = (chunk + 1) % NBUF;
+            stage((chunk + NBUF - 1) % NBUF, min(chunk + NBUF - 1, chunks - 1));
 #pragma unroll
-        for (int s = 0; s < STEPS; ++s) {
-            if (s == STEPS - 1) {
-                // the next step's operands come from the other buffer: its copies (issued one
-                // chunk ago) must have landed for every wave; nobody reads this buffer after
-                // this point (the last step's operands are already in registers)
-                wait_all_memory();
-                __syncthreads();
+            for (int s = 0; s < STEPS; ++s) {
+                if (s == STEPS - 1) {
+                    // plain barrier: the copies are tracked by the explicit wait, and a fence
+                    // here would wait for the younger copies too
+                    wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
+                    __builtin_amdgcn_s_barrier();
+                }
+                __builtin_amdgcn_sched_barrier(0);      // steps are scheduled one at a time
+                ops[(s + 1) & 1] = (s + 1 < STEPS) ? load_ops(buf, s + 1) : load_ops(nbuf, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 3 + CT, 0);      // LDS reads first
+                StateStep<NA, CT, 0>::run(ops[s & 1], ops[(s + 1) & 1], frag, acc);
             }
-            const StateOps<CT> nxt = (s + 1 < STEPS) ? load_ops(buf, s + 1)
-                                                      : load_ops(chunk + 1 < chunks ? buf ^ 1 : buf, 0);
-            StateStep<NA, CT, 0>::run(cur, nxt, frag, acc);
-            cur = nxt;
         }
-        if ((chunk + 1) % chunks_per_block == 0) {
-            // snapshot: Z_{l+1} = sum over blocks 0..l, stored [a][b'/8][c][8] bf16
-            const int l = chunk / chunks_per_block;
-            bf16_t *z = Zg + ((size_t)u * (t - 1) + l) * R * R * D;
-#pragma unroll
-            for (int i = 0; i < NA; ++i)
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                    for (int gq = 0; gq < 4; ++gq) {
-                        f32x4 q4 = {acc[i][ct][4 * gq], acc[i][ct][4 * gq + 1], acc[i][ct][4 * gq + 2],
-                                    acc[i][ct][4 * gq + 3]};
-                        const size_t o = 4 * bh + gq;
-                        *(bf16x4 *)&z[(((size_t)(a0 + i) * (R / 8) + o) * D + 32 * ct + x) * 8 + 4 * h] =
-                            cvt4(q4);
-                    }
-        }
+        snapshot(l);
     }
 }
 
@@ -637,19 +663,21 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
                             dsum += w;
                         }
                         den[tt] += dsum;
-                        // P^T as B operand: k index = key 16sp + 8*(e/4) + 4h + e%4, which is the
-                        // register order of the score tile; V^T fragments use the same order.
+                        // P^T as B operand.  The score registers give lane (token, h) the keys
+                        // 16sp + 8*(e/4) + 4h + e%4; one half-wave swap per register pair turns that
+                        // into keys 16sp + 8h + e, so that V^T fragments are whole token octets.
 #pragma unroll
                         for (int sp = 0; sp < 2; ++sp) {
-                            const bf16x8 pfr = cvt8_from16(sc, 8 * sp);
-                            const int oct = 4 * sub + 2 * sp;
+                            const bf16x8 raw = cvt8_from16(sc, 8 * sp);
+                            uint4 w = __builtin_bit_cast(uint4, raw);
+                            const auto s0 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
+                            const auto s1 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
+                            w.x = s0[0]; w.z = s0[1]; w.y = s1[0]; w.w = s1[1];
+                            const bf16x8 pfr = __builtin_bit_cast(bf16x8, w);
+                            const int oct = 4 * sub + 2 * sp + h;
 #pragma unroll
                             for (int ct = 0; ct < CT; ++ct) {
-                                const bf16x4 lo = *(const bf16x4 *)&vs[((oct)*D + 32 * ct + x) * 8 + 4 * h];
-                                const bf16x4 hi = *(const bf16x4 *)&vs[((oct + 1) * D + 32 * ct + x) * 8 + 4 * h];
-                                bf16x8 vfr;
-#pragma unroll
-                                for (int e = 0; e < 4; ++e) { vfr[e] = lo[e]; vfr[4 + e] = hi[e]; }
+                                const bf16x8 vfr = *(const bf16x8 *)&vs[(oct * D + 32 * ct + x) * 8];
                                 out[tt][ct] = mfma32(vfr, pfr, out[tt][ct]);
                             }
                         }
