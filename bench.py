@@ -79,6 +79,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config3", help="config2|config3|config5|sweep_n.._r.._b..")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also issue one 256 MiB device copy, so that a counter run can scale "
+                         "FETCH_SIZE / WRITE_SIZE by a transfer of known size")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (units = batch x heads would shard with "
@@ -107,6 +110,12 @@ def main():
     ws = psf.alloc_workspace(desc, dev)
     stream = torch.cuda.current_stream()
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
     torch.cuda.synchronize()

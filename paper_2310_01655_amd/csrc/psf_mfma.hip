@@ -77,8 +77,14 @@ __device__ __forceinline__ float pow_p(float x, int p)
 // 16*i.  Completion is tracked by vmcnt; callers wait before the barrier that publishes it.
 __device__ __forceinline__ void dma16(const void *gsrc_lane, void *lds_wave_base)
 {
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)gsrc_lane,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+    // Written as assembly so that the compiler does not tie later LDS reads to these copies
+    // with a full vmcnt(0) wait; callers count the copies in flight themselves (wait_vmem_le).
+    // m0 carries the LDS destination; nothing else in these kernels uses m0.
+    const uint32_t lds_off = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)lds_wave_base;
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gsrc_lane), "s"(__builtin_amdgcn_readfirstlane(lds_off))
+                 : "memory");
 }
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 // Wait until at most N vector-memory operations of this wave are outstanding (they complete in
@@ -583,9 +589,14 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int x = lane & 31, h = lane >> 5;
     const int tiles_per_unit = n / TOK_WG;
-    const int u = blockIdx.x / tiles_per_unit;
-    // late tiles of a block have the most in-block work: hand them out first
-    const int tile = tiles_per_unit - 1 - (blockIdx.x % tiles_per_unit);
+    // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
+    // contiguous range of tiles; the workgroups that stream the same Z_l (same unit, same
+    // block) then share one L2 and run at about the same time.
+    int wg = blockIdx.x;
+    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int u = wg / tiles_per_unit;
+    // late tiles of a unit first: they carry the cross-block term
+    const int tile = tiles_per_unit - 1 - (wg % tiles_per_unit);
     const int i0 = tile * TOK_WG;                         // first token of the workgroup (in unit)
     const int l = i0 / b, jb = l * b;
     const size_t urow = (size_t)u * n;
