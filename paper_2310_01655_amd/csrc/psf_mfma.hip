@@ -39,7 +39,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWg = 256;          // 4 wavefronts
 constexpr int kStateChunk = 64;   // tokens staged per step in k_state
-constexpr int kKeyTile = 64;      // keys staged per step in the in-block phase of k_out
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
 {
@@ -563,8 +562,9 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
 // ------------------------------------------------------------------------------------
 // Output kernel.  Workgroup = 128*TT consecutive tokens of one block; wave = TT tiles of 32
 // tokens.  All accumulators are D^T-oriented: lane = token, registers = value columns.
-// Two workgroups share a CU (2 waves per SIMD) so that one wave's VALU work (x^p, the
-// m_i[a] * T_a updates) overlaps the other's MFMAs.
+// Both phases are software-pipelined inside a wave so that the MFMAs of the next 32x32 item
+// are in flight while the VALU works on the current one (x^p, mask, row sums, bf16 packing in
+// the in-block phase; the m_i[a] * T_a updates in the cross-block phase).
 // ------------------------------------------------------------------------------------
 template <int R, int D, int P, int TT>
 __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
@@ -577,14 +577,19 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
 {
     constexpr int CT = D / 32, KS = D / 16, RS = R / 16, AT = R / 32;
     constexpr int TOK_WAVE = 32 * TT, TOK_WG = 4 * TOK_WAVE;
+    constexpr int KEYT = TOK_WAVE;                        // keys per staged tile = tokens per wave
+    constexpr int SUBS = KEYT / 32, IPT = SUBS * TT;      // 32x32 items per staged tile and wave
+    constexpr int KV_BYTES = KEYT * D * 2 * 2;            // staged K tile + V tile (16 KB)
+    constexpr int NKV = 4;                                // key tiles in flight
+    constexpr int DMA_KV = KV_BYTES / 16 / kWg;           // copies per thread and tile
     constexpr int ZA = 16384 / (R * D);                   // sketch rows a per staged Z chunk
     constexpr int Z_PER_A = R * D;                        // bf16 elements of Z for one a
     constexpr int Z_CHUNK_BYTES = ZA * Z_PER_A * 2;       // 32 KB
     constexpr int MQ_CHUNK_BYTES = ZA * TOK_WG * 4;       // m_i[a] of the chunk, fp32 [ZA][TOK_WG]
-    constexpr int KV_BYTES = kKeyTile * D * 2 * 2;        // staged K tile + V tile
-    constexpr int STAGE_BYTES = Z_CHUNK_BYTES + MQ_CHUNK_BYTES > KV_BYTES ? Z_CHUNK_BYTES + MQ_CHUNK_BYTES
-                                                                          : KV_BYTES;
-    __shared__ __attribute__((aligned(16))) unsigned char stage[2][STAGE_BYTES];
+    constexpr int CROSS_BYTES = 2 * (Z_CHUNK_BYTES + MQ_CHUNK_BYTES);
+    constexpr int STAGE_BYTES = CROSS_BYTES > NKV * KV_BYTES ? CROSS_BYTES : NKV * KV_BYTES;
+    static_assert(KV_BYTES % (16 * kWg) == 0, "whole copies");
+    __shared__ __attribute__((aligned(16))) unsigned char stage[STAGE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int x = lane & 31, h = lane >> 5;
@@ -620,84 +625,127 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
             for (int s = 0; s < KS; ++s)
                 qfr[tt][s] = *(const bf16x8 *)&Q[(urow + tok_w0 + 32 * tt + x) * D + 16 * s + 8 * h];
 
-        // K tile in LDS as [D/8][64 keys][8] (A fragments are then contiguous 16-byte reads),
-        // V tile as [8 octets][D][8], both filled by direct global->LDS copies.
-        auto stage_kv = [&](int buf, int j0) {
-            bf16_t *ks = (bf16_t *)stage[buf];
-            bf16_t *vs = ks + kKeyTile * D;
+        // K tile in LDS as [D/8][KEYT keys][8] (A fragments are then contiguous 16-byte reads),
+        // V tile as [KEYT/8 octets][D][8], both filled by direct global->LDS copies.
+        const int ntiles_wg = (i0 + TOK_WG - jb) / KEYT;         // tiles staged by the workgroup
+        const int ntiles_w = (tok_w0 + TOK_WAVE - jb) / KEYT;    // tiles this wave has keys in
+        auto stage_kv = [&](int kt) {
+            const int ktc = min(kt, ntiles_wg - 1);              // clamped: keeps the copy count uniform
+            bf16_t *ks = (bf16_t *)(stage + (kt % NKV) * KV_BYTES);
+            bf16_t *vs = ks + KEYT * D;
+            const size_t j0 = urow + jb + (size_t)ktc * KEYT;
 #pragma unroll
-            for (int q = 0; q < D / 32; ++q) {
-                const int o = q * 4 + wave;               // d-octet handled by this wave
-                dma16(&K[(urow + j0 + lane) * D + 8 * o], ks + (size_t)o * kKeyTile * 8);
+            for (int q = 0; q < DMA_KV / 2; ++q) {
+                const int slot = q * kWg + tid;                  // (d-octet, key)
+                dma16(&K[(j0 + slot % KEYT) * D + 8 * (slot / KEYT)], ks + (size_t)(q * kWg + wave * 64) * 8);
             }
 #pragma unroll
-            for (int q = 0; q < kKeyTile * D / 8 / kWg; ++q)
-                dma16(&V8[(urow + j0) * D + (size_t)(q * kWg + tid) * 8], vs + (size_t)(q * kWg + wave * 64) * 8);
+            for (int q = 0; q < DMA_KV / 2; ++q)
+                dma16(&V8[j0 * D + (size_t)(q * kWg + tid) * 8], vs + (size_t)(q * kWg + wave * 64) * 8);
         };
 
-        const int ntiles = (i0 + TOK_WG - jb) / kKeyTile;
-        stage_kv(0, jb);
-        wait_all_memory();
-        __syncthreads();
-#pragma unroll 1
-        for (int kt = 0; kt < ntiles; ++kt) {
-            const int buf = kt & 1, j0 = jb + kt * kKeyTile;
-            if (kt + 1 < ntiles) stage_kv(buf ^ 1, j0 + kKeyTile);
-            if (j0 <= tok_w0 + TOK_WAVE - 1) {            // otherwise every key of this tile is masked
-                const bf16_t *ks = (const bf16_t *)stage[buf];
-                const bf16_t *vs = ks + kKeyTile * D;
+        f32x16 sc_cur, sc_nxt = {0};
+        bf16x8 p_prev[2] = {bf16x8{0}, bf16x8{0}};
+        bf16x8 kfr[KS];
+        // S^T[key][token] for item q (tile q / IPT, sub-tile, token tile)
+        auto score = [&](int q, int jsub, int jtt) {
+            const bf16_t *ks = (const bf16_t *)(stage + ((q / IPT) % NKV) * KV_BYTES);
+            if (jtt == 0) {
 #pragma unroll
-                for (int sub = 0; sub < kKeyTile / 32; ++sub) {
-                    const int key0 = j0 + 32 * sub;
-                    if (key0 > tok_w0 + TOK_WAVE - 1) continue;
-                    bf16x8 kfr[KS];
+                for (int s = 0; s < KS; ++s)
+                    kfr[s] = *(const bf16x8 *)&ks[((2 * s + h) * KEYT + 32 * jsub + x) * 8];
+            }
+            f32x16 sc = {0};
 #pragma unroll
-                    for (int s = 0; s < KS; ++s)
-                        kfr[s] = *(const bf16x8 *)&ks[((2 * s + h) * kKeyTile + 32 * sub + x) * 8];
+            for (int s = 0; s < KS; ++s) sc = mfma32(kfr[s], qfr[jtt][s], sc);
+            return sc;
+        };
+        // out^T += V^T P^T for item q with the packed weights p_prev
+        auto apply_pv = [&](int q, int jsub, int jtt) {
+            const bf16_t *vs = (const bf16_t *)(stage + ((q / IPT) % NKV) * KV_BYTES) + KEYT * D;
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) {
-                        const int tok0 = tok_w0 + 32 * tt;
-                        if (key0 > tok0 + 31) continue;   // tile entirely above the diagonal
-                        f32x16 sc = {0};                  // S^T[key][token]
+            for (int sp = 0; sp < 2; ++sp) {
+                const int oct = 4 * jsub + 2 * sp + h;
 #pragma unroll
-                        for (int s = 0; s < KS; ++s) sc = mfma32(kfr[s], qfr[tt][s], sc);
-                        const bool diag = key0 + 31 > tok0;
-                        float dsum = 0.f;
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            float w = pow_p(sc[v], P);
-                            if (diag) {
-                                const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
-                                w = key <= tok0 + x ? w : 0.f;
-                            }
-                            sc[v] = w;
-                            dsum += w;
-                        }
-                        den[tt] += dsum;
-                        // P^T as B operand.  The score registers give lane (token, h) the keys
-                        // 16sp + 8*(e/4) + 4h + e%4; one half-wave swap per register pair turns that
-                        // into keys 16sp + 8h + e, so that V^T fragments are whole token octets.
-#pragma unroll
-                        for (int sp = 0; sp < 2; ++sp) {
-                            const bf16x8 raw = cvt8_from16(sc, 8 * sp);
-                            uint4 w = __builtin_bit_cast(uint4, raw);
-                            const auto s0 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
-                            const auto s1 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
-                            w.x = s0[0]; w.z = s0[1]; w.y = s1[0]; w.w = s1[1];
-                            const bf16x8 pfr = __builtin_bit_cast(bf16x8, w);
-                            const int oct = 4 * sub + 2 * sp + h;
-#pragma unroll
-                            for (int ct = 0; ct < CT; ++ct) {
-                                const bf16x8 vfr = *(const bf16x8 *)&vs[(oct * D + 32 * ct + x) * 8];
-                                out[tt][ct] = mfma32(vfr, pfr, out[tt][ct]);
-                            }
-                        }
-                    }
+                for (int ct = 0; ct < CT; ++ct) {
+                    const bf16x8 vfr = *(const bf16x8 *)&vs[(oct * D + 32 * ct + x) * 8];
+                    out[jtt][ct] = mfma32(vfr, p_prev[sp], out[jtt][ct]);
                 }
             }
-            wait_all_memory();
-            __syncthreads();
+        };
+        // weights of item q: x^p, causal mask (diagonal tile only), row sums, bf16 pack.  The
+        // score registers give lane (token, h) the keys 16sp + 8*(e/4) + 4h + e%4; one half-wave
+        // swap per register pair turns that into keys 16sp + 8h + e, so that V^T fragments are
+        // whole token octets.
+        auto weights = [&](int jsub, int jtt, bool diag, int key0, int tok0, bf16x8 *pk) {
+            float dsum = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float w = pow_p(sc_cur[v], P);
+                if (diag) {
+                    const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
+                    w = key <= tok0 + x ? w : 0.f;
+                }
+                sc_cur[v] = w;
+                dsum += w;
+            }
+            den[jtt] += dsum;
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp) {
+                uint4 w = __builtin_bit_cast(uint4, cvt8_from16(sc_cur, 8 * sp));
+                const auto s0 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
+                const auto s1 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
+                w.x = s0[0]; w.z = s0[1]; w.y = s1[0]; w.w = s1[1];
+                pk[sp] = __builtin_bit_cast(bf16x8, w);
+            }
+        };
+
+#pragma unroll
+        for (int kt = 0; kt < NKV - 1; ++kt) stage_kv(kt);
+        wait_vmem_le<(NKV - 2) * DMA_KV>();
+        __syncthreads();
+        const int nitems = ntiles_w * IPT;
+        sc_cur = score(0, 0, 0);
+#pragma unroll 1
+        for (int kt = 0; kt < ntiles_wg; ++kt) {
+#pragma unroll
+            for (int j = 0; j < IPT; ++j) {
+                const int q = kt * IPT + j;
+                if (j == IPT - 1) {
+                    // the next tile must have landed for every wave before its first score;
+                    // the tile before this one is no longer read by anybody, refill its buffer
+                    wait_vmem_le<(NKV - 3) * DMA_KV>();
+                    __builtin_amdgcn_s_barrier();
+                    if (IPT > 1) stage_kv(kt + NKV - 1);
+                }
+                if (q < nitems) {                         // wave-uniform
+                    const int jn = (j + 1) % IPT, jp = (j + IPT - 1) % IPT;   // compile-time after unrolling
+                    __builtin_amdgcn_sched_barrier(0);
+                    sc_nxt = score(q + 1, jn / TT, jn % TT);           // garbage past the end, unused
+                    apply_pv(q - 1 < 0 ? 0 : q - 1, jp / TT, jp % TT);   // adds zeros at q == 0
+                    bf16x8 pk[2];
+                    const int key0 = jb + kt * KEYT + 32 * (j / TT), tok0 = tok_w0 + 32 * (j % TT);
+                    if (kt == ntiles_w - 1) weights(j / TT, j % TT, true, key0, tok0, pk);
+                    else weights(j / TT, j % TT, false, key0, tok0, pk);
+                    p_prev[0] = pk[0];
+                    p_prev[1] = pk[1];
+                    sc_cur = sc_nxt;
+                } else if (q == nitems) {
+                    // this wave's keys are exhausted: flush the pending item while its tile is
+                    // still in LDS (later iterations only keep the barriers and copies going)
+                    apply_pv(q - 1, (IPT - 1) / TT, (IPT - 1) % TT);
+                }
+                if (IPT == 1) {
+                    // with one item per tile the previous tile is read right after the barrier:
+                    // a second barrier separates those reads from the refill
+                    __builtin_amdgcn_s_barrier();
+                    stage_kv(kt + NKV - 1);
+                }
+            }
         }
+        if (nitems == ntiles_wg * IPT) apply_pv(nitems - 1, (IPT - 1) / TT, (IPT - 1) % TT);
+        wait_vmem_le<0>();                                // drain the clamped copies
+        __syncthreads();
     }
 
     // ---------------- cross-block term phi'(Q_l) Z_l (Section 3.1) ----------------
@@ -742,7 +790,8 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
         // numerator: for every a, T_a = Z_l[a]^T m_i (D x tokens), out += m_i[a] * T_a
         const bf16_t *zsrc = Zg + ((size_t)u * (t - 1) + (l - 1)) * R * R * D;
         constexpr int NCHUNK = R / ZA;
-        constexpr int DMA_PER_THREAD = Z_CHUNK_BYTES / 16 / kWg;     // 8
+        constexpr int DMA_Z = Z_CHUNK_BYTES / 16 / kWg;     // 8
+        constexpr int BUF_BYTES = Z_CHUNK_BYTES + MQ_CHUNK_BYTES;
         // m_i[a] of the chunk as fp32 [ZA][TOK_WG]: each thread converts MQ_PER consecutive a of
         // one token; loaded early into registers, written to LDS after the chunk's MFMAs
         constexpr int MQ_PER = ZA * TOK_WG / kWg;
@@ -750,17 +799,17 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
         const int mq_tok = tid % TOK_WG, mq_grp = tid / TOK_WG;
         mqvec mqv;
         auto stage_z = [&](int buf, int chunk) {
-            unsigned char *dst = stage[buf];
+            unsigned char *dst = stage + buf * BUF_BYTES;
             const bf16_t *src = zsrc + (size_t)chunk * ZA * Z_PER_A;
 #pragma unroll
-            for (int q = 0; q < DMA_PER_THREAD; ++q)
+            for (int q = 0; q < DMA_Z; ++q)
                 dma16(src + (size_t)(q * kWg + tid) * 8, dst + (size_t)(q * kWg + wave * 64) * 16);
         };
         auto load_mq = [&](int chunk) {
             mqv = *(const mqvec *)&MQ[(urow + i0 + mq_tok) * R + chunk * ZA + mq_grp * MQ_PER];
         };
         auto store_mq = [&](int buf) {
-            float *dst = (float *)(stage[buf] + Z_CHUNK_BYTES);      // [ZA][TOK_WG]
+            float *dst = (float *)(stage + buf * BUF_BYTES + Z_CHUNK_BYTES);      // [ZA][TOK_WG]
 #pragma unroll
             for (int e = 0; e < MQ_PER; ++e) dst[(mq_grp * MQ_PER + e) * TOK_WG + mq_tok] = (float)mqv[e];
         };
@@ -776,27 +825,43 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
                 stage_z(buf ^ 1, chunk + 1);
                 load_mq(chunk + 1);
             }
-            const bf16_t *zc = (const bf16_t *)stage[buf];
-            const float *mqs = (const float *)(stage[buf] + Z_CHUNK_BYTES);
+            const bf16_t *zc = (const bf16_t *)(stage + buf * BUF_BYTES);
+            const float *mqs = (const float *)(stage + buf * BUF_BYTES + Z_CHUNK_BYTES);
+            bf16x8 zf[2][RS];                               // fragments of Z[a][.][value tile]
+            auto load_zf = [&](int ai, int ct) {
+                const bf16_t *za = zc + ai * Z_PER_A;
+#pragma unroll
+                for (int s = 0; s < RS; ++s)
+                    zf[ct & 1][s] = *(const bf16x8 *)&za[((2 * s + h) * D + 32 * ct + x) * 8];
+            };
+            auto chain = [&](int ct, int tt) {
+                f32x16 tacc = {0};
+#pragma unroll
+                for (int s = 0; s < RS; ++s) tacc = mfma32(zf[ct & 1][s], mfr[tt][s], tacc);
+                return tacc;
+            };
+            static_assert(CT % 2 == 0, "fragment ping-pong");
+            load_zf(0, 0);
+            f32x16 t_cur = chain(0, 0);
 #pragma unroll 1
             for (int ai = 0; ai < ZA; ++ai) {
-                const bf16_t *za = zc + ai * Z_PER_A;     // [R/8][D][8]
-                float mq[TT];
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt) mq[tt] = mqs[ai * TOK_WG + wave * TOK_WAVE + 32 * tt + x];
+                for (int it = 0; it < CT * TT; ++it) {
+                    const int ct = it / TT, tt = it % TT;
+                    const int itn = (it + 1) % (CT * TT), ctn = itn / TT, ttn = itn % TT;
+                    __builtin_amdgcn_sched_barrier(0);
+                    // fragments of the next value tile (the first one of the next a after the
+                    // last; clamped at the end of the chunk, where the result is discarded)
+                    if (tt == 0) load_zf(ct + 1 < CT ? ai : min(ai + 1, ZA - 1), (ct + 1) % CT);
+                    const float mq = mqs[ai * TOK_WG + wave * TOK_WAVE + 32 * tt + x];
+                    const f32x16 t_nxt = chain(ctn, ttn);
+                    out[tt][ct] += mq * t_cur;
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    bf16x8 zf[RS];
-#pragma unroll
-                    for (int s = 0; s < RS; ++s)
-                        zf[s] = *(const bf16x8 *)&za[((2 * s + h) * D + 32 * ct + x) * 8];
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) {
-                        f32x16 tacc = {0};
-#pragma unroll
-                        for (int s = 0; s < RS; ++s) tacc = mfma32(zf[s], mfr[tt][s], tacc);
-                        out[tt][ct] += mq[tt] * tacc;
+                    for (int s = 0; s < RS; ++s) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, 16 / RS, 0);
                     }
+                    t_cur = t_nxt;
                 }
             }
             if (chunk + 1 < NCHUNK) store_mq(buf ^ 1);
