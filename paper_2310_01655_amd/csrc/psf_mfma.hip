@@ -503,7 +503,9 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
     };
 
     auto snapshot = [&](int l) {
-        // Z_{l+1} = sum over blocks 0..l, stored [a][b'/8][c][8] bf16
+        // Z_{l+1} = sum over blocks 0..l, stored [a][b'/8][c][8] bf16.  Z[a][b'] = Z[b'][a]
+        // (phi' = m (x) m), so the output kernel only contracts b' >= a: entries with b' > a are
+        // stored doubled, b' < a as zero.
         bf16_t *z = Zg + ((size_t)u * (t - 1) + l) * R * R * D;
 #pragma unroll
         for (int i = 0; i < NA; ++i)
@@ -511,8 +513,13 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
             for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
-                    f32x4 q4 = {acc[i][ct][4 * gq], acc[i][ct][4 * gq + 1], acc[i][ct][4 * gq + 2],
-                                acc[i][ct][4 * gq + 3]};
+                    f32x4 q4;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int bq = 32 * bh + 8 * gq + 4 * h + j;
+                        const float wsym = bq > a0 + i ? 2.f : (bq == a0 + i ? 1.f : 0.f);
+                        q4[j] = acc[i][ct][4 * gq + j] * wsym;
+                    }
                     const size_t o = 4 * bh + gq;
                     *(bf16x4 *)&z[(((size_t)(a0 + i) * (R / 8) + o) * D + 32 * ct + x) * 8 + 4 * h] = cvt4(q4);
                 }
@@ -567,7 +574,7 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
 // the in-block phase; the m_i[a] * T_a updates in the cross-block phase).
 // ------------------------------------------------------------------------------------
 template <int R, int D, int P, int TT>
-__global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+__global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                 const bf16_t *__restrict__ V8,
                                                 const bf16_t *__restrict__ MQ,
                                                 const bf16_t *__restrict__ Zg,
@@ -646,7 +653,11 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
 
         f32x16 sc_cur, sc_nxt = {0};
         bf16x8 p_prev[2] = {bf16x8{0}, bf16x8{0}};
-        bf16x8 kfr[KS];
+        bf16x8 kfr[KS], vfr[2][CT];
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp)                    // the pipeline's first P V step multiplies these by zero weights
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) vfr[sp][ct] = bf16x8{0};
         // S^T[key][token] for item q (tile q / IPT, sub-tile, token tile)
         auto score = [&](int q, int jsub, int jtt) {
             const bf16_t *ks = (const bf16_t *)(stage + ((q / IPT) % NKV) * KV_BYTES);
@@ -663,15 +674,17 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
         // out^T += V^T P^T for item q with the packed weights p_prev
         auto apply_pv = [&](int q, int jsub, int jtt) {
             const bf16_t *vs = (const bf16_t *)(stage + ((q / IPT) % NKV) * KV_BYTES) + KEYT * D;
+            if (jtt == 0) {                               // fragments serve all token tiles of the sub-tile
 #pragma unroll
-            for (int sp = 0; sp < 2; ++sp) {
-                const int oct = 4 * jsub + 2 * sp + h;
+                for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    const bf16x8 vfr = *(const bf16x8 *)&vs[(oct * D + 32 * ct + x) * 8];
-                    out[jtt][ct] = mfma32(vfr, p_prev[sp], out[jtt][ct]);
-                }
+                    for (int ct = 0; ct < CT; ++ct)
+                        vfr[sp][ct] = *(const bf16x8 *)&vs[((4 * jsub + 2 * sp + h) * D + 32 * ct + x) * 8];
             }
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) out[jtt][ct] = mfma32(vfr[sp][ct], p_prev[sp], out[jtt][ct]);
         };
         // weights of item q: x^p, causal mask (diagonal tile only), row sums, bf16 pack.  The
         // score registers give lane (token, h) the keys 16sp + 8*(e/4) + 4h + e%4; one half-wave
@@ -790,28 +803,42 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
         // numerator: for every a, T_a = Z_l[a]^T m_i (D x tokens), out += m_i[a] * T_a
         const bf16_t *zsrc = Zg + ((size_t)u * (t - 1) + (l - 1)) * R * R * D;
         constexpr int NCHUNK = R / ZA;
-        constexpr int DMA_Z = Z_CHUNK_BYTES / 16 / kWg;     // 8
         constexpr int BUF_BYTES = Z_CHUNK_BYTES + MQ_CHUNK_BYTES;
         // m_i[a] of the chunk as fp32 [ZA][TOK_WG]: each thread converts MQ_PER consecutive a of
-        // one token; loaded early into registers, written to LDS after the chunk's MFMAs
-        constexpr int MQ_PER = ZA * TOK_WG / kWg;
+        // MQ_TOKS tokens; loaded early into registers, written to LDS after the chunk's MFMAs
+        constexpr int MQ_TOKS = TOK_WG > kWg ? TOK_WG / kWg : 1;
+        constexpr int MQ_PER = ZA * TOK_WG / kWg / MQ_TOKS;
         typedef __bf16 mqvec __attribute__((ext_vector_type(MQ_PER)));
         const int mq_tok = tid % TOK_WG, mq_grp = tid / TOK_WG;
-        mqvec mqv;
+        mqvec mqv[MQ_TOKS];
+        // Z is stored with the symmetry weights baked in (see k_state): for sketch row a only
+        // b' >= 16 * (a / 16) contributes, i.e. 16-wide steps s >= s0 = a / 16 and octets >= 2 s0.
+        // All rows of a chunk share s0.
+        static_assert(16 % ZA == 0, "one s0 per chunk");
         auto stage_z = [&](int buf, int chunk) {
+            const int s0 = chunk * ZA / 16;
+            const int per_a = (R / 8 - 2 * s0) * D;          // 16-byte units needed per row a
+            const int per_thread = per_a * ZA / kWg;
             unsigned char *dst = stage + buf * BUF_BYTES;
             const bf16_t *src = zsrc + (size_t)chunk * ZA * Z_PER_A;
-#pragma unroll
-            for (int q = 0; q < DMA_Z; ++q)
-                dma16(src + (size_t)(q * kWg + tid) * 8, dst + (size_t)(q * kWg + wave * 64) * 16);
+            for (int q = 0; q < per_thread; ++q) {
+                const int w0 = q * kWg + wave * 64;          // first unit of this wave's copy
+                const int off = (w0 / per_a) * (Z_PER_A / 8) + 2 * s0 * D + w0 % per_a;   // in 16-byte units
+                dma16(src + (size_t)(off + lane) * 8, dst + (size_t)off * 16);
+            }
         };
         auto load_mq = [&](int chunk) {
-            mqv = *(const mqvec *)&MQ[(urow + i0 + mq_tok) * R + chunk * ZA + mq_grp * MQ_PER];
+#pragma unroll
+            for (int k = 0; k < MQ_TOKS; ++k)
+                mqv[k] = *(const mqvec *)&MQ[(urow + i0 + mq_tok + k * kWg) * R + chunk * ZA + mq_grp * MQ_PER];
         };
         auto store_mq = [&](int buf) {
             float *dst = (float *)(stage + buf * BUF_BYTES + Z_CHUNK_BYTES);      // [ZA][TOK_WG]
 #pragma unroll
-            for (int e = 0; e < MQ_PER; ++e) dst[(mq_grp * MQ_PER + e) * TOK_WG + mq_tok] = (float)mqv[e];
+            for (int k = 0; k < MQ_TOKS; ++k)
+#pragma unroll
+                for (int e = 0; e < MQ_PER; ++e)
+                    dst[(mq_grp * MQ_PER + e) * TOK_WG + mq_tok + k * kWg] = (float)mqv[k][e];
         };
         stage_z(0, 0);
         load_mq(0);
@@ -828,41 +855,52 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
             const bf16_t *zc = (const bf16_t *)(stage + buf * BUF_BYTES);
             const float *mqs = (const float *)(stage + buf * BUF_BYTES + Z_CHUNK_BYTES);
             bf16x8 zf[2][RS];                               // fragments of Z[a][.][value tile]
-            auto load_zf = [&](int ai, int ct) {
-                const bf16_t *za = zc + ai * Z_PER_A;
+            auto run_chunk = [&](auto s0_tag) {
+                constexpr int S0 = decltype(s0_tag)::value;  // first 16-wide step with b' >= a
+                constexpr int NS = RS - S0;
+                auto load_zf = [&](int ai, int ct) {
+                    const bf16_t *za = zc + ai * Z_PER_A;
 #pragma unroll
-                for (int s = 0; s < RS; ++s)
-                    zf[ct & 1][s] = *(const bf16x8 *)&za[((2 * s + h) * D + 32 * ct + x) * 8];
-            };
-            auto chain = [&](int ct, int tt) {
-                f32x16 tacc = {0};
+                    for (int s = S0; s < RS; ++s)
+                        zf[ct & 1][s] = *(const bf16x8 *)&za[((2 * s + h) * D + 32 * ct + x) * 8];
+                };
+                auto chain = [&](int ct, int tt) {
+                    f32x16 tacc = {0};
 #pragma unroll
-                for (int s = 0; s < RS; ++s) tacc = mfma32(zf[ct & 1][s], mfr[tt][s], tacc);
-                return tacc;
+                    for (int s = S0; s < RS; ++s) tacc = mfma32(zf[ct & 1][s], mfr[tt][s], tacc);
+                    return tacc;
+                };
+                load_zf(0, 0);
+                f32x16 t_cur = chain(0, 0);
+#pragma unroll 1
+                for (int ai = 0; ai < ZA; ++ai) {
+#pragma unroll
+                    for (int it = 0; it < CT * TT; ++it) {
+                        const int ct = it / TT, tt = it % TT;
+                        const int itn = (it + 1) % (CT * TT), ctn = itn / TT, ttn = itn % TT;
+                        __builtin_amdgcn_sched_barrier(0);
+                        // fragments of the next value tile (the first one of the next a after the
+                        // last; clamped at the end of the chunk, where the result is discarded)
+                        if (tt == 0) load_zf(ct + 1 < CT ? ai : min(ai + 1, ZA - 1), (ct + 1) % CT);
+                        const float mq = mqs[ai * TOK_WG + wave * TOK_WAVE + 32 * tt + x];
+                        const f32x16 t_nxt = chain(ctn, ttn);
+                        out[tt][ct] += mq * t_cur;
+#pragma unroll
+                        for (int s = 0; s < NS; ++s) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x002, 16 / NS, 0);
+                        }
+                        t_cur = t_nxt;
+                    }
+                }
             };
             static_assert(CT % 2 == 0, "fragment ping-pong");
-            load_zf(0, 0);
-            f32x16 t_cur = chain(0, 0);
-#pragma unroll 1
-            for (int ai = 0; ai < ZA; ++ai) {
-#pragma unroll
-                for (int it = 0; it < CT * TT; ++it) {
-                    const int ct = it / TT, tt = it % TT;
-                    const int itn = (it + 1) % (CT * TT), ctn = itn / TT, ttn = itn % TT;
-                    __builtin_amdgcn_sched_barrier(0);
-                    // fragments of the next value tile (the first one of the next a after the
-                    // last; clamped at the end of the chunk, where the result is discarded)
-                    if (tt == 0) load_zf(ct + 1 < CT ? ai : min(ai + 1, ZA - 1), (ct + 1) % CT);
-                    const float mq = mqs[ai * TOK_WG + wave * TOK_WAVE + 32 * tt + x];
-                    const f32x16 t_nxt = chain(ctn, ttn);
-                    out[tt][ct] += mq * t_cur;
-#pragma unroll
-                    for (int s = 0; s < RS; ++s) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x002, 16 / RS, 0);
-                    }
-                    t_cur = t_nxt;
-                }
+            static_assert(RS <= 4, "step variants");
+            switch (chunk * ZA / 16) {
+            case 0: run_chunk(std::integral_constant<int, 0>{}); break;
+            case 1: run_chunk(std::integral_constant<int, RS >= 2 ? 1 : 0>{}); break;
+            case 2: run_chunk(std::integral_constant<int, RS >= 3 ? 2 : 0>{}); break;
+            default: run_chunk(std::integral_constant<int, RS >= 4 ? 3 : 0>{}); break;
             }
             if (chunk + 1 < NCHUNK) store_mq(buf ^ 1);
             wait_all_memory();
@@ -979,6 +1017,8 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     }
     if (tm) tm->mark();
     {
+        // tokens per workgroup = 128 * TT.  (TT = 4 halves the LDS traffic per token but needs
+        // one workgroup per CU; it measured 1.7x slower than TT = 2 with two per CU.)
         constexpr int TT = (D == 64) ? 2 : 1;
         const unsigned grid = (unsigned)((size_t)pb.units * (pb.n / (128 * TT)));
         hipLaunchKernelGGL((k_out<R, D, P, TT>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
