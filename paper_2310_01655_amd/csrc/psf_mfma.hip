@@ -194,6 +194,7 @@ __global__ __launch_bounds__(kWg) void k_sketch(const bf16_t *__restrict__ X,
 {
     __shared__ __attribute__((aligned(16))) SketchLds<D, R> lds;
     __shared__ float red[QSIDE ? 1 : 4][QSIDE ? 1 : 32][33];
+    __shared__ __attribute__((aligned(16))) bf16_t qtile[QSIDE ? 4 : 1][QSIDE ? 32 : 1][R + 8];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int x = lane & 31, h = lane >> 5;
     const size_t tok_wg0 = (size_t)blockIdx.x * tiles_per_wg * 128;   // global token (row) index
@@ -265,15 +266,23 @@ __global__ __launch_bounds__(kWg) void k_sketch(const bf16_t *__restrict__ X,
         }
 
         if (QSIDE) {
-            // lane = token x, register v = sketch column 32ct + 8(v/4) + 4h + v%4
+            // lane = token x, register v = sketch column 32ct + 8(v/4) + 4h + v%4.  The 32 x R
+            // tile goes through LDS so that the row-major store is contiguous (16 bytes per lane).
+            bf16_t *tile = qtile[wave][0];
 #pragma unroll
             for (int ct = 0; ct < NT; ++ct)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const int c0 = 32 * ct + 8 * gq + 4 * h;
                     f32x4 q4 = {m[ct][4 * gq], m[ct][4 * gq + 1], m[ct][4 * gq + 2], m[ct][4 * gq + 3]};
-                    *(bf16x4 *)&M_rm[(row0 + x) * R + c0] = cvt4(q4);
+                    *(bf16x4 *)&tile[x * (R + 8) + c0] = cvt4(q4);
                 }
+            __builtin_amdgcn_s_waitcnt((0x3F & 0xF) | (0x7 << 4) | (0x0 << 8) | ((0x3F >> 4) << 14));   // own LDS writes
+#pragma unroll
+            for (int i = 0; i < 32 * R / 8 / 64; ++i) {
+                const int w = i * 64 + lane, tok = w / (R / 8), part = w % (R / 8);
+                *(uint4 *)&M_rm[(row0 + tok) * R + 8 * part] = *(const uint4 *)&tile[tok * (R + 8) + 8 * part];
+            }
         } else {
             // lane = sketch column 32ct + x, register v = token 8(v/4) + 4h + v%4
 #pragma unroll
