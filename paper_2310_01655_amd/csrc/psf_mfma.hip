@@ -415,13 +415,14 @@ template <int CT>
 struct StateOps {           // LDS operands of one 16-token step
     f32x4 af;               // m_j[a] source values (see gen_frag)
     f32x8 bfv;              // m_j[b'] for this lane's b' and 8 tokens
+    f32x8 bfv2;             // same for the second b' range of a wave with mixed tiles
     bf16x8 vf[CT];          // V fragments (B operand)
 };
 
-// One 16-token step: for every a of the wave, two things overlap -- the MFMAs that consume the
-// fragment generated last, and the VALU work generating the next fragment (the first one of
-// the following step comes from `nxt`).
-template <int NA, int CT, int AI>
+// One 16-token step: for every tile of the wave, two things overlap -- the MFMAs that consume
+// the fragment generated last, and the VALU work generating the next fragment (the first one
+// of the following step comes from `nxt`).  MIXED: tiles 1.. use the second b' range.
+template <int NA, int CT, int AI, bool MIXED>
 struct StateStep {
     static __device__ __forceinline__ void run(const StateOps<CT> &cur, const StateOps<CT> &nxt,
                                                bf16x8 &frag, f32x16 (*acc)[CT])
@@ -429,7 +430,7 @@ struct StateStep {
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) acc[AI][ct] = mfma32(frag, cur.vf[ct], acc[AI][ct]);
         if constexpr (AI + 1 < NA) {
-            frag = gen_frag<AI + 1>(cur.af, cur.bfv);
+            frag = gen_frag<AI + 1>(cur.af, MIXED ? cur.bfv2 : cur.bfv);
         } else {
             frag = gen_frag<0>(nxt.af, nxt.bfv);
         }
@@ -439,40 +440,51 @@ struct StateStep {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 12 / CT, 0);
         }
-        if constexpr (AI + 1 < NA) StateStep<NA, CT, AI + 1>::run(cur, nxt, frag, acc);
+        if constexpr (AI + 1 < NA) StateStep<NA, CT, AI + 1, MIXED>::run(cur, nxt, frag, acc);
     }
 };
 
-template <int R, int D, int NA>
-__global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
-                                               const bf16_t *__restrict__ V8,
-                                               bf16_t *__restrict__ Zg, int n, int b, int t,
-                                               int units)
+// SYM (R = 64 only): Z[a][b'] = Z[b'][a] and the output kernel reads only b' >= 16*(a/16), so
+// the 32 tiles (a >= 32, b' < 32) are never needed.  The remaining 96 tiles (a, 32-wide b'
+// range) of a unit are dealt three per wave to 32 waves = 8 workgroups: waves 0..20 take
+// b' in [32,64) with a = 3w..3w+2, waves 21..30 take b' in [0,32) with a = 3(w-21)..+2, and
+// wave 31 takes the leftovers (63, upper), (30, lower), (31, lower).
+template <int R, int D, int NA, bool SYM, bool MIXED>
+__device__ __forceinline__ void state_body(const float *__restrict__ M8, const bf16_t *__restrict__ V8,
+                                           bf16_t *__restrict__ Zg, int n, int b, int t, int u, int grp,
+                                           unsigned char *lds_base)
 {
     constexpr int NB = R / 32;                 // 32-wide b' ranges
-    constexpr int AG = NA * 4 / NB;            // sketch rows a per workgroup
+    constexpr int AG = NA * 4 / NB;            // sketch rows a per workgroup (!SYM)
     constexpr int CT = D / 32;
     constexpr int TC = kStateChunk;
     constexpr int STEPS = TC / 16;
-    constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2;
-    static_assert(NA <= 8, "DPP source lanes");
+    constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2, BUF_BYTES = M_BYTES + V_BYTES;
     constexpr int NBUF = 4;                    // staged chunks in flight: covers HBM latency
-    constexpr int DMA_PER_CHUNK = (M_BYTES + V_BYTES) / 16 / kWg;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF][M_BYTES + V_BYTES];
-
-    // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
-    // contiguous range of (unit, group) pairs; the groups of one unit then share one L2.
-    int wg = blockIdx.x;
-    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    constexpr int GROUPS = R / AG;
-    const int u = wg / GROUPS, grp = wg % GROUPS;
-    if (u >= units) return;
+    constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
+    static_assert(NA <= 8, "DPP source lanes");
+    static_assert(STEPS % 2 == 0, "operand ping-pong");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int x = lane & 31, h = lane >> 5, n16 = lane & 15;
-    const int bh = wave % NB, ag = wave / NB;
-    const int a0 = grp * AG + ag * NA;
-    const int a_src = a0 + ((n16 & 7) < NA ? (n16 & 7) : NA - 1);
+    // tiles of this wave: sketch row ta[i], b' range 32 * tb[i]
+    int ta[NA], tb[NA];
+    if (SYM) {
+        const int w = grp * 4 + wave;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            if (MIXED) { ta[i] = i == 0 ? 63 : 29 + i; tb[i] = i == 0 ? 1 : 0; }
+            else if (w < 21) { ta[i] = 3 * w + i; tb[i] = 1; }
+            else { ta[i] = 3 * (w - 21) + i; tb[i] = 0; }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) { ta[i] = grp * AG + (wave / NB) * NA + i; tb[i] = wave % NB; }
+    }
+    int a_src = ta[NA - 1];
+#pragma unroll
+    for (int i = 0; i < NA - 1; ++i)
+        if ((n16 & 7) == i) a_src = ta[i];
     const int q_src = n16 >> 3;
 
     f32x16 acc[NA][CT];
@@ -484,33 +496,38 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
     const float *gm = M8 + (size_t)u * n * R;
     const bf16_t *gv = V8 + (size_t)u * n * D;
     const int chunks = (t - 1) * (b / TC), chunks_per_block = b / TC;
-    if (chunks == 0) return;
 
     auto stage = [&](int buf, int chunk) {      // straight copies: global layout == LDS layout
         const float *sm = gm + (size_t)chunk * TC * R;
         const bf16_t *sv = gv + (size_t)chunk * TC * D;
+        unsigned char *dst = lds_base + buf * BUF_BYTES;
 #pragma unroll
         for (int q = 0; q < M_BYTES / 16 / kWg; ++q)
-            dma16(sm + (size_t)(q * kWg + tid) * 4, lds[buf] + (size_t)(q * kWg + wave * 64) * 16);
+            dma16(sm + (size_t)(q * kWg + tid) * 4, dst + (size_t)(q * kWg + wave * 64) * 16);
 #pragma unroll
         for (int q = 0; q < V_BYTES / 16 / kWg; ++q)
-            dma16(sv + (size_t)(q * kWg + tid) * 8, lds[buf] + M_BYTES + (size_t)(q * kWg + wave * 64) * 16);
+            dma16(sv + (size_t)(q * kWg + tid) * 8, dst + M_BYTES + (size_t)(q * kWg + wave * 64) * 16);
     };
     auto load_ops = [&](int buf, int s) {
         StateOps<CT> o;
-        const float *lm = (const float *)lds[buf];
-        const bf16_t *lv = (const bf16_t *)(lds[buf] + M_BYTES);
+        const float *lm = (const float *)(lds_base + buf * BUF_BYTES);
+        const bf16_t *lv = (const bf16_t *)(lds_base + buf * BUF_BYTES + M_BYTES);
         const int oct = 2 * s + h;
-        const f32x4 b_lo = *(const f32x4 *)&lm[((oct * 2 + 0) * R + 32 * bh + x) * 4];
-        const f32x4 b_hi = *(const f32x4 *)&lm[((oct * 2 + 1) * R + 32 * bh + x) * 4];
+        const f32x4 b_lo = *(const f32x4 *)&lm[((oct * 2 + 0) * R + 32 * tb[0] + x) * 4];
+        const f32x4 b_hi = *(const f32x4 *)&lm[((oct * 2 + 1) * R + 32 * tb[0] + x) * 4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) { o.bfv[e] = b_lo[e]; o.bfv[4 + e] = b_hi[e]; }
+        if (MIXED) {
+            const f32x4 c_lo = *(const f32x4 *)&lm[((oct * 2 + 0) * R + 32 * tb[NA - 1] + x) * 4];
+            const f32x4 c_hi = *(const f32x4 *)&lm[((oct * 2 + 1) * R + 32 * tb[NA - 1] + x) * 4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { o.bfv2[e] = c_lo[e]; o.bfv2[4 + e] = c_hi[e]; }
+        }
         o.af = *(const f32x4 *)&lm[((oct * 2 + q_src) * R + a_src) * 4];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) o.vf[ct] = *(const bf16x8 *)&lv[(oct * D + 32 * ct + x) * 8];
         return o;
     };
-
     auto snapshot = [&](int l) {
         // Z_{l+1} = sum over blocks 0..l, stored [a][b'/8][c][8] bf16.  Z[a][b'] = Z[b'][a]
         // (phi' = m (x) m), so the output kernel only contracts b' >= a: entries with b' > a are
@@ -525,27 +542,18 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
                     f32x4 q4;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const int bq = 32 * bh + 8 * gq + 4 * h + j;
-                        const float wsym = bq > a0 + i ? 2.f : (bq == a0 + i ? 1.f : 0.f);
+                        const int bq = 32 * tb[i] + 8 * gq + 4 * h + j;
+                        const float wsym = bq > ta[i] ? 2.f : (bq == ta[i] ? 1.f : 0.f);
                         q4[j] = acc[i][ct][4 * gq + j] * wsym;
                     }
-                    const size_t o = 4 * bh + gq;
-                    *(bf16x4 *)&z[(((size_t)(a0 + i) * (R / 8) + o) * D + 32 * ct + x) * 8 + 4 * h] = cvt4(q4);
+                    const size_t o = 4 * tb[i] + gq;
+                    *(bf16x4 *)&z[(((size_t)ta[i] * (R / 8) + o) * D + 32 * ct + x) * 8 + 4 * h] = cvt4(q4);
                 }
     };
 
-    // Prologue: NBUF-1 chunks in flight, the first one landed.  Chunk indices past the end are
-    // clamped: the copies are redundant but keep the in-flight count, and with it the wait
-    // below, the same in every iteration.
-#pragma unroll
-    for (int c = 0; c < NBUF - 1; ++c) stage(c, min(c, chunks - 1));
-    wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
-    __syncthreads();
     StateOps<CT> ops[2];
     ops[0] = load_ops(0, 0);
     bf16x8 frag = gen_frag<0>(ops[0].af, ops[0].bfv);
-    static_assert(STEPS % 2 == 0, "operand ping-pong");
-
     // One chunk = STEPS steps.  Operands of step s+1 are read from LDS at the start of step s.
     // Before the last step the next chunk must have landed for every wave (wait + barrier);
     // after that barrier nobody reads this chunk's buffer again, so the next iteration may
@@ -567,12 +575,61 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
                 }
                 __builtin_amdgcn_sched_barrier(0);      // steps are scheduled one at a time
                 ops[(s + 1) & 1] = (s + 1 < STEPS) ? load_ops(buf, s + 1) : load_ops(nbuf, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 3 + CT, 0);      // LDS reads first
-                StateStep<NA, CT, 0>::run(ops[s & 1], ops[(s + 1) & 1], frag, acc);
+                __builtin_amdgcn_sched_group_barrier(0x100, 3 + CT + (MIXED ? 2 : 0), 0);   // LDS reads first
+                StateStep<NA, CT, 0, MIXED>::run(ops[s & 1], ops[(s + 1) & 1], frag, acc);
             }
         }
         snapshot(l);
     }
+}
+
+template <int R, int D, int NA, bool SYM>
+__global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
+                                               const bf16_t *__restrict__ V8,
+                                               bf16_t *__restrict__ Zg, int n, int b, int t,
+                                               int units)
+{
+    constexpr int TC = kStateChunk, NBUF = 4;
+    constexpr int BUF_BYTES = TC * R * 4 + TC * D * 2;
+    constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
+    constexpr int AG = NA * 4 / (R / 32);
+    static_assert(!SYM || (R == 64 && NA == 3), "tile deal of the symmetric variant");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF * BUF_BYTES];
+
+    // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
+    // contiguous range of (unit, group) pairs; the groups of one unit then share one L2.
+    int wg = blockIdx.x;
+    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    constexpr int GROUPS = SYM ? 8 : R / AG;
+    const int u = wg / GROUPS, grp = wg % GROUPS;
+    if (u >= units || t < 2) return;
+
+    // Prologue shared by both bodies: NBUF-1 chunks in flight, the first one landed.  Chunk
+    // indices past the end are clamped: the copies are redundant but keep the in-flight count,
+    // and with it the waits, the same in every iteration.
+    {
+        const int tid = threadIdx.x, wave = tid >> 6;
+        const int chunks = (t - 1) * (b / TC);
+        const float *gm = M8 + (size_t)u * n * R;
+        const bf16_t *gv = V8 + (size_t)u * n * D;
+#pragma unroll
+        for (int c = 0; c < NBUF - 1; ++c) {
+            const int chunk = min(c, chunks - 1);
+            unsigned char *dst = lds + c * BUF_BYTES;
+#pragma unroll
+            for (int q = 0; q < TC * R * 4 / 16 / kWg; ++q)
+                dma16(gm + (size_t)chunk * TC * R + (size_t)(q * kWg + tid) * 4, dst + (size_t)(q * kWg + wave * 64) * 16);
+#pragma unroll
+            for (int q = 0; q < TC * D * 2 / 16 / kWg; ++q)
+                dma16(gv + (size_t)chunk * TC * D + (size_t)(q * kWg + tid) * 8,
+                      dst + TC * R * 4 + (size_t)(q * kWg + wave * 64) * 16);
+        }
+        wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
+        __syncthreads();
+    }
+    // wave 31 of a unit holds tiles from both b' ranges and runs the body that reads both
+    if (SYM && grp * 4 + (int)(threadIdx.x >> 6) == 31) state_body<R, D, NA, SYM, true>(M8, V8, Zg, n, b, t, u, grp, lds);
+    else state_body<R, D, NA, SYM, false>(M8, V8, Zg, n, b, t, u, grp, lds);
 }
 
 // ------------------------------------------------------------------------------------
@@ -824,17 +881,18 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
         // b' >= 16 * (a / 16) contributes, i.e. 16-wide steps s >= s0 = a / 16 and octets >= 2 s0.
         // All rows of a chunk share s0.
         static_assert(16 % ZA == 0, "one s0 per chunk");
-        auto stage_z = [&](int buf, int chunk) {
+        // one 16-byte-per-lane copy (number q of this thread) of the needed part of a chunk
+        auto z_copies = [&](int chunk) { return (R / 8 - 2 * (chunk * ZA / 16)) * D * ZA / kWg; };
+        auto stage_z_one = [&](int buf, int chunk, int q) {
             const int s0 = chunk * ZA / 16;
             const int per_a = (R / 8 - 2 * s0) * D;          // 16-byte units needed per row a
-            const int per_thread = per_a * ZA / kWg;
-            unsigned char *dst = stage + buf * BUF_BYTES;
-            const bf16_t *src = zsrc + (size_t)chunk * ZA * Z_PER_A;
-            for (int q = 0; q < per_thread; ++q) {
-                const int w0 = q * kWg + wave * 64;          // first unit of this wave's copy
-                const int off = (w0 / per_a) * (Z_PER_A / 8) + 2 * s0 * D + w0 % per_a;   // in 16-byte units
-                dma16(src + (size_t)(off + lane) * 8, dst + (size_t)off * 16);
-            }
+            const int w0 = q * kWg + wave * 64;              // first unit of this wave's copy
+            const int off = (w0 / per_a) * (Z_PER_A / 8) + 2 * s0 * D + w0 % per_a;   // in 16-byte units
+            dma16(zsrc + (size_t)chunk * ZA * Z_PER_A + (size_t)(off + lane) * 8,
+                  stage + buf * BUF_BYTES + (size_t)off * 16);
+        };
+        auto stage_z = [&](int buf, int chunk) {
+            for (int q = 0; q < z_copies(chunk); ++q) stage_z_one(buf, chunk, q);
         };
         auto load_mq = [&](int chunk) {
 #pragma unroll
@@ -857,10 +915,11 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
 #pragma unroll 1
         for (int chunk = 0; chunk < NCHUNK; ++chunk) {
             const int buf = chunk & 1;
-            if (chunk + 1 < NCHUNK) {
-                stage_z(buf ^ 1, chunk + 1);
-                load_mq(chunk + 1);
-            }
+            // the next chunk's copies are issued a few per row a inside the loop below: issued
+            // back to back they stall this wave on the memory pipeline's queue
+            const int n_copies = chunk + 1 < NCHUNK ? z_copies(chunk + 1) : 0;
+            constexpr int COPIES_PER_A = (R / 8 * D * ZA / kWg + ZA - 1) / ZA;
+            if (chunk + 1 < NCHUNK) load_mq(chunk + 1);
             const bf16_t *zc = (const bf16_t *)(stage + buf * BUF_BYTES);
             const float *mqs = (const float *)(stage + buf * BUF_BYTES + Z_CHUNK_BYTES);
             bf16x8 zf[2][RS];                               // fragments of Z[a][.][value tile]
@@ -883,6 +942,9 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
                 f32x16 t_cur = chain(0, 0);
 #pragma unroll 1
                 for (int ai = 0; ai < ZA; ++ai) {
+#pragma unroll
+                    for (int c = 0; c < COPIES_PER_A; ++c)
+                        if (ai * COPIES_PER_A + c < n_copies) stage_z_one(buf ^ 1, chunk + 1, ai * COPIES_PER_A + c);
 #pragma unroll
                     for (int it = 0; it < CT * TT; ++it) {
                         const int ct = it / TT, tt = it % TT;
@@ -1017,11 +1079,17 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     }
     if (tm) tm->mark();
     if (pb.t > 1) {
-        constexpr int NA = (D == 64) ? 4 : 2;
-        constexpr int AG = NA * 4 / (R / 32);
-        const unsigned grid = (unsigned)(pb.units * (R / AG));
-        hipLaunchKernelGGL((k_state<R, D, NA>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg, pb.n, pb.b,
-                           pb.t, pb.units);
+        if constexpr (R == 64 && D == 64) {
+            // symmetric tile deal: 96 of the 128 (a, b' range) tiles, three per wave
+            hipLaunchKernelGGL((k_state<R, D, 3, true>), dim3((unsigned)(pb.units * 8)), dim3(kWg), 0, s,
+                               w.MK8, w.V8, w.Zg, pb.n, pb.b, pb.t, pb.units);
+        } else {
+            constexpr int NA = (D == 64) ? 4 : 2;
+            constexpr int AG = NA * 4 / (R / 32);
+            const unsigned grid = (unsigned)(pb.units * (R / AG));
+            hipLaunchKernelGGL((k_state<R, D, NA, false>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+                               pb.n, pb.b, pb.t, pb.units);
+        }
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
