@@ -16,6 +16,14 @@ if ROOT not in sys.path:
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs summarised in profiles/ (scaled by the copy calibration described there).  bench.py
+# cannot collect counters itself; workloads without a committed counter run report null.
+MEASURED_TRAFFIC_BYTES = {
+    ("config3", "output"): 1.23e9,
+    ("config3", "block_states_scan"): 0.60e9,
+}
+
 
 def workloads():
     from paper_2310_01655_amd import inputs
@@ -152,7 +160,8 @@ def main():
         achieved = fl[dom] / (acc[dom] * 1e-3) / 1e12
         out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": achieved,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                           "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                           "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
                            "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc if nm in fl}}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, G)
