@@ -664,7 +664,8 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
     static_assert(KV_BYTES % (16 * kWg) == 0, "whole copies");
     __shared__ __attribute__((aligned(16))) unsigned char stage[STAGE_BYTES];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
     const int x = lane & 31, h = lane >> 5;
     const int tiles_per_unit = n / TOK_WG;
     // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
@@ -866,7 +867,18 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
             }
         }
 
-        // numerator: for every a, T_a = Z_l[a]^T m_i (D x tokens), out += m_i[a] * T_a
+        // numerator: phi'(q_i)^T Z_l with phi'(q_i) = m_i (x) m_i expanded in registers.  For
+        // sketch row a and 16-wide step s the B operand is B[k = b'][j = token] = m_i[a] * m_i[b']
+        // (12 VALU operations per fragment, each feeding CT MFMAs that accumulate straight into
+        // `out`), the A operand a fragment of Z_l[a] read from LDS.
+        f32x8 mb[TT][RS];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int s = 0; s < RS; ++s)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mb[tt][s][e] = (float)mfr[tt][s][e];
+
         const bf16_t *zsrc = Zg + ((size_t)u * (t - 1) + (l - 1)) * R * R * D;
         constexpr int NCHUNK = R / ZA;
         constexpr int BUF_BYTES = Z_CHUNK_BYTES + MQ_CHUNK_BYTES;
@@ -881,18 +893,19 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
         // b' >= 16 * (a / 16) contributes, i.e. 16-wide steps s >= s0 = a / 16 and octets >= 2 s0.
         // All rows of a chunk share s0.
         static_assert(16 % ZA == 0, "one s0 per chunk");
-        // one 16-byte-per-lane copy (number q of this thread) of the needed part of a chunk
-        auto z_copies = [&](int chunk) { return (R / 8 - 2 * (chunk * ZA / 16)) * D * ZA / kWg; };
-        auto stage_z_one = [&](int buf, int chunk, int q) {
-            const int s0 = chunk * ZA / 16;
-            const int per_a = (R / 8 - 2 * s0) * D;          // 16-byte units needed per row a
-            const int w0 = q * kWg + wave * 64;              // first unit of this wave's copy
-            const int off = (w0 / per_a) * (Z_PER_A / 8) + 2 * s0 * D + w0 % per_a;   // in 16-byte units
+        // The needed part of a chunk is copied in 1 KB pieces (one per wave and copy): piece c
+        // covers columns 64 * (c % DW).. of octet 2 s0 + c / (DW * ZA) of row (c / DW) % ZA;
+        // wave w issues the pieces w, w + 4, ...
+        constexpr int DW = D / 64;
+        constexpr int KPA = R * D / 2048;                    // copies per wave and row a, at most
+        static_assert(DW >= 1 && KPA >= 1 && (ZA * DW) % 2 == 0, "piece enumeration");
+        auto z_ncopy = [&](int chunk) { return (R / 8 - 2 * (chunk * ZA / 16)) * ZA * DW / 4; };
+        auto stage_z_k = [&](int buf, int chunk, int k) {
+            const int c = wave + 4 * k;
+            const int off = (((c / DW) % ZA) * (R / 8) + 2 * (chunk * ZA / 16) + c / (DW * ZA)) * D +
+                            (c % DW) * 64;                   // 16-byte units inside the chunk
             dma16(zsrc + (size_t)chunk * ZA * Z_PER_A + (size_t)(off + lane) * 8,
                   stage + buf * BUF_BYTES + (size_t)off * 16);
-        };
-        auto stage_z = [&](int buf, int chunk) {
-            for (int q = 0; q < z_copies(chunk); ++q) stage_z_one(buf, chunk, q);
         };
         auto load_mq = [&](int chunk) {
 #pragma unroll
@@ -907,7 +920,13 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
                 for (int e = 0; e < MQ_PER; ++e)
                     dst[(mq_grp * MQ_PER + e) * TOK_WG + mq_tok + k * kWg] = (float)mqv[k][e];
         };
-        stage_z(0, 0);
+        auto gen = [&](float ma, const f32x8 &mbv) {
+            f32x8 pr;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pr[e] = ma * mbv[e];
+            return cvt8(pr);
+        };
+        for (int k = 0; k < z_ncopy(0); ++k) stage_z_k(0, 0, k);
         load_mq(0);
         store_mq(0);
         wait_all_memory();
@@ -917,55 +936,53 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
             const int buf = chunk & 1;
             // the next chunk's copies are issued a few per row a inside the loop below: issued
             // back to back they stall this wave on the memory pipeline's queue
-            const int n_copies = chunk + 1 < NCHUNK ? z_copies(chunk + 1) : 0;
-            constexpr int COPIES_PER_A = (R / 8 * D * ZA / kWg + ZA - 1) / ZA;
+            const int n_copies = chunk + 1 < NCHUNK ? z_ncopy(chunk + 1) : 0;
             if (chunk + 1 < NCHUNK) load_mq(chunk + 1);
             const bf16_t *zc = (const bf16_t *)(stage + buf * BUF_BYTES);
             const float *mqs = (const float *)(stage + buf * BUF_BYTES + Z_CHUNK_BYTES);
-            bf16x8 zf[2][RS];                               // fragments of Z[a][.][value tile]
             auto run_chunk = [&](auto s0_tag) {
                 constexpr int S0 = decltype(s0_tag)::value;  // first 16-wide step with b' >= a
                 constexpr int NS = RS - S0;
-                auto load_zf = [&](int ai, int ct) {
+                bf16x8 zf[2][CT][RS];                        // fragments of Z[a], ping-pong over a
+                float ma[2][TT];                             // m_i[a] of this lane's tokens
+                auto load_a = [&](int ai) {
                     const bf16_t *za = zc + ai * Z_PER_A;
 #pragma unroll
                     for (int s = S0; s < RS; ++s)
-                        zf[ct & 1][s] = *(const bf16x8 *)&za[((2 * s + h) * D + 32 * ct + x) * 8];
-                };
-                auto chain = [&](int ct, int tt) {
-                    f32x16 tacc = {0};
 #pragma unroll
-                    for (int s = S0; s < RS; ++s) tacc = mfma32(zf[ct & 1][s], mfr[tt][s], tacc);
-                    return tacc;
+                        for (int ct = 0; ct < CT; ++ct)
+                            zf[ai & 1][ct][s] = *(const bf16x8 *)&za[((2 * s + h) * D + 32 * ct + x) * 8];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        ma[ai & 1][tt] = mqs[ai * TOK_WG + wave * TOK_WAVE + 32 * tt + x];
                 };
-                load_zf(0, 0);
-                f32x16 t_cur = chain(0, 0);
-#pragma unroll 1
+                load_a(0);
+                bf16x8 frag = gen(ma[0][0], mb[0][S0]);
+#pragma unroll
                 for (int ai = 0; ai < ZA; ++ai) {
 #pragma unroll
-                    for (int c = 0; c < COPIES_PER_A; ++c)
-                        if (ai * COPIES_PER_A + c < n_copies) stage_z_one(buf ^ 1, chunk + 1, ai * COPIES_PER_A + c);
+                    for (int c = 0; c < KPA; ++c)
+                        if (ai * KPA + c < n_copies) stage_z_k(buf ^ 1, chunk + 1, ai * KPA + c);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (ai + 1 < ZA) load_a(ai + 1);
 #pragma unroll
-                    for (int it = 0; it < CT * TT; ++it) {
-                        const int ct = it / TT, tt = it % TT;
-                        const int itn = (it + 1) % (CT * TT), ctn = itn / TT, ttn = itn % TT;
-                        __builtin_amdgcn_sched_barrier(0);
-                        // fragments of the next value tile (the first one of the next a after the
-                        // last; clamped at the end of the chunk, where the result is discarded)
-                        if (tt == 0) load_zf(ct + 1 < CT ? ai : min(ai + 1, ZA - 1), (ct + 1) % CT);
-                        const float mq = mqs[ai * TOK_WG + wave * TOK_WAVE + 32 * tt + x];
-                        const f32x16 t_nxt = chain(ctn, ttn);
-                        out[tt][ct] += mq * t_cur;
+                    for (int it = 0; it < NS * TT; ++it) {
+                        const int s = S0 + it / TT, tt = it % TT, itn = it + 1;
+                        bf16x8 nxt = frag;
+                        if (itn < NS * TT) nxt = gen(ma[ai & 1][itn % TT], mb[itn % TT][S0 + itn / TT]);
+                        else if (ai + 1 < ZA) nxt = gen(ma[(ai + 1) & 1][0], mb[0][S0]);
 #pragma unroll
-                        for (int s = 0; s < NS; ++s) {
+                        for (int ct = 0; ct < CT; ++ct)
+                            out[tt][ct] = mfma32(zf[ai & 1][ct][s], frag, out[tt][ct]);
+#pragma unroll
+                        for (int ct = 0; ct < CT; ++ct) {
                             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x002, 16 / NS, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x002, 12 / CT, 0);
                         }
-                        t_cur = t_nxt;
+                        frag = nxt;
                     }
                 }
             };
-            static_assert(CT % 2 == 0, "fragment ping-pong");
             static_assert(RS <= 4, "step variants");
             switch (chunk * ZA / 16) {
             case 0: run_chunk(std::integral_constant<int, 0>{}); break;
