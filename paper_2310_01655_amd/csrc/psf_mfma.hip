@@ -25,6 +25,7 @@
 //   B[k][j]: lane x = j, half h supplies k = 8h..8h+7
 //   D[i][j]: lane x = j, register v holds row i = 8*(v/4) + 4*h + (v%4)
 #include <type_traits>
+#include <utility>
 
 #include "psf_internal.h"
 
@@ -33,6 +34,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -54,6 +56,18 @@ __device__ __forceinline__ bf16x8 cvt8_from16(const f32x16 &v, int first)
 #pragma unroll
     for (int e = 0; e < 8; ++e) t[e] = v[first + e];
     return cvt8(t);
+}
+
+template <int... Js, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Js...>, F &&f)
+{
+    (f(std::integral_constant<int, Js>{}), ...);
+}
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
 template <int LANE>
@@ -718,13 +732,20 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
                 dma16(&V8[j0 * D + (size_t)(q * kWg + tid) * 8], vs + (size_t)(q * kWg + wave * 64) * 8);
         };
 
-        f32x16 sc_cur, sc_nxt = {0};
-        bf16x8 p_prev[2] = {bf16x8{0}, bf16x8{0}};
+        // Software pipeline over the 32x32 items q of this wave: in one straight-line step the
+        // score MFMAs of item q+1 and the P V MFMAs of item q-1 are issued between the VALU work
+        // on item q (x^p, mask on the diagonal tile, row sums, bf16 packing).  Score registers
+        // and packed weights alternate between two sets by item parity.
+        constexpr int PAR = IPT % 2 == 0 ? 1 : 0;          // parity alternates inside a tile only if IPT is even
+        f32x16 sc[2];
+        bf16x8 pk[2][2];
         bf16x8 kfr[KS], vfr[2][CT];
 #pragma unroll
-        for (int sp = 0; sp < 2; ++sp)                    // the pipeline's first P V step multiplies these by zero weights
+        for (int sp = 0; sp < 2; ++sp) {                  // the pipeline's first P V step multiplies these by zero weights
+            pk[0][sp] = pk[1][sp] = bf16x8{0};
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) vfr[sp][ct] = bf16x8{0};
+        }
         // S^T[key][token] for item q (tile q / IPT, sub-tile, token tile)
         auto score = [&](int q, int jsub, int jtt) {
             const bf16_t *ks = (const bf16_t *)(stage + ((q / IPT) % NKV) * KV_BYTES);
@@ -733,13 +754,13 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
                 for (int s = 0; s < KS; ++s)
                     kfr[s] = *(const bf16x8 *)&ks[((2 * s + h) * KEYT + 32 * jsub + x) * 8];
             }
-            f32x16 sc = {0};
+            f32x16 acc = {0};
 #pragma unroll
-            for (int s = 0; s < KS; ++s) sc = mfma32(kfr[s], qfr[jtt][s], sc);
-            return sc;
+            for (int s = 0; s < KS; ++s) acc = mfma32(kfr[s], qfr[jtt][s], acc);
+            return acc;
         };
-        // out^T += V^T P^T for item q with the packed weights p_prev
-        auto apply_pv = [&](int q, int jsub, int jtt) {
+        // out^T += V^T P^T for item q with the packed weights pw
+        auto apply_pv = [&](int q, int jsub, int jtt, const bf16x8 *pw) {
             const bf16_t *vs = (const bf16_t *)(stage + ((q / IPT) % NKV) * KV_BYTES) + KEYT * D;
             if (jtt == 0) {                               // fragments serve all token tiles of the sub-tile
 #pragma unroll
@@ -751,79 +772,110 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
 #pragma unroll
             for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) out[jtt][ct] = mfma32(vfr[sp][ct], p_prev[sp], out[jtt][ct]);
+                for (int ct = 0; ct < CT; ++ct) out[jtt][ct] = mfma32(vfr[sp][ct], pw[sp], out[jtt][ct]);
         };
-        // weights of item q: x^p, causal mask (diagonal tile only), row sums, bf16 pack.  The
-        // score registers give lane (token, h) the keys 16sp + 8*(e/4) + 4h + e%4; one half-wave
-        // swap per register pair turns that into keys 16sp + 8h + e, so that V^T fragments are
-        // whole token octets.
-        auto weights = [&](int jsub, int jtt, bool diag, int key0, int tok0, bf16x8 *pk) {
-            float dsum = 0.f;
+        // weights of one item: x^p, causal mask (diagonal tile only), bf16 pack, row sums of the
+        // packed values.  The score registers give lane (token, h) the keys
+        // 16sp + 8*(e/4) + 4h + e%4; one half-wave swap per register pair turns that into keys
+        // 16sp + 8h + e, so that V^T fragments are whole token octets.
+        auto weights = [&](auto diag_tag, f32x16 &scv, int jtt, int key0, int tok0, bf16x8 *pw) {
+            constexpr bool DIAG = decltype(diag_tag)::value;
+            const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                float w = pow_p(sc_cur[v], P);
-                if (diag) {
+                float w = pow_p(scv[v], P);
+                if (DIAG) {
                     const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
                     w = key <= tok0 + x ? w : 0.f;
                 }
-                sc_cur[v] = w;
-                dsum += w;
+                scv[v] = w;
             }
-            den[jtt] += dsum;
+            float dsum = den[jtt];
 #pragma unroll
             for (int sp = 0; sp < 2; ++sp) {
-                uint4 w = __builtin_bit_cast(uint4, cvt8_from16(sc_cur, 8 * sp));
+                uint4 w = __builtin_bit_cast(uint4, cvt8_from16(scv, 8 * sp));
+                dsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.x), ones, dsum, false);
+                dsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.y), ones, dsum, false);
+                dsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.z), ones, dsum, false);
+                dsum = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w.w), ones, dsum, false);
                 const auto s0 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
                 const auto s1 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
                 w.x = s0[0]; w.z = s0[1]; w.y = s1[0]; w.w = s1[1];
-                pk[sp] = __builtin_bit_cast(bf16x8, w);
+                pw[sp] = __builtin_bit_cast(bf16x8, w);
             }
+            den[jtt] = dsum;
+        };
+        // one item: j = position inside the staged tile kt
+        auto item = [&](auto diag_tag, auto j_tag, int kt) {
+            constexpr int j = decltype(j_tag)::value;
+            constexpr int jn = (j + 1) % IPT, jp = (j + IPT - 1) % IPT;
+            constexpr int cur = PAR * (j & 1), nxt = PAR * ((j + 1) & 1);
+            constexpr int NM = KS + 2 * CT;                       // MFMAs of one step
+            constexpr int NV = (P == 8 ? 68 : 52) + (decltype(diag_tag)::value ? 48 : 0);
+            const int q = kt * IPT + j;
+            __builtin_amdgcn_sched_barrier(0);
+            f32x16 sn = score(q + 1, jn / TT, jn % TT);           // garbage past the end, unused
+            apply_pv(q - 1 < 0 ? 0 : q - 1, jp / TT, jp % TT, pk[PAR ? nxt : 0]);   // adds zeros at q == 0
+            bf16x8 pw[2];
+            weights(diag_tag, sc[cur], j % TT, jb + kt * KEYT + 32 * (j / TT), tok_w0 + 32 * (j % TT), pw);
+            // LDS reads first, a few VALU operations to cover their latency, then one MFMA per
+            // share of the remaining VALU work
+            __builtin_amdgcn_sched_group_barrier(0x100, (jn % TT == 0 ? KS : 0) + (jp % TT == 0 ? 2 * CT : 0), 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, NV / (NM + 1), 0);
+#pragma unroll
+            for (int m = 0; m < NM; ++m) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, NV / (NM + 1), 0);
+            }
+            sc[PAR ? nxt : 0] = sn;
+            pk[PAR ? cur : 0][0] = pw[0];
+            pk[PAR ? cur : 0][1] = pw[1];
+        };
+        // one staged tile: all waves run the same barriers and copies
+        auto tile_sync = [&](int kt) {
+            // the next tile must have landed for every wave before its first score; the tile
+            // before this one is no longer read by anybody, refill its buffer
+            wait_vmem_le<(NKV - 3) * DMA_KV>();
+            __builtin_amdgcn_s_barrier();
+            if (IPT > 1) stage_kv(kt + NKV - 1);
+        };
+        auto tile_sync_single = [&](int kt) {
+            // with one item per tile the previous tile is read right after the barrier: a
+            // second barrier separates those reads from the refill
+            __builtin_amdgcn_s_barrier();
+            stage_kv(kt + NKV - 1);
+        };
+        auto tile = [&](auto diag_tag, int kt) {
+            static_for<IPT>([&](auto j_tag) {
+                if (decltype(j_tag)::value == IPT - 1) tile_sync(kt);
+                item(diag_tag, j_tag, kt);
+                if (IPT == 1) tile_sync_single(kt);
+            });
         };
 
 #pragma unroll
         for (int kt = 0; kt < NKV - 1; ++kt) stage_kv(kt);
         wait_vmem_le<(NKV - 2) * DMA_KV>();
         __syncthreads();
-        const int nitems = ntiles_w * IPT;
-        sc_cur = score(0, 0, 0);
-#pragma unroll 1
-        for (int kt = 0; kt < ntiles_wg; ++kt) {
+        sc[0] = score(0, 0, 0);
+        sc[1] = sc[0];
+        // Pin the arrival of the Q fragments here.  Left to the compiler, the wait for them sits
+        // inside the loop, where it also waits for every key tile copy in flight (the copies
+        // are invisible to its counter bookkeeping) and so defeats the ring.
 #pragma unroll
-            for (int j = 0; j < IPT; ++j) {
-                const int q = kt * IPT + j;
-                if (j == IPT - 1) {
-                    // the next tile must have landed for every wave before its first score;
-                    // the tile before this one is no longer read by anybody, refill its buffer
-                    wait_vmem_le<(NKV - 3) * DMA_KV>();
-                    __builtin_amdgcn_s_barrier();
-                    if (IPT > 1) stage_kv(kt + NKV - 1);
-                }
-                if (q < nitems) {                         // wave-uniform
-                    const int jn = (j + 1) % IPT, jp = (j + IPT - 1) % IPT;   // compile-time after unrolling
-                    __builtin_amdgcn_sched_barrier(0);
-                    sc_nxt = score(q + 1, jn / TT, jn % TT);           // garbage past the end, unused
-                    apply_pv(q - 1 < 0 ? 0 : q - 1, jp / TT, jp % TT);   // adds zeros at q == 0
-                    bf16x8 pk[2];
-                    const int key0 = jb + kt * KEYT + 32 * (j / TT), tok0 = tok_w0 + 32 * (j % TT);
-                    if (kt == ntiles_w - 1) weights(j / TT, j % TT, true, key0, tok0, pk);
-                    else weights(j / TT, j % TT, false, key0, tok0, pk);
-                    p_prev[0] = pk[0];
-                    p_prev[1] = pk[1];
-                    sc_cur = sc_nxt;
-                } else if (q == nitems) {
-                    // this wave's keys are exhausted: flush the pending item while its tile is
-                    // still in LDS (later iterations only keep the barriers and copies going)
-                    apply_pv(q - 1, (IPT - 1) / TT, (IPT - 1) % TT);
-                }
-                if (IPT == 1) {
-                    // with one item per tile the previous tile is read right after the barrier:
-                    // a second barrier separates those reads from the refill
-                    __builtin_amdgcn_s_barrier();
-                    stage_kv(kt + NKV - 1);
-                }
-            }
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int s = 0; s < KS; ++s) asm volatile("" ::"v"(qfr[tt][s]));
+#pragma unroll 1
+        for (int kt = 0; kt < ntiles_w - 1; ++kt) tile(std::false_type{}, kt);
+        tile(std::true_type{}, ntiles_w - 1);             // the tile that holds this wave's own tokens
+        // this wave's keys are exhausted: flush the pending item while its tile is still in LDS
+        apply_pv(ntiles_w * IPT - 1, (IPT - 1) / TT, (IPT - 1) % TT, pk[PAR * ((IPT - 1) & 1)]);
+#pragma unroll 1
+        for (int kt = ntiles_w; kt < ntiles_wg; ++kt) {   // later tiles: only keep the barriers and copies going
+            tile_sync(kt);
+            if (IPT == 1) tile_sync_single(kt);
         }
-        if (nitems == ntiles_wg * IPT) apply_pv(nitems - 1, (IPT - 1) / TT, (IPT - 1) % TT);
         wait_vmem_le<0>();                                // drain the clamped copies
         __syncthreads();
     }
