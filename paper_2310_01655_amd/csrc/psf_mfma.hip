@@ -429,14 +429,13 @@ template <int CT>
 struct StateOps {           // LDS operands of one 16-token step
     f32x4 af;               // m_j[a] source values (see gen_frag)
     f32x8 bfv;              // m_j[b'] for this lane's b' and 8 tokens
-    f32x8 bfv2;             // same for the second b' range of a wave with mixed tiles
     bf16x8 vf[CT];          // V fragments (B operand)
 };
 
 // One 16-token step: for every tile of the wave, two things overlap -- the MFMAs that consume
 // the fragment generated last, and the VALU work generating the next fragment (the first one
-// of the following step comes from `nxt`).  MIXED: tiles 1.. use the second b' range.
-template <int NA, int CT, int AI, bool MIXED>
+// of the following step comes from `nxt`).
+template <int NA, int CT, int AI>
 struct StateStep {
     static __device__ __forceinline__ void run(const StateOps<CT> &cur, const StateOps<CT> &nxt,
                                                bf16x8 &frag, f32x16 (*acc)[CT])
@@ -444,7 +443,7 @@ struct StateStep {
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) acc[AI][ct] = mfma32(frag, cur.vf[ct], acc[AI][ct]);
         if constexpr (AI + 1 < NA) {
-            frag = gen_frag<AI + 1>(cur.af, MIXED ? cur.bfv2 : cur.bfv);
+            frag = gen_frag<AI + 1>(cur.af, cur.bfv);
         } else {
             frag = gen_frag<0>(nxt.af, nxt.bfv);
         }
@@ -454,16 +453,17 @@ struct StateStep {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x002, 12 / CT, 0);
         }
-        if constexpr (AI + 1 < NA) StateStep<NA, CT, AI + 1, MIXED>::run(cur, nxt, frag, acc);
+        if constexpr (AI + 1 < NA) StateStep<NA, CT, AI + 1>::run(cur, nxt, frag, acc);
     }
 };
 
-// SYM (R = 64 only): Z[a][b'] = Z[b'][a] and the output kernel reads only b' >= 16*(a/16), so
-// the 32 tiles (a >= 32, b' < 32) are never needed.  The remaining 96 tiles (a, 32-wide b'
-// range) of a unit are dealt three per wave to 32 waves = 8 workgroups: waves 0..20 take
-// b' in [32,64) with a = 3w..3w+2, waves 21..30 take b' in [0,32) with a = 3(w-21)..+2, and
-// wave 31 takes the leftovers (63, upper), (30, lower), (31, lower).
-template <int R, int D, int NA, bool SYM, bool MIXED>
+// SYM: Z[a][b'] = Z[b'][a] and the output kernel reads, for sketch row a, only the 16-wide
+// column ranges beta >= a / 16, so only those (a, beta) segments are computed: 16 (beta + 1)
+// rows a per range beta, R/16 * (R/16 + 1) / 2 * 16 segments in all (160 of 256 for R = 64).
+// A 32-row MFMA tile is two segments that share beta (lanes x < 16 and x >= 16 of the A operand
+// carry different rows a), a wave owns NA = 2 tiles = four consecutive rows a of one beta, and
+// the waves are numbered range by range: beta = 0 first (4 waves), then 1 (8 waves), ...
+template <int R, int D, int NA, bool SYM>
 __device__ __forceinline__ void state_body(const float *__restrict__ M8, const bf16_t *__restrict__ V8,
                                            bf16_t *__restrict__ Zg, int n, int b, int t, int u, int grp,
                                            unsigned char *lds_base)
@@ -476,29 +476,28 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
     constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2, BUF_BYTES = M_BYTES + V_BYTES;
     constexpr int NBUF = 4;                    // staged chunks in flight: covers HBM latency
     constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
+    constexpr int SEG = SYM ? 2 : 1;           // rows a per tile
     static_assert(NA <= 8, "DPP source lanes");
     static_assert(STEPS % 2 == 0, "operand ping-pong");
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int x = lane & 31, h = lane >> 5, n16 = lane & 15;
-    // tiles of this wave: sketch row ta[i], b' range 32 * tb[i]
-    int ta[NA], tb[NA];
+    // tiles of this wave: tile i holds the sketch rows a0 + i * SEG + (0..SEG-1); bcol is the
+    // column b' of lane x
+    int a0, beta = 0, bcol;
     if (SYM) {
-        const int w = grp * 4 + wave;
-#pragma unroll
-        for (int i = 0; i < NA; ++i) {
-            if (MIXED) { ta[i] = i == 0 ? 63 : 29 + i; tb[i] = i == 0 ? 1 : 0; }
-            else if (w < 21) { ta[i] = 3 * w + i; tb[i] = 1; }
-            else { ta[i] = 3 * (w - 21) + i; tb[i] = 0; }
-        }
+        int w = grp * 4 + wave;                // wave of the unit
+        while (w >= 4 * (beta + 1)) { w -= 4 * (beta + 1); ++beta; }
+        a0 = w * NA * SEG;
+        bcol = 16 * beta + (x & 15);
     } else {
-#pragma unroll
-        for (int i = 0; i < NA; ++i) { ta[i] = grp * AG + (wave / NB) * NA + i; tb[i] = wave % NB; }
+        a0 = grp * AG + (wave / NB) * NA;
+        beta = wave % NB;                      // 32-wide range here
+        bcol = 32 * beta + x;
     }
-    int a_src = ta[NA - 1];
-#pragma unroll
-    for (int i = 0; i < NA - 1; ++i)
-        if ((n16 & 7) == i) a_src = ta[i];
+    // lanes i and 8 + i of each row of 16 lanes fetch m_j[a] of tile i for the DPP broadcast;
+    // with two segments per tile the odd rows (x >= 16) fetch the second row a
+    const int a_src = a0 + min(n16 & 7, NA - 1) * SEG + (SYM ? (lane >> 4) & 1 : 0);
     const int q_src = n16 >> 3;
 
     f32x16 acc[NA][CT];
@@ -527,16 +526,10 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
         const float *lm = (const float *)(lds_base + buf * BUF_BYTES);
         const bf16_t *lv = (const bf16_t *)(lds_base + buf * BUF_BYTES + M_BYTES);
         const int oct = 2 * s + h;
-        const f32x4 b_lo = *(const f32x4 *)&lm[((oct * 2 + 0) * R + 32 * tb[0] + x) * 4];
-        const f32x4 b_hi = *(const f32x4 *)&lm[((oct * 2 + 1) * R + 32 * tb[0] + x) * 4];
+        const f32x4 b_lo = *(const f32x4 *)&lm[((oct * 2 + 0) * R + bcol) * 4];
+        const f32x4 b_hi = *(const f32x4 *)&lm[((oct * 2 + 1) * R + bcol) * 4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) { o.bfv[e] = b_lo[e]; o.bfv[4 + e] = b_hi[e]; }
-        if (MIXED) {
-            const f32x4 c_lo = *(const f32x4 *)&lm[((oct * 2 + 0) * R + 32 * tb[NA - 1] + x) * 4];
-            const f32x4 c_hi = *(const f32x4 *)&lm[((oct * 2 + 1) * R + 32 * tb[NA - 1] + x) * 4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { o.bfv2[e] = c_lo[e]; o.bfv2[4 + e] = c_hi[e]; }
-        }
         o.af = *(const f32x4 *)&lm[((oct * 2 + q_src) * R + a_src) * 4];
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) o.vf[ct] = *(const bf16x8 *)&lv[(oct * D + 32 * ct + x) * 8];
@@ -553,15 +546,16 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
             for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
+                    // accumulator rows 8 gq + 4 h + j: segment gq / 2 of the tile when SYM
+                    const int a = a0 + i * SEG + (SYM ? gq / 2 : 0);
+                    const int bq0 = SYM ? 16 * beta + 8 * (gq % 2) + 4 * h : 32 * beta + 8 * gq + 4 * h;
                     f32x4 q4;
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const int bq = 32 * tb[i] + 8 * gq + 4 * h + j;
-                        const float wsym = bq > ta[i] ? 2.f : (bq == ta[i] ? 1.f : 0.f);
+                        const float wsym = bq0 + j > a ? 2.f : (bq0 + j == a ? 1.f : 0.f);
                         q4[j] = acc[i][ct][4 * gq + j] * wsym;
                     }
-                    const size_t o = 4 * tb[i] + gq;
-                    *(bf16x4 *)&z[(((size_t)ta[i] * (R / 8) + o) * D + 32 * ct + x) * 8 + 4 * h] = cvt4(q4);
+                    *(bf16x4 *)&z[(((size_t)a * (R / 8) + bq0 / 8) * D + 32 * ct + x) * 8 + 4 * h] = cvt4(q4);
                 }
     };
 
@@ -589,8 +583,8 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
                 }
                 __builtin_amdgcn_sched_barrier(0);      // steps are scheduled one at a time
                 ops[(s + 1) & 1] = (s + 1 < STEPS) ? load_ops(buf, s + 1) : load_ops(nbuf, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 3 + CT + (MIXED ? 2 : 0), 0);   // LDS reads first
-                StateStep<NA, CT, 0, MIXED>::run(ops[s & 1], ops[(s + 1) & 1], frag, acc);
+                __builtin_amdgcn_sched_group_barrier(0x100, 3 + CT, 0);   // LDS reads first
+                StateStep<NA, CT, 0>::run(ops[s & 1], ops[(s + 1) & 1], frag, acc);
             }
         }
         snapshot(l);
@@ -607,14 +601,14 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
     constexpr int BUF_BYTES = TC * R * 4 + TC * D * 2;
     constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
     constexpr int AG = NA * 4 / (R / 32);
-    static_assert(!SYM || (R == 64 && NA == 3), "tile deal of the symmetric variant");
+    static_assert(!SYM || NA == 2, "tile deal of the symmetric variant");
     __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF * BUF_BYTES];
 
     // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
     // contiguous range of (unit, group) pairs; the groups of one unit then share one L2.
     int wg = blockIdx.x;
     if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    constexpr int GROUPS = SYM ? 8 : R / AG;
+    constexpr int GROUPS = SYM ? (R / 16) * (R / 16 + 1) / 2 : R / AG;   // workgroups per unit
     const int u = wg / GROUPS, grp = wg % GROUPS;
     if (u >= units || t < 2) return;
 
@@ -641,9 +635,7 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
         wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
         __syncthreads();
     }
-    // wave 31 of a unit holds tiles from both b' ranges and runs the body that reads both
-    if (SYM && grp * 4 + (int)(threadIdx.x >> 6) == 31) state_body<R, D, NA, SYM, true>(M8, V8, Zg, n, b, t, u, grp, lds);
-    else state_body<R, D, NA, SYM, false>(M8, V8, Zg, n, b, t, u, grp, lds);
+    state_body<R, D, NA, SYM>(M8, V8, Zg, n, b, t, u, grp, lds);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1149,8 +1141,9 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     if (tm) tm->mark();
     if (pb.t > 1) {
         if constexpr (R == 64 && D == 64) {
-            // symmetric tile deal: 96 of the 128 (a, b' range) tiles, three per wave
-            hipLaunchKernelGGL((k_state<R, D, 3, true>), dim3((unsigned)(pb.units * 8)), dim3(kWg), 0, s,
+            // symmetric deal: only the (a, 16-wide column range) segments the output kernel reads
+            constexpr int GROUPS = (R / 16) * (R / 16 + 1) / 2;
+            hipLaunchKernelGGL((k_state<R, D, 2, true>), dim3((unsigned)(pb.units * GROUPS)), dim3(kWg), 0, s,
                                w.MK8, w.V8, w.Zg, pb.n, pb.b, pb.t, pb.units);
         } else {
             constexpr int NA = (D == 64) ? 4 : 2;
