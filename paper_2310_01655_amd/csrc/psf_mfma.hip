@@ -463,7 +463,7 @@ struct StateStep {
 // A 32-row MFMA tile is two segments that share beta (lanes x < 16 and x >= 16 of the A operand
 // carry different rows a), a wave owns NA = 2 tiles = four consecutive rows a of one beta, and
 // the waves are numbered range by range: beta = 0 first (4 waves), then 1 (8 waves), ...
-template <int R, int D, int NA, bool SYM>
+template <int R, int D, int NA, bool SYM, int NBUF>
 __device__ __forceinline__ void state_body(const float *__restrict__ M8, const bf16_t *__restrict__ V8,
                                            bf16_t *__restrict__ Zg, int n, int b, int t, int u, int grp,
                                            unsigned char *lds_base)
@@ -474,7 +474,6 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
     constexpr int TC = kStateChunk;
     constexpr int STEPS = TC / 16;
     constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2, BUF_BYTES = M_BYTES + V_BYTES;
-    constexpr int NBUF = 4;                    // staged chunks in flight: covers HBM latency
     constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
     constexpr int SEG = SYM ? 2 : 1;           // rows a per tile
     static_assert(NA <= 8, "DPP source lanes");
@@ -591,13 +590,15 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
     }
 }
 
-template <int R, int D, int NA, bool SYM>
-__global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
+// NBUF staged chunks per workgroup (NBUF - 1 in flight to cover the memory latency); OCC
+// workgroups per CU: grids that exceed one workgroup per CU run two per CU with a shorter ring.
+template <int R, int D, int NA, bool SYM, int NBUF, int OCC>
+__global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8,
                                                const bf16_t *__restrict__ V8,
                                                bf16_t *__restrict__ Zg, int n, int b, int t,
                                                int units)
 {
-    constexpr int TC = kStateChunk, NBUF = 4;
+    constexpr int TC = kStateChunk;
     constexpr int BUF_BYTES = TC * R * 4 + TC * D * 2;
     constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
     constexpr int AG = NA * 4 / (R / 32);
@@ -635,7 +636,7 @@ __global__ __launch_bounds__(kWg) void k_state(const float *__restrict__ M8,
         wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
         __syncthreads();
     }
-    state_body<R, D, NA, SYM>(M8, V8, Zg, n, b, t, u, grp, lds);
+    state_body<R, D, NA, SYM, NBUF>(M8, V8, Zg, n, b, t, u, grp, lds);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1143,13 +1144,18 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         if constexpr (R == 64 && D == 64) {
             // symmetric deal: only the (a, 16-wide column range) segments the output kernel reads
             constexpr int GROUPS = (R / 16) * (R / 16 + 1) / 2;
-            hipLaunchKernelGGL((k_state<R, D, 2, true>), dim3((unsigned)(pb.units * GROUPS)), dim3(kWg), 0, s,
-                               w.MK8, w.V8, w.Zg, pb.n, pb.b, pb.t, pb.units);
+            const unsigned grid = (unsigned)(pb.units * GROUPS);
+            if (grid <= 256)
+                hipLaunchKernelGGL((k_state<R, D, 2, true, 4, 1>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+                                   pb.n, pb.b, pb.t, pb.units);
+            else
+                hipLaunchKernelGGL((k_state<R, D, 2, true, 3, 2>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+                                   pb.n, pb.b, pb.t, pb.units);
         } else {
             constexpr int NA = (D == 64) ? 4 : 2;
             constexpr int AG = NA * 4 / (R / 32);
             const unsigned grid = (unsigned)(pb.units * (R / AG));
-            hipLaunchKernelGGL((k_state<R, D, NA, false>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+            hipLaunchKernelGGL((k_state<R, D, NA, false, 4, 1>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
                                pb.n, pb.b, pb.t, pb.units);
         }
         PSF_LAUNCH_CHECK();
