@@ -40,7 +40,7 @@ typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWg = 256;          // 4 wavefronts
-constexpr int kStateChunk = 64;   // tokens staged per step in k_state
+constexpr int kStateRing = 4;     // staged chunks per workgroup in k_state (ring of LDS buffers)
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c)
 {
@@ -98,6 +98,20 @@ __device__ __forceinline__ void dma16(const void *gsrc_lane, void *lds_wave_base
                  :
                  : "v"(gsrc_lane), "s"(__builtin_amdgcn_readfirstlane(lds_off))
                  : "memory");
+}
+// Same copy with the address split into a wave-uniform base (scalar registers) and a 32-bit
+// per-lane byte offset: a loop that walks the base then spends no vector instructions on it.
+// The destination is given as an LDS byte address (see lds_address).
+__device__ __forceinline__ void dma16_sbase(const void *gsrc_uniform, uint32_t lane_byte_off, uint32_t lds_wave_addr)
+{
+    asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(lane_byte_off), "s"(gsrc_uniform), "s"(__builtin_amdgcn_readfirstlane(lds_wave_addr))
+                 : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void *)p;
 }
 __device__ __forceinline__ void wait_all_memory() { __builtin_amdgcn_s_waitcnt(0); }
 // Wait until at most N vector-memory operations of this wave are outstanding (they complete in
@@ -463,7 +477,7 @@ struct StateStep {
 // A 32-row MFMA tile is two segments that share beta (lanes x < 16 and x >= 16 of the A operand
 // carry different rows a), a wave owns NA = 2 tiles = four consecutive rows a of one beta, and
 // the waves are numbered range by range: beta = 0 first (4 waves), then 1 (8 waves), ...
-template <int R, int D, int NA, bool SYM, int NBUF>
+template <int R, int D, int NA, bool SYM, int TC>
 __device__ __forceinline__ void state_body(const float *__restrict__ M8, const bf16_t *__restrict__ V8,
                                            bf16_t *__restrict__ Zg, int n, int b, int t, int u, int grp,
                                            unsigned char *lds_base)
@@ -471,15 +485,17 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
     constexpr int NB = R / 32;                 // 32-wide b' ranges
     constexpr int AG = NA * 4 / NB;            // sketch rows a per workgroup (!SYM)
     constexpr int CT = D / 32;
-    constexpr int TC = kStateChunk;
+    constexpr int NBUF = kStateRing;
     constexpr int STEPS = TC / 16;
     constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2, BUF_BYTES = M_BYTES + V_BYTES;
     constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
     constexpr int SEG = SYM ? 2 : 1;           // rows a per tile
+    static_assert(M_BYTES % 4096 == 0 && V_BYTES % 4096 == 0, "whole 4 KB pieces");
     static_assert(NA <= 8, "DPP source lanes");
     static_assert(STEPS % 2 == 0, "operand ping-pong");
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
     const int x = lane & 31, h = lane >> 5, n16 = lane & 15;
     // tiles of this wave: tile i holds the sketch rows a0 + i * SEG + (0..SEG-1); bcol is the
     // column b' of lane x
@@ -509,29 +525,35 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
     const bf16_t *gv = V8 + (size_t)u * n * D;
     const int chunks = (t - 1) * (b / TC), chunks_per_block = b / TC;
 
-    auto stage = [&](int buf, int chunk) {      // straight copies: global layout == LDS layout
-        const float *sm = gm + (size_t)chunk * TC * R;
-        const bf16_t *sv = gv + (size_t)chunk * TC * D;
-        unsigned char *dst = lds_base + buf * BUF_BYTES;
+    // Ring slots are compile-time constants (the chunk loop dispatches on the slot), so every
+    // LDS address below is a per-lane base plus an immediate and the copies take a scalar base.
+    const uint32_t copy_off = (uint32_t)tid * 16;             // lane's byte offset inside a 4 KB piece
+    const uint32_t lds0 = lds_address(lds_base);
+    auto stage = [&](auto slot_tag, int chunk) {              // straight copies: global layout == LDS layout
+        constexpr int SLOT = decltype(slot_tag)::value;
+        const unsigned char *sm = (const unsigned char *)(gm + (size_t)chunk * TC * R);
+        const unsigned char *sv = (const unsigned char *)(gv + (size_t)chunk * TC * D);
+        const uint32_t dst = lds0 + SLOT * BUF_BYTES + wave * 1024;
 #pragma unroll
-        for (int q = 0; q < M_BYTES / 16 / kWg; ++q)
-            dma16(sm + (size_t)(q * kWg + tid) * 4, dst + (size_t)(q * kWg + wave * 64) * 16);
+        for (int q = 0; q < M_BYTES / 16 / kWg; ++q) dma16_sbase(sm + q * 4096, copy_off, dst + q * 4096);
 #pragma unroll
         for (int q = 0; q < V_BYTES / 16 / kWg; ++q)
-            dma16(sv + (size_t)(q * kWg + tid) * 8, dst + M_BYTES + (size_t)(q * kWg + wave * 64) * 16);
+            dma16_sbase(sv + q * 4096, copy_off, dst + M_BYTES + q * 4096);
     };
-    auto load_ops = [&](int buf, int s) {
+    const unsigned char *lane_b = lds_base + ((h * 2 * R + bcol) * 16);
+    const unsigned char *lane_a = lds_base + (((h * 2 + q_src) * R + a_src) * 16);
+    const unsigned char *lane_v = lds_base + M_BYTES + ((h * D + x) * 16);
+    auto load_ops = [&](auto slot_tag, auto step_tag) {
+        constexpr int OFF = decltype(slot_tag)::value * BUF_BYTES;
+        constexpr int S = decltype(step_tag)::value;          // octet 2 S + h
         StateOps<CT> o;
-        const float *lm = (const float *)(lds_base + buf * BUF_BYTES);
-        const bf16_t *lv = (const bf16_t *)(lds_base + buf * BUF_BYTES + M_BYTES);
-        const int oct = 2 * s + h;
-        const f32x4 b_lo = *(const f32x4 *)&lm[((oct * 2 + 0) * R + bcol) * 4];
-        const f32x4 b_hi = *(const f32x4 *)&lm[((oct * 2 + 1) * R + bcol) * 4];
+        const f32x4 b_lo = *(const f32x4 *)(lane_b + OFF + S * 4 * R * 16);
+        const f32x4 b_hi = *(const f32x4 *)(lane_b + OFF + S * 4 * R * 16 + R * 16);
 #pragma unroll
         for (int e = 0; e < 4; ++e) { o.bfv[e] = b_lo[e]; o.bfv[4 + e] = b_hi[e]; }
-        o.af = *(const f32x4 *)&lm[((oct * 2 + q_src) * R + a_src) * 4];
+        o.af = *(const f32x4 *)(lane_a + OFF + S * 4 * R * 16);
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) o.vf[ct] = *(const bf16x8 *)&lv[(oct * D + 32 * ct + x) * 8];
+        for (int ct = 0; ct < CT; ++ct) o.vf[ct] = *(const bf16x8 *)(lane_v + OFF + S * 2 * D * 16 + ct * 32 * 16);
         return o;
     };
     auto snapshot = [&](int l) {
@@ -559,46 +581,55 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
     };
 
     StateOps<CT> ops[2];
-    ops[0] = load_ops(0, 0);
+    ops[0] = load_ops(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
     bf16x8 frag = gen_frag<0>(ops[0].af, ops[0].bfv);
     // One chunk = STEPS steps.  Operands of step s+1 are read from LDS at the start of step s.
     // Before the last step the next chunk must have landed for every wave (wait + barrier);
     // after that barrier nobody reads this chunk's buffer again, so the next iteration may
     // refill it.
+    auto run_chunk = [&](auto slot_tag, int chunk) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        stage(std::integral_constant<int, (SLOT + NBUF - 1) % NBUF>{}, min(chunk + NBUF - 1, chunks - 1));
+        static_for<STEPS>([&](auto s_tag) {
+            constexpr int s = decltype(s_tag)::value;
+            if (s == STEPS - 1) {
+                // plain barrier: the copies are tracked by the explicit wait, and a fence
+                // here would wait for the younger copies too
+                wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
+                __builtin_amdgcn_s_barrier();
+            }
+            __builtin_amdgcn_sched_barrier(0);      // steps are scheduled one at a time
+            if constexpr (s + 1 < STEPS)
+                ops[(s + 1) & 1] = load_ops(slot_tag, std::integral_constant<int, s + 1>{});
+            else
+                ops[(s + 1) & 1] = load_ops(std::integral_constant<int, (SLOT + 1) % NBUF>{},
+                                            std::integral_constant<int, 0>{});
+            __builtin_amdgcn_sched_group_barrier(0x100, 3 + CT, 0);   // LDS reads first
+            StateStep<NA, CT, 0>::run(ops[s & 1], ops[(s + 1) & 1], frag, acc);
+        });
+    };
+    // The slots follow each other inside one loop body (a block holds a multiple of NBUF
+    // chunks), so the accumulators stay in place from chunk to chunk.
     int chunk = 0;
 #pragma unroll 1
     for (int l = 0; l < t - 1; ++l) {
 #pragma unroll 1
-        for (int cb = 0; cb < chunks_per_block; ++cb, ++chunk) {
-            const int buf = chunk % NBUF, nbuf = (chunk + 1) % NBUF;
-            stage((chunk + NBUF - 1) % NBUF, min(chunk + NBUF - 1, chunks - 1));
-#pragma unroll
-            for (int s = 0; s < STEPS; ++s) {
-                if (s == STEPS - 1) {
-                    // plain barrier: the copies are tracked by the explicit wait, and a fence
-                    // here would wait for the younger copies too
-                    wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
-                    __builtin_amdgcn_s_barrier();
-                }
-                __builtin_amdgcn_sched_barrier(0);      // steps are scheduled one at a time
-                ops[(s + 1) & 1] = (s + 1 < STEPS) ? load_ops(buf, s + 1) : load_ops(nbuf, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 3 + CT, 0);   // LDS reads first
-                StateStep<NA, CT, 0>::run(ops[s & 1], ops[(s + 1) & 1], frag, acc);
-            }
-        }
+        for (int cb = 0; cb < chunks_per_block; cb += NBUF, chunk += NBUF)
+            static_for<NBUF>([&](auto slot_tag) { run_chunk(slot_tag, chunk + decltype(slot_tag)::value); });
         snapshot(l);
     }
 }
 
-// NBUF staged chunks per workgroup (NBUF - 1 in flight to cover the memory latency); OCC
-// workgroups per CU: grids that exceed one workgroup per CU run two per CU with a shorter ring.
-template <int R, int D, int NA, bool SYM, int NBUF, int OCC>
+// TC tokens per staged chunk, kStateRing chunks per workgroup (one less in flight to cover the
+// memory latency); OCC workgroups per CU: grids that exceed one workgroup per CU run two per CU
+// with half-size chunks.
+template <int R, int D, int NA, bool SYM, int TC, int OCC>
 __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8,
                                                const bf16_t *__restrict__ V8,
                                                bf16_t *__restrict__ Zg, int n, int b, int t,
                                                int units)
 {
-    constexpr int TC = kStateChunk;
+    constexpr int NBUF = kStateRing;
     constexpr int BUF_BYTES = TC * R * 4 + TC * D * 2;
     constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
     constexpr int AG = NA * 4 / (R / 32);
@@ -636,7 +667,7 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
         wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
         __syncthreads();
     }
-    state_body<R, D, NA, SYM, NBUF>(M8, V8, Zg, n, b, t, u, grp, lds);
+    state_body<R, D, NA, SYM, TC>(M8, V8, Zg, n, b, t, u, grp, lds);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1146,16 +1177,16 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
             constexpr int GROUPS = (R / 16) * (R / 16 + 1) / 2;
             const unsigned grid = (unsigned)(pb.units * GROUPS);
             if (grid <= 256)
-                hipLaunchKernelGGL((k_state<R, D, 2, true, 4, 1>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+                hipLaunchKernelGGL((k_state<R, D, 2, true, 64, 1>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
                                    pb.n, pb.b, pb.t, pb.units);
             else
-                hipLaunchKernelGGL((k_state<R, D, 2, true, 3, 2>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+                hipLaunchKernelGGL((k_state<R, D, 2, true, 32, 2>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
                                    pb.n, pb.b, pb.t, pb.units);
         } else {
             constexpr int NA = (D == 64) ? 4 : 2;
             constexpr int AG = NA * 4 / (R / 32);
             const unsigned grid = (unsigned)(pb.units * (R / AG));
-            hipLaunchKernelGGL((k_state<R, D, NA, false, 4, 1>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+            hipLaunchKernelGGL((k_state<R, D, NA, false, 64, 1>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
                                pb.n, pb.b, pb.t, pb.units);
         }
         PSF_LAUNCH_CHECK();
