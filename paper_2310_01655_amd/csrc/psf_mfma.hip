@@ -741,19 +741,22 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
         // V tile as [KEYT/8 octets][D][8], both filled by direct global->LDS copies.
         const int ntiles_wg = (i0 + TOK_WG - jb) / KEYT;         // tiles staged by the workgroup
         const int ntiles_w = (tok_w0 + TOK_WAVE - jb) / KEYT;    // tiles this wave has keys in
+        // (copies: wave-uniform base address in scalar registers + a fixed per-lane offset)
+        static_assert(kWg % KEYT == 0, "key index of a copy slot");
+        const uint32_t stage0 = lds_address(stage);
+        const uint32_t k_lane = (uint32_t)(((tid % KEYT) * D + 8 * (tid / KEYT)) * 2);
+        const uint32_t v_lane = (uint32_t)tid * 16;
         auto stage_kv = [&](int kt) {
             const int ktc = min(kt, ntiles_wg - 1);              // clamped: keeps the copy count uniform
-            bf16_t *ks = (bf16_t *)(stage + (kt % NKV) * KV_BYTES);
-            bf16_t *vs = ks + KEYT * D;
+            const uint32_t dst = stage0 + (kt % NKV) * KV_BYTES + wave * 1024;
             const size_t j0 = urow + jb + (size_t)ktc * KEYT;
+            const bf16_t *ksrc = K + j0 * D, *vsrc = V8 + j0 * D;
 #pragma unroll
-            for (int q = 0; q < DMA_KV / 2; ++q) {
-                const int slot = q * kWg + tid;                  // (d-octet, key)
-                dma16(&K[(j0 + slot % KEYT) * D + 8 * (slot / KEYT)], ks + (size_t)(q * kWg + wave * 64) * 8);
-            }
+            for (int q = 0; q < DMA_KV / 2; ++q)                  // copy slot q * kWg + tid = (d-octet, key)
+                dma16_sbase(ksrc + q * 8 * (kWg / KEYT), k_lane, dst + q * 4096);
 #pragma unroll
             for (int q = 0; q < DMA_KV / 2; ++q)
-                dma16(&V8[j0 * D + (size_t)(q * kWg + tid) * 8], vs + (size_t)(q * kWg + wave * 64) * 8);
+                dma16_sbase(vsrc + q * kWg * 8, v_lane, dst + KEYT * D * 2 + q * 4096);
         };
 
         // Software pipeline over the 32x32 items q of this wave: in one straight-line step the
@@ -956,6 +959,7 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
                 for (int e = 0; e < 8; ++e) mb[tt][s][e] = (float)mfr[tt][s][e];
 
         const bf16_t *zsrc = Zg + ((size_t)u * (t - 1) + (l - 1)) * R * R * D;
+        const uint32_t stage0 = lds_address(stage);
         constexpr int NCHUNK = R / ZA;
         constexpr int BUF_BYTES = Z_CHUNK_BYTES + MQ_CHUNK_BYTES;
         // m_i[a] of the chunk as fp32 [ZA][TOK_WG]: each thread converts MQ_PER consecutive a of
@@ -980,8 +984,8 @@ __global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__re
             const int c = wave + 4 * k;
             const int off = (((c / DW) % ZA) * (R / 8) + 2 * (chunk * ZA / 16) + c / (DW * ZA)) * D +
                             (c % DW) * 64;                   // 16-byte units inside the chunk
-            dma16(zsrc + (size_t)chunk * ZA * Z_PER_A + (size_t)(off + lane) * 8,
-                  stage + buf * BUF_BYTES + (size_t)off * 16);
+            dma16_sbase(zsrc + (size_t)chunk * ZA * Z_PER_A + (size_t)off * 8, (uint32_t)lane * 16,
+                        stage0 + buf * BUF_BYTES + off * 16);
         };
         auto load_mq = [&](int chunk) {
 #pragma unroll
