@@ -389,10 +389,12 @@ __global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spar
                                                   int t, int parts_per_block)
 {
     const int u = blockIdx.y;
-    const int e = blockIdx.x * kWg + threadIdx.x;          // one entry of S per thread
-    if (e >= R * R) return;
-    const int a = e / R, bq = e % R;
-    const size_t dst = ((size_t)(bq / 8) * R + a) * 8 + (bq % 8);
+    // one entry of S per thread, threads in the order of the output layout [b'/8][a][8] so that
+    // a wave's 2-byte stores are contiguous (its reads are 32-byte pieces)
+    const int dst = blockIdx.x * kWg + threadIdx.x;
+    if (dst >= R * R) return;
+    const int a = (dst / 8) % R, bq = (dst / (8 * R)) * 8 + dst % 8;
+    const int e = a * R + bq;
     const size_t parts_per_unit = (size_t)t * parts_per_block;
     const float *src = Spart + (size_t)u * parts_per_unit * R * R + e;
     const int total = (t - 1) * parts_per_block;
