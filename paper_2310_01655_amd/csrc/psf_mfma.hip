@@ -1178,17 +1178,21 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     }
     if (tm) tm->mark();
     if (pb.t > 1) {
-        if constexpr (R == 64 && D == 64) {
-            // symmetric deal: only the (a, 16-wide column range) segments the output kernel reads
-            constexpr int GROUPS = (R / 16) * (R / 16 + 1) / 2;
-            const unsigned grid = (unsigned)(pb.units * GROUPS);
-            if (grid <= 256)
-                hipLaunchKernelGGL((k_state<R, D, 2, true, 64, 1>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
-                                   pb.n, pb.b, pb.t, pb.units);
-            else
-                hipLaunchKernelGGL((k_state<R, D, 2, true, 32, 2>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
-                                   pb.n, pb.b, pb.t, pb.units);
-        } else {
+        // Symmetric deal (d = 64): only the (a, 16-wide column range) segments the output kernel
+        // reads.  For r = 32 it pays once the grid is a few workgroups per CU; small grids keep
+        // the full tiles with four per wave, which fill the CUs better.
+        constexpr int GROUPS = (R / 16) * (R / 16 + 1) / 2;
+        const unsigned grid_sym = (unsigned)(pb.units * GROUPS);
+        if (D == 64 && (R == 64 || grid_sym > 512)) {
+            if constexpr (D == 64) {
+                if (grid_sym <= 256)
+                    hipLaunchKernelGGL((k_state<R, D, 2, true, 64, 1>), dim3(grid_sym), dim3(kWg), 0, s, w.MK8,
+                                       w.V8, w.Zg, pb.n, pb.b, pb.t, pb.units);
+                else
+                    hipLaunchKernelGGL((k_state<R, D, 2, true, 32, 2>), dim3(grid_sym), dim3(kWg), 0, s, w.MK8,
+                                       w.V8, w.Zg, pb.n, pb.b, pb.t, pb.units);
+            }
+        } else if constexpr (!(D == 64 && R == 64)) {
             constexpr int NA = (D == 64) ? 4 : 2;
             constexpr int AG = NA * 4 / (R / 32);
             const unsigned grid = (unsigned)(pb.units * (R / AG));
