@@ -14,11 +14,13 @@
 //                  one workgroup walks the blocks in order; phi'(k_j) = m_j (x) m_j is expanded
 //                  in registers (one operand broadcast across lanes with DPP) and never
 //                  written to memory.  A bf16 snapshot Z_{l+1} is stored after each block, so
-//                  the exclusive scan over blocks (Section 3.1) costs nothing extra.
+//                  the exclusive scan over blocks (Section 3.1) costs nothing extra.  Z is
+//                  symmetric in its two sketch indices; for d = 64 only the half the output
+//                  kernel reads is computed.
 //   k_out          per 256-token tile: exact in-block weights lt((Q_l K_l^T)^p) [V_l | 1]
-//                  (Section 3.2) kept in registers, plus phi'(Q_l) Z_l evaluated as
-//                  sum_a m_i[a] * (Z_l[a,:,:]^T m_i) so that no phi' operand is ever formed,
-//                  then the division by 1 + denominator (Section 3).
+//                  (Section 3.2) kept in registers, plus phi'(Q_l) Z_l with phi'(q_i) expanded
+//                  in registers as the MFMA operand, then the division by 1 + denominator
+//                  (Section 3).
 //
 // MFMA v_mfma_f32_32x32x16_bf16 operand layout used throughout (lane = 32*h + x, x < 32):
 //   A[i][k]: lane x = i, half h supplies k = 8h..8h+7 (8 bf16 per lane)

@@ -105,6 +105,29 @@ def test_config4_sweep_points_reduced_batch(n, r, b):
     sampled_parity(cfg, q, k, v, G, [(0, 0), (1, 11)], "config 4 n=%d r=%d b=%d" % (n, r, b))
 
 
+def test_state_kernel_two_workgroups_per_cu_variant():
+    # 36 units x 10 workgroups exceed one per CU: the state kernel runs its half-chunk variant
+    cfg = mk(3, 12, 2048, 64, 4, 64, 512)
+    q, k, v, G = draw(cfg, seed=23)
+    sampled_parity(cfg, q, k, v, G, [(0, 0), (1, 5), (2, 11)], "r=64, 36 units")
+
+
+def test_state_kernel_symmetric_variant_r32_large_grid():
+    # 192 units x 3 workgroups: r = 32 switches to the symmetric 16-wide segments
+    cfg = mk(16, 12, 1024, 64, 4, 32, 256)
+    q, k, v, G = draw(cfg, seed=29)
+    sampled_parity(cfg, q, k, v, G, [(0, 0), (7, 3), (15, 11)], "r=32, 192 units")
+
+
+def test_single_block_several_units():
+    # t = 1: no state kernel, no cross-block phase, every unit still gets its own tiles
+    cfg = mk(2, 3, 512, 64, 4, 64, 512, per_head=True)
+    q, k, v, G = draw(cfg, seed=31)
+    got, desc = gpu_attn(cfg, q, k, v, G)
+    assert psf.kernel_path(desc) == 1
+    assert_close(got.numpy(), oracle_attn(cfg, q, k, v, G), "bf16", "t = 1, 6 units")
+
+
 def test_deterministic_across_runs():
     cfg = mk(1, 2, 2048, 64, 4, 64, 512)
     q, k, v, G = draw(cfg)
