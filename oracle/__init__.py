@@ -52,6 +52,15 @@ def lib():
         L.psf_oracle_attn_def_batch.argtypes = ([_dp] * 4 + [ctypes.c_long] * 9
                                                 + [ctypes.c_int] * 2
                                                 + [_lp, ctypes.c_long, _dp, ctypes.c_int])
+        L.psf_oracle_sketch_bwd.restype = ctypes.c_int
+        L.psf_oracle_sketch_bwd.argtypes = [_dp] + [ctypes.c_long] * 4 + [_dp, _dp, _dp]
+        L.psf_oracle_attn_bwd.restype = ctypes.c_int
+        L.psf_oracle_attn_bwd.argtypes = ([_dp] * 5 + [ctypes.c_long] * 6 + [ctypes.c_int] * 2
+                                          + [_dp] * 3)
+        L.psf_oracle_attn_bwd_batch.restype = ctypes.c_int
+        L.psf_oracle_attn_bwd_batch.argtypes = ([_dp] * 4 + [ctypes.c_long] * 2 + [_dp]
+                                                + [ctypes.c_long] * 7 + [ctypes.c_int] * 2
+                                                + [_dp] * 3 + [ctypes.c_int])
         _lib = L
     return _lib
 
@@ -170,3 +179,49 @@ def attn_def_batch(Q, K, V, G, p, r, b, feat=FEAT_SKETCH, local=LOCAL_EXACT, row
     if rc < 0:
         raise ValueError("psf_oracle_attn_def_batch failed: %d" % rc)
     return O, rc
+
+
+def sketch_bwd(X, G, r, p, dM):
+    """(d m(x) / d x)^T dM for every row of X, m as in `sketch` (gradient of Algorithm 1)."""
+    X, dM = _f64(X), _f64(dM)
+    k, d = X.shape
+    G = _f64(G).reshape(-1) if p > 2 else np.zeros(1)
+    dX = np.empty((k, d))
+    rc = lib().psf_oracle_sketch_bwd(_ptr(X), k, d, r, p, _ptr(G), _ptr(dM), _ptr(dX))
+    if rc:
+        raise ValueError("psf_oracle_sketch_bwd failed: %d" % rc)
+    return dX
+
+
+def attn_bwd(Q, K, V, G, dO, p, r, b, feat=FEAT_SKETCH, local=LOCAL_EXACT):
+    """Gradient of `attn_def` (all rows) with respect to Q, K, V for dL/dO = dO; one unit."""
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    n, d = Q.shape
+    dv = V.shape[1]
+    G = _f64(G).reshape(-1) if (feat == FEAT_SKETCH and p > 2) else np.zeros(1)
+    dQ, dK, dV = np.empty((n, d)), np.empty((n, d)), np.empty((n, dv))
+    rc = lib().psf_oracle_attn_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(G), _ptr(dO), n, d, dv, r, p, b,
+                                   feat, local, _ptr(dQ), _ptr(dK), _ptr(dV))
+    if rc:
+        raise ValueError("psf_oracle_attn_bwd failed: %d" % rc)
+    return dQ, dK, dV
+
+
+def attn_bwd_batch(Q, K, V, G, dO, p, r, b, feat=FEAT_SKETCH, local=LOCAL_EXACT, max_threads=0):
+    """attn_bwd over [batch, heads, n, *] inputs; returns (dQ, dK, dV, threads_used)."""
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    B, H, n, d = Q.shape
+    dv = V.shape[-1]
+    if feat == FEAT_SKETCH and p > 2:
+        G = _f64(G).reshape(-1, g_len(d, r, p))
+        if G.shape[0] not in (1, H):
+            raise ValueError("G must have 1 or `heads` sets")
+    else:
+        G = np.zeros((1, 1))
+    dQ, dK, dV = np.empty_like(Q), np.empty_like(K), np.empty_like(V)
+    rc = lib().psf_oracle_attn_bwd_batch(
+        _ptr(Q), _ptr(K), _ptr(V), _ptr(G), G.shape[0], H, _ptr(dO), B * H, n, d, dv, p, r, b,
+        feat, local, _ptr(dQ), _ptr(dK), _ptr(dV), int(max_threads))
+    if rc < 0:
+        raise ValueError("psf_oracle_attn_bwd_batch failed: %d" % rc)
+    return dQ, dK, dV, rc

@@ -22,11 +22,18 @@
  *                            Section 2.2 (<x,y>^p = <x^{(x)p}, y^{(x)p}>)
  *   psf_oracle_attn_block    Section 3.1 block lower-triangular multiplication
  *                            (H_l, Z_l, P_l, row = p + a_i^T Z_l), Section 3.2 for P_l
+ *   oracle_pswn_bwd,         gradient of the same definition (Section 3 with the weights of
+ *   psf_oracle_attn_bwd      Sections 3.1/3.2, sketch of Algorithm 1) with respect to Q, K, V:
+ *                            the chain rule written out pair by pair; the paper trains
+ *                            through this function but prints no formula for it
  *
  * Pins (tests/test_oracle_*.py): brute-force masked polynomial attention written
  * in numpy, block-size invariance, definition == block algorithm, p = 2 base
  * case, closed forms for row 0 and V == 1, Monte-Carlo moments of the sketch,
- * non-negativity and the convex-hull bound.  No function here is unpinned.
+ * non-negativity and the convex-hull bound; the gradient functions against central
+ * finite differences of the forward functions above, automatic differentiation of an
+ * independently written forward, and closed forms (tests/test_oracle_bwd_pins.py).
+ * No function here is unpinned.
  */
 #include <math.h>
 #include <stdlib.h>
@@ -263,6 +270,149 @@ int psf_oracle_attn_block(const double *Q, const double *K, const double *V,
     return 0;
 }
 
+/* ---- gradient of Algorithm 1 -------------------------------------------------------
+ * Given dOut = dL/d PolySketchWithNegativity(A, r, deg) (k x cols), adds dL/dA (k x m) into
+ * dA.  Mirrors oracle_pswn: the node's output is sqrt(1/r) (M1 G1) * (M2 G2), so with
+ * U = M1 G1, W = M2 G2:  dU = sqrt(1/r) dOut * W,  dW = sqrt(1/r) dOut * U,
+ * dM1 = dU G1^T,  dM2 = dW G2^T, and the two subtrees are differentiated in turn with the
+ * matrices they consumed in the forward recursion (left subtree first, then right, then
+ * the node). */
+static int oracle_pswn_bwd(const double *A, long k, long m, long r, long deg,
+                           const double **g_first, const double **g_inner,
+                           const double *dOut, double *dA)
+{
+    if (deg == 1) {
+        for (long i = 0; i < k * m; ++i) dA[i] += dOut[i];
+        return 0;
+    }
+    const double *gf0 = *g_first, *gi0 = *g_inner;            /* where the left subtree starts */
+    double *M1 = oracle_pswn(A, k, m, r, deg / 2, g_first, g_inner);
+    const double *gf1 = *g_first, *gi1 = *g_inner;            /* where the right subtree starts */
+    double *M2 = oracle_pswn(A, k, m, r, deg / 2, g_first, g_inner);
+    long rows = (deg / 2 == 1) ? m : r;
+    const double *G1, *G2;
+    if (deg / 2 == 1) { G1 = *g_first;  G2 = G1 + rows * r;  *g_first = G2 + rows * r; }
+    else              { G1 = *g_inner;  G2 = G1 + rows * r;  *g_inner = G2 + rows * r; }
+    double *dM1 = (double *)calloc((size_t)k * (size_t)rows, sizeof(double));
+    double *dM2 = (double *)calloc((size_t)k * (size_t)rows, sizeof(double));
+    if (!M1 || !M2 || !dM1 || !dM2) { free(M1); free(M2); free(dM1); free(dM2); return 2; }
+    double scale = sqrt(1.0 / (double)r);
+    for (long i = 0; i < k; ++i) {
+        for (long c = 0; c < r; ++c) {
+            double u = 0.0, w = 0.0;
+            for (long e = 0; e < rows; ++e) {
+                u += M1[i * rows + e] * G1[e * r + c];
+                w += M2[i * rows + e] * G2[e * r + c];
+            }
+            double du = scale * dOut[i * r + c] * w, dw = scale * dOut[i * r + c] * u;
+            for (long e = 0; e < rows; ++e) {
+                dM1[i * rows + e] += du * G1[e * r + c];
+                dM2[i * rows + e] += dw * G2[e * r + c];
+            }
+        }
+    }
+    const double *a = gf0, *b = gi0;
+    int e1 = oracle_pswn_bwd(A, k, m, r, deg / 2, &a, &b, dM1, dA);
+    a = gf1; b = gi1;
+    int e2 = oracle_pswn_bwd(A, k, m, r, deg / 2, &a, &b, dM2, dA);
+    free(M1); free(M2); free(dM1); free(dM2);
+    return e1 ? e1 : e2;
+}
+
+/* dX (k x d, overwritten) = (d m(x) / d x)^T dM for every row, m = PolySketchWithNegativity
+ * (x, r, p/2) as in psf_oracle_sketch. */
+int psf_oracle_sketch_bwd(const double *X, long k, long d, long r, long p,
+                          const double *G, const double *dM, double *dX)
+{
+    if (!is_pow2(p) || p < 2 || k < 0 || d <= 0 || r <= 0) return 1;
+    const double *gf = G;
+    const double *gi = G ? G + psf_oracle_num_g_first(p) * d * r : NULL;
+    for (long i = 0; i < k * d; ++i) dX[i] = 0.0;
+    return oracle_pswn_bwd(X, k, d, r, p / 2, &gf, &gi, dM, dX);
+}
+
+/* ---- gradient of the definition -----------------------------------------------------
+ * L is any scalar with dL/dO = dO (n x dv).  With N_i = sum_{j<=i} w_ij v_j,
+ * D_i = 1 + sum_{j<=i} w_ij, o_i = N_i / D_i:
+ *   g_i = dO_i / D_i,  c_i = -<dO_i, o_i> / D_i,  dL/dw_ij = <g_i, v_j> + c_i,
+ *   dV_j = sum_{i>=j} w_ij g_i,
+ *   w = <q,k>^p   (exact pair):    ds = p <q,k>^{p-1} dw,  dq_i += ds k_j,  dk_j += ds q_i
+ *   w = <m(q),m(k)>^2 (sketched):  du = 2 <m(q),m(k)> dw,  dm(q_i) += du m(k_j), and v.v.,
+ * then dQ += J_m(Q)^T dm(Q), dK += J_m(K)^T dm(K) through oracle_pswn_bwd.  The sketch
+ * matrices G are constants.  One unit; dQ, dK (n x d) and dV (n x dv) are overwritten. */
+int psf_oracle_attn_bwd(const double *Q, const double *K, const double *V, const double *G,
+                        const double *dO, long n, long d, long dv, long r, long p, long b,
+                        int feat, int local, double *dQ, double *dK, double *dV)
+{
+    if (n <= 0 || b <= 0 || n % b != 0 || !is_pow2(p) || p < 2) return 1;
+    long mcols = (p == 2) ? d : r;
+    int sketch = feat == FEAT_SKETCH;
+    double *mq = NULL, *mk = NULL, *dmq = NULL, *dmk = NULL;
+    double *w = (double *)malloc(sizeof(double) * (size_t)n);
+    double *num = (double *)malloc(sizeof(double) * (size_t)dv);
+    double *tmp = (double *)malloc(sizeof(double) * (size_t)n * (size_t)d);
+    int err = (!w || !num || !tmp) ? 2 : 0;
+    if (sketch && !err) {
+        mq = (double *)malloc(sizeof(double) * (size_t)n * (size_t)mcols);
+        mk = (double *)malloc(sizeof(double) * (size_t)n * (size_t)mcols);
+        dmq = (double *)calloc((size_t)n * (size_t)mcols, sizeof(double));
+        dmk = (double *)calloc((size_t)n * (size_t)mcols, sizeof(double));
+        if (!mq || !mk || !dmq || !dmk) err = 2;
+        if (!err) err = psf_oracle_sketch(Q, n, d, r, p, G, mq);
+        if (!err) err = psf_oracle_sketch(K, n, d, r, p, G, mk);
+    }
+    if (!err) {
+        for (long i = 0; i < n * d; ++i) dQ[i] = dK[i] = 0.0;
+        for (long i = 0; i < n * dv; ++i) dV[i] = 0.0;
+        for (long i = 0; i < n; ++i) {
+            double den = 1.0;
+            for (long c = 0; c < dv; ++c) num[c] = 0.0;
+            for (long j = 0; j <= i; ++j) {
+                int exact = feat == FEAT_EXACT || (local == LOCAL_EXACT && (i / b) == (j / b));
+                if (exact) w[j] = ipow(dot(Q + i * d, K + j * d, d), p);
+                else { double u = dot(mq + i * mcols, mk + j * mcols, mcols); w[j] = u * u; }
+                den += w[j];
+                for (long c = 0; c < dv; ++c) num[c] += w[j] * V[j * dv + c];
+            }
+            double ci = 0.0;                       /* c_i = -<dO_i, o_i> / D_i */
+            for (long c = 0; c < dv; ++c) ci -= dO[i * dv + c] * (num[c] / den);
+            ci /= den;
+            for (long j = 0; j <= i; ++j) {
+                double dw = ci;
+                for (long c = 0; c < dv; ++c) {
+                    double g = dO[i * dv + c] / den;
+                    dw += g * V[j * dv + c];
+                    dV[j * dv + c] += w[j] * g;
+                }
+                int exact = feat == FEAT_EXACT || (local == LOCAL_EXACT && (i / b) == (j / b));
+                if (exact) {
+                    double s = dot(Q + i * d, K + j * d, d);
+                    double ds = (double)p * ipow(s, p - 1) * dw;
+                    for (long e = 0; e < d; ++e) {
+                        dQ[i * d + e] += ds * K[j * d + e];
+                        dK[j * d + e] += ds * Q[i * d + e];
+                    }
+                } else {
+                    double u = dot(mq + i * mcols, mk + j * mcols, mcols);
+                    double du = 2.0 * u * dw;
+                    for (long e = 0; e < mcols; ++e) {
+                        dmq[i * mcols + e] += du * mk[j * mcols + e];
+                        dmk[j * mcols + e] += du * mq[i * mcols + e];
+                    }
+                }
+            }
+        }
+        if (sketch) {
+            err = psf_oracle_sketch_bwd(Q, n, d, r, p, G, dmq, tmp);
+            for (long i = 0; i < n * d && !err; ++i) dQ[i] += tmp[i];
+            if (!err) err = psf_oracle_sketch_bwd(K, n, d, r, p, G, dmk, tmp);
+            for (long i = 0; i < n * d && !err; ++i) dK[i] += tmp[i];
+        }
+    }
+    free(w); free(num); free(tmp); free(mq); free(mk); free(dmq); free(dmk);
+    return err;
+}
+
 /* ---- drivers over (batch, head) units ---------------------------------------------
  * Q, K, V are [units, n, d|dv]; G is [g_sets, g_len] with unit u using set
  * (u % heads) when g_sets == heads, set 0 when g_sets == 1.  Rows are shared by all
@@ -309,6 +459,40 @@ int psf_oracle_attn_def_batch(const double *Q, const double *K, const double *V,
                                     rows, nrows, O_out + u * orows * dv, NULL);
         free(mq);
         free(mk);
+        if (e) {
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+            err = e;
+        }
+    }
+    return err ? -err : used;
+}
+
+/* Same driver for the gradient: dO is [units, n, dv]; dQ, dK [units, n, d], dV [units, n, dv]. */
+int psf_oracle_attn_bwd_batch(const double *Q, const double *K, const double *V,
+                              const double *G, long g_sets, long heads, const double *dO,
+                              long units, long n, long d, long dv, long p, long r, long b,
+                              int feat, int local, double *dQ, double *dK, double *dV,
+                              int max_threads)
+{
+    if (!is_pow2(p) || p < 2) return -1;
+    long g_len = psf_oracle_num_g_first(p) * d * r + psf_oracle_num_g_inner(p) * r * r;
+    int err = 0, used = 1;
+#ifdef _OPENMP
+    if (max_threads > 0) omp_set_num_threads(max_threads);
+#pragma omp parallel
+    {
+#pragma omp single
+        used = omp_get_num_threads();
+    }
+#pragma omp parallel for schedule(dynamic, 1)
+#endif
+    for (long u = 0; u < units; ++u) {
+        const double *g = G ? G + ((g_sets == 1) ? 0 : (u % heads)) * g_len : NULL;
+        int e = psf_oracle_attn_bwd(Q + u * n * d, K + u * n * d, V + u * n * dv, g,
+                                    dO + u * n * dv, n, d, dv, r, p, b, feat, local,
+                                    dQ + u * n * d, dK + u * n * d, dV + u * n * dv);
         if (e) {
 #ifdef _OPENMP
 #pragma omp critical
