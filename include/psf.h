@@ -123,6 +123,33 @@ psf_status psf_causal_attn_fwd_timed(const psf_desc *desc, const void *Q, const 
                                      float *stage_ms, int32_t n_stages, int32_t *n_written);
 const char *psf_stage_name(int path, int32_t stage);
 
+/*
+ * psf_causal_attn_bwd -- gradient of psf_causal_attn_fwd's output with respect to Q, K and V.
+ * The paper trains through the attention of Section 3 (weights of Sections 3.1 / 3.2, sketch of
+ * Algorithm 1); this is the chain rule through exactly that function, evaluated with the same
+ * block decomposition: the prefix states Z_l of Section 3.1 for the query side and their mirror
+ * image (sums over later blocks of phi'(q_i) [dO_i / D_i | -<dO_i, o_i> / D_i]^T) for keys and
+ * values.  The sketch matrices G are constants (no gradient).
+ *   Q, K, V, G as for the forward call; dO [batch, heads, n, dv]: dL/dO (device, never written)
+ *   dQ, dK [batch, heads, n, d], dV [batch, heads, n, dv]: device outputs in desc->dtype,
+ *   each written once; must not alias any input.
+ *   workspace: at least psf_bwd_workspace_bytes(desc) bytes, 256-byte aligned.  The forward
+ *   quantities are recomputed inside; nothing has to be kept from the forward call.
+ * Supported: PSF_FEAT_SKETCH with either in-block rule, every p, r, d, dv, b and dtype the
+ * descriptor check admits (fp32 arithmetic).  PSF_FEAT_EXACT returns PSF_ERR_UNSUPPORTED.
+ * The _timed variant reports per-stage milliseconds like psf_causal_attn_fwd_timed, stage
+ * names via psf_stage_name(2, i).
+ */
+size_t psf_bwd_workspace_bytes(const psf_desc *desc);
+psf_status psf_causal_attn_bwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                               const void *G, const void *dO, void *dQ, void *dK, void *dV,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+psf_status psf_causal_attn_bwd_timed(const psf_desc *desc, const void *Q, const void *K,
+                                     const void *V, const void *G, const void *dO, void *dQ,
+                                     void *dK, void *dV, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream, float *stage_ms, int32_t n_stages,
+                                     int32_t *n_written);
+
 const char *psf_status_string(psf_status status);
 
 #ifdef __cplusplus

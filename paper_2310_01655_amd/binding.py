@@ -19,7 +19,8 @@ LOCAL_EXACT, LOCAL_SKETCH = 0, 1
 
 EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_len", "psf_sketch",
            "psf_causal_attn_fwd", "psf_causal_attn_fwd_timed", "psf_stage_name",
-           "psf_status_string")
+           "psf_status_string", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
+           "psf_causal_attn_bwd_timed")
 
 
 class PsfDesc(ctypes.Structure):
@@ -64,6 +65,15 @@ def lib():
         L.psf_causal_attn_fwd_timed.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp,
                                                 ctypes.POINTER(ctypes.c_float), ctypes.c_int32,
                                                 ctypes.POINTER(ctypes.c_int32)]
+        L.psf_bwd_workspace_bytes.restype = ctypes.c_size_t
+        L.psf_bwd_workspace_bytes.argtypes = [dp]
+        L.psf_causal_attn_bwd.restype = ctypes.c_int
+        L.psf_causal_attn_bwd.argtypes = [dp] + [vp] * 9 + [ctypes.c_size_t, vp]
+        L.psf_causal_attn_bwd_timed.restype = ctypes.c_int
+        L.psf_causal_attn_bwd_timed.argtypes = [dp] + [vp] * 9 + [ctypes.c_size_t, vp,
+                                                                  ctypes.POINTER(ctypes.c_float),
+                                                                  ctypes.c_int32,
+                                                                  ctypes.POINTER(ctypes.c_int32)]
         L.psf_stage_name.restype = ctypes.c_char_p
         L.psf_stage_name.argtypes = [ctypes.c_int, ctypes.c_int32]
         L.psf_status_string.restype = ctypes.c_char_p
@@ -199,3 +209,57 @@ def psf_causal_attn_fwd_timed(desc, Q, K, V, G, O=None, workspace=None, stream=N
     path = kernel_path(desc)
     names = [lib().psf_stage_name(path, i).decode() for i in range(written.value)]
     return O, {nm: float(ms[i]) for i, nm in enumerate(names)}
+
+
+def bwd_workspace_bytes(desc):
+    return lib().psf_bwd_workspace_bytes(ctypes.byref(desc))
+
+
+def alloc_bwd_workspace(desc, device="cuda"):
+    return torch.empty(max(bwd_workspace_bytes(desc), 256), dtype=torch.uint8, device=device)
+
+
+def _bwd_args(desc, Q, K, V, G, dO, workspace):
+    B, H, n, d, dv = desc.batch, desc.heads, desc.n, desc.d, desc.dv
+    if workspace is None:
+        workspace = alloc_bwd_workspace(desc, Q.device)
+    if not workspace.is_cuda or workspace.dtype != torch.uint8:
+        raise ValueError("workspace must be a uint8 GPU tensor")
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    gs = _g_shape(desc)
+    ptrs = [_dev_ptr(Q, desc, (B, H, n, d), "Q"), _dev_ptr(K, desc, (B, H, n, d), "K"),
+            _dev_ptr(V, desc, (B, H, n, dv), "V"),
+            _dev_ptr(G, desc, gs, "G") if gs else None,
+            _dev_ptr(dO, desc, (B, H, n, dv), "dO"),
+            ctypes.c_void_p(dQ.data_ptr()), ctypes.c_void_p(dK.data_ptr()),
+            ctypes.c_void_p(dV.data_ptr()),
+            ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel())]
+    return (dQ, dK, dV), ptrs
+
+
+def psf_causal_attn_bwd(desc, Q, K, V, G, dO, workspace=None, stream=None):
+    """Gradient of the forward output with respect to Q, K, V; returns (dQ, dK, dV)."""
+    st = check_desc(desc)
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_bwd")
+    grads, ptrs = _bwd_args(desc, Q, K, V, G, dO, workspace)
+    st = lib().psf_causal_attn_bwd(ctypes.byref(desc), *ptrs, _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_bwd")
+    return grads
+
+
+def psf_causal_attn_bwd_timed(desc, Q, K, V, G, dO, workspace=None, stream=None):
+    """Same call with per-stage HIP-event timing; returns ((dQ, dK, dV), {stage_name: ms})."""
+    st = check_desc(desc)
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_bwd_timed")
+    grads, ptrs = _bwd_args(desc, Q, K, V, G, dO, workspace)
+    ms = (ctypes.c_float * 16)()
+    written = ctypes.c_int32(0)
+    st = lib().psf_causal_attn_bwd_timed(ctypes.byref(desc), *ptrs, _stream_ptr(stream), ms, 16,
+                                         ctypes.byref(written))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_bwd_timed")
+    names = [lib().psf_stage_name(2, i).decode() for i in range(written.value)]
+    return grads, {nm: float(ms[i]) for i, nm in enumerate(names)}

@@ -106,6 +106,23 @@ static psf_status run_attn(const psf_desc *desc, const void *Q, const void *K, c
                                 : general_attn(pb, Q, K, V, G, O, ws, s, tm);
 }
 
+static psf_status run_bwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                          const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
+                          size_t ws_bytes, void *stream, StageTimer *tm)
+{
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);
+    if (st != PSF_OK) return st;
+    if (!general_bwd_supported(pb)) return PSF_ERR_UNSUPPORTED;
+    if (!Q || !K || !V || !dO || !dQ || !dK || !dV) return PSF_ERR_NULL;
+    if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
+    const size_t need = general_bwd_workspace_bytes(pb);
+    if (!ws) return PSF_ERR_NULL;
+    if (ws_bytes < need) return PSF_ERR_WORKSPACE;
+    if (((uintptr_t)ws & 255u) != 0) return PSF_ERR_WORKSPACE;
+    return general_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm);
+}
+
 }  // namespace psf
 
 using namespace psf;
@@ -184,8 +201,47 @@ psf_status psf_causal_attn_fwd_timed(const psf_desc *desc, const void *Q, const 
     return st != PSF_OK ? st : st2;
 }
 
+size_t psf_bwd_workspace_bytes(const psf_desc *desc)
+{
+    Problem pb;
+    if (make_problem(desc, &pb) != PSF_OK || !general_bwd_supported(pb)) return 0;
+    return general_bwd_workspace_bytes(pb);
+}
+
+psf_status psf_causal_attn_bwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                               const void *G, const void *dO, void *dQ, void *dK, void *dV,
+                               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return run_bwd(desc, Q, K, V, G, dO, dQ, dK, dV, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+psf_status psf_causal_attn_bwd_timed(const psf_desc *desc, const void *Q, const void *K,
+                                     const void *V, const void *G, const void *dO, void *dQ,
+                                     void *dK, void *dV, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream, float *stage_ms, int32_t n_stages,
+                                     int32_t *n_written)
+{
+    if (!stage_ms || n_stages <= 0) return PSF_ERR_NULL;
+    if (n_written) *n_written = 0;
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);       // validate before creating any event
+    if (st != PSF_OK) return st;
+    if (!general_bwd_supported(pb)) return PSF_ERR_UNSUPPORTED;
+    StageTimer tm;
+    st = tm.begin((hipStream_t)hip_stream);
+    if (st != PSF_OK) return st;
+    st = run_bwd(desc, Q, K, V, G, dO, dQ, dK, dV, workspace, workspace_bytes, hip_stream, &tm);
+    int w = 0;
+    psf_status st2 = tm.finish(stage_ms, n_stages, &w);
+    if (n_written) *n_written = w;
+    return st != PSF_OK ? st : st2;
+}
+
 const char *psf_stage_name(int path, int32_t stage)
 {
+    static const char *bwd[] = {"sketches", "forward_rows", "reverse_states", "query_side",
+                                "key_side", "sketch_gradient"};
+    if (path == 2 && stage >= 0 && stage < 6) return bwd[stage];
     static const char *general[] = {"sketch_q", "sketch_k", "block_states", "exclusive_scan",
                                     "output"};
     static const char *mfma[] = {"sketch_and_layouts", "denominator_scan", "block_states_scan",

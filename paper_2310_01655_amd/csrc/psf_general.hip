@@ -359,6 +359,12 @@ psf_status general_sketch(const Problem &pb, const void *X, const void *G, void 
                    : sketch_launch<float>(pb, X, G, nullptr, M_out, Phi_out, s);
 }
 
+psf_status general_sketch_f32(const Problem &pb, const void *X, const void *G, float *M_f32, hipStream_t s)
+{
+    return pb.bf16 ? sketch_launch<bf16_t>(pb, X, G, M_f32, nullptr, nullptr, s)
+                   : sketch_launch<float>(pb, X, G, M_f32, nullptr, nullptr, s);
+}
+
 psf_status general_attn(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                         void *O, void *ws, hipStream_t s, StageTimer *tm)
 {

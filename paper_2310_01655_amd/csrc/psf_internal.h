@@ -44,6 +44,17 @@ psf_status general_sketch(const Problem &pb, const void *X, const void *G, void 
 psf_status general_attn(const Problem &pb, const void *Q, const void *K, const void *V,
                         const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);
 
+// m(x) of every row as fp32 [rows][mcols] (general sketch kernel).
+psf_status general_sketch_f32(const Problem &pb, const void *X, const void *G, float *M_f32,
+                              hipStream_t s);
+
+// Backward pass (general fp32 kernels; sketch features only).
+bool general_bwd_supported(const Problem &pb);
+size_t general_bwd_workspace_bytes(const Problem &pb);
+psf_status general_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V,
+                            const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
+                            hipStream_t s, StageTimer *tm);
+
 // bf16 MFMA path.
 size_t mfma_workspace_bytes(const Problem &pb);
 psf_status mfma_sketch(const Problem &pb, const void *X, const void *G, void *M_out,

@@ -76,6 +76,15 @@ def make_qkv(batch, heads, n, d, dv=None, seed=0, dist="normal", dtype="f32"):
     return q.to(td).contiguous(), k.to(td).contiguous(), v.to(td).contiguous()
 
 
+def make_dout(batch, heads, n, dv, seed=0, dtype="f32"):
+    """dL/dO for the backward pass: entries N(0,1) (stand-in for the gradient that the layers
+    after the attention send back), CPU tensor in the storage dtype."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(int(seed) + 7919)
+    z = torch.randn(batch, heads, n, dv, generator=g, dtype=torch.float32)
+    return z.to(torch_dtype(dtype)).contiguous()
+
+
 def make_sketch_matrices(heads, d, r, p, per_head=False, seed=0, dtype="f32"):
     """Gaussian sketch matrices, [heads if per_head else 1, g_len(d, r, p)]; set h is
     drawn from seed + h.  Within a set: the p/2 matrices d x r, then the p/2 - 2

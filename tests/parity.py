@@ -26,6 +26,19 @@ def assert_close(got, want, dtype, what=""):
     return max_abs, rel
 
 
+def assert_close_scaled(got, want, dtype, what=""):
+    """For gradients, whose entries have no fixed scale (a bf16 result of magnitude 8 is already
+    1.6e-2 away from its float64 value): max-abs error relative to the largest entry (at least
+    1) and relative Frobenius error, both within the storage type's tolerance."""
+    max_abs, rel = errors(got, want)
+    scale = max(1.0, float(np.abs(np.asarray(want, dtype=np.float64)).max()))
+    tol = TOL[dtype]
+    assert np.isfinite(np.asarray(got, dtype=np.float64)).all(), what
+    assert max_abs <= tol * scale and rel <= tol, "%s: max_abs %.3e (scale %.2e) rel_fro %.3e (tol %.0e)" % (
+        what, max_abs, scale, rel, tol)
+    return max_abs, rel
+
+
 def as_f64(t):
     return t.to(torch.float64).numpy()
 

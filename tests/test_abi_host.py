@@ -77,6 +77,32 @@ def test_null_pointers_are_rejected_before_any_launch():
     assert L.psf_causal_attn_fwd_timed(ref, one, one, one, one, one, one, 1 << 40, None, None, 0, None) == 1
 
 
+def test_backward_entry_point_validates_on_the_host():
+    L = psf.lib()
+    d = psf.make_desc(1, 1, 1024, 64, 4, 16, 128, "f32")
+    ref = ctypes.byref(d)
+    one = ctypes.c_void_p(256)   # never dereferenced: every call below fails validation first
+    need = psf.bwd_workspace_bytes(d)
+    # m(Q), m(K) and their gradients, [V|1] and G_i rows, both state arrays, direct dQ / dK terms
+    rows, kc = 1024, 65
+    assert need >= 4 * rows * 16 * 4 + 2 * rows * kc * 4 + 2 * 8 * 256 * kc * 4 + 2 * rows * 64 * 4
+    big = 1 << 40
+    args = [one] * 8
+    for hole in (0, 1, 2, 3, 4, 5, 6, 7):                                    # each required pointer
+        a = list(args)
+        a[hole] = None
+        assert L.psf_causal_attn_bwd(ref, *a, one, big, None) == 1, hole
+    assert L.psf_causal_attn_bwd(ref, *args, None, big, None) == 1
+    assert L.psf_causal_attn_bwd(ref, *args, one, need - 1, None) == 4
+    assert L.psf_causal_attn_bwd(ref, *args, ctypes.c_void_p(264), big, None) == 4
+    exact = psf.make_desc(1, 1, 64, 8, 4, 1, 8, "f32", feat=psf.FEAT_EXACT)
+    assert psf.bwd_workspace_bytes(exact) == 0
+    assert L.psf_causal_attn_bwd(ctypes.byref(exact), *args, one, big, None) == 3
+    assert L.psf_causal_attn_bwd_timed(ref, *args, one, big, None, None, 0, None) == 1
+    assert psf.lib().psf_stage_name(2, 0) == b"sketches"
+    assert psf.lib().psf_stage_name(2, 5) == b"sketch_gradient"
+
+
 def test_status_strings_and_stage_names():
     assert psf.status_string(0) == "ok"
     assert all(psf.status_string(c) for c in range(6))

@@ -1,0 +1,83 @@
+"""GPU parity of psf_causal_attn_bwd (through the C ABI) against the float64 gradient oracle.
+Same seeded inputs on both sides; the oracle consumes the storage-rounded values upcast to
+float64.  Tolerance: 1e-4 (fp32 storage) / 2e-2 (bf16 storage) on relative Frobenius error and on
+max-abs error relative to the largest entry (gradients have no fixed scale), for each of dQ,
+dK, dV."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2310_01655_amd import binding as psf
+from paper_2310_01655_amd import inputs
+from parity import as_f64, assert_close_scaled
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(batch, heads, n, d, dv, p, r, b, dtype, local=psf.LOCAL_EXACT, per_head=False, seed=41,
+             dist="normal"):
+    q, k, v = inputs.make_qkv(batch, heads, n, d, dv=dv, seed=seed, dist=dist, dtype=dtype)
+    dO = inputs.make_dout(batch, heads, n, dv, seed=seed, dtype=dtype)
+    G = inputs.make_sketch_matrices(heads, d, r, p, per_head=per_head, seed=0, dtype=dtype) if p > 2 else None
+    desc = psf.make_desc(batch, heads, n, d, p, r, b, dtype, dv=dv, local=local, per_head=per_head)
+    dev = torch.device("cuda:0")
+    args = [x.to(dev) if x is not None else None for x in (q, k, v, G, dO)]
+    dQ, dK, dV = psf.psf_causal_attn_bwd(desc, *args)
+    torch.cuda.synchronize()
+    wQ, wK, wV, _ = oracle.attn_bwd_batch(as_f64(q), as_f64(k), as_f64(v),
+                                          as_f64(G) if G is not None else None, as_f64(dO), p, r, b,
+                                          local=oracle.LOCAL_EXACT if local == psf.LOCAL_EXACT else oracle.LOCAL_SKETCH)
+    res = {}
+    for name, got, want in (("dQ", dQ, wQ), ("dK", dK, wK), ("dV", dV, wV)):
+        res[name] = assert_close_scaled(got.float().cpu().numpy(), want, dtype, "%s n=%d d=%d p=%d r=%d b=%d" % (name, n, d, p, r, b))
+    print((n, d, dv, p, r, b, dtype), {k2: ("%.2e" % v2[0], "%.2e" % v2[1]) for k2, v2 in res.items()})
+    return dQ, dK, dV
+
+
+@pytest.mark.parametrize("n,d,dv,p,r,b", [
+    (256, 64, 64, 4, 16, 64),      # config-1 shape, shorter
+    (128, 32, 48, 4, 16, 32),      # dv != d
+    (128, 24, 24, 2, 16, 32),      # base case p = 2: m(x) = x
+    (128, 32, 32, 8, 16, 32),      # one inner level
+    (96, 16, 16, 16, 8, 32),       # two inner levels
+    (128, 32, 32, 4, 16, 128),     # single block
+    (64, 16, 16, 4, 8, 1),         # every token its own block
+    (192, 40, 24, 4, 20, 64),      # sizes that are no powers of two
+])
+def test_backward_fp32_small_full_parity(n, d, dv, p, r, b):
+    run_case(2, 2, n, d, dv, p, r, b, "f32", per_head=True)
+
+
+@pytest.mark.parametrize("p", [4, 8])
+def test_backward_fp32_sketched_local_weights(p):
+    run_case(1, 3, 128, 32, 32, p, 16, 32, "f32", local=psf.LOCAL_SKETCH, per_head=True)
+
+
+def test_backward_config1_full_size():
+    run_case(1, 1, 1024, 64, 64, 4, 16, 128, "f32", seed=1001)
+
+
+@pytest.mark.parametrize("n,d,p,r,b", [(256, 64, 4, 32, 64), (256, 64, 4, 64, 128), (128, 128, 8, 64, 64)])
+def test_backward_bf16_storage(n, d, p, r, b):
+    run_case(1, 2, n, d, d, p, r, b, "bf16", per_head=True)
+
+
+def test_backward_heavy_tailed_inputs():
+    run_case(1, 2, 256, 64, 64, 4, 32, 64, "f32", dist="student_t3")
+
+
+def test_backward_is_deterministic():
+    a = run_case(1, 2, 256, 64, 64, 4, 32, 64, "f32")
+    b2 = run_case(1, 2, 256, 64, 64, 4, 32, 64, "f32")
+    for x, y in zip(a, b2):
+        assert torch.equal(x, y)
+
+
+def test_backward_exact_features_are_refused():
+    desc = psf.make_desc(1, 1, 64, 4, 4, 4, 16, "f32", feat=psf.FEAT_EXACT)
+    assert psf.bwd_workspace_bytes(desc) == 0
+    x = torch.zeros(1, 1, 64, 4, device="cuda")
+    with pytest.raises(psf.PsfError) as e:
+        psf.psf_causal_attn_bwd(desc, x, x, x, None, x)
+    assert e.value.code == 3
