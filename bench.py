@@ -1,7 +1,9 @@
-"""Benchmark of the causal polysketch attention forward path on one MI355X.
+"""Benchmark of causal polysketch attention on one MI355X.
 
-A step = one full pass of the hot path (sketch of Q and K, block prefix states, fused output)
-over one synthetic batch.  Prints ONE JSON line ("Measurement").
+Default: the forward hot path; a step = one full pass (sketch of Q and K, block prefix states,
+fused output) over one synthetic batch.  `--pass bwd` times the backward entry point instead
+(a step = gradients with respect to Q, K, V, forward quantities recomputed inside).  Prints ONE
+JSON line ("Measurement").
 """
 import argparse
 import json
@@ -14,6 +16,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+FP32_VALU_PEAK_TFLOPS = 157.3       # MI355X fp32 vector, published (256 CUs x 128 FMA lanes x 2.4 GHz)
 HBM_PEAK_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
@@ -46,6 +49,92 @@ def stage_flops(cfg):
     }
     f["total"] = sum(f.values())
     return f
+
+
+def bwd_stage_flops(cfg):
+    """Algorithmic flops of one backward step (multiply-add = 2) by stage of
+    psf_causal_attn_bwd.  F = r^2 features, kc = dv + 1 columns, pairs = causal pairs inside
+    blocks; states cover n - b tokens (first / last block excluded as in the forward count)."""
+    U = cfg["batch"] * cfg["heads"]
+    n, d, r, b, p = cfg["n"], cfg["d"], cfg["r"], cfg["b"], cfg["p"]
+    F, kc = r * r, d + 1
+    pairs = n * (b + 1) // 2
+    sketch = 8 * n * d * r if p == 4 else 16 * n * d * r + 8 * n * r * r      # one side: Q or K
+    cross = 2 * (n - b) * F * kc                                             # one state-sized contraction
+    f = {
+        "sketches": U * 2 * sketch,
+        "forward_rows": U * (2 * cross + pairs * 2 * (d + kc)),              # H_l, phi^T Z_l, in-block rows
+        "reverse_states": U * cross,
+        "query_side": U * (cross + 4 * (n - b) * F + pairs * 2 * (kc + 2 * d)),
+        "key_side": U * (2 * cross + 4 * (n - b) * F + pairs * 2 * (kc + 2 * d + d)),
+        "sketch_gradient": U * 2 * 2 * sketch,                               # recompute + transposed products
+    }
+    f["total"] = sum(f.values())
+    return f
+
+
+def cpu_baseline_bwd(cfg, q, k, v, G, dO):
+    """The float64 gradient oracle (O(n^2) pair loop) on `cores` whole units."""
+    import numpy as np
+    import oracle
+    cores = min(os.cpu_count() or 1, 16)
+    units = min(cores, cfg["batch"] * cfg["heads"])
+    sel = [(i // cfg["heads"], i % cfg["heads"]) for i in range(units)]
+    f64 = lambda t: np.stack([t[bi, h].double().numpy() for bi, h in sel])[None]
+    Gs = G.double().numpy()
+    Gs = Gs[[h for _, h in sel]] if Gs.shape[0] > 1 else Gs
+    t0 = time.perf_counter()
+    *_, threads = oracle.attn_bwd_batch(f64(q), f64(k), f64(v), Gs, f64(dO), cfg["p"], cfg["r"], cfg["b"],
+                                        max_threads=cores)
+    dt = time.perf_counter() - t0
+    return {"value": units * cfg["n"] / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d whole units of n=%d (float64 pair-by-pair gradient, O(n^2))" % (units, cfg["n"]),
+            "seconds_measured": dt}
+
+
+def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
+    dev = torch.device("cuda:0")
+    dO = inputs.make_dout(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], seed=1000 + idx, dtype=cfg["dtype"])
+    desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
+                         cfg["dtype"], per_head=cfg["per_head"])
+    qd, kd, vd, Gd, dOd = (x.to(dev) for x in (q, k, v, G, dO))
+    ws = psf.alloc_bwd_workspace(desc, dev)
+    stream = torch.cuda.current_stream()
+    for _ in range(args.warmup):
+        psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    reps = max(2, min(args.steps, 5))
+    acc = {}
+    for _ in range(reps):
+        _, st = psf.psf_causal_attn_bwd_timed(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream)
+        for nm, ms in st.items():
+            acc[nm] = acc.get(nm, 0.0) + ms / reps
+    fl = bwd_stage_flops(cfg)
+    dom = max(acc, key=lambda nm: acc[nm])
+    achieved = fl[dom] / (acc[dom] * 1e-3) / 1e12
+    out = {
+        "metric": "causal_polysketch_attention_bwd_tokens_per_s",
+        "value": cfg["batch"] * cfg["n"] * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "pass": "bwd", "batch": cfg["batch"], "heads": cfg["heads"],
+                   "n": cfg["n"], "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
+                   "storage": cfg["dtype"], "kernel_path": "general_fp32"},
+        "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
+        "tflops": fl["total"] / (ms_per_step * 1e-3) / 1e12,
+        "roofline": {"kernel": dom, "bound": "alu", "achieved": achieved, "peak": FP32_VALU_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": None,
+                     "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc}},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_bwd(cfg, q, k, v, G, dO)
+    print(json.dumps(out))
 
 
 def cpu_baseline(cfg, q, k, v, G, rows_per_unit=16384):
@@ -85,7 +174,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="config3", help="config2|config3|config5|sweep_n.._r.._b..")
+    ap.add_argument("--workload", default=None,
+                    help="config1|config2|config3|config5|sweep_n.._r.._b.. (default config3; config2 with --pass bwd)")
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd"],
+                    help="fwd: psf_causal_attn_fwd (the headline); bwd: psf_causal_attn_bwd")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also issue one 256 MiB device copy, so that a counter run can scale "
@@ -100,6 +192,8 @@ def main():
     from paper_2310_01655_amd import inputs
 
     wl = workloads()
+    if args.workload is None:
+        args.workload = "config3" if args.which == "fwd" else "config2"
     if args.workload not in wl:
         sys.exit("unknown workload %s; choose from %s" % (args.workload, ", ".join(sorted(wl))))
     cfg = wl[args.workload]
@@ -110,6 +204,9 @@ def main():
                               dist=cfg["dist"], dtype=cfg["dtype"])
     G = inputs.make_sketch_matrices(cfg["heads"], cfg["d"], cfg["r"], cfg["p"], per_head=cfg["per_head"],
                                     seed=0, dtype=cfg["dtype"])
+    if args.which == "bwd":
+        run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx)
+        return
     desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
                          cfg["dtype"], per_head=cfg["per_head"])
     path = psf.kernel_path(desc)
@@ -147,7 +244,7 @@ def main():
         "metric": "causal_polysketch_attention_fwd_tokens_per_s", "value": tokens * args.steps / elapsed,
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg["dtype"], "data": "synthetic",
+        "dtype": "bf16" if path == 1 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"],
                    "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
                    "kernel_path": "mfma_bf16" if path == 1 else "general_fp32"},

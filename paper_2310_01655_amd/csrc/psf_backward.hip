@@ -21,7 +21,8 @@ namespace psf {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kFeatChunk = 4096;   // features staged per step (16 KB of LDS)
+constexpr int kRows = 8;            // tokens per workgroup in the row / column kernels (at most)
+constexpr int kChunk = 256;         // features or tokens staged per step and row (8 KB of LDS for 8 rows)
 constexpr int kStateFeat = 8;      // features per workgroup in the state kernel
 constexpr int kStateChunk = 64;    // tokens staged per step in the state kernel
 
@@ -107,269 +108,425 @@ __global__ __launch_bounds__(kThreads) void bwd_scan_kernel(float *__restrict__ 
     }
 }
 
-// ---- helpers for one workgroup --------------------------------------------------------
-// out[c] (c < kc, in LDS) += sum_{k < K} wt[k] * Mat[k * ld + c]; wt in LDS.  The threads are
-// split into slices over k; `red` is kThreads floats of LDS scratch.
-__device__ void wg_weighted_rows(const float *wt, int K, const float *__restrict__ Mat, size_t ld,
-                                 int kc, float *out, float *red)
+// ---- helpers for one workgroup of RT rows (RT <= kRows) ------------------------------------
+// Every workgroup handles RT consecutive tokens of one block, so that a state (F x kc floats)
+// is streamed once per RT tokens.  LDS arrays are [kRows][pitch].
+
+// out[rt][c] += sum_{k < K} wt[k][rt] * Mat[k * ld + c] for c < kc; wt ([K][kRows], rows
+// rt >= RT hold zeros) and out in LDS.  The threads are split into slices over k; `red` is
+// kRows * kThreads floats of LDS scratch.  Reads of Mat are contiguous in c.
+__device__ void wg_weighted_rows(const float *wt, int RT, int K, const float *__restrict__ Mat,
+                                 size_t ld, int kc, float *out, int out_pitch, float *red)
 {
     const int tid = threadIdx.x;
     int kcp = 32;
     while (kcp < kc && kcp < kThreads) kcp *= 2;        // columns per slice (power of two)
     const int nsl = kThreads / kcp;
-    for (int c0 = 0; c0 < kc; c0 += kcp) {              // kc > 256 is excluded by the limits
+    for (int c0 = 0; c0 < kc; c0 += kcp) {
         const int c = c0 + tid % kcp, sl = tid / kcp;
-        float a = 0.f;
+        float a[kRows];
+        for (int rt = 0; rt < kRows; ++rt) a[rt] = 0.f;
         if (c < kc)
-            for (int k = sl; k < K; k += nsl) a += wt[k] * Mat[(size_t)k * ld + c];
+            for (int k = sl; k < K; k += nsl) {
+                const float mv = Mat[(size_t)k * ld + c];
+                const float4 w0 = *(const float4 *)&wt[k * kRows], w1 = *(const float4 *)&wt[k * kRows + 4];
+                a[0] += w0.x * mv; a[1] += w0.y * mv; a[2] += w0.z * mv; a[3] += w0.w * mv;
+                a[4] += w1.x * mv; a[5] += w1.y * mv; a[6] += w1.z * mv; a[7] += w1.w * mv;
+            }
         __syncthreads();
-        red[tid] = a;
+        for (int rt = 0; rt < kRows; ++rt) red[rt * kThreads + tid] = a[rt];
         __syncthreads();
-        if (tid < kcp && c0 + tid < kc) {
-            float s = 0.f;
-            for (int q = 0; q < nsl; ++q) s += red[q * kcp + tid];
-            out[c0 + tid] += s;
+        for (int idx = tid; idx < RT * kcp; idx += kThreads) {
+            const int rt = idx / kcp, cc = idx % kcp;
+            if (c0 + cc < kc) {
+                float sacc = 0.f;
+                for (int q = 0; q < nsl; ++q) sacc += red[rt * kThreads + q * kcp + cc];
+                out[rt * out_pitch + c0 + cc] += sacc;
+            }
         }
         __syncthreads();
     }
 }
 
-// dm[a] += sum_b (T[a,b] + T[b,a]) m[b] with T[f] = sum_c S[f][c] g[c], f = a * mcols + b, for
-// all F = mcols^2 features of the state S.  m, g, dm in LDS; tbuf is kFeatChunk floats of LDS.
-// T is formed in chunks of whole rows a; every dm entry is updated by one thread per phase, so
-// the result does not depend on scheduling.
-__device__ void wg_state_times_vector(const float *__restrict__ S, int kc, int mcols, const float *m,
-                                      const float *g, float *dm, float *tbuf)
+// dm[rt][a] += 2 sum_c g[rt][c] sum_b mT[b][rt] S[(a * mcols + b) * kc + c]: the contraction of
+// a state S (mcols^2 features x kc columns, symmetric in its two sketch indices because
+// phi' = m (x) m) with g over the columns and with m over one sketch index; by that symmetry
+// this equals sum_b (T[a,b] + T[b,a]) m[b] for T = S g.  mT is [mcols][kRows] (rows rt >= RT
+// zero), g is [kRows][g_pitch], dm [kRows][dm_pitch]; wsum is 4 * kRows floats of LDS.  Thread (c, slice) walks the
+// rows a of its slice, so reads of S are contiguous in c and every dm entry has one writer.
+__device__ void wg_state_bilinear(const float *__restrict__ S, int kc, int mcols, int RT,
+                                  const float *mT, const float *g, int g_pitch, float *dm,
+                                  int dm_pitch, float *wsum)
 {
-    const int tid = threadIdx.x;
-    const int rows_per_chunk = kFeatChunk / mcols;          // mcols <= 256: at least 16 rows
-    for (int a0 = 0; a0 < mcols; a0 += rows_per_chunk) {
-        const int na = min(rows_per_chunk, mcols - a0), nf = na * mcols;
-        __syncthreads();
-        for (int ff = tid; ff < nf; ff += kThreads) {
-            const float *srow = S + ((size_t)a0 * mcols + ff) * kc;
-            float tv = 0.f;
-            for (int c = 0; c < kc; ++c) tv += srow[c] * g[c];
-            tbuf[ff] = tv;
-        }
-        __syncthreads();
-        for (int aa = tid; aa < na; aa += kThreads) {       // sum_b T[a,b] m[b]
-            float sacc = 0.f;
-            for (int bq = 0; bq < mcols; ++bq) sacc += tbuf[aa * mcols + bq] * m[bq];
-            dm[a0 + aa] += sacc;
-        }
-        __syncthreads();
-        for (int bq = tid; bq < mcols; bq += kThreads) {    // sum_a T[a,b] m[a]
-            float sacc = 0.f;
-            for (int aa = 0; aa < na; ++aa) sacc += tbuf[aa * mcols + bq] * m[a0 + aa];
-            dm[bq] += sacc;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int kcp = 32;
+    while (kcp < kc && kcp < kThreads) kcp *= 2;
+    const int nsl = kThreads / kcp, c = tid % kcp, sl = tid / kcp;
+    const int iters = (mcols + nsl - 1) / nsl;
+    for (int c0 = 0; c0 < kc; c0 += kcp) {                  // one pass unless kc = 257
+        const int cc = c0 + c;
+        for (int it = 0; it < iters; ++it) {
+            const int a = it * nsl + sl;
+            float part[kRows];
+            for (int rt = 0; rt < kRows; ++rt) part[rt] = 0.f;
+            if (a < mcols && cc < kc) {
+                const float *sa = S + (size_t)a * mcols * kc + cc;
+                for (int bq = 0; bq < mcols; ++bq) {
+                    const float zv = sa[(size_t)bq * kc];
+                    const float4 m0 = *(const float4 *)&mT[bq * kRows], m1 = *(const float4 *)&mT[bq * kRows + 4];
+                    part[0] += m0.x * zv; part[1] += m0.y * zv; part[2] += m0.z * zv; part[3] += m0.w * zv;
+                    part[4] += m1.x * zv; part[5] += m1.y * zv; part[6] += m1.z * zv; part[7] += m1.w * zv;
+                }
+                for (int rt = 0; rt < kRows; ++rt) part[rt] *= (rt < RT) ? g[rt * g_pitch + cc] : 0.f;
+            }
+            const int width = kcp < 64 ? kcp : 64;          // lanes of this slice inside the wave
+            for (int off = width / 2; off > 0; off >>= 1)
+                for (int rt = 0; rt < kRows; ++rt) part[rt] += __shfl_xor(part[rt], off);
+            if (kcp <= 64) {
+                if (lane % kcp == 0 && a < mcols)
+                    for (int rt = 0; rt < kRows; ++rt)
+                        if (rt < RT) dm[rt * dm_pitch + a] += 2.f * part[rt];
+            } else {
+                const int wps = kcp / 64;                   // waves per slice
+                __syncthreads();
+                if (lane == 0)
+                    for (int rt = 0; rt < kRows; ++rt) wsum[wave * kRows + rt] = part[rt];
+                __syncthreads();
+                if (c == 0 && a < mcols)
+                    for (int rt = 0; rt < kRows; ++rt)
+                        if (rt < RT) {
+                            float sacc = 0.f;
+                            for (int w = 0; w < wps; ++w) sacc += wsum[(sl * wps + w) * kRows + rt];
+                            dm[rt * dm_pitch + a] += 2.f * sacc;
+                        }
+            }
         }
     }
     __syncthreads();
 }
 
+// LDS of the three token kernels is carved at run time from the actual sizes (d, dv, sketch
+// columns), so that the common shapes keep several workgroups per CU.  In-block pairs are
+// handled tile by tile: kTile tokens of the other side are staged in LDS (rows padded by one
+// float) together with their [V | 1] or G rows, then every (token, staged token) pair is one
+// thread's dot product out of LDS.
+constexpr int kTile = 32;
+
+struct Carver {
+    float *base;
+    size_t used = 0;
+    __host__ __device__ explicit Carver(float *b) : base(b) {}
+    __host__ __device__ float *take(size_t floats)
+    {
+        float *p = base + used;
+        used += (floats + 3) & ~(size_t)3;              // keep 16-byte alignment
+        return p;
+    }
+};
+
+// rows [r0, r0 + nr) of a row-major array of `width` columns -> LDS tile with pitch width + 1
+template <typename S>
+__device__ __forceinline__ void stage_rows(const S *__restrict__ src, size_t r0, int nr, int width,
+                                           float *dst)
+{
+    for (int idx = threadIdx.x; idx < nr * width; idx += kThreads)
+        dst[(idx / width) * (width + 1) + idx % width] = load_f(src, r0 * width + idx);
+}
+
+struct TokenLds {                                        // what every token kernel carves
+    float *wt, *red, *mT, *wsum, *ta, *tc, *pw, *pd;
+};
+__host__ __device__ inline size_t carve_common(Carver &cv, TokenLds *t, int wa, int kc, int mcols)
+{
+    TokenLds x;
+    x.wt = cv.take((size_t)kRows * kChunk);              // features of RT tokens, [k][kRows]
+    x.red = cv.take((size_t)kRows * kThreads);
+    x.mT = cv.take((size_t)mcols * kRows);
+    x.wsum = cv.take(4 * kRows);
+    x.ta = cv.take((size_t)kTile * (wa + 1));            // staged q / k (or m) rows
+    x.tc = cv.take((size_t)kTile * (kc + 1));            // staged [V | 1] or G rows
+    x.pw = cv.take((size_t)kRows * kTile);               // pair weights
+    x.pd = cv.take((size_t)kRows * kTile);               // pair gradients
+    if (t) *t = x;
+    return cv.used;
+}
+
 // ---- forward rows and G_i ------------------------------------------------------------
-// One workgroup per row i: row_i = phi_i^T Z_l + sum_{j <= i, same block} w_ij C_j, then
-// GC[i] = [dO_i / D_i | -<dO_i, o_i> / D_i].
+// Rows i0 .. i0 + RT - 1 of one block: row_i = phi_i^T Z_l + sum_{j <= i, same block} w_ij C_j,
+// then GC[i] = [dO_i / D_i | -<dO_i, o_i> / D_i].
+__host__ __device__ inline size_t rows_lds(float *base, int d, int kc, int mcols, int wa, TokenLds *t,
+                                           float **rowv, float **mq, float **qs, float **dots)
+{
+    Carver cv(base);
+    carve_common(cv, t, wa, kc, mcols);
+    float *a = cv.take((size_t)kRows * kc), *b2 = cv.take((size_t)kRows * mcols),
+          *c = cv.take((size_t)kRows * d), *e = cv.take(2 * kRows);
+    if (rowv) { *rowv = a; *mq = b2; *qs = c; *dots = e; }
+    return cv.used * sizeof(float);
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void bwd_rows_kernel(
     const float *__restrict__ MQ, const float *__restrict__ MK, const T *__restrict__ Q,
     const T *__restrict__ K, const float *__restrict__ CV, const float *__restrict__ Z,
     const T *__restrict__ dO, float *__restrict__ GC, int n, int d, int dv, int p, int b, int t,
-    int mcols, long long F, int local_exact)
+    int mcols, long long F, int local_exact, int RT)
 {
-    __shared__ float wt[kFeatChunk];
-    __shared__ float rowv[PSF_MAX_DIM + 1], mq[PSF_MAX_DIM], qs[PSF_MAX_DIM], red[kThreads];
-    __shared__ float dots[2];
-    const int tid = threadIdx.x, i = blockIdx.x, u = blockIdx.y;
-    const int l = i / b, kc = dv + 1;
-    const size_t urow = (size_t)u * n, row = urow + i;
-    for (int c = tid; c < kc; c += kThreads) rowv[c] = 0.f;
-    for (int e = tid; e < mcols; e += kThreads) mq[e] = MQ[row * mcols + e];
-    for (int e = tid; e < d; e += kThreads) qs[e] = load_f(Q, row * d + e);
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int tid = threadIdx.x, i0 = blockIdx.x * RT, u = blockIdx.y;
+    const int l = i0 / b, kc = dv + 1, wa = local_exact ? d : mcols;
+    TokenLds L;
+    float *rowv, *mq, *qs, *dots;
+    rows_lds(smem, d, kc, mcols, wa, &L, &rowv, &mq, &qs, &dots);
+    const size_t urow = (size_t)u * n;
+    for (int idx = tid; idx < kRows * kChunk; idx += kThreads) L.wt[idx] = 0.f;   // rows >= RT stay zero
+    for (int idx = tid; idx < RT * kc; idx += kThreads) rowv[idx] = 0.f;
+    for (int idx = tid; idx < RT * mcols; idx += kThreads) mq[idx] = MQ[(urow + i0) * mcols + idx];
+    for (int idx = tid; idx < RT * d; idx += kThreads) qs[idx] = load_f(Q, (urow + i0) * d + idx);
     __syncthreads();
     if (l > 0) {
         const float *z = Z + (((size_t)u * t + l) * (size_t)F) * kc;
-        for (long long f0 = 0; f0 < F; f0 += kFeatChunk) {
-            const int nf = (int)min((long long)kFeatChunk, F - f0);
+        for (long long f0 = 0; f0 < F; f0 += kChunk) {
+            const int nf = (int)min((long long)kChunk, F - f0);
             __syncthreads();
-            for (int ff = tid; ff < nf; ff += kThreads) {
+            for (int idx = tid; idx < RT * nf; idx += kThreads) {
+                const int rt = idx / nf, ff = idx % nf;
                 const long long f = f0 + ff;
-                wt[ff] = mq[f / mcols] * mq[f % mcols];
+                L.wt[ff * kRows + rt] = mq[rt * mcols + f / mcols] * mq[rt * mcols + f % mcols];
             }
             __syncthreads();
-            wg_weighted_rows(wt, nf, z + (size_t)f0 * kc, kc, kc, rowv, red);
+            wg_weighted_rows(L.wt, RT, nf, z + (size_t)f0 * kc, kc, kc, rowv, kc, L.red);
         }
     }
-    const int jbeg = l * b;
-    for (int j0 = jbeg; j0 <= i; j0 += kFeatChunk) {
-        const int nj = min(kFeatChunk, i + 1 - j0);
+    const float *qrow = local_exact ? qs : mq;
+    const int jbeg = l * b, jend = i0 + RT;               // keys jbeg .. jend - 1; row rt keeps j <= i0 + rt
+    for (int j0 = jbeg; j0 < jend; j0 += kTile) {
+        const int nj = min(kTile, jend - j0);
         __syncthreads();
-        for (int jj = tid; jj < nj; jj += kThreads) {
-            const size_t rj = urow + j0 + jj;
-            float s = 0.f, w;
-            if (local_exact) {
-                for (int e = 0; e < d; ++e) s += qs[e] * load_f(K, rj * d + e);
-                w = pow_int(s, p);
-            } else {
-                for (int e = 0; e < mcols; ++e) s += mq[e] * MK[rj * mcols + e];
-                w = s * s;
+        if (local_exact) stage_rows(K, urow + j0, nj, d, L.ta);
+        else stage_rows(MK, urow + j0, nj, mcols, L.ta);
+        stage_rows(CV, urow + j0, nj, kc, L.tc);
+        __syncthreads();
+        for (int idx = tid; idx < RT * nj; idx += kThreads) {
+            const int rt = idx / nj, jj = idx % nj;
+            float w = 0.f;
+            if (j0 + jj <= i0 + rt) {
+                float sdot = 0.f;
+                for (int e = 0; e < wa; ++e) sdot += qrow[rt * wa + e] * L.ta[jj * (wa + 1) + e];
+                w = local_exact ? pow_int(sdot, p) : sdot * sdot;
             }
-            wt[jj] = w;
+            L.pw[rt * kTile + jj] = w;
         }
         __syncthreads();
-        wg_weighted_rows(wt, nj, CV + (urow + j0) * kc, kc, kc, rowv, red);
+        for (int idx = tid; idx < RT * kc; idx += kThreads) {
+            const int rt = idx / kc, c = idx % kc;
+            float a = 0.f;
+            for (int jj = 0; jj < nj; ++jj) a += L.pw[rt * kTile + jj] * L.tc[jj * (kc + 1) + c];
+            rowv[rt * kc + c] += a;
+        }
     }
     __syncthreads();
-    // <dO_i, N_i>
-    float part = 0.f;
-    for (int c = tid; c < dv; c += kThreads) part += load_f(dO, row * dv + c) * rowv[c];
-    red[tid] = part;
-    __syncthreads();
-    if (tid == 0) {
-        float s = 0.f;
-        for (int q = 0; q < kThreads; ++q) s += red[q];
-        const float den = 1.f + rowv[dv];
-        dots[0] = den;
-        dots[1] = -(s / den) / den;          // -<dO_i, o_i> / D_i
+    if (tid < RT) {                                       // <dO_i, N_i>, D_i
+        const size_t row = urow + i0 + tid;
+        float sdot = 0.f;
+        for (int c = 0; c < dv; ++c) sdot += load_f(dO, row * dv + c) * rowv[tid * kc + c];
+        const float den = 1.f + rowv[tid * kc + dv];
+        dots[2 * tid] = den;
+        dots[2 * tid + 1] = -(sdot / den) / den;          // -<dO_i, o_i> / D_i
     }
     __syncthreads();
-    for (int c = tid; c < dv; c += kThreads) GC[row * kc + c] = load_f(dO, row * dv + c) / dots[0];
-    if (tid == 0) GC[row * kc + dv] = dots[1];
+    for (int idx = tid; idx < RT * dv; idx += kThreads) {
+        const int rt = idx / dv, c = idx % dv;
+        const size_t row = urow + i0 + rt;
+        GC[row * kc + c] = load_f(dO, row * dv + c) / dots[2 * rt];
+    }
+    if (tid < RT) GC[(urow + i0 + tid) * kc + dv] = dots[2 * tid + 1];
 }
 
-// ---- gradient with respect to the query side, one workgroup per row i -------------------
+// ---- gradient with respect to the query side, rows i0 .. i0 + RT - 1 ---------------------
+__host__ __device__ inline size_t q_lds(float *base, int d, int kc, int mcols, int wa, TokenLds *t,
+                                        float **g, float **mq, float **qs, float **dm, float **dq)
+{
+    Carver cv(base);
+    carve_common(cv, t, wa, kc, mcols);
+    float *a = cv.take((size_t)kRows * kc), *b2 = cv.take((size_t)kRows * mcols),
+          *c = cv.take((size_t)kRows * d), *e = cv.take((size_t)kRows * mcols),
+          *f = cv.take((size_t)kRows * d);
+    if (g) { *g = a; *mq = b2; *qs = c; *dm = e; *dq = f; }
+    return cv.used * sizeof(float);
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void bwd_q_kernel(
     const float *__restrict__ MQ, const float *__restrict__ MK, const T *__restrict__ Q,
     const T *__restrict__ K, const float *__restrict__ CV, const float *__restrict__ GC,
     const float *__restrict__ Z, float *__restrict__ dMQ, float *__restrict__ dQd, int n, int d,
-    int dv, int p, int b, int t, int mcols, long long F, int local_exact)
+    int dv, int p, int b, int t, int mcols, long long F, int local_exact, int RT)
 {
-    __shared__ float ds[kFeatChunk];
-    __shared__ float g[PSF_MAX_DIM + 1], mq[PSF_MAX_DIM], qs[PSF_MAX_DIM], dm[PSF_MAX_DIM],
-        dq[PSF_MAX_DIM];
-    const int tid = threadIdx.x, i = blockIdx.x, u = blockIdx.y;
-    const int l = i / b, kc = dv + 1;
-    const size_t urow = (size_t)u * n, row = urow + i;
-    for (int c = tid; c < kc; c += kThreads) g[c] = GC[row * kc + c];
-    for (int e = tid; e < mcols; e += kThreads) { mq[e] = MQ[row * mcols + e]; dm[e] = 0.f; }
-    for (int e = tid; e < d; e += kThreads) { qs[e] = load_f(Q, row * d + e); dq[e] = 0.f; }
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int tid = threadIdx.x, i0 = blockIdx.x * RT, u = blockIdx.y;
+    const int l = i0 / b, kc = dv + 1, wa = local_exact ? d : mcols;
+    TokenLds L;
+    float *g, *mq, *qs, *dm, *dq;
+    q_lds(smem, d, kc, mcols, wa, &L, &g, &mq, &qs, &dm, &dq);
+    const size_t urow = (size_t)u * n;
+    for (int idx = tid; idx < RT * kc; idx += kThreads) g[idx] = GC[(urow + i0) * kc + idx];
+    for (int idx = tid; idx < kRows * mcols; idx += kThreads) {
+        const int rt = idx / mcols, e = idx % mcols;
+        const float mv = rt < RT ? MQ[(urow + i0 + rt) * mcols + e] : 0.f;
+        mq[idx] = mv;
+        L.mT[e * kRows + rt] = mv;
+        dm[idx] = 0.f;
+    }
+    for (int idx = tid; idx < RT * d; idx += kThreads) {
+        qs[idx] = load_f(Q, (urow + i0) * d + idx);
+        dq[idx] = 0.f;
+    }
     __syncthreads();
     if (l > 0) {
         const float *z = Z + (((size_t)u * t + l) * (size_t)F) * kc;
-        wg_state_times_vector(z, kc, mcols, mq, g, dm, ds);
+        wg_state_bilinear(z, kc, mcols, RT, L.mT, g, kc, dm, mcols, L.wsum);
     }
     __syncthreads();
-    const int jbeg = l * b;
-    for (int j0 = jbeg; j0 <= i; j0 += kFeatChunk) {
-        const int nj = min(kFeatChunk, i + 1 - j0);
+    const float *qrow = local_exact ? qs : mq;
+    float *gout = local_exact ? dq : dm;                  // where the in-block term goes
+    const int jbeg = l * b, jend = i0 + RT;
+    for (int j0 = jbeg; j0 < jend; j0 += kTile) {
+        const int nj = min(kTile, jend - j0);
         __syncthreads();
-        for (int jj = tid; jj < nj; jj += kThreads) {
-            const size_t rj = urow + j0 + jj;
-            float dw = 0.f, s = 0.f;
-            for (int c = 0; c < kc; ++c) dw += g[c] * CV[rj * kc + c];
-            if (local_exact) {
-                for (int e = 0; e < d; ++e) s += qs[e] * load_f(K, rj * d + e);
-                ds[jj] = (float)p * pow_int(s, p - 1) * dw;
-            } else {
-                for (int e = 0; e < mcols; ++e) s += mq[e] * MK[rj * mcols + e];
-                ds[jj] = 2.f * s * dw;
+        if (local_exact) stage_rows(K, urow + j0, nj, d, L.ta);
+        else stage_rows(MK, urow + j0, nj, mcols, L.ta);
+        stage_rows(CV, urow + j0, nj, kc, L.tc);
+        __syncthreads();
+        for (int idx = tid; idx < RT * nj; idx += kThreads) {
+            const int rt = idx / nj, jj = idx % nj;
+            float val = 0.f;
+            if (j0 + jj <= i0 + rt) {
+                float dw = 0.f, sdot = 0.f;
+                for (int c = 0; c < kc; ++c) dw += g[rt * kc + c] * L.tc[jj * (kc + 1) + c];
+                for (int e = 0; e < wa; ++e) sdot += qrow[rt * wa + e] * L.ta[jj * (wa + 1) + e];
+                val = local_exact ? (float)p * pow_int(sdot, p - 1) * dw : 2.f * sdot * dw;
             }
+            L.pd[rt * kTile + jj] = val;
         }
         __syncthreads();
-        if (local_exact) {
-            for (int e = tid; e < d; e += kThreads) {
-                float a = 0.f;
-                for (int jj = 0; jj < nj; ++jj) a += ds[jj] * load_f(K, (urow + j0 + jj) * d + e);
-                dq[e] += a;
-            }
-        } else {
-            for (int e = tid; e < mcols; e += kThreads) {
-                float a = 0.f;
-                for (int jj = 0; jj < nj; ++jj) a += ds[jj] * MK[(urow + j0 + jj) * mcols + e];
-                dm[e] += a;
-            }
+        for (int idx = tid; idx < RT * wa; idx += kThreads) {
+            const int rt = idx / wa, e = idx % wa;
+            float a = 0.f;
+            for (int jj = 0; jj < nj; ++jj) a += L.pd[rt * kTile + jj] * L.ta[jj * (wa + 1) + e];
+            gout[rt * wa + e] += a;
         }
     }
     __syncthreads();
-    for (int e = tid; e < mcols; e += kThreads) dMQ[row * mcols + e] = dm[e];
-    for (int e = tid; e < d; e += kThreads) dQd[row * d + e] = dq[e];
+    for (int idx = tid; idx < RT * mcols; idx += kThreads) dMQ[(urow + i0) * mcols + idx] = dm[idx];
+    for (int idx = tid; idx < RT * d; idx += kThreads) dQd[(urow + i0) * d + idx] = dq[idx];
 }
 
-// ---- gradient with respect to the key side and V, one workgroup per column j --------------
+// ---- gradient with respect to the key side and V, columns j0 .. j0 + RT - 1 ----------------
+__host__ __device__ inline size_t k_lds(float *base, int d, int kc, int mcols, int wa, TokenLds *t,
+                                        float **cj, float **dc, float **mk, float **ks, float **dm,
+                                        float **dk)
+{
+    Carver cv(base);
+    carve_common(cv, t, wa, kc, mcols);
+    float *a = cv.take((size_t)kRows * kc), *b2 = cv.take((size_t)kRows * kc),
+          *c = cv.take((size_t)kRows * mcols), *e = cv.take((size_t)kRows * d),
+          *f = cv.take((size_t)kRows * mcols), *h = cv.take((size_t)kRows * d);
+    if (cj) { *cj = a; *dc = b2; *mk = c; *ks = e; *dm = f; *dk = h; }
+    return cv.used * sizeof(float);
+}
+
 template <typename T>
 __global__ __launch_bounds__(kThreads) void bwd_k_kernel(
     const float *__restrict__ MQ, const float *__restrict__ MK, const T *__restrict__ Q,
     const T *__restrict__ K, const float *__restrict__ CV, const float *__restrict__ GC,
     const float *__restrict__ RB, float *__restrict__ dMK, float *__restrict__ dKd,
     T *__restrict__ dV, int n, int d, int dv, int p, int b, int t, int mcols, long long F,
-    int local_exact)
+    int local_exact, int RT)
 {
-    __shared__ float wt[kFeatChunk], ds[kFeatChunk];
-    __shared__ float cj[PSF_MAX_DIM + 1], mk[PSF_MAX_DIM], ks[PSF_MAX_DIM], dm[PSF_MAX_DIM],
-        dk[PSF_MAX_DIM], dc[PSF_MAX_DIM + 1], red[kThreads];
-    const int tid = threadIdx.x, j = blockIdx.x, u = blockIdx.y;
-    const int l = j / b, kc = dv + 1;
-    const size_t urow = (size_t)u * n, row = urow + j;
-    for (int c = tid; c < kc; c += kThreads) { cj[c] = CV[row * kc + c]; dc[c] = 0.f; }
-    for (int e = tid; e < mcols; e += kThreads) { mk[e] = MK[row * mcols + e]; dm[e] = 0.f; }
-    for (int e = tid; e < d; e += kThreads) { ks[e] = load_f(K, row * d + e); dk[e] = 0.f; }
+    extern __shared__ __attribute__((aligned(16))) float smem[];
+    const int tid = threadIdx.x, j0 = blockIdx.x * RT, u = blockIdx.y;
+    const int l = j0 / b, kc = dv + 1, wa = local_exact ? d : mcols;
+    TokenLds L;
+    float *cj, *dc, *mk, *ks, *dm, *dk;
+    k_lds(smem, d, kc, mcols, wa, &L, &cj, &dc, &mk, &ks, &dm, &dk);
+    const size_t urow = (size_t)u * n;
+    for (int idx = tid; idx < kRows * kChunk; idx += kThreads) L.wt[idx] = 0.f;   // rows >= RT stay zero
+    for (int idx = tid; idx < RT * kc; idx += kThreads) {
+        cj[idx] = CV[(urow + j0) * kc + idx];
+        dc[idx] = 0.f;
+    }
+    for (int idx = tid; idx < kRows * mcols; idx += kThreads) {
+        const int rt = idx / mcols, e = idx % mcols;
+        const float mv = rt < RT ? MK[(urow + j0 + rt) * mcols + e] : 0.f;
+        mk[idx] = mv;
+        L.mT[e * kRows + rt] = mv;
+        dm[idx] = 0.f;
+    }
+    for (int idx = tid; idx < RT * d; idx += kThreads) {
+        ks[idx] = load_f(K, (urow + j0) * d + idx);
+        dk[idx] = 0.f;
+    }
     __syncthreads();
     if (l < t - 1) {
         const float *rb = RB + (((size_t)u * t + l) * (size_t)F) * kc;
-        wg_state_times_vector(rb, kc, mcols, mk, cj, dm, ds);
-        for (long long f0 = 0; f0 < F; f0 += kFeatChunk) {       // dC_j = R_l^T psi_j
-            const int nf = (int)min((long long)kFeatChunk, F - f0);
+        wg_state_bilinear(rb, kc, mcols, RT, L.mT, cj, kc, dm, mcols, L.wsum);
+        for (long long f0 = 0; f0 < F; f0 += kChunk) {            // dC_j = R_l^T psi_j
+            const int nf = (int)min((long long)kChunk, F - f0);
             __syncthreads();
-            for (int ff = tid; ff < nf; ff += kThreads) {
+            for (int idx = tid; idx < RT * nf; idx += kThreads) {
+                const int rt = idx / nf, ff = idx % nf;
                 const long long f = f0 + ff;
-                wt[ff] = mk[f / mcols] * mk[f % mcols];
+                L.wt[ff * kRows + rt] = mk[rt * mcols + f / mcols] * mk[rt * mcols + f % mcols];
             }
             __syncthreads();
-            wg_weighted_rows(wt, nf, rb + (size_t)f0 * kc, kc, kc, dc, red);
+            wg_weighted_rows(L.wt, RT, nf, rb + (size_t)f0 * kc, kc, kc, dc, kc, L.red);
         }
     }
     __syncthreads();
-    const int iend = (l + 1) * b;                         // rows i = j .. iend - 1 share j's block
-    for (int i0 = j; i0 < iend; i0 += kFeatChunk) {
-        const int ni = min(kFeatChunk, iend - i0);
+    // in-block pairs: rows i = j0 .. iend - 1; column rt keeps i >= j0 + rt
+    const float *krow = local_exact ? ks : mk;
+    float *gout = local_exact ? dk : dm;
+    const int iend = (l + 1) * b;
+    for (int ib = j0; ib < iend; ib += kTile) {
+        const int ni = min(kTile, iend - ib);
         __syncthreads();
-        for (int ii = tid; ii < ni; ii += kThreads) {
-            const size_t ri = urow + i0 + ii;
-            float dw = 0.f, s = 0.f;
-            for (int c = 0; c < kc; ++c) dw += GC[ri * kc + c] * cj[c];
-            if (local_exact) {
-                for (int e = 0; e < d; ++e) s += load_f(Q, ri * d + e) * ks[e];
-                wt[ii] = pow_int(s, p);
-                ds[ii] = (float)p * pow_int(s, p - 1) * dw;
-            } else {
-                for (int e = 0; e < mcols; ++e) s += MQ[ri * mcols + e] * mk[e];
-                wt[ii] = s * s;
-                ds[ii] = 2.f * s * dw;
+        if (local_exact) stage_rows(Q, urow + ib, ni, d, L.ta);
+        else stage_rows(MQ, urow + ib, ni, mcols, L.ta);
+        stage_rows(GC, urow + ib, ni, kc, L.tc);
+        __syncthreads();
+        for (int idx = tid; idx < RT * ni; idx += kThreads) {
+            const int rt = idx / ni, ii = idx % ni;
+            float w = 0.f, val = 0.f;
+            if (ib + ii >= j0 + rt) {
+                float dw = 0.f, sdot = 0.f;
+                for (int c = 0; c < kc; ++c) dw += L.tc[ii * (kc + 1) + c] * cj[rt * kc + c];
+                for (int e = 0; e < wa; ++e) sdot += L.ta[ii * (wa + 1) + e] * krow[rt * wa + e];
+                w = local_exact ? pow_int(sdot, p) : sdot * sdot;
+                val = local_exact ? (float)p * pow_int(sdot, p - 1) * dw : 2.f * sdot * dw;
             }
+            L.pw[rt * kTile + ii] = w;
+            L.pd[rt * kTile + ii] = val;
         }
         __syncthreads();
-        if (local_exact) {
-            for (int e = tid; e < d; e += kThreads) {
-                float a = 0.f;
-                for (int ii = 0; ii < ni; ++ii) a += ds[ii] * load_f(Q, (urow + i0 + ii) * d + e);
-                dk[e] += a;
-            }
-        } else {
-            for (int e = tid; e < mcols; e += kThreads) {
-                float a = 0.f;
-                for (int ii = 0; ii < ni; ++ii) a += ds[ii] * MQ[(urow + i0 + ii) * mcols + e];
-                dm[e] += a;
-            }
+        for (int idx = tid; idx < RT * wa; idx += kThreads) {
+            const int rt = idx / wa, e = idx % wa;
+            float a = 0.f;
+            for (int ii = 0; ii < ni; ++ii) a += L.pd[rt * kTile + ii] * L.ta[ii * (wa + 1) + e];
+            gout[rt * wa + e] += a;
         }
-        // dV_j += sum_i w_ij g_i: the first dv columns of GC
-        wg_weighted_rows(wt, ni, GC + (urow + i0) * kc, kc, dv, dc, red);
+        for (int idx = tid; idx < RT * dv; idx += kThreads) {     // dV_j += sum_i w_ij g_i
+            const int rt = idx / dv, c = idx % dv;
+            float a = 0.f;
+            for (int ii = 0; ii < ni; ++ii) a += L.pw[rt * kTile + ii] * L.tc[ii * (kc + 1) + c];
+            dc[rt * kc + c] += a;
+        }
     }
     __syncthreads();
-    for (int e = tid; e < mcols; e += kThreads) dMK[row * mcols + e] = dm[e];
-    for (int e = tid; e < d; e += kThreads) dKd[row * d + e] = dk[e];
-    for (int c = tid; c < dv; c += kThreads) store_f(dV, row * dv + c, dc[c]);
+    for (int idx = tid; idx < RT * mcols; idx += kThreads) dMK[(urow + j0) * mcols + idx] = dm[idx];
+    for (int idx = tid; idx < RT * d; idx += kThreads) dKd[(urow + j0) * d + idx] = dk[idx];
+    for (int idx = tid; idx < RT * dv; idx += kThreads)
+        store_f(dV, (urow + j0 + idx / dv) * dv + idx % dv, dc[(idx / dv) * kc + idx % dv]);
 }
 
 // ---- gradient through Algorithm 1, one row per loop iteration --------------------------
@@ -533,10 +690,24 @@ psf_status bwd_launch(const Problem &pb, const void *Q, const void *K, const voi
                            per_block, 0);
         PSF_LAUNCH_CHECK();
     }
-    const dim3 rgrid((unsigned)pb.n, (unsigned)pb.units);
-    hipLaunchKernelGGL(bwd_rows_kernel<T>, rgrid, dim3(kThreads), 0, s, w.MQ, w.MK, (const T *)Q,
+    int RT = kRows;                                       // tokens per workgroup, all in one block
+    while (pb.b % RT != 0) RT /= 2;
+    const dim3 rgrid((unsigned)(pb.n / RT), (unsigned)pb.units);
+    const int wa = pb.local_exact ? pb.d : pb.mcols;
+    const size_t lds_rows = rows_lds(nullptr, pb.d, kc, pb.mcols, wa, nullptr, nullptr, nullptr, nullptr, nullptr);
+    const size_t lds_q = q_lds(nullptr, pb.d, kc, pb.mcols, wa, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr);
+    const size_t lds_k = k_lds(nullptr, pb.d, kc, pb.mcols, wa, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                               nullptr);
+    // the largest admitted sizes (d = dv = r = 256) need more than the default dynamic LDS limit
+    PSF_HIP_TRY(hipFuncSetAttribute((const void *)bwd_rows_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds_rows));
+    PSF_HIP_TRY(hipFuncSetAttribute((const void *)bwd_q_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds_q));
+    PSF_HIP_TRY(hipFuncSetAttribute((const void *)bwd_k_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)lds_k));
+    hipLaunchKernelGGL(bwd_rows_kernel<T>, rgrid, dim3(kThreads), lds_rows, s, w.MQ, w.MK, (const T *)Q,
                        (const T *)K, w.CV, w.Z, (const T *)dO, w.GC, pb.n, pb.d, pb.dv, pb.p, pb.b, pb.t,
-                       pb.mcols, pb.F, le);
+                       pb.mcols, pb.F, le, RT);
     PSF_LAUNCH_CHECK();
     if (tm) tm->mark();                                   // stage: forward rows
 
@@ -550,13 +721,13 @@ psf_status bwd_launch(const Problem &pb, const void *Q, const void *K, const voi
     }
     if (tm) tm->mark();                                   // stage: reverse states
 
-    hipLaunchKernelGGL(bwd_q_kernel<T>, rgrid, dim3(kThreads), 0, s, w.MQ, w.MK, (const T *)Q, (const T *)K,
-                       w.CV, w.GC, w.Z, w.dMQ, w.dQd, pb.n, pb.d, pb.dv, pb.p, pb.b, pb.t, pb.mcols, pb.F, le);
+    hipLaunchKernelGGL(bwd_q_kernel<T>, rgrid, dim3(kThreads), lds_q, s, w.MQ, w.MK, (const T *)Q, (const T *)K,
+                       w.CV, w.GC, w.Z, w.dMQ, w.dQd, pb.n, pb.d, pb.dv, pb.p, pb.b, pb.t, pb.mcols, pb.F, le, RT);
     PSF_LAUNCH_CHECK();
     if (tm) tm->mark();                                   // stage: query side
-    hipLaunchKernelGGL(bwd_k_kernel<T>, rgrid, dim3(kThreads), 0, s, w.MQ, w.MK, (const T *)Q, (const T *)K,
+    hipLaunchKernelGGL(bwd_k_kernel<T>, rgrid, dim3(kThreads), lds_k, s, w.MQ, w.MK, (const T *)Q, (const T *)K,
                        w.CV, w.GC, w.RB, w.dMK, w.dKd, (T *)dV, pb.n, pb.d, pb.dv, pb.p, pb.b, pb.t,
-                       pb.mcols, pb.F, le);
+                       pb.mcols, pb.F, le, RT);
     PSF_LAUNCH_CHECK();
     if (tm) tm->mark();                                   // stage: key side
 
