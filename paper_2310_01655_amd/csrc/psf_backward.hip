@@ -23,7 +23,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kRows = 8;            // tokens per workgroup in the row / column kernels (at most)
 constexpr int kChunk = 256;         // features or tokens staged per step and row (8 KB of LDS for 8 rows)
-constexpr int kStateFeat = 8;      // features per workgroup in the state kernel
+constexpr int kStateFeat = 32;     // features per workgroup in the state kernel
 constexpr int kStateChunk = 64;    // tokens staged per step in the state kernel
 
 __device__ __forceinline__ float pow_int(float x, int p)
