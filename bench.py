@@ -137,6 +137,73 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     print(json.dumps(out))
 
 
+def run_decode(args, psf, inputs, torch):
+    """Token-by-token evaluation at serving shape: 64 sequences x 12 heads, d = 64, r = 64,
+    b = 1024 (the headline per-unit shape).  One block is fed first (untimed) so that the prefix
+    state is populated; the timed steps follow it."""
+    import numpy as np
+    cfg = dict(batch=64, heads=12, n=32768, d=64, p=4, r=64, b=1024, dtype="bf16", per_head=False)
+    dev = torch.device("cuda:0")
+    U = cfg["batch"] * cfg["heads"]
+    steps_total = 2 * cfg["b"]                              # two whole blocks of tokens are drawn
+    assert args.warmup + args.steps + 64 < cfg["b"], "timed steps must stay inside the second block"
+    q, k, v = inputs.make_qkv(cfg["batch"], cfg["heads"], steps_total, cfg["d"], seed=1006, dtype=cfg["dtype"])
+    G = inputs.make_sketch_matrices(cfg["heads"], cfg["d"], cfg["r"], cfg["p"], seed=0, dtype=cfg["dtype"])
+    desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"], cfg["dtype"])
+    qd, kd, vd, Gd = q.to(dev), k.to(dev), v.to(dev), G.to(dev)
+    toks = [(qd[:, :, i:i + 1].contiguous(), kd[:, :, i:i + 1].contiguous(), vd[:, :, i:i + 1].contiguous())
+            for i in range(cfg["b"] + args.warmup + args.steps)]
+    state = psf.decode_new_state(desc, dev)
+    o = torch.empty(cfg["batch"], cfg["heads"], 1, cfg["d"], dtype=qd.dtype, device=dev)
+    stream = torch.cuda.current_stream()
+    pos = 0
+    for _ in range(cfg["b"] + args.warmup):
+        psf.psf_decode_step(desc, *toks[pos], Gd, pos, state, o=o, stream=stream)
+        pos += 1
+    torch.cuda.synchronize()
+    first_timed = pos
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        psf.psf_decode_step(desc, *toks[pos], Gd, pos, state, o=o, stream=stream)
+        pos += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    # the last output against the oracle's row of the same position (one unit)
+    got = o[0, 0, 0].float().cpu().numpy()
+    import oracle
+    want = oracle.attn_def(q[0, 0].double().numpy(), k[0, 0].double().numpy(), v[0, 0].double().numpy(),
+                           G[0].double().numpy(), cfg["p"], cfg["r"], cfg["b"], rows=[pos - 1])[0]
+    assert np.abs(got - want).max() <= 2e-2, "decode output does not match the oracle"
+    state_bytes = U * cfg["r"] ** 2 * (cfg["d"] + 1) * 4          # Z is read once per step
+    achieved = state_bytes / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": "causal_polysketch_attention_decode_tokens_per_s", "value": cfg["batch"] * args.steps / elapsed,
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "decode_b64", "pass": "decode", "batch": cfg["batch"], "heads": cfg["heads"],
+                   "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"], "storage": cfg["dtype"],
+                   "first_timed_position": first_timed, "state_bytes": psf.decode_state_bytes(desc)},
+        "roofline": {"kernel": "dec_state_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "note": "whole step time against the bytes of the prefix states (read once per step)"},
+    }
+    if not args.no_cpu_baseline:
+        cores = min(os.cpu_count() or 1, 16)
+        nrow = 64                                              # rows of one unit at the timed positions
+        rows = list(range(first_timed, first_timed + nrow))
+        t0 = time.perf_counter()
+        oracle.attn_def(q[0, 0].double().numpy(), k[0, 0].double().numpy(), v[0, 0].double().numpy(),
+                        G[0].double().numpy(), cfg["p"], cfg["r"], cfg["b"], rows=rows)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": nrow / dt * cores / cfg["heads"], "unit": "tokens/s", "cores": 1, "kind": "oracle",
+                               "sample": "%d rows (positions %d..) of one unit by the float64 definition on one core, "
+                                         "including the sketches of two blocks; value scaled to %d cores / %d heads "
+                                         "per token" % (nrow, first_timed, cores, cfg["heads"]),
+                               "seconds_measured": dt}
+    print(json.dumps(out))
+
+
 def cpu_baseline(cfg, q, k, v, G, rows_per_unit=16384):
     """The float64 oracle, as it stands, on a bounded sample: `cores` units, a uniform random
     sample of rows of each.  The full-unit time is estimated as sketch time + row time * n/rows
@@ -176,8 +243,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default=None,
                     help="config1|config2|config3|config5|sweep_n.._r.._b.. (default config3; config2 with --pass bwd)")
-    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd"],
-                    help="fwd: psf_causal_attn_fwd (the headline); bwd: psf_causal_attn_bwd")
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "decode"],
+                    help="fwd: psf_causal_attn_fwd (the headline); bwd: psf_causal_attn_bwd; "
+                         "decode: psf_decode_step at a fixed serving shape")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also issue one 256 MiB device copy, so that a counter run can scale "
@@ -191,6 +259,10 @@ def main():
     from paper_2310_01655_amd import binding as psf
     from paper_2310_01655_amd import inputs
 
+    if args.which == "decode":
+        assert torch.cuda.is_available(), "bench.py needs a GPU"
+        run_decode(args, psf, inputs, torch)
+        return
     wl = workloads()
     if args.workload is None:
         args.workload = "config3" if args.which == "fwd" else "config2"

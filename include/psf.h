@@ -150,6 +150,27 @@ psf_status psf_causal_attn_bwd_timed(const psf_desc *desc, const void *Q, const 
                                      void *hip_stream, float *stage_ms, int32_t n_stages,
                                      int32_t *n_written);
 
+/*
+ * Token-by-token evaluation (the recurrent form behind the paper's remark, Section 5, that the
+ * state kept for generation does not grow with the context).  psf_decode_step consumes q, k, v
+ * of position `pos` ([batch, heads, 1, d | dv], device, desc->dtype) and writes row `pos` of
+ * psf_causal_attn_fwd's output for the sequence fed so far ([batch, heads, 1, dv]): the prefix
+ * state Z_l of Section 3.1 over the completed blocks plus the weights of Section 3.2 (or 3.1)
+ * inside the current block of desc->b tokens, whose keys are folded into the state when the
+ * block completes.  desc->n is the longest context (pos < n); positions must be fed in order
+ * 0, 1, 2, ... after psf_decode_reset.
+ *   state: device memory of psf_decode_state_bytes(desc) bytes, 256-byte aligned, owned by the
+ *   caller: per unit the r^2 x (dv+1) fp32 state and the current block's keys, values and
+ *   sketches; its size does not depend on n.
+ * PSF_FEAT_SKETCH only (PSF_FEAT_EXACT returns PSF_ERR_UNSUPPORTED).  Nothing is allocated and
+ * nothing synchronises; everything is enqueued on hip_stream.
+ */
+size_t psf_decode_state_bytes(const psf_desc *desc);
+psf_status psf_decode_reset(const psf_desc *desc, void *state, size_t state_bytes, void *hip_stream);
+psf_status psf_decode_step(const psf_desc *desc, const void *q, const void *k, const void *v,
+                           const void *G, int32_t pos, void *state, size_t state_bytes, void *o,
+                           void *hip_stream);
+
 const char *psf_status_string(psf_status status);
 
 #ifdef __cplusplus

@@ -20,7 +20,8 @@ LOCAL_EXACT, LOCAL_SKETCH = 0, 1
 EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_len", "psf_sketch",
            "psf_causal_attn_fwd", "psf_causal_attn_fwd_timed", "psf_stage_name",
            "psf_status_string", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
-           "psf_causal_attn_bwd_timed")
+           "psf_causal_attn_bwd_timed", "psf_decode_state_bytes", "psf_decode_reset",
+           "psf_decode_step")
 
 
 class PsfDesc(ctypes.Structure):
@@ -74,6 +75,12 @@ def lib():
                                                                   ctypes.POINTER(ctypes.c_float),
                                                                   ctypes.c_int32,
                                                                   ctypes.POINTER(ctypes.c_int32)]
+        L.psf_decode_state_bytes.restype = ctypes.c_size_t
+        L.psf_decode_state_bytes.argtypes = [dp]
+        L.psf_decode_reset.restype = ctypes.c_int
+        L.psf_decode_reset.argtypes = [dp, vp, ctypes.c_size_t, vp]
+        L.psf_decode_step.restype = ctypes.c_int
+        L.psf_decode_step.argtypes = [dp, vp, vp, vp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp, vp]
         L.psf_stage_name.restype = ctypes.c_char_p
         L.psf_stage_name.argtypes = [ctypes.c_int, ctypes.c_int32]
         L.psf_status_string.restype = ctypes.c_char_p
@@ -263,3 +270,36 @@ def psf_causal_attn_bwd_timed(desc, Q, K, V, G, dO, workspace=None, stream=None)
         raise PsfError(st, "psf_causal_attn_bwd_timed")
     names = [lib().psf_stage_name(2, i).decode() for i in range(written.value)]
     return grads, {nm: float(ms[i]) for i, nm in enumerate(names)}
+
+
+def decode_state_bytes(desc):
+    return lib().psf_decode_state_bytes(ctypes.byref(desc))
+
+
+def decode_new_state(desc, device="cuda", stream=None):
+    """Allocate (torch) and reset the state of token-by-token evaluation."""
+    nbytes = decode_state_bytes(desc)
+    if nbytes == 0:
+        raise PsfError(lib().psf_check_desc(ctypes.byref(desc)) or 3, "psf_decode_state_bytes")
+    state = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    st = lib().psf_decode_reset(ctypes.byref(desc), ctypes.c_void_p(state.data_ptr()),
+                                ctypes.c_size_t(state.numel()), _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_decode_reset")
+    return state
+
+
+def psf_decode_step(desc, q, k, v, G, pos, state, o=None, stream=None):
+    """Row `pos` of the attention for the sequence fed so far; q, k, v are [batch, heads, 1, d|dv]."""
+    B, H, d, dv = desc.batch, desc.heads, desc.d, desc.dv
+    if o is None:
+        o = torch.empty(B, H, 1, dv, dtype=q.dtype, device=q.device)
+    gs = _g_shape(desc)
+    st = lib().psf_decode_step(
+        ctypes.byref(desc), _dev_ptr(q, desc, (B, H, 1, d), "q"), _dev_ptr(k, desc, (B, H, 1, d), "k"),
+        _dev_ptr(v, desc, (B, H, 1, dv), "v"), _dev_ptr(G, desc, gs, "G") if gs else None, int(pos),
+        ctypes.c_void_p(state.data_ptr()), ctypes.c_size_t(state.numel()),
+        _dev_ptr(o, desc, (B, H, 1, dv), "o"), _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_decode_step")
+    return o

@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpsf.so")
-SOURCES = ["psf_api.hip", "psf_general.hip", "psf_backward.hip", "psf_mfma.hip"]
+SOURCES = ["psf_api.hip", "psf_general.hip", "psf_backward.hip", "psf_decode.hip", "psf_mfma.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed fp32 VALU forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

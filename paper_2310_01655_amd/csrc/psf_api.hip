@@ -237,6 +237,44 @@ psf_status psf_causal_attn_bwd_timed(const psf_desc *desc, const void *Q, const 
     return st != PSF_OK ? st : st2;
 }
 
+size_t psf_decode_state_bytes(const psf_desc *desc)
+{
+    Problem pb;
+    if (make_problem(desc, &pb) != PSF_OK || !decode_supported(pb)) return 0;
+    return decode_state_bytes(pb);
+}
+
+static psf_status decode_check(const psf_desc *desc, Problem *pb, const void *state, size_t state_bytes)
+{
+    psf_status st = make_problem(desc, pb);
+    if (st != PSF_OK) return st;
+    if (!decode_supported(*pb)) return PSF_ERR_UNSUPPORTED;
+    if (!state) return PSF_ERR_NULL;
+    if (state_bytes < decode_state_bytes(*pb) || ((uintptr_t)state & 255u) != 0) return PSF_ERR_WORKSPACE;
+    return PSF_OK;
+}
+
+psf_status psf_decode_reset(const psf_desc *desc, void *state, size_t state_bytes, void *hip_stream)
+{
+    Problem pb;
+    psf_status st = decode_check(desc, &pb, state, state_bytes);
+    if (st != PSF_OK) return st;
+    return decode_reset(pb, state, (hipStream_t)hip_stream);
+}
+
+psf_status psf_decode_step(const psf_desc *desc, const void *q, const void *k, const void *v,
+                           const void *G, int32_t pos, void *state, size_t state_bytes, void *o,
+                           void *hip_stream)
+{
+    Problem pb;
+    psf_status st = decode_check(desc, &pb, state, state_bytes);
+    if (st != PSF_OK) return st;
+    if (!q || !k || !v || !o) return PSF_ERR_NULL;
+    if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
+    if (pos < 0 || pos >= pb.n) return PSF_ERR_SHAPE;
+    return decode_step(pb, q, k, v, G, pos, state, o, (hipStream_t)hip_stream);
+}
+
 const char *psf_stage_name(int path, int32_t stage)
 {
     static const char *bwd[] = {"sketches", "forward_rows", "reverse_states", "query_side",

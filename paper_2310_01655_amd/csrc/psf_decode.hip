@@ -1,0 +1,317 @@
+// Token-by-token evaluation of causal Polysketch attention (PolySketchFormer, arXiv 2310.01655):
+// the recurrent form the paper points to when it notes that the state kept for generation does
+// not grow with the context (Section 5).  One step consumes the (q, k, v) of position `pos` and
+// returns row `pos` of the attention of Section 3, identical to what the block algorithm of
+// Sections 3.1 / 3.2 with block size b returns for the sequence so far:
+//   o = (phi'(q)^T Z + sum_{j in current block, j <= pos} w_j [v_j | 1]) -> N / (1 + S)
+// where Z = sum over the *completed* blocks of phi'(k_j) [v_j | 1]^T is the prefix state Z_l of
+// Section 3.1 and w_j = <q, k_j>^p (Section 3.2) or <m(q), m(k_j)>^2 (Section 3.1) inside the
+// current block.  When a block completes, its keys are folded into Z.
+//
+// State per (batch, head) unit, all fp32, caller-owned:
+//   ZV [F][dv] and ZD [F]: the value columns and the "ones" column of Z (F = mcols^2 features),
+//   kept apart so that rows of ZV are aligned and a step streams them with full-width loads;
+//   then the current block's cache: CK [b][d] keys, CV [b][dv] values, CM [b][mcols] sketches
+//   m(k).  After the units come the scratch areas: m(q), m(k) of the new token [units][mcols]
+//   each and the partial sums of the state product [units][kSlices][dv + 1].
+// A step is bound by reading Z once (F * (dv + 1) * 4 bytes per unit) from HBM.
+#include "psf_internal.h"
+
+namespace psf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kSlices = 16;        // workgroups per unit in the state product
+
+struct DecodeLayout {
+    size_t zv, zd, ck, cv, cm, per_unit;     // float offsets inside one unit, floats per unit
+    size_t mq, mk, part, total;              // float offsets of the scratch areas, total floats
+};
+
+DecodeLayout decode_layout(const Problem &pb)
+{
+    DecodeLayout L;
+    auto up = [](size_t v) { return (v + 63) / 64 * 64; };            // 256-byte pieces
+    L.zv = 0;
+    L.zd = up((size_t)pb.F * pb.dv);
+    L.ck = L.zd + up((size_t)pb.F);
+    L.cv = L.ck + up((size_t)pb.b * pb.d);
+    L.cm = L.cv + up((size_t)pb.b * pb.dv);
+    L.per_unit = L.cm + up((size_t)pb.b * pb.mcols);
+    L.mq = L.per_unit * pb.units;
+    L.mk = L.mq + up((size_t)pb.units * pb.mcols);
+    L.part = L.mk + up((size_t)pb.units * pb.mcols);
+    L.total = L.part + up((size_t)pb.units * kSlices * (pb.dv + 1));
+    return L;
+}
+
+__device__ __forceinline__ int pow2_at_least(int v, int lo, int hi)
+{
+    int p = lo;
+    while (p < v && p < hi) p *= 2;
+    return p;
+}
+
+__global__ __launch_bounds__(kThreads) void dec_zero_kernel(float *__restrict__ p, size_t count)
+{
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += (size_t)gridDim.x * kThreads)
+        p[i] = 0.f;
+}
+
+// cache slot of the new token: key, value, m(k)
+template <typename T>
+__global__ __launch_bounds__(kThreads) void dec_append_kernel(const T *__restrict__ k, const T *__restrict__ v,
+                                                              const float *__restrict__ mk_new,
+                                                              float *__restrict__ state, DecodeLayout L,
+                                                              int d, int dv, int mcols, int slot)
+{
+    const int u = blockIdx.x, tid = threadIdx.x;
+    float *su = state + (size_t)u * L.per_unit;
+    for (int e = tid; e < d; e += kThreads) su[L.ck + (size_t)slot * d + e] = load_f(k, (size_t)u * d + e);
+    for (int c = tid; c < dv; c += kThreads) su[L.cv + (size_t)slot * dv + c] = load_f(v, (size_t)u * dv + c);
+    for (int e = tid; e < mcols; e += kThreads) su[L.cm + (size_t)slot * mcols + e] = mk_new[(size_t)u * mcols + e];
+}
+
+// part[u][s][c] = sum over the features f of slice s of phi'(q)[f] ZV[f][c] (c < dv) and, at
+// c = dv, of phi'(q)[f] ZD[f].  phi'(q) of the slice sits in LDS; thread (c, g) walks the rows
+// g, g + groups, ... four at a time, so a wave reads whole contiguous rows of ZV.
+__global__ __launch_bounds__(kThreads) void dec_state_kernel(const float *__restrict__ state,
+                                                             const float *__restrict__ mq_new,
+                                                             float *__restrict__ part, DecodeLayout L,
+                                                             int dv, int mcols, long long F)
+{
+    constexpr int kMaxPer = 4096;                          // F / kSlices <= 65536 / 16
+    __shared__ float mq[PSF_MAX_DIM], phi[kMaxPer], red[kThreads];
+    const int u = blockIdx.y, sl = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
+    for (int e = tid; e < mcols; e += kThreads) mq[e] = mq_new[(size_t)u * mcols + e];
+    __syncthreads();
+    const long long per = (F + kSlices - 1) / kSlices;
+    const long long f_beg = sl * per;
+    const int nf = (int)max(0LL, min(F, f_beg + per) - f_beg);
+    for (int ff = tid; ff < nf; ff += kThreads) {
+        const long long f = f_beg + ff;
+        phi[ff] = mq[f / mcols] * mq[f % mcols];
+    }
+    __syncthreads();
+    const float *zv = state + (size_t)u * L.per_unit + L.zv + (size_t)f_beg * dv;
+    const float *zd = state + (size_t)u * L.per_unit + L.zd + f_beg;
+    const int dvp = pow2_at_least(dv, 32, kThreads), groups = kThreads / dvp;
+    float *out = part + ((size_t)u * kSlices + sl) * kc;
+    for (int c0 = 0; c0 < dv; c0 += dvp) {
+        const int c = c0 + tid % dvp, g = tid / dvp;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        if (c < dv) {
+            int ff = g;
+            for (; ff + 3 * groups < nf; ff += 4 * groups) {
+                a0 += phi[ff] * zv[(size_t)ff * dv + c];
+                a1 += phi[ff + groups] * zv[(size_t)(ff + groups) * dv + c];
+                a2 += phi[ff + 2 * groups] * zv[(size_t)(ff + 2 * groups) * dv + c];
+                a3 += phi[ff + 3 * groups] * zv[(size_t)(ff + 3 * groups) * dv + c];
+            }
+            for (; ff < nf; ff += groups) a0 += phi[ff] * zv[(size_t)ff * dv + c];
+        }
+        __syncthreads();
+        red[tid] = (a0 + a1) + (a2 + a3);
+        __syncthreads();
+        if (tid < dvp && c0 + tid < dv) {
+            float sacc = 0.f;
+            for (int q = 0; q < groups; ++q) sacc += red[q * dvp + tid];
+            out[c0 + tid] = sacc;
+        }
+    }
+    // the "ones" column
+    float a = 0.f;
+    for (int ff = tid; ff < nf; ff += kThreads) a += phi[ff] * zd[ff];
+    __syncthreads();
+    red[tid] = a;
+    __syncthreads();
+    if (tid == 0) {
+        float sacc = 0.f;
+        for (int q = 0; q < kThreads; ++q) sacc += red[q];
+        out[dv] = sacc;
+    }
+}
+
+// row = sum of the slices + the in-block term over the cache slots 0 .. slot, then N / (1 + S)
+template <typename T>
+__global__ __launch_bounds__(kThreads) void dec_finish_kernel(const T *__restrict__ q,
+                                                              const float *__restrict__ state,
+                                                              const float *__restrict__ mq_new,
+                                                              const float *__restrict__ part,
+                                                              T *__restrict__ o, DecodeLayout L, int d,
+                                                              int dv, int p, int mcols, int slot,
+                                                              int have_state, int local_exact)
+{
+    __shared__ float qs[PSF_MAX_DIM], w[kThreads], row[PSF_MAX_DIM + 1], red[kThreads];
+    const int u = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
+    const float *su = state + (size_t)u * L.per_unit;
+    const int wa = local_exact ? d : mcols;
+    for (int e = tid; e < wa; e += kThreads)
+        qs[e] = local_exact ? load_f(q, (size_t)u * d + e) : mq_new[(size_t)u * mcols + e];
+    for (int c = tid; c < kc; c += kThreads) {
+        float a = 0.f;
+        if (have_state)
+            for (int s = 0; s < kSlices; ++s) a += part[((size_t)u * kSlices + s) * kc + c];
+        row[c] = a;
+    }
+    __syncthreads();
+    const float *keys = su + (local_exact ? L.ck : L.cm);
+    const int dvp = pow2_at_least(dv, 32, kThreads), groups = kThreads / dvp;
+    for (int j0 = 0; j0 <= slot; j0 += kThreads) {
+        const int nj = min(kThreads, slot + 1 - j0);
+        __syncthreads();
+        float wv = 0.f;
+        if (tid < nj) {
+            const float *kr = keys + (size_t)(j0 + tid) * wa;
+            float sdot = 0.f;
+            for (int e = 0; e < wa; ++e) sdot += qs[e] * kr[e];
+            wv = sdot * sdot;
+            if (local_exact) {
+                wv = 1.f;
+                for (int e = 0; e < p; ++e) wv *= sdot;
+            }
+        }
+        w[tid] = wv;
+        __syncthreads();
+        for (int c0 = 0; c0 < dv; c0 += dvp) {            // values: thread (c, g) takes slots g, g + groups, ...
+            const int c = c0 + tid % dvp, g = tid / dvp;
+            float a = 0.f;
+            if (c < dv)
+                for (int jj = g; jj < nj; jj += groups) a += w[jj] * su[L.cv + (size_t)(j0 + jj) * dv + c];
+            __syncthreads();
+            red[tid] = a;
+            __syncthreads();
+            if (tid < dvp && c0 + tid < dv) {
+                float sacc = 0.f;
+                for (int q2 = 0; q2 < groups; ++q2) sacc += red[q2 * dvp + tid];
+                row[c0 + tid] += sacc;
+            }
+        }
+        if (tid == 0) {                                   // the "ones" column: sum of the weights
+            float sacc = 0.f;
+            for (int jj = 0; jj < nj; ++jj) sacc += w[jj];
+            row[dv] += sacc;
+        }
+    }
+    __syncthreads();
+    const float den = 1.f + row[dv];
+    for (int c = tid; c < dv; c += kThreads) store_f(o, (size_t)u * dv + c, row[c] / den);
+}
+
+// ZV[f][c] += sum over the b cached tokens of phi'(k_j)[f] v_j[c], ZD[f] += sum_j phi'(k_j)[f].
+// Workgroup = kFoldFeat features; thread (c, g) owns the PER = kFoldFeat / groups features
+// g * PER .. of column c (groups = 256 / columns per pass).
+constexpr int kFoldFeat = 64, kFoldTok = 32;
+template <int PER>
+__global__ __launch_bounds__(kThreads) void dec_fold_kernel(float *__restrict__ state, DecodeLayout L,
+                                                            int dv, int b, int mcols, long long F)
+{
+    __shared__ float phi[kFoldTok][kFoldFeat + 1], vt[kFoldTok][PSF_MAX_DIM];
+    constexpr int groups = kFoldFeat / PER, dvp = kThreads / groups;
+    const int tid = threadIdx.x, u = blockIdx.y;
+    const long long f0 = (long long)blockIdx.x * kFoldFeat;
+    float *su = state + (size_t)u * L.per_unit;
+    for (int c0 = 0; c0 < dv; c0 += dvp) {
+        const int c = c0 + tid % dvp, g = tid / dvp;
+        float acc[PER];
+#pragma unroll
+        for (int ff = 0; ff < PER; ++ff) acc[ff] = 0.f;
+        float dacc = 0.f;                                 // ZD: thread tid < kFoldFeat owns feature tid
+        for (int j0 = 0; j0 < b; j0 += kFoldTok) {
+            const int lim = min(kFoldTok, b - j0);
+            __syncthreads();
+            for (int idx = tid; idx < kFoldTok * kFoldFeat; idx += kThreads) {
+                const int jj = idx / kFoldFeat, ff = idx % kFoldFeat;
+                float v = 0.f;
+                if (jj < lim && f0 + ff < F) {
+                    const float *m = su + L.cm + (size_t)(j0 + jj) * mcols;
+                    const long long f = f0 + ff;
+                    v = m[f / mcols] * m[f % mcols];
+                }
+                phi[jj][ff] = v;
+            }
+            for (int idx = tid; idx < kFoldTok * dv; idx += kThreads) {
+                const int jj = idx / dv, cc = idx % dv;
+                vt[jj][cc] = jj < lim ? su[L.cv + (size_t)(j0 + jj) * dv + cc] : 0.f;
+            }
+            __syncthreads();
+            if (c < dv)
+                for (int jj = 0; jj < kFoldTok; ++jj) {
+                    const float vv = vt[jj][c];
+#pragma unroll
+                    for (int ff = 0; ff < PER; ++ff) acc[ff] += phi[jj][g * PER + ff] * vv;
+                }
+            if (c0 == 0 && tid < kFoldFeat)
+                for (int jj = 0; jj < kFoldTok; ++jj) dacc += phi[jj][tid];
+        }
+        if (c < dv) {
+#pragma unroll
+            for (int ff = 0; ff < PER; ++ff)
+                if (f0 + g * PER + ff < F) su[L.zv + (size_t)(f0 + g * PER + ff) * dv + c] += acc[ff];
+        }
+        if (c0 == 0 && tid < kFoldFeat && f0 + tid < F) su[L.zd + f0 + tid] += dacc;
+    }
+}
+
+template <typename T>
+psf_status step_launch(const Problem &pb, const void *q, const void *k, const void *v, const void *G, int pos,
+                       float *state, void *o, hipStream_t s)
+{
+    const DecodeLayout L = decode_layout(pb);
+    const int slot = pos % pb.b, le = pb.local_exact ? 1 : 0;
+    // sketches of the new token: the general sketch kernel on [units, 1, d]
+    Problem one = pb;
+    one.n = 1;
+    psf_status st = general_sketch_f32(one, q, G, state + L.mq, s);
+    if (st != PSF_OK) return st;
+    st = general_sketch_f32(one, k, G, state + L.mk, s);
+    if (st != PSF_OK) return st;
+    hipLaunchKernelGGL(dec_append_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)k,
+                       (const T *)v, state + L.mk, state, L, pb.d, pb.dv, pb.mcols, slot);
+    PSF_LAUNCH_CHECK();
+    const int have_state = pos >= pb.b ? 1 : 0;          // Z is zero during the first block
+    if (have_state) {
+        hipLaunchKernelGGL(dec_state_kernel, dim3(kSlices, (unsigned)pb.units), dim3(kThreads), 0, s, state,
+                           state + L.mq, state + L.part, L, pb.dv, pb.mcols, pb.F);
+        PSF_LAUNCH_CHECK();
+    }
+    hipLaunchKernelGGL(dec_finish_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q, state,
+                       state + L.mq, state + L.part, (T *)o, L, pb.d, pb.dv, pb.p, pb.mcols, slot, have_state, le);
+    PSF_LAUNCH_CHECK();
+    if (slot == pb.b - 1) {                               // the block is complete: fold it into Z
+        const dim3 fgrid((unsigned)((pb.F + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
+        if (pb.dv <= 32)
+            hipLaunchKernelGGL(dec_fold_kernel<8>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+        else if (pb.dv <= 64)
+            hipLaunchKernelGGL(dec_fold_kernel<16>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+        else if (pb.dv <= 128)
+            hipLaunchKernelGGL(dec_fold_kernel<32>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+        else
+            hipLaunchKernelGGL(dec_fold_kernel<64>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+        PSF_LAUNCH_CHECK();
+    }
+    return PSF_OK;
+}
+
+}  // namespace
+
+bool decode_supported(const Problem &pb) { return !pb.exact_feat; }
+
+size_t decode_state_bytes(const Problem &pb) { return decode_layout(pb).total * sizeof(float); }
+
+psf_status decode_reset(const Problem &pb, void *state, hipStream_t s)
+{
+    const size_t count = decode_layout(pb).total;
+    hipLaunchKernelGGL(dec_zero_kernel, dim3(2048), dim3(kThreads), 0, s, (float *)state, count);
+    PSF_LAUNCH_CHECK();
+    return PSF_OK;
+}
+
+psf_status decode_step(const Problem &pb, const void *q, const void *k, const void *v, const void *G, int pos,
+                       void *state, void *o, hipStream_t s)
+{
+    return pb.bf16 ? step_launch<bf16_t>(pb, q, k, v, G, pos, (float *)state, o, s)
+                   : step_launch<float>(pb, q, k, v, G, pos, (float *)state, o, s);
+}
+
+}  // namespace psf

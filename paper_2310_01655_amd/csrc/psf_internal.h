@@ -55,6 +55,13 @@ psf_status general_attn_bwd(const Problem &pb, const void *Q, const void *K, con
                             const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
                             hipStream_t s, StageTimer *tm);
 
+// Token-by-token evaluation (fp32 kernels; sketch features only).
+bool decode_supported(const Problem &pb);
+size_t decode_state_bytes(const Problem &pb);
+psf_status decode_reset(const Problem &pb, void *state, hipStream_t s);
+psf_status decode_step(const Problem &pb, const void *q, const void *k, const void *v, const void *G,
+                       int pos, void *state, void *o, hipStream_t s);
+
 // bf16 MFMA path.
 size_t mfma_workspace_bytes(const Problem &pb);
 psf_status mfma_sketch(const Problem &pb, const void *X, const void *G, void *M_out,

@@ -103,6 +103,34 @@ def test_backward_entry_point_validates_on_the_host():
     assert psf.lib().psf_stage_name(2, 5) == b"sketch_gradient"
 
 
+def test_decode_entry_points_validate_on_the_host():
+    L = psf.lib()
+    d = psf.make_desc(2, 3, 4096, 64, 4, 32, 256, "bf16")
+    ref = ctypes.byref(d)
+    one = ctypes.c_void_p(256)   # never dereferenced: every call below fails validation first
+    need = psf.decode_state_bytes(d)
+    # per unit: r^2 x (dv + 1) fp32 state and the block cache (keys, values, sketches); no n in it
+    assert need >= 6 * (1024 * 65 + 256 * (64 + 64 + 32)) * 4
+    d2 = psf.make_desc(2, 3, 65536, 64, 4, 32, 256, "bf16")
+    assert psf.decode_state_bytes(d2) == need
+    assert L.psf_decode_reset(ref, None, need, None) == 1
+    assert L.psf_decode_reset(ref, one, need - 1, None) == 4
+    assert L.psf_decode_reset(ref, ctypes.c_void_p(264), need, None) == 4
+    args = [one, one, one, one]
+    for hole in (0, 1, 2, 3):
+        a = list(args)
+        a[hole] = None
+        assert L.psf_decode_step(ref, *a, 0, one, need, one, None) == 1, hole
+    assert L.psf_decode_step(ref, *args, 0, one, need, None, None) == 1
+    assert L.psf_decode_step(ref, *args, 0, None, need, one, None) == 1
+    assert L.psf_decode_step(ref, *args, -1, one, need, one, None) == 2
+    assert L.psf_decode_step(ref, *args, 4096, one, need, one, None) == 2
+    assert L.psf_decode_step(ref, *args, 0, one, need - 1, one, None) == 4
+    exact = psf.make_desc(1, 1, 64, 8, 4, 1, 8, "f32", feat=psf.FEAT_EXACT)
+    assert psf.decode_state_bytes(exact) == 0
+    assert L.psf_decode_step(ctypes.byref(exact), *args, 0, one, 1 << 40, one, None) == 3
+
+
 def test_status_strings_and_stage_names():
     assert psf.status_string(0) == "ok"
     assert all(psf.status_string(c) for c in range(6))

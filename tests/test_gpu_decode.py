@@ -1,0 +1,81 @@
+"""GPU parity of token-by-token evaluation (psf_decode_step through the C ABI): feeding a
+sequence one position at a time must reproduce, row by row, the float64 oracle's rows of the
+full causal attention with the same block size (tolerance 1e-4 fp32 / 2e-2 bf16 storage)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2310_01655_amd import binding as psf
+from paper_2310_01655_amd import inputs
+from parity import as_f64, assert_close
+
+pytestmark = pytest.mark.gpu
+
+
+def decode_all(batch, heads, n, d, dv, p, r, b, dtype, local=psf.LOCAL_EXACT, per_head=True, seed=51, steps=None):
+    q, k, v = inputs.make_qkv(batch, heads, n, d, dv=dv, seed=seed, dtype=dtype)
+    G = inputs.make_sketch_matrices(heads, d, r, p, per_head=per_head, seed=0, dtype=dtype) if p > 2 else None
+    desc = psf.make_desc(batch, heads, n, d, p, r, b, dtype, dv=dv, local=local, per_head=per_head)
+    dev = torch.device("cuda:0")
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    Gd = G.to(dev) if G is not None else None
+    state = psf.decode_new_state(desc, dev)
+    steps = n if steps is None else steps
+    out = torch.empty(batch, heads, steps, dv, dtype=q.dtype, device=dev)
+    for pos in range(steps):
+        o = psf.psf_decode_step(desc, qd[:, :, pos:pos + 1].contiguous(), kd[:, :, pos:pos + 1].contiguous(),
+                                vd[:, :, pos:pos + 1].contiguous(), Gd, pos, state)
+        out[:, :, pos] = o[:, :, 0]
+    torch.cuda.synchronize()
+    want, _ = oracle.attn_def_batch(as_f64(q), as_f64(k), as_f64(v), as_f64(G) if G is not None else None,
+                                    p, r, b, local=oracle.LOCAL_EXACT if local == psf.LOCAL_EXACT else oracle.LOCAL_SKETCH,
+                                    rows=list(range(steps)))
+    res = assert_close(out.float().cpu().numpy(), want, dtype, "decode n=%d d=%d p=%d r=%d b=%d" % (n, d, p, r, b))
+    print((n, d, dv, p, r, b, dtype), res)
+    return out
+
+
+@pytest.mark.parametrize("n,d,dv,p,r,b", [
+    (192, 32, 32, 4, 16, 64),      # three blocks: two folds
+    (96, 24, 40, 4, 12, 32),       # dv != d, sizes that are no powers of two
+    (64, 16, 16, 2, 8, 16),        # p = 2: m(x) = x
+    (64, 16, 16, 8, 8, 16),        # one inner level
+    (48, 16, 16, 4, 8, 1),         # every token its own block: pure recurrence
+    (64, 32, 32, 4, 16, 64),       # single block: only the cache is used
+])
+def test_decode_fp32_matches_forward_rows(n, d, dv, p, r, b):
+    decode_all(1, 2, n, d, dv, p, r, b, "f32")
+
+
+def test_decode_sketched_local_weights():
+    decode_all(2, 2, 96, 32, 32, 4, 16, 32, "f32", local=psf.LOCAL_SKETCH)
+
+
+def test_decode_bf16_storage_headline_shape_per_unit():
+    # d = 64, r = 64, b = 256: the per-unit state of the headline configuration, shorter context
+    decode_all(1, 3, 768, 64, 64, 4, 64, 256, "bf16")
+
+
+def test_decode_equals_the_forward_entry_point():
+    batch, heads, n, d, p, r, b = 1, 2, 128, 32, 4, 16, 32
+    out = decode_all(batch, heads, n, d, d, p, r, b, "f32", seed=53)
+    q, k, v = inputs.make_qkv(batch, heads, n, d, seed=53, dtype="f32")
+    G = inputs.make_sketch_matrices(heads, d, r, p, per_head=True, seed=0, dtype="f32")
+    desc = psf.make_desc(batch, heads, n, d, p, r, b, "f32", per_head=True)
+    O = psf.psf_causal_attn_fwd(desc, q.cuda(), k.cuda(), v.cuda(), G.cuda())
+    torch.cuda.synchronize()
+    assert (out - O).abs().max().item() <= 2e-5
+
+
+def test_decode_rejects_bad_positions_and_exact_features():
+    desc = psf.make_desc(1, 1, 64, 8, 4, 4, 16, "f32")
+    state = psf.decode_new_state(desc)
+    x = torch.zeros(1, 1, 1, 8, device="cuda")
+    G = torch.zeros(1, psf.g_len(8, 4, 4), device="cuda")
+    for pos in (-1, 64):
+        with pytest.raises(psf.PsfError) as e:
+            psf.psf_decode_step(desc, x, x, x, G, pos, state)
+        assert e.value.code == 2
+    exact = psf.make_desc(1, 1, 64, 4, 4, 4, 16, "f32", feat=psf.FEAT_EXACT)
+    assert psf.decode_state_bytes(exact) == 0
