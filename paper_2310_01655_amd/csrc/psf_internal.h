@@ -64,8 +64,6 @@ psf_status decode_step(const Problem &pb, const void *q, const void *k, const vo
 
 // bf16 MFMA path.
 size_t mfma_workspace_bytes(const Problem &pb);
-psf_status mfma_sketch(const Problem &pb, const void *X, const void *G, void *M_out,
-                       void *Phi_out, hipStream_t s);
 psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void *V,
                      const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);
 

@@ -682,7 +682,7 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
 // the in-block phase; the m_i[a] * T_a updates in the cross-block phase).
 // ------------------------------------------------------------------------------------
 template <int R, int D, int P, int TT>
-__global__ __launch_bounds__(kWg, TT >= 4 ? 1 : 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+__global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                 const bf16_t *__restrict__ V8,
                                                 const bf16_t *__restrict__ MQ,
                                                 const bf16_t *__restrict__ Zg,
@@ -1220,13 +1220,6 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
 }  // namespace
 
 size_t mfma_workspace_bytes(const Problem &pb) { return carve(pb, nullptr).total; }
-
-// psf_sketch on the MFMA path: needs scratch for the transposed sketch matrices, which the
-// entry point does not have, so the general kernel serves it.
-psf_status mfma_sketch(const Problem &, const void *, const void *, void *, void *, hipStream_t)
-{
-    return PSF_ERR_UNSUPPORTED;
-}
 
 #define PSF_DISPATCH(CALL)                                                   \
     do {                                                                     \

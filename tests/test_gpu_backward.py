@@ -63,6 +63,12 @@ def test_backward_bf16_storage(n, d, p, r, b):
     run_case(1, 2, n, d, d, p, r, b, "bf16", per_head=True)
 
 
+def test_backward_largest_admitted_dimensions():
+    # d = dv = r = 256 (r^2 = 65536 features): the run-time LDS carving beyond 64 KB per workgroup
+    run_case(1, 1, 32, 256, 256, 4, 256, 16, "f32")
+    run_case(1, 1, 64, 256, 256, 4, 64, 32, "f32", local=psf.LOCAL_SKETCH)
+
+
 def test_backward_heavy_tailed_inputs():
     run_case(1, 2, 256, 64, 64, 4, 32, 64, "f32", dist="student_t3")
 

@@ -48,6 +48,10 @@ def test_decode_fp32_matches_forward_rows(n, d, dv, p, r, b):
     decode_all(1, 2, n, d, dv, p, r, b, "f32")
 
 
+def test_decode_largest_admitted_dimensions():
+    decode_all(1, 1, 32, 256, 256, 4, 256, 16, "f32", per_head=False)
+
+
 def test_decode_sketched_local_weights():
     decode_all(2, 2, 96, 32, 32, 4, 16, 32, "f32", local=psf.LOCAL_SKETCH)
 

@@ -126,3 +126,12 @@ def test_timed_entry_point_reports_stages():
     assert list(stages) == ["sketch_q", "sketch_k", "block_states", "exclusive_scan", "output"]
     assert all(ms >= 0 for ms in stages.values())
     assert_close(got.numpy(), oracle_attn(cfg, q, k, v, G), "f32", "timed")
+
+
+def test_largest_admitted_dimensions():
+    # d = dv = r = 256: every per-token array at its stated maximum (r^2 = 65536 features)
+    cfg = dict(batch=1, heads=1, n=32, d=256, p=4, r=256, b=16, dtype="f32", per_head=False, dist="normal")
+    q, k, v = inputs.make_qkv(1, 1, 32, 256, seed=3, dtype="f32")
+    G = inputs.make_sketch_matrices(1, 256, 256, 4, seed=0, dtype="f32")
+    got, _ = gpu_attn(cfg, q, k, v, G)
+    assert_close(got.numpy(), oracle_attn(cfg, q, k, v, G), "f32", "d = dv = r = 256")
