@@ -52,6 +52,10 @@ def lib():
         L.psf_oracle_attn_def_batch.argtypes = ([_dp] * 4 + [ctypes.c_long] * 9
                                                 + [ctypes.c_int] * 2
                                                 + [_lp, ctypes.c_long, _dp, ctypes.c_int])
+        L.psf_oracle_learned_len.restype = ctypes.c_long
+        L.psf_oracle_learned_len.argtypes = [ctypes.c_long] * 3
+        L.psf_oracle_sketch_learned.restype = ctypes.c_int
+        L.psf_oracle_sketch_learned.argtypes = [_dp] + [ctypes.c_long] * 4 + [_dp, _dp]
         L.psf_oracle_sketch_bwd.restype = ctypes.c_int
         L.psf_oracle_sketch_bwd.argtypes = [_dp] + [ctypes.c_long] * 4 + [_dp, _dp, _dp]
         L.psf_oracle_attn_bwd.restype = ctypes.c_int
@@ -112,16 +116,38 @@ def power_tensor(X, p):
     return Phi
 
 
+def learned_len(d, r, p):
+    """Number of parameters of the learned degree-p sketch (Appendix D): p - 2 networks."""
+    return lib().psf_oracle_learned_len(d, r, p)
+
+
+def sketch_learned(X, params, r, p):
+    """m(x) = LearnablePolysketchWithNegativity(x, r, p/2) for every row of X (Algorithm 2)."""
+    X = _f64(X)
+    k, d = X.shape
+    P = _f64(params).reshape(-1) if p > 2 else np.zeros(1)
+    if p > 2 and P.size != learned_len(d, r, p):
+        raise ValueError("params has %d entries, expected %d" % (P.size, learned_len(d, r, p)))
+    M = np.empty((k, d if p == 2 else r))
+    rc = lib().psf_oracle_sketch_learned(_ptr(X), k, d, r, p, _ptr(P), _ptr(M))
+    if rc:
+        raise ValueError("psf_oracle_sketch_learned failed: %d" % rc)
+    return M
+
+
 def attn_def(Q, K, V, G, p, r, b, feat=FEAT_SKETCH, local=LOCAL_EXACT, rows=None,
-             explicit_features=False, return_weights=False):
+             explicit_features=False, return_weights=False, learned=False):
     """Rows of causal Polysketch attention straight from its definition (Section 3,
-    with Section 3.2's exact in-block weights when local == LOCAL_EXACT)."""
+    with Section 3.2's exact in-block weights when local == LOCAL_EXACT).  learned=True: G holds
+    the parameters of the learned sketch (Algorithm 2) instead of Gaussian matrices."""
     Q, K, V = _f64(Q), _f64(K), _f64(V)
     n, d = Q.shape
     dv = V.shape[1]
     MQ = MK = None
     mcols = d if p == 2 else r
-    if feat == FEAT_SKETCH:
+    if feat == FEAT_SKETCH and learned:
+        MQ, MK = sketch_learned(Q, G, r, p), sketch_learned(K, G, r, p)
+    elif feat == FEAT_SKETCH:
         MQ, MK = sketch(Q, G, r, p), sketch(K, G, r, p)
     rows_a = None if rows is None else np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
     nrows = n if rows_a is None else rows_a.size

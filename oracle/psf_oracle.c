@@ -22,6 +22,9 @@
  *                            Section 2.2 (<x,y>^p = <x^{(x)p}, y^{(x)p}>)
  *   psf_oracle_attn_block    Section 3.1 block lower-triangular multiplication
  *                            (H_l, Z_l, P_l, row = p + a_i^T Z_l), Section 3.2 for P_l
+ *   oracle_lpswn,            Algorithm 2 (learnable sketches, Appendix D): the recursion of
+ *   psf_oracle_sketch_learned  Algorithm 1 with each projection M G replaced by a dense network
+ *                            f(M) and sqrt(r) tanh(sqrt(1/r) .) around the Hadamard product
  *   oracle_pswn_bwd,         gradient of the same definition (Section 3 with the weights of
  *   psf_oracle_attn_bwd      Sections 3.1/3.2, sketch of Algorithm 1) with respect to Q, K, V:
  *                            the chain rule written out pair by pair; the paper trains
@@ -115,6 +118,124 @@ int psf_oracle_sketch(const double *X, long k, long d, long r, long p,
     if (!M) return 2;
     long cols = (p == 2) ? d : r;
     memcpy(M_out, M, sizeof(double) * (size_t)k * (size_t)cols);
+    free(M);
+    return 0;
+}
+
+/* ---- Algorithm 2: learnable sketches (Appendix D) -----------------------------------
+ * One network f: R^win -> R^r, applied to every row (the reading of Appendix D taken here):
+ *   u  = LayerNorm(a; g1, b1)                  layer normalisation "before the input"
+ *   h1 = gelu(u W1)          W1: win x 8r      first hidden layer, size 8r
+ *   v  = LayerNorm(h1; g2, b2)                 "and [before] the second hidden layer"
+ *   h2 = v W2                W2: 8r x r        second hidden layer, size r, no activation
+ *   h3 = gelu(h2 W3)         W3: r x 8r        third hidden layer, size 8r
+ *   f  = h3 W4               W4: 8r x r        output, dimension r
+ * Dense layers carry no bias (the appendix counts 8 h r + 24 r^2 parameters per network, which
+ * is exactly the four matrices); layer normalisation has a learnable scale and bias and uses
+ * the biased variance with eps = 1e-6; gelu is the tanh form
+ * 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))).  Parameters of one network are stored as
+ * [g1, b1, W1, g2, b2, W2, W3, W4], matrices row-major (input index first). */
+static long learned_net_len(long win, long r)
+{
+    return 2 * win + win * 8 * r + 2 * 8 * r + 8 * r * r + r * 8 * r + 8 * r * r;
+}
+
+static double gelu_tanh(double x)
+{
+    return 0.5 * x * (1.0 + tanh(0.7978845608028654 * (x + 0.044715 * x * x * x)));
+}
+
+static void layer_norm(const double *x, long m, const double *g, const double *b, double *out)
+{
+    double mean = 0.0, var = 0.0;
+    for (long e = 0; e < m; ++e) mean += x[e];
+    mean /= (double)m;
+    for (long e = 0; e < m; ++e) var += (x[e] - mean) * (x[e] - mean);
+    var /= (double)m;
+    double inv = 1.0 / sqrt(var + 1e-6);
+    for (long e = 0; e < m; ++e) out[e] = (x[e] - mean) * inv * g[e] + b[e];
+}
+
+static double *oracle_learned_net(const double *A, long k, long win, long r, const double **params)
+{
+    const double *g1 = *params, *b1 = g1 + win, *W1 = b1 + win;
+    const double *g2 = W1 + win * 8 * r, *b2 = g2 + 8 * r, *W2 = b2 + 8 * r;
+    const double *W3 = W2 + 8 * r * r, *W4 = W3 + r * 8 * r;
+    *params = W4 + 8 * r * r;
+    long hid = 8 * r;
+    double *out = (double *)malloc(sizeof(double) * (size_t)k * (size_t)r);
+    double *u = (double *)malloc(sizeof(double) * (size_t)(win > hid ? win : hid));
+    double *h = (double *)malloc(sizeof(double) * (size_t)hid);
+    double *h2 = (double *)malloc(sizeof(double) * (size_t)r);
+    if (!out || !u || !h || !h2) { free(out); free(u); free(h); free(h2); return NULL; }
+    for (long i = 0; i < k; ++i) {
+        layer_norm(A + i * win, win, g1, b1, u);
+        for (long c = 0; c < hid; ++c) {
+            double s = 0.0;
+            for (long e = 0; e < win; ++e) s += u[e] * W1[e * hid + c];
+            h[c] = gelu_tanh(s);
+        }
+        layer_norm(h, hid, g2, b2, u);
+        for (long c = 0; c < r; ++c) {
+            double s = 0.0;
+            for (long e = 0; e < hid; ++e) s += u[e] * W2[e * r + c];
+            h2[c] = s;
+        }
+        for (long c = 0; c < hid; ++c) {
+            double s = 0.0;
+            for (long e = 0; e < r; ++e) s += h2[e] * W3[e * hid + c];
+            h[c] = gelu_tanh(s);
+        }
+        for (long c = 0; c < r; ++c) {
+            double s = 0.0;
+            for (long e = 0; e < hid; ++e) s += h[e] * W4[e * r + c];
+            out[i * r + c] = s;
+        }
+    }
+    free(u); free(h); free(h2);
+    return out;
+}
+
+/* LearnablePolysketchWithNegativity(A, r, deg): as oracle_pswn, with f1(M1) * f2(M2) inside
+ * sqrt(r) tanh(sqrt(1/r) .).  Networks are consumed from *params in the order the recursion
+ * reaches them: left subtree, right subtree, then f1, f2 of the node. */
+static double *oracle_lpswn(const double *A, long k, long m, long r, long deg, const double **params)
+{
+    if (deg == 1) {
+        double *out = (double *)malloc(sizeof(double) * (size_t)k * (size_t)m);
+        if (out) memcpy(out, A, sizeof(double) * (size_t)k * (size_t)m);
+        return out;
+    }
+    double *M1 = oracle_lpswn(A, k, m, r, deg / 2, params);
+    double *M2 = oracle_lpswn(A, k, m, r, deg / 2, params);
+    long win = (deg / 2 == 1) ? m : r;
+    double *F1 = M1 ? oracle_learned_net(M1, k, win, r, params) : NULL;
+    double *F2 = M2 ? oracle_learned_net(M2, k, win, r, params) : NULL;
+    double *out = (double *)malloc(sizeof(double) * (size_t)k * (size_t)r);
+    if (!F1 || !F2 || !out) { free(M1); free(M2); free(F1); free(F2); free(out); return NULL; }
+    double sr = sqrt((double)r);
+    for (long i = 0; i < k * r; ++i) out[i] = sr * tanh(F1[i] * F2[i] / sr);
+    free(M1); free(M2); free(F1); free(F2);
+    return out;
+}
+
+/* Number of parameters of the learned degree-p sketch: p - 2 networks (Appendix D), the
+ * p/2 first-level ones with input width d, the others with input width r. */
+long psf_oracle_learned_len(long d, long r, long p)
+{
+    if (p < 4) return 0;
+    return (p / 2) * learned_net_len(d, r) + (p / 2 - 2) * learned_net_len(r, r);
+}
+
+/* M = LearnablePolysketchWithNegativity(X, r, p/2); M_out is k x r (k x d when p == 2). */
+int psf_oracle_sketch_learned(const double *X, long k, long d, long r, long p,
+                              const double *params, double *M_out)
+{
+    if (!is_pow2(p) || p < 2 || k < 0 || d <= 0 || r <= 0) return 1;
+    const double *pp = params;
+    double *M = oracle_lpswn(X, k, d, r, p / 2, &pp);
+    if (!M) return 2;
+    memcpy(M_out, M, sizeof(double) * (size_t)k * (size_t)((p == 2) ? d : r));
     free(M);
     return 0;
 }
