@@ -69,6 +69,9 @@ typedef struct {
     int32_t feat;            /* psf_feat                                                       */
     int32_t local;           /* psf_local (ignored with FEAT_EXACT: all weights are exact)     */
     int32_t sketch_per_head; /* 0: one set of G for all heads, 1: G has a leading [heads] axis */
+    int32_t learned;         /* 0: Gaussian sketch matrices (Algorithm 1); 1: learned sketches
+                                (Algorithm 2, Appendix D): G then holds the networks' parameters,
+                                psf_learned_len(d, r, p) entries per set.  p in {2, 4, 8}         */
 } psf_desc;
 
 /* Host-only check of a descriptor; what the other entry points run first. */
@@ -85,6 +88,20 @@ size_t psf_workspace_bytes(const psf_desc *desc);
 
 /* Number of entries of one set of sketch matrices for (d, r, p). */
 size_t psf_g_len(int32_t d, int32_t r, int32_t p);
+
+/*
+ * Learned sketches (Algorithm 2, Appendix D): every projection M G of Algorithm 1 is replaced by
+ * a dense network f(M) and the Hadamard product is wrapped as sqrt(r) tanh(sqrt(1/r) f1 * f2).
+ * Reading of the appendix taken here: f(a) = gelu(gelu(LN(a) W1) -> LN -> W2 -> W3) W4 with
+ * hidden sizes 8r, r, 8r, output r, no dense biases (the appendix counts 8 h r + 24 r^2
+ * parameters per network), layer normalisation (scale, bias, eps 1e-6, biased variance) before
+ * the input and before the second hidden layer, gelu in its tanh form.  One set of parameters
+ * is the p - 2 networks in the order the recursion reaches them (left subtree, right subtree,
+ * then f1, f2 of the node), each stored as [g1, b1, W1 (in x 8r), g2, b2, W2 (8r x r),
+ * W3 (r x 8r), W4 (8r x r)], matrices row-major with the input index first, in desc->dtype.
+ * psf_learned_len returns the entries of one set (0 for p = 2).
+ */
+size_t psf_learned_len(int32_t d, int32_t r, int32_t p);
 
 /*
  * psf_sketch -- Algorithm 1 applied to every row of X [batch, heads, n, d] (device).

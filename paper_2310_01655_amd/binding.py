@@ -17,7 +17,8 @@ F32, BF16 = 0, 1
 FEAT_SKETCH, FEAT_EXACT = 0, 1
 LOCAL_EXACT, LOCAL_SKETCH = 0, 1
 
-EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_len", "psf_sketch",
+EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_len", "psf_learned_len",
+           "psf_sketch",
            "psf_causal_attn_fwd", "psf_causal_attn_fwd_timed", "psf_stage_name",
            "psf_status_string", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
            "psf_causal_attn_bwd_timed", "psf_decode_state_bytes", "psf_decode_reset",
@@ -27,7 +28,7 @@ EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_le
 class PsfDesc(ctypes.Structure):
     _fields_ = [(name, ctypes.c_int32) for name in
                 ("batch", "heads", "n", "d", "dv", "p", "r", "b", "dtype", "feat", "local",
-                 "sketch_per_head")]
+                 "sketch_per_head", "learned")]
 
 
 class PsfError(RuntimeError):
@@ -58,6 +59,8 @@ def lib():
         L.psf_workspace_bytes.argtypes = [dp]
         L.psf_g_len.restype = ctypes.c_size_t
         L.psf_g_len.argtypes = [ctypes.c_int32] * 3
+        L.psf_learned_len.restype = ctypes.c_size_t
+        L.psf_learned_len.argtypes = [ctypes.c_int32] * 3
         L.psf_sketch.restype = ctypes.c_int
         L.psf_sketch.argtypes = [dp, vp, vp, vp, vp, vp]
         L.psf_causal_attn_fwd.restype = ctypes.c_int
@@ -94,10 +97,10 @@ def status_string(code):
 
 
 def make_desc(batch, heads, n, d, p, r, b, dtype="bf16", dv=None, feat=FEAT_SKETCH,
-              local=LOCAL_EXACT, per_head=False):
+              local=LOCAL_EXACT, per_head=False, learned=False):
     code = {"f32": F32, "bf16": BF16}[dtype] if isinstance(dtype, str) else int(dtype)
     return PsfDesc(batch, heads, n, d, d if dv is None else dv, p, r, b, code, int(feat),
-                   int(local), int(bool(per_head)))
+                   int(local), int(bool(per_head)), int(bool(learned)))
 
 
 def check_desc(desc):
@@ -139,10 +142,15 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(s.cuda_stream)
 
 
+def learned_len(d, r, p):
+    return lib().psf_learned_len(d, r, p)
+
+
 def _g_shape(desc):
     if desc.feat == FEAT_EXACT or desc.p == 2:
         return None
-    return (desc.heads if desc.sketch_per_head else 1, g_len(desc.d, desc.r, desc.p))
+    per_set = learned_len(desc.d, desc.r, desc.p) if desc.learned else g_len(desc.d, desc.r, desc.p)
+    return (desc.heads if desc.sketch_per_head else 1, per_set)
 
 
 def alloc_workspace(desc, device="cuda"):

@@ -16,6 +16,8 @@ psf_status make_problem(const psf_desc *desc, Problem *out)
     if (desc->dtype != PSF_F32 && desc->dtype != PSF_BF16) return PSF_ERR_UNSUPPORTED;
     if (desc->feat != PSF_FEAT_SKETCH && desc->feat != PSF_FEAT_EXACT) return PSF_ERR_UNSUPPORTED;
     if (desc->local != PSF_LOCAL_EXACT && desc->local != PSF_LOCAL_SKETCH) return PSF_ERR_UNSUPPORTED;
+    if (desc->learned != 0 && desc->learned != 1) return PSF_ERR_UNSUPPORTED;
+    if (desc->learned && (desc->feat != PSF_FEAT_SKETCH || desc->p > 8)) return PSF_ERR_UNSUPPORTED;
     const bool needs_r = desc->feat == PSF_FEAT_SKETCH && desc->p > 2;
     if (needs_r && desc->r <= 0) return PSF_ERR_SHAPE;
     if (desc->d > PSF_MAX_DIM || desc->dv > PSF_MAX_DIM || (needs_r && desc->r > PSF_MAX_DIM))
@@ -46,7 +48,9 @@ psf_status make_problem(const psf_desc *desc, Problem *out)
         pb.F = (long long)pb.mcols * pb.mcols;
         if (pb.F > PSF_MAX_FEATURES) return PSF_ERR_UNSUPPORTED;
     }
-    pb.g_len = (pb.exact_feat || desc->p == 2) ? 0 : psf_g_len(desc->d, pb.r, desc->p);
+    pb.learned = desc->learned != 0;
+    pb.g_len = (pb.exact_feat || desc->p == 2) ? 0
+               : pb.learned ? psf_learned_len(desc->d, pb.r, desc->p) : psf_g_len(desc->d, pb.r, desc->p);
     *out = pb;
     return PSF_OK;
 }
@@ -55,7 +59,7 @@ int select_path(const Problem &pb)
 {
     const bool shapes = (pb.r == 32 || pb.r == 64) && pb.d == pb.dv && (pb.d == 64 || pb.d == 128) &&
                         (pb.p == 4 || pb.p == 8) && pb.b % 256 == 0;
-    return (pb.bf16 && !pb.exact_feat && pb.local_exact && shapes) ? 1 : 0;
+    return (pb.bf16 && !pb.exact_feat && pb.local_exact && shapes) ? 1 : 0;   // learned sketches included
 }
 
 psf_status StageTimer::begin(hipStream_t s)
@@ -149,6 +153,17 @@ size_t psf_g_len(int32_t d, int32_t r, int32_t p)
     const size_t n_first = half >= 2 ? half : 0;          // d x r matrices (Theorem 1.1 item 3)
     const size_t n_inner = half >= 4 ? half - 2 : 0;      // r x r matrices
     return n_first * (size_t)d * (size_t)r + n_inner * (size_t)r * (size_t)r;
+}
+
+size_t psf_learned_len(int32_t d, int32_t r, int32_t p)
+{
+    if (d <= 0 || r <= 0 || p < 4) return 0;
+    auto net = [&](size_t win) {                          // g1, b1, W1, g2, b2, W2, W3, W4
+        const size_t hid = 8 * (size_t)r;
+        return 2 * win + win * hid + 2 * hid + hid * r + (size_t)r * hid + hid * r;
+    };
+    const size_t half = (size_t)p / 2;
+    return half * net((size_t)d) + (half >= 4 ? half - 2 : 0) * net((size_t)r);
 }
 
 size_t psf_workspace_bytes(const psf_desc *desc)

@@ -748,9 +748,9 @@ psf_status bwd_launch(const Problem &pb, const void *Q, const void *K, const voi
 
 bool general_bwd_supported(const Problem &pb)
 {
-    // explicit x^{(x)p} features have no backward here; the feature staging assumes F and a
+    // explicit x^{(x)p} features and learned sketches have no backward here; the feature staging assumes F and a
     // block fit the chunked LDS loops (any size) and the 32-bit feature index of one pass
-    return !pb.exact_feat && pb.F <= PSF_MAX_FEATURES;
+    return !pb.exact_feat && !pb.learned && pb.F <= PSF_MAX_FEATURES;
 }
 
 size_t general_bwd_workspace_bytes(const Problem &pb) { return carve_bwd(pb, nullptr).total; }

@@ -111,6 +111,122 @@ __global__ __launch_bounds__(kThreads) void gen_sketch_kernel(
     }
 }
 
+// ---- Algorithm 2 (learnable sketches, Appendix D), one row per loop iteration -------------
+// Every projection M G of Algorithm 1 becomes a dense network f(M); the node returns
+// sqrt(r) tanh(sqrt(1/r) f1(M1) * f2(M2)).  The reading of the appendix (layer order, no dense
+// biases, layer-norm eps, tanh form of gelu, parameter order) is stated in include/psf.h.
+constexpr int kMaxHidden = 8 * PSF_MAX_DIM;
+
+__device__ __forceinline__ float gelu_tanh(float x)
+{
+    return 0.5f * x * (1.0f + tanhf(0.7978845608028654f * (x + 0.044715f * x * x * x)));
+}
+
+// out[e] = (x[e] - mean) / sqrt(var + eps) * g[e] + b[e], e < m; x, out in LDS (may alias);
+// red is kThreads + 2 floats of LDS.
+template <typename T>
+__device__ void wg_layer_norm(const float *x, int m, const T *g, const T *b, float *out, float *red)
+{
+    const int tid = threadIdx.x;
+    float s = 0.f;
+    for (int e = tid; e < m; e += kThreads) s += x[e];
+    red[tid] = s;
+    __syncthreads();
+    if (tid == 0) {
+        float t = 0.f;
+        for (int q = 0; q < kThreads; ++q) t += red[q];
+        red[kThreads] = t / (float)m;
+    }
+    __syncthreads();
+    const float mean = red[kThreads];
+    s = 0.f;
+    for (int e = tid; e < m; e += kThreads) s += (x[e] - mean) * (x[e] - mean);
+    __syncthreads();
+    red[tid] = s;
+    __syncthreads();
+    if (tid == 0) {
+        float t = 0.f;
+        for (int q = 0; q < kThreads; ++q) t += red[q];
+        red[kThreads + 1] = rsqrtf(t / (float)m + 1e-6f);
+    }
+    __syncthreads();
+    const float inv = red[kThreads + 1];
+    for (int e = tid; e < m; e += kThreads) out[e] = (x[e] - mean) * inv * load_f(g, e) + load_f(b, e);
+    __syncthreads();
+}
+
+// out[c] = act(sum_e x[e] W[e * cols + c]) for c < cols; x, out in LDS (must not alias)
+template <typename T, bool GELU>
+__device__ void wg_dense(const float *x, int rows, const T *W, int cols, float *out)
+{
+    for (int c = threadIdx.x; c < cols; c += kThreads) {
+        float s = 0.f;
+        for (int e = 0; e < rows; ++e) s += x[e] * load_f(W, (size_t)e * cols + c);
+        out[c] = GELU ? gelu_tanh(s) : s;
+    }
+    __syncthreads();
+}
+
+// one network: inp (LDS, win) -> out (LDS, r); P points at its parameters
+template <typename T>
+__device__ void wg_learned_net(const float *inp, int win, int r, const T *P, float *out, float *u,
+                               float *h, float *red)
+{
+    const int hid = 8 * r;
+    const T *g1 = P, *b1 = g1 + win, *W1 = b1 + win;
+    const T *g2 = W1 + (size_t)win * hid, *b2 = g2 + hid, *W2 = b2 + hid;
+    const T *W3 = W2 + (size_t)hid * r, *W4 = W3 + (size_t)r * hid;
+    wg_layer_norm(inp, win, g1, b1, u, red);
+    wg_dense<T, true>(u, win, W1, hid, h);
+    wg_layer_norm(h, hid, g2, b2, h, red);
+    wg_dense<T, false>(h, hid, W2, r, u);
+    wg_dense<T, true>(u, r, W3, hid, h);
+    wg_dense<T, false>(h, hid, W4, r, out);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void gen_sketch_learned_kernel(
+    const T *__restrict__ X, const T *__restrict__ P, long long rows, int n, int heads, int per_head,
+    int d, int r, int p, size_t p_len, float *__restrict__ M_f32, T *__restrict__ M_st,
+    T *__restrict__ Phi)
+{
+    __shared__ float xs[PSF_MAX_DIM], u[kMaxHidden], h[kMaxHidden], red[kThreads + 2];
+    __shared__ float f1[PSF_MAX_DIM], f2[PSF_MAX_DIM], m1[PSF_MAX_DIM], m2[PSF_MAX_DIM];
+    const int tid = threadIdx.x;
+    const size_t len_d = 2 * (size_t)d + (size_t)d * 8 * r + 16 * (size_t)r + 24 * (size_t)r * r;
+    const float sr = sqrtf((float)r);
+    for (long long row = blockIdx.x; row < rows; row += gridDim.x) {
+        __syncthreads();
+        if (tid < d) xs[tid] = load_f(X, (size_t)row * d + tid);
+        __syncthreads();
+        const int head = (int)((row / n) % heads);
+        const T *P0 = P + (per_head ? (size_t)head * p_len : 0);
+        // first-level node 0: networks 0 and 1 on x
+        wg_learned_net(xs, d, r, P0, f1, u, h, red);
+        wg_learned_net(xs, d, r, P0 + len_d, f2, u, h, red);
+        if (tid < r) m1[tid] = sr * tanhf(f1[tid] * f2[tid] / sr);
+        __syncthreads();
+        if (p == 8) {                                     // second first-level node, then the root
+            wg_learned_net(xs, d, r, P0 + 2 * len_d, f1, u, h, red);
+            wg_learned_net(xs, d, r, P0 + 3 * len_d, f2, u, h, red);
+            if (tid < r) m2[tid] = sr * tanhf(f1[tid] * f2[tid] / sr);
+            __syncthreads();
+            const size_t len_r = 2 * (size_t)r + (size_t)r * 8 * r + 16 * (size_t)r + 24 * (size_t)r * r;
+            wg_learned_net(m1, r, r, P0 + 4 * len_d, f1, u, h, red);
+            wg_learned_net(m2, r, r, P0 + 4 * len_d + len_r, f2, u, h, red);
+            if (tid < r) m1[tid] = sr * tanhf(f1[tid] * f2[tid] / sr);
+            __syncthreads();
+        }
+        if (tid < r) {
+            if (M_f32) M_f32[(size_t)row * r + tid] = m1[tid];
+            if (M_st) store_f(M_st, (size_t)row * r + tid, m1[tid]);
+        }
+        if (Phi)
+            for (int idx = tid; idx < r * r; idx += kThreads)
+                store_f(Phi, (size_t)row * r * r + idx, m1[idx / r] * m1[idx % r]);
+    }
+}
+
 // ---- H_l = phi(K_l)^T [V_l | 1]  (Section 3.1), one block l per blockIdx.y ----------
 template <typename T>
 __global__ __launch_bounds__(kThreads) void gen_state_kernel(
@@ -293,6 +409,13 @@ psf_status sketch_launch(const Problem &pb, const void *X, const void *G, float 
 {
     const long long rows = (long long)pb.units * pb.n;
     const int grid = (int)(rows < 65536 ? rows : 65536);
+    if (pb.learned && pb.p > 2) {
+        hipLaunchKernelGGL(gen_sketch_learned_kernel<T>, dim3(grid), dim3(kThreads), 0, s, (const T *)X,
+                           (const T *)G, rows, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.d, pb.r, pb.p,
+                           pb.g_len, M_f32, (T *)M_out, (T *)Phi_out);
+        PSF_LAUNCH_CHECK();
+        return PSF_OK;
+    }
     hipLaunchKernelGGL(gen_sketch_kernel<T>, dim3(grid), dim3(kThreads), 0, s, (const T *)X,
                        (const T *)G, rows, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.d, pb.r, pb.p,
                        pb.exact_feat ? 1 : 0, pb.F, pb.g_len, M_f32, (T *)M_out, (T *)Phi_out);

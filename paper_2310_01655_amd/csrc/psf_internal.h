@@ -16,7 +16,7 @@ struct Problem {
     int n, d, dv, p, r, b, t;
     int mcols;        // columns of m(x): r, or d when p == 2 (Algorithm 1 base case)
     long long F;      // explicit feature count: mcols^2, or d^p with exact features
-    bool bf16, exact_feat, local_exact, per_head;
+    bool bf16, exact_feat, local_exact, per_head, learned;
     size_t g_len;     // entries of one set of sketch matrices
 };
 

@@ -1097,8 +1097,62 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Learned sketches (Algorithm 2): m(x) comes from the general fp32 sketch kernel as row-major
+// fp32 [rows][R]; these two kernels put it into the layouts the state and output kernels read.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kWg) void k_m_to_bf16(const float *__restrict__ M, bf16_t *__restrict__ MQ,
+                                                   size_t count)
+{
+    const size_t i = ((size_t)blockIdx.x * kWg + threadIdx.x) * 4;
+    if (i + 3 < count) {
+        const f32x4 v = *(const f32x4 *)&M[i];
+        *(bf16x4 *)&MQ[i] = cvt4(v);
+    } else {
+        for (size_t e = i; e < count; ++e) MQ[e] = f32_to_bf16(M[e]);
+    }
+}
+
+// One workgroup per part of `tokens` consecutive tokens of one unit: m(K) rows -> token octets
+// [n/8][2][R][4] fp32, and the part's S = m^T m (R x R, fp32) for the denominator scan.
+template <int R>
+__global__ __launch_bounds__(kWg) void k_m_to_octets_and_partials(const float *__restrict__ M,
+                                                                  float *__restrict__ MK8,
+                                                                  float *__restrict__ Spart, int tokens)
+{
+    constexpr int TCH = 64, PER = R * R / kWg;            // staged tokens; S entries per thread
+    __shared__ float ms[TCH][R + 1];
+    const int tid = threadIdx.x;
+    const size_t row0 = (size_t)blockIdx.x * tokens;      // parts tile the rows of all units in order
+    float acc[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) acc[q] = 0.f;
+    for (int t0 = 0; t0 < tokens; t0 += TCH) {
+        __syncthreads();
+        for (int idx = tid; idx < TCH * R; idx += kWg) {
+            const int tk = idx / R, c = idx % R;
+            const float v = M[(row0 + t0 + tk) * R + c];
+            ms[tk][c] = v;
+            const size_t tok = row0 + t0 + tk;            // octet layout: ((tok/8 * 2 + (tok%8)/4) * R + c) * 4 + tok%4
+            MK8[((tok / 8 * 2 + (tok % 8) / 4) * R + c) * 4 + tok % 4] = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int e = q * kWg + tid, a = e / R, c = e % R;
+            float sacc = 0.f;
+            for (int tk = 0; tk < TCH; ++tk) sacc += ms[tk][a] * ms[tk][c];
+            acc[q] += sacc;
+        }
+    }
+    float *out = Spart + (size_t)blockIdx.x * R * R;
+#pragma unroll
+    for (int q = 0; q < PER; ++q) out[q * kWg + tid] = acc[q];
+}
+
 struct MfmaWs {
     bf16_t *Gt; bf16_t *MQ; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
+    float *M32;                                  // learned sketches only: m(x) as fp32 rows
     size_t total;
 };
 
@@ -1118,7 +1172,7 @@ MfmaWs carve(const Problem &pb, void *ws)
     size_t off = 0;
     char *base = (char *)ws;
     auto take = [&](size_t bytes) { char *p = base + off; off += align_up(bytes, 256); return p; };
-    w.Gt = (bf16_t *)take(sets * pb.g_len * 2);
+    w.Gt = (bf16_t *)take(pb.learned ? 0 : sets * pb.g_len * 2);
     w.MQ = (bf16_t *)take(rows * R * 2);
     w.MK8 = (float *)take(rows * R * 4);
     w.V8 = (bf16_t *)take(rows * D * 2);
@@ -1126,6 +1180,7 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.Spart = (float *)take(parts * R * R * 4);
     w.Shi = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
     w.Slo = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
+    w.M32 = (float *)take(pb.learned ? rows * R * 4 : 0);
     w.total = off;
     return w;
 }
@@ -1160,12 +1215,29 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
 {
     MfmaWs w = carve(pb, ws);
     const int tiles = sketch_tiles_per_wg(pb.b);
-    psf_status st = launch_transpose_g(pb, G, w.Gt, s);
-    if (st != PSF_OK) return st;
-    st = launch_sketch<D, R, P>(pb, Q, w.Gt, true, w.MQ, nullptr, nullptr, tiles, s);
-    if (st != PSF_OK) return st;
-    st = launch_sketch<D, R, P>(pb, K, w.Gt, false, nullptr, w.MK8, w.Spart, tiles, s);
-    if (st != PSF_OK) return st;
+    psf_status st;
+    if (pb.learned) {
+        // Algorithm 2 runs in the general fp32 sketch kernel; only the layouts are made here
+        const size_t rows = (size_t)pb.units * pb.n, count = rows * R;
+        st = general_sketch_f32(pb, Q, G, w.M32, s);
+        if (st != PSF_OK) return st;
+        hipLaunchKernelGGL(k_m_to_bf16, dim3((unsigned)((count / 4 + kWg - 1) / kWg)), dim3(kWg), 0, s, w.M32,
+                           w.MQ, count);
+        PSF_LAUNCH_CHECK();
+        st = general_sketch_f32(pb, K, G, w.M32, s);
+        if (st != PSF_OK) return st;
+        const int part_tokens = 128 * tiles;
+        hipLaunchKernelGGL((k_m_to_octets_and_partials<R>), dim3((unsigned)(rows / part_tokens)), dim3(kWg), 0, s,
+                           w.M32, w.MK8, w.Spart, part_tokens);
+        PSF_LAUNCH_CHECK();
+    } else {
+        st = launch_transpose_g(pb, G, w.Gt, s);
+        if (st != PSF_OK) return st;
+        st = launch_sketch<D, R, P>(pb, Q, w.Gt, true, w.MQ, nullptr, nullptr, tiles, s);
+        if (st != PSF_OK) return st;
+        st = launch_sketch<D, R, P>(pb, K, w.Gt, false, nullptr, w.MK8, w.Spart, tiles, s);
+        if (st != PSF_OK) return st;
+    }
     {
         const size_t octets = (size_t)pb.units * pb.n / 8;
         hipLaunchKernelGGL((k_v_octets<D>), dim3((unsigned)((octets * D + kWg - 1) / kWg)), dim3(kWg), 0,

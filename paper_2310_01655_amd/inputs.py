@@ -76,6 +76,38 @@ def make_qkv(batch, heads, n, d, dv=None, seed=0, dist="normal", dtype="f32"):
     return q.to(td).contiguous(), k.to(td).contiguous(), v.to(td).contiguous()
 
 
+def learned_len(d, r, p):
+    """Entries of one parameter set of the learned sketch (Appendix D): p - 2 networks, each
+    [g1, b1, W1 (in x 8r), g2, b2, W2 (8r x r), W3 (r x 8r), W4 (8r x r)]."""
+    if p < 4:
+        return 0
+    net = lambda win: 2 * win + win * 8 * r + 16 * r + 24 * r * r
+    return (p // 2) * net(d) + max(p // 2 - 2, 0) * net(r)
+
+
+def make_learned_params(heads, d, r, p, per_head=False, seed=0, dtype="f32"):
+    """Synthetic parameters of the learned sketch, [heads if per_head else 1, learned_len]:
+    dense matrices N(0, 1/fan_in), layer-norm scales 1 + 0.1 N(0,1), biases 0.1 N(0,1) (random
+    stand-ins for trained weights, which are not available), networks in the order the
+    recursion of Algorithm 2 reaches them."""
+    sets = heads if per_head else 1
+    out = torch.empty(sets, max(learned_len(d, r, p), 1), dtype=torch.float32)
+    widths = [d] * (p // 2) + [r] * max(p // 2 - 2, 0) if p >= 4 else []
+    for h in range(sets):
+        g = torch.Generator(device="cpu")
+        g.manual_seed(int(seed) + 31 * h + 5)
+        rn = lambda *shape: torch.randn(*shape, generator=g, dtype=torch.float32)
+        pieces = []
+        for win in widths:
+            hid = 8 * r
+            pieces += [1.0 + 0.1 * rn(win), 0.1 * rn(win), rn(win, hid) / win ** 0.5,
+                       1.0 + 0.1 * rn(hid), 0.1 * rn(hid), rn(hid, r) / hid ** 0.5,
+                       rn(r, hid) / r ** 0.5, rn(hid, r) / hid ** 0.5]
+        if pieces:
+            out[h] = torch.cat([x.reshape(-1) for x in pieces])
+    return out.to(torch_dtype(dtype)).contiguous()
+
+
 def make_dout(batch, heads, n, dv, seed=0, dtype="f32"):
     """dL/dO for the backward pass: entries N(0,1) (stand-in for the gradient that the layers
     after the attention send back), CPU tensor in the storage dtype."""
