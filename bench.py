@@ -36,12 +36,15 @@ def workloads():
     return w
 
 
-def stage_flops(cfg):
+def stage_flops(cfg, learned=False):
     """Algorithmic flops per step (multiply-add = 2), split by kernel stage.  Causal lower
     triangle only; the first block has no prefix and the last block's state is never needed."""
     U = cfg["batch"] * cfg["heads"]
     n, d, r, b, p = cfg["n"], cfg["d"], cfg["r"], cfg["b"], cfg["p"]
     sketch = 2 * (8 * n * d * r if p == 4 else 16 * n * d * r + 8 * n * r * r)   # Q and K
+    if learned:          # p - 2 networks per row: four dense layers each (Appendix D)
+        net = lambda win: 2 * (win * 8 * r + 24 * r * r)
+        sketch = 2 * n * ((p // 2) * net(d) + max(p // 2 - 2, 0) * net(r))
     f = {
         "sketch_and_layouts": U * (sketch + 2 * (n - b) * r * r),      # + ones column of H_l
         "block_states_scan": U * 2 * (n - b) * r * r * d,               # H_l and Z_l
@@ -246,6 +249,8 @@ def main():
     ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "decode"],
                     help="fwd: psf_causal_attn_fwd (the headline); bwd: psf_causal_attn_bwd; "
                          "decode: psf_decode_step at a fixed serving shape")
+    ap.add_argument("--learned", action="store_true",
+                    help="forward pass with learned sketches (Algorithm 2) instead of Gaussian ones")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also issue one 256 MiB device copy, so that a counter run can scale "
@@ -274,13 +279,17 @@ def main():
     idx = int(args.workload[6:]) if args.workload.startswith("config") else 4
     q, k, v = inputs.make_qkv(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], seed=1000 + idx,
                               dist=cfg["dist"], dtype=cfg["dtype"])
-    G = inputs.make_sketch_matrices(cfg["heads"], cfg["d"], cfg["r"], cfg["p"], per_head=cfg["per_head"],
-                                    seed=0, dtype=cfg["dtype"])
+    if args.learned:
+        G = inputs.make_learned_params(cfg["heads"], cfg["d"], cfg["r"], cfg["p"], per_head=cfg["per_head"],
+                                       seed=0, dtype=cfg["dtype"])
+    else:
+        G = inputs.make_sketch_matrices(cfg["heads"], cfg["d"], cfg["r"], cfg["p"], per_head=cfg["per_head"],
+                                        seed=0, dtype=cfg["dtype"])
     if args.which == "bwd":
         run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx)
         return
     desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
-                         cfg["dtype"], per_head=cfg["per_head"])
+                         cfg["dtype"], per_head=cfg["per_head"], learned=args.learned)
     path = psf.kernel_path(desc)
     qd, kd, vd, Gd = q.to(dev), k.to(dev), v.to(dev), G.to(dev)
     O = torch.empty_like(vd)
@@ -311,13 +320,14 @@ def main():
         _, st = psf.psf_causal_attn_fwd_timed(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
         for nm, ms in st.items():
             acc[nm] = acc.get(nm, 0.0) + ms / reps
-    fl = stage_flops(cfg) if path == 1 else None
+    fl = stage_flops(cfg, learned=args.learned) if path == 1 else None
     out = {
         "metric": "causal_polysketch_attention_fwd_tokens_per_s", "value": tokens * args.steps / elapsed,
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if path == 1 else "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"],
+        "config": {"workload": args.workload, "sketch": "learned" if args.learned else "gaussian",
+                   "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"],
                    "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
                    "kernel_path": "mfma_bf16" if path == 1 else "general_fp32"},
         "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
@@ -332,7 +342,7 @@ def main():
                            "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                            "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
                            "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc if nm in fl}}
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.learned:      # the batch oracle driver takes Gaussian sketches
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, G)
     print(json.dumps(out))
 

@@ -1150,9 +1150,339 @@ __global__ __launch_bounds__(kWg) void k_m_to_octets_and_partials(const float *_
     for (int q = 0; q < PER; ++q) out[q * kWg + tid] = acc[q];
 }
 
+// ------------------------------------------------------------------------------------
+// Learned sketch of degree 4 on MFMA (Algorithm 2 with p = 4, d = 64): m(x) =
+// sqrt(r) tanh(f1(x) * f2(x) / sqrt(r)), f = the four-layer network of Appendix D.
+// Everything is "transposed": accumulators hold [feature][token] (lane = token), so a layer's
+// output registers are the next layer's B operand after a bf16 conversion; the weights are
+// the A operands, pre-arranged by k_learned_prep so that every fragment is one 16-byte read
+// and the contraction order matches the accumulator register order.  Layer normalisation is
+// folded into the weights:  LN(a) W = (a (g . W) - mean (sum_k g_k W_k)) / sigma + b W.  For
+// the input layer the mean / sigma terms ride on a fifth contraction step (hi + lo bf16 pairs),
+// for the second one they are applied after the product has been accumulated over all hidden
+// chunks, together with the sums of h and h^2.  Hidden width 8r is walked in chunks of 32;
+// the weights of a chunk (8 KB) stream through a ring of LDS slots.
+// ------------------------------------------------------------------------------------
+constexpr int kLsSlotBytes = 8192;     // one chunk: [W1' | W2'] or [W3 | W4], second part at +4096
+constexpr int kLsRing = 4;
+
+__device__ __forceinline__ float gelu_fast(float x)
+{
+    // tanh form: 0.5 x (1 + tanh(u)), u = sqrt(2/pi) (x + 0.044715 x^3)  =  x - x / (1 + exp(2u))
+    const float e = __builtin_amdgcn_exp2f(x * (2.3022082f + 0.10294324f * x * x));   // exp(2u) as 2^(.)
+    return x - x * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+__device__ __forceinline__ float tanh_fast(float y)
+{
+    const float e = __builtin_amdgcn_exp2f(2.8853900f * y);                           // exp(2y)
+    return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+// Parameter blob of one network (input width 64): g1, b1, W1 [64][8R], g2, b2, W2 [8R][R],
+// W3 [R][8R], W4 [8R][R].
+template <int R>
+struct LearnedNet {
+    static constexpr int HID = 8 * R, NCH = HID / 32, D = 64;
+    static constexpr size_t LEN = 2 * D + (size_t)D * HID + 2 * HID + 3 * (size_t)HID * R;
+    const bf16_t *g1, *b1, *W1, *g2, *b2, *W2, *W3, *W4;
+    __device__ explicit LearnedNet(const bf16_t *P)
+    {
+        g1 = P; b1 = g1 + D; W1 = b1 + D; g2 = W1 + (size_t)D * HID; b2 = g2 + HID; W2 = b2 + HID;
+        W3 = W2 + (size_t)HID * R; W4 = W3 + (size_t)R * HID;
+    }
+};
+
+// Slot (net, phase, chunk) of the weight stream of one parameter set; grid (4 * NCH, sets).
+//   phase 0: [0, 4 KB)  W1' fragments: k-step s < 4, hidden row i, half h, e: k = 16 s + 8 h + e,
+//                       value bf16(g1[k] W1[k][32 ch + i])
+//            [4 KB, ..) W2' fragments: out tile ot, k-step s < 2, out row i, half h, e:
+//                       hidden = 32 ch + 16 s + 8 (e / 4) + 4 h + e % 4 (accumulator row order),
+//                       value bf16(g2[hidden] W2[hidden][32 ot + i])
+//   phase 1: [0, 4 KB)  W3 fragments: k-step t < R / 16, hidden row i, half h, e:
+//                       feature = 32 (t / 2) + 16 (t % 2) + 8 (e / 4) + 4 h + e % 4
+//            [4 KB, ..) W4 fragments, arranged like W2' without the scale.
+template <int R>
+__global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__ P, size_t p_len,
+                                                      bf16_t *__restrict__ LW)
+{
+    using Net = LearnedNet<R>;
+    constexpr int NCH = Net::NCH, HID = Net::HID;
+    const int q = blockIdx.x, set = blockIdx.y;
+    const int net = q / (2 * NCH), phase = (q / NCH) % 2, ch = q % NCH;
+    const Net nt(P + (size_t)set * p_len + (size_t)net * Net::LEN);
+    bf16_t *slot = LW + ((size_t)set * 4 * NCH + q) * (kLsSlotBytes / 2);
+    for (int idx = threadIdx.x; idx < kLsSlotBytes / 2; idx += kWg) {
+        float v = 0.f;
+        const int part = idx / 2048, r2 = idx % 2048;
+        const int i = (r2 % 512) / 16, h = (r2 / 8) % 2, e = r2 % 8, blk = r2 / 512;
+        const int perm = 8 * (e / 4) + 4 * h + e % 4;           // accumulator row order inside 16
+        if (phase == 0 && part == 0) {
+            const int k = 16 * blk + 8 * h + e;
+            v = bf16_to_f32(nt.g1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + 32 * ch + i]);
+        } else if (phase == 0) {
+            if (blk < 2 * (R / 32)) {
+                const int ot = blk / 2, sstep = blk % 2, hid = 32 * ch + 16 * sstep + perm;
+                v = bf16_to_f32(nt.g2[hid]) * bf16_to_f32(nt.W2[(size_t)hid * R + 32 * ot + i]);
+            }
+        } else if (part == 0) {
+            if (blk < R / 16) {
+                const int feat = 32 * (blk / 2) + 16 * (blk % 2) + perm;
+                v = bf16_to_f32(nt.W3[(size_t)feat * HID + 32 * ch + i]);
+            }
+        } else {
+            if (blk < 2 * (R / 32)) {
+                const int ot = blk / 2, sstep = blk % 2, hid = 32 * ch + 16 * sstep + perm;
+                v = bf16_to_f32(nt.W4[(size_t)hid * R + 32 * ot + i]);
+            }
+        }
+        slot[idx] = f32_to_bf16(v);
+    }
+}
+
+// Constants of the folded layer normalisations; grid (2 nets, sets).
+//   LX [set][net][NCH][32][8] bf16: for hidden row 32 ch + i the pairs
+//      (s1_hi, s1_hi, s1_lo, s1_lo, c1_hi, c1_hi, c1_lo, c1_lo), s1 = sum_k bf16(g1[k] W1[k][.]),
+//      c1 = sum_k b1[k] W1[k][.]  (the fifth contraction step of the input layer)
+//   LV [set][net][2][R] fp32: s2 = sum_hid bf16(g2 W2), c2 = sum_hid b2 W2
+template <int R>
+__global__ __launch_bounds__(kWg) void k_learned_prep_consts(const bf16_t *__restrict__ P, size_t p_len,
+                                                             bf16_t *__restrict__ LX, float *__restrict__ LV)
+{
+    using Net = LearnedNet<R>;
+    constexpr int NCH = Net::NCH, HID = Net::HID, D = Net::D;
+    const int net = blockIdx.x, set = blockIdx.y;
+    const Net nt(P + (size_t)set * p_len + (size_t)net * Net::LEN);
+    bf16_t *lx = LX + ((size_t)set * 2 + net) * NCH * 32 * 8;
+    float *lv = LV + ((size_t)set * 2 + net) * 2 * R;
+    for (int hid = threadIdx.x; hid < HID; hid += kWg) {
+        float s1 = 0.f, c1 = 0.f;
+        for (int k = 0; k < D; ++k) {
+            const float w = bf16_to_f32(nt.W1[(size_t)k * HID + hid]);
+            s1 += bf16_to_f32(f32_to_bf16(bf16_to_f32(nt.g1[k]) * w));
+            c1 += bf16_to_f32(nt.b1[k]) * w;
+        }
+        const bf16_t s_hi = f32_to_bf16(s1), s_lo = f32_to_bf16(s1 - bf16_to_f32(s_hi));
+        const bf16_t c_hi = f32_to_bf16(c1), c_lo = f32_to_bf16(c1 - bf16_to_f32(c_hi));
+        bf16_t *o = lx + (size_t)hid * 8;
+        o[0] = s_hi; o[1] = s_hi; o[2] = s_lo; o[3] = s_lo; o[4] = c_hi; o[5] = c_hi; o[6] = c_lo; o[7] = c_lo;
+    }
+    for (int out = threadIdx.x; out < R; out += kWg) {
+        float s2 = 0.f, c2 = 0.f;
+        for (int hid = 0; hid < HID; ++hid) {
+            const float w = bf16_to_f32(nt.W2[(size_t)hid * R + out]);
+            s2 += bf16_to_f32(f32_to_bf16(bf16_to_f32(nt.g2[hid]) * w));
+            c2 += bf16_to_f32(nt.b2[hid]) * w;
+        }
+        lv[out] = s2;
+        lv[R + out] = c2;
+    }
+}
+
+// Workgroup = 256 consecutive tokens of one unit (wave = 2 tiles of 32 tokens); writes m(x)
+// as fp32 rows [rows][R].
+template <int R>
+__global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restrict__ X,
+                                                           const bf16_t *__restrict__ LW,
+                                                           const bf16_t *__restrict__ LX,
+                                                           const float *__restrict__ LV,
+                                                           float *__restrict__ M32, int n, int heads,
+                                                           int per_head)
+{
+    using Net = LearnedNet<R>;
+    constexpr int NCH = Net::NCH, HID = Net::HID, D = 64, OT = R / 32, TT = 2, KS = D / 16, RS = R / 16;
+    constexpr int QN = 4 * NCH;                            // slots of the weight stream
+    constexpr int DMA = kLsSlotBytes / 16 / kWg;           // copies per thread and slot
+    __shared__ __attribute__((aligned(16))) unsigned char ring[kLsRing * kLsSlotBytes];
+    __shared__ __attribute__((aligned(16))) bf16_t lx[2 * NCH * 32 * 8];
+    __shared__ __attribute__((aligned(16))) float lv[2 * 2 * R];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int x = lane & 31, h = lane >> 5;
+    const size_t row0 = (size_t)blockIdx.x * (kWg * TT / 2);          // 256 tokens per workgroup
+    const int set = per_head ? (int)((row0 / n) % heads) : 0;
+    const unsigned char *stream = (const unsigned char *)(LW + (size_t)set * QN * (kLsSlotBytes / 2));
+    const uint32_t ring0 = lds_address(ring);
+    auto stage = [&](int q) {
+        const int qc = min(q, QN - 1);                     // clamped: keeps the copy count uniform
+        const uint32_t dst = ring0 + (q % kLsRing) * kLsSlotBytes + wave * 1024;
+#pragma unroll
+        for (int c = 0; c < DMA; ++c)
+            dma16_sbase(stream + (size_t)qc * kLsSlotBytes + c * 4096, (uint32_t)tid * 16, dst + c * 4096);
+    };
+#pragma unroll
+    for (int q = 0; q < kLsRing - 1; ++q) stage(q);
+    for (int idx = tid; idx < 2 * NCH * 32 * 8 / 8; idx += kWg)
+        ((uint4 *)lx)[idx] = ((const uint4 *)(LX + (size_t)set * 2 * NCH * 32 * 8))[idx];
+    for (int idx = tid; idx < 2 * 2 * R; idx += kWg) lv[idx] = LV[(size_t)set * 2 * 2 * R + idx];
+
+    // input fragments (B operands of the first layer) and the statistics of the input rows
+    bf16x8 xfr[TT][KS], xb[TT];
+    float inv_x[TT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const size_t row = row0 + wave * 64 + 32 * tt + x;
+        float sum = 0.f, sq = 0.f;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            xfr[tt][s] = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float v = (float)xfr[tt][s][e];
+                sum += v;
+                sq += v * v;
+            }
+        }
+        sum += __shfl_xor(sum, 32);
+        sq += __shfl_xor(sq, 32);
+        const float mean = sum * (1.0f / D), var = sq * (1.0f / D) - mean * mean;
+        const float sigma = sqrtf(var + 1e-6f);
+        inv_x[tt] = 1.0f / sigma;
+        // fifth contraction step: (-mean) s1 + sigma c1 with hi + lo pairs (half h = 0 only)
+        const __bf16 m_hi = (__bf16)(-mean), m_lo = (__bf16)(-mean - (float)m_hi);
+        const __bf16 g_hi = (__bf16)sigma, g_lo = (__bf16)(sigma - (float)g_hi);
+        const __bf16 z = (__bf16)0.0f;
+        xb[tt] = h == 0 ? bf16x8{m_hi, m_lo, m_hi, m_lo, g_hi, g_lo, g_hi, g_lo} : bf16x8{z, z, z, z, z, z, z, z};
+    }
+
+    f32x16 f1[TT][OT];
+    int q = 0;
+#pragma unroll 1
+    for (int net = 0; net < 2; ++net) {
+        // ---- layers 1 and 2: P2 = gelu(LN(x) W1) (g2 . W2), with the sums for the second LN ----
+        f32x16 acc2[TT][OT];
+        float sh[TT], sqh[TT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            sh[tt] = sqh[tt] = 0.f;
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot) acc2[tt][ot] = f32x16{0};
+        }
+#pragma unroll 1
+        for (int ch = 0; ch < NCH; ++ch, ++q) {
+            wait_vmem_le<(kLsRing - 2) * DMA>();
+            __syncthreads();                               // slot q has landed for everybody; slot q-1 is free
+            stage(q + kLsRing - 1);
+            const unsigned char *sl = ring + (q % kLsRing) * kLsSlotBytes;
+            bf16x8 a1[KS], a2[OT][2];
+#pragma unroll
+            for (int s = 0; s < KS; ++s) a1[s] = *(const bf16x8 *)(sl + ((s * 32 + x) * 2 + h) * 16);
+            const bf16_t *lxr = lx + ((size_t)(net * NCH + ch) * 32 + x) * 8;
+            const bf16x8 zero8 = {(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
+            const bf16x8 a1x = h == 0 ? *(const bf16x8 *)lxr : zero8;
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+                    a2[ot][s] = *(const bf16x8 *)(sl + 4096 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                f32x16 acc = {0};
+#pragma unroll
+                for (int s = 0; s < KS; ++s) acc = mfma32(a1[s], xfr[tt][s], acc);
+                acc = mfma32(a1x, xb[tt], acc);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float hv = gelu_fast(acc[v] * inv_x[tt]);
+                    sh[tt] += hv;
+                    sqh[tt] += hv * hv;
+                    acc[v] = hv;
+                }
+                const bf16x8 hf0 = cvt8_from16(acc, 0), hf1 = cvt8_from16(acc, 8);
+#pragma unroll
+                for (int ot = 0; ot < OT; ++ot) {
+                    acc2[tt][ot] = mfma32(a2[ot][0], hf0, acc2[tt][ot]);
+                    acc2[tt][ot] = mfma32(a2[ot][1], hf1, acc2[tt][ot]);
+                }
+            }
+        }
+        // ---- second layer normalisation applied to the accumulated product ----
+        bf16x8 h2f[TT][RS];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const float s_all = sh[tt] + __shfl_xor(sh[tt], 32), q_all = sqh[tt] + __shfl_xor(sqh[tt], 32);
+            const float mean = s_all * (1.0f / HID), var = q_all * (1.0f / HID) - mean * mean;
+            const float inv = rsqrtf(fmaxf(var, 0.f) + 1e-6f);
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot) {
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const f32x4 s2 = *(const f32x4 *)&lv[(net * 2 + 0) * R + 32 * ot + 8 * g4 + 4 * h];
+                    const f32x4 c2 = *(const f32x4 *)&lv[(net * 2 + 1) * R + 32 * ot + 8 * g4 + 4 * h];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc2[tt][ot][4 * g4 + j] = (acc2[tt][ot][4 * g4 + j] - mean * s2[j]) * inv + c2[j];
+                }
+                h2f[tt][2 * ot] = cvt8_from16(acc2[tt][ot], 0);
+                h2f[tt][2 * ot + 1] = cvt8_from16(acc2[tt][ot], 8);
+            }
+        }
+        // ---- layers 3 and 4: out = gelu(h2 W3) W4 ----
+        f32x16 out[TT][OT];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot) out[tt][ot] = f32x16{0};
+#pragma unroll 1
+        for (int ch = 0; ch < NCH; ++ch, ++q) {
+            wait_vmem_le<(kLsRing - 2) * DMA>();
+            __syncthreads();
+            stage(q + kLsRing - 1);
+            const unsigned char *sl = ring + (q % kLsRing) * kLsSlotBytes;
+            bf16x8 a3[RS], a4[OT][2];
+#pragma unroll
+            for (int t = 0; t < RS; ++t) a3[t] = *(const bf16x8 *)(sl + ((t * 32 + x) * 2 + h) * 16);
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+                for (int s = 0; s < 2; ++s)
+                    a4[ot][s] = *(const bf16x8 *)(sl + 4096 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                f32x16 acc = {0};
+#pragma unroll
+                for (int t = 0; t < RS; ++t) acc = mfma32(a3[t], h2f[tt][t], acc);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = gelu_fast(acc[v]);
+                const bf16x8 hf0 = cvt8_from16(acc, 0), hf1 = cvt8_from16(acc, 8);
+#pragma unroll
+                for (int ot = 0; ot < OT; ++ot) {
+                    out[tt][ot] = mfma32(a4[ot][0], hf0, out[tt][ot]);
+                    out[tt][ot] = mfma32(a4[ot][1], hf1, out[tt][ot]);
+                }
+            }
+        }
+        if (net == 0) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                for (int ot = 0; ot < OT; ++ot) f1[tt][ot] = out[tt][ot];
+        } else {
+            const float sr = sqrtf((float)R), isr = 1.0f / sr;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const size_t row = row0 + wave * 64 + 32 * tt + x;
+#pragma unroll
+                for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+                    for (int g4 = 0; g4 < 4; ++g4) {
+                        f32x4 m4;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            m4[j] = sr * tanh_fast(f1[tt][ot][4 * g4 + j] * out[tt][ot][4 * g4 + j] * isr);
+                        *(f32x4 *)&M32[row * R + 32 * ot + 8 * g4 + 4 * h] = m4;
+                    }
+            }
+        }
+    }
+    wait_vmem_le<0>();                                     // drain the clamped copies
+}
+
 struct MfmaWs {
     bf16_t *Gt; bf16_t *MQ; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
     float *M32;                                  // learned sketches only: m(x) as fp32 rows
+    bf16_t *LW, *LX; float *LV;                  // learned sketches on MFMA: arranged weights
     size_t total;
 };
 
@@ -1181,6 +1511,11 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.Shi = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
     w.Slo = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
     w.M32 = (float *)take(pb.learned ? rows * R * 4 : 0);
+    const bool fast_learned = pb.learned && pb.p == 4 && pb.d == 64;
+    const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
+    w.LW = (bf16_t *)take(fast_learned ? sets * 4 * nch * kLsSlotBytes : 0);
+    w.LX = (bf16_t *)take(fast_learned ? sets * 2 * nch * 32 * 8 * 2 : 0);
+    w.LV = (float *)take(fast_learned ? sets * 2 * 2 * R * 4 : 0);
     w.total = off;
     return w;
 }
@@ -1219,12 +1554,31 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     if (pb.learned) {
         // Algorithm 2 runs in the general fp32 sketch kernel; only the layouts are made here
         const size_t rows = (size_t)pb.units * pb.n, count = rows * R;
-        st = general_sketch_f32(pb, Q, G, w.M32, s);
+        const int sets = pb.per_head ? pb.heads : 1;
+        auto sketch = [&](const void *X) -> psf_status {
+            if constexpr (P == 4 && D == 64) {              // degree 4 on MFMA
+                hipLaunchKernelGGL((k_learned_sketch<R>), dim3((unsigned)(rows / 256)), dim3(kWg), 0, s,
+                                   (const bf16_t *)X, w.LW, w.LX, w.LV, w.M32, pb.n, pb.heads, pb.per_head ? 1 : 0);
+                PSF_LAUNCH_CHECK();
+                return PSF_OK;
+            } else {
+                return general_sketch_f32(pb, X, G, w.M32, s);
+            }
+        };
+        if constexpr (P == 4 && D == 64) {
+            hipLaunchKernelGGL((k_learned_prep<R>), dim3(4 * (R / 4), sets), dim3(kWg), 0, s, (const bf16_t *)G,
+                               pb.g_len, w.LW);
+            PSF_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_learned_prep_consts<R>), dim3(2, sets), dim3(kWg), 0, s, (const bf16_t *)G,
+                               pb.g_len, w.LX, w.LV);
+            PSF_LAUNCH_CHECK();
+        }
+        st = sketch(Q);
         if (st != PSF_OK) return st;
         hipLaunchKernelGGL(k_m_to_bf16, dim3((unsigned)((count / 4 + kWg - 1) / kWg)), dim3(kWg), 0, s, w.M32,
                            w.MQ, count);
         PSF_LAUNCH_CHECK();
-        st = general_sketch_f32(pb, K, G, w.M32, s);
+        st = sketch(K);
         if (st != PSF_OK) return st;
         const int part_tokens = 128 * tiles;
         hipLaunchKernelGGL((k_m_to_octets_and_partials<R>), dim3((unsigned)(rows / part_tokens)), dim3(kWg), 0, s,
