@@ -1204,15 +1204,17 @@ struct LearnedNet {
 //            [4 KB, ..) W4 fragments, arranged like W2' without the scale.
 template <int R>
 __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__ P, size_t p_len,
-                                                      bf16_t *__restrict__ LW)
+                                                      bf16_t *__restrict__ LW, bf16_t *__restrict__ LX,
+                                                      float *__restrict__ LVp)
 {
     using Net = LearnedNet<R>;
-    constexpr int NCH = Net::NCH, HID = Net::HID;
-    const int q = blockIdx.x, set = blockIdx.y;
+    constexpr int NCH = Net::NCH, HID = Net::HID, D = Net::D;
+    __shared__ float red[2][kWg];
+    const int q = blockIdx.x, set = blockIdx.y, tid = threadIdx.x;
     const int net = q / (2 * NCH), phase = (q / NCH) % 2, ch = q % NCH;
     const Net nt(P + (size_t)set * p_len + (size_t)net * Net::LEN);
     bf16_t *slot = LW + ((size_t)set * 4 * NCH + q) * (kLsSlotBytes / 2);
-    for (int idx = threadIdx.x; idx < kLsSlotBytes / 2; idx += kWg) {
+    for (int idx = tid; idx < kLsSlotBytes / 2; idx += kWg) {
         float v = 0.f;
         const int part = idx / 2048, r2 = idx % 2048;
         const int i = (r2 % 512) / 16, h = (r2 / 8) % 2, e = r2 % 8, blk = r2 / 512;
@@ -1238,55 +1240,67 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
         }
         slot[idx] = f32_to_bf16(v);
     }
-}
-
-// Constants of the folded layer normalisations; grid (2 nets, sets).
-//   LX [set][net][NCH][32][8] bf16: for hidden row 32 ch + i the pairs
-//      (s1_hi, s1_hi, s1_lo, s1_lo, c1_hi, c1_hi, c1_lo, c1_lo), s1 = sum_k bf16(g1[k] W1[k][.]),
-//      c1 = sum_k b1[k] W1[k][.]  (the fifth contraction step of the input layer)
-//   LV [set][net][2][R] fp32: s2 = sum_hid bf16(g2 W2), c2 = sum_hid b2 W2
-template <int R>
-__global__ __launch_bounds__(kWg) void k_learned_prep_consts(const bf16_t *__restrict__ P, size_t p_len,
-                                                             bf16_t *__restrict__ LX, float *__restrict__ LV)
-{
-    using Net = LearnedNet<R>;
-    constexpr int NCH = Net::NCH, HID = Net::HID, D = Net::D;
-    const int net = blockIdx.x, set = blockIdx.y;
-    const Net nt(P + (size_t)set * p_len + (size_t)net * Net::LEN);
-    bf16_t *lx = LX + ((size_t)set * 2 + net) * NCH * 32 * 8;
-    float *lv = LV + ((size_t)set * 2 + net) * 2 * R;
-    for (int hid = threadIdx.x; hid < HID; hid += kWg) {
+    if (phase != 0) return;
+    // constants of the folded layer normalisations for the 32 hidden units of this chunk:
+    //   LX [set][net][NCH][32][8] bf16: (s1_hi, s1_hi, s1_lo, s1_lo, c1_hi, c1_hi, c1_lo, c1_lo) with
+    //      s1 = sum_k bf16(g1[k] W1[k][.]), c1 = sum_k b1[k] W1[k][.]   (fifth contraction step)
+    //   LVp [set][net][NCH][2][R] fp32: this chunk's part of s2 = sum_hid bf16(g2 W2), c2 = sum_hid b2 W2
+    {
+        const int i = tid & 31, kp = tid >> 5, hid = 32 * ch + i;
         float s1 = 0.f, c1 = 0.f;
-        for (int k = 0; k < D; ++k) {
+        for (int k = 8 * kp; k < 8 * kp + 8; ++k) {
             const float w = bf16_to_f32(nt.W1[(size_t)k * HID + hid]);
             s1 += bf16_to_f32(f32_to_bf16(bf16_to_f32(nt.g1[k]) * w));
             c1 += bf16_to_f32(nt.b1[k]) * w;
         }
-        const bf16_t s_hi = f32_to_bf16(s1), s_lo = f32_to_bf16(s1 - bf16_to_f32(s_hi));
-        const bf16_t c_hi = f32_to_bf16(c1), c_lo = f32_to_bf16(c1 - bf16_to_f32(c_hi));
-        bf16_t *o = lx + (size_t)hid * 8;
-        o[0] = s_hi; o[1] = s_hi; o[2] = s_lo; o[3] = s_lo; o[4] = c_hi; o[5] = c_hi; o[6] = c_lo; o[7] = c_lo;
+        red[0][tid] = s1;
+        red[1][tid] = c1;
+        __syncthreads();
+        if (tid < 32) {
+            s1 = c1 = 0.f;
+            for (int kk = 0; kk < D / 8; ++kk) { s1 += red[0][32 * kk + tid]; c1 += red[1][32 * kk + tid]; }
+            const bf16_t s_hi = f32_to_bf16(s1), s_lo = f32_to_bf16(s1 - bf16_to_f32(s_hi));
+            const bf16_t c_hi = f32_to_bf16(c1), c_lo = f32_to_bf16(c1 - bf16_to_f32(c_hi));
+            bf16_t *o = LX + ((((size_t)set * 2 + net) * NCH + ch) * 32 + tid) * 8;
+            o[0] = s_hi; o[1] = s_hi; o[2] = s_lo; o[3] = s_lo; o[4] = c_hi; o[5] = c_hi; o[6] = c_lo; o[7] = c_lo;
+        }
+        __syncthreads();
     }
-    for (int out = threadIdx.x; out < R; out += kWg) {
+    {
+        constexpr int GR = kWg / R, PER = 32 / GR;              // hidden units of the chunk per thread
+        const int out = tid % R, hp = tid / R;
         float s2 = 0.f, c2 = 0.f;
-        for (int hid = 0; hid < HID; ++hid) {
+        for (int hh = 0; hh < PER; ++hh) {
+            const int hid = 32 * ch + hp * PER + hh;
             const float w = bf16_to_f32(nt.W2[(size_t)hid * R + out]);
             s2 += bf16_to_f32(f32_to_bf16(bf16_to_f32(nt.g2[hid]) * w));
             c2 += bf16_to_f32(nt.b2[hid]) * w;
         }
-        lv[out] = s2;
-        lv[R + out] = c2;
+        red[0][tid] = s2;
+        red[1][tid] = c2;
+        __syncthreads();
+        if (tid < R) {
+            s2 = c2 = 0.f;
+            for (int g = 0; g < GR; ++g) { s2 += red[0][g * R + tid]; c2 += red[1][g * R + tid]; }
+            float *o = LVp + (((size_t)set * 2 + net) * NCH + ch) * 2 * R;
+            o[tid] = s2;
+            o[R + tid] = c2;
+        }
     }
 }
 
-// Workgroup = 256 consecutive tokens of one unit (wave = 2 tiles of 32 tokens); writes m(x)
-// as fp32 rows [rows][R].
-template <int R>
+// Workgroup = 256 consecutive tokens of one unit (wave = 2 tiles of 32 tokens).
+//   QSIDE: writes m(x) as bf16 rows [rows][R].
+//   key side: the last layer runs with the operand roles swapped, so that lanes hold sketch
+//   columns and registers tokens; writes the token octets [rows/8][2][R][4] fp32 and the
+//   workgroup's S = m^T m (R x R fp32, from the bf16 m like the random-sketch kernel does).
+template <int R, bool QSIDE>
 __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restrict__ X,
                                                            const bf16_t *__restrict__ LW,
                                                            const bf16_t *__restrict__ LX,
-                                                           const float *__restrict__ LV,
-                                                           float *__restrict__ M32, int n, int heads,
+                                                           const float *__restrict__ LVp,
+                                                           bf16_t *__restrict__ M_rm, float *__restrict__ M8,
+                                                           float *__restrict__ Spart, int n, int heads,
                                                            int per_head)
 {
     using Net = LearnedNet<R>;
@@ -1296,6 +1310,7 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
     __shared__ __attribute__((aligned(16))) unsigned char ring[kLsRing * kLsSlotBytes];
     __shared__ __attribute__((aligned(16))) bf16_t lx[2 * NCH * 32 * 8];
     __shared__ __attribute__((aligned(16))) float lv[2 * 2 * R];
+    __shared__ float red[QSIDE ? 1 : 4][QSIDE ? 1 : 32][33];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1315,7 +1330,13 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
     for (int q = 0; q < kLsRing - 1; ++q) stage(q);
     for (int idx = tid; idx < 2 * NCH * 32 * 8 / 8; idx += kWg)
         ((uint4 *)lx)[idx] = ((const uint4 *)(LX + (size_t)set * 2 * NCH * 32 * 8))[idx];
-    for (int idx = tid; idx < 2 * 2 * R; idx += kWg) lv[idx] = LV[(size_t)set * 2 * 2 * R + idx];
+    for (int idx = tid; idx < 2 * 2 * R; idx += kWg) {     // s2, c2: sum of the per-chunk parts
+        const int net = idx / (2 * R), rest = idx % (2 * R);
+        const float *src = LVp + ((size_t)set * 2 + net) * NCH * 2 * R + rest;
+        float acc = 0.f;
+        for (int ch = 0; ch < NCH; ++ch) acc += src[(size_t)ch * 2 * R];
+        lv[idx] = acc;
+    }
 
     // input fragments (B operands of the first layer) and the statistics of the input rows
     bf16x8 xfr[TT][KS], xb[TT];
@@ -1337,7 +1358,7 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
         sum += __shfl_xor(sum, 32);
         sq += __shfl_xor(sq, 32);
         const float mean = sum * (1.0f / D), var = sq * (1.0f / D) - mean * mean;
-        const float sigma = sqrtf(var + 1e-6f);
+        const float sigma = sqrtf(fmaxf(var, 0.f) + 1e-6f);
         inv_x[tt] = 1.0f / sigma;
         // fifth contraction step: (-mean) s1 + sigma c1 with hi + lo pairs (half h = 0 only)
         const __bf16 m_hi = (__bf16)(-mean), m_lo = (__bf16)(-mean - (float)m_hi);
@@ -1369,8 +1390,8 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
 #pragma unroll
             for (int s = 0; s < KS; ++s) a1[s] = *(const bf16x8 *)(sl + ((s * 32 + x) * 2 + h) * 16);
             const bf16_t *lxr = lx + ((size_t)(net * NCH + ch) * 32 + x) * 8;
-            const bf16x8 zero8 = {(__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f, (__bf16)0.f};
-            const bf16x8 a1x = h == 0 ? *(const bf16x8 *)lxr : zero8;
+            const __bf16 z = (__bf16)0.0f;
+            const bf16x8 a1x = h == 0 ? *(const bf16x8 *)lxr : bf16x8{z, z, z, z, z, z, z, z};
 #pragma unroll
             for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
@@ -1448,8 +1469,13 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
                 const bf16x8 hf0 = cvt8_from16(acc, 0), hf1 = cvt8_from16(acc, 8);
 #pragma unroll
                 for (int ot = 0; ot < OT; ++ot) {
-                    out[tt][ot] = mfma32(a4[ot][0], hf0, out[tt][ot]);
-                    out[tt][ot] = mfma32(a4[ot][1], hf1, out[tt][ot]);
+                    if (QSIDE) {                           // [feature][token]
+                        out[tt][ot] = mfma32(a4[ot][0], hf0, out[tt][ot]);
+                        out[tt][ot] = mfma32(a4[ot][1], hf1, out[tt][ot]);
+                    } else {                               // [token][feature]: lanes = sketch columns
+                        out[tt][ot] = mfma32(hf0, a4[ot][0], out[tt][ot]);
+                        out[tt][ot] = mfma32(hf1, a4[ot][1], out[tt][ot]);
+                    }
                 }
             }
         }
@@ -1461,30 +1487,95 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
         } else {
             const float sr = sqrtf((float)R), isr = 1.0f / sr;
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                const size_t row = row0 + wave * 64 + 32 * tt + x;
+            for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
                 for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
-                    for (int g4 = 0; g4 < 4; ++g4) {
-                        f32x4 m4;
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            m4[j] = sr * tanh_fast(f1[tt][ot][4 * g4 + j] * out[tt][ot][4 * g4 + j] * isr);
-                        *(f32x4 *)&M32[row * R + 32 * ot + 8 * g4 + 4 * h] = m4;
-                    }
-            }
+                    for (int v = 0; v < 16; ++v) f1[tt][ot][v] = sr * tanh_fast(f1[tt][ot][v] * out[tt][ot][v] * isr);
         }
     }
     wait_vmem_le<0>();                                     // drain the clamped copies
+
+    // ---- f1 now holds m ----
+    if (QSIDE) {
+        // lane = token x, register v = sketch column 32 ot + 8 (v / 4) + 4 h + v % 4
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const size_t row = row0 + wave * 64 + 32 * tt + x;
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const f32x4 m4 = {f1[tt][ot][4 * g4], f1[tt][ot][4 * g4 + 1], f1[tt][ot][4 * g4 + 2],
+                                      f1[tt][ot][4 * g4 + 3]};
+                    *(bf16x4 *)&M_rm[row * R + 32 * ot + 8 * g4 + 4 * h] = cvt4(m4);
+                }
+        }
+    } else {
+        // lane = sketch column 32 ot + x, register v = token 8 (v / 4) + 4 h + v % 4 of the tile
+        f32x16 sacc[OT][OT];
+#pragma unroll
+        for (int i = 0; i < OT; ++i)
+#pragma unroll
+            for (int j = 0; j < OT; ++j) sacc[i][j] = f32x16{0};
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const size_t tile0 = row0 + wave * 64 + 32 * tt;
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+                for (int g4 = 0; g4 < 4; ++g4) {
+                    const f32x4 m4 = {f1[tt][ot][4 * g4], f1[tt][ot][4 * g4 + 1], f1[tt][ot][4 * g4 + 2],
+                                      f1[tt][ot][4 * g4 + 3]};
+                    const size_t oct = (tile0 >> 3) + g4;
+                    *(f32x4 *)&M8[((oct * 2 + h) * R + 32 * ot + x) * 4] = m4;
+                }
+            // S += m^T m over the tile: the registers, eight at a time, are A and B fragments at
+            // once (k = token, same order on both sides)
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp) {
+                bf16x8 f[OT];
+#pragma unroll
+                for (int ot = 0; ot < OT; ++ot) f[ot] = cvt8_from16(f1[tt][ot], 8 * sp);
+#pragma unroll
+                for (int i = 0; i < OT; ++i)
+#pragma unroll
+                    for (int j = 0; j < OT; ++j) sacc[i][j] = mfma32(f[i], f[j], sacc[i][j]);
+            }
+        }
+        float *outp = Spart + (size_t)blockIdx.x * R * R;
+#pragma unroll
+        for (int i = 0; i < OT; ++i)
+#pragma unroll
+            for (int j = 0; j < OT; ++j) {
+                __syncthreads();
+#pragma unroll
+                for (int v = 0; v < 16; ++v) red[wave][8 * (v / 4) + 4 * h + (v % 4)][x] = sacc[i][j][v];
+                __syncthreads();
+                for (int idx = tid; idx < 32 * 32; idx += kWg) {
+                    const int a = idx / 32, c = idx % 32;
+                    outp[(size_t)(32 * i + a) * R + 32 * j + c] =
+                        red[0][a][c] + red[1][a][c] + red[2][a][c] + red[3][a][c];
+                }
+            }
+    }
 }
+
+int sketch_tiles_per_wg(int b);
 
 struct MfmaWs {
     bf16_t *Gt; bf16_t *MQ; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
     float *M32;                                  // learned sketches only: m(x) as fp32 rows
-    bf16_t *LW, *LX; float *LV;                  // learned sketches on MFMA: arranged weights
+    bf16_t *LW, *LX; float *LVp;                 // learned sketches on MFMA: arranged weights
     size_t total;
 };
+
+// Degree-4 learned sketches with d = 64 run on MFMA when a 256-token workgroup stays inside
+// one block; everything else goes through the general fp32 sketch kernel.
+bool learned_on_mfma(const Problem &pb) { return pb.learned && pb.p == 4 && pb.d == 64 && pb.b % 256 == 0; }
+
+// tokens per partial S = m^T m handed to the denominator scan
+int part_tokens(const Problem &pb) { return learned_on_mfma(pb) ? 256 : 128 * sketch_tiles_per_wg(pb.b); }
 
 int sketch_tiles_per_wg(int b)
 {
@@ -1498,7 +1589,7 @@ MfmaWs carve(const Problem &pb, void *ws)
     MfmaWs w;
     const size_t rows = (size_t)pb.units * pb.n, R = pb.r, D = pb.d, tb = pb.t > 1 ? pb.t - 1 : 0;
     const size_t sets = pb.per_head ? pb.heads : 1;
-    const size_t parts = rows / (128 * (size_t)sketch_tiles_per_wg(pb.b));
+    const size_t parts = rows / (size_t)part_tokens(pb);
     size_t off = 0;
     char *base = (char *)ws;
     auto take = [&](size_t bytes) { char *p = base + off; off += align_up(bytes, 256); return p; };
@@ -1510,12 +1601,12 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.Spart = (float *)take(parts * R * R * 4);
     w.Shi = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
     w.Slo = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
-    w.M32 = (float *)take(pb.learned ? rows * R * 4 : 0);
-    const bool fast_learned = pb.learned && pb.p == 4 && pb.d == 64;
+    const bool fast_learned = learned_on_mfma(pb);
+    w.M32 = (float *)take(pb.learned && !fast_learned ? rows * R * 4 : 0);
     const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
     w.LW = (bf16_t *)take(fast_learned ? sets * 4 * nch * kLsSlotBytes : 0);
     w.LX = (bf16_t *)take(fast_learned ? sets * 2 * nch * 32 * 8 * 2 : 0);
-    w.LV = (float *)take(fast_learned ? sets * 2 * 2 * R * 4 : 0);
+    w.LVp = (float *)take(fast_learned ? sets * 2 * nch * 2 * R * 4 : 0);
     w.total = off;
     return w;
 }
@@ -1552,38 +1643,39 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     const int tiles = sketch_tiles_per_wg(pb.b);
     psf_status st;
     if (pb.learned) {
-        // Algorithm 2 runs in the general fp32 sketch kernel; only the layouts are made here
         const size_t rows = (size_t)pb.units * pb.n, count = rows * R;
-        const int sets = pb.per_head ? pb.heads : 1;
-        auto sketch = [&](const void *X) -> psf_status {
-            if constexpr (P == 4 && D == 64) {              // degree 4 on MFMA
-                hipLaunchKernelGGL((k_learned_sketch<R>), dim3((unsigned)(rows / 256)), dim3(kWg), 0, s,
-                                   (const bf16_t *)X, w.LW, w.LX, w.LV, w.M32, pb.n, pb.heads, pb.per_head ? 1 : 0);
-                PSF_LAUNCH_CHECK();
-                return PSF_OK;
-            } else {
-                return general_sketch_f32(pb, X, G, w.M32, s);
-            }
-        };
+        bool fast = false;
         if constexpr (P == 4 && D == 64) {
-            hipLaunchKernelGGL((k_learned_prep<R>), dim3(4 * (R / 4), sets), dim3(kWg), 0, s, (const bf16_t *)G,
-                               pb.g_len, w.LW);
+            if (learned_on_mfma(pb)) {
+                fast = true;
+                const int sets = pb.per_head ? pb.heads : 1;
+                const unsigned grid = (unsigned)(rows / 256);
+                hipLaunchKernelGGL((k_learned_prep<R>), dim3(4 * (R / 4), sets), dim3(kWg), 0, s,
+                                   (const bf16_t *)G, pb.g_len, w.LW, w.LX, w.LVp);
+                PSF_LAUNCH_CHECK();
+                hipLaunchKernelGGL((k_learned_sketch<R, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
+                                   w.LW, w.LX, w.LVp, w.MQ, nullptr, nullptr, pb.n, pb.heads,
+                                   pb.per_head ? 1 : 0);
+                PSF_LAUNCH_CHECK();
+                hipLaunchKernelGGL((k_learned_sketch<R, false>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)K,
+                                   w.LW, w.LX, w.LVp, nullptr, w.MK8, w.Spart, pb.n, pb.heads,
+                                   pb.per_head ? 1 : 0);
+                PSF_LAUNCH_CHECK();
+            }
+        }
+        if (!fast) {
+            // other degrees and shapes: the general fp32 sketch kernel, then the layouts
+            st = general_sketch_f32(pb, Q, G, w.M32, s);
+            if (st != PSF_OK) return st;
+            hipLaunchKernelGGL(k_m_to_bf16, dim3((unsigned)((count / 4 + kWg - 1) / kWg)), dim3(kWg), 0, s,
+                               w.M32, w.MQ, count);
             PSF_LAUNCH_CHECK();
-            hipLaunchKernelGGL((k_learned_prep_consts<R>), dim3(2, sets), dim3(kWg), 0, s, (const bf16_t *)G,
-                               pb.g_len, w.LX, w.LV);
+            st = general_sketch_f32(pb, K, G, w.M32, s);
+            if (st != PSF_OK) return st;
+            hipLaunchKernelGGL((k_m_to_octets_and_partials<R>), dim3((unsigned)(rows / part_tokens(pb))),
+                               dim3(kWg), 0, s, w.M32, w.MK8, w.Spart, part_tokens(pb));
             PSF_LAUNCH_CHECK();
         }
-        st = sketch(Q);
-        if (st != PSF_OK) return st;
-        hipLaunchKernelGGL(k_m_to_bf16, dim3((unsigned)((count / 4 + kWg - 1) / kWg)), dim3(kWg), 0, s, w.M32,
-                           w.MQ, count);
-        PSF_LAUNCH_CHECK();
-        st = sketch(K);
-        if (st != PSF_OK) return st;
-        const int part_tokens = 128 * tiles;
-        hipLaunchKernelGGL((k_m_to_octets_and_partials<R>), dim3((unsigned)(rows / part_tokens)), dim3(kWg), 0, s,
-                           w.M32, w.MK8, w.Spart, part_tokens);
-        PSF_LAUNCH_CHECK();
     } else {
         st = launch_transpose_g(pb, G, w.Gt, s);
         if (st != PSF_OK) return st;
@@ -1601,7 +1693,7 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     if (tm) tm->mark();
     if (pb.t > 1) {
         hipLaunchKernelGGL((k_den_scan<R>), dim3(R * R / kWg, pb.units), dim3(kWg), 0, s, w.Spart, w.Shi,
-                           w.Slo, pb.t, pb.b / (128 * tiles));
+                           w.Slo, pb.t, pb.b / part_tokens(pb));
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
