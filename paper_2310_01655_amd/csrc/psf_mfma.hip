@@ -1204,7 +1204,7 @@ struct LearnedNet {
 //            [4 KB, ..) W4 fragments, arranged like W2' without the scale.
 template <int R>
 __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__ P, size_t p_len,
-                                                      bf16_t *__restrict__ LW, bf16_t *__restrict__ LX,
+                                                      bf16_t *__restrict__ LW, float *__restrict__ C1,
                                                       float *__restrict__ LVp)
 {
     using Net = LearnedNet<R>;
@@ -1242,27 +1242,19 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
     }
     if (phase != 0) return;
     // constants of the folded layer normalisations for the 32 hidden units of this chunk:
-    //   LX [set][net][NCH][32][8] bf16: (s1_hi, s1_hi, s1_lo, s1_lo, c1_hi, c1_hi, c1_lo, c1_lo) with
-    //      s1 = sum_k bf16(g1[k] W1[k][.]), c1 = sum_k b1[k] W1[k][.]   (fifth contraction step)
+    //   C1 [set][net][NCH][32] fp32: c1 = sum_k b1[k] W1[k][.]  (the accumulators of the input layer start there)
     //   LVp [set][net][NCH][2][R] fp32: this chunk's part of s2 = sum_hid bf16(g2 W2), c2 = sum_hid b2 W2
     {
         const int i = tid & 31, kp = tid >> 5, hid = 32 * ch + i;
-        float s1 = 0.f, c1 = 0.f;
-        for (int k = 8 * kp; k < 8 * kp + 8; ++k) {
-            const float w = bf16_to_f32(nt.W1[(size_t)k * HID + hid]);
-            s1 += bf16_to_f32(f32_to_bf16(bf16_to_f32(nt.g1[k]) * w));
-            c1 += bf16_to_f32(nt.b1[k]) * w;
-        }
-        red[0][tid] = s1;
-        red[1][tid] = c1;
+        float c1 = 0.f;
+        for (int k = 8 * kp; k < 8 * kp + 8; ++k)
+            c1 += bf16_to_f32(nt.b1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + hid]);
+        red[0][tid] = c1;
         __syncthreads();
         if (tid < 32) {
-            s1 = c1 = 0.f;
-            for (int kk = 0; kk < D / 8; ++kk) { s1 += red[0][32 * kk + tid]; c1 += red[1][32 * kk + tid]; }
-            const bf16_t s_hi = f32_to_bf16(s1), s_lo = f32_to_bf16(s1 - bf16_to_f32(s_hi));
-            const bf16_t c_hi = f32_to_bf16(c1), c_lo = f32_to_bf16(c1 - bf16_to_f32(c_hi));
-            bf16_t *o = LX + ((((size_t)set * 2 + net) * NCH + ch) * 32 + tid) * 8;
-            o[0] = s_hi; o[1] = s_hi; o[2] = s_lo; o[3] = s_lo; o[4] = c_hi; o[5] = c_hi; o[6] = c_lo; o[7] = c_lo;
+            c1 = 0.f;
+            for (int kk = 0; kk < D / 8; ++kk) c1 += red[0][32 * kk + tid];
+            C1[(((size_t)set * 2 + net) * NCH + ch) * 32 + tid] = c1;
         }
         __syncthreads();
     }
@@ -1289,33 +1281,35 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
     }
 }
 
-// Workgroup = 256 consecutive tokens of one unit (wave = 2 tiles of 32 tokens).
+// Workgroup = 256 consecutive tokens of one unit, 8 / TT waves with TT tiles of 32 tokens each.
 //   QSIDE: writes m(x) as bf16 rows [rows][R].
 //   key side: the last layer runs with the operand roles swapped, so that lanes hold sketch
 //   columns and registers tokens; writes the token octets [rows/8][2][R][4] fp32 and the
 //   workgroup's S = m^T m (R x R fp32, from the bf16 m like the random-sketch kernel does).
-template <int R, bool QSIDE>
-__global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restrict__ X,
-                                                           const bf16_t *__restrict__ LW,
-                                                           const bf16_t *__restrict__ LX,
-                                                           const float *__restrict__ LVp,
-                                                           bf16_t *__restrict__ M_rm, float *__restrict__ M8,
-                                                           float *__restrict__ Spart, int n, int heads,
-                                                           int per_head)
+template <int R, bool QSIDE, int TT>
+__global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__restrict__ X,
+                                                                const bf16_t *__restrict__ LW,
+                                                                const float *__restrict__ C1,
+                                                                const float *__restrict__ LVp,
+                                                                bf16_t *__restrict__ M_rm,
+                                                                float *__restrict__ M8,
+                                                                float *__restrict__ Spart, int n, int heads,
+                                                                int per_head)
 {
     using Net = LearnedNet<R>;
-    constexpr int NCH = Net::NCH, HID = Net::HID, D = 64, OT = R / 32, TT = 2, KS = D / 16, RS = R / 16;
+    constexpr int NCH = Net::NCH, HID = Net::HID, D = 64, OT = R / 32, KS = D / 16, RS = R / 16;
+    constexpr int NW = 8 / TT, NTHR = 64 * NW;             // waves, threads
     constexpr int QN = 4 * NCH;                            // slots of the weight stream
-    constexpr int DMA = kLsSlotBytes / 16 / kWg;           // copies per thread and slot
+    constexpr int DMA = kLsSlotBytes / 16 / NTHR;          // copies per thread and slot
+    static_assert(NW * 32 * 32 * 4 <= kLsRing * kLsSlotBytes, "the reduction of S reuses the ring");
     __shared__ __attribute__((aligned(16))) unsigned char ring[kLsRing * kLsSlotBytes];
-    __shared__ __attribute__((aligned(16))) bf16_t lx[2 * NCH * 32 * 8];
+    __shared__ __attribute__((aligned(16))) float c1s[2 * NCH * 32];
     __shared__ __attribute__((aligned(16))) float lv[2 * 2 * R];
-    __shared__ float red[QSIDE ? 1 : 4][QSIDE ? 1 : 32][33];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int x = lane & 31, h = lane >> 5;
-    const size_t row0 = (size_t)blockIdx.x * (kWg * TT / 2);          // 256 tokens per workgroup
+    const size_t row0 = (size_t)blockIdx.x * 256;
     const int set = per_head ? (int)((row0 / n) % heads) : 0;
     const unsigned char *stream = (const unsigned char *)(LW + (size_t)set * QN * (kLsSlotBytes / 2));
     const uint32_t ring0 = lds_address(ring);
@@ -1324,13 +1318,13 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
         const uint32_t dst = ring0 + (q % kLsRing) * kLsSlotBytes + wave * 1024;
 #pragma unroll
         for (int c = 0; c < DMA; ++c)
-            dma16_sbase(stream + (size_t)qc * kLsSlotBytes + c * 4096, (uint32_t)tid * 16, dst + c * 4096);
+            dma16_sbase(stream + (size_t)qc * kLsSlotBytes + c * (NTHR * 16), (uint32_t)tid * 16,
+                        dst + c * (NTHR * 16));
     };
 #pragma unroll
     for (int q = 0; q < kLsRing - 1; ++q) stage(q);
-    for (int idx = tid; idx < 2 * NCH * 32 * 8 / 8; idx += kWg)
-        ((uint4 *)lx)[idx] = ((const uint4 *)(LX + (size_t)set * 2 * NCH * 32 * 8))[idx];
-    for (int idx = tid; idx < 2 * 2 * R; idx += kWg) {     // s2, c2: sum of the per-chunk parts
+    for (int idx = tid; idx < 2 * NCH * 32; idx += NTHR) c1s[idx] = C1[(size_t)set * 2 * NCH * 32 + idx];
+    for (int idx = tid; idx < 2 * 2 * R; idx += NTHR) {    // s2, c2: sum of the per-chunk parts
         const int net = idx / (2 * R), rest = idx % (2 * R);
         const float *src = LVp + ((size_t)set * 2 + net) * NCH * 2 * R + rest;
         float acc = 0.f;
@@ -1338,33 +1332,31 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
         lv[idx] = acc;
     }
 
-    // input fragments (B operands of the first layer) and the statistics of the input rows
-    bf16x8 xfr[TT][KS], xb[TT];
-    float inv_x[TT];
+    // B operands of the first layer: the rows of X, normalised (zero mean, unit variance)
+    bf16x8 xfr[TT][KS];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-        const size_t row = row0 + wave * 64 + 32 * tt + x;
+        const size_t row = row0 + wave * (32 * TT) + 32 * tt + x;
+        float xv[KS][8];
         float sum = 0.f, sq = 0.f;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            xfr[tt][s] = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
+            const bf16x8 raw = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float v = (float)xfr[tt][s][e];
-                sum += v;
-                sq += v * v;
+                xv[s][e] = (float)raw[e];
+                sum += xv[s][e];
+                sq += xv[s][e] * xv[s][e];
             }
         }
         sum += __shfl_xor(sum, 32);
         sq += __shfl_xor(sq, 32);
         const float mean = sum * (1.0f / D), var = sq * (1.0f / D) - mean * mean;
-        const float sigma = sqrtf(fmaxf(var, 0.f) + 1e-6f);
-        inv_x[tt] = 1.0f / sigma;
-        // fifth contraction step: (-mean) s1 + sigma c1 with hi + lo pairs (half h = 0 only)
-        const __bf16 m_hi = (__bf16)(-mean), m_lo = (__bf16)(-mean - (float)m_hi);
-        const __bf16 g_hi = (__bf16)sigma, g_lo = (__bf16)(sigma - (float)g_hi);
-        const __bf16 z = (__bf16)0.0f;
-        xb[tt] = h == 0 ? bf16x8{m_hi, m_lo, m_hi, m_lo, g_hi, g_lo, g_hi, g_lo} : bf16x8{z, z, z, z, z, z, z, z};
+        const float inv = rsqrtf(fmaxf(var, 0.f) + 1e-6f);
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xfr[tt][s][e] = (__bf16)((xv[s][e] - mean) * inv);
     }
 
     f32x16 f1[TT][OT];
@@ -1389,9 +1381,13 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
             bf16x8 a1[KS], a2[OT][2];
 #pragma unroll
             for (int s = 0; s < KS; ++s) a1[s] = *(const bf16x8 *)(sl + ((s * 32 + x) * 2 + h) * 16);
-            const bf16_t *lxr = lx + ((size_t)(net * NCH + ch) * 32 + x) * 8;
-            const __bf16 z = (__bf16)0.0f;
-            const bf16x8 a1x = h == 0 ? *(const bf16x8 *)lxr : bf16x8{z, z, z, z, z, z, z, z};
+            f32x16 init;                                   // b1 W1 of this chunk's hidden rows
+#pragma unroll
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const f32x4 c = *(const f32x4 *)&c1s[(net * NCH + ch) * 32 + 8 * g4 + 4 * h];
+#pragma unroll
+                for (int j2 = 0; j2 < 4; ++j2) init[4 * g4 + j2] = c[j2];
+            }
 #pragma unroll
             for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
@@ -1399,13 +1395,12 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
                     a2[ot][s] = *(const bf16x8 *)(sl + 4096 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                f32x16 acc = {0};
+                f32x16 acc = init;
 #pragma unroll
                 for (int s = 0; s < KS; ++s) acc = mfma32(a1[s], xfr[tt][s], acc);
-                acc = mfma32(a1x, xb[tt], acc);
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float hv = gelu_fast(acc[v] * inv_x[tt]);
+                    const float hv = gelu_fast(acc[v]);
                     sh[tt] += hv;
                     sqh[tt] += hv * hv;
                     acc[v] = hv;
@@ -1432,8 +1427,8 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
                     const f32x4 s2 = *(const f32x4 *)&lv[(net * 2 + 0) * R + 32 * ot + 8 * g4 + 4 * h];
                     const f32x4 c2 = *(const f32x4 *)&lv[(net * 2 + 1) * R + 32 * ot + 8 * g4 + 4 * h];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc2[tt][ot][4 * g4 + j] = (acc2[tt][ot][4 * g4 + j] - mean * s2[j]) * inv + c2[j];
+                    for (int j2 = 0; j2 < 4; ++j2)
+                        acc2[tt][ot][4 * g4 + j2] = (acc2[tt][ot][4 * g4 + j2] - mean * s2[j2]) * inv + c2[j2];
                 }
                 h2f[tt][2 * ot] = cvt8_from16(acc2[tt][ot], 0);
                 h2f[tt][2 * ot + 1] = cvt8_from16(acc2[tt][ot], 8);
@@ -1501,7 +1496,7 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
         // lane = token x, register v = sketch column 32 ot + 8 (v / 4) + 4 h + v % 4
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
-            const size_t row = row0 + wave * 64 + 32 * tt + x;
+            const size_t row = row0 + wave * (32 * TT) + 32 * tt + x;
 #pragma unroll
             for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
@@ -1517,10 +1512,10 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
 #pragma unroll
         for (int i = 0; i < OT; ++i)
 #pragma unroll
-            for (int j = 0; j < OT; ++j) sacc[i][j] = f32x16{0};
+            for (int j2 = 0; j2 < OT; ++j2) sacc[i][j2] = f32x16{0};
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
-            const size_t tile0 = row0 + wave * 64 + 32 * tt;
+            const size_t tile0 = row0 + wave * (32 * TT) + 32 * tt;
 #pragma unroll
             for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
@@ -1540,22 +1535,25 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_sketch(const bf16_t *__restr
 #pragma unroll
                 for (int i = 0; i < OT; ++i)
 #pragma unroll
-                    for (int j = 0; j < OT; ++j) sacc[i][j] = mfma32(f[i], f[j], sacc[i][j]);
+                    for (int j2 = 0; j2 < OT; ++j2) sacc[i][j2] = mfma32(f[i], f[j2], sacc[i][j2]);
             }
         }
         float *outp = Spart + (size_t)blockIdx.x * R * R;
+        float *red = (float *)ring;                        // [NW][32][32]; the ring is idle by now
 #pragma unroll
         for (int i = 0; i < OT; ++i)
 #pragma unroll
-            for (int j = 0; j < OT; ++j) {
+            for (int j2 = 0; j2 < OT; ++j2) {
                 __syncthreads();
 #pragma unroll
-                for (int v = 0; v < 16; ++v) red[wave][8 * (v / 4) + 4 * h + (v % 4)][x] = sacc[i][j][v];
+                for (int v = 0; v < 16; ++v)
+                    red[(wave * 32 + 8 * (v / 4) + 4 * h + (v % 4)) * 32 + x] = sacc[i][j2][v];
                 __syncthreads();
-                for (int idx = tid; idx < 32 * 32; idx += kWg) {
-                    const int a = idx / 32, c = idx % 32;
-                    outp[(size_t)(32 * i + a) * R + 32 * j + c] =
-                        red[0][a][c] + red[1][a][c] + red[2][a][c] + red[3][a][c];
+                for (int idx = tid; idx < 32 * 32; idx += NTHR) {
+                    float sum = 0.f;
+#pragma unroll
+                    for (int wv = 0; wv < NW; ++wv) sum += red[wv * 1024 + idx];
+                    outp[(size_t)(32 * i + idx / 32) * R + 32 * j2 + idx % 32] = sum;
                 }
             }
     }
@@ -1566,7 +1564,7 @@ int sketch_tiles_per_wg(int b);
 struct MfmaWs {
     bf16_t *Gt; bf16_t *MQ; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
     float *M32;                                  // learned sketches only: m(x) as fp32 rows
-    bf16_t *LW, *LX; float *LVp;                 // learned sketches on MFMA: arranged weights
+    bf16_t *LW; float *C1, *LVp;                 // learned sketches on MFMA: arranged weights
     size_t total;
 };
 
@@ -1605,7 +1603,7 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.M32 = (float *)take(pb.learned && !fast_learned ? rows * R * 4 : 0);
     const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
     w.LW = (bf16_t *)take(fast_learned ? sets * 4 * nch * kLsSlotBytes : 0);
-    w.LX = (bf16_t *)take(fast_learned ? sets * 2 * nch * 32 * 8 * 2 : 0);
+    w.C1 = (float *)take(fast_learned ? sets * 2 * nch * 32 * 4 : 0);
     w.LVp = (float *)take(fast_learned ? sets * 2 * nch * 2 * R * 4 : 0);
     w.total = off;
     return w;
@@ -1651,14 +1649,15 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
                 const int sets = pb.per_head ? pb.heads : 1;
                 const unsigned grid = (unsigned)(rows / 256);
                 hipLaunchKernelGGL((k_learned_prep<R>), dim3(4 * (R / 4), sets), dim3(kWg), 0, s,
-                                   (const bf16_t *)G, pb.g_len, w.LW, w.LX, w.LVp);
+                                   (const bf16_t *)G, pb.g_len, w.LW, w.C1, w.LVp);
                 PSF_LAUNCH_CHECK();
-                hipLaunchKernelGGL((k_learned_sketch<R, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
-                                   w.LW, w.LX, w.LVp, w.MQ, nullptr, nullptr, pb.n, pb.heads,
+                constexpr int TT = 1;                       // 8 waves of one tile: two waves per SIMD
+                hipLaunchKernelGGL((k_learned_sketch<R, true, TT>), dim3(grid), dim3(512 / TT), 0, s,
+                                   (const bf16_t *)Q, w.LW, w.C1, w.LVp, w.MQ, nullptr, nullptr, pb.n, pb.heads,
                                    pb.per_head ? 1 : 0);
                 PSF_LAUNCH_CHECK();
-                hipLaunchKernelGGL((k_learned_sketch<R, false>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)K,
-                                   w.LW, w.LX, w.LVp, nullptr, w.MK8, w.Spart, pb.n, pb.heads,
+                hipLaunchKernelGGL((k_learned_sketch<R, false, TT>), dim3(grid), dim3(512 / TT), 0, s,
+                                   (const bf16_t *)K, w.LW, w.C1, w.LVp, nullptr, w.MK8, w.Spart, pb.n, pb.heads,
                                    pb.per_head ? 1 : 0);
                 PSF_LAUNCH_CHECK();
             }
