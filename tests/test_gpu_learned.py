@@ -1,6 +1,7 @@
 """GPU parity of the learned-sketch variant (Algorithm 2) against the float64 oracle, through
 the C ABI: the sketch entry point, the general fp32 attention path and the bf16 MFMA path
-(sketches from the fp32 kernel, then the MFMA state / output kernels)."""
+(degree 4 with d = 64: the MFMA network kernel; otherwise sketches from the fp32 kernel; then the
+MFMA state / output kernels)."""
 import numpy as np
 import pytest
 import torch
@@ -70,6 +71,50 @@ def test_attention_mfma_path_learned_bf16(d, p, r, b):
     torch.cuda.synchronize()
     want = oracle_rows(q, k, v, P, p, r, b)
     print("mfma learned", (d, p, r, b), assert_close(O.float().cpu().numpy(), want, "bf16", "mfma learned"))
+
+
+@pytest.mark.parametrize("per_head,heads,n,b,r", [(False, 3, 2048, 512, 64), (True, 3, 2048, 1024, 32),
+                                                  (True, 2, 1536, 768, 64)])
+def test_attention_mfma_learned_kernel_sets_and_blocks(per_head, heads, n, b, r):
+    """Degree 4, d = 64: the MFMA network kernel with shared and per-head parameters, several
+    256-token workgroups per block and several blocks."""
+    q, k, v, P, desc = case(2, heads, n, 64, 4, r, b, "bf16", per_head=per_head, seed=67)
+    assert psf.kernel_path(desc) == 1
+    O = psf.psf_causal_attn_fwd(desc, q.cuda(), k.cuda(), v.cuda(), P.cuda())
+    torch.cuda.synchronize()
+    want = oracle_rows(q, k, v, P, 4, r, b)
+    print("mfma learned sets", (per_head, heads, n, b, r),
+          assert_close(O.float().cpu().numpy(), want, "bf16", "mfma learned sets"))
+
+
+def test_config3_shape_learned_sampled_rows():
+    """The workload `bench.py --learned` times (config 3 shapes, per-head parameters), on sampled
+    rows of two units.  The oracle's network runs over all keys of the unit (in slices on a few
+    threads: its C loops release the interpreter lock), the weights of the sampled rows are then
+    the definition written out: exact degree-4 inside the row's block, squared inner product of
+    the learned sketches before it, causal, `1 +` in the denominator."""
+    from concurrent.futures import ThreadPoolExecutor
+    from parity import probe_rows
+    cfg = dict(inputs.CONFIGS[3])
+    n, b, r, heads = cfg["n"], cfg["b"], cfg["r"], cfg["heads"]
+    q, k, v, P, desc = case(cfg["batch"], heads, n, cfg["d"], 4, r, b, "bf16", per_head=True, seed=1003)
+    assert psf.kernel_path(desc) == 1
+    O = psf.psf_causal_attn_fwd(desc, q.cuda(), k.cuda(), v.cuda(), P.cuda())
+    torch.cuda.synchronize()
+    got = O.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    rows = np.array(probe_rows(n, b))
+    for bi, h in ((0, 0), (1, 7)):
+        Q, K, V, Ph = as_f64(q[bi, h]), as_f64(k[bi, h]), as_f64(v[bi, h]), as_f64(P[h])
+        with ThreadPoolExecutor(8) as ex:
+            parts = list(ex.map(lambda lo: oracle.sketch_learned(K[lo:lo + 2048], Ph, r, 4), range(0, n, 2048)))
+        MK = np.concatenate(parts)
+        MQ = oracle.sketch_learned(Q[rows], Ph, r, 4)
+        W = (MQ @ MK.T) ** 2
+        same = (rows[:, None] // b) == (np.arange(n)[None, :] // b)
+        W = np.where(same, (Q[rows] @ K.T) ** 4, W) * (np.arange(n)[None, :] <= rows[:, None])
+        want = (W @ V) / (1.0 + W.sum(1, keepdims=True))
+        print("config 3 learned", (bi, h), assert_close(got[bi, h][rows], want, "bf16", "config 3 learned"))
 
 
 def test_decode_with_learned_sketches():
