@@ -76,22 +76,45 @@ def bwd_stage_flops(cfg):
     return f
 
 
+def bwd_stage_flops_mfma(cfg):
+    """The same count by stage of the MFMA backward kernels (d = dv, p = 4)."""
+    U = cfg["batch"] * cfg["heads"]
+    n, d, r, b = cfg["n"], cfg["d"], cfg["r"], cfg["b"]
+    F, kc = r * r, d + 1
+    pairs = n * (b + 1) // 2
+    cross = 2 * (n - b) * F * kc
+    f = {
+        "forward_again": stage_flops(cfg)["total"],
+        "g_c_and_layouts": U * 4 * n * d,
+        "mirror_states": U * cross,
+        "cross_block": U * (3 * cross + 8 * (n - b) * F),                    # dm(q), dm(k), dV; S and Rc terms
+        "in_block": U * pairs * 2 * 7 * d,                                   # 3 + 4 tile products per pair
+        "sketch_gradient": U * 2 * 16 * n * d * r,                           # projections again + transposed products
+    }
+    f["total"] = sum(f.values())
+    return f
+
+
 def cpu_baseline_bwd(cfg, q, k, v, G, dO):
-    """The float64 gradient oracle (O(n^2) pair loop) on `cores` whole units."""
+    """The float64 gradient oracle (O(n^2) pair loop) on `cores` units; sequences longer than
+    8192 are cut to their first 8192 tokens (a prefix of a causal sequence is a smaller instance
+    of the same problem) so that the sample stays within tens of seconds."""
     import numpy as np
     import oracle
     cores = min(os.cpu_count() or 1, 16)
     units = min(cores, cfg["batch"] * cfg["heads"])
     sel = [(i // cfg["heads"], i % cfg["heads"]) for i in range(units)]
-    f64 = lambda t: np.stack([t[bi, h].double().numpy() for bi, h in sel])[None]
+    n_s = min(cfg["n"], 8192)
+    f64 = lambda t: np.stack([t[bi, h, :n_s].double().numpy() for bi, h in sel])[None]
     Gs = G.double().numpy()
     Gs = Gs[[h for _, h in sel]] if Gs.shape[0] > 1 else Gs
     t0 = time.perf_counter()
     *_, threads = oracle.attn_bwd_batch(f64(q), f64(k), f64(v), Gs, f64(dO), cfg["p"], cfg["r"], cfg["b"],
                                         max_threads=cores)
     dt = time.perf_counter() - t0
-    return {"value": units * cfg["n"] / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%d whole units of n=%d (float64 pair-by-pair gradient, O(n^2))" % (units, cfg["n"]),
+    return {"value": units * n_s / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%d units, first %d of n=%d tokens each (float64 pair-by-pair gradient, O(n^2))"
+                      % (units, n_s, cfg["n"]),
             "seconds_measured": dt}
 
 
@@ -118,21 +141,23 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
         _, st = psf.psf_causal_attn_bwd_timed(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream)
         for nm, ms in st.items():
             acc[nm] = acc.get(nm, 0.0) + ms / reps
-    fl = bwd_stage_flops(cfg)
+    mfma = psf.bwd_kernel_path(desc) == 3
+    fl = bwd_stage_flops_mfma(cfg) if mfma else bwd_stage_flops(cfg)
     dom = max(acc, key=lambda nm: acc[nm])
     achieved = fl[dom] / (acc[dom] * 1e-3) / 1e12
+    peak = MFMA_BF16_PEAK_TFLOPS if mfma else FP32_VALU_PEAK_TFLOPS
     out = {
         "metric": "causal_polysketch_attention_bwd_tokens_per_s",
         "value": cfg["batch"] * cfg["n"] * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if mfma else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "pass": "bwd", "batch": cfg["batch"], "heads": cfg["heads"],
                    "n": cfg["n"], "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
-                   "storage": cfg["dtype"], "kernel_path": "general_fp32"},
+                   "storage": cfg["dtype"], "kernel_path": "mfma_bf16" if mfma else "general_fp32"},
         "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
         "tflops": fl["total"] / (ms_per_step * 1e-3) / 1e12,
-        "roofline": {"kernel": dom, "bound": "alu", "achieved": achieved, "peak": FP32_VALU_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": None,
+        "roofline": {"kernel": dom, "bound": "mfma" if mfma else "alu", "achieved": achieved, "peak": peak,
+                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
                      "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc}},
     }
     if not args.no_cpu_baseline:
@@ -270,7 +295,7 @@ def main():
         return
     wl = workloads()
     if args.workload is None:
-        args.workload = "config3" if args.which == "fwd" else "config2"
+        args.workload = "config3"
     if args.workload not in wl:
         sys.exit("unknown workload %s; choose from %s" % (args.workload, ", ".join(sorted(wl))))
     cfg = wl[args.workload]

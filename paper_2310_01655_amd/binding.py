@@ -20,7 +20,7 @@ LOCAL_EXACT, LOCAL_SKETCH = 0, 1
 EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_len", "psf_learned_len",
            "psf_sketch",
            "psf_causal_attn_fwd", "psf_causal_attn_fwd_timed", "psf_stage_name",
-           "psf_status_string", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
+           "psf_status_string", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
            "psf_causal_attn_bwd_timed", "psf_decode_state_bytes", "psf_decode_reset",
            "psf_decode_step")
 
@@ -69,6 +69,8 @@ def lib():
         L.psf_causal_attn_fwd_timed.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp,
                                                 ctypes.POINTER(ctypes.c_float), ctypes.c_int32,
                                                 ctypes.POINTER(ctypes.c_int32)]
+        L.psf_bwd_kernel_path.restype = ctypes.c_int
+        L.psf_bwd_kernel_path.argtypes = [dp]
         L.psf_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.psf_bwd_workspace_bytes.argtypes = [dp]
         L.psf_causal_attn_bwd.restype = ctypes.c_int
@@ -226,6 +228,11 @@ def psf_causal_attn_fwd_timed(desc, Q, K, V, G, O=None, workspace=None, stream=N
     return O, {nm: float(ms[i]) for i, nm in enumerate(names)}
 
 
+def bwd_kernel_path(desc):
+    """2 = general fp32 kernels, 3 = MFMA kernels, -1 = invalid or unsupported."""
+    return lib().psf_bwd_kernel_path(ctypes.byref(desc))
+
+
 def bwd_workspace_bytes(desc):
     return lib().psf_bwd_workspace_bytes(ctypes.byref(desc))
 
@@ -276,7 +283,8 @@ def psf_causal_attn_bwd_timed(desc, Q, K, V, G, dO, workspace=None, stream=None)
                                          ctypes.byref(written))
     if st != PSF_OK:
         raise PsfError(st, "psf_causal_attn_bwd_timed")
-    names = [lib().psf_stage_name(2, i).decode() for i in range(written.value)]
+    path = lib().psf_bwd_kernel_path(ctypes.byref(desc))
+    names = [lib().psf_stage_name(path, i).decode() for i in range(written.value)]
     return grads, {nm: float(ms[i]) for i, nm in enumerate(names)}
 
 

@@ -110,6 +110,9 @@ static psf_status run_attn(const psf_desc *desc, const void *Q, const void *K, c
                                 : general_attn(pb, Q, K, V, G, O, ws, s, tm);
 }
 
+// The backward pass runs on MFMA for the shapes of the bf16 forward path it covers.
+static bool bwd_on_mfma(const Problem &pb) { return select_path(pb) == 1 && mfma_bwd_supported(pb); }
+
 static psf_status run_bwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
                           const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
                           size_t ws_bytes, void *stream, StageTimer *tm)
@@ -120,10 +123,12 @@ static psf_status run_bwd(const psf_desc *desc, const void *Q, const void *K, co
     if (!general_bwd_supported(pb)) return PSF_ERR_UNSUPPORTED;
     if (!Q || !K || !V || !dO || !dQ || !dK || !dV) return PSF_ERR_NULL;
     if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
-    const size_t need = general_bwd_workspace_bytes(pb);
+    const bool mfma = bwd_on_mfma(pb);
+    const size_t need = mfma ? mfma_bwd_workspace_bytes(pb) : general_bwd_workspace_bytes(pb);
     if (!ws) return PSF_ERR_NULL;
     if (ws_bytes < need) return PSF_ERR_WORKSPACE;
     if (((uintptr_t)ws & 255u) != 0) return PSF_ERR_WORKSPACE;
+    if (mfma) return mfma_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm);
     return general_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm);
 }
 
@@ -216,11 +221,18 @@ psf_status psf_causal_attn_fwd_timed(const psf_desc *desc, const void *Q, const 
     return st != PSF_OK ? st : st2;
 }
 
+int psf_bwd_kernel_path(const psf_desc *desc)
+{
+    Problem pb;
+    if (make_problem(desc, &pb) != PSF_OK || !general_bwd_supported(pb)) return -1;
+    return bwd_on_mfma(pb) ? 3 : 2;
+}
+
 size_t psf_bwd_workspace_bytes(const psf_desc *desc)
 {
     Problem pb;
     if (make_problem(desc, &pb) != PSF_OK || !general_bwd_supported(pb)) return 0;
-    return general_bwd_workspace_bytes(pb);
+    return bwd_on_mfma(pb) ? mfma_bwd_workspace_bytes(pb) : general_bwd_workspace_bytes(pb);
 }
 
 psf_status psf_causal_attn_bwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
@@ -295,6 +307,9 @@ const char *psf_stage_name(int path, int32_t stage)
     static const char *bwd[] = {"sketches", "forward_rows", "reverse_states", "query_side",
                                 "key_side", "sketch_gradient"};
     if (path == 2 && stage >= 0 && stage < 6) return bwd[stage];
+    static const char *bwd_mfma[] = {"forward_again", "g_c_and_layouts", "mirror_states", "cross_block",
+                                     "in_block", "sketch_gradient"};
+    if (path == 3 && stage >= 0 && stage < 6) return bwd_mfma[stage];
     static const char *general[] = {"sketch_q", "sketch_k", "block_states", "exclusive_scan",
                                     "output"};
     static const char *mfma[] = {"sketch_and_layouts", "denominator_scan", "block_states_scan",

@@ -55,6 +55,13 @@ psf_status general_attn_bwd(const Problem &pb, const void *Q, const void *K, con
                             const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
                             hipStream_t s, StageTimer *tm);
 
+// Backward pass on MFMA (bf16, d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0, random sketches).
+bool mfma_bwd_supported(const Problem &pb);
+size_t mfma_bwd_workspace_bytes(const Problem &pb);
+psf_status mfma_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+                         const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s,
+                         StageTimer *tm);
+
 // Token-by-token evaluation (fp32 kernels; sketch features only).
 bool decode_supported(const Problem &pb);
 size_t decode_state_bytes(const Problem &pb);

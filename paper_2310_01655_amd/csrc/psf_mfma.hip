@@ -681,14 +681,14 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
 // are in flight while the VALU works on the current one (x^p, mask, row sums, bf16 packing in
 // the in-block phase; the m_i[a] * T_a updates in the cross-block phase).
 // ------------------------------------------------------------------------------------
-template <int R, int D, int P, int TT>
+template <int R, int D, int P, int TT, bool DEN>
 __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                 const bf16_t *__restrict__ V8,
                                                 const bf16_t *__restrict__ MQ,
                                                 const bf16_t *__restrict__ Zg,
                                                 const bf16_t *__restrict__ Shi,
                                                 const bf16_t *__restrict__ Slo, bf16_t *__restrict__ O,
-                                                int n, int b, int t)
+                                                float *__restrict__ Den, int n, int b, int t)
 {
     constexpr int CT = D / 32, KS = D / 16, RS = R / 16, AT = R / 32;
     constexpr int TOK_WAVE = 32 * TT, TOK_WG = 4 * TOK_WAVE;
@@ -1086,6 +1086,7 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
         const float total = den[tt] + __shfl_xor(den[tt], 32);   // the two halves hold different keys / rows
         const float inv = 1.0f / (1.0f + total);
         const size_t row = urow + tok_w0 + 32 * tt + x;
+        if (DEN && h == 0) Den[row] = 1.0f + total;        // kept for the backward pass
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -1633,9 +1634,41 @@ psf_status launch_sketch(const Problem &pb, const void *X, const bf16_t *Gt, boo
     return PSF_OK;
 }
 
+// Running prefix states of (M8, V8) for every unit, snapshots into Zg.
+template <int D, int R>
+psf_status launch_state(const Problem &pb, const float *M8, const bf16_t *V8, bf16_t *Zg, hipStream_t s)
+{
+    // Symmetric deal (d = 64): only the (a, 16-wide column range) segments the output kernel
+    // reads.  For r = 32 it pays once the grid is a few workgroups per CU; small grids keep
+    // the full tiles with four per wave, which fill the CUs better.
+    constexpr int GROUPS = (R / 16) * (R / 16 + 1) / 2;
+    const unsigned grid_sym = (unsigned)(pb.units * GROUPS);
+    if (D == 64 && (R == 64 || grid_sym > 512)) {
+        if constexpr (D == 64) {
+            if (grid_sym <= 256)
+                hipLaunchKernelGGL((k_state<R, D, 2, true, 64, 1>), dim3(grid_sym), dim3(kWg), 0, s, M8, V8, Zg,
+                                   pb.n, pb.b, pb.t, pb.units);
+            else
+                hipLaunchKernelGGL((k_state<R, D, 2, true, 32, 2>), dim3(grid_sym), dim3(kWg), 0, s, M8, V8, Zg,
+                                   pb.n, pb.b, pb.t, pb.units);
+        }
+    } else if constexpr (!(D == 64 && R == 64)) {
+        constexpr int NA = (D == 64) ? 4 : 2;
+        constexpr int AG = NA * 4 / (R / 32);
+        const unsigned grid = (unsigned)(pb.units * (R / AG));
+        hipLaunchKernelGGL((k_state<R, D, NA, false, 64, 1>), dim3(grid), dim3(kWg), 0, s, M8, V8, Zg, pb.n,
+                           pb.b, pb.t, pb.units);
+    }
+    PSF_LAUNCH_CHECK();
+    return PSF_OK;
+}
+
+// Den (1 + sum of weights per row, fp32) and MK_rm (m(K) as bf16 rows) are extra outputs the
+// backward pass asks for; the forward entry point passes null.
 template <int D, int R, int P>
 psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
-                     void *O, void *ws, hipStream_t s, StageTimer *tm)
+                     void *O, void *ws, hipStream_t s, StageTimer *tm, float *Den = nullptr,
+                     bf16_t *MK_rm = nullptr)
 {
     MfmaWs w = carve(pb, ws);
     const int tiles = sketch_tiles_per_wg(pb.b);
@@ -1680,7 +1713,7 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         if (st != PSF_OK) return st;
         st = launch_sketch<D, R, P>(pb, Q, w.Gt, true, w.MQ, nullptr, nullptr, tiles, s);
         if (st != PSF_OK) return st;
-        st = launch_sketch<D, R, P>(pb, K, w.Gt, false, nullptr, w.MK8, w.Spart, tiles, s);
+        st = launch_sketch<D, R, P>(pb, K, w.Gt, false, MK_rm, w.MK8, w.Spart, tiles, s);
         if (st != PSF_OK) return st;
     }
     {
@@ -1697,28 +1730,8 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     }
     if (tm) tm->mark();
     if (pb.t > 1) {
-        // Symmetric deal (d = 64): only the (a, 16-wide column range) segments the output kernel
-        // reads.  For r = 32 it pays once the grid is a few workgroups per CU; small grids keep
-        // the full tiles with four per wave, which fill the CUs better.
-        constexpr int GROUPS = (R / 16) * (R / 16 + 1) / 2;
-        const unsigned grid_sym = (unsigned)(pb.units * GROUPS);
-        if (D == 64 && (R == 64 || grid_sym > 512)) {
-            if constexpr (D == 64) {
-                if (grid_sym <= 256)
-                    hipLaunchKernelGGL((k_state<R, D, 2, true, 64, 1>), dim3(grid_sym), dim3(kWg), 0, s, w.MK8,
-                                       w.V8, w.Zg, pb.n, pb.b, pb.t, pb.units);
-                else
-                    hipLaunchKernelGGL((k_state<R, D, 2, true, 32, 2>), dim3(grid_sym), dim3(kWg), 0, s, w.MK8,
-                                       w.V8, w.Zg, pb.n, pb.b, pb.t, pb.units);
-            }
-        } else if constexpr (!(D == 64 && R == 64)) {
-            constexpr int NA = (D == 64) ? 4 : 2;
-            constexpr int AG = NA * 4 / (R / 32);
-            const unsigned grid = (unsigned)(pb.units * (R / AG));
-            hipLaunchKernelGGL((k_state<R, D, NA, false, 64, 1>), dim3(grid), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
-                               pb.n, pb.b, pb.t, pb.units);
-        }
-        PSF_LAUNCH_CHECK();
+        st = launch_state<D, R>(pb, w.MK8, w.V8, w.Zg, s);
+        if (st != PSF_OK) return st;
     }
     if (tm) tm->mark();
     {
@@ -1726,17 +1739,40 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         // one workgroup per CU; it measured 1.7x slower than TT = 2 with two per CU.)
         constexpr int TT = (D == 64) ? 2 : 1;
         const unsigned grid = (unsigned)((size_t)pb.units * (pb.n / (128 * TT)));
-        hipLaunchKernelGGL((k_out<R, D, P, TT>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
-                           (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, pb.n, pb.b, pb.t);
+        if (Den)
+            hipLaunchKernelGGL((k_out<R, D, P, TT, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
+                               (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b,
+                               pb.t);
+        else
+            hipLaunchKernelGGL((k_out<R, D, P, TT, false>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
+                               (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b,
+                               pb.t);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
     return PSF_OK;
 }
 
+#include "psf_mfma_bwd.inl"
+
 }  // namespace
 
 size_t mfma_workspace_bytes(const Problem &pb) { return carve(pb, nullptr).total; }
+
+bool mfma_bwd_supported(const Problem &pb)
+{
+    return pb.d == 64 && pb.dv == 64 && pb.p == 4 && (pb.r == 32 || pb.r == 64) && pb.b % 256 == 0 &&
+           !pb.learned && !pb.exact_feat && pb.local_exact;
+}
+
+size_t mfma_bwd_workspace_bytes(const Problem &pb) { return carve_bwd(pb, nullptr).total; }
+
+psf_status mfma_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+                         const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm)
+{
+    if (pb.r == 64) return attn_bwd_impl<64>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm);
+    return attn_bwd_impl<32>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm);
+}
 
 #define PSF_DISPATCH(CALL)                                                   \
     do {                                                                     \

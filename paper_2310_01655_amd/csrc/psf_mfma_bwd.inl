@@ -1,0 +1,810 @@
+// Backward pass on MFMA (bf16 storage, d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0).
+// Included inside the anonymous namespace of psf_mfma.hip, after the forward kernels it reuses.
+//
+// Gradient of the forward function of Sections 3, 3.1, 3.2 (the paper prints no formula; this is
+// the chain rule through the definition).  With C_j = [v_j | 1], row_i = sum_j w_ij C_j,
+// D_i = 1 + row_i[dv], o_i = row_i[0:dv] / D_i:
+//     g_i = dO_i / D_i,  c_i = -<dO_i, o_i> / D_i,  dw_ij = <g_i, v_j> + c_i,  dV_j = sum_i w_ij g_i
+// pairs inside a block:  w = <q, k>^p,        dq_i += sum_j dw_ij p <q_i, k_j>^(p-1) k_j   (dk alike)
+// pairs across blocks:   w = <m(q), m(k)>^2,  dm(q_i) = 2 sum_j dw_ij <m(q_i), m(k_j)> m(k_j) (dm(k) alike)
+// The cross-block sums are linear-time through the prefix states Z_l of Section 3.1 and their
+// mirror R_l = sum over later blocks of phi'(q_i) [g_i | c_i]^T:
+//     dm(q_i)[e] = 2 sum_{b,c} Z_l[e,b,c] m(q_i)[b] g_i[c]  +  2 c_i (S_l m(q_i))[e]
+//     dm(k_j)[e] = 2 sum_{b,c} R_l[e,b,c] m(k_j)[b] v_j[c]  +  2 (Rc_l m(k_j))[e]
+//     dV_j      +=   phi'(k_j)^T R_l            (the forward cross-block product with R in place of Z)
+// where S_l / Rc_l are the ones-column parts of the states.  Finally dq_i += J_m(q_i)^T dm(q_i)
+// through Algorithm 1 (p = 4: m = sqrt(1/r) (x G1) * (x G2)).
+
+template <int E>
+__device__ __forceinline__ float pow_n(float x)
+{
+    float r = x;
+#pragma unroll
+    for (int e = 1; e < E; ++e) r *= x;
+    return r;
+}
+
+// ---- g, c and the layouts of g ------------------------------------------------------------
+// One wave per token octet, lane = value column.  G_rm: g as bf16 rows; G8: octets [rows/8][D][8];
+// G8r: the same octets with the blocks of every unit in reverse order (input of the mirror
+// state kernel, which then is the forward state kernel unchanged); Cc: c as fp32.
+template <int D>
+__global__ __launch_bounds__(kWg) void k_bwd_prep(const bf16_t *__restrict__ dO, const bf16_t *__restrict__ O,
+                                                  const float *__restrict__ Den, bf16_t *__restrict__ G_rm,
+                                                  bf16_t *__restrict__ G8, bf16_t *__restrict__ G8r,
+                                                  float *__restrict__ Cc, int n, int b, int t)
+{
+    static_assert(D == 64, "one lane per value column");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t oct = (size_t)blockIdx.x * 4 + wave, row0 = oct * 8;
+    uint16_t gb[8];
+    float dot[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float d_o = bf16_to_f32(dO[(row0 + j) * D + lane]);
+        const float o = bf16_to_f32(O[(row0 + j) * D + lane]);
+        const float inv = 1.0f / Den[row0 + j];
+        gb[j] = f32_to_bf16(d_o * inv);
+        dot[j] = d_o * o * inv;
+        G_rm[(row0 + j) * D + lane] = gb[j];
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) dot[j] += __shfl_xor(dot[j], m);
+        if (lane == j) Cc[row0 + j] = -dot[j];
+    }
+    uint4 pk;
+    pk.x = gb[0] | ((uint32_t)gb[1] << 16);
+    pk.y = gb[2] | ((uint32_t)gb[3] << 16);
+    pk.z = gb[4] | ((uint32_t)gb[5] << 16);
+    pk.w = gb[6] | ((uint32_t)gb[7] << 16);
+    *(uint4 *)&G8[(oct * D + lane) * 8] = pk;
+    const size_t u = row0 / n, pos = row0 % n;
+    const size_t rpos = (size_t)(t - 1 - (int)(pos / b)) * b + pos % b;
+    *(uint4 *)&G8r[(((u * n + rpos) >> 3) * D + lane) * 8] = pk;
+}
+
+// ---- m(Q) octets in reverse block order and the c-weighted partial sums --------------------
+// Workgroup = 256 tokens: M8r [rows/8][2][R][4] fp32 (reverse block order) and
+// Sc = sum_i c_i m_i m_i^T (R x R fp32) at the part's reverse-order position.
+template <int R>
+__global__ __launch_bounds__(kWg) void k_bwd_qoct(const bf16_t *__restrict__ MQ, const float *__restrict__ Cc,
+                                                  float *__restrict__ M8r, float *__restrict__ ScPart, int n,
+                                                  int b, int t)
+{
+    constexpr int OT = R / 32;
+    __shared__ float red[4][32][33];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, x = lane & 31, h = lane >> 5;
+    const size_t row0 = (size_t)blockIdx.x * 256;
+    const size_t u = row0 / n, pos0 = row0 % n;
+    const size_t rrow0 = u * n + (size_t)(t - 1 - (int)(pos0 / b)) * b + pos0 % b;
+    f32x16 sacc[OT][OT];
+#pragma unroll
+    for (int i = 0; i < OT; ++i)
+#pragma unroll
+        for (int j = 0; j < OT; ++j) sacc[i][j] = f32x16{0};
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+        const size_t tile0 = row0 + wave * 64 + 32 * tt, rtile0 = rrow0 + wave * 64 + 32 * tt;
+        // lane = sketch column 32 ot + x, register v = token 8 (v / 4) + 4 h + v % 4
+        f32x16 m[OT], mw[OT];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const size_t tok = tile0 + 8 * (v / 4) + 4 * h + (v % 4);
+            const float cw = Cc[tok];
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot) {
+                m[ot][v] = bf16_to_f32(MQ[tok * R + 32 * ot + x]);
+                mw[ot][v] = m[ot][v] * cw;
+            }
+        }
+#pragma unroll
+        for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 q4 = {m[ot][4 * gq], m[ot][4 * gq + 1], m[ot][4 * gq + 2], m[ot][4 * gq + 3]};
+                const size_t oct = (rtile0 >> 3) + gq;
+                *(f32x4 *)&M8r[((oct * 2 + h) * R + 32 * ot + x) * 4] = q4;
+            }
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+            bf16x8 f[OT], fw[OT];
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot) {
+                f[ot] = cvt8_from16(m[ot], 8 * sp);
+                fw[ot] = cvt8_from16(mw[ot], 8 * sp);
+            }
+#pragma unroll
+            for (int i = 0; i < OT; ++i)
+#pragma unroll
+                for (int j = 0; j < OT; ++j) sacc[i][j] = mfma32(f[i], fw[j], sacc[i][j]);
+        }
+    }
+    float *out = ScPart + (rrow0 / 256) * R * R;
+#pragma unroll
+    for (int i = 0; i < OT; ++i)
+#pragma unroll
+        for (int j = 0; j < OT; ++j) {
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[wave][8 * (v / 4) + 4 * h + (v % 4)][x] = sacc[i][j][v];
+            __syncthreads();
+            for (int idx = tid; idx < 32 * 32; idx += kWg) {
+                const int a = idx / 32, c = idx % 32;
+                out[(size_t)(32 * i + a) * R + 32 * j + c] = red[0][a][c] + red[1][a][c] + red[2][a][c] + red[3][a][c];
+            }
+        }
+}
+
+// ---- state snapshots re-laid for the gradient ------------------------------------------------
+// In:  Zs [snap][a][b'/8][c][8], the format the state kernel writes (b' > a doubled, b' = a once,
+//      b' < a zero).  Out: ZT [snap][b][c/8][e][8] = Z[e][b][c], the full symmetric state with the
+//      value column as the contraction octet and the free sketch index e as the row of an MFMA A
+//      operand.  Workgroup = (octet of b, snapshot).
+template <int R, int D>
+__global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__ Zs, bf16_t *__restrict__ ZT)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t F[8][R][D];      // [b % 8][e][c]
+    const int tid = threadIdx.x, ob = blockIdx.x;
+    const bf16_t *src = Zs + (size_t)blockIdx.y * R * R * D;
+    bf16_t *dst = ZT + (size_t)blockIdx.y * R * R * D;
+    auto half = [](uint32_t bits) { return f32_to_bf16(0.5f * bf16_to_f32((bf16_t)bits)); };
+    // e < 8 ob: Z[e][b][c] = Zs[e][b][c] / 2 (b > e there)
+    for (int idx = tid; idx < 8 * ob * D; idx += kWg) {
+        const int e = idx / D, c = idx % D;
+        const uint4 pk = *(const uint4 *)&src[(((size_t)e * (R / 8) + ob) * D + c) * 8];
+        const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) F[j][e][c] = half((w[j / 2] >> (16 * (j % 2))) & 0xffffu);
+    }
+    // rows a of this octet, columns b' >= 8 ob
+    const int per_a = (R / 8 - ob) * D;
+    for (int idx = tid; idx < 8 * per_a; idx += kWg) {
+        const int a8 = idx / per_a, rem = idx % per_a, ob2 = ob + rem / D, c = rem % D;
+        const int a = 8 * ob + a8;
+        const uint4 pk = *(const uint4 *)&src[(((size_t)a * (R / 8) + ob2) * D + c) * 8];
+        const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int bp = 8 * ob2 + j;
+            const uint32_t bits = (w[j / 2] >> (16 * (j % 2))) & 0xffffu;
+            if (bp > a) {
+                const bf16_t v = half(bits);
+                F[a8][bp][c] = v;                          // (b = a, e = b')
+                if (ob2 == ob) F[j][a][c] = v;             // mirror inside the diagonal octet: (b = b', e = a)
+            } else if (bp == a) {
+                F[a8][a][c] = (bf16_t)bits;
+            }
+        }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < 8 * (D / 8) * R; idx += kWg) {
+        const int b8 = idx / ((D / 8) * R), c8 = (idx / R) % (D / 8), e = idx % R;
+        *(uint4 *)&dst[((((size_t)(8 * ob + b8)) * (D / 8) + c8) * R + e) * 8] = *(const uint4 *)&F[b8][e][8 * c8];
+    }
+}
+
+// ---- generic cross-block contraction ---------------------------------------------------------
+// out^T[o][token] += sum_{a < NS} sum_{k < NV} (sc_token[a] * vec_token[k]) * Z[a][k][o],  Z stored
+// [NS][NV/8][NO][8] bf16 (k octets innermost: 16-byte A fragments with rows o).  The B operand
+// (the products) is generated in registers from the token's scalar sc[a] and its vector vec[.],
+// which the caller holds as fp32 in contraction order (element e of step s = index 16 s + 8 h + e).
+// SYM: Z carries the symmetry weights of the state kernel, steps below 16 (a / 16) are skipped.
+// Workgroup = 128 TT tokens; rows of Z stream through LDS in chunks of ZA, double buffered.
+template <int NS, int NV, int NO, bool SYM, int TT>
+struct Cross {
+    static constexpr int CT = NO / 32, VS = NV / 16;
+    static constexpr int Z_PER = NV * NO;                      // bf16 elements per scalar index
+    static constexpr int ZA = 16384 / Z_PER;                   // scalar indices per chunk (32 KB)
+    static constexpr int CHUNK_BYTES = ZA * Z_PER * 2;
+    static constexpr int NCHUNK = NS / ZA;
+    static constexpr int LDS_BYTES = 2 * CHUNK_BYTES;
+    static constexpr int DMA = CHUNK_BYTES / 16 / kWg;
+    static_assert(ZA >= 1 && ZA <= 8 && 16 % ZA == 0 && NS % ZA == 0, "chunking");
+    typedef __bf16 scvec __attribute__((ext_vector_type(ZA)));
+
+    // sc_rows: bf16 rows [tokens][NS] of the workgroup's first token
+    static __device__ __forceinline__ void run(const bf16_t *__restrict__ sc_rows, const f32x8 (&vec)[TT][VS],
+                                               const bf16_t *__restrict__ Z, f32x16 (&out)[TT][CT],
+                                               unsigned char *stage)
+    {
+        const int tid = threadIdx.x, lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        const int x = lane & 31, h = lane >> 5;
+        auto copy_chunk = [&](int buf, int chunk) {
+            const bf16_t *src = Z + (size_t)chunk * ZA * Z_PER;
+#pragma unroll
+            for (int q = 0; q < DMA; ++q)
+                dma16(src + (size_t)(q * kWg + tid) * 8, stage + buf * CHUNK_BYTES + (size_t)(q * kWg + wave * 64) * 16);
+        };
+        auto load_sc = [&](int chunk, scvec (&dst)[TT]) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt)
+                dst[tt] = *(const scvec *)&sc_rows[(size_t)(wave * 32 * TT + 32 * tt + x) * NS + chunk * ZA];
+        };
+        scvec sc[TT], sc_next[TT];
+        copy_chunk(0, 0);
+        load_sc(0, sc);
+#pragma unroll 1
+        for (int chunk = 0; chunk < NCHUNK; ++chunk) {
+            const int buf = chunk & 1;
+            wait_vmem_le<0>();
+            __syncthreads();                               // chunk landed; the other buffer is free
+            if (chunk + 1 < NCHUNK) {
+                copy_chunk(buf ^ 1, chunk + 1);
+                load_sc(chunk + 1, sc_next);
+            }
+            const bf16_t *zc = (const bf16_t *)(stage + buf * CHUNK_BYTES);
+            const int s0 = SYM ? (chunk * ZA) / 16 : 0;
+#pragma unroll
+            for (int ai = 0; ai < ZA; ++ai) {
+                const bf16_t *za = zc + ai * Z_PER;
+#pragma unroll
+                for (int s = 0; s < VS; ++s) {
+                    if (s < s0) continue;
+                    bf16x8 zf[CT];
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) zf[ct] = *(const bf16x8 *)&za[((2 * s + h) * NO + 32 * ct + x) * 8];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        const float ma = (float)sc[tt][ai];
+                        f32x8 pr;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) pr[e] = ma * vec[tt][s][e];
+                        const bf16x8 frag = cvt8(pr);
+#pragma unroll
+                        for (int ct = 0; ct < CT; ++ct) out[tt][ct] = mfma32(zf[ct], frag, out[tt][ct]);
+                    }
+                }
+            }
+            if (chunk + 1 < NCHUNK) {
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) sc[tt] = sc_next[tt];
+            }
+        }
+        __syncthreads();                                   // the caller may reuse the stage
+    }
+};
+
+// ---- dm(q) and dm(k): cross-block part -------------------------------------------------------
+// QSIDE: tokens of block l >= 1 with ZT / S of slot l - 1, vec = g, coefficient c_i.
+// key side: tokens of block l <= t - 2 with RT / Rc of the mirror slot t - 2 - l, vec = v,
+// coefficient 1.  Blocks without a cross-block term get zeros.  dM: fp32 rows [rows][R].
+template <int R, int D, bool QSIDE, int TT>
+__global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M, const bf16_t *__restrict__ Vec,
+                                                  const float *__restrict__ Cc, const bf16_t *__restrict__ ZT,
+                                                  const bf16_t *__restrict__ Shi, const bf16_t *__restrict__ Slo,
+                                                  float *__restrict__ dM, int n, int b, int t)
+{
+    using X = Cross<R, D, R, false, TT>;
+    constexpr int AT = R / 32, RS = R / 16, VS = D / 16, TOK_WG = 128 * TT;
+    __shared__ __attribute__((aligned(16))) unsigned char stage[X::LDS_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tiles_per_unit = n / TOK_WG;
+    const int u = blockIdx.x / tiles_per_unit, i0 = (blockIdx.x % tiles_per_unit) * TOK_WG;
+    const int l = i0 / b;
+    const size_t urow = (size_t)u * n;
+    const bool has = QSIDE ? l > 0 : l < t - 1;
+    const int slot = QSIDE ? l - 1 : t - 2 - l;
+
+    f32x16 out[TT][AT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int at = 0; at < AT; ++at) out[tt][at] = f32x16{0};
+    if (has) {
+        f32x8 vec[TT][VS];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int s = 0; s < VS; ++s) {
+                const bf16x8 raw = *(const bf16x8 *)&Vec[(urow + i0 + wave * 32 * TT + 32 * tt + x) * D + 16 * s + 8 * h];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vec[tt][s][e] = (float)raw[e];
+            }
+        X::run(M + (urow + i0) * R, vec, ZT + ((size_t)u * (t - 1) + slot) * R * R * D, out, stage);
+
+        // ones column: (S m)[a] per token with S as hi + lo A operands [b'/8][a][8]
+        bf16x8 mfr[TT][RS];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int s = 0; s < RS; ++s)
+                mfr[tt][s] = *(const bf16x8 *)&M[(urow + i0 + wave * 32 * TT + 32 * tt + x) * R + 16 * s + 8 * h];
+        const size_t sbase = ((size_t)u * (t - 1) + slot) * R * R;
+#pragma unroll
+        for (int at = 0; at < AT; ++at) {
+            f32x16 td[TT];
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) td[tt] = f32x16{0};
+#pragma unroll
+            for (int s = 0; s < RS; ++s) {
+                const size_t off = sbase + ((size_t)(2 * s + h) * R + 32 * at + x) * 8;
+                const bf16x8 s_hi = *(const bf16x8 *)&Shi[off], s_lo = *(const bf16x8 *)&Slo[off];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    td[tt] = mfma32(s_hi, mfr[tt][s], td[tt]);
+                    td[tt] = mfma32(s_lo, mfr[tt][s], td[tt]);
+                }
+            }
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                const float coef = QSIDE ? Cc[urow + i0 + wave * 32 * TT + 32 * tt + x] : 1.0f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) out[tt][at][v] = 2.0f * (out[tt][at][v] + coef * td[tt][v]);
+            }
+        }
+    }
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const size_t row = urow + i0 + wave * 32 * TT + 32 * tt + x;
+#pragma unroll
+        for (int at = 0; at < AT; ++at)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 q4 = {out[tt][at][4 * gq], out[tt][at][4 * gq + 1], out[tt][at][4 * gq + 2],
+                                  out[tt][at][4 * gq + 3]};
+                *(f32x4 *)&dM[row * R + 32 * at + 8 * gq + 4 * h] = q4;
+            }
+    }
+}
+
+// ---- dV: cross-block part = phi'(k_j)^T R_l (value columns) ----------------------------------
+template <int R, int D, int TT>
+__global__ __launch_bounds__(kWg, 2) void k_bwd_dvc(const bf16_t *__restrict__ MK, const bf16_t *__restrict__ Rg,
+                                                   float *__restrict__ dVc, int n, int b, int t)
+{
+    using X = Cross<R, R, D, true, TT>;
+    constexpr int CT = D / 32, RS = R / 16, TOK_WG = 128 * TT;
+    __shared__ __attribute__((aligned(16))) unsigned char stage[X::LDS_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tiles_per_unit = n / TOK_WG;
+    const int u = blockIdx.x / tiles_per_unit, i0 = (blockIdx.x % tiles_per_unit) * TOK_WG;
+    const int l = i0 / b;
+    const size_t urow = (size_t)u * n;
+    f32x16 out[TT][CT];
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) out[tt][ct] = f32x16{0};
+    if (l < t - 1) {
+        f32x8 vec[TT][RS];
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int s = 0; s < RS; ++s) {
+                const bf16x8 raw = *(const bf16x8 *)&MK[(urow + i0 + wave * 32 * TT + 32 * tt + x) * R + 16 * s + 8 * h];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vec[tt][s][e] = (float)raw[e];
+            }
+        X::run(MK + (urow + i0) * R, vec, Rg + ((size_t)u * (t - 1) + (t - 2 - l)) * R * R * D, out, stage);
+    }
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const size_t row = urow + i0 + wave * 32 * TT + 32 * tt + x;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 q4 = {out[tt][ct][4 * gq], out[tt][ct][4 * gq + 1], out[tt][ct][4 * gq + 2],
+                                  out[tt][ct][4 * gq + 3]};
+                *(f32x4 *)&dVc[row * D + 32 * ct + 8 * gq + 4 * h] = q4;
+            }
+    }
+}
+
+// ---- in-block pairs ---------------------------------------------------------------------------
+// Both kernels: workgroup = 128 "own" rows (wave = 32, held in registers as B operands), the
+// other side streams through LDS in tiles of 64 rows, double buffered: its rows as
+// [D/8][64][8] (16-byte A fragments, contraction over d) and its octets [8][D][8] (A fragments
+// with contraction over the tile's rows).  Score tiles come out transposed (lane = own row,
+// registers = streamed rows), are turned into bf16 B operands with one half-wave swap per
+// register pair (as in the forward output kernel) and contracted with the octets.
+constexpr int kLocT = 64;                                   // streamed rows per tile
+constexpr int kLocRows = kLocT * 64 * 2;                    // bytes of one [D/8][64][8] / [8][D][8] array, D = 64
+
+// rows [j0, j0 + 64) of X ([.][64] bf16) -> LDS [8][64][8]
+__device__ __forceinline__ void loc_stage_rows(const bf16_t *X, size_t j0, unsigned char *dst, int tid, int wave)
+{
+#pragma unroll
+    for (int q = 0; q < kLocRows / 16 / kWg; ++q) {
+        const int slot = q * kWg + tid, key = slot % kLocT, doct = slot / kLocT;
+        dma16(X + (j0 + key) * 64 + 8 * doct, dst + (size_t)(q * kWg + wave * 64) * 16);
+    }
+}
+// octets of rows [j0, j0 + 64) of X8 ([rows/8][64][8]) -> LDS, straight copy
+__device__ __forceinline__ void loc_stage_octets(const bf16_t *X8, size_t j0, unsigned char *dst, int tid, int wave)
+{
+#pragma unroll
+    for (int q = 0; q < kLocRows / 16 / kWg; ++q)
+        dma16(X8 + j0 * 64 + (size_t)(q * kWg + tid) * 8, dst + (size_t)(q * kWg + wave * 64) * 16);
+}
+// 16 fp32 (lane = own row, register v = streamed row 8 (v / 4) + 4 h + v % 4) -> two bf16 B
+// fragments whose 8 entries are the streamed rows 16 sp + 8 h + e
+__device__ __forceinline__ void loc_pack(const f32x16 &w, bf16x8 (&pw)[2])
+{
+#pragma unroll
+    for (int sp = 0; sp < 2; ++sp) {
+        uint4 u = __builtin_bit_cast(uint4, cvt8_from16(w, 8 * sp));
+        const auto s0 = __builtin_amdgcn_permlane32_swap(u.x, u.z, false, false);
+        const auto s1 = __builtin_amdgcn_permlane32_swap(u.y, u.w, false, false);
+        u.x = s0[0]; u.z = s0[1]; u.y = s1[0]; u.w = s1[1];
+        pw[sp] = __builtin_bit_cast(bf16x8, u);
+    }
+}
+
+// dQ (in-block): own rows = queries, streamed = keys of the same block up to the diagonal.
+//   dq_i = sum_{j <= i} (<g_i, v_j> + c_i) p <q_i, k_j>^(p-1) k_j          -> dQacc fp32 rows
+template <int P>
+__global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                       const bf16_t *__restrict__ V, const bf16_t *__restrict__ K8,
+                                                       const bf16_t *__restrict__ G_rm, const float *__restrict__ Cc,
+                                                       float *__restrict__ dQacc, int n, int b)
+{
+    constexpr int D = 64, KS = 4, CT = 2, BUF = 3 * kLocRows;
+    __shared__ __attribute__((aligned(16))) unsigned char stage[2 * BUF];
+    const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tiles_per_unit = n / 128;
+    const int u = blockIdx.x / tiles_per_unit, i0 = (blockIdx.x % tiles_per_unit) * 128;
+    const int jb = (i0 / b) * b;
+    const size_t urow = (size_t)u * n;
+    const int tok0 = i0 + 32 * wave, tok = tok0 + x;
+    bf16x8 qfr[KS], gfr[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        qfr[s] = *(const bf16x8 *)&Q[(urow + tok) * D + 16 * s + 8 * h];
+        gfr[s] = *(const bf16x8 *)&G_rm[(urow + tok) * D + 16 * s + 8 * h];
+    }
+    const float c_me = Cc[urow + tok];
+    f32x16 dq[CT] = {f32x16{0}, f32x16{0}};
+    const int ntiles = (i0 + 128 - jb) / kLocT;
+    auto stage_tile = [&](int kt) {
+        unsigned char *dst = stage + (kt & 1) * BUF;
+        const size_t j0 = urow + jb + (size_t)kt * kLocT;
+        loc_stage_rows(K, j0, dst, tid, wave);
+        loc_stage_rows(V, j0, dst + kLocRows, tid, wave);
+        loc_stage_octets(K8, j0, dst + 2 * kLocRows, tid, wave);
+    };
+    stage_tile(0);
+#pragma unroll 1
+    for (int kt = 0; kt < ntiles; ++kt) {
+        wait_vmem_le<0>();
+        __syncthreads();
+        if (kt + 1 < ntiles) stage_tile(kt + 1);
+        const bf16_t *ks = (const bf16_t *)(stage + (kt & 1) * BUF);
+        const bf16_t *vs = ks + kLocRows / 2, *k8 = ks + kLocRows;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int key0 = jb + kt * kLocT + 32 * sub;
+            if (key0 > tok0 + 31) continue;                // wave-uniform: all keys later than all own tokens
+            f32x16 sc = {0}, dw = {0};
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const bf16x8 kf = *(const bf16x8 *)&ks[((2 * s + h) * kLocT + 32 * sub + x) * 8];
+                const bf16x8 vf = *(const bf16x8 *)&vs[((2 * s + h) * kLocT + 32 * sub + x) * 8];
+                sc = mfma32(kf, qfr[s], sc);
+                dw = mfma32(vf, gfr[s], dw);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
+                const float dp = (dw[v] + c_me) * (float)P * pow_n<P - 1>(sc[v]);
+                dw[v] = key <= tok ? dp : 0.f;
+            }
+            bf16x8 pw[2];
+            loc_pack(dw, pw);
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    const bf16x8 kf8 = *(const bf16x8 *)&k8[((4 * sub + 2 * sp + h) * D + 32 * ct + x) * 8];
+                    dq[ct] = mfma32(kf8, pw[sp], dq[ct]);
+                }
+        }
+    }
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const f32x4 q4 = {dq[ct][4 * gq], dq[ct][4 * gq + 1], dq[ct][4 * gq + 2], dq[ct][4 * gq + 3]};
+            *(f32x4 *)&dQacc[(urow + tok) * D + 32 * ct + 8 * gq + 4 * h] = q4;
+        }
+}
+
+// dK (in-block) and dV (in-block + the cross-block part already in dVc): own rows = keys,
+// streamed = queries of the same block from the diagonal on.
+//   dk_j = sum_{i >= j} (<g_i, v_j> + c_i) p <q_i, k_j>^(p-1) q_i   -> dKacc fp32 rows
+//   dv_j = sum_{i >= j} <q_i, k_j>^p g_i + dVc_j                     -> dV bf16 rows
+template <int P>
+__global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                       const bf16_t *__restrict__ V, const bf16_t *__restrict__ Q8,
+                                                       const bf16_t *__restrict__ G_rm, const bf16_t *__restrict__ G8,
+                                                       const float *__restrict__ Cc, const float *__restrict__ dVc,
+                                                       float *__restrict__ dKacc, bf16_t *__restrict__ dV, int n,
+                                                       int b)
+{
+    constexpr int D = 64, KS = 4, CT = 2, BUF = 4 * kLocRows + kLocT * 4;
+    __shared__ __attribute__((aligned(16))) unsigned char stage[2 * BUF];
+    const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tiles_per_unit = n / 128;
+    const int u = blockIdx.x / tiles_per_unit, j0 = (blockIdx.x % tiles_per_unit) * 128;
+    const int jb = (j0 / b) * b;
+    const size_t urow = (size_t)u * n;
+    const int key0 = j0 + 32 * wave, key = key0 + x;
+    bf16x8 kfr[KS], vfr[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        kfr[s] = *(const bf16x8 *)&K[(urow + key) * D + 16 * s + 8 * h];
+        vfr[s] = *(const bf16x8 *)&V[(urow + key) * D + 16 * s + 8 * h];
+    }
+    f32x16 dk[CT] = {f32x16{0}, f32x16{0}}, dv[CT] = {f32x16{0}, f32x16{0}};
+    const int first = (j0 - jb) / kLocT, ntiles = b / kLocT;
+    auto stage_tile = [&](int qt) {
+        unsigned char *dst = stage + (qt & 1) * BUF;
+        const size_t t0 = urow + jb + (size_t)qt * kLocT;
+        loc_stage_rows(Q, t0, dst, tid, wave);
+        loc_stage_rows(G_rm, t0, dst + kLocRows, tid, wave);
+        loc_stage_octets(Q8, t0, dst + 2 * kLocRows, tid, wave);
+        loc_stage_octets(G8, t0, dst + 3 * kLocRows, tid, wave);
+        if (tid < kLocT) ((float *)(dst + 4 * kLocRows))[tid] = Cc[t0 + tid];
+    };
+    stage_tile(first);
+#pragma unroll 1
+    for (int qt = first; qt < ntiles; ++qt) {
+        wait_all_memory();
+        __syncthreads();
+        if (qt + 1 < ntiles) stage_tile(qt + 1);
+        const bf16_t *qs = (const bf16_t *)(stage + (qt & 1) * BUF);
+        const bf16_t *gs = qs + kLocRows / 2, *q8 = qs + kLocRows, *g8 = qs + 3 * (kLocRows / 2);
+        const float *cs = (const float *)(stage + (qt & 1) * BUF + 4 * kLocRows);
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            const int t0 = jb + qt * kLocT + 32 * sub;
+            if (t0 + 31 < key0) continue;                  // wave-uniform: all tokens earlier than all own keys
+            f32x16 sc = {0}, dw = {0};
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                const bf16x8 qf = *(const bf16x8 *)&qs[((2 * s + h) * kLocT + 32 * sub + x) * 8];
+                const bf16x8 gf = *(const bf16x8 *)&gs[((2 * s + h) * kLocT + 32 * sub + x) * 8];
+                sc = mfma32(qf, kfr[s], sc);
+                dw = mfma32(gf, vfr[s], dw);
+            }
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 c4 = *(const f32x4 *)&cs[32 * sub + 8 * gq + 4 * h];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int v = 4 * gq + j, tokv = t0 + 8 * gq + 4 * h + j;
+                    const float s1 = sc[v], pm1 = pow_n<P - 1>(s1);
+                    const bool keep = key <= tokv;
+                    sc[v] = keep ? pm1 * s1 : 0.f;
+                    dw[v] = keep ? (dw[v] + c4[j]) * (float)P * pm1 : 0.f;
+                }
+            }
+            bf16x8 pww[2], pwp[2];
+            loc_pack(sc, pww);
+            loc_pack(dw, pwp);
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    const bf16x8 qf8 = *(const bf16x8 *)&q8[((4 * sub + 2 * sp + h) * D + 32 * ct + x) * 8];
+                    const bf16x8 gf8 = *(const bf16x8 *)&g8[((4 * sub + 2 * sp + h) * D + 32 * ct + x) * 8];
+                    dk[ct] = mfma32(qf8, pwp[sp], dk[ct]);
+                    dv[ct] = mfma32(gf8, pww[sp], dv[ct]);
+                }
+        }
+    }
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const size_t off = (urow + key) * D + 32 * ct + 8 * gq + 4 * h;
+            const f32x4 k4 = {dk[ct][4 * gq], dk[ct][4 * gq + 1], dk[ct][4 * gq + 2], dk[ct][4 * gq + 3]};
+            *(f32x4 *)&dKacc[off] = k4;
+            const f32x4 c4 = *(const f32x4 *)&dVc[off];
+            const f32x4 v4 = {dv[ct][4 * gq] + c4[0], dv[ct][4 * gq + 1] + c4[1], dv[ct][4 * gq + 2] + c4[2],
+                              dv[ct][4 * gq + 3] + c4[3]};
+            *(bf16x4 *)&dV[off] = cvt4(v4);
+        }
+}
+
+// ---- through Algorithm 1 (p = 4): dx = dXacc + sqrt(1/r) [(dm * (x G2)) G1^T + (dm * (x G1)) G2^T]
+// Workgroup = 128 tokens; Gt = transposed sketch matrices (as the forward sketch kernel stages
+// them) for the recomputed projections, G = the matrices as given ([d][r] rows) for the
+// transposed products, whose A fragments are read straight from them in accumulator order.
+template <int D, int R>
+__global__ __launch_bounds__(kWg) void k_bwd_sketch(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Gt,
+                                                    const bf16_t *__restrict__ G, const float *__restrict__ dM,
+                                                    const float *__restrict__ dXacc, bf16_t *__restrict__ dX,
+                                                    int n, int heads, int per_head, size_t g_len)
+{
+    __shared__ __attribute__((aligned(16))) SketchLds<D, R> lds;
+    constexpr int KS = D / 16, NT = R / 32, DT = D / 32;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, x = lane & 31, h = lane >> 5;
+    const size_t row = (size_t)blockIdx.x * 128 + wave * 32 + x;
+    const int head = (int)((((size_t)blockIdx.x * 128) / n) % heads);
+    const size_t goff = per_head ? (size_t)head * g_len : 0;
+    const float scale = sqrtf(1.0f / (float)R);
+    stage_gt<D, R, D>(lds.gt[0], Gt + goff);
+    stage_gt<D, R, D>(lds.gt[1], Gt + goff + (size_t)D * R);
+    bf16x8 xfr[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
+    __syncthreads();
+    f32x16 a0[NT], a1[NT];                                  // lane = token, register = sketch column
+    project<D, R, KS, true>(lds.gt[0], xfr, a0, x, h);
+    project<D, R, KS, true>(lds.gt[1], xfr, a1, x, h);
+    bf16x8 d0[2 * NT], d1[2 * NT];                          // B operands, contraction over sketch columns
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        f32x16 da0, da1;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const f32x4 m4 = *(const f32x4 *)&dM[row * R + 32 * ct + 8 * gq + 4 * h];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                da0[4 * gq + j] = scale * m4[j] * a1[ct][4 * gq + j];
+                da1[4 * gq + j] = scale * m4[j] * a0[ct][4 * gq + j];
+            }
+        }
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+            d0[2 * ct + sp] = cvt8_from16(da0, 8 * sp);
+            d1[2 * ct + sp] = cvt8_from16(da1, 8 * sp);
+        }
+    }
+    const bf16_t *g1 = G + goff, *g2 = G + goff + (size_t)D * R;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+        f32x16 acc = {0};
+#pragma unroll
+        for (int ks = 0; ks < 2 * NT; ++ks) {
+            // entries e of the step are sketch columns 16 ks + 8 (e / 4) + 4 h + e % 4
+            const size_t off = (size_t)(32 * dt + x) * R + 16 * ks + 4 * h;
+            const bf16x4 lo1 = *(const bf16x4 *)&g1[off], hi1 = *(const bf16x4 *)&g1[off + 8];
+            const bf16x4 lo2 = *(const bf16x4 *)&g2[off], hi2 = *(const bf16x4 *)&g2[off + 8];
+            bf16x8 f1, f2;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { f1[e] = lo1[e]; f1[4 + e] = hi1[e]; f2[e] = lo2[e]; f2[4 + e] = hi2[e]; }
+            acc = mfma32(f1, d0[ks], acc);
+            acc = mfma32(f2, d1[ks], acc);
+        }
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const size_t off = row * D + 32 * dt + 8 * gq + 4 * h;
+            const f32x4 base = *(const f32x4 *)&dXacc[off];
+            const f32x4 q4 = {acc[4 * gq] + base[0], acc[4 * gq + 1] + base[1], acc[4 * gq + 2] + base[2],
+                              acc[4 * gq + 3] + base[3]};
+            *(bf16x4 *)&dX[off] = cvt4(q4);
+        }
+    }
+}
+
+// ---- host ---------------------------------------------------------------------------------------
+struct MfmaBwdWs {
+    void *fwd;                                               // the forward workspace
+    bf16_t *O, *MK, *G_rm, *G8, *G8r, *Q8, *K8, *Rg, *ZT, *RT, *Rchi, *Rclo;
+    float *Den, *Cc, *M8r, *ScPart, *dMQ, *dMK, *dVc, *dQacc, *dKacc;
+    size_t total;
+};
+
+MfmaBwdWs carve_bwd(const Problem &pb, void *ws)
+{
+    MfmaBwdWs w;
+    const size_t rows = (size_t)pb.units * pb.n, R = pb.r, D = pb.d, tb = pb.t > 1 ? pb.t - 1 : 0;
+    const size_t snaps = (size_t)pb.units * tb;
+    size_t off = 0;
+    char *base = (char *)ws;
+    auto take = [&](size_t bytes) { char *p = base + off; off += align_up(bytes, 256); return (void *)p; };
+    w.fwd = take(carve(pb, nullptr).total);
+    w.O = (bf16_t *)take(rows * D * 2);
+    w.MK = (bf16_t *)take(rows * R * 2);
+    w.G_rm = (bf16_t *)take(rows * D * 2);
+    w.G8 = (bf16_t *)take(rows * D * 2);
+    w.G8r = (bf16_t *)take(rows * D * 2);
+    w.Q8 = (bf16_t *)take(rows * D * 2);
+    w.K8 = (bf16_t *)take(rows * D * 2);
+    w.Rg = (bf16_t *)take(snaps * R * R * D * 2);
+    w.ZT = (bf16_t *)take(snaps * R * R * D * 2);
+    w.RT = (bf16_t *)take(snaps * R * R * D * 2);
+    w.Rchi = (bf16_t *)take(snaps * R * R * 2);
+    w.Rclo = (bf16_t *)take(snaps * R * R * 2);
+    w.Den = (float *)take(rows * 4);
+    w.Cc = (float *)take(rows * 4);
+    w.M8r = (float *)take(rows * R * 4);
+    w.ScPart = (float *)take(rows / 256 * R * R * 4);
+    w.dMQ = (float *)take(rows * R * 4);
+    w.dMK = (float *)take(rows * R * 4);
+    w.dVc = (float *)take(rows * D * 4);
+    w.dQacc = (float *)take(rows * D * 4);
+    w.dKacc = (float *)take(rows * D * 4);
+    w.total = off;
+    return w;
+}
+
+template <int R>
+psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+                         const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm)
+{
+    constexpr int D = 64, P = 4, TT = 2;
+    MfmaBwdWs w = carve_bwd(pb, ws);
+    MfmaWs f = carve(pb, w.fwd);
+    const size_t rows = (size_t)pb.units * pb.n;
+    const bf16_t *q = (const bf16_t *)Q, *k = (const bf16_t *)K, *v = (const bf16_t *)V;
+    // forward pass again: O, the denominators, m(Q), m(K), the states Z_l and S_l
+    psf_status st = attn_impl<D, R, P>(pb, Q, K, V, G, w.O, w.fwd, s, nullptr, w.Den, w.MK);
+    if (st != PSF_OK) return st;
+    if (tm) tm->mark();
+    // g, c, layouts
+    hipLaunchKernelGGL((k_bwd_prep<D>), dim3((unsigned)(rows / 32)), dim3(kWg), 0, s, (const bf16_t *)dO, w.O,
+                       w.Den, w.G_rm, w.G8, w.G8r, w.Cc, pb.n, pb.b, pb.t);
+    PSF_LAUNCH_CHECK();
+    {
+        const size_t octets = rows / 8;
+        const unsigned grid = (unsigned)((octets * D + kWg - 1) / kWg);
+        hipLaunchKernelGGL((k_v_octets<D>), dim3(grid), dim3(kWg), 0, s, q, w.Q8, octets);
+        PSF_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_v_octets<D>), dim3(grid), dim3(kWg), 0, s, k, w.K8, octets);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    // mirror states R_l (the forward state kernel on block-reversed inputs), re-laid states
+    if (pb.t > 1) {
+        hipLaunchKernelGGL((k_bwd_qoct<R>), dim3((unsigned)(rows / 256)), dim3(kWg), 0, s, f.MQ, w.Cc, w.M8r,
+                           w.ScPart, pb.n, pb.b, pb.t);
+        PSF_LAUNCH_CHECK();
+        st = launch_state<D, R>(pb, w.M8r, w.G8r, w.Rg, s);
+        if (st != PSF_OK) return st;
+        hipLaunchKernelGGL((k_den_scan<R>), dim3(R * R / kWg, pb.units), dim3(kWg), 0, s, w.ScPart, w.Rchi, w.Rclo,
+                           pb.t, pb.b / 256);
+        PSF_LAUNCH_CHECK();
+        const dim3 grid(R / 8, (unsigned)((size_t)pb.units * (pb.t - 1)));
+        hipLaunchKernelGGL((k_bwd_relayout<R, D>), grid, dim3(kWg), 0, s, f.Zg, w.ZT);
+        PSF_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_bwd_relayout<R, D>), grid, dim3(kWg), 0, s, w.Rg, w.RT);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    // cross-block parts
+    {
+        const unsigned grid = (unsigned)(rows / (128 * TT));
+        hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm, w.Cc, w.ZT, f.Shi,
+                           f.Slo, w.dMQ, pb.n, pb.b, pb.t);
+        PSF_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_bwd_dm<R, D, false, TT>), dim3(grid), dim3(kWg), 0, s, w.MK, v, w.Cc, w.RT, w.Rchi,
+                           w.Rclo, w.dMK, pb.n, pb.b, pb.t);
+        PSF_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_bwd_dvc<R, D, TT>), dim3(grid), dim3(kWg), 0, s, w.MK, w.Rg, w.dVc, pb.n, pb.b, pb.t);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    // in-block parts
+    {
+        const unsigned grid = (unsigned)(rows / 128);
+        hipLaunchKernelGGL((k_bwd_local_q<P>), dim3(grid), dim3(kWg), 0, s, q, k, v, w.K8, w.G_rm, w.Cc, w.dQacc,
+                           pb.n, pb.b);
+        PSF_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_bwd_local_k<P>), dim3(grid), dim3(kWg), 0, s, q, k, v, w.Q8, w.G_rm, w.G8, w.Cc, w.dVc,
+                           w.dKacc, (bf16_t *)dV, pb.n, pb.b);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    // through the sketch
+    {
+        const unsigned grid = (unsigned)(rows / 128);
+        hipLaunchKernelGGL((k_bwd_sketch<D, R>), dim3(grid), dim3(kWg), 0, s, q, f.Gt, (const bf16_t *)G, w.dMQ,
+                           w.dQacc, (bf16_t *)dQ, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len);
+        PSF_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_bwd_sketch<D, R>), dim3(grid), dim3(kWg), 0, s, k, f.Gt, (const bf16_t *)G, w.dMK,
+                           w.dKacc, (bf16_t *)dK, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len);
+        PSF_LAUNCH_CHECK();
+    }
+    if (tm) tm->mark();
+    return PSF_OK;
+}

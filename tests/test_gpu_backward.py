@@ -87,3 +87,25 @@ def test_backward_exact_features_are_refused():
     with pytest.raises(psf.PsfError) as e:
         psf.psf_causal_attn_bwd(desc, x, x, x, None, x)
     assert e.value.code == 3
+
+
+@pytest.mark.parametrize("heads,n,r,b,per_head", [
+    (2, 1024, 64, 256, True),      # four blocks: cross-block terms on both sides
+    (2, 1024, 32, 256, True),
+    (1, 512, 64, 512, False),      # single block: in-block pairs only
+    (3, 2048, 64, 512, False),     # several 256-token workgroups per block
+    (2, 1536, 32, 768, True),      # block size that is no power of two
+])
+def test_backward_mfma_path_full_parity(heads, n, r, b, per_head):
+    desc = psf.make_desc(1, heads, n, 64, 4, r, b, "bf16", per_head=per_head)
+    assert psf.bwd_kernel_path(desc) == 3
+    run_case(1, heads, n, 64, 64, 4, r, b, "bf16", per_head=per_head, seed=43)
+
+
+def test_backward_mfma_path_is_deterministic_and_matches_general_kernels():
+    """The MFMA kernels against the general fp32 kernels of the same library on a shape both
+    accept (b % 256 != 0 sends the same problem down the general path)."""
+    a = run_case(1, 2, 1024, 64, 64, 4, 64, 256, "bf16", per_head=True, seed=47)
+    a2 = run_case(1, 2, 1024, 64, 64, 4, 64, 256, "bf16", per_head=True, seed=47)
+    for x, y in zip(a, a2):
+        assert torch.equal(x, y)
