@@ -145,7 +145,10 @@ __global__ __launch_bounds__(kWg) void k_bwd_qoct(const bf16_t *__restrict__ MQ,
 template <int R, int D>
 __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__ Zs, bf16_t *__restrict__ ZT)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t F[8][R][D];      // [b % 8][e][c]
+    // [b % 8][e][c], the 16-byte column c / 8 of row e stored at (c / 8) ^ (e % 8): the final
+    // reads walk e with a fixed column and would otherwise all hit the same banks
+    __shared__ __attribute__((aligned(16))) bf16_t F[8][R][D];
+    auto at = [&](int b8, int e, int c) -> bf16_t & { return F[b8][e][(((c >> 3) ^ (e & 7)) << 3) + (c & 7)]; };
     const int tid = threadIdx.x, ob = blockIdx.x;
     const bf16_t *src = Zs + (size_t)blockIdx.y * R * R * D;
     bf16_t *dst = ZT + (size_t)blockIdx.y * R * R * D;
@@ -156,7 +159,7 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
         const uint4 pk = *(const uint4 *)&src[(((size_t)e * (R / 8) + ob) * D + c) * 8];
         const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) F[j][e][c] = half((w[j / 2] >> (16 * (j % 2))) & 0xffffu);
+        for (int j = 0; j < 8; ++j) at(j, e, c) = half((w[j / 2] >> (16 * (j % 2))) & 0xffffu);
     }
     // rows a of this octet, columns b' >= 8 ob
     const int per_a = (R / 8 - ob) * D;
@@ -171,17 +174,17 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
             const uint32_t bits = (w[j / 2] >> (16 * (j % 2))) & 0xffffu;
             if (bp > a) {
                 const bf16_t v = half(bits);
-                F[a8][bp][c] = v;                          // (b = a, e = b')
-                if (ob2 == ob) F[j][a][c] = v;             // mirror inside the diagonal octet: (b = b', e = a)
+                at(a8, bp, c) = v;                         // (b = a, e = b')
+                if (ob2 == ob) at(j, a, c) = v;            // mirror inside the diagonal octet: (b = b', e = a)
             } else if (bp == a) {
-                F[a8][a][c] = (bf16_t)bits;
+                at(a8, a, c) = (bf16_t)bits;
             }
         }
     }
     __syncthreads();
     for (int idx = tid; idx < 8 * (D / 8) * R; idx += kWg) {
         const int b8 = idx / ((D / 8) * R), c8 = (idx / R) % (D / 8), e = idx % R;
-        *(uint4 *)&dst[((((size_t)(8 * ob + b8)) * (D / 8) + c8) * R + e) * 8] = *(const uint4 *)&F[b8][e][8 * c8];
+        *(uint4 *)&dst[((((size_t)(8 * ob + b8)) * (D / 8) + c8) * R + e) * 8] = *(const uint4 *)&F[b8][e][8 * (c8 ^ (e & 7))];
     }
 }
 
@@ -283,7 +286,9 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M,
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tiles_per_unit = n / TOK_WG;
-    const int u = blockIdx.x / tiles_per_unit, i0 = (blockIdx.x % tiles_per_unit) * TOK_WG;
+    int wg = blockIdx.x;                                    // XCD-aware order: one state snapshot, one L2
+    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int u = wg / tiles_per_unit, i0 = (wg % tiles_per_unit) * TOK_WG;
     const int l = i0 / b;
     const size_t urow = (size_t)u * n;
     const bool has = QSIDE ? l > 0 : l < t - 1;
@@ -362,7 +367,9 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dvc(const bf16_t *__restrict__ M
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tiles_per_unit = n / TOK_WG;
-    const int u = blockIdx.x / tiles_per_unit, i0 = (blockIdx.x % tiles_per_unit) * TOK_WG;
+    int wg = blockIdx.x;                                    // XCD-aware order: one state snapshot, one L2
+    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int u = wg / tiles_per_unit, i0 = (wg % tiles_per_unit) * TOK_WG;
     const int l = i0 / b;
     const size_t urow = (size_t)u * n;
     f32x16 out[TT][CT];
@@ -406,14 +413,24 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dvc(const bf16_t *__restrict__ M
 constexpr int kLocT = 64;                                   // streamed rows per tile
 constexpr int kLocRows = kLocT * 64 * 2;                    // bytes of one [D/8][64][8] / [8][D][8] array, D = 64
 
-// rows [j0, j0 + 64) of X ([.][64] bf16) -> LDS [8][64][8]
-__device__ __forceinline__ void loc_stage_rows(const bf16_t *X, size_t j0, unsigned char *dst, int tid, int wave)
+// X [rows][64] bf16 -> XF [rows/64][8][64][8]: per 64-row tile the layout the in-block kernels keep
+// in LDS (16-byte A fragments with contraction over the 64 columns), so that staging a tile is
+// a straight, fully coalesced copy.
+__global__ __launch_bounds__(kWg) void k_bwd_row_tiles(const bf16_t *__restrict__ X, bf16_t *__restrict__ XF,
+                                                       size_t pieces)
+{
+    const size_t idx = (size_t)blockIdx.x * kWg + threadIdx.x;         // (tile, row, column octet)
+    if (idx >= pieces) return;
+    const size_t tile = idx / 512;
+    const int key = (int)(idx % 512) / 8, doct = (int)(idx % 8);
+    *(uint4 *)&XF[((tile * 8 + doct) * kLocT + key) * 8] = *(const uint4 *)&X[idx * 8];
+}
+// tile of rows [j0, j0 + 64) of XF -> LDS, straight copy
+__device__ __forceinline__ void loc_stage_rows(const bf16_t *XF, size_t j0, unsigned char *dst, int tid, int wave)
 {
 #pragma unroll
-    for (int q = 0; q < kLocRows / 16 / kWg; ++q) {
-        const int slot = q * kWg + tid, key = slot % kLocT, doct = slot / kLocT;
-        dma16(X + (j0 + key) * 64 + 8 * doct, dst + (size_t)(q * kWg + wave * 64) * 16);
-    }
+    for (int q = 0; q < kLocRows / 16 / kWg; ++q)
+        dma16(XF + j0 * 64 + (size_t)(q * kWg + tid) * 8, dst + (size_t)(q * kWg + wave * 64) * 16);
 }
 // octets of rows [j0, j0 + 64) of X8 ([rows/8][64][8]) -> LDS, straight copy
 __device__ __forceinline__ void loc_stage_octets(const bf16_t *X8, size_t j0, unsigned char *dst, int tid, int wave)
@@ -439,8 +456,8 @@ __device__ __forceinline__ void loc_pack(const f32x16 &w, bf16x8 (&pw)[2])
 // dQ (in-block): own rows = queries, streamed = keys of the same block up to the diagonal.
 //   dq_i = sum_{j <= i} (<g_i, v_j> + c_i) p <q_i, k_j>^(p-1) k_j          -> dQacc fp32 rows
 template <int P>
-__global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
-                                                       const bf16_t *__restrict__ V, const bf16_t *__restrict__ K8,
+__global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ KF,
+                                                       const bf16_t *__restrict__ VF, const bf16_t *__restrict__ K8,
                                                        const bf16_t *__restrict__ G_rm, const float *__restrict__ Cc,
                                                        float *__restrict__ dQacc, int n, int b)
 {
@@ -449,7 +466,11 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tiles_per_unit = n / 128;
-    const int u = blockIdx.x / tiles_per_unit, i0 = (blockIdx.x % tiles_per_unit) * 128;
+    // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
+    // contiguous range of tiles: the workgroups that stream the same rows then share one L2
+    int wg = blockIdx.x;
+    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int u = wg / tiles_per_unit, i0 = (wg % tiles_per_unit) * 128;
     const int jb = (i0 / b) * b;
     const size_t urow = (size_t)u * n;
     const int tok0 = i0 + 32 * wave, tok = tok0 + x;
@@ -465,8 +486,8 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict
     auto stage_tile = [&](int kt) {
         unsigned char *dst = stage + (kt & 1) * BUF;
         const size_t j0 = urow + jb + (size_t)kt * kLocT;
-        loc_stage_rows(K, j0, dst, tid, wave);
-        loc_stage_rows(V, j0, dst + kLocRows, tid, wave);
+        loc_stage_rows(KF, j0, dst, tid, wave);
+        loc_stage_rows(VF, j0, dst + kLocRows, tid, wave);
         loc_stage_octets(K8, j0, dst + 2 * kLocRows, tid, wave);
     };
     stage_tile(0);
@@ -520,9 +541,9 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict
 //   dk_j = sum_{i >= j} (<g_i, v_j> + c_i) p <q_i, k_j>^(p-1) q_i   -> dKacc fp32 rows
 //   dv_j = sum_{i >= j} <q_i, k_j>^p g_i + dVc_j                     -> dV bf16 rows
 template <int P>
-__global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+__global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict__ QF, const bf16_t *__restrict__ K,
                                                        const bf16_t *__restrict__ V, const bf16_t *__restrict__ Q8,
-                                                       const bf16_t *__restrict__ G_rm, const bf16_t *__restrict__ G8,
+                                                       const bf16_t *__restrict__ GF, const bf16_t *__restrict__ G8,
                                                        const float *__restrict__ Cc, const float *__restrict__ dVc,
                                                        float *__restrict__ dKacc, bf16_t *__restrict__ dV, int n,
                                                        int b)
@@ -532,7 +553,9 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tiles_per_unit = n / 128;
-    const int u = blockIdx.x / tiles_per_unit, j0 = (blockIdx.x % tiles_per_unit) * 128;
+    int wg = blockIdx.x;                                    // XCD-aware order, as in k_bwd_local_q
+    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int u = wg / tiles_per_unit, j0 = (wg % tiles_per_unit) * 128;
     const int jb = (j0 / b) * b;
     const size_t urow = (size_t)u * n;
     const int key0 = j0 + 32 * wave, key = key0 + x;
@@ -547,8 +570,8 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict
     auto stage_tile = [&](int qt) {
         unsigned char *dst = stage + (qt & 1) * BUF;
         const size_t t0 = urow + jb + (size_t)qt * kLocT;
-        loc_stage_rows(Q, t0, dst, tid, wave);
-        loc_stage_rows(G_rm, t0, dst + kLocRows, tid, wave);
+        loc_stage_rows(QF, t0, dst, tid, wave);
+        loc_stage_rows(GF, t0, dst + kLocRows, tid, wave);
         loc_stage_octets(Q8, t0, dst + 2 * kLocRows, tid, wave);
         loc_stage_octets(G8, t0, dst + 3 * kLocRows, tid, wave);
         if (tid < kLocT) ((float *)(dst + 4 * kLocRows))[tid] = Cc[t0 + tid];
@@ -619,69 +642,77 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict
 // them) for the recomputed projections, G = the matrices as given ([d][r] rows) for the
 // transposed products, whose A fragments are read straight from them in accumulator order.
 template <int D, int R>
-__global__ __launch_bounds__(kWg) void k_bwd_sketch(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Gt,
+__global__ __launch_bounds__(kWg, 2) void k_bwd_sketch(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Gt,
                                                     const bf16_t *__restrict__ G, const float *__restrict__ dM,
                                                     const float *__restrict__ dXacc, bf16_t *__restrict__ dX,
-                                                    int n, int heads, int per_head, size_t g_len)
+                                                    int n, int heads, int per_head, size_t g_len, int tiles_per_wg)
 {
+    constexpr int KS = D / 16, NT = R / 32, DT = D / 32, GP = R + 8;
     __shared__ __attribute__((aligned(16))) SketchLds<D, R> lds;
-    constexpr int KS = D / 16, NT = R / 32, DT = D / 32;
+    __shared__ __attribute__((aligned(16))) bf16_t go[2][D * GP];       // G1, G2 as given: rows [d][r], padded
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, x = lane & 31, h = lane >> 5;
-    const size_t row = (size_t)blockIdx.x * 128 + wave * 32 + x;
-    const int head = (int)((((size_t)blockIdx.x * 128) / n) % heads);
+    const size_t row_wg0 = (size_t)blockIdx.x * tiles_per_wg * 128;
+    const int head = (int)((row_wg0 / n) % heads);
     const size_t goff = per_head ? (size_t)head * g_len : 0;
     const float scale = sqrtf(1.0f / (float)R);
     stage_gt<D, R, D>(lds.gt[0], Gt + goff);
     stage_gt<D, R, D>(lds.gt[1], Gt + goff + (size_t)D * R);
-    bf16x8 xfr[KS];
-#pragma unroll
-    for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
+    for (int idx = threadIdx.x; idx < 2 * D * (R / 8); idx += kWg) {
+        const int m = idx / (D * (R / 8)), rem = idx % (D * (R / 8)), e = rem / (R / 8), part = rem % (R / 8);
+        *(uint4 *)&go[m][e * GP + 8 * part] = *(const uint4 *)&G[goff + (size_t)m * D * R + (size_t)e * R + 8 * part];
+    }
     __syncthreads();
-    f32x16 a0[NT], a1[NT];                                  // lane = token, register = sketch column
-    project<D, R, KS, true>(lds.gt[0], xfr, a0, x, h);
-    project<D, R, KS, true>(lds.gt[1], xfr, a1, x, h);
-    bf16x8 d0[2 * NT], d1[2 * NT];                          // B operands, contraction over sketch columns
+#pragma unroll 1
+    for (int tile = 0; tile < tiles_per_wg; ++tile) {
+        const size_t row = row_wg0 + (size_t)tile * 128 + wave * 32 + x;
+        bf16x8 xfr[KS];
 #pragma unroll
-    for (int ct = 0; ct < NT; ++ct) {
-        f32x16 da0, da1;
+        for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
+        f32x16 a0[NT], a1[NT];                              // lane = token, register = sketch column
+        project<D, R, KS, true>(lds.gt[0], xfr, a0, x, h);
+        project<D, R, KS, true>(lds.gt[1], xfr, a1, x, h);
+        bf16x8 d0[2 * NT], d1[2 * NT];                      // B operands, contraction over sketch columns
 #pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const f32x4 m4 = *(const f32x4 *)&dM[row * R + 32 * ct + 8 * gq + 4 * h];
+        for (int ct = 0; ct < NT; ++ct) {
+            f32x16 da0, da1;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                da0[4 * gq + j] = scale * m4[j] * a1[ct][4 * gq + j];
-                da1[4 * gq + j] = scale * m4[j] * a0[ct][4 * gq + j];
+            for (int gq = 0; gq < 4; ++gq) {
+                const f32x4 m4 = *(const f32x4 *)&dM[row * R + 32 * ct + 8 * gq + 4 * h];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    da0[4 * gq + j] = scale * m4[j] * a1[ct][4 * gq + j];
+                    da1[4 * gq + j] = scale * m4[j] * a0[ct][4 * gq + j];
+                }
+            }
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp) {
+                d0[2 * ct + sp] = cvt8_from16(da0, 8 * sp);
+                d1[2 * ct + sp] = cvt8_from16(da1, 8 * sp);
             }
         }
 #pragma unroll
-        for (int sp = 0; sp < 2; ++sp) {
-            d0[2 * ct + sp] = cvt8_from16(da0, 8 * sp);
-            d1[2 * ct + sp] = cvt8_from16(da1, 8 * sp);
-        }
-    }
-    const bf16_t *g1 = G + goff, *g2 = G + goff + (size_t)D * R;
+        for (int dt = 0; dt < DT; ++dt) {
+            f32x16 acc = {0};
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-        f32x16 acc = {0};
+            for (int ks = 0; ks < 2 * NT; ++ks) {
+                // entries e of the step are sketch columns 16 ks + 8 (e / 4) + 4 h + e % 4
+                const int off = (32 * dt + x) * GP + 16 * ks + 4 * h;
+                const bf16x4 lo1 = *(const bf16x4 *)&go[0][off], hi1 = *(const bf16x4 *)&go[0][off + 8];
+                const bf16x4 lo2 = *(const bf16x4 *)&go[1][off], hi2 = *(const bf16x4 *)&go[1][off + 8];
+                bf16x8 f1, f2;
 #pragma unroll
-        for (int ks = 0; ks < 2 * NT; ++ks) {
-            // entries e of the step are sketch columns 16 ks + 8 (e / 4) + 4 h + e % 4
-            const size_t off = (size_t)(32 * dt + x) * R + 16 * ks + 4 * h;
-            const bf16x4 lo1 = *(const bf16x4 *)&g1[off], hi1 = *(const bf16x4 *)&g1[off + 8];
-            const bf16x4 lo2 = *(const bf16x4 *)&g2[off], hi2 = *(const bf16x4 *)&g2[off + 8];
-            bf16x8 f1, f2;
+                for (int e = 0; e < 4; ++e) { f1[e] = lo1[e]; f1[4 + e] = hi1[e]; f2[e] = lo2[e]; f2[4 + e] = hi2[e]; }
+                acc = mfma32(f1, d0[ks], acc);
+                acc = mfma32(f2, d1[ks], acc);
+            }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { f1[e] = lo1[e]; f1[4 + e] = hi1[e]; f2[e] = lo2[e]; f2[4 + e] = hi2[e]; }
-            acc = mfma32(f1, d0[ks], acc);
-            acc = mfma32(f2, d1[ks], acc);
-        }
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const size_t off = row * D + 32 * dt + 8 * gq + 4 * h;
-            const f32x4 base = *(const f32x4 *)&dXacc[off];
-            const f32x4 q4 = {acc[4 * gq] + base[0], acc[4 * gq + 1] + base[1], acc[4 * gq + 2] + base[2],
-                              acc[4 * gq + 3] + base[3]};
-            *(bf16x4 *)&dX[off] = cvt4(q4);
+            for (int gq = 0; gq < 4; ++gq) {
+                const size_t off = row * D + 32 * dt + 8 * gq + 4 * h;
+                const f32x4 base = *(const f32x4 *)&dXacc[off];
+                const f32x4 q4 = {acc[4 * gq] + base[0], acc[4 * gq + 1] + base[1], acc[4 * gq + 2] + base[2],
+                                  acc[4 * gq + 3] + base[3]};
+                *(bf16x4 *)&dX[off] = cvt4(q4);
+            }
         }
     }
 }
@@ -689,7 +720,7 @@ __global__ __launch_bounds__(kWg) void k_bwd_sketch(const bf16_t *__restrict__ X
 // ---- host ---------------------------------------------------------------------------------------
 struct MfmaBwdWs {
     void *fwd;                                               // the forward workspace
-    bf16_t *O, *MK, *G_rm, *G8, *G8r, *Q8, *K8, *Rg, *ZT, *RT, *Rchi, *Rclo;
+    bf16_t *O, *MK, *G_rm, *G8, *G8r, *Q8, *K8, *QF, *KF, *VF, *GF, *Rg, *ZT, *RT, *Rchi, *Rclo;
     float *Den, *Cc, *M8r, *ScPart, *dMQ, *dMK, *dVc, *dQacc, *dKacc;
     size_t total;
 };
@@ -710,6 +741,10 @@ MfmaBwdWs carve_bwd(const Problem &pb, void *ws)
     w.G8r = (bf16_t *)take(rows * D * 2);
     w.Q8 = (bf16_t *)take(rows * D * 2);
     w.K8 = (bf16_t *)take(rows * D * 2);
+    w.QF = (bf16_t *)take(rows * D * 2);
+    w.KF = (bf16_t *)take(rows * D * 2);
+    w.VF = (bf16_t *)take(rows * D * 2);
+    w.GF = (bf16_t *)take(rows * D * 2);
     w.Rg = (bf16_t *)take(snaps * R * R * D * 2);
     w.ZT = (bf16_t *)take(snaps * R * R * D * 2);
     w.RT = (bf16_t *)take(snaps * R * R * D * 2);
@@ -752,6 +787,14 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
         PSF_LAUNCH_CHECK();
         hipLaunchKernelGGL((k_v_octets<D>), dim3(grid), dim3(kWg), 0, s, k, w.K8, octets);
         PSF_LAUNCH_CHECK();
+        const size_t pieces = rows * D / 8;
+        const unsigned gridp = (unsigned)((pieces + kWg - 1) / kWg);
+        const bf16_t *src[4] = {q, k, v, w.G_rm};
+        bf16_t *dstf[4] = {w.QF, w.KF, w.VF, w.GF};
+        for (int i = 0; i < 4; ++i) {
+            hipLaunchKernelGGL(k_bwd_row_tiles, dim3(gridp), dim3(kWg), 0, s, src[i], dstf[i], pieces);
+            PSF_LAUNCH_CHECK();
+        }
     }
     if (tm) tm->mark();
     // mirror states R_l (the forward state kernel on block-reversed inputs), re-laid states
@@ -787,22 +830,23 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     // in-block parts
     {
         const unsigned grid = (unsigned)(rows / 128);
-        hipLaunchKernelGGL((k_bwd_local_q<P>), dim3(grid), dim3(kWg), 0, s, q, k, v, w.K8, w.G_rm, w.Cc, w.dQacc,
-                           pb.n, pb.b);
+        hipLaunchKernelGGL((k_bwd_local_q<P>), dim3(grid), dim3(kWg), 0, s, q, w.KF, w.VF, w.K8, w.G_rm, w.Cc,
+                           w.dQacc, pb.n, pb.b);
         PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_bwd_local_k<P>), dim3(grid), dim3(kWg), 0, s, q, k, v, w.Q8, w.G_rm, w.G8, w.Cc, w.dVc,
-                           w.dKacc, (bf16_t *)dV, pb.n, pb.b);
+        hipLaunchKernelGGL((k_bwd_local_k<P>), dim3(grid), dim3(kWg), 0, s, w.QF, k, v, w.Q8, w.GF, w.G8, w.Cc,
+                           w.dVc, w.dKacc, (bf16_t *)dV, pb.n, pb.b);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
     // through the sketch
     {
-        const unsigned grid = (unsigned)(rows / 128);
+        const int tiles = sketch_tiles_per_wg(pb.b);
+        const unsigned grid = (unsigned)(rows / (128 * (size_t)tiles));
         hipLaunchKernelGGL((k_bwd_sketch<D, R>), dim3(grid), dim3(kWg), 0, s, q, f.Gt, (const bf16_t *)G, w.dMQ,
-                           w.dQacc, (bf16_t *)dQ, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len);
+                           w.dQacc, (bf16_t *)dQ, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles);
         PSF_LAUNCH_CHECK();
         hipLaunchKernelGGL((k_bwd_sketch<D, R>), dim3(grid), dim3(kWg), 0, s, k, f.Gt, (const bf16_t *)G, w.dMK,
-                           w.dKacc, (bf16_t *)dK, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len);
+                           w.dKacc, (bf16_t *)dK, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
