@@ -153,36 +153,53 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
     const bf16_t *src = Zs + (size_t)blockIdx.y * R * R * D;
     bf16_t *dst = ZT + (size_t)blockIdx.y * R * R * D;
     auto half = [](uint32_t bits) { return f32_to_bf16(0.5f * bf16_to_f32((bf16_t)bits)); };
-    // e < 8 ob: Z[e][b][c] = Zs[e][b][c] / 2 (b > e there)
-    for (int idx = tid; idx < 8 * ob * D; idx += kWg) {
-        const int e = idx / D, c = idx % D;
-        const uint4 pk = *(const uint4 *)&src[(((size_t)e * (R / 8) + ob) * D + c) * 8];
-        const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
+    // 16-byte pieces of the source, all loads of a thread issued before their use:
+    //   pieces [0, 8 ob D): rows e < 8 ob, octet ob (b > e there: Z[e][b][c] = Zs[e][b][c] / 2)
+    //   the rest: rows a of this octet, column octets ob2 >= ob
+    constexpr int PIECES = 8 * D * (R / 8) / kWg;
+    const int n_a = 8 * ob * D, per_a = (R / 8 - ob) * D;
+    uint4 pk[PIECES];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) at(j, e, c) = half((w[j / 2] >> (16 * (j % 2))) & 0xffffu);
+    for (int i = 0; i < PIECES; ++i) {
+        const int idx = tid + i * kWg;
+        size_t off;
+        if (idx < n_a) {
+            off = ((size_t)(idx / D) * (R / 8) + ob) * D + idx % D;
+        } else {
+            const int k2 = idx - n_a, a8 = k2 / per_a, rem = k2 % per_a;
+            off = ((size_t)(8 * ob + a8) * (R / 8) + ob + rem / D) * D + rem % D;
+        }
+        pk[i] = *(const uint4 *)&src[off * 8];
     }
-    // rows a of this octet, columns b' >= 8 ob
-    const int per_a = (R / 8 - ob) * D;
-    for (int idx = tid; idx < 8 * per_a; idx += kWg) {
-        const int a8 = idx / per_a, rem = idx % per_a, ob2 = ob + rem / D, c = rem % D;
-        const int a = 8 * ob + a8;
-        const uint4 pk = *(const uint4 *)&src[(((size_t)a * (R / 8) + ob2) * D + c) * 8];
-        const uint32_t w[4] = {pk.x, pk.y, pk.z, pk.w};
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int bp = 8 * ob2 + j;
-            const uint32_t bits = (w[j / 2] >> (16 * (j % 2))) & 0xffffu;
-            if (bp > a) {
-                const bf16_t v = half(bits);
-                at(a8, bp, c) = v;                         // (b = a, e = b')
-                if (ob2 == ob) at(j, a, c) = v;            // mirror inside the diagonal octet: (b = b', e = a)
-            } else if (bp == a) {
-                at(a8, a, c) = (bf16_t)bits;
+    for (int i = 0; i < PIECES; ++i) {
+        const int idx = tid + i * kWg;
+        const uint32_t w[4] = {pk[i].x, pk[i].y, pk[i].z, pk[i].w};
+        if (idx < n_a) {
+            const int e = idx / D, c = idx % D;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) at(j, e, c) = half((w[j / 2] >> (16 * (j % 2))) & 0xffffu);
+        } else {
+            const int k2 = idx - n_a, a8 = k2 / per_a, rem = k2 % per_a, ob2 = ob + rem / D, c = rem % D;
+            const int a = 8 * ob + a8;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int bp = 8 * ob2 + j;
+                const uint32_t bits = (w[j / 2] >> (16 * (j % 2))) & 0xffffu;
+                if (bp > a) {
+                    const bf16_t v = half(bits);
+                    at(a8, bp, c) = v;                     // (b = a, e = b')
+                    if (ob2 == ob) at(j, a, c) = v;        // mirror inside the diagonal octet: (b = b', e = a)
+                } else if (bp == a) {
+                    at(a8, a, c) = (bf16_t)bits;
+                }
             }
         }
     }
     __syncthreads();
-    for (int idx = tid; idx < 8 * (D / 8) * R; idx += kWg) {
+#pragma unroll
+    for (int i = 0; i < PIECES; ++i) {
+        const int idx = tid + i * kWg;
         const int b8 = idx / ((D / 8) * R), c8 = (idx / R) % (D / 8), e = idx % R;
         *(uint4 *)&dst[((((size_t)(8 * ob + b8)) * (D / 8) + c8) * R + e) * 8] = *(const uint4 *)&F[b8][e][8 * (c8 ^ (e & 7))];
     }
@@ -498,33 +515,42 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict
         if (kt + 1 < ntiles) stage_tile(kt + 1);
         const bf16_t *ks = (const bf16_t *)(stage + (kt & 1) * BUF);
         const bf16_t *vs = ks + kLocRows / 2, *k8 = ks + kLocRows;
+        if (jb + kt * kLocT <= tok0 + 31) {                // wave-uniform: some key of the tile is not later than every own token
+            // both 32-key halves in one straight line: scores, then weights, then products
+            f32x16 sc[2], dw[2];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int key0 = jb + kt * kLocT + 32 * sub;
-            if (key0 > tok0 + 31) continue;                // wave-uniform: all keys later than all own tokens
-            f32x16 sc = {0}, dw = {0};
+            for (int sub = 0; sub < 2; ++sub) {
+                sc[sub] = f32x16{0};
+                dw[sub] = f32x16{0};
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                const bf16x8 kf = *(const bf16x8 *)&ks[((2 * s + h) * kLocT + 32 * sub + x) * 8];
-                const bf16x8 vf = *(const bf16x8 *)&vs[((2 * s + h) * kLocT + 32 * sub + x) * 8];
-                sc = mfma32(kf, qfr[s], sc);
-                dw = mfma32(vf, gfr[s], dw);
-            }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
-                const float dp = (dw[v] + c_me) * (float)P * pow_n<P - 1>(sc[v]);
-                dw[v] = key <= tok ? dp : 0.f;
-            }
-            bf16x8 pw[2];
-            loc_pack(dw, pw);
-#pragma unroll
-            for (int sp = 0; sp < 2; ++sp)
-#pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    const bf16x8 kf8 = *(const bf16x8 *)&k8[((4 * sub + 2 * sp + h) * D + 32 * ct + x) * 8];
-                    dq[ct] = mfma32(kf8, pw[sp], dq[ct]);
+                for (int s = 0; s < KS; ++s) {
+                    const bf16x8 kf = *(const bf16x8 *)&ks[((2 * s + h) * kLocT + 32 * sub + x) * 8];
+                    const bf16x8 vf = *(const bf16x8 *)&vs[((2 * s + h) * kLocT + 32 * sub + x) * 8];
+                    sc[sub] = mfma32(kf, qfr[s], sc[sub]);
+                    dw[sub] = mfma32(vf, gfr[s], dw[sub]);
                 }
+            }
+            bf16x8 pw[2][2];
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub) {
+                const int key0 = jb + kt * kLocT + 32 * sub;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
+                    const float dp = (dw[sub][v] + c_me) * (float)P * pow_n<P - 1>(sc[sub][v]);
+                    dw[sub][v] = key <= tok ? dp : 0.f;
+                }
+                loc_pack(dw[sub], pw[sub]);
+            }
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const bf16x8 kf8 = *(const bf16x8 *)&k8[((4 * sub + 2 * sp + h) * D + 32 * ct + x) * 8];
+                        dq[ct] = mfma32(kf8, pw[sub][sp], dq[ct]);
+                    }
         }
     }
 #pragma unroll
@@ -585,42 +611,50 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict
         const bf16_t *qs = (const bf16_t *)(stage + (qt & 1) * BUF);
         const bf16_t *gs = qs + kLocRows / 2, *q8 = qs + kLocRows, *g8 = qs + 3 * (kLocRows / 2);
         const float *cs = (const float *)(stage + (qt & 1) * BUF + 4 * kLocRows);
+        if (jb + qt * kLocT + kLocT - 1 >= key0) {         // wave-uniform: some token of the tile is not earlier than every own key
+            f32x16 sc[2], dw[2];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            const int t0 = jb + qt * kLocT + 32 * sub;
-            if (t0 + 31 < key0) continue;                  // wave-uniform: all tokens earlier than all own keys
-            f32x16 sc = {0}, dw = {0};
+            for (int sub = 0; sub < 2; ++sub) {
+                sc[sub] = f32x16{0};
+                dw[sub] = f32x16{0};
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                const bf16x8 qf = *(const bf16x8 *)&qs[((2 * s + h) * kLocT + 32 * sub + x) * 8];
-                const bf16x8 gf = *(const bf16x8 *)&gs[((2 * s + h) * kLocT + 32 * sub + x) * 8];
-                sc = mfma32(qf, kfr[s], sc);
-                dw = mfma32(gf, vfr[s], dw);
-            }
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const f32x4 c4 = *(const f32x4 *)&cs[32 * sub + 8 * gq + 4 * h];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int v = 4 * gq + j, tokv = t0 + 8 * gq + 4 * h + j;
-                    const float s1 = sc[v], pm1 = pow_n<P - 1>(s1);
-                    const bool keep = key <= tokv;
-                    sc[v] = keep ? pm1 * s1 : 0.f;
-                    dw[v] = keep ? (dw[v] + c4[j]) * (float)P * pm1 : 0.f;
+                for (int s = 0; s < KS; ++s) {
+                    const bf16x8 qf = *(const bf16x8 *)&qs[((2 * s + h) * kLocT + 32 * sub + x) * 8];
+                    const bf16x8 gf = *(const bf16x8 *)&gs[((2 * s + h) * kLocT + 32 * sub + x) * 8];
+                    sc[sub] = mfma32(qf, kfr[s], sc[sub]);
+                    dw[sub] = mfma32(gf, vfr[s], dw[sub]);
                 }
             }
-            bf16x8 pww[2], pwp[2];
-            loc_pack(sc, pww);
-            loc_pack(dw, pwp);
+            bf16x8 pww[2][2], pwp[2][2];
 #pragma unroll
-            for (int sp = 0; sp < 2; ++sp)
+            for (int sub = 0; sub < 2; ++sub) {
+                const int t0 = jb + qt * kLocT + 32 * sub;
 #pragma unroll
-                for (int ct = 0; ct < CT; ++ct) {
-                    const bf16x8 qf8 = *(const bf16x8 *)&q8[((4 * sub + 2 * sp + h) * D + 32 * ct + x) * 8];
-                    const bf16x8 gf8 = *(const bf16x8 *)&g8[((4 * sub + 2 * sp + h) * D + 32 * ct + x) * 8];
-                    dk[ct] = mfma32(qf8, pwp[sp], dk[ct]);
-                    dv[ct] = mfma32(gf8, pww[sp], dv[ct]);
+                for (int gq = 0; gq < 4; ++gq) {
+                    const f32x4 c4 = *(const f32x4 *)&cs[32 * sub + 8 * gq + 4 * h];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int v = 4 * gq + j, tokv = t0 + 8 * gq + 4 * h + j;
+                        const float s1 = sc[sub][v], pm1 = pow_n<P - 1>(s1);
+                        const bool keep = key <= tokv;
+                        sc[sub][v] = keep ? pm1 * s1 : 0.f;
+                        dw[sub][v] = keep ? (dw[sub][v] + c4[j]) * (float)P * pm1 : 0.f;
+                    }
                 }
+                loc_pack(sc[sub], pww[sub]);
+                loc_pack(dw[sub], pwp[sub]);
+            }
+#pragma unroll
+            for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+                for (int sp = 0; sp < 2; ++sp)
+#pragma unroll
+                    for (int ct = 0; ct < CT; ++ct) {
+                        const bf16x8 qf8 = *(const bf16x8 *)&q8[((4 * sub + 2 * sp + h) * D + 32 * ct + x) * 8];
+                        const bf16x8 gf8 = *(const bf16x8 *)&g8[((4 * sub + 2 * sp + h) * D + 32 * ct + x) * 8];
+                        dk[ct] = mfma32(qf8, pwp[sub][sp], dk[ct]);
+                        dv[ct] = mfma32(gf8, pww[sub][sp], dv[ct]);
+                    }
         }
     }
 #pragma unroll
