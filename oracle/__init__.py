@@ -61,6 +61,9 @@ def lib():
         L.psf_oracle_attn_bwd.restype = ctypes.c_int
         L.psf_oracle_attn_bwd.argtypes = ([_dp] * 5 + [ctypes.c_long] * 6 + [ctypes.c_int] * 2
                                           + [_dp] * 3)
+        L.psf_oracle_attn_bwd_rows.restype = ctypes.c_int
+        L.psf_oracle_attn_bwd_rows.argtypes = ([_dp] * 5 + [ctypes.c_long] * 6 + [ctypes.c_int] * 2
+                                               + [_lp, ctypes.c_long] + [_dp] * 3)
         L.psf_oracle_attn_bwd_batch.restype = ctypes.c_int
         L.psf_oracle_attn_bwd_batch.argtypes = ([_dp] * 4 + [ctypes.c_long] * 2 + [_dp]
                                                 + [ctypes.c_long] * 7 + [ctypes.c_int] * 2
@@ -230,6 +233,23 @@ def attn_bwd(Q, K, V, G, dO, p, r, b, feat=FEAT_SKETCH, local=LOCAL_EXACT):
                                    feat, local, _ptr(dQ), _ptr(dK), _ptr(dV))
     if rc:
         raise ValueError("psf_oracle_attn_bwd failed: %d" % rc)
+    return dQ, dK, dV
+
+
+def attn_bwd_rows(Q, K, V, G, dO, p, r, b, rows, feat=FEAT_SKETCH, local=LOCAL_EXACT):
+    """The sums of `attn_bwd` over the listed query rows only: dQ[i] is complete for listed i,
+    dK[j] and dV[j] are complete when every i >= j is listed; other rows are partial."""
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    n, d = Q.shape
+    dv = V.shape[1]
+    G = _f64(G).reshape(-1) if (feat == FEAT_SKETCH and p > 2) else np.zeros(1)
+    rows_a = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+    dQ, dK, dV = np.empty((n, d)), np.empty((n, d)), np.empty((n, dv))
+    rc = lib().psf_oracle_attn_bwd_rows(_ptr(Q), _ptr(K), _ptr(V), _ptr(G), _ptr(dO), n, d, dv, r, p, b,
+                                        feat, local, rows_a.ctypes.data_as(_lp), rows_a.size,
+                                        _ptr(dQ), _ptr(dK), _ptr(dV))
+    if rc:
+        raise ValueError("psf_oracle_attn_bwd_rows failed: %d" % rc)
     return dQ, dK, dV
 
 

@@ -461,9 +461,10 @@ int psf_oracle_sketch_bwd(const double *X, long k, long d, long r, long p,
  *   w = <m(q),m(k)>^2 (sketched):  du = 2 <m(q),m(k)> dw,  dm(q_i) += du m(k_j), and v.v.,
  * then dQ += J_m(Q)^T dm(Q), dK += J_m(K)^T dm(K) through oracle_pswn_bwd.  The sketch
  * matrices G are constants.  One unit; dQ, dK (n x d) and dV (n x dv) are overwritten. */
-int psf_oracle_attn_bwd(const double *Q, const double *K, const double *V, const double *G,
-                        const double *dO, long n, long d, long dv, long r, long p, long b,
-                        int feat, int local, double *dQ, double *dK, double *dV)
+static int oracle_attn_bwd_rows(const double *Q, const double *K, const double *V, const double *G,
+                                const double *dO, long n, long d, long dv, long r, long p, long b,
+                                int feat, int local, const long *rows, long nrows,
+                                double *dQ, double *dK, double *dV)
 {
     if (n <= 0 || b <= 0 || n % b != 0 || !is_pow2(p) || p < 2) return 1;
     long mcols = (p == 2) ? d : r;
@@ -485,7 +486,9 @@ int psf_oracle_attn_bwd(const double *Q, const double *K, const double *V, const
     if (!err) {
         for (long i = 0; i < n * d; ++i) dQ[i] = dK[i] = 0.0;
         for (long i = 0; i < n * dv; ++i) dV[i] = 0.0;
-        for (long i = 0; i < n; ++i) {
+        for (long ri = 0; ri < (rows ? nrows : n); ++ri) {
+            long i = rows ? rows[ri] : ri;
+            if (i < 0 || i >= n) { err = 1; break; }
             double den = 1.0;
             for (long c = 0; c < dv; ++c) num[c] = 0.0;
             for (long j = 0; j <= i; ++j) {
@@ -523,7 +526,7 @@ int psf_oracle_attn_bwd(const double *Q, const double *K, const double *V, const
                 }
             }
         }
-        if (sketch) {
+        if (sketch && !err) {
             err = psf_oracle_sketch_bwd(Q, n, d, r, p, G, dmq, tmp);
             for (long i = 0; i < n * d && !err; ++i) dQ[i] += tmp[i];
             if (!err) err = psf_oracle_sketch_bwd(K, n, d, r, p, G, dmk, tmp);
@@ -532,6 +535,26 @@ int psf_oracle_attn_bwd(const double *Q, const double *K, const double *V, const
     }
     free(w); free(num); free(tmp); free(mq); free(mk); free(dmq); free(dmk);
     return err;
+}
+
+int psf_oracle_attn_bwd(const double *Q, const double *K, const double *V, const double *G,
+                        const double *dO, long n, long d, long dv, long r, long p, long b,
+                        int feat, int local, double *dQ, double *dK, double *dV)
+{
+    return oracle_attn_bwd_rows(Q, K, V, G, dO, n, d, dv, r, p, b, feat, local, NULL, 0, dQ, dK, dV);
+}
+
+/* The same sums restricted to the listed query rows i (each listed once): row i of dQ is complete
+ * for every listed i; row j of dK and dV is complete when every i >= j is listed (list a whole
+ * tail of the sequence for that); all other rows hold partial sums and are to be ignored.  For
+ * sequences too long for the full O(n^2) loop. */
+int psf_oracle_attn_bwd_rows(const double *Q, const double *K, const double *V, const double *G,
+                             const double *dO, long n, long d, long dv, long r, long p, long b,
+                             int feat, int local, const long *rows, long nrows,
+                             double *dQ, double *dK, double *dV)
+{
+    if (!rows || nrows < 0) return 1;
+    return oracle_attn_bwd_rows(Q, K, V, G, dO, n, d, dv, r, p, b, feat, local, rows, nrows, dQ, dK, dV);
 }
 
 /* ---- drivers over (batch, head) units ---------------------------------------------

@@ -109,3 +109,54 @@ def test_backward_mfma_path_is_deterministic_and_matches_general_kernels():
     a2 = run_case(1, 2, 1024, 64, 64, 4, 64, 256, "bf16", per_head=True, seed=47)
     for x, y in zip(a, a2):
         assert torch.equal(x, y)
+
+
+def test_backward_config3_full_size_sampled_rows_and_identities():
+    """The workload `bench.py --pass bwd` times (config 3: 2 x 12 units of 32768 tokens, MFMA
+    kernels).  Element-wise against the oracle where it can afford the sums: dQ on probe rows
+    spread over the sequence, dK and dV on the last block plus the end of the block before it
+    (those rows see in-block pairs and one later block's cross-block pairs), for two units.
+    Over all tokens of every unit, two identities that hold at any size: the weights are
+    homogeneous of degree p in q_i and in k_j, so sum_i <q_i, dQ_i> = sum_j <k_j, dK_j>
+    (= p sum w dw, Euler); the output is linear in V, so <dV, V> = <dO, O>."""
+    from concurrent.futures import ThreadPoolExecutor
+    from parity import probe_rows
+    cfg, q, k, v, G = inputs.make_config(3)
+    n, b, r, p, heads = cfg["n"], cfg["b"], cfg["r"], cfg["p"], cfg["heads"]
+    dO = inputs.make_dout(cfg["batch"], heads, n, cfg["d"], seed=1003, dtype="bf16")
+    desc = psf.make_desc(cfg["batch"], heads, n, cfg["d"], p, r, b, "bf16", per_head=cfg["per_head"])
+    assert psf.bwd_kernel_path(desc) == 3
+    dev = torch.device("cuda:0")
+    qd, kd, vd, Gd, dOd = (x.to(dev) for x in (q, k, v, G, dO))
+    dQ, dK, dV = psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd)
+    O = psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd)
+    torch.cuda.synchronize()
+    f = lambda t: t.float()
+    # identities, per unit
+    a = (f(qd) * f(dQ)).sum((-1, -2))
+    c = (f(kd) * f(dK)).sum((-1, -2))
+    scale = ((f(qd) * f(dQ)).sum(-1).abs().sum(-1) + (f(kd) * f(dK)).sum(-1).abs().sum(-1)) / 2
+    assert ((a - c).abs() <= 2e-2 * scale).all(), ((a - c).abs() / scale).max()
+    lv, lo = (f(dV) * f(vd)).sum((-1, -2)), (f(dOd) * f(O)).sum((-1, -2))
+    scale_v = (f(dOd) * f(O)).sum(-1).abs().sum(-1)
+    assert ((lv - lo).abs() <= 2e-2 * scale_v).all(), ((lv - lo).abs() / scale_v).max()
+    # sampled rows against the oracle
+    tail0 = n - b - 128
+    probe = [x for x in probe_rows(n, b, extra=12) if x < tail0]
+    rows = probe + list(range(tail0, n))
+    units = [(0, 0), (1, 7)]
+
+    def one(unit):
+        bi, h = unit
+        g = as_f64(G[h]) if G.shape[0] > 1 else as_f64(G[0])
+        return oracle.attn_bwd_rows(as_f64(q[bi, h]), as_f64(k[bi, h]), as_f64(v[bi, h]), g, as_f64(dO[bi, h]),
+                                    p, r, b, rows)
+
+    with ThreadPoolExecutor(2) as ex:
+        want = list(ex.map(one, units))
+    for (bi, h), (wQ, wK, wV) in zip(units, want):
+        gq, gk, gv = (x[bi, h].float().cpu().numpy() for x in (dQ, dK, dV))
+        print("config 3 bwd", (bi, h),
+              assert_close_scaled(gq[rows], wQ[rows], "bf16", "dQ"),
+              assert_close_scaled(gk[tail0:], wK[tail0:], "bf16", "dK"),
+              assert_close_scaled(gv[tail0:], wV[tail0:], "bf16", "dV"))

@@ -203,3 +203,37 @@ def test_batch_driver_matches_single_units():
             want = oracle.attn_bwd(Q[bi, h], K[bi, h], V[bi, h], G[h], dO[bi, h], p, r, b)
             for got, w in zip((dQ[bi, h], dK[bi, h], dV[bi, h]), want):
                 np.testing.assert_allclose(got, w, rtol=1e-13, atol=1e-15)
+
+
+def test_row_restricted_gradient_against_finite_differences_and_the_full_sums():
+    """attn_bwd_rows: dQ rows of listed queries and dK / dV rows whose whole tail of queries is
+    listed.  Pinned two ways: against the full pair loop (itself pinned above), and directly
+    against central differences of the forward oracle for a loss that only involves the listed
+    output rows (dO zero elsewhere makes the restricted sums the whole gradient)."""
+    rng = np.random.default_rng(77)
+    n, d, dv, r, p, b = 24, 6, 5, 4, 4, 8
+    Q, K = rng.standard_normal((n, d)) * 0.6, rng.standard_normal((n, d)) * 0.6
+    V, dO = rng.standard_normal((n, dv)), rng.standard_normal((n, dv))
+    G = rng.standard_normal(oracle.g_len(d, r, p))
+    tail = 10                                           # keys >= tail have every later query listed
+    rows = [3, 7] + list(range(tail, n))
+    dQ, dK, dV = oracle.attn_bwd_rows(Q, K, V, G, dO, p, r, b, rows)
+    fQ, fK, fV = oracle.attn_bwd(Q, K, V, G, dO, p, r, b)
+    np.testing.assert_allclose(dQ[rows], fQ[rows], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(dK[tail:], fK[tail:], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(dV[tail:], fV[tail:], rtol=1e-12, atol=1e-14)
+    assert not np.allclose(dK[:tail], fK[:tail])        # earlier keys are partial sums, as documented
+    # loss over the listed rows only: its full gradient is what the restricted call returns
+    dO_m = np.zeros_like(dO)
+    dO_m[rows] = dO[rows]
+    loss = lambda q_, k_, v_: float((oracle.attn_def(q_, k_, v_, G, p, r, b) * dO_m).sum())
+    eps = 1e-6
+    for (name, X, got) in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV)):
+        for (i, c) in ((3, 1), (12, 0), (n - 1, 2), (5, 3)):
+            Xp, Xm = X.copy(), X.copy()
+            Xp[i, c] += eps
+            Xm[i, c] -= eps
+            args_p = {"Q": (Xp, K, V), "K": (Q, Xp, V), "V": (Q, K, Xp)}[name]
+            args_m = {"Q": (Xm, K, V), "K": (Q, Xm, V), "V": (Q, K, Xm)}[name]
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+            np.testing.assert_allclose(got[i, c], fd, rtol=2e-6, atol=1e-8, err_msg="%s[%d,%d]" % (name, i, c))
