@@ -56,6 +56,8 @@ def lib():
         L.psf_oracle_learned_len.argtypes = [ctypes.c_long] * 3
         L.psf_oracle_sketch_learned.restype = ctypes.c_int
         L.psf_oracle_sketch_learned.argtypes = [_dp] + [ctypes.c_long] * 4 + [_dp, _dp]
+        L.psf_oracle_attn_noncausal.restype = ctypes.c_int
+        L.psf_oracle_attn_noncausal.argtypes = ([_dp] * 5 + [ctypes.c_long] * 6 + [ctypes.c_int] * 2 + [_dp])
         L.psf_oracle_sketch_bwd.restype = ctypes.c_int
         L.psf_oracle_sketch_bwd.argtypes = [_dp] + [ctypes.c_long] * 4 + [_dp, _dp, _dp]
         L.psf_oracle_attn_bwd.restype = ctypes.c_int
@@ -220,6 +222,26 @@ def sketch_bwd(X, G, r, p, dM):
     if rc:
         raise ValueError("psf_oracle_sketch_bwd failed: %d" % rc)
     return dX
+
+
+def attn_noncausal(Q, K, V, G, p, r, feat=FEAT_SKETCH, explicit_features=False, learned=False):
+    """Non-causal Polysketch attention (Section 2.2): every query row sees every key row.
+    Q is [nq, d]; K, V are [nk, d], [nk, dv]."""
+    Q, K, V = _f64(Q), _f64(K), _f64(V)
+    nq, d = Q.shape
+    nk, dv = V.shape
+    MQ = MK = None
+    mcols = d if p == 2 else r
+    if feat == FEAT_SKETCH and learned:
+        MQ, MK = sketch_learned(Q, G, r, p), sketch_learned(K, G, r, p)
+    elif feat == FEAT_SKETCH:
+        MQ, MK = sketch(Q, G, r, p), sketch(K, G, r, p)
+    O = np.empty((nq, dv))
+    rc = lib().psf_oracle_attn_noncausal(_ptr(Q), _ptr(K), _ptr(V), _ptr(MQ), _ptr(MK), nq, nk, d, dv, mcols, p,
+                                         feat, int(bool(explicit_features)), _ptr(O))
+    if rc:
+        raise ValueError("psf_oracle_attn_noncausal failed: %d" % rc)
+    return O
 
 
 def attn_bwd(Q, K, V, G, dO, p, r, b, feat=FEAT_SKETCH, local=LOCAL_EXACT):

@@ -20,6 +20,7 @@
  *   psf_oracle_attn_def      Section 3 (causal Polysketch attention, 1 + sum in the
  *                            denominator), Section 3.2 (exact weights inside a block),
  *                            Section 2.2 (<x,y>^p = <x^{(x)p}, y^{(x)p}>)
+ *   psf_oracle_attn_noncausal  Section 2.2, Polysketch attention without a mask
  *   psf_oracle_attn_block    Section 3.1 block lower-triangular multiplication
  *                            (H_l, Z_l, P_l, row = p + a_i^T Z_l), Section 3.2 for P_l
  *   oracle_lpswn,            Algorithm 2 (learnable sketches, Appendix D): the recursion of
@@ -318,6 +319,46 @@ int psf_oracle_attn_def(const double *Q, const double *K, const double *V,
             if (W_out) W_out[t * n + j] = w;
         }
         for (long c = 0; c < dv; ++c) O_out[t * dv + c] = acc[c] / den;
+    }
+    free(acc);
+    return 0;
+}
+
+/* ---- non-causal Polysketch attention (Section 2.2) -------------------------------------
+ * Attn = D^-1 phi'(Q) phi'(K)^T V with D = diag(1 + phi'(Q) phi'(K)^T 1): every query sees all
+ * nk keys, there is no mask and no block structure,
+ *   o_i = sum_j w_ij v_j / (1 + sum_j w_ij),   w_ij = <phi'(q_i), phi'(k_j)> = <m(q_i), m(k_j)>^2
+ * (feat == EXACT: w_ij = <q_i, k_j>^p, the polynomial attention the sketch approximates).
+ * explicit_features != 0 evaluates the weight as the r^2-term sum over phi' = m (x) m.
+ * Q, MQ have nq rows; K, V, MK have nk rows. */
+int psf_oracle_attn_noncausal(const double *Q, const double *K, const double *V,
+                              const double *MQ, const double *MK, long nq, long nk, long d, long dv,
+                              long mcols, long p, int feat, int explicit_features, double *O_out)
+{
+    if (nq <= 0 || nk <= 0) return 1;
+    double *acc = (double *)malloc(sizeof(double) * (size_t)dv);
+    if (!acc) return 2;
+    for (long i = 0; i < nq; ++i) {
+        double den = 1.0;
+        for (long c = 0; c < dv; ++c) acc[c] = 0.0;
+        for (long j = 0; j < nk; ++j) {
+            double w;
+            if (feat == FEAT_EXACT) {
+                w = ipow(dot(Q + i * d, K + j * d, d), p);
+            } else if (explicit_features) {
+                w = 0.0;
+                for (long a = 0; a < mcols; ++a)
+                    for (long e = 0; e < mcols; ++e)
+                        w += (MQ[i * mcols + a] * MQ[i * mcols + e]) *
+                             (MK[j * mcols + a] * MK[j * mcols + e]);
+            } else {
+                double u = dot(MQ + i * mcols, MK + j * mcols, mcols);
+                w = u * u;
+            }
+            den += w;
+            for (long c = 0; c < dv; ++c) acc[c] += w * V[j * dv + c];
+        }
+        for (long c = 0; c < dv; ++c) O_out[i * dv + c] = acc[c] / den;
     }
     free(acc);
     return 0;
