@@ -36,15 +36,21 @@ def workloads():
     return w
 
 
-def stage_flops(cfg, learned=False):
+def stage_flops(cfg, learned=False, noncausal=False):
     """Algorithmic flops per step (multiply-add = 2), split by kernel stage.  Causal lower
-    triangle only; the first block has no prefix and the last block's state is never needed."""
+    triangle only; the first block has no prefix and the last block's state is never needed.
+    noncausal: one state over all n keys, applied to all n queries, no in-block pairs."""
     U = cfg["batch"] * cfg["heads"]
     n, d, r, b, p = cfg["n"], cfg["d"], cfg["r"], cfg["b"], cfg["p"]
     sketch = 2 * (8 * n * d * r if p == 4 else 16 * n * d * r + 8 * n * r * r)   # Q and K
     if learned:          # p - 2 networks per row: four dense layers each (Appendix D)
         net = lambda win: 2 * (win * 8 * r + 24 * r * r)
         sketch = 2 * n * ((p // 2) * net(d) + max(p // 2 - 2, 0) * net(r))
+    if noncausal:
+        f = {"sketch_and_layouts": U * (sketch + 2 * n * r * r), "block_states_scan": U * 2 * n * r * r * d,
+             "output": U * 2 * n * r * r * (d + 1)}
+        f["total"] = sum(f.values())
+        return f
     f = {
         "sketch_and_layouts": U * (sketch + 2 * (n - b) * r * r),      # + ones column of H_l
         "block_states_scan": U * 2 * (n - b) * r * r * d,               # H_l and Z_l
@@ -52,6 +58,31 @@ def stage_flops(cfg, learned=False):
     }
     f["total"] = sum(f.values())
     return f
+
+
+def cpu_baseline_noncausal(cfg, q, k, v, G):
+    """The float64 oracle of the unmasked attention: the first 1024 queries of `cores` units
+    against all n keys of their unit, one unit per thread (the C loops release the lock)."""
+    from concurrent.futures import ThreadPoolExecutor
+    import oracle
+    cores = min(os.cpu_count() or 1, 16)
+    units = min(cores, cfg["batch"] * cfg["heads"])
+    sel = [(i // cfg["heads"], i % cfg["heads"]) for i in range(units)]
+    nq = min(cfg["n"], 1024)
+    f64 = lambda t: t.double().numpy()
+
+    def one(unit):
+        bi, h = unit
+        g = f64(G[h] if G.shape[0] > 1 else G[0])
+        return oracle.attn_noncausal(f64(q[bi, h, :nq]), f64(k[bi, h]), f64(v[bi, h]), g, cfg["p"], cfg["r"])
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(units) as ex:
+        list(ex.map(one, sel))
+    dt = time.perf_counter() - t0
+    return {"value": units * nq / dt, "unit": "tokens/s", "cores": units, "kind": "oracle",
+            "sample": "first %d queries of %d units against all n=%d keys (float64 definition)" % (nq, units, cfg["n"]),
+            "seconds_measured": dt}
 
 
 def bwd_stage_flops(cfg):
@@ -274,6 +305,8 @@ def main():
     ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "decode"],
                     help="fwd: psf_causal_attn_fwd (the headline); bwd: psf_causal_attn_bwd; "
                          "decode: psf_decode_step at a fixed serving shape")
+    ap.add_argument("--noncausal", action="store_true",
+                    help="forward pass without the causal mask (psf_noncausal_attn_fwd)")
     ap.add_argument("--learned", action="store_true",
                     help="forward pass with learned sketches (Algorithm 2) instead of Gaussian ones")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -318,8 +351,10 @@ def main():
     path = psf.kernel_path(desc)
     qd, kd, vd, Gd = q.to(dev), k.to(dev), v.to(dev), G.to(dev)
     O = torch.empty_like(vd)
-    ws = psf.alloc_workspace(desc, dev)
+    ws = psf.alloc_noncausal_workspace(desc, dev) if args.noncausal else psf.alloc_workspace(desc, dev)
     stream = torch.cuda.current_stream()
+    fwd = psf.psf_noncausal_attn_fwd if args.noncausal else psf.psf_causal_attn_fwd
+    fwd_timed = psf.psf_noncausal_attn_fwd_timed if args.noncausal else psf.psf_causal_attn_fwd_timed
 
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
@@ -328,11 +363,11 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     for _ in range(args.warmup):
-        psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
+        fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
+        fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
@@ -342,17 +377,18 @@ def main():
     reps = max(3, min(args.steps, 10))
     acc = {}
     for _ in range(reps):
-        _, st = psf.psf_causal_attn_fwd_timed(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
+        _, st = fwd_timed(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
         for nm, ms in st.items():
             acc[nm] = acc.get(nm, 0.0) + ms / reps
-    fl = stage_flops(cfg, learned=args.learned) if path == 1 else None
+    fl = stage_flops(cfg, learned=args.learned, noncausal=args.noncausal) if path == 1 else None
     out = {
-        "metric": "causal_polysketch_attention_fwd_tokens_per_s", "value": tokens * args.steps / elapsed,
+        "metric": ("noncausal" if args.noncausal else "causal") + "_polysketch_attention_fwd_tokens_per_s",
+        "value": tokens * args.steps / elapsed,
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if path == 1 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "sketch": "learned" if args.learned else "gaussian",
-                   "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"],
+                   "mask": "none" if args.noncausal else "causal", "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"],
                    "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
                    "kernel_path": "mfma_bf16" if path == 1 else "general_fp32"},
         "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
@@ -365,10 +401,11 @@ def main():
         out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": achieved,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                           "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
+                           "traffic": None if (args.noncausal or args.learned)
+                           else MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
                            "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc if nm in fl}}
-    if not args.no_cpu_baseline and not args.learned:      # the batch oracle driver takes Gaussian sketches
-        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, G)
+    if not args.no_cpu_baseline and not args.learned:      # the oracle drivers used here take Gaussian sketches
+        out["cpu_baseline"] = cpu_baseline_noncausal(cfg, q, k, v, G) if args.noncausal else cpu_baseline(cfg, q, k, v, G)
     print(json.dumps(out))
 
 

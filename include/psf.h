@@ -141,6 +141,27 @@ psf_status psf_causal_attn_fwd_timed(const psf_desc *desc, const void *Q, const 
 const char *psf_stage_name(int path, int32_t stage);
 
 /*
+ * psf_noncausal_attn_fwd -- Polysketch attention without a mask (Section 2.2):
+ *   O = D^-1 phi'(Q) phi'(K)^T V,  D = diag(1 + phi'(Q) phi'(K)^T 1)
+ * i.e. o_i = sum over ALL j of w_ij v_j / (1 + sum_j w_ij), w_ij = <phi'(q_i), phi'(k_j)>
+ * (PSF_FEAT_EXACT: w_ij = <q_i, k_j>^p).  Same descriptor, arguments, layouts, dtype rules and
+ * error behaviour as psf_causal_attn_fwd; there is no in-block rule here, so `local` is ignored,
+ * and `b` only partitions the work (it must still divide n).  Learned sketches are accepted.
+ * The same two kernel paths (psf_kernel_path); the workspace size is its own:
+ * psf_noncausal_workspace_bytes(desc).  One state per unit is built from all keys and applied
+ * to every query: cost linear in n.  Stage names of the _timed variant: psf_stage_name(path, i)
+ * of the causal call (the same kernels run).
+ */
+size_t psf_noncausal_workspace_bytes(const psf_desc *desc);
+psf_status psf_noncausal_attn_fwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                  const void *G, void *O,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+psf_status psf_noncausal_attn_fwd_timed(const psf_desc *desc, const void *Q, const void *K,
+                                        const void *V, const void *G, void *O,
+                                        void *workspace, size_t workspace_bytes, void *hip_stream,
+                                        float *stage_ms, int32_t n_stages, int32_t *n_written);
+
+/*
  * psf_causal_attn_bwd -- gradient of psf_causal_attn_fwd's output with respect to Q, K and V.
  * The paper trains through the attention of Section 3 (weights of Sections 3.1 / 3.2, sketch of
  * Algorithm 1); this is the chain rule through exactly that function, evaluated with the same

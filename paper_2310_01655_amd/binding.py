@@ -20,7 +20,8 @@ LOCAL_EXACT, LOCAL_SKETCH = 0, 1
 EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_len", "psf_learned_len",
            "psf_sketch",
            "psf_causal_attn_fwd", "psf_causal_attn_fwd_timed", "psf_stage_name",
-           "psf_status_string", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
+           "psf_status_string", "psf_noncausal_workspace_bytes", "psf_noncausal_attn_fwd",
+           "psf_noncausal_attn_fwd_timed", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
            "psf_causal_attn_bwd_timed", "psf_decode_state_bytes", "psf_decode_reset",
            "psf_decode_step")
 
@@ -69,6 +70,12 @@ def lib():
         L.psf_causal_attn_fwd_timed.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp,
                                                 ctypes.POINTER(ctypes.c_float), ctypes.c_int32,
                                                 ctypes.POINTER(ctypes.c_int32)]
+        L.psf_noncausal_workspace_bytes.restype = ctypes.c_size_t
+        L.psf_noncausal_workspace_bytes.argtypes = [dp]
+        L.psf_noncausal_attn_fwd.restype = ctypes.c_int
+        L.psf_noncausal_attn_fwd.argtypes = L.psf_causal_attn_fwd.argtypes
+        L.psf_noncausal_attn_fwd_timed.restype = ctypes.c_int
+        L.psf_noncausal_attn_fwd_timed.argtypes = L.psf_causal_attn_fwd_timed.argtypes
         L.psf_bwd_kernel_path.restype = ctypes.c_int
         L.psf_bwd_kernel_path.argtypes = [dp]
         L.psf_bwd_workspace_bytes.restype = ctypes.c_size_t
@@ -182,12 +189,12 @@ def psf_sketch(desc, X, G, want_m=True, want_phi=False, stream=None):
     return M, Phi
 
 
-def _attn_args(desc, Q, K, V, G, O, workspace):
+def _attn_args(desc, Q, K, V, G, O, workspace, noncausal=False):
     B, H, n, d, dv = desc.batch, desc.heads, desc.n, desc.d, desc.dv
     if O is None:
         O = torch.empty(B, H, n, dv, dtype=Q.dtype, device=Q.device)
     if workspace is None:
-        workspace = alloc_workspace(desc, Q.device)
+        workspace = alloc_noncausal_workspace(desc, Q.device) if noncausal else alloc_workspace(desc, Q.device)
     if not workspace.is_cuda or workspace.dtype != torch.uint8:
         raise ValueError("workspace must be a uint8 GPU tensor")
     gs = _g_shape(desc)
@@ -223,6 +230,43 @@ def psf_causal_attn_fwd_timed(desc, Q, K, V, G, O=None, workspace=None, stream=N
                                          ctypes.byref(written))
     if st != PSF_OK:
         raise PsfError(st, "psf_causal_attn_fwd_timed")
+    path = kernel_path(desc)
+    names = [lib().psf_stage_name(path, i).decode() for i in range(written.value)]
+    return O, {nm: float(ms[i]) for i, nm in enumerate(names)}
+
+
+def noncausal_workspace_bytes(desc):
+    return lib().psf_noncausal_workspace_bytes(ctypes.byref(desc))
+
+
+def alloc_noncausal_workspace(desc, device="cuda"):
+    return torch.empty(max(noncausal_workspace_bytes(desc), 256), dtype=torch.uint8, device=device)
+
+
+def psf_noncausal_attn_fwd(desc, Q, K, V, G, O=None, workspace=None, stream=None):
+    """Polysketch attention without a mask (every query sees every key); returns O."""
+    st = check_desc(desc)
+    if st != PSF_OK:
+        raise PsfError(st, "psf_noncausal_attn_fwd")
+    O, workspace, ptrs = _attn_args(desc, Q, K, V, G, O, workspace, noncausal=True)
+    st = lib().psf_noncausal_attn_fwd(ctypes.byref(desc), *ptrs, _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_noncausal_attn_fwd")
+    return O
+
+
+def psf_noncausal_attn_fwd_timed(desc, Q, K, V, G, O=None, workspace=None, stream=None):
+    """Same call with per-kernel HIP-event timing; returns (O, {stage_name: ms})."""
+    st = check_desc(desc)
+    if st != PSF_OK:
+        raise PsfError(st, "psf_noncausal_attn_fwd_timed")
+    O, workspace, ptrs = _attn_args(desc, Q, K, V, G, O, workspace, noncausal=True)
+    ms = (ctypes.c_float * 16)()
+    written = ctypes.c_int32(0)
+    st = lib().psf_noncausal_attn_fwd_timed(ctypes.byref(desc), *ptrs, _stream_ptr(stream), ms, 16,
+                                            ctypes.byref(written))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_noncausal_attn_fwd_timed")
     path = kernel_path(desc)
     names = [lib().psf_stage_name(path, i).decode() for i in range(written.value)]
     return O, {nm: float(ms[i]) for i, nm in enumerate(names)}

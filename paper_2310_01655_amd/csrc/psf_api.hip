@@ -110,6 +110,23 @@ static psf_status run_attn(const psf_desc *desc, const void *Q, const void *K, c
                                 : general_attn(pb, Q, K, V, G, O, ws, s, tm);
 }
 
+static psf_status run_noncausal(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                const void *G, void *O, void *ws, size_t ws_bytes, void *stream, StageTimer *tm)
+{
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);
+    if (st != PSF_OK) return st;
+    if (!Q || !K || !V || !O) return PSF_ERR_NULL;
+    if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
+    const size_t need = psf_noncausal_workspace_bytes(desc);
+    if (need > 0 && !ws) return PSF_ERR_NULL;
+    if (ws_bytes < need) return PSF_ERR_WORKSPACE;
+    if (((uintptr_t)ws & 255u) != 0) return PSF_ERR_WORKSPACE;
+    hipStream_t s = (hipStream_t)stream;
+    return select_path(pb) == 1 ? mfma_attn_noncausal(pb, Q, K, V, G, O, ws, s, tm)
+                                : general_attn(pb, Q, K, V, G, O, ws, s, tm, true);
+}
+
 // The backward pass runs on MFMA for the shapes of the bf16 forward path it covers.
 static bool bwd_on_mfma(const Problem &pb) { return select_path(pb) == 1 && mfma_bwd_supported(pb); }
 
@@ -215,6 +232,40 @@ psf_status psf_causal_attn_fwd_timed(const psf_desc *desc, const void *Q, const 
     st = tm.begin((hipStream_t)hip_stream);
     if (st != PSF_OK) return st;
     st = run_attn(desc, Q, K, V, G, O, workspace, workspace_bytes, hip_stream, &tm);
+    int w = 0;
+    psf_status st2 = tm.finish(stage_ms, n_stages, &w);
+    if (n_written) *n_written = w;
+    return st != PSF_OK ? st : st2;
+}
+
+size_t psf_noncausal_workspace_bytes(const psf_desc *desc)
+{
+    Problem pb;
+    if (make_problem(desc, &pb) != PSF_OK) return 0;
+    return select_path(pb) == 1 ? mfma_noncausal_workspace_bytes(pb) : general_workspace_bytes(pb);
+}
+
+psf_status psf_noncausal_attn_fwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                  const void *G, void *O, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream)
+{
+    return run_noncausal(desc, Q, K, V, G, O, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+psf_status psf_noncausal_attn_fwd_timed(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                        const void *G, void *O, void *workspace, size_t workspace_bytes,
+                                        void *hip_stream, float *stage_ms, int32_t n_stages,
+                                        int32_t *n_written)
+{
+    if (!stage_ms || n_stages <= 0) return PSF_ERR_NULL;
+    if (n_written) *n_written = 0;
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);       // validate before creating any event
+    if (st != PSF_OK) return st;
+    StageTimer tm;
+    st = tm.begin((hipStream_t)hip_stream);
+    if (st != PSF_OK) return st;
+    st = run_noncausal(desc, Q, K, V, G, O, workspace, workspace_bytes, hip_stream, &tm);
     int w = 0;
     psf_status st2 = tm.finish(stage_ms, n_stages, &w);
     if (n_written) *n_written = w;

@@ -290,13 +290,27 @@ __global__ __launch_bounds__(kThreads) void gen_scan_kernel(float *__restrict__ 
     }
 }
 
+// ---- non-causal attention (Section 2.2): one state for all keys, sum of every H_l, in slot 0 ----
+__global__ __launch_bounds__(kThreads) void gen_total_kernel(float *__restrict__ Z, int units, int t,
+                                                             size_t per_block)
+{
+    const size_t idx = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (idx >= (size_t)units * per_block) return;
+    const size_t u = idx / per_block, e = idx % per_block;
+    float *z = Z + u * (size_t)t * per_block + e;
+    float run = 0.f;
+    for (int l = 0; l < t; ++l) run += z[(size_t)l * per_block];
+    z[0] = run;
+}
+
 // ---- rows of the output: P_l row + phi(q_i)^T Z_l, then divide by 1 + last column ---------
+// noncausal: every row takes phi(q_i)^T Z with the one state in slot 0 and has no in-block part
 template <typename T>
 __global__ __launch_bounds__(kThreads) void gen_out_kernel(
     const float *__restrict__ MQ, const float *__restrict__ MK, const T *__restrict__ Q,
     const T *__restrict__ K, const T *__restrict__ V, const float *__restrict__ Z,
     T *__restrict__ O, int n, int d, int dv, int p, int b, int t, int mcols, long long F,
-    int exact_feat, int local_exact, int rows_per_wg)
+    int exact_feat, int local_exact, int rows_per_wg, int noncausal)
 {
     __shared__ float stage[kOutRows][kOutChunk];
     __shared__ float den_s[kOutRows];
@@ -308,8 +322,8 @@ __global__ __launch_bounds__(kThreads) void gen_out_kernel(
     for (int rt = 0; rt < kOutRows; ++rt) acc[rt][0] = acc[rt][1] = 0.f;
     const size_t urow = (size_t)u * n;
 
-    if (l > 0) {                                        // a_i^T Z_l
-        const float *z = Z + (((size_t)u * t + l) * (size_t)F) * kc;
+    if (l > 0 || noncausal) {                           // a_i^T Z_l
+        const float *z = Z + (((size_t)u * t + (noncausal ? 0 : l)) * (size_t)F) * kc;
         for (long long f0 = 0; f0 < F; f0 += kOutChunk) {
             __syncthreads();
             for (int idx = tid; idx < RT * kOutChunk; idx += kThreads) {
@@ -337,7 +351,7 @@ __global__ __launch_bounds__(kThreads) void gen_out_kernel(
         }
     }
 
-    const int jbeg = l * b, jend = i0 + RT;             // keys jbeg .. i0+RT-1 (row rt keeps j <= i0+rt)
+    const int jbeg = l * b, jend = noncausal ? jbeg : i0 + RT;   // keys jbeg .. i0+RT-1 (row rt keeps j <= i0+rt)
     for (int j0 = jbeg; j0 < jend; j0 += kOutChunk) {   // row of P_l = lt(.) [V_l | 1]
         __syncthreads();
         for (int idx = tid; idx < RT * kOutChunk; idx += kThreads) {
@@ -425,7 +439,7 @@ psf_status sketch_launch(const Problem &pb, const void *X, const void *G, float 
 
 template <typename T>
 psf_status attn_launch(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
-                       void *O, void *ws, hipStream_t s, StageTimer *tm)
+                       void *O, void *ws, hipStream_t s, StageTimer *tm, bool noncausal)
 {
     GeneralWs w = carve(pb, ws);
     psf_status st;
@@ -439,8 +453,8 @@ psf_status attn_launch(const Problem &pb, const void *Q, const void *K, const vo
         if (st != PSF_OK) return st;
     }
     if (tm) tm->mark();
-    if (pb.t > 1) {
-        dim3 grid((unsigned)((pb.F + kStateFeat - 1) / kStateFeat), (unsigned)(pb.t - 1),
+    if (pb.t > 1 || noncausal) {                        // H_l of every block but the last; all of them without a mask
+        dim3 grid((unsigned)((pb.F + kStateFeat - 1) / kStateFeat), (unsigned)(noncausal ? pb.t : pb.t - 1),
                   (unsigned)pb.units);
         hipLaunchKernelGGL(gen_state_kernel<T>, grid, dim3(kThreads), 0, s, w.MK, (const T *)K,
                            (const T *)V, w.Z, pb.n, pb.d, pb.dv, pb.p, pb.b, pb.t, pb.mcols, pb.F,
@@ -448,11 +462,14 @@ psf_status attn_launch(const Problem &pb, const void *Q, const void *K, const vo
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
-    if (pb.t > 1) {
+    if (pb.t > 1 || noncausal) {
         const size_t per_block = (size_t)pb.F * (pb.dv + 1);
         const size_t total = (size_t)pb.units * per_block;
-        hipLaunchKernelGGL(gen_scan_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads)),
-                           dim3(kThreads), 0, s, w.Z, pb.units, pb.t, per_block);
+        const dim3 grid((unsigned)((total + kThreads - 1) / kThreads));
+        if (noncausal)
+            hipLaunchKernelGGL(gen_total_kernel, grid, dim3(kThreads), 0, s, w.Z, pb.units, pb.t, per_block);
+        else
+            hipLaunchKernelGGL(gen_scan_kernel, grid, dim3(kThreads), 0, s, w.Z, pb.units, pb.t, per_block);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
@@ -461,7 +478,8 @@ psf_status attn_launch(const Problem &pb, const void *Q, const void *K, const vo
     dim3 grid((unsigned)(pb.n / rows_per_wg), (unsigned)pb.units);
     hipLaunchKernelGGL(gen_out_kernel<T>, grid, dim3(kThreads), 0, s, w.MQ, w.MK, (const T *)Q,
                        (const T *)K, (const T *)V, w.Z, (T *)O, pb.n, pb.d, pb.dv, pb.p, pb.b, pb.t,
-                       pb.mcols, pb.F, pb.exact_feat ? 1 : 0, pb.local_exact ? 1 : 0, rows_per_wg);
+                       pb.mcols, pb.F, pb.exact_feat ? 1 : 0, pb.local_exact ? 1 : 0, rows_per_wg,
+                       noncausal ? 1 : 0);
     PSF_LAUNCH_CHECK();
     if (tm) tm->mark();
     return PSF_OK;
@@ -489,10 +507,10 @@ psf_status general_sketch_f32(const Problem &pb, const void *X, const void *G, f
 }
 
 psf_status general_attn(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
-                        void *O, void *ws, hipStream_t s, StageTimer *tm)
+                        void *O, void *ws, hipStream_t s, StageTimer *tm, bool noncausal)
 {
-    return pb.bf16 ? attn_launch<bf16_t>(pb, Q, K, V, G, O, ws, s, tm)
-                   : attn_launch<float>(pb, Q, K, V, G, O, ws, s, tm);
+    return pb.bf16 ? attn_launch<bf16_t>(pb, Q, K, V, G, O, ws, s, tm, noncausal)
+                   : attn_launch<float>(pb, Q, K, V, G, O, ws, s, tm, noncausal);
 }
 
 }  // namespace psf

@@ -41,8 +41,10 @@ struct StageTimer {
 size_t general_workspace_bytes(const Problem &pb);
 psf_status general_sketch(const Problem &pb, const void *X, const void *G, void *M_out,
                           void *Phi_out, hipStream_t s);
+// noncausal: Section 2.2 (every query sees every key; b only partitions the work).
 psf_status general_attn(const Problem &pb, const void *Q, const void *K, const void *V,
-                        const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);
+                        const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm,
+                        bool noncausal = false);
 
 // m(x) of every row as fp32 [rows][mcols] (general sketch kernel).
 psf_status general_sketch_f32(const Problem &pb, const void *X, const void *G, float *M_f32,
@@ -73,6 +75,9 @@ psf_status decode_step(const Problem &pb, const void *q, const void *k, const vo
 size_t mfma_workspace_bytes(const Problem &pb);
 psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void *V,
                      const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);
+size_t mfma_noncausal_workspace_bytes(const Problem &pb);
+psf_status mfma_attn_noncausal(const Problem &pb, const void *Q, const void *K, const void *V,
+                               const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);
 
 #define PSF_HIP_TRY(expr)                                   \
     do {                                                    \

@@ -388,7 +388,7 @@ __global__ __launch_bounds__(kWg) void k_v_octets(const bf16_t *__restrict__ V,
 template <int R>
 __global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spart,
                                                   bf16_t *__restrict__ Shi, bf16_t *__restrict__ Slo,
-                                                  int t, int parts_per_block)
+                                                  int t, int parts_per_block, int parts_per_unit)
 {
     const int u = blockIdx.y;
     // one entry of S per thread, threads in the order of the output layout [b'/8][a][8] so that
@@ -397,7 +397,6 @@ __global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spar
     if (dst >= R * R) return;
     const int a = (dst / 8) % R, bq = (dst / (8 * R)) * 8 + dst % 8;
     const int e = a * R + bq;
-    const size_t parts_per_unit = (size_t)t * parts_per_block;
     const float *src = Spart + (size_t)u * parts_per_unit * R * R + e;
     const int total = (t - 1) * parts_per_block;
     float run = 0.f;
@@ -681,7 +680,9 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
 // are in flight while the VALU works on the current one (x^p, mask, row sums, bf16 packing in
 // the in-block phase; the m_i[a] * T_a updates in the cross-block phase).
 // ------------------------------------------------------------------------------------
-template <int R, int D, int P, int TT, bool DEN>
+// NONCAUSAL (Section 2.2): no in-block phase, every token takes the cross-block term with the
+// one state of its unit (slot 0; the caller passes b = n, t = 2).
+template <int R, int D, int P, int TT, bool DEN, bool NONCAUSAL = false>
 __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                 const bf16_t *__restrict__ V8,
                                                 const bf16_t *__restrict__ MQ,
@@ -733,7 +734,7 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
     }
 
     // ---------------- in-block exact weights (Section 3.2) ----------------
-    {
+    if constexpr (!NONCAUSAL) {
         bf16x8 qfr[TT][KS];
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
@@ -912,7 +913,9 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
     }
 
     // ---------------- cross-block term phi'(Q_l) Z_l (Section 3.1) ----------------
-    if (l > 0) {
+    bool cross = l > 0;
+    if constexpr (NONCAUSAL) cross = t > 1;               // always true there; kept a run-time branch on purpose
+    if (cross) {
         bf16x8 mfr[TT][RS];                               // B operands: m(q_i), k index = b'
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
@@ -922,7 +925,7 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
 
         // denominator: m_i^T S m_i with S = prefix of m_j m_j^T, hi + lo operands
         {
-            const size_t sbase = ((size_t)u * (t - 1) + (l - 1)) * R * R;
+            const size_t sbase = ((size_t)u * (t - 1) + (NONCAUSAL ? 0 : l - 1)) * R * R;
 #pragma unroll
             for (int at = 0; at < AT; ++at) {
                 f32x16 td[TT];
@@ -962,7 +965,7 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
 #pragma unroll
                 for (int e = 0; e < 8; ++e) mb[tt][s][e] = (float)mfr[tt][s][e];
 
-        const bf16_t *zsrc = Zg + ((size_t)u * (t - 1) + (l - 1)) * R * R * D;
+        const bf16_t *zsrc = Zg + ((size_t)u * (t - 1) + (NONCAUSAL ? 0 : l - 1)) * R * R * D;
         const uint32_t stage0 = lds_address(stage);
         constexpr int NCHUNK = R / ZA;
         constexpr int BUF_BYTES = Z_CHUNK_BYTES + MQ_CHUNK_BYTES;
@@ -1668,7 +1671,7 @@ psf_status launch_state(const Problem &pb, const float *M8, const bf16_t *V8, bf
 template <int D, int R, int P>
 psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                      void *O, void *ws, hipStream_t s, StageTimer *tm, float *Den = nullptr,
-                     bf16_t *MK_rm = nullptr)
+                     bf16_t *MK_rm = nullptr, bool noncausal = false)
 {
     MfmaWs w = carve(pb, ws);
     const int tiles = sketch_tiles_per_wg(pb.b);
@@ -1725,7 +1728,7 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     if (tm) tm->mark();
     if (pb.t > 1) {
         hipLaunchKernelGGL((k_den_scan<R>), dim3(R * R / kWg, pb.units), dim3(kWg), 0, s, w.Spart, w.Shi,
-                           w.Slo, pb.t, pb.b / part_tokens(pb));
+                           w.Slo, pb.t, pb.b / part_tokens(pb), pb.n / part_tokens(pb));
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
@@ -1739,7 +1742,11 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         // one workgroup per CU; it measured 1.7x slower than TT = 2 with two per CU.)
         constexpr int TT = (D == 64) ? 2 : 1;
         const unsigned grid = (unsigned)((size_t)pb.units * (pb.n / (128 * TT)));
-        if (Den)
+        if (noncausal)
+            hipLaunchKernelGGL((k_out<R, D, P, TT, false, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
+                               (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b,
+                               pb.t);
+        else if (Den)
             hipLaunchKernelGGL((k_out<R, D, P, TT, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
                                (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b,
                                pb.t);
@@ -1791,6 +1798,28 @@ psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void
                      void *O, void *ws, hipStream_t s, StageTimer *tm)
 {
 #define PSF_AT(D_, R_, P_) (attn_impl<D_, R_, P_>(pb, Q, K, V, G, O, ws, s, tm))
+    PSF_DISPATCH(PSF_AT);
+#undef PSF_AT
+}
+
+// Non-causal attention (Section 2.2) = the causal kernels on one "block" of all n tokens whose
+// state every token reads: the state kernel accumulates that block, the output kernel skips
+// its in-block phase.
+static Problem noncausal_problem(const Problem &pb0)
+{
+    Problem pb = pb0;
+    pb.b = pb0.n;
+    pb.t = 2;
+    return pb;
+}
+
+size_t mfma_noncausal_workspace_bytes(const Problem &pb) { return carve(noncausal_problem(pb), nullptr).total; }
+
+psf_status mfma_attn_noncausal(const Problem &pb0, const void *Q, const void *K, const void *V, const void *G,
+                               void *O, void *ws, hipStream_t s, StageTimer *tm)
+{
+    const Problem pb = noncausal_problem(pb0);
+#define PSF_AT(D_, R_, P_) (attn_impl<D_, R_, P_>(pb, Q, K, V, G, O, ws, s, tm, nullptr, nullptr, true))
     PSF_DISPATCH(PSF_AT);
 #undef PSF_AT
 }

@@ -839,7 +839,7 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
         st = launch_state<D, R>(pb, w.M8r, w.G8r, w.Rg, s);
         if (st != PSF_OK) return st;
         hipLaunchKernelGGL((k_den_scan<R>), dim3(R * R / kWg, pb.units), dim3(kWg), 0, s, w.ScPart, w.Rchi, w.Rclo,
-                           pb.t, pb.b / 256);
+                           pb.t, pb.b / 256, pb.n / 256);
         PSF_LAUNCH_CHECK();
         const dim3 grid(R / 8, (unsigned)((size_t)pb.units * (pb.t - 1)));
         hipLaunchKernelGGL((k_bwd_relayout<R, D>), grid, dim3(kWg), 0, s, f.Zg, w.ZT);
