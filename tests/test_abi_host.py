@@ -103,6 +103,44 @@ def test_backward_entry_point_validates_on_the_host():
     assert psf.lib().psf_stage_name(2, 5) == b"sketch_gradient"
 
 
+def test_backward_kernel_path_and_mfma_workspace():
+    mf = psf.make_desc(2, 12, 32768, 64, 4, 64, 1024, "bf16")                 # config 3
+    assert psf.bwd_kernel_path(mf) == 3
+    rows = 2 * 12 * 32768
+    snaps = 2 * 12 * 31
+    # forward workspace + two more sets of state snapshots + the fp32 gradient accumulators
+    assert psf.bwd_workspace_bytes(mf) >= psf.workspace_bytes(mf) + 2 * snaps * 64 * 64 * 64 * 2 + 5 * rows * 64 * 4
+    assert psf.bwd_kernel_path(psf.make_desc(1, 1, 1024, 64, 4, 16, 128, "f32")) == 2
+    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 128, 4, 64, 256, "bf16")) == 2     # d = 128: general kernels
+    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 8, 64, 256, "bf16")) == 2      # p = 8
+    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 4, 64, 256, "bf16", learned=True)) == -1
+    assert psf.lib().psf_stage_name(3, 0) == b"forward_again"
+    assert psf.lib().psf_stage_name(3, 5) == b"sketch_gradient"
+
+
+def test_noncausal_entry_point_validates_on_the_host():
+    L = psf.lib()
+    d = psf.make_desc(1, 1, 1024, 64, 4, 16, 128, "f32")
+    ref = ctypes.byref(d)
+    one = ctypes.c_void_p(256)   # never dereferenced: every call below fails validation first
+    need = psf.noncausal_workspace_bytes(d)
+    assert need >= 2 * 1024 * 16 * 4 + 8 * 256 * 65 * 4          # sketches + one state per block, fp32
+    assert L.psf_noncausal_attn_fwd(ref, None, one, one, one, one, one, 1 << 40, None) == 1
+    assert L.psf_noncausal_attn_fwd(ref, one, one, one, None, one, one, 1 << 40, None) == 1
+    assert L.psf_noncausal_attn_fwd(ref, one, one, one, one, None, one, 1 << 40, None) == 1
+    assert L.psf_noncausal_attn_fwd(ref, one, one, one, one, one, None, 1 << 40, None) == 1
+    assert L.psf_noncausal_attn_fwd(ref, one, one, one, one, one, one, need - 1, None) == 4
+    assert L.psf_noncausal_attn_fwd(ref, one, one, one, one, one, ctypes.c_void_p(264), 1 << 40, None) == 4
+    assert L.psf_noncausal_attn_fwd_timed(ref, one, one, one, one, one, one, 1 << 40, None, None, 0, None) == 1
+    # MFMA path: one snapshot per unit however many blocks the descriptor names
+    a = psf.make_desc(2, 12, 32768, 64, 4, 64, 1024, "bf16")
+    b = psf.make_desc(2, 12, 32768, 64, 4, 64, 256, "bf16")
+    assert psf.noncausal_workspace_bytes(a) == psf.noncausal_workspace_bytes(b) < psf.workspace_bytes(a)
+    d.p = 5
+    assert L.psf_noncausal_attn_fwd(ref, one, one, one, one, one, one, 1 << 40, None) == 3
+    assert psf.noncausal_workspace_bytes(d) == 0
+
+
 def test_decode_entry_points_validate_on_the_host():
     L = psf.lib()
     d = psf.make_desc(2, 3, 4096, 64, 4, 32, 256, "bf16")
