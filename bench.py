@@ -118,9 +118,9 @@ def bwd_stage_flops_mfma(cfg):
         "forward_again": stage_flops(cfg)["total"],
         "g_c_and_layouts": U * 4 * n * d,
         "mirror_states": U * cross,
-        "cross_block": U * (3 * cross + 8 * (n - b) * F),                    # dm(q), dm(k), dV; S and Rc terms
-        "in_block": U * pairs * 2 * 7 * d,                                   # 3 + 4 tile products per pair
-        "sketch_gradient": U * 2 * 16 * n * d * r,                           # projections again + transposed products
+        "in_block_and_dv": U * (pairs * 2 * 7 * d + cross),                  # 3 + 4 tile products per pair; phi'(K)^T R_l
+        # dm(q), dm(k) with their S / Rc terms; projections again + transposed products
+        "cross_block_and_sketch_gradient": U * (2 * cross + 8 * (n - b) * F + 2 * 16 * n * d * r),
     }
     f["total"] = sum(f.values())
     return f

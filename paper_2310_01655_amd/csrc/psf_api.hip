@@ -358,9 +358,9 @@ const char *psf_stage_name(int path, int32_t stage)
     static const char *bwd[] = {"sketches", "forward_rows", "reverse_states", "query_side",
                                 "key_side", "sketch_gradient"};
     if (path == 2 && stage >= 0 && stage < 6) return bwd[stage];
-    static const char *bwd_mfma[] = {"forward_again", "g_c_and_layouts", "mirror_states", "cross_block",
-                                     "in_block", "sketch_gradient"};
-    if (path == 3 && stage >= 0 && stage < 6) return bwd_mfma[stage];
+    static const char *bwd_mfma[] = {"forward_again", "g_c_and_layouts", "mirror_states", "in_block_and_dv",
+                                     "cross_block_and_sketch_gradient"};
+    if (path == 3 && stage >= 0 && stage < 5) return bwd_mfma[stage];
     static const char *general[] = {"sketch_q", "sketch_k", "block_states", "exclusive_scan",
                                     "output"};
     static const char *mfma[] = {"sketch_and_layouts", "denominator_scan", "block_states_scan",

@@ -20,7 +20,13 @@
 //   k_out          per 256-token tile: exact in-block weights lt((Q_l K_l^T)^p) [V_l | 1]
 //                  (Section 3.2) kept in registers, plus phi'(Q_l) Z_l with phi'(q_i) expanded
 //                  in registers as the MFMA operand, then the division by 1 + denominator
-//                  (Section 3).
+//                  (Section 3).  NONCAUSAL instantiation (Section 2.2): no in-block phase, one
+//                  state for all tokens.
+//   k_learned_prep, k_learned_sketch
+//                  Algorithm 2 (learned sketches) of degree 4 with d = 64 on MFMA; other learned
+//                  cases take m(x) from the general fp32 kernel through k_m_to_bf16 /
+//                  k_m_to_octets_and_partials.
+//   psf_mfma_bwd.inl (included below): the backward pass for d = 64, p = 4.
 //
 // MFMA v_mfma_f32_32x32x16_bf16 operand layout used throughout (lane = 32*h + x, x < 32):
 //   A[i][k]: lane x = i, half h supplies k = 8h..8h+7 (8 bf16 per lane)

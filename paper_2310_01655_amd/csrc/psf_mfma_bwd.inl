@@ -205,6 +205,81 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
     }
 }
 
+// ---- through Algorithm 1 (p = 4), one 32-token tile of a wave --------------------------------
+// dx = dXacc + sqrt(1/r) [(dm * (x G2)) G1^T + (dm * (x G1)) G2^T].  lds: the transposed sketch
+// matrices as the forward sketch kernel stages them (for the recomputed projections); go: G1,
+// G2 as given, rows [d][r] padded to GP (for the transposed products, whose A fragments are read
+// in accumulator order).  dm: lane = token, register = sketch column, as the accumulators of
+// the cross-block kernel leave it.
+template <int D, int R>
+__device__ __forceinline__ void sketch_grad_tile(const SketchLds<D, R> &lds, const bf16_t *go,
+                                                 const bf16_t *__restrict__ X, const f32x16 *dm,
+                                                 const float *__restrict__ dXacc, bf16_t *__restrict__ dX,
+                                                 size_t row, int x, int h)
+{
+    constexpr int KS = D / 16, NT = R / 32, DT = D / 32, GP = R + 8;
+    const float scale = sqrtf(1.0f / (float)R);
+    bf16x8 xfr[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
+    f32x16 a0[NT], a1[NT];                                  // lane = token, register = sketch column
+    project<D, R, KS, true>(lds.gt[0], xfr, a0, x, h);
+    project<D, R, KS, true>(lds.gt[1], xfr, a1, x, h);
+    bf16x8 d0[2 * NT], d1[2 * NT];                          // B operands, contraction over sketch columns
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct) {
+        f32x16 da0, da1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            da0[v] = scale * dm[ct][v] * a1[ct][v];
+            da1[v] = scale * dm[ct][v] * a0[ct][v];
+        }
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+            d0[2 * ct + sp] = cvt8_from16(da0, 8 * sp);
+            d1[2 * ct + sp] = cvt8_from16(da1, 8 * sp);
+        }
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+        f32x16 acc = {0};
+#pragma unroll
+        for (int ks = 0; ks < 2 * NT; ++ks) {
+            // entries e of the step are sketch columns 16 ks + 8 (e / 4) + 4 h + e % 4
+            const int off = (32 * dt + x) * GP + 16 * ks + 4 * h;
+            const bf16x4 lo1 = *(const bf16x4 *)&go[off], hi1 = *(const bf16x4 *)&go[off + 8];
+            const bf16x4 lo2 = *(const bf16x4 *)&go[D * GP + off], hi2 = *(const bf16x4 *)&go[D * GP + off + 8];
+            bf16x8 f1, f2;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { f1[e] = lo1[e]; f1[4 + e] = hi1[e]; f2[e] = lo2[e]; f2[4 + e] = hi2[e]; }
+            acc = mfma32(f1, d0[ks], acc);
+            acc = mfma32(f2, d1[ks], acc);
+        }
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const size_t off = row * D + 32 * dt + 8 * gq + 4 * h;
+            const f32x4 base = *(const f32x4 *)&dXacc[off];
+            const f32x4 q4 = {acc[4 * gq] + base[0], acc[4 * gq + 1] + base[1], acc[4 * gq + 2] + base[2],
+                              acc[4 * gq + 3] + base[3]};
+            *(bf16x4 *)&dX[off] = cvt4(q4);
+        }
+    }
+}
+
+// Both sets of sketch matrices of one parameter set into LDS (see sketch_grad_tile).
+template <int D, int R>
+__device__ __forceinline__ void sketch_grad_stage(SketchLds<D, R> &lds, bf16_t *go, const bf16_t *__restrict__ Gt,
+                                                  const bf16_t *__restrict__ G)
+{
+    constexpr int GP = R + 8;
+    stage_gt<D, R, D>(lds.gt[0], Gt);
+    stage_gt<D, R, D>(lds.gt[1], Gt + (size_t)D * R);
+    for (int idx = threadIdx.x; idx < 2 * D * (R / 8); idx += kWg) {
+        const int m = idx / (D * (R / 8)), rem = idx % (D * (R / 8)), e = rem / (R / 8), part = rem % (R / 8);
+        *(uint4 *)&go[(m * D + e) * GP + 8 * part] = *(const uint4 *)&G[(size_t)m * D * R + (size_t)e * R + 8 * part];
+    }
+}
+
 // ---- generic cross-block contraction ---------------------------------------------------------
 // out^T[o][token] += sum_{a < NS} sum_{k < NV} (sc_token[a] * vec_token[k]) * Z[a][k][o],  Z stored
 // [NS][NV/8][NO][8] bf16 (k octets innermost: 16-byte A fragments with rows o).  The B operand
@@ -290,14 +365,20 @@ struct Cross {
 // ---- dm(q) and dm(k): cross-block part -------------------------------------------------------
 // QSIDE: tokens of block l >= 1 with ZT / S of slot l - 1, vec = g, coefficient c_i.
 // key side: tokens of block l <= t - 2 with RT / Rc of the mirror slot t - 2 - l, vec = v,
-// coefficient 1.  Blocks without a cross-block term get zeros.  dM: fp32 rows [rows][R].
+// coefficient 1.  Blocks without a cross-block term have dm = 0.  dm stays in registers and goes
+// straight through Algorithm 1 (sketch_grad_tile): dX = bf16(dXacc + J_m(x)^T dm), with dXacc the
+// in-block part, for the rows X (Q or K) of the workgroup.
 template <int R, int D, bool QSIDE, int TT>
 __global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M, const bf16_t *__restrict__ Vec,
                                                   const float *__restrict__ Cc, const bf16_t *__restrict__ ZT,
                                                   const bf16_t *__restrict__ Shi, const bf16_t *__restrict__ Slo,
-                                                  float *__restrict__ dM, int n, int b, int t)
+                                                  const bf16_t *__restrict__ Xrows, const bf16_t *__restrict__ Gt,
+                                                  const bf16_t *__restrict__ G, const float *__restrict__ dXacc,
+                                                  bf16_t *__restrict__ dX, int n, int b, int t, int heads,
+                                                  int per_head, size_t g_len)
 {
     using X = Cross<R, D, R, false, TT>;
+    static_assert(sizeof(SketchLds<D, R>) + 2 * D * (R + 8) * 2 <= X::LDS_BYTES, "the sketch matrices reuse the stage");
     constexpr int AT = R / 32, RS = R / 16, VS = D / 16, TOK_WG = 128 * TT;
     __shared__ __attribute__((aligned(16))) unsigned char stage[X::LDS_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
@@ -359,18 +440,15 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M,
             }
         }
     }
+    // through the sketch; the stage is free again (the contraction ends with a barrier)
+    SketchLds<D, R> &lds = *(SketchLds<D, R> *)stage;
+    bf16_t *go = (bf16_t *)(stage + sizeof(SketchLds<D, R>));
+    const size_t goff = per_head ? (size_t)(u % heads) * g_len : 0;
+    sketch_grad_stage<D, R>(lds, go, Gt + goff, G + goff);
+    __syncthreads();
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        const size_t row = urow + i0 + wave * 32 * TT + 32 * tt + x;
-#pragma unroll
-        for (int at = 0; at < AT; ++at)
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const f32x4 q4 = {out[tt][at][4 * gq], out[tt][at][4 * gq + 1], out[tt][at][4 * gq + 2],
-                                  out[tt][at][4 * gq + 3]};
-                *(f32x4 *)&dM[row * R + 32 * at + 8 * gq + 4 * h] = q4;
-            }
-    }
+    for (int tt = 0; tt < TT; ++tt)
+        sketch_grad_tile<D, R>(lds, go, Xrows, out[tt], dXacc, dX, urow + i0 + wave * 32 * TT + 32 * tt + x, x, h);
 }
 
 // ---- dV: cross-block part = phi'(k_j)^T R_l (value columns) ----------------------------------
@@ -671,91 +749,11 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict
         }
 }
 
-// ---- through Algorithm 1 (p = 4): dx = dXacc + sqrt(1/r) [(dm * (x G2)) G1^T + (dm * (x G1)) G2^T]
-// Workgroup = 128 tokens; Gt = transposed sketch matrices (as the forward sketch kernel stages
-// them) for the recomputed projections, G = the matrices as given ([d][r] rows) for the
-// transposed products, whose A fragments are read straight from them in accumulator order.
-template <int D, int R>
-__global__ __launch_bounds__(kWg, 2) void k_bwd_sketch(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Gt,
-                                                    const bf16_t *__restrict__ G, const float *__restrict__ dM,
-                                                    const float *__restrict__ dXacc, bf16_t *__restrict__ dX,
-                                                    int n, int heads, int per_head, size_t g_len, int tiles_per_wg)
-{
-    constexpr int KS = D / 16, NT = R / 32, DT = D / 32, GP = R + 8;
-    __shared__ __attribute__((aligned(16))) SketchLds<D, R> lds;
-    __shared__ __attribute__((aligned(16))) bf16_t go[2][D * GP];       // G1, G2 as given: rows [d][r], padded
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, x = lane & 31, h = lane >> 5;
-    const size_t row_wg0 = (size_t)blockIdx.x * tiles_per_wg * 128;
-    const int head = (int)((row_wg0 / n) % heads);
-    const size_t goff = per_head ? (size_t)head * g_len : 0;
-    const float scale = sqrtf(1.0f / (float)R);
-    stage_gt<D, R, D>(lds.gt[0], Gt + goff);
-    stage_gt<D, R, D>(lds.gt[1], Gt + goff + (size_t)D * R);
-    for (int idx = threadIdx.x; idx < 2 * D * (R / 8); idx += kWg) {
-        const int m = idx / (D * (R / 8)), rem = idx % (D * (R / 8)), e = rem / (R / 8), part = rem % (R / 8);
-        *(uint4 *)&go[m][e * GP + 8 * part] = *(const uint4 *)&G[goff + (size_t)m * D * R + (size_t)e * R + 8 * part];
-    }
-    __syncthreads();
-#pragma unroll 1
-    for (int tile = 0; tile < tiles_per_wg; ++tile) {
-        const size_t row = row_wg0 + (size_t)tile * 128 + wave * 32 + x;
-        bf16x8 xfr[KS];
-#pragma unroll
-        for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
-        f32x16 a0[NT], a1[NT];                              // lane = token, register = sketch column
-        project<D, R, KS, true>(lds.gt[0], xfr, a0, x, h);
-        project<D, R, KS, true>(lds.gt[1], xfr, a1, x, h);
-        bf16x8 d0[2 * NT], d1[2 * NT];                      // B operands, contraction over sketch columns
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct) {
-            f32x16 da0, da1;
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const f32x4 m4 = *(const f32x4 *)&dM[row * R + 32 * ct + 8 * gq + 4 * h];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    da0[4 * gq + j] = scale * m4[j] * a1[ct][4 * gq + j];
-                    da1[4 * gq + j] = scale * m4[j] * a0[ct][4 * gq + j];
-                }
-            }
-#pragma unroll
-            for (int sp = 0; sp < 2; ++sp) {
-                d0[2 * ct + sp] = cvt8_from16(da0, 8 * sp);
-                d1[2 * ct + sp] = cvt8_from16(da1, 8 * sp);
-            }
-        }
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            f32x16 acc = {0};
-#pragma unroll
-            for (int ks = 0; ks < 2 * NT; ++ks) {
-                // entries e of the step are sketch columns 16 ks + 8 (e / 4) + 4 h + e % 4
-                const int off = (32 * dt + x) * GP + 16 * ks + 4 * h;
-                const bf16x4 lo1 = *(const bf16x4 *)&go[0][off], hi1 = *(const bf16x4 *)&go[0][off + 8];
-                const bf16x4 lo2 = *(const bf16x4 *)&go[1][off], hi2 = *(const bf16x4 *)&go[1][off + 8];
-                bf16x8 f1, f2;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { f1[e] = lo1[e]; f1[4 + e] = hi1[e]; f2[e] = lo2[e]; f2[4 + e] = hi2[e]; }
-                acc = mfma32(f1, d0[ks], acc);
-                acc = mfma32(f2, d1[ks], acc);
-            }
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const size_t off = row * D + 32 * dt + 8 * gq + 4 * h;
-                const f32x4 base = *(const f32x4 *)&dXacc[off];
-                const f32x4 q4 = {acc[4 * gq] + base[0], acc[4 * gq + 1] + base[1], acc[4 * gq + 2] + base[2],
-                                  acc[4 * gq + 3] + base[3]};
-                *(bf16x4 *)&dX[off] = cvt4(q4);
-            }
-        }
-    }
-}
-
 // ---- host ---------------------------------------------------------------------------------------
 struct MfmaBwdWs {
     void *fwd;                                               // the forward workspace
     bf16_t *O, *MK, *G_rm, *G8, *G8r, *Q8, *K8, *QF, *KF, *VF, *GF, *Rg, *ZT, *RT, *Rchi, *Rclo;
-    float *Den, *Cc, *M8r, *ScPart, *dMQ, *dMK, *dVc, *dQacc, *dKacc;
+    float *Den, *Cc, *M8r, *ScPart, *dVc, *dQacc, *dKacc;
     size_t total;
 };
 
@@ -788,8 +786,6 @@ MfmaBwdWs carve_bwd(const Problem &pb, void *ws)
     w.Cc = (float *)take(rows * 4);
     w.M8r = (float *)take(rows * R * 4);
     w.ScPart = (float *)take(rows / 256 * R * R * 4);
-    w.dMQ = (float *)take(rows * R * 4);
-    w.dMK = (float *)take(rows * R * 4);
     w.dVc = (float *)take(rows * D * 4);
     w.dQacc = (float *)take(rows * D * 4);
     w.dKacc = (float *)take(rows * D * 4);
@@ -848,39 +844,34 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
-    // cross-block parts
-    {
-        const unsigned grid = (unsigned)(rows / (128 * TT));
-        hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm, w.Cc, w.ZT, f.Shi,
-                           f.Slo, w.dMQ, pb.n, pb.b, pb.t);
-        PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_bwd_dm<R, D, false, TT>), dim3(grid), dim3(kWg), 0, s, w.MK, v, w.Cc, w.RT, w.Rchi,
-                           w.Rclo, w.dMK, pb.n, pb.b, pb.t);
-        PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_bwd_dvc<R, D, TT>), dim3(grid), dim3(kWg), 0, s, w.MK, w.Rg, w.dVc, pb.n, pb.b, pb.t);
-        PSF_LAUNCH_CHECK();
-    }
-    if (tm) tm->mark();
     // in-block parts
     {
         const unsigned grid = (unsigned)(rows / 128);
         hipLaunchKernelGGL((k_bwd_local_q<P>), dim3(grid), dim3(kWg), 0, s, q, w.KF, w.VF, w.K8, w.G_rm, w.Cc,
                            w.dQacc, pb.n, pb.b);
         PSF_LAUNCH_CHECK();
+    }
+    {
+        // dV: the cross-block part first, the in-block kernel adds to it
+        const unsigned gridc = (unsigned)(rows / (128 * TT)), grid = (unsigned)(rows / 128);
+        hipLaunchKernelGGL((k_bwd_dvc<R, D, TT>), dim3(gridc), dim3(kWg), 0, s, w.MK, w.Rg, w.dVc, pb.n, pb.b, pb.t);
+        PSF_LAUNCH_CHECK();
         hipLaunchKernelGGL((k_bwd_local_k<P>), dim3(grid), dim3(kWg), 0, s, w.QF, k, v, w.Q8, w.GF, w.G8, w.Cc,
                            w.dVc, w.dKacc, (bf16_t *)dV, pb.n, pb.b);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
-    // through the sketch
+    // cross-block parts of dm(q), dm(k), then through the sketch together with the in-block parts
     {
-        const int tiles = sketch_tiles_per_wg(pb.b);
-        const unsigned grid = (unsigned)(rows / (128 * (size_t)tiles));
-        hipLaunchKernelGGL((k_bwd_sketch<D, R>), dim3(grid), dim3(kWg), 0, s, q, f.Gt, (const bf16_t *)G, w.dMQ,
-                           w.dQacc, (bf16_t *)dQ, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles);
+        const unsigned grid = (unsigned)(rows / (128 * TT));
+        const int ph = pb.per_head ? 1 : 0;
+        hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm, w.Cc, w.ZT, f.Shi,
+                           f.Slo, q, f.Gt, (const bf16_t *)G, w.dQacc, (bf16_t *)dQ, pb.n, pb.b, pb.t, pb.heads, ph,
+                           pb.g_len);
         PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_bwd_sketch<D, R>), dim3(grid), dim3(kWg), 0, s, k, f.Gt, (const bf16_t *)G, w.dMK,
-                           w.dKacc, (bf16_t *)dK, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles);
+        hipLaunchKernelGGL((k_bwd_dm<R, D, false, TT>), dim3(grid), dim3(kWg), 0, s, w.MK, v, w.Cc, w.RT, w.Rchi,
+                           w.Rclo, k, f.Gt, (const bf16_t *)G, w.dKacc, (bf16_t *)dK, pb.n, pb.b, pb.t, pb.heads, ph,
+                           pb.g_len);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();

@@ -115,7 +115,7 @@ def test_backward_kernel_path_and_mfma_workspace():
     assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 8, 64, 256, "bf16")) == 2      # p = 8
     assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 4, 64, 256, "bf16", learned=True)) == -1
     assert psf.lib().psf_stage_name(3, 0) == b"forward_again"
-    assert psf.lib().psf_stage_name(3, 5) == b"sketch_gradient"
+    assert psf.lib().psf_stage_name(3, 4) == b"cross_block_and_sketch_gradient"
 
 
 def test_noncausal_entry_point_validates_on_the_host():
