@@ -139,9 +139,9 @@ __global__ __launch_bounds__(kWg) void k_bwd_qoct(const bf16_t *__restrict__ MQ,
 
 // ---- state snapshots re-laid for the gradient ------------------------------------------------
 // In:  Zs [snap][a][b'/8][c][8], the format the state kernel writes (b' > a doubled, b' = a once,
-//      b' < a zero).  Out: ZT [snap][b][c/8][e][8] = Z[e][b][c], the full symmetric state with the
-//      value column as the contraction octet and the free sketch index e as the row of an MFMA A
-//      operand.  Workgroup = (octet of b, snapshot).
+//      b' < a zero).  Out: ZT [snap][b][c/8][e][8] = 2 Z[e][b][c], twice the full symmetric state
+//      (so only the diagonal needs arithmetic) with the value column as the contraction octet and
+//      the free sketch index e as the row of an MFMA A operand.  Workgroup = (octet of b, snapshot).
 template <int R, int D>
 __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__ Zs, bf16_t *__restrict__ ZT)
 {
@@ -152,9 +152,9 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
     const int tid = threadIdx.x, ob = blockIdx.x;
     const bf16_t *src = Zs + (size_t)blockIdx.y * R * R * D;
     bf16_t *dst = ZT + (size_t)blockIdx.y * R * R * D;
-    auto half = [](uint32_t bits) { return f32_to_bf16(0.5f * bf16_to_f32((bf16_t)bits)); };
+    auto twice = [](uint32_t bits) { return f32_to_bf16(2.0f * bf16_to_f32((bf16_t)bits)); };
     // 16-byte pieces of the source, all loads of a thread issued before their use:
-    //   pieces [0, 8 ob D): rows e < 8 ob, octet ob (b > e there: Z[e][b][c] = Zs[e][b][c] / 2)
+    //   pieces [0, 8 ob D): rows e < 8 ob, octet ob (b > e there: 2 Z[e][b][c] = Zs[e][b][c])
     //   the rest: rows a of this octet, column octets ob2 >= ob
     constexpr int PIECES = 8 * D * (R / 8) / kWg;
     const int n_a = 8 * ob * D, per_a = (R / 8 - ob) * D;
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
         if (idx < n_a) {
             const int e = idx / D, c = idx % D;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) at(j, e, c) = half((w[j / 2] >> (16 * (j % 2))) & 0xffffu);
+            for (int j = 0; j < 8; ++j) at(j, e, c) = (bf16_t)((w[j / 2] >> (16 * (j % 2))) & 0xffffu);
         } else {
             const int k2 = idx - n_a, a8 = k2 / per_a, rem = k2 % per_a, ob2 = ob + rem / D, c = rem % D;
             const int a = 8 * ob + a8;
@@ -187,11 +187,10 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
                 const int bp = 8 * ob2 + j;
                 const uint32_t bits = (w[j / 2] >> (16 * (j % 2))) & 0xffffu;
                 if (bp > a) {
-                    const bf16_t v = half(bits);
-                    at(a8, bp, c) = v;                     // (b = a, e = b')
-                    if (ob2 == ob) at(j, a, c) = v;        // mirror inside the diagonal octet: (b = b', e = a)
+                    at(a8, bp, c) = (bf16_t)bits;          // (b = a, e = b')
+                    if (ob2 == ob) at(j, a, c) = (bf16_t)bits;   // mirror inside the diagonal octet: (b = b', e = a)
                 } else if (bp == a) {
-                    at(a8, a, c) = (bf16_t)bits;
+                    at(a8, a, c) = twice(bits);
                 }
             }
         }
@@ -436,7 +435,7 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M,
             for (int tt = 0; tt < TT; ++tt) {
                 const float coef = QSIDE ? Cc[urow + i0 + wave * 32 * TT + 32 * tt + x] : 1.0f;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) out[tt][at][v] = 2.0f * (out[tt][at][v] + coef * td[tt][v]);
+                for (int v = 0; v < 16; ++v) out[tt][at][v] += 2.0f * coef * td[tt][v];   // the state operand is stored doubled
             }
         }
     }
