@@ -498,7 +498,7 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dvc(const bf16_t *__restrict__ M
 }
 
 // ---- in-block pairs ---------------------------------------------------------------------------
-// Both kernels: workgroup = 128 "own" rows (wave = 32, held in registers as B operands), the
+// Both kernels: workgroup = 32 NW "own" rows (wave = 32, held in registers as B operands), the
 // other side streams through LDS in tiles of 64 rows, double buffered: its rows as
 // [D/8][64][8] (16-byte A fragments, contraction over d) and its octets [8][D][8] (A fragments
 // with contraction over the tile's rows).  Score tiles come out transposed (lane = own row,
@@ -510,28 +510,36 @@ constexpr int kLocRows = kLocT * 64 * 2;                    // bytes of one [D/8
 // X [rows][64] bf16 -> XF [rows/64][8][64][8]: per 64-row tile the layout the in-block kernels keep
 // in LDS (16-byte A fragments with contraction over the 64 columns), so that staging a tile is
 // a straight, fully coalesced copy.
+// scale: a power of two (exact in bf16) the copy is multiplied by; 1 for a plain re-layout.
 __global__ __launch_bounds__(kWg) void k_bwd_row_tiles(const bf16_t *__restrict__ X, bf16_t *__restrict__ XF,
-                                                       size_t pieces)
+                                                       size_t pieces, float scale)
 {
     const size_t idx = (size_t)blockIdx.x * kWg + threadIdx.x;         // (tile, row, column octet)
     if (idx >= pieces) return;
     const size_t tile = idx / 512;
     const int key = (int)(idx % 512) / 8, doct = (int)(idx % 8);
-    *(uint4 *)&XF[((tile * 8 + doct) * kLocT + key) * 8] = *(const uint4 *)&X[idx * 8];
+    bf16x8 v = *(const bf16x8 *)&X[idx * 8];
+    if (scale != 1.0f) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (__bf16)((float)v[e] * scale);
+    }
+    *(bf16x8 *)&XF[((tile * 8 + doct) * kLocT + key) * 8] = v;
 }
 // tile of rows [j0, j0 + 64) of XF -> LDS, straight copy
+template <int NTHR>
 __device__ __forceinline__ void loc_stage_rows(const bf16_t *XF, size_t j0, unsigned char *dst, int tid, int wave)
 {
 #pragma unroll
-    for (int q = 0; q < kLocRows / 16 / kWg; ++q)
-        dma16(XF + j0 * 64 + (size_t)(q * kWg + tid) * 8, dst + (size_t)(q * kWg + wave * 64) * 16);
+    for (int q = 0; q < kLocRows / 16 / NTHR; ++q)
+        dma16(XF + j0 * 64 + (size_t)(q * NTHR + tid) * 8, dst + (size_t)(q * NTHR + wave * 64) * 16);
 }
 // octets of rows [j0, j0 + 64) of X8 ([rows/8][64][8]) -> LDS, straight copy
+template <int NTHR>
 __device__ __forceinline__ void loc_stage_octets(const bf16_t *X8, size_t j0, unsigned char *dst, int tid, int wave)
 {
 #pragma unroll
-    for (int q = 0; q < kLocRows / 16 / kWg; ++q)
-        dma16(X8 + j0 * 64 + (size_t)(q * kWg + tid) * 8, dst + (size_t)(q * kWg + wave * 64) * 16);
+    for (int q = 0; q < kLocRows / 16 / NTHR; ++q)
+        dma16(X8 + j0 * 64 + (size_t)(q * NTHR + tid) * 8, dst + (size_t)(q * NTHR + wave * 64) * 16);
 }
 // 16 fp32 (lane = own row, register v = streamed row 8 (v / 4) + 4 h + v % 4) -> two bf16 B
 // fragments whose 8 entries are the streamed rows 16 sp + 8 h + e
@@ -549,22 +557,22 @@ __device__ __forceinline__ void loc_pack(const f32x16 &w, bf16x8 (&pw)[2])
 
 // dQ (in-block): own rows = queries, streamed = keys of the same block up to the diagonal.
 //   dq_i = sum_{j <= i} (<g_i, v_j> + c_i) p <q_i, k_j>^(p-1) k_j          -> dQacc fp32 rows
-template <int P>
-__global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ KF,
+template <int P, int NW>
+__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void k_bwd_local_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ KF,
                                                        const bf16_t *__restrict__ VF, const bf16_t *__restrict__ K8,
                                                        const bf16_t *__restrict__ G_rm, const float *__restrict__ Cc,
                                                        float *__restrict__ dQacc, int n, int b)
 {
-    constexpr int D = 64, KS = 4, CT = 2, BUF = 3 * kLocRows;
+    constexpr int D = 64, KS = 4, CT = 2, BUF = 3 * kLocRows, NTHR = 64 * NW, OWN = 32 * NW;
     __shared__ __attribute__((aligned(16))) unsigned char stage[2 * BUF];
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tiles_per_unit = n / 128;
+    const int tiles_per_unit = n / OWN;
     // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
     // contiguous range of tiles: the workgroups that stream the same rows then share one L2
     int wg = blockIdx.x;
     if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int u = wg / tiles_per_unit, i0 = (wg % tiles_per_unit) * 128;
+    const int u = wg / tiles_per_unit, i0 = (wg % tiles_per_unit) * OWN;
     const int jb = (i0 / b) * b;
     const size_t urow = (size_t)u * n;
     const int tok0 = i0 + 32 * wave, tok = tok0 + x;
@@ -573,16 +581,18 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict
     for (int s = 0; s < KS; ++s) {
         qfr[s] = *(const bf16x8 *)&Q[(urow + tok) * D + 16 * s + 8 * h];
         gfr[s] = *(const bf16x8 *)&G_rm[(urow + tok) * D + 16 * s + 8 * h];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gfr[s][e] = (__bf16)((float)gfr[s][e] * (float)P);   // p of p s^(p-1), exact (power of two)
     }
-    const float c_me = Cc[urow + tok];
+    const float c_me = (float)P * Cc[urow + tok];
     f32x16 dq[CT] = {f32x16{0}, f32x16{0}};
-    const int ntiles = (i0 + 128 - jb) / kLocT;
+    const int ntiles = (i0 + OWN - jb) / kLocT;
     auto stage_tile = [&](int kt) {
         unsigned char *dst = stage + (kt & 1) * BUF;
         const size_t j0 = urow + jb + (size_t)kt * kLocT;
-        loc_stage_rows(KF, j0, dst, tid, wave);
-        loc_stage_rows(VF, j0, dst + kLocRows, tid, wave);
-        loc_stage_octets(K8, j0, dst + 2 * kLocRows, tid, wave);
+        loc_stage_rows<NTHR>(KF, j0, dst, tid, wave);
+        loc_stage_rows<NTHR>(VF, j0, dst + kLocRows, tid, wave);
+        loc_stage_octets<NTHR>(K8, j0, dst + 2 * kLocRows, tid, wave);
     };
     stage_tile(0);
 #pragma unroll 1
@@ -610,12 +620,12 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict
             bf16x8 pw[2][2];
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
-                const int key0 = jb + kt * kLocT + 32 * sub;
+                // key = key0 + 8 (v / 4) + 4 h + v % 4 <= tok  <=>  8 (v / 4) + v % 4 <= lim
+                const int lim = tok - (jb + kt * kLocT + 32 * sub) - 4 * h;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
-                    const float dp = (dw[sub][v] + c_me) * (float)P * pow_n<P - 1>(sc[sub][v]);
-                    dw[sub][v] = key <= tok ? dp : 0.f;
+                    const float sm = (8 * (v / 4) + (v % 4) <= lim) ? sc[sub][v] : 0.f;   // masked pairs: every power is 0
+                    dw[sub][v] = (dw[sub][v] + c_me) * pow_n<P - 1>(sm);
                 }
                 loc_pack(dw[sub], pw[sub]);
             }
@@ -642,23 +652,24 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_q(const bf16_t *__restrict
 // dK (in-block) and dV (in-block + the cross-block part already in dVc): own rows = keys,
 // streamed = queries of the same block from the diagonal on.
 //   dk_j = sum_{i >= j} (<g_i, v_j> + c_i) p <q_i, k_j>^(p-1) q_i   -> dKacc fp32 rows
+//          (GF, the streamed rows of g for the first product, and the staged c carry the factor p)
 //   dv_j = sum_{i >= j} <q_i, k_j>^p g_i + dVc_j                     -> dV bf16 rows
-template <int P>
-__global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict__ QF, const bf16_t *__restrict__ K,
+template <int P, int NW>
+__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void k_bwd_local_k(const bf16_t *__restrict__ QF, const bf16_t *__restrict__ K,
                                                        const bf16_t *__restrict__ V, const bf16_t *__restrict__ Q8,
                                                        const bf16_t *__restrict__ GF, const bf16_t *__restrict__ G8,
                                                        const float *__restrict__ Cc, const float *__restrict__ dVc,
                                                        float *__restrict__ dKacc, bf16_t *__restrict__ dV, int n,
                                                        int b)
 {
-    constexpr int D = 64, KS = 4, CT = 2, BUF = 4 * kLocRows + kLocT * 4;
+    constexpr int D = 64, KS = 4, CT = 2, BUF = 4 * kLocRows + kLocT * 4, NTHR = 64 * NW, OWN = 32 * NW;
     __shared__ __attribute__((aligned(16))) unsigned char stage[2 * BUF];
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tiles_per_unit = n / 128;
+    const int tiles_per_unit = n / OWN;
     int wg = blockIdx.x;                                    // XCD-aware order, as in k_bwd_local_q
     if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
-    const int u = wg / tiles_per_unit, j0 = (wg % tiles_per_unit) * 128;
+    const int u = wg / tiles_per_unit, j0 = (wg % tiles_per_unit) * OWN;
     const int jb = (j0 / b) * b;
     const size_t urow = (size_t)u * n;
     const int key0 = j0 + 32 * wave, key = key0 + x;
@@ -673,11 +684,11 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict
     auto stage_tile = [&](int qt) {
         unsigned char *dst = stage + (qt & 1) * BUF;
         const size_t t0 = urow + jb + (size_t)qt * kLocT;
-        loc_stage_rows(QF, t0, dst, tid, wave);
-        loc_stage_rows(GF, t0, dst + kLocRows, tid, wave);
-        loc_stage_octets(Q8, t0, dst + 2 * kLocRows, tid, wave);
-        loc_stage_octets(G8, t0, dst + 3 * kLocRows, tid, wave);
-        if (tid < kLocT) ((float *)(dst + 4 * kLocRows))[tid] = Cc[t0 + tid];
+        loc_stage_rows<NTHR>(QF, t0, dst, tid, wave);
+        loc_stage_rows<NTHR>(GF, t0, dst + kLocRows, tid, wave);
+        loc_stage_octets<NTHR>(Q8, t0, dst + 2 * kLocRows, tid, wave);
+        loc_stage_octets<NTHR>(G8, t0, dst + 3 * kLocRows, tid, wave);
+        if (tid < kLocT) ((float *)(dst + 4 * kLocRows))[tid] = (float)P * Cc[t0 + tid];
     };
     stage_tile(first);
 #pragma unroll 1
@@ -705,17 +716,18 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_local_k(const bf16_t *__restrict
             bf16x8 pww[2][2], pwp[2][2];
 #pragma unroll
             for (int sub = 0; sub < 2; ++sub) {
-                const int t0 = jb + qt * kLocT + 32 * sub;
+                // key <= token t0 + 8 gq + 4 h + j  <=>  8 gq + j >= lim
+                const int lim = key - (jb + qt * kLocT + 32 * sub) - 4 * h;
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     const f32x4 c4 = *(const f32x4 *)&cs[32 * sub + 8 * gq + 4 * h];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const int v = 4 * gq + j, tokv = t0 + 8 * gq + 4 * h + j;
-                        const float s1 = sc[sub][v], pm1 = pow_n<P - 1>(s1);
-                        const bool keep = key <= tokv;
-                        sc[sub][v] = keep ? pm1 * s1 : 0.f;
-                        dw[sub][v] = keep ? (dw[sub][v] + c4[j]) * (float)P * pm1 : 0.f;
+                        const int v = 4 * gq + j;
+                        const float sm = (8 * gq + j >= lim) ? sc[sub][v] : 0.f;   // masked pairs: every power is 0
+                        const float pm1 = pow_n<P - 1>(sm);
+                        sc[sub][v] = pm1 * sm;
+                        dw[sub][v] = (dw[sub][v] + c4[j]) * pm1;      // g and c arrive multiplied by p
                     }
                 }
                 loc_pack(sc[sub], pww[sub]);
@@ -797,6 +809,7 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
                          const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm)
 {
     constexpr int D = 64, P = 4, TT = 2;
+    constexpr int NWL = 4;                                  // waves per in-block workgroup: 256 own rows share a streamed tile
     MfmaBwdWs w = carve_bwd(pb, ws);
     MfmaWs f = carve(pb, w.fwd);
     const size_t rows = (size_t)pb.units * pb.n;
@@ -821,7 +834,9 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
         const bf16_t *src[4] = {q, k, v, w.G_rm};
         bf16_t *dstf[4] = {w.QF, w.KF, w.VF, w.GF};
         for (int i = 0; i < 4; ++i) {
-            hipLaunchKernelGGL(k_bwd_row_tiles, dim3(gridp), dim3(kWg), 0, s, src[i], dstf[i], pieces);
+            // the copy of g that only feeds dW = <g, v> + c carries the factor p of d(s^p) = p s^(p-1) ds
+            hipLaunchKernelGGL(k_bwd_row_tiles, dim3(gridp), dim3(kWg), 0, s, src[i], dstf[i], pieces,
+                               i == 3 ? (float)P : 1.0f);
             PSF_LAUNCH_CHECK();
         }
     }
@@ -845,17 +860,17 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     if (tm) tm->mark();
     // in-block parts
     {
-        const unsigned grid = (unsigned)(rows / 128);
-        hipLaunchKernelGGL((k_bwd_local_q<P>), dim3(grid), dim3(kWg), 0, s, q, w.KF, w.VF, w.K8, w.G_rm, w.Cc,
+        const unsigned grid = (unsigned)(rows / (32 * NWL));
+        hipLaunchKernelGGL((k_bwd_local_q<P, NWL>), dim3(grid), dim3(64 * NWL), 0, s, q, w.KF, w.VF, w.K8, w.G_rm, w.Cc,
                            w.dQacc, pb.n, pb.b);
         PSF_LAUNCH_CHECK();
     }
     {
         // dV: the cross-block part first, the in-block kernel adds to it
-        const unsigned gridc = (unsigned)(rows / (128 * TT)), grid = (unsigned)(rows / 128);
+        const unsigned gridc = (unsigned)(rows / (128 * TT)), grid = (unsigned)(rows / (32 * NWL));
         hipLaunchKernelGGL((k_bwd_dvc<R, D, TT>), dim3(gridc), dim3(kWg), 0, s, w.MK, w.Rg, w.dVc, pb.n, pb.b, pb.t);
         PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_bwd_local_k<P>), dim3(grid), dim3(kWg), 0, s, w.QF, k, v, w.Q8, w.GF, w.G8, w.Cc,
+        hipLaunchKernelGGL((k_bwd_local_k<P, NWL>), dim3(grid), dim3(64 * NWL), 0, s, w.QF, k, v, w.Q8, w.GF, w.G8, w.Cc,
                            w.dVc, w.dKacc, (bf16_t *)dV, pb.n, pb.b);
         PSF_LAUNCH_CHECK();
     }
