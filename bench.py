@@ -36,7 +36,7 @@ def workloads():
     return w
 
 
-def stage_flops(cfg, learned=False, noncausal=False):
+def stage_flops(cfg, learned=False, noncausal=False, local_sketch=False):
     """Algorithmic flops per step (multiply-add = 2), split by kernel stage.  Causal lower
     triangle only; the first block has no prefix and the last block's state is never needed.
     noncausal: one state over all n keys, applied to all n queries, no in-block pairs."""
@@ -54,7 +54,8 @@ def stage_flops(cfg, learned=False, noncausal=False):
     f = {
         "sketch_and_layouts": U * (sketch + 2 * (n - b) * r * r),      # + ones column of H_l
         "block_states_scan": U * 2 * (n - b) * r * r * d,               # H_l and Z_l
-        "output": U * (2 * (n - b) * r * r * (d + 1) + n * (b + 1) * (2 * d + 1)),
+        # in-block pairs: score over d (or over r with the sketched in-block rule), weights x [V | 1]
+        "output": U * (2 * (n - b) * r * r * (d + 1) + n * (b + 1) * ((r if local_sketch else d) + d + 1)),
     }
     f["total"] = sum(f.values())
     return f
@@ -305,6 +306,8 @@ def main():
     ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "decode"],
                     help="fwd: psf_causal_attn_fwd (the headline); bwd: psf_causal_attn_bwd; "
                          "decode: psf_decode_step at a fixed serving shape")
+    ap.add_argument("--local-sketch", action="store_true",
+                    help="in-block weights from the sketches ((L R^T)^2, Section 3.1) instead of exact ones")
     ap.add_argument("--noncausal", action="store_true",
                     help="forward pass without the causal mask (psf_noncausal_attn_fwd)")
     ap.add_argument("--learned", action="store_true",
@@ -347,7 +350,8 @@ def main():
         run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx)
         return
     desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
-                         cfg["dtype"], per_head=cfg["per_head"], learned=args.learned)
+                         cfg["dtype"], per_head=cfg["per_head"], learned=args.learned,
+                         local=psf.LOCAL_SKETCH if args.local_sketch else psf.LOCAL_EXACT)
     path = psf.kernel_path(desc)
     qd, kd, vd, Gd = q.to(dev), k.to(dev), v.to(dev), G.to(dev)
     O = torch.empty_like(vd)
@@ -380,7 +384,8 @@ def main():
         _, st = fwd_timed(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
         for nm, ms in st.items():
             acc[nm] = acc.get(nm, 0.0) + ms / reps
-    fl = stage_flops(cfg, learned=args.learned, noncausal=args.noncausal) if path == 1 else None
+    fl = stage_flops(cfg, learned=args.learned, noncausal=args.noncausal,
+                     local_sketch=args.local_sketch) if path == 1 else None
     out = {
         "metric": ("noncausal" if args.noncausal else "causal") + "_polysketch_attention_fwd_tokens_per_s",
         "value": tokens * args.steps / elapsed,
@@ -388,7 +393,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if path == 1 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "sketch": "learned" if args.learned else "gaussian",
-                   "mask": "none" if args.noncausal else "causal", "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"],
+                   "mask": "none" if args.noncausal else "causal",
+                   "in_block": "sketch" if args.local_sketch else "exact", "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"],
                    "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
                    "kernel_path": "mfma_bf16" if path == 1 else "general_fp32"},
         "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
@@ -401,10 +407,10 @@ def main():
         out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": achieved,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
-                           "traffic": None if (args.noncausal or args.learned)
+                           "traffic": None if (args.noncausal or args.learned or args.local_sketch)
                            else MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
                            "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc if nm in fl}}
-    if not args.no_cpu_baseline and not args.learned:      # the oracle drivers used here take Gaussian sketches
+    if not args.no_cpu_baseline and not args.learned and not args.local_sketch:   # oracle drivers used here: Gaussian sketches, exact in-block
         out["cpu_baseline"] = cpu_baseline_noncausal(cfg, q, k, v, G) if args.noncausal else cpu_baseline(cfg, q, k, v, G)
     print(json.dumps(out))
 

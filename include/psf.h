@@ -77,8 +77,9 @@ typedef struct {
 /* Host-only check of a descriptor; what the other entry points run first. */
 psf_status psf_check_desc(const psf_desc *desc);
 
-/* Which kernels the descriptor selects: 1 = bf16 MFMA path (FEAT_SKETCH, LOCAL_EXACT, bf16,
- * p in {4,8}, r in {32,64}, d = dv in {64,128}, b % 256 == 0), 0 = general fp32 path
+/* Which kernels the descriptor selects: 1 = bf16 MFMA path (FEAT_SKETCH, bf16, p in {4,8},
+ * r in {32,64}, d = dv in {64,128}, b % 256 == 0; LOCAL_EXACT, or LOCAL_SKETCH with Gaussian
+ * sketches unless d = 128 and r = 32), 0 = general fp32 path
  * (everything else the descriptor check admits), -1 = invalid descriptor. */
 int psf_kernel_path(const psf_desc *desc);
 

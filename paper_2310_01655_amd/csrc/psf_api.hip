@@ -59,7 +59,10 @@ int select_path(const Problem &pb)
 {
     const bool shapes = (pb.r == 32 || pb.r == 64) && pb.d == pb.dv && (pb.d == 64 || pb.d == 128) &&
                         (pb.p == 4 || pb.p == 8) && pb.b % 256 == 0;
-    return (pb.bf16 && !pb.exact_feat && pb.local_exact && shapes) ? 1 : 0;   // learned sketches included
+    // learned sketches included; the in-block rule of Section 3.1 (weights from the sketches) with
+    // Gaussian sketches, except d = 128 with r = 32 (a key tile of m(K) rows is half a copy there)
+    const bool local_ok = pb.local_exact || (!pb.learned && !(pb.d == 128 && pb.r == 32));
+    return (pb.bf16 && !pb.exact_feat && local_ok && shapes) ? 1 : 0;
 }
 
 psf_status StageTimer::begin(hipStream_t s)

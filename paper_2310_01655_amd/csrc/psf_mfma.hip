@@ -688,7 +688,9 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
 // ------------------------------------------------------------------------------------
 // NONCAUSAL (Section 2.2): no in-block phase, every token takes the cross-block term with the
 // one state of its unit (slot 0; the caller passes b = n, t = 2).
-template <int R, int D, int P, int TT, bool DEN, bool NONCAUSAL = false>
+// LS (Section 3.1, in-block rule (L R^T)^2): the in-block weights are <m(q_i), m(k_j)>^2 like the
+// cross-block ones; Q, K then point to the bf16 rows of m(Q), m(K) (width R instead of D).
+template <int R, int D, int P, int TT, bool DEN, bool NONCAUSAL = false, bool LS = false>
 __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                 const bf16_t *__restrict__ V8,
                                                 const bf16_t *__restrict__ MQ,
@@ -697,11 +699,13 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
                                                 const bf16_t *__restrict__ Slo, bf16_t *__restrict__ O,
                                                 float *__restrict__ Den, int n, int b, int t)
 {
-    constexpr int CT = D / 32, KS = D / 16, RS = R / 16, AT = R / 32;
+    constexpr int KD = LS ? R : D;                        // row width of the in-block score operands
+    constexpr int CT = D / 32, KS = KD / 16, RS = R / 16, AT = R / 32;
     constexpr int TOK_WAVE = 32 * TT, TOK_WG = 4 * TOK_WAVE;
     constexpr int KEYT = TOK_WAVE;                        // keys per staged tile = tokens per wave
     constexpr int SUBS = KEYT / 32, IPT = SUBS * TT;      // 32x32 items per staged tile and wave
-    constexpr int KV_BYTES = KEYT * D * 2 * 2;            // staged K tile + V tile (16 KB)
+    constexpr int K_BYTES = KEYT * KD * 2, V_BYTES = KEYT * D * 2;
+    constexpr int KV_BYTES = K_BYTES + V_BYTES;           // staged K tile + V tile (16 KB)
     constexpr int NKV = 4;                                // key tiles in flight
     constexpr int DMA_KV = KV_BYTES / 16 / kWg;           // copies per thread and tile
     constexpr int ZA = 16384 / (R * D);                   // sketch rows a per staged Z chunk
@@ -710,7 +714,7 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
     constexpr int MQ_CHUNK_BYTES = ZA * TOK_WG * 4;       // m_i[a] of the chunk, fp32 [ZA][TOK_WG]
     constexpr int CROSS_BYTES = 2 * (Z_CHUNK_BYTES + MQ_CHUNK_BYTES);
     constexpr int STAGE_BYTES = CROSS_BYTES > NKV * KV_BYTES ? CROSS_BYTES : NKV * KV_BYTES;
-    static_assert(KV_BYTES % (16 * kWg) == 0, "whole copies");
+    static_assert(K_BYTES % (16 * kWg) == 0 && V_BYTES % (16 * kWg) == 0, "whole copies");
     __shared__ __attribute__((aligned(16))) unsigned char stage[STAGE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -746,7 +750,7 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
         for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
             for (int s = 0; s < KS; ++s)
-                qfr[tt][s] = *(const bf16x8 *)&Q[(urow + tok_w0 + 32 * tt + x) * D + 16 * s + 8 * h];
+                qfr[tt][s] = *(const bf16x8 *)&Q[(urow + tok_w0 + 32 * tt + x) * KD + 16 * s + 8 * h];
 
         // K tile in LDS as [D/8][KEYT keys][8] (A fragments are then contiguous 16-byte reads),
         // V tile as [KEYT/8 octets][D][8], both filled by direct global->LDS copies.
@@ -755,19 +759,19 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
         // (copies: wave-uniform base address in scalar registers + a fixed per-lane offset)
         static_assert(kWg % KEYT == 0, "key index of a copy slot");
         const uint32_t stage0 = lds_address(stage);
-        const uint32_t k_lane = (uint32_t)(((tid % KEYT) * D + 8 * (tid / KEYT)) * 2);
+        const uint32_t k_lane = (uint32_t)(((tid % KEYT) * KD + 8 * (tid / KEYT)) * 2);
         const uint32_t v_lane = (uint32_t)tid * 16;
         auto stage_kv = [&](int kt) {
             const int ktc = min(kt, ntiles_wg - 1);              // clamped: keeps the copy count uniform
             const uint32_t dst = stage0 + (kt % NKV) * KV_BYTES + wave * 1024;
             const size_t j0 = urow + jb + (size_t)ktc * KEYT;
-            const bf16_t *ksrc = K + j0 * D, *vsrc = V8 + j0 * D;
+            const bf16_t *ksrc = K + j0 * KD, *vsrc = V8 + j0 * D;
 #pragma unroll
-            for (int q = 0; q < DMA_KV / 2; ++q)                  // copy slot q * kWg + tid = (d-octet, key)
+            for (int q = 0; q < K_BYTES / 16 / kWg; ++q)          // copy slot q * kWg + tid = (d-octet, key)
                 dma16_sbase(ksrc + q * 8 * (kWg / KEYT), k_lane, dst + q * 4096);
 #pragma unroll
-            for (int q = 0; q < DMA_KV / 2; ++q)
-                dma16_sbase(vsrc + q * kWg * 8, v_lane, dst + KEYT * D * 2 + q * 4096);
+            for (int q = 0; q < V_BYTES / 16 / kWg; ++q)
+                dma16_sbase(vsrc + q * kWg * 8, v_lane, dst + K_BYTES + q * 4096);
         };
 
         // Software pipeline over the 32x32 items q of this wave: in one straight-line step the
@@ -799,7 +803,7 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
         };
         // out^T += V^T P^T for item q with the packed weights pw
         auto apply_pv = [&](int q, int jsub, int jtt, const bf16x8 *pw) {
-            const bf16_t *vs = (const bf16_t *)(stage + ((q / IPT) % NKV) * KV_BYTES) + KEYT * D;
+            const bf16_t *vs = (const bf16_t *)(stage + ((q / IPT) % NKV) * KV_BYTES) + KEYT * KD;
             if (jtt == 0) {                               // fragments serve all token tiles of the sub-tile
 #pragma unroll
                 for (int sp = 0; sp < 2; ++sp)
@@ -821,7 +825,7 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
             const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                float w = pow_p(scv[v], P);
+                float w = LS ? scv[v] * scv[v] : pow_p(scv[v], P);
                 if (DIAG) {
                     const int key = key0 + 8 * (v / 4) + 4 * h + (v % 4);
                     w = key <= tok0 + x ? w : 0.f;
@@ -1574,6 +1578,7 @@ int sketch_tiles_per_wg(int b);
 struct MfmaWs {
     bf16_t *Gt; bf16_t *MQ; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
     float *M32;                                  // learned sketches only: m(x) as fp32 rows
+    bf16_t *MKrm;                                // m(K) as bf16 rows: in-block rule of Section 3.1 only
     bf16_t *LW; float *C1, *LVp;                 // learned sketches on MFMA: arranged weights
     size_t total;
 };
@@ -1609,6 +1614,7 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.Spart = (float *)take(parts * R * R * 4);
     w.Shi = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
     w.Slo = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
+    w.MKrm = (bf16_t *)take(pb.local_exact ? 0 : rows * R * 2);
     const bool fast_learned = learned_on_mfma(pb);
     w.M32 = (float *)take(pb.learned && !fast_learned ? rows * R * 4 : 0);
     const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
@@ -1722,7 +1728,8 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         if (st != PSF_OK) return st;
         st = launch_sketch<D, R, P>(pb, Q, w.Gt, true, w.MQ, nullptr, nullptr, tiles, s);
         if (st != PSF_OK) return st;
-        st = launch_sketch<D, R, P>(pb, K, w.Gt, false, MK_rm, w.MK8, w.Spart, tiles, s);
+        st = launch_sketch<D, R, P>(pb, K, w.Gt, false, MK_rm ? MK_rm : (pb.local_exact ? nullptr : w.MKrm), w.MK8,
+                                    w.Spart, tiles, s);
         if (st != PSF_OK) return st;
     }
     {
@@ -1748,7 +1755,16 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         // one workgroup per CU; it measured 1.7x slower than TT = 2 with two per CU.)
         constexpr int TT = (D == 64) ? 2 : 1;
         const unsigned grid = (unsigned)((size_t)pb.units * (pb.n / (128 * TT)));
-        if (noncausal)
+        constexpr bool LS_OK = (32 * TT * R * 2) % (16 * kWg) == 0;    // whole copies of a key tile of m(K) rows
+        if (!noncausal && !pb.local_exact) {
+            if constexpr (LS_OK) {
+                if (pb.learned || Den) return PSF_ERR_UNSUPPORTED;  // (not routed here: see select_path)
+                hipLaunchKernelGGL((k_out<R, D, P, TT, false, false, true>), dim3(grid), dim3(kWg), 0, s, w.MQ,
+                                   w.MKrm, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b, pb.t);
+            } else {
+                return PSF_ERR_UNSUPPORTED;
+            }
+        } else if (noncausal)
             hipLaunchKernelGGL((k_out<R, D, P, TT, false, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
                                (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b,
                                pb.t);

@@ -134,3 +134,43 @@ def test_deterministic_across_runs():
     a, _ = gpu_attn(cfg, q, k, v, G)
     b2, _ = gpu_attn(cfg, q, k, v, G)
     assert torch.equal(a, b2)
+
+
+@pytest.mark.parametrize("d,p,r,b", [(64, 4, 64, 256), (64, 4, 32, 256), (64, 4, 64, 512), (128, 8, 64, 256),
+                                     (64, 8, 32, 512)])
+def test_in_block_weights_from_the_sketches_full_parity(d, p, r, b):
+    """Section 3.1's in-block rule (L R^T)^2 on the MFMA path: every weight is <m(q), m(k)>^2."""
+    cfg = mk(1, 2, 1024, d, p, r, b, per_head=True)
+    q, k, v, G = draw(cfg, seed=37)
+    got, desc = gpu_attn(cfg, q, k, v, G, local=psf.LOCAL_SKETCH)
+    assert psf.kernel_path(desc) == 1
+    want = oracle_attn(cfg, q, k, v, G, local=oracle.LOCAL_SKETCH)
+    print("local sketch", (d, p, r, b), assert_close(got.numpy(), want, "bf16", "local sketch d=%d p=%d r=%d b=%d" % (d, p, r, b)))
+
+
+@pytest.mark.parametrize("n,r", [(8192, 64), (16384, 32)])
+def test_block_size_invariance_at_sweep_shapes(n, r):
+    """With every weight taken from the sketches the function does not depend on b (the block
+    decomposition is exact): the three block sizes of the sweep agree with each other within
+    the bf16 tolerance and with the oracle (evaluated once, b irrelevant) on sampled rows."""
+    outs = {}
+    for b in (256, 512, 1024):
+        cfg = mk(2, 12, n, 64, 4, r, b)
+        q, k, v, G = draw(cfg, seed=1004)
+        got, desc = gpu_attn(cfg, q, k, v, G, local=psf.LOCAL_SKETCH)
+        assert psf.kernel_path(desc) == 1
+        outs[b] = got.numpy()
+    for b in (512, 1024):
+        assert_close(outs[b], outs[256], "bf16", "b=%d against b=256" % b)
+    rows = probe_rows(n, 1024)
+    units = [(0, 0), (1, 11)]
+    want = oracle_units_rows(cfg, q, k, v, G, units, rows, local=oracle.LOCAL_SKETCH, b=1024)
+    for b in (256, 512, 1024):
+        g = np.stack([outs[b][bi, h][rows] for bi, h in units])
+        print("b-invariance", (n, r, b), assert_close(g, np.stack([want[u] for u in units]), "bf16", "b=%d" % b))
+
+
+def test_in_block_sketch_rule_path_selection():
+    assert psf.kernel_path(psf.make_desc(1, 2, 1024, 128, 4, 32, 256, "bf16", local=psf.LOCAL_SKETCH)) == 0
+    assert psf.kernel_path(psf.make_desc(1, 2, 1024, 64, 4, 32, 256, "bf16", local=psf.LOCAL_SKETCH, learned=True)) == 0
+    assert psf.kernel_path(psf.make_desc(1, 2, 1024, 128, 4, 64, 256, "bf16", local=psf.LOCAL_SKETCH)) == 1
