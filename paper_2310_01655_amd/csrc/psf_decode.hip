@@ -262,9 +262,7 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
     // sketches of the new token: the general sketch kernel on [units, 1, d]
     Problem one = pb;
     one.n = 1;
-    psf_status st = general_sketch_f32(one, q, G, state + L.mq, s);
-    if (st != PSF_OK) return st;
-    st = general_sketch_f32(one, k, G, state + L.mk, s);
+    psf_status st = general_sketch_pair_f32(one, q, k, G, state + L.mq, state + L.mk, s);   // one launch for both
     if (st != PSF_OK) return st;
     hipLaunchKernelGGL(dec_append_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)k,
                        (const T *)v, state + L.mk, state, L, pb.d, pb.dv, pb.mcols, slot);

@@ -38,14 +38,19 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void gen_sketch_kernel(
     const T *__restrict__ X, const T *__restrict__ G, long long rows, int n, int heads,
     int per_head, int d, int r, int p, int exact, long long F, size_t g_len,
-    float *__restrict__ M_f32, T *__restrict__ M_st, T *__restrict__ Phi)
+    float *__restrict__ M_f32, T *__restrict__ M_st, T *__restrict__ Phi,
+    const T *__restrict__ X2, float *__restrict__ M2_f32)
 {
+    // X2 / M2_f32 (optional): a second set of `rows` rows sketched by the same launch (fp32 out only)
     __shared__ float xs[PSF_MAX_DIM];
     __shared__ float lev[2][4][PSF_MAX_DIM];
     const int tid = threadIdx.x;
     const int mcols = (p == 2) ? d : r;
-    for (long long row = blockIdx.x; row < rows; row += gridDim.x) {
-        const T *x = X + (size_t)row * d;
+    const long long total = X2 ? 2 * rows : rows;
+    for (long long row_all = blockIdx.x; row_all < total; row_all += gridDim.x) {
+        const bool second = row_all >= rows;
+        const long long row = second ? row_all - rows : row_all;
+        const T *x = (second ? X2 : X) + (size_t)row * d;
         __syncthreads();
         if (tid < d) xs[tid] = load_f(x, tid);
         __syncthreads();
@@ -93,6 +98,10 @@ __global__ __launch_bounds__(kThreads) void gen_sketch_kernel(
             fin = lev[cur][0];
         }
         if (!exact) {
+            if (second) {
+                if (tid < mcols) M2_f32[(size_t)row * mcols + tid] = fin[tid];
+                continue;
+            }
             if (tid < mcols) {
                 if (M_f32) M_f32[(size_t)row * mcols + tid] = fin[tid];
                 if (M_st) store_f(M_st, (size_t)row * mcols + tid, fin[tid]);
@@ -188,16 +197,20 @@ template <typename T>
 __global__ __launch_bounds__(kThreads) void gen_sketch_learned_kernel(
     const T *__restrict__ X, const T *__restrict__ P, long long rows, int n, int heads, int per_head,
     int d, int r, int p, size_t p_len, float *__restrict__ M_f32, T *__restrict__ M_st,
-    T *__restrict__ Phi)
+    T *__restrict__ Phi, const T *__restrict__ X2, float *__restrict__ M2_f32)
 {
+    // X2 / M2_f32 (optional): a second set of `rows` rows sketched by the same launch (fp32 out only)
     __shared__ float xs[PSF_MAX_DIM], u[kMaxHidden], h[kMaxHidden], red[kThreads + 2];
     __shared__ float f1[PSF_MAX_DIM], f2[PSF_MAX_DIM], m1[PSF_MAX_DIM], m2[PSF_MAX_DIM];
     const int tid = threadIdx.x;
     const size_t len_d = 2 * (size_t)d + (size_t)d * 8 * r + 16 * (size_t)r + 24 * (size_t)r * r;
     const float sr = sqrtf((float)r);
-    for (long long row = blockIdx.x; row < rows; row += gridDim.x) {
+    const long long total = X2 ? 2 * rows : rows;
+    for (long long row_all = blockIdx.x; row_all < total; row_all += gridDim.x) {
+        const bool second = row_all >= rows;
+        const long long row = second ? row_all - rows : row_all;
         __syncthreads();
-        if (tid < d) xs[tid] = load_f(X, (size_t)row * d + tid);
+        if (tid < d) xs[tid] = load_f(second ? X2 : X, (size_t)row * d + tid);
         __syncthreads();
         const int head = (int)((row / n) % heads);
         const T *P0 = P + (per_head ? (size_t)head * p_len : 0);
@@ -216,6 +229,10 @@ __global__ __launch_bounds__(kThreads) void gen_sketch_learned_kernel(
             wg_learned_net(m2, r, r, P0 + 4 * len_d + len_r, f2, u, h, red);
             if (tid < r) m1[tid] = sr * tanhf(f1[tid] * f2[tid] / sr);
             __syncthreads();
+        }
+        if (second) {
+            if (tid < r) M2_f32[(size_t)row * r + tid] = m1[tid];
+            continue;
         }
         if (tid < r) {
             if (M_f32) M_f32[(size_t)row * r + tid] = m1[tid];
@@ -419,20 +436,21 @@ GeneralWs carve(const Problem &pb, void *ws)
 
 template <typename T>
 psf_status sketch_launch(const Problem &pb, const void *X, const void *G, float *M_f32, void *M_out,
-                         void *Phi_out, hipStream_t s)
+                         void *Phi_out, hipStream_t s, const void *X2 = nullptr, float *M2_f32 = nullptr)
 {
-    const long long rows = (long long)pb.units * pb.n;
-    const int grid = (int)(rows < 65536 ? rows : 65536);
+    const long long rows = (long long)pb.units * pb.n, all = X2 ? 2 * rows : rows;
+    const int grid = (int)(all < 65536 ? all : 65536);
     if (pb.learned && pb.p > 2) {
         hipLaunchKernelGGL(gen_sketch_learned_kernel<T>, dim3(grid), dim3(kThreads), 0, s, (const T *)X,
                            (const T *)G, rows, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.d, pb.r, pb.p,
-                           pb.g_len, M_f32, (T *)M_out, (T *)Phi_out);
+                           pb.g_len, M_f32, (T *)M_out, (T *)Phi_out, (const T *)X2, M2_f32);
         PSF_LAUNCH_CHECK();
         return PSF_OK;
     }
     hipLaunchKernelGGL(gen_sketch_kernel<T>, dim3(grid), dim3(kThreads), 0, s, (const T *)X,
                        (const T *)G, rows, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.d, pb.r, pb.p,
-                       pb.exact_feat ? 1 : 0, pb.F, pb.g_len, M_f32, (T *)M_out, (T *)Phi_out);
+                       pb.exact_feat ? 1 : 0, pb.F, pb.g_len, M_f32, (T *)M_out, (T *)Phi_out, (const T *)X2,
+                       M2_f32);
     PSF_LAUNCH_CHECK();
     return PSF_OK;
 }
@@ -504,6 +522,13 @@ psf_status general_sketch_f32(const Problem &pb, const void *X, const void *G, f
 {
     return pb.bf16 ? sketch_launch<bf16_t>(pb, X, G, M_f32, nullptr, nullptr, s)
                    : sketch_launch<float>(pb, X, G, M_f32, nullptr, nullptr, s);
+}
+
+psf_status general_sketch_pair_f32(const Problem &pb, const void *X, const void *X2, const void *G, float *M_f32,
+                                   float *M2_f32, hipStream_t s)
+{
+    return pb.bf16 ? sketch_launch<bf16_t>(pb, X, G, M_f32, nullptr, nullptr, s, X2, M2_f32)
+                   : sketch_launch<float>(pb, X, G, M_f32, nullptr, nullptr, s, X2, M2_f32);
 }
 
 psf_status general_attn(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,

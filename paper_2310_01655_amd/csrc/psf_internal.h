@@ -49,6 +49,9 @@ psf_status general_attn(const Problem &pb, const void *Q, const void *K, const v
 // m(x) of every row as fp32 [rows][mcols] (general sketch kernel).
 psf_status general_sketch_f32(const Problem &pb, const void *X, const void *G, float *M_f32,
                               hipStream_t s);
+// The same for two sets of rows (X -> M_f32, X2 -> M2_f32) in one launch.
+psf_status general_sketch_pair_f32(const Problem &pb, const void *X, const void *X2, const void *G,
+                                   float *M_f32, float *M2_f32, hipStream_t s);
 
 // Backward pass (general fp32 kernels; sketch features only).
 bool general_bwd_supported(const Problem &pb);
