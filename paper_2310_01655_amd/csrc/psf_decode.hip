@@ -58,120 +58,115 @@ __global__ __launch_bounds__(kThreads) void dec_zero_kernel(float *__restrict__ 
         p[i] = 0.f;
 }
 
-// cache slot of the new token: key, value, m(k)
+// part[u][s][c] = the share of slice s in row [N | S] of the new token:
+//   cross-block: sum over the features f of the slice of phi'(q)[f] ZV[f][c] (c < dv) and, at
+//   c = dv, of phi'(q)[f] ZD[f] (only once a block is complete: have_state); phi'(q) of the slice
+//   sits in LDS; thread (c, g) walks the rows g, g + groups, ... four at a time, so a wave reads
+//   whole contiguous rows of ZV;
+//   in-block: the slice's share of the `slot` tokens cached since the last block boundary,
+//   sum_j w_j [v_j | 1] with the weights of Section 3.2 (or 3.1).  The new token itself is not in
+//   the cache yet: its own pair is added by dec_finish_kernel.
 template <typename T>
-__global__ __launch_bounds__(kThreads) void dec_append_kernel(const T *__restrict__ k, const T *__restrict__ v,
-                                                              const float *__restrict__ mk_new,
-                                                              float *__restrict__ state, DecodeLayout L,
-                                                              int d, int dv, int mcols, int slot)
-{
-    const int u = blockIdx.x, tid = threadIdx.x;
-    float *su = state + (size_t)u * L.per_unit;
-    for (int e = tid; e < d; e += kThreads) su[L.ck + (size_t)slot * d + e] = load_f(k, (size_t)u * d + e);
-    for (int c = tid; c < dv; c += kThreads) su[L.cv + (size_t)slot * dv + c] = load_f(v, (size_t)u * dv + c);
-    for (int e = tid; e < mcols; e += kThreads) su[L.cm + (size_t)slot * mcols + e] = mk_new[(size_t)u * mcols + e];
-}
-
-// part[u][s][c] = sum over the features f of slice s of phi'(q)[f] ZV[f][c] (c < dv) and, at
-// c = dv, of phi'(q)[f] ZD[f].  phi'(q) of the slice sits in LDS; thread (c, g) walks the rows
-// g, g + groups, ... four at a time, so a wave reads whole contiguous rows of ZV.
-__global__ __launch_bounds__(kThreads) void dec_state_kernel(const float *__restrict__ state,
+__global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict__ q,
+                                                             const float *__restrict__ state,
                                                              const float *__restrict__ mq_new,
-                                                             float *__restrict__ part, DecodeLayout L,
-                                                             int dv, int mcols, long long F)
+                                                             float *__restrict__ part, DecodeLayout L, int d,
+                                                             int dv, int p, int mcols, long long F, int slot,
+                                                             int have_state, int local_exact)
 {
     constexpr int kMaxPer = 4096;                          // F / kSlices <= 65536 / 16
-    __shared__ float mq[PSF_MAX_DIM], phi[kMaxPer], red[kThreads];
+    __shared__ float mq[PSF_MAX_DIM], qs[PSF_MAX_DIM], phi[kMaxPer], red[kThreads], w[kThreads], rowp[PSF_MAX_DIM + 1];
     const int u = blockIdx.y, sl = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
-    for (int e = tid; e < mcols; e += kThreads) mq[e] = mq_new[(size_t)u * mcols + e];
-    __syncthreads();
-    const long long per = (F + kSlices - 1) / kSlices;
-    const long long f_beg = sl * per;
-    const int nf = (int)max(0LL, min(F, f_beg + per) - f_beg);
-    for (int ff = tid; ff < nf; ff += kThreads) {
-        const long long f = f_beg + ff;
-        phi[ff] = mq[f / mcols] * mq[f % mcols];
-    }
-    __syncthreads();
-    const float *zv = state + (size_t)u * L.per_unit + L.zv + (size_t)f_beg * dv;
-    const float *zd = state + (size_t)u * L.per_unit + L.zd + f_beg;
-    const int dvp = pow2_at_least(dv, 32, kThreads), groups = kThreads / dvp;
-    float *out = part + ((size_t)u * kSlices + sl) * kc;
-    for (int c0 = 0; c0 < dv; c0 += dvp) {
-        const int c = c0 + tid % dvp, g = tid / dvp;
-        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-        if (c < dv) {
-            int ff = g;
-            for (; ff + 3 * groups < nf; ff += 4 * groups) {
-                a0 += phi[ff] * zv[(size_t)ff * dv + c];
-                a1 += phi[ff + groups] * zv[(size_t)(ff + groups) * dv + c];
-                a2 += phi[ff + 2 * groups] * zv[(size_t)(ff + 2 * groups) * dv + c];
-                a3 += phi[ff + 3 * groups] * zv[(size_t)(ff + 3 * groups) * dv + c];
-            }
-            for (; ff < nf; ff += groups) a0 += phi[ff] * zv[(size_t)ff * dv + c];
-        }
-        __syncthreads();
-        red[tid] = (a0 + a1) + (a2 + a3);
-        __syncthreads();
-        if (tid < dvp && c0 + tid < dv) {
-            float sacc = 0.f;
-            for (int q = 0; q < groups; ++q) sacc += red[q * dvp + tid];
-            out[c0 + tid] = sacc;
-        }
-    }
-    // the "ones" column
-    float a = 0.f;
-    for (int ff = tid; ff < nf; ff += kThreads) a += phi[ff] * zd[ff];
-    __syncthreads();
-    red[tid] = a;
-    __syncthreads();
-    if (tid == 0) {
-        float sacc = 0.f;
-        for (int q = 0; q < kThreads; ++q) sacc += red[q];
-        out[dv] = sacc;
-    }
-}
-
-// row = sum of the slices + the in-block term over the cache slots 0 .. slot, then N / (1 + S)
-template <typename T>
-__global__ __launch_bounds__(kThreads) void dec_finish_kernel(const T *__restrict__ q,
-                                                              const float *__restrict__ state,
-                                                              const float *__restrict__ mq_new,
-                                                              const float *__restrict__ part,
-                                                              T *__restrict__ o, DecodeLayout L, int d,
-                                                              int dv, int p, int mcols, int slot,
-                                                              int have_state, int local_exact)
-{
-    __shared__ float qs[PSF_MAX_DIM], w[kThreads], row[PSF_MAX_DIM + 1], red[kThreads];
-    const int u = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
     const float *su = state + (size_t)u * L.per_unit;
+    for (int e = tid; e < mcols; e += kThreads) mq[e] = mq_new[(size_t)u * mcols + e];
     const int wa = local_exact ? d : mcols;
     for (int e = tid; e < wa; e += kThreads)
         qs[e] = local_exact ? load_f(q, (size_t)u * d + e) : mq_new[(size_t)u * mcols + e];
-    for (int c = tid; c < kc; c += kThreads) {
-        float a = 0.f;
-        if (have_state)
-            for (int s = 0; s < kSlices; ++s) a += part[((size_t)u * kSlices + s) * kc + c];
-        row[c] = a;
-    }
+    for (int c = tid; c < kc; c += kThreads) rowp[c] = 0.f;
     __syncthreads();
-    const float *keys = su + (local_exact ? L.ck : L.cm);
     const int dvp = pow2_at_least(dv, 32, kThreads), groups = kThreads / dvp;
-    for (int j0 = 0; j0 <= slot; j0 += kThreads) {
-        const int nj = min(kThreads, slot + 1 - j0);
+    float *out = part + ((size_t)u * kSlices + sl) * kc;
+
+    if (have_state) {
+        const long long per = (F + kSlices - 1) / kSlices;
+        const long long f_beg = sl * per;
+        const int nf = (int)max(0LL, min(F, f_beg + per) - f_beg);
+        for (int ff = tid; ff < nf; ff += kThreads) {
+            const long long f = f_beg + ff;
+            phi[ff] = mq[f / mcols] * mq[f % mcols];
+        }
         __syncthreads();
-        float wv = 0.f;
-        if (tid < nj) {
-            const float *kr = keys + (size_t)(j0 + tid) * wa;
-            float sdot = 0.f;
-            for (int e = 0; e < wa; ++e) sdot += qs[e] * kr[e];
-            wv = sdot * sdot;
-            if (local_exact) {
-                wv = 1.f;
-                for (int e = 0; e < p; ++e) wv *= sdot;
+        const float *zv = su + L.zv + (size_t)f_beg * dv;
+        const float *zd = su + L.zd + f_beg;
+        for (int c0 = 0; c0 < dv; c0 += dvp) {
+            const int c = c0 + tid % dvp, g = tid / dvp;
+            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+            if (c < dv) {
+                int ff = g;
+                for (; ff + 3 * groups < nf; ff += 4 * groups) {
+                    a0 += phi[ff] * zv[(size_t)ff * dv + c];
+                    a1 += phi[ff + groups] * zv[(size_t)(ff + groups) * dv + c];
+                    a2 += phi[ff + 2 * groups] * zv[(size_t)(ff + 2 * groups) * dv + c];
+                    a3 += phi[ff + 3 * groups] * zv[(size_t)(ff + 3 * groups) * dv + c];
+                }
+                for (; ff < nf; ff += groups) a0 += phi[ff] * zv[(size_t)ff * dv + c];
+            }
+            __syncthreads();
+            red[tid] = (a0 + a1) + (a2 + a3);
+            __syncthreads();
+            if (tid < dvp && c0 + tid < dv) {
+                float sacc = 0.f;
+                for (int q2 = 0; q2 < groups; ++q2) sacc += red[q2 * dvp + tid];
+                rowp[c0 + tid] = sacc;
             }
         }
-        w[tid] = wv;
+        // the "ones" column
+        float a = 0.f;
+        for (int ff = tid; ff < nf; ff += kThreads) a += phi[ff] * zd[ff];
+        __syncthreads();
+        red[tid] = a;
+        __syncthreads();
+        if (tid == 0) {
+            float sacc = 0.f;
+            for (int q2 = 0; q2 < kThreads; ++q2) sacc += red[q2];
+            rowp[dv] = sacc;
+        }
+    }
+
+    // in-block: cached tokens j_beg .. j_end - 1 of this slice
+    const int per_j = (slot + kSlices - 1) / kSlices;
+    const int j_beg = min(slot, sl * per_j), j_end = min(slot, j_beg + per_j);
+    const float *keys = su + (local_exact ? L.ck : L.cm);
+    for (int j0 = j_beg; j0 < j_end; j0 += kThreads) {
+        const int nj = min(kThreads, j_end - j0);
+        __syncthreads();
+        // weights of the pass: four threads per key (consecutive lanes read consecutive pieces of
+        // a cached row), 64 keys at a time
+        for (int kk = 0; kk < nj; kk += kThreads / 4) {
+            const int kj = kk + (tid >> 2), part4 = tid & 3;
+            float sdot = 0.f;
+            if (kj < nj) {
+                const float *kr = keys + (size_t)(j0 + kj) * wa;
+                if ((wa & 15) == 0) {
+                    for (int e = 4 * part4; e < wa; e += 16) {
+                        const float4 kv = *(const float4 *)&kr[e];
+                        sdot += qs[e] * kv.x + qs[e + 1] * kv.y + qs[e + 2] * kv.z + qs[e + 3] * kv.w;
+                    }
+                } else {
+                    for (int e = part4; e < wa; e += 4) sdot += qs[e] * kr[e];
+                }
+            }
+            sdot += __shfl_xor(sdot, 1);
+            sdot += __shfl_xor(sdot, 2);
+            if (part4 == 0 && kj < nj) {
+                float wv = sdot * sdot;
+                if (local_exact) {
+                    wv = 1.f;
+                    for (int e = 0; e < p; ++e) wv *= sdot;
+                }
+                w[kj] = wv;
+            }
+        }
         __syncthreads();
         for (int c0 = 0; c0 < dv; c0 += dvp) {            // values: thread (c, g) takes slots g, g + groups, ...
             const int c = c0 + tid % dvp, g = tid / dvp;
@@ -184,18 +179,65 @@ __global__ __launch_bounds__(kThreads) void dec_finish_kernel(const T *__restric
             if (tid < dvp && c0 + tid < dv) {
                 float sacc = 0.f;
                 for (int q2 = 0; q2 < groups; ++q2) sacc += red[q2 * dvp + tid];
-                row[c0 + tid] += sacc;
+                rowp[c0 + tid] += sacc;
             }
         }
         if (tid == 0) {                                   // the "ones" column: sum of the weights
             float sacc = 0.f;
             for (int jj = 0; jj < nj; ++jj) sacc += w[jj];
-            row[dv] += sacc;
+            rowp[dv] += sacc;
         }
     }
     __syncthreads();
-    const float den = 1.f + row[dv];
-    for (int c = tid; c < dv; c += kThreads) store_f(o, (size_t)u * dv + c, row[c] / den);
+    for (int c = tid; c < kc; c += kThreads) out[c] = rowp[c];
+}
+
+// The new token's key, value and m(k) go into cache slot `slot`; row = sum of the slices + the
+// new token's own pair; then N / (1 + S).
+template <typename T>
+__global__ __launch_bounds__(kThreads) void dec_finish_kernel(const T *__restrict__ q, const T *__restrict__ k,
+                                                              const T *__restrict__ v,
+                                                              float *__restrict__ state,
+                                                              const float *__restrict__ mq_new,
+                                                              const float *__restrict__ mk_new,
+                                                              const float *__restrict__ part,
+                                                              T *__restrict__ o, DecodeLayout L, int d,
+                                                              int dv, int p, int mcols, int slot,
+                                                              int local_exact)
+{
+    __shared__ float red[kThreads];
+    __shared__ float w_self;
+    const int u = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
+    float *su = state + (size_t)u * L.per_unit;
+    for (int e = tid; e < d; e += kThreads) su[L.ck + (size_t)slot * d + e] = load_f(k, (size_t)u * d + e);
+    for (int c = tid; c < dv; c += kThreads) su[L.cv + (size_t)slot * dv + c] = load_f(v, (size_t)u * dv + c);
+    for (int e = tid; e < mcols; e += kThreads) su[L.cm + (size_t)slot * mcols + e] = mk_new[(size_t)u * mcols + e];
+    // own pair: <q, k>^p, or <m(q), m(k)>^2 with the sketched in-block rule
+    const int wa = local_exact ? d : mcols;
+    float a = 0.f;
+    for (int e = tid; e < wa; e += kThreads)
+        a += local_exact ? load_f(q, (size_t)u * d + e) * load_f(k, (size_t)u * d + e)
+                         : mq_new[(size_t)u * mcols + e] * mk_new[(size_t)u * mcols + e];
+    red[tid] = a;
+    __syncthreads();
+    if (tid == 0) {
+        float sdot = 0.f;
+        for (int q2 = 0; q2 < kThreads; ++q2) sdot += red[q2];
+        float wv = sdot * sdot;
+        if (local_exact) {
+            wv = 1.f;
+            for (int e = 0; e < p; ++e) wv *= sdot;
+        }
+        w_self = wv;
+    }
+    __syncthreads();
+    float den = 1.f + w_self;
+    for (int sidx = 0; sidx < kSlices; ++sidx) den += part[((size_t)u * kSlices + sidx) * kc + dv];
+    for (int c = tid; c < dv; c += kThreads) {
+        float acc = w_self * load_f(v, (size_t)u * dv + c);
+        for (int sidx = 0; sidx < kSlices; ++sidx) acc += part[((size_t)u * kSlices + sidx) * kc + c];
+        store_f(o, (size_t)u * dv + c, acc / den);
+    }
 }
 
 // ZV[f][c] += sum over the b cached tokens of phi'(k_j)[f] v_j[c], ZD[f] += sum_j phi'(k_j)[f].
@@ -264,17 +306,13 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
     one.n = 1;
     psf_status st = general_sketch_pair_f32(one, q, k, G, state + L.mq, state + L.mk, s);   // one launch for both
     if (st != PSF_OK) return st;
-    hipLaunchKernelGGL(dec_append_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)k,
-                       (const T *)v, state + L.mk, state, L, pb.d, pb.dv, pb.mcols, slot);
-    PSF_LAUNCH_CHECK();
     const int have_state = pos >= pb.b ? 1 : 0;          // Z is zero during the first block
-    if (have_state) {
-        hipLaunchKernelGGL(dec_state_kernel, dim3(kSlices, (unsigned)pb.units), dim3(kThreads), 0, s, state,
-                           state + L.mq, state + L.part, L, pb.dv, pb.mcols, pb.F);
-        PSF_LAUNCH_CHECK();
-    }
-    hipLaunchKernelGGL(dec_finish_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q, state,
-                       state + L.mq, state + L.part, (T *)o, L, pb.d, pb.dv, pb.p, pb.mcols, slot, have_state, le);
+    hipLaunchKernelGGL(dec_state_kernel<T>, dim3(kSlices, (unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q,
+                       state, state + L.mq, state + L.part, L, pb.d, pb.dv, pb.p, pb.mcols, pb.F, slot, have_state, le);
+    PSF_LAUNCH_CHECK();
+    hipLaunchKernelGGL(dec_finish_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q,
+                       (const T *)k, (const T *)v, state, state + L.mq, state + L.mk, state + L.part, (T *)o, L, pb.d,
+                       pb.dv, pb.p, pb.mcols, slot, le);
     PSF_LAUNCH_CHECK();
     if (slot == pb.b - 1) {                               // the block is complete: fold it into Z
         const dim3 fgrid((unsigned)((pb.F + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
