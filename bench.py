@@ -197,6 +197,56 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     print(json.dumps(out))
 
 
+def run_train(args, cfg, psf, inputs, torch, q, k, v, G, idx):
+    """One training step of the attention layer: forward that keeps its states, then backward
+    from them (psf_causal_attn_fwd_save + psf_causal_attn_bwd_saved)."""
+    dev = torch.device("cuda:0")
+    dO = inputs.make_dout(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], seed=1000 + idx, dtype=cfg["dtype"])
+    desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
+                         cfg["dtype"], per_head=cfg["per_head"])
+    if psf.bwd_kernel_path(desc) != 3:
+        sys.exit("--pass train needs a workload the MFMA backward kernels cover (config2, config3, d = 64 sweep points)")
+    qd, kd, vd, Gd, dOd = (x.to(dev) for x in (q, k, v, G, dO))
+    ws = psf.alloc_bwd_workspace(desc, dev)
+    save = torch.empty(psf.fwd_save_bytes(desc), dtype=torch.uint8, device=dev)
+    O = torch.empty_like(vd)
+    grads = (torch.empty_like(qd), torch.empty_like(kd), torch.empty_like(vd))
+    stream = torch.cuda.current_stream()
+
+    def step():
+        psf.psf_causal_attn_fwd_save(desc, qd, kd, vd, Gd, O=O, save=save, stream=stream)
+        psf.psf_causal_attn_bwd_saved(desc, qd, kd, vd, Gd, O, dOd, save, workspace=ws, stream=stream, out=grads)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    fb = bwd_stage_flops_mfma(cfg)
+    total = fb["total"]                                     # forward once + the backward stages
+    tfl = total / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "causal_polysketch_attention_fwd_bwd_tokens_per_s",
+        "value": cfg["batch"] * cfg["n"] * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "pass": "train (forward with saved states + backward)",
+                   "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"], "d": cfg["d"], "p": cfg["p"],
+                   "r": cfg["r"], "b": cfg["b"], "kernel_path": "mfma_bf16"},
+        "tflops": tfl,
+        "roofline": {"kernel": "whole step", "bound": "mfma", "achieved": tfl, "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": tfl / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_bwd(cfg, q, k, v, G, dO)
+        out["cpu_baseline"]["sample"] += "; gradient only, the oracle's forward is inside it"
+    print(json.dumps(out))
+
+
 def run_decode(args, psf, inputs, torch):
     """Token-by-token evaluation at serving shape: 64 sequences x 12 heads, d = 64, r = 64,
     b = 1024 (the headline per-unit shape).  The first block and the first half of the second are
@@ -323,9 +373,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default=None,
                     help="config1|config2|config3|config5|sweep_n.._r.._b.. (default config3; config2 with --pass bwd)")
-    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "decode"],
-                    help="fwd: psf_causal_attn_fwd (the headline); bwd: psf_causal_attn_bwd; "
-                         "decode: psf_decode_step at a fixed serving shape")
+    ap.add_argument("--pass", dest="which", default="fwd", choices=["fwd", "bwd", "train", "decode"],
+                    help="fwd: psf_causal_attn_fwd (the headline); bwd: psf_causal_attn_bwd; train: forward "
+                         "that keeps its states + backward from them; decode: psf_decode_step at a fixed "
+                         "serving shape")
     ap.add_argument("--local-sketch", action="store_true",
                     help="in-block weights from the sketches ((L R^T)^2, Section 3.1) instead of exact ones")
     ap.add_argument("--noncausal", action="store_true",
@@ -368,6 +419,9 @@ def main():
                                         seed=0, dtype=cfg["dtype"])
     if args.which == "bwd":
         run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx)
+        return
+    if args.which == "train":
+        run_train(args, cfg, psf, inputs, torch, q, k, v, G, idx)
         return
     desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
                          cfg["dtype"], per_head=cfg["per_head"], learned=args.learned,

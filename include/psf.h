@@ -195,6 +195,26 @@ psf_status psf_causal_attn_bwd_timed(const psf_desc *desc, const void *Q, const 
                                      int32_t *n_written);
 
 /*
+ * Forward + backward without running the forward pass twice (for callers that train).
+ * psf_causal_attn_fwd_save computes the same O as psf_causal_attn_fwd and leaves in `save`
+ * (caller memory, psf_fwd_save_bytes(desc) bytes, 256-byte aligned) what the backward pass would
+ * otherwise recompute: the sketches, the block states and the denominators.
+ * psf_causal_attn_bwd_saved takes that buffer untouched since, the same Q, K, V, G and the O the
+ * forward call wrote, and returns the same gradients as psf_causal_attn_bwd (bit for bit).
+ * workspace: psf_bwd_workspace_bytes(desc) as for psf_causal_attn_bwd.  Available where
+ * psf_bwd_kernel_path(desc) == 3; elsewhere psf_fwd_save_bytes is 0 and both calls return
+ * PSF_ERR_UNSUPPORTED (use psf_causal_attn_fwd / psf_causal_attn_bwd there).
+ */
+size_t psf_fwd_save_bytes(const psf_desc *desc);
+psf_status psf_causal_attn_fwd_save(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                    const void *G, void *O, void *save, size_t save_bytes,
+                                    void *hip_stream);
+psf_status psf_causal_attn_bwd_saved(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                     const void *G, const void *O, const void *dO, void *dQ, void *dK,
+                                     void *dV, void *save, size_t save_bytes, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream);
+
+/*
  * Token-by-token evaluation (the recurrent form behind the paper's remark, Section 5, that the
  * state kept for generation does not grow with the context).  psf_decode_step consumes q, k, v
  * of position `pos` ([batch, heads, 1, d | dv], device, desc->dtype) and writes row `pos` of

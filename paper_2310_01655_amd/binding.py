@@ -21,7 +21,8 @@ EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_le
            "psf_sketch",
            "psf_causal_attn_fwd", "psf_causal_attn_fwd_timed", "psf_stage_name",
            "psf_status_string", "psf_noncausal_workspace_bytes", "psf_noncausal_attn_fwd",
-           "psf_noncausal_attn_fwd_timed", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
+           "psf_noncausal_attn_fwd_timed", "psf_fwd_save_bytes", "psf_causal_attn_fwd_save",
+           "psf_causal_attn_bwd_saved", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
            "psf_causal_attn_bwd_timed", "psf_decode_state_bytes", "psf_decode_reset",
            "psf_decode_step")
 
@@ -76,6 +77,12 @@ def lib():
         L.psf_noncausal_attn_fwd.argtypes = L.psf_causal_attn_fwd.argtypes
         L.psf_noncausal_attn_fwd_timed.restype = ctypes.c_int
         L.psf_noncausal_attn_fwd_timed.argtypes = L.psf_causal_attn_fwd_timed.argtypes
+        L.psf_fwd_save_bytes.restype = ctypes.c_size_t
+        L.psf_fwd_save_bytes.argtypes = [dp]
+        L.psf_causal_attn_fwd_save.restype = ctypes.c_int
+        L.psf_causal_attn_fwd_save.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.psf_causal_attn_bwd_saved.restype = ctypes.c_int
+        L.psf_causal_attn_bwd_saved.argtypes = [dp] + [vp] * 9 + [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
         L.psf_bwd_kernel_path.restype = ctypes.c_int
         L.psf_bwd_kernel_path.argtypes = [dp]
         L.psf_bwd_workspace_bytes.restype = ctypes.c_size_t
@@ -270,6 +277,44 @@ def psf_noncausal_attn_fwd_timed(desc, Q, K, V, G, O=None, workspace=None, strea
     path = kernel_path(desc)
     names = [lib().psf_stage_name(path, i).decode() for i in range(written.value)]
     return O, {nm: float(ms[i]) for i, nm in enumerate(names)}
+
+
+def fwd_save_bytes(desc):
+    """Bytes of the buffer psf_causal_attn_fwd_save fills for psf_causal_attn_bwd_saved (0: not available)."""
+    return lib().psf_fwd_save_bytes(ctypes.byref(desc))
+
+
+def psf_causal_attn_fwd_save(desc, Q, K, V, G, O=None, save=None, stream=None):
+    """Forward pass that keeps what the backward pass needs; returns (O, save)."""
+    st = check_desc(desc)
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_fwd_save")
+    if save is None:
+        save = torch.empty(max(fwd_save_bytes(desc), 256), dtype=torch.uint8, device=Q.device)
+    O, _, ptrs = _attn_args(desc, Q, K, V, G, O, save)
+    st = lib().psf_causal_attn_fwd_save(ctypes.byref(desc), *ptrs, _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_fwd_save")
+    return O, save
+
+
+def psf_causal_attn_bwd_saved(desc, Q, K, V, G, O, dO, save, workspace=None, stream=None, out=None):
+    """Backward pass from the buffer psf_causal_attn_fwd_save left; returns (dQ, dK, dV)."""
+    B, H, n, d, dv = desc.batch, desc.heads, desc.n, desc.d, desc.dv
+    if workspace is None:
+        workspace = alloc_bwd_workspace(desc, Q.device)
+    dQ, dK, dV = out if out is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
+    gs = _g_shape(desc)
+    st = lib().psf_causal_attn_bwd_saved(
+        ctypes.byref(desc), _dev_ptr(Q, desc, (B, H, n, d), "Q"), _dev_ptr(K, desc, (B, H, n, d), "K"),
+        _dev_ptr(V, desc, (B, H, n, dv), "V"), _dev_ptr(G, desc, gs, "G") if gs else None,
+        _dev_ptr(O, desc, (B, H, n, dv), "O"), _dev_ptr(dO, desc, (B, H, n, dv), "dO"),
+        _dev_ptr(dQ, desc, (B, H, n, d), "dQ"), _dev_ptr(dK, desc, (B, H, n, d), "dK"),
+        _dev_ptr(dV, desc, (B, H, n, dv), "dV"), ctypes.c_void_p(save.data_ptr()), ctypes.c_size_t(save.numel()),
+        ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_bwd_saved")
+    return dQ, dK, dV
 
 
 def bwd_kernel_path(desc):

@@ -275,6 +275,42 @@ psf_status psf_noncausal_attn_fwd_timed(const psf_desc *desc, const void *Q, con
     return st != PSF_OK ? st : st2;
 }
 
+size_t psf_fwd_save_bytes(const psf_desc *desc)
+{
+    Problem pb;
+    if (make_problem(desc, &pb) != PSF_OK || !general_bwd_supported(pb) || !bwd_on_mfma(pb)) return 0;
+    return mfma_fwd_save_bytes(pb);
+}
+
+psf_status psf_causal_attn_fwd_save(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                    const void *G, void *O, void *save, size_t save_bytes, void *hip_stream)
+{
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);
+    if (st != PSF_OK) return st;
+    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb)) return PSF_ERR_UNSUPPORTED;
+    if (!Q || !K || !V || !O || !save) return PSF_ERR_NULL;
+    if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
+    if (save_bytes < mfma_fwd_save_bytes(pb) || ((uintptr_t)save & 255u) != 0) return PSF_ERR_WORKSPACE;
+    return mfma_attn_fwd_save(pb, Q, K, V, G, O, save, (hipStream_t)hip_stream, nullptr);
+}
+
+psf_status psf_causal_attn_bwd_saved(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                     const void *G, const void *O, const void *dO, void *dQ, void *dK,
+                                     void *dV, void *save, size_t save_bytes, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream)
+{
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);
+    if (st != PSF_OK) return st;
+    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb)) return PSF_ERR_UNSUPPORTED;
+    if (!Q || !K || !V || !O || !dO || !dQ || !dK || !dV || !save || !workspace) return PSF_ERR_NULL;
+    if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
+    if (save_bytes < mfma_fwd_save_bytes(pb) || ((uintptr_t)save & 255u) != 0) return PSF_ERR_WORKSPACE;
+    if (workspace_bytes < mfma_bwd_workspace_bytes(pb) || ((uintptr_t)workspace & 255u) != 0) return PSF_ERR_WORKSPACE;
+    return mfma_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, workspace, (hipStream_t)hip_stream, nullptr, save, O);
+}
+
 int psf_bwd_kernel_path(const psf_desc *desc)
 {
     Problem pb;

@@ -63,9 +63,14 @@ psf_status general_attn_bwd(const Problem &pb, const void *Q, const void *K, con
 // Backward pass on MFMA (bf16, d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0, random sketches).
 bool mfma_bwd_supported(const Problem &pb);
 size_t mfma_bwd_workspace_bytes(const Problem &pb);
+// saved / O_saved: what mfma_attn_fwd_save left and the output it wrote (skips the forward pass
+// inside), or null.
 psf_status mfma_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                          const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s,
-                         StageTimer *tm);
+                         StageTimer *tm, void *saved = nullptr, const void *O_saved = nullptr);
+size_t mfma_fwd_save_bytes(const Problem &pb);
+psf_status mfma_attn_fwd_save(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+                              void *O, void *saved, hipStream_t s, StageTimer *tm);
 
 // Token-by-token evaluation (fp32 kernels; sketch features only).
 bool decode_supported(const Problem &pb);

@@ -1797,10 +1797,21 @@ bool mfma_bwd_supported(const Problem &pb)
 size_t mfma_bwd_workspace_bytes(const Problem &pb) { return carve_bwd(pb, nullptr).total; }
 
 psf_status mfma_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
-                         const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm)
+                         const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm,
+                         void *saved, const void *O_saved)
 {
-    if (pb.r == 64) return attn_bwd_impl<64>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm);
-    return attn_bwd_impl<32>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm);
+    if (pb.r == 64) return attn_bwd_impl<64>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm, saved, O_saved);
+    return attn_bwd_impl<32>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm, saved, O_saved);
+}
+
+size_t mfma_fwd_save_bytes(const Problem &pb) { return carve_saved(pb, nullptr).total; }
+
+psf_status mfma_attn_fwd_save(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+                              void *O, void *saved, hipStream_t s, StageTimer *tm)
+{
+    const MfmaSaved sv = carve_saved(pb, saved);
+    if (pb.r == 64) return attn_impl<64, 64, 4>(pb, Q, K, V, G, O, sv.fwd, s, tm, sv.Den, sv.MK);
+    return attn_impl<64, 32, 4>(pb, Q, K, V, G, O, sv.fwd, s, tm, sv.Den, sv.MK);
 }
 
 #define PSF_DISPATCH(CALL)                                                   \

@@ -804,9 +804,36 @@ MfmaBwdWs carve_bwd(const Problem &pb, void *ws)
     return w;
 }
 
+// What a forward call leaves for the backward pass when asked to (psf_causal_attn_fwd_save): its
+// whole workspace (m(Q), the states Z_l and S_l, the transposed sketch matrices), the
+// denominators and m(K) as bf16 rows.
+struct MfmaSaved {
+    void *fwd;
+    float *Den;
+    bf16_t *MK;
+    size_t total;
+};
+
+MfmaSaved carve_saved(const Problem &pb, void *ptr)
+{
+    MfmaSaved sv;
+    const size_t rows = (size_t)pb.units * pb.n;
+    size_t off = 0;
+    char *base = (char *)ptr;
+    auto take = [&](size_t bytes) { char *p = base + off; off += align_up(bytes, 256); return (void *)p; };
+    sv.fwd = take(carve(pb, nullptr).total);
+    sv.Den = (float *)take(rows * 4);
+    sv.MK = (bf16_t *)take(rows * pb.r * 2);
+    sv.total = off;
+    return sv;
+}
+
+// saved / O_saved: null = run the forward pass again inside; otherwise what psf_causal_attn_fwd_save
+// left and the output it wrote.
 template <int R>
 psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
-                         const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm)
+                         const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm,
+                         void *saved = nullptr, const void *O_saved = nullptr)
 {
     constexpr int D = 64, P = 4, TT = 2;
     constexpr int NWL = 4;                                  // waves per in-block workgroup: 256 own rows share a streamed tile
@@ -814,9 +841,18 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     MfmaWs f = carve(pb, w.fwd);
     const size_t rows = (size_t)pb.units * pb.n;
     const bf16_t *q = (const bf16_t *)Q, *k = (const bf16_t *)K, *v = (const bf16_t *)V;
-    // forward pass again: O, the denominators, m(Q), m(K), the states Z_l and S_l
-    psf_status st = attn_impl<D, R, P>(pb, Q, K, V, G, w.O, w.fwd, s, nullptr, w.Den, w.MK);
-    if (st != PSF_OK) return st;
+    psf_status st;
+    if (saved) {
+        const MfmaSaved sv = carve_saved(pb, saved);
+        f = carve(pb, sv.fwd);
+        w.Den = sv.Den;
+        w.MK = sv.MK;
+        w.O = (bf16_t *)O_saved;                           // read only
+    } else {
+        // forward pass again: O, the denominators, m(Q), m(K), the states Z_l and S_l
+        st = attn_impl<D, R, P>(pb, Q, K, V, G, w.O, w.fwd, s, nullptr, w.Den, w.MK);
+        if (st != PSF_OK) return st;
+    }
     if (tm) tm->mark();
     // g, c, layouts
     hipLaunchKernelGGL((k_bwd_prep<D>), dim3((unsigned)(rows / 32)), dim3(kWg), 0, s, (const bf16_t *)dO, w.O,

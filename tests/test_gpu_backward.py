@@ -160,3 +160,35 @@ def test_backward_config3_full_size_sampled_rows_and_identities():
               assert_close_scaled(gq[rows], wQ[rows], "bf16", "dQ"),
               assert_close_scaled(gk[tail0:], wK[tail0:], "bf16", "dK"),
               assert_close_scaled(gv[tail0:], wV[tail0:], "bf16", "dV"))
+
+
+@pytest.mark.parametrize("r,b", [(64, 256), (32, 512)])
+def test_saved_forward_gives_the_same_output_and_gradients(r, b):
+    """psf_causal_attn_fwd_save + psf_causal_attn_bwd_saved against the plain forward and the
+    plain (recomputing) backward of the same library: identical bits, since the same kernels run
+    on the same data; the plain calls are the ones checked against the oracle above."""
+    batch, heads, n, d, p = 1, 3, 1024, 64, 4
+    q, k, v = inputs.make_qkv(batch, heads, n, d, seed=53, dtype="bf16")
+    dO = inputs.make_dout(batch, heads, n, d, seed=53, dtype="bf16")
+    G = inputs.make_sketch_matrices(heads, d, r, p, per_head=True, seed=0, dtype="bf16")
+    desc = psf.make_desc(batch, heads, n, d, p, r, b, "bf16", per_head=True)
+    assert psf.bwd_kernel_path(desc) == 3 and psf.fwd_save_bytes(desc) > psf.workspace_bytes(desc)
+    dev = torch.device("cuda:0")
+    qd, kd, vd, Gd, dOd = (x.to(dev) for x in (q, k, v, G, dO))
+    O1 = psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd)
+    O2, save = psf.psf_causal_attn_fwd_save(desc, qd, kd, vd, Gd)
+    g1 = psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd)
+    g2 = psf.psf_causal_attn_bwd_saved(desc, qd, kd, vd, Gd, O2, dOd, save)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2)
+    for a, c in zip(g1, g2):
+        assert torch.equal(a, c)
+
+
+def test_saved_forward_is_refused_where_the_general_kernels_run():
+    desc = psf.make_desc(1, 1, 256, 64, 4, 16, 64, "f32")
+    assert psf.bwd_kernel_path(desc) == 2 and psf.fwd_save_bytes(desc) == 0
+    q, k, v = inputs.make_qkv(1, 1, 256, 64, seed=1, dtype="f32")
+    G = inputs.make_sketch_matrices(1, 64, 16, 4, seed=0, dtype="f32")
+    with pytest.raises(psf.PsfError):
+        psf.psf_causal_attn_fwd_save(desc, q.cuda(), k.cuda(), v.cuda(), G.cuda())
