@@ -295,6 +295,98 @@ __global__ __launch_bounds__(kThreads) void dec_fold_kernel(float *__restrict__ 
     }
 }
 
+// The same fold on MFMA for bf16 storage (phi'(k) and v as bf16 operands, fp32 accumulation, as
+// the forward state kernel does): Z[a][b'][c] += sum_j (m_j[a] m_j[b']) v_j[c].  Workgroup =
+// (NA consecutive sketch rows a, unit); wave w owns the 32 x 32 tiles w, w + 4, ... (SLOTS of
+// them) of each row's [mcols][dv] block.  64 tokens at a time are staged transposed
+// ([column][token]) so that a lane's eight tokens of one column are neighbours; the fragments of
+// m_j[b'] and of v are shared by the NA rows.
+typedef __bf16 dec_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float dec_f32x16 __attribute__((ext_vector_type(16)));
+constexpr int kFoldMfmaTok = 64, kFoldMfmaMaxM = 64, kFoldMfmaMaxDv = 128;
+
+template <int SLOTS>
+__global__ __launch_bounds__(kThreads) void dec_fold_mfma_kernel(float *__restrict__ state, DecodeLayout L,
+                                                                 int dv, int b, int mcols)
+{
+    constexpr int TOK = kFoldMfmaTok, PITCH = TOK + 1;      // odd pitch: conflict-free column reads
+    constexpr int NA = 8 / SLOTS;
+    __shared__ float mts[kFoldMfmaMaxM][PITCH], vts[kFoldMfmaMaxDv][PITCH];
+    const int a0 = blockIdx.x * NA, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int x = lane & 31, h = lane >> 5;
+    float *su = state + (size_t)u * L.per_unit;
+    const int tiles_c = dv / 32, ntiles = (mcols / 32) * tiles_c;
+    dec_f32x16 acc[SLOTS][NA];
+    float drow[SLOTS][NA];
+#pragma unroll
+    for (int sl = 0; sl < SLOTS; ++sl)
+#pragma unroll
+        for (int ai = 0; ai < NA; ++ai) {
+            drow[sl][ai] = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[sl][ai][v] = 0.f;
+        }
+    for (int j0 = 0; j0 < b; j0 += TOK) {
+        __syncthreads();
+        for (int idx = tid; idx < TOK * mcols; idx += kThreads) {
+            const int jj = idx / mcols, col = idx % mcols;
+            mts[col][jj] = j0 + jj < b ? su[L.cm + (size_t)(j0 + jj) * mcols + col] : 0.f;
+        }
+        for (int idx = tid; idx < TOK * dv; idx += kThreads) {
+            const int jj = idx / dv, c = idx % dv;
+            vts[c][jj] = j0 + jj < b ? su[L.cv + (size_t)(j0 + jj) * dv + c] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int sl = 0; sl < SLOTS; ++sl) {
+            const int ti = wave + 4 * sl;
+            if (ti >= ntiles) break;
+            const int bt = ti / tiles_c, ct = ti % tiles_c;
+#pragma unroll
+            for (int sstep = 0; sstep < TOK / 16; ++sstep) {
+                float mb[8];
+                dec_bf16x8 fb;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int tok = 16 * sstep + 8 * h + e;
+                    mb[e] = mts[32 * bt + x][tok];
+                    fb[e] = (__bf16)vts[32 * ct + x][tok];
+                }
+#pragma unroll
+                for (int ai = 0; ai < NA; ++ai) {
+                    dec_bf16x8 fa;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float pr = mts[a0 + ai][16 * sstep + 8 * h + e] * mb[e];
+                        fa[e] = (__bf16)pr;
+                        if (ct == 0) drow[sl][ai] += pr;
+                    }
+                    acc[sl][ai] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[sl][ai], 0, 0, 0);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int sl = 0; sl < SLOTS; ++sl) {
+        const int ti = wave + 4 * sl;
+        if (ti >= ntiles) break;
+        const int bt = ti / tiles_c, ct = ti % tiles_c;
+#pragma unroll
+        for (int ai = 0; ai < NA; ++ai) {
+            // accumulator: lane x = column c, register v = row b' = 8 (v / 4) + 4 h + v % 4
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int bp = 32 * bt + 8 * (v / 4) + 4 * h + (v % 4);
+                su[L.zv + ((size_t)(a0 + ai) * mcols + bp) * dv + 32 * ct + x] += acc[sl][ai][v];
+            }
+            if (ct == 0) {                                 // the "ones" column: lanes x = row b', both halves
+                const float tot = drow[sl][ai] + __shfl_xor(drow[sl][ai], 32);
+                if (h == 0) su[L.zd + (size_t)(a0 + ai) * mcols + 32 * bt + x] += tot;
+            }
+        }
+    }
+}
+
 template <typename T>
 psf_status step_launch(const Problem &pb, const void *q, const void *k, const void *v, const void *G, int pos,
                        float *state, void *o, hipStream_t s)
@@ -316,7 +408,14 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
     PSF_LAUNCH_CHECK();
     if (slot == pb.b - 1) {                               // the block is complete: fold it into Z
         const dim3 fgrid((unsigned)((pb.F + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
-        if (pb.dv <= 32)
+        if (pb.bf16 && pb.mcols % 32 == 0 && pb.mcols <= kFoldMfmaMaxM && pb.dv % 32 == 0 && pb.dv <= kFoldMfmaMaxDv) {
+            if ((pb.mcols / 32) * (pb.dv / 32) <= 4)        // one tile per wave: eight sketch rows per workgroup
+                hipLaunchKernelGGL(dec_fold_mfma_kernel<1>, dim3((unsigned)pb.mcols / 8, (unsigned)pb.units),
+                                   dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols);
+            else                                            // two tiles per wave: four rows
+                hipLaunchKernelGGL(dec_fold_mfma_kernel<2>, dim3((unsigned)pb.mcols / 4, (unsigned)pb.units),
+                                   dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols);
+        } else if (pb.dv <= 32)
             hipLaunchKernelGGL(dec_fold_kernel<8>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
         else if (pb.dv <= 64)
             hipLaunchKernelGGL(dec_fold_kernel<16>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);

@@ -61,6 +61,13 @@ def test_decode_bf16_storage_headline_shape_per_unit():
     decode_all(1, 3, 768, 64, 64, 4, 64, 256, "bf16")
 
 
+@pytest.mark.parametrize("n,d,r,b", [(384, 128, 32, 128), (288, 64, 64, 96), (512, 64, 32, 256)])
+def test_decode_bf16_block_fold_on_mfma(n, d, r, b):
+    # bf16 storage with r, dv multiples of 32: completed blocks are folded into the state by the
+    # MFMA kernel (one 32 x 32 tile per wave and more; b = 96 leaves a padded token chunk)
+    decode_all(1, 2, n, d, d, 4, r, b, "bf16")
+
+
 def test_decode_equals_the_forward_entry_point():
     batch, heads, n, d, p, r, b = 1, 2, 128, 32, 4, 16, 32
     out = decode_all(batch, heads, n, d, d, p, r, b, "f32", seed=53)
