@@ -11,8 +11,8 @@
 // State per (batch, head) unit, all fp32, caller-owned:
 //   ZV [F][dv] and ZD [F]: the value columns and the "ones" column of Z (F = mcols^2 features),
 //   kept apart so that rows of ZV are aligned and a step streams them with full-width loads;
-//   then the current block's cache: CK [b][d] keys, CV [b][dv] values, CM [b][mcols] sketches
-//   m(k).  After the units come the scratch areas: m(q), m(k) of the new token [units][mcols]
+//   then the current block's cache: CK [b][d] keys and CV [b][dv] values in the storage type
+//   of the call (fp32 or bf16), CM [b][mcols] sketches m(k) in fp32.  After the units come the scratch areas: m(q), m(k) of the new token [units][mcols]
 //   each and the partial sums of the state product [units][kSlices][dv + 1].
 // A step is bound by reading Z once (F * (dv + 1) * 4 bytes per unit) from HBM.
 #include "psf_internal.h"
@@ -34,9 +34,10 @@ DecodeLayout decode_layout(const Problem &pb)
     auto up = [](size_t v) { return (v + 63) / 64 * 64; };            // 256-byte pieces
     L.zv = 0;
     L.zd = up((size_t)pb.F * pb.dv);
+    const size_t per_float = pb.bf16 ? 2 : 1;                         // cached keys / values keep the storage type
     L.ck = L.zd + up((size_t)pb.F);
-    L.cv = L.ck + up((size_t)pb.b * pb.d);
-    L.cm = L.cv + up((size_t)pb.b * pb.dv);
+    L.cv = L.ck + up(((size_t)pb.b * pb.d + per_float - 1) / per_float);
+    L.cm = L.cv + up(((size_t)pb.b * pb.dv + per_float - 1) / per_float);
     L.per_unit = L.cm + up((size_t)pb.b * pb.mcols);
     L.mq = L.per_unit * pb.units;
     L.mk = L.mq + up((size_t)pb.units * pb.mcols);
@@ -50,6 +51,14 @@ __device__ __forceinline__ int pow2_at_least(int v, int lo, int hi)
     int p = lo;
     while (p < v && p < hi) p *= 2;
     return p;
+}
+
+__device__ __forceinline__ float4 load4_f(const float *p) { return *(const float4 *)p; }
+__device__ __forceinline__ float4 load4_f(const bf16_t *p)
+{
+    const uint2 w = *(const uint2 *)p;
+    return make_float4(__uint_as_float(w.x << 16), __uint_as_float(w.x & 0xffff0000u), __uint_as_float(w.y << 16),
+                       __uint_as_float(w.y & 0xffff0000u));
 }
 
 __global__ __launch_bounds__(kThreads) void dec_zero_kernel(float *__restrict__ p, size_t count)
@@ -136,7 +145,9 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
     // in-block: cached tokens j_beg .. j_end - 1 of this slice
     const int per_j = (slot + kSlices - 1) / kSlices;
     const int j_beg = min(slot, sl * per_j), j_end = min(slot, j_beg + per_j);
-    const float *keys = su + (local_exact ? L.ck : L.cm);
+    const T *ckeys = (const T *)(su + L.ck);             // local_exact: the cached keys, storage type
+    const float *mkeys = su + L.cm;                        // otherwise: their sketches
+    const T *cvals = (const T *)(su + L.cv);
     for (int j0 = j_beg; j0 < j_end; j0 += kThreads) {
         const int nj = min(kThreads, j_end - j0);
         __syncthreads();
@@ -146,14 +157,15 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
             const int kj = kk + (tid >> 2), part4 = tid & 3;
             float sdot = 0.f;
             if (kj < nj) {
-                const float *kr = keys + (size_t)(j0 + kj) * wa;
+                const size_t roff = (size_t)(j0 + kj) * wa;
                 if ((wa & 15) == 0) {
                     for (int e = 4 * part4; e < wa; e += 16) {
-                        const float4 kv = *(const float4 *)&kr[e];
+                        const float4 kv = local_exact ? load4_f(ckeys + roff + e) : load4_f(mkeys + roff + e);
                         sdot += qs[e] * kv.x + qs[e + 1] * kv.y + qs[e + 2] * kv.z + qs[e + 3] * kv.w;
                     }
                 } else {
-                    for (int e = part4; e < wa; e += 4) sdot += qs[e] * kr[e];
+                    for (int e = part4; e < wa; e += 4)
+                        sdot += qs[e] * (local_exact ? load_f(ckeys, roff + e) : mkeys[roff + e]);
                 }
             }
             sdot += __shfl_xor(sdot, 1);
@@ -172,7 +184,7 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
             const int c = c0 + tid % dvp, g = tid / dvp;
             float a = 0.f;
             if (c < dv)
-                for (int jj = g; jj < nj; jj += groups) a += w[jj] * su[L.cv + (size_t)(j0 + jj) * dv + c];
+                for (int jj = g; jj < nj; jj += groups) a += w[jj] * load_f(cvals, (size_t)(j0 + jj) * dv + c);
             __syncthreads();
             red[tid] = a;
             __syncthreads();
@@ -209,8 +221,9 @@ __global__ __launch_bounds__(kThreads) void dec_finish_kernel(const T *__restric
     __shared__ float w_self;
     const int u = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
     float *su = state + (size_t)u * L.per_unit;
-    for (int e = tid; e < d; e += kThreads) su[L.ck + (size_t)slot * d + e] = load_f(k, (size_t)u * d + e);
-    for (int c = tid; c < dv; c += kThreads) su[L.cv + (size_t)slot * dv + c] = load_f(v, (size_t)u * dv + c);
+    T *ckeys = (T *)(su + L.ck), *cvals = (T *)(su + L.cv);
+    for (int e = tid; e < d; e += kThreads) ckeys[(size_t)slot * d + e] = k[(size_t)u * d + e];
+    for (int c = tid; c < dv; c += kThreads) cvals[(size_t)slot * dv + c] = v[(size_t)u * dv + c];
     for (int e = tid; e < mcols; e += kThreads) su[L.cm + (size_t)slot * mcols + e] = mk_new[(size_t)u * mcols + e];
     // own pair: <q, k>^p, or <m(q), m(k)>^2 with the sketched in-block rule
     const int wa = local_exact ? d : mcols;
@@ -244,7 +257,7 @@ __global__ __launch_bounds__(kThreads) void dec_finish_kernel(const T *__restric
 // Workgroup = kFoldFeat features; thread (c, g) owns the PER = kFoldFeat / groups features
 // g * PER .. of column c (groups = 256 / columns per pass).
 constexpr int kFoldFeat = 64, kFoldTok = 32;
-template <int PER>
+template <typename T, int PER>
 __global__ __launch_bounds__(kThreads) void dec_fold_kernel(float *__restrict__ state, DecodeLayout L,
                                                             int dv, int b, int mcols, long long F)
 {
@@ -274,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void dec_fold_kernel(float *__restrict__ 
             }
             for (int idx = tid; idx < kFoldTok * dv; idx += kThreads) {
                 const int jj = idx / dv, cc = idx % dv;
-                vt[jj][cc] = jj < lim ? su[L.cv + (size_t)(j0 + jj) * dv + cc] : 0.f;
+                vt[jj][cc] = jj < lim ? load_f((const T *)(su + L.cv), (size_t)(j0 + jj) * dv + cc) : 0.f;
             }
             __syncthreads();
             if (c < dv)
@@ -334,7 +347,7 @@ __global__ __launch_bounds__(kThreads) void dec_fold_mfma_kernel(float *__restri
         }
         for (int idx = tid; idx < TOK * dv; idx += kThreads) {
             const int jj = idx / dv, c = idx % dv;
-            vts[c][jj] = j0 + jj < b ? su[L.cv + (size_t)(j0 + jj) * dv + c] : 0.f;
+            vts[c][jj] = j0 + jj < b ? bf16_to_f32(((const bf16_t *)(su + L.cv))[(size_t)(j0 + jj) * dv + c]) : 0.f;
         }
         __syncthreads();
 #pragma unroll
@@ -416,13 +429,13 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
                 hipLaunchKernelGGL(dec_fold_mfma_kernel<2>, dim3((unsigned)pb.mcols / 4, (unsigned)pb.units),
                                    dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols);
         } else if (pb.dv <= 32)
-            hipLaunchKernelGGL(dec_fold_kernel<8>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+            hipLaunchKernelGGL((dec_fold_kernel<T, 8>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
         else if (pb.dv <= 64)
-            hipLaunchKernelGGL(dec_fold_kernel<16>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+            hipLaunchKernelGGL((dec_fold_kernel<T, 16>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
         else if (pb.dv <= 128)
-            hipLaunchKernelGGL(dec_fold_kernel<32>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+            hipLaunchKernelGGL((dec_fold_kernel<T, 32>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
         else
-            hipLaunchKernelGGL(dec_fold_kernel<64>, fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+            hipLaunchKernelGGL((dec_fold_kernel<T, 64>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
         PSF_LAUNCH_CHECK();
     }
     return PSF_OK;

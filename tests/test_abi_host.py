@@ -147,8 +147,10 @@ def test_decode_entry_points_validate_on_the_host():
     ref = ctypes.byref(d)
     one = ctypes.c_void_p(256)   # never dereferenced: every call below fails validation first
     need = psf.decode_state_bytes(d)
-    # per unit: r^2 x (dv + 1) fp32 state and the block cache (keys, values, sketches); no n in it
-    assert need >= 6 * (1024 * 65 + 256 * (64 + 64 + 32)) * 4
+    # per unit: r^2 x (dv + 1) fp32 state and the block cache (keys and values in the storage
+    # type, sketches in fp32); no n in it
+    assert need >= 6 * ((1024 * 65 + 256 * 32) * 4 + 256 * (64 + 64) * 2)
+    assert need < 6 * (1024 * 65 + 256 * (64 + 64 + 32)) * 4 + (1 << 16)
     d2 = psf.make_desc(2, 3, 65536, 64, 4, 32, 256, "bf16")
     assert psf.decode_state_bytes(d2) == need
     assert L.psf_decode_reset(ref, None, need, None) == 1
