@@ -44,6 +44,7 @@ __global__ __launch_bounds__(kThreads) void gen_sketch_kernel(
     // X2 / M2_f32 (optional): a second set of `rows` rows sketched by the same launch (fp32 out only)
     __shared__ float xs[PSF_MAX_DIM];
     __shared__ float lev[2][4][PSF_MAX_DIM];
+    __shared__ float pu[kThreads], pv[kThreads];
     const int tid = threadIdx.x;
     const int mcols = (p == 2) ? d : r;
     const long long total = X2 ? 2 * rows : rows;
@@ -61,16 +62,27 @@ __global__ __launch_bounds__(kThreads) void gen_sketch_kernel(
             const T *g_inner = g_first + (size_t)(p / 2) * d * r;
             const float sc = sqrtf(1.0f / (float)r);
             int cur = 0, count = p / 4;                       // degree-2 sketches of x
-            if (tid < r) {
-                for (int j = 0; j < count; ++j) {
-                    const T *ga = g_first + (size_t)(2 * j) * d * r;
-                    const T *gb = ga + (size_t)d * r;
-                    float u = 0.f, v = 0.f;
-                    for (int e = 0; e < d; ++e) {
-                        u += xs[e] * load_f(ga, (size_t)e * r + tid);
-                        v += xs[e] * load_f(gb, (size_t)e * r + tid);
+            // all threads take part: thread (col, part) sums the rows e = part, part + nparts, ...
+            // of both projections; the partial sums are then added in a fixed order
+            const int nparts = kThreads / r > 0 ? kThreads / r : 1, part = tid / r, col = tid % r;
+            for (int j = 0; j < count; ++j) {
+                const T *ga = g_first + (size_t)(2 * j) * d * r;
+                const T *gb = ga + (size_t)d * r;
+                float u = 0.f, v = 0.f;
+                if (part < nparts && col < r) {
+                    for (int e = part; e < d; e += nparts) {
+                        u += xs[e] * load_f(ga, (size_t)e * r + col);
+                        v += xs[e] * load_f(gb, (size_t)e * r + col);
                     }
-                    lev[cur][j][tid] = sc * (u * v);
+                }
+                __syncthreads();
+                pu[tid] = u;
+                pv[tid] = v;
+                __syncthreads();
+                if (tid < r) {
+                    float us = 0.f, vs = 0.f;
+                    for (int q2 = 0; q2 < nparts; ++q2) { us += pu[q2 * r + tid]; vs += pv[q2 * r + tid]; }
+                    lev[cur][j][tid] = sc * (us * vs);
                 }
             }
             __syncthreads();
