@@ -107,38 +107,90 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
         __syncthreads();
         const float *zv = su + L.zv + (size_t)f_beg * dv;
         const float *zd = su + L.zd + f_beg;
-        for (int c0 = 0; c0 < dv; c0 += dvp) {
-            const int c = c0 + tid % dvp, g = tid / dvp;
-            float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-            if (c < dv) {
+        if ((dv & 3) == 0 && dv <= 4 * kThreads) {
+            // four columns per thread (16-byte loads), consecutive lane groups on consecutive rows:
+            // a wave reads contiguous kilobytes; eight rows in flight per thread
+            const int c4n = dv / 4, c4p = pow2_at_least(c4n, 1, kThreads), grp4 = kThreads / c4p;
+            const int c4 = tid % c4p, g = tid / c4p;
+            float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0;
+            if (c4 < c4n) {
+                const float4 *z4 = (const float4 *)zv + c4;
                 int ff = g;
-                for (; ff + 3 * groups < nf; ff += 4 * groups) {
-                    a0 += phi[ff] * zv[(size_t)ff * dv + c];
-                    a1 += phi[ff + groups] * zv[(size_t)(ff + groups) * dv + c];
-                    a2 += phi[ff + 2 * groups] * zv[(size_t)(ff + 2 * groups) * dv + c];
-                    a3 += phi[ff + 3 * groups] * zv[(size_t)(ff + 3 * groups) * dv + c];
+                for (; ff + 7 * grp4 < nf; ff += 8 * grp4) {
+                    float4 zr[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) zr[i] = z4[(size_t)(ff + i * grp4) * c4n];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float ph = phi[ff + i * grp4];
+                        float4 &acc4 = (i & 1) ? s1 : s0;
+                        acc4.x += ph * zr[i].x; acc4.y += ph * zr[i].y; acc4.z += ph * zr[i].z; acc4.w += ph * zr[i].w;
+                    }
                 }
-                for (; ff < nf; ff += groups) a0 += phi[ff] * zv[(size_t)ff * dv + c];
+                for (; ff < nf; ff += grp4) {
+                    const float4 zr = z4[(size_t)ff * c4n];
+                    const float ph = phi[ff];
+                    s0.x += ph * zr.x; s0.y += ph * zr.y; s0.z += ph * zr.z; s0.w += ph * zr.w;
+                }
             }
+            float *red4 = phi;                              // phi of the slice is no longer needed after this
+            // (the ones column below reads phi: do it first)
+            float a1c = 0.f;
+            for (int ff = tid; ff < nf; ff += kThreads) a1c += phi[ff] * zd[ff];
             __syncthreads();
-            red[tid] = (a0 + a1) + (a2 + a3);
+            red[tid] = a1c;
+            red4[4 * tid + 0] = s0.x + s1.x; red4[4 * tid + 1] = s0.y + s1.y;
+            red4[4 * tid + 2] = s0.z + s1.z; red4[4 * tid + 3] = s0.w + s1.w;
             __syncthreads();
-            if (tid < dvp && c0 + tid < dv) {
+            if (tid < dv) {
+                const int cc4 = tid / 4, j4 = tid % 4;
                 float sacc = 0.f;
-                for (int q2 = 0; q2 < groups; ++q2) sacc += red[q2 * dvp + tid];
-                rowp[c0 + tid] = sacc;
+                for (int q2 = 0; q2 < grp4; ++q2) sacc += red4[4 * (q2 * c4p + cc4) + j4];
+                rowp[tid] = sacc;
             }
-        }
-        // the "ones" column
-        float a = 0.f;
-        for (int ff = tid; ff < nf; ff += kThreads) a += phi[ff] * zd[ff];
-        __syncthreads();
-        red[tid] = a;
-        __syncthreads();
-        if (tid == 0) {
-            float sacc = 0.f;
-            for (int q2 = 0; q2 < kThreads; ++q2) sacc += red[q2];
-            rowp[dv] = sacc;
+            if (tid == 0) {
+                float sacc = 0.f;
+                for (int q2 = 0; q2 < kThreads; ++q2) sacc += red[q2];
+                rowp[dv] = sacc;
+            }
+        } else {
+            for (int c0 = 0; c0 < dv; c0 += dvp) {
+                const int c = c0 + tid % dvp, g = tid / dvp;
+                float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+                if (c < dv) {
+                    int ff = g;
+                    for (; ff + 7 * groups < nf; ff += 8 * groups) {          // eight rows in flight per thread
+                        const float z0 = zv[(size_t)ff * dv + c], z1 = zv[(size_t)(ff + groups) * dv + c];
+                        const float z2 = zv[(size_t)(ff + 2 * groups) * dv + c], z3 = zv[(size_t)(ff + 3 * groups) * dv + c];
+                        const float z4 = zv[(size_t)(ff + 4 * groups) * dv + c], z5 = zv[(size_t)(ff + 5 * groups) * dv + c];
+                        const float z6 = zv[(size_t)(ff + 6 * groups) * dv + c], z7 = zv[(size_t)(ff + 7 * groups) * dv + c];
+                        a0 += phi[ff] * z0 + phi[ff + 4 * groups] * z4;
+                        a1 += phi[ff + groups] * z1 + phi[ff + 5 * groups] * z5;
+                        a2 += phi[ff + 2 * groups] * z2 + phi[ff + 6 * groups] * z6;
+                        a3 += phi[ff + 3 * groups] * z3 + phi[ff + 7 * groups] * z7;
+                    }
+                    for (; ff < nf; ff += groups) a0 += phi[ff] * zv[(size_t)ff * dv + c];
+                }
+                __syncthreads();
+                red[tid] = (a0 + a1) + (a2 + a3);
+                __syncthreads();
+                if (tid < dvp && c0 + tid < dv) {
+                    float sacc = 0.f;
+                    for (int q2 = 0; q2 < groups; ++q2) sacc += red[q2 * dvp + tid];
+                    rowp[c0 + tid] = sacc;
+                }
+            }
+            // the "ones" column
+            float a = 0.f;
+            for (int ff = tid; ff < nf; ff += kThreads) a += phi[ff] * zd[ff];
+            __syncthreads();
+            red[tid] = a;
+            __syncthreads();
+            if (tid == 0) {
+                float sacc = 0.f;
+                for (int q2 = 0; q2 < kThreads; ++q2) sacc += red[q2];
+                rowp[dv] = sacc;
+            }
         }
     }
 
