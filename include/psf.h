@@ -1,5 +1,10 @@
 /*
- * psf.h -- C ABI of libpsf: causal polynomial-sketch attention (forward) on AMD CDNA4.
+ * psf.h -- C ABI of libpsf: causal polynomial-sketch attention on AMD CDNA4 (gfx950).
+ *
+ * Entry points: psf_sketch, psf_causal_attn_fwd (the hot path), psf_noncausal_attn_fwd,
+ * psf_causal_attn_bwd, psf_causal_attn_fwd_save + psf_causal_attn_bwd_saved (forward and
+ * backward without a second forward pass), psf_decode_step (token by token), the *_timed
+ * variants for benchmarking, and the host-only sizing / selection queries.
  *
  * Method: PolySketchFormer (arXiv 2310.01655).  Every query/key row x is mapped to
  *   m(x)    = PolySketchWithNegativity(x, r, p/2)            (Algorithm 1)
@@ -8,7 +13,8 @@
  *   o_i = sum_{j<=i} w_ij v_j / (1 + sum_{j<=i} w_ij),   w_ij = <phi'(q_i), phi'(k_j)>
  * is evaluated with the block lower-triangular algorithm of Section 3.1 (per-block states
  * H_l = phi'(K_l)^T [V_l | 1], exclusive prefix Z_l over blocks, in-block term P_l) and, by
- * default, exact weights <q_i,k_j>^p for pairs inside one block (Section 3.2).
+ * default, exact weights <q_i,k_j>^p for pairs inside one block (Section 3.2).  With
+ * desc.learned the sketch m(x) is Algorithm 2's (small networks instead of Gaussian matrices).
  *
  * Conventions
  *   - Every data pointer is DEVICE memory owned by the caller.  The library never allocates,
