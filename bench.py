@@ -300,11 +300,14 @@ def run_decode(args, psf, inputs, torch):
     want = oracle.attn_def(q[0, 0].double().numpy(), k[0, 0].double().numpy(), v[0, 0].double().numpy(),
                            G[0].double().numpy(), cfg["p"], cfg["r"], cfg["b"], rows=[pos - 1])[0]
     assert np.abs(got - want).max() <= 2e-2, "decode output does not match the oracle"
-    # bytes a step has to read: the prefix state Z once (fp32), and the keys and values cached
-    # since the last block boundary (storage type), on average over the timed positions
+    # bytes a step has to read: the prefix state once (r (r + 1) / 2 rows, the distinct pairs of
+    # the symmetric feature grid), and the keys and values cached since the last block boundary
+    # (storage type), on average over the timed positions
     mid_slot = (first_timed + pos - 1) / 2 - cfg["b"]
     esize = 2 if cfg["dtype"] == "bf16" else 4
-    state_bytes = U * cfg["r"] ** 2 * (cfg["d"] + 1) * 4 + int(U * mid_slot * 2 * cfg["d"] * esize)
+    pairs = cfg["r"] * (cfg["r"] + 1) // 2
+    # bf16 storage: the steps read the value columns of the state from its bf16 copy
+    state_bytes = U * pairs * (cfg["d"] * esize + 4) + int(U * mid_slot * 2 * cfg["d"] * esize)
     achieved = state_bytes / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": "causal_polysketch_attention_decode_tokens_per_s", "value": cfg["batch"] / (ms_per_step * 1e-3),

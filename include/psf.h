@@ -230,8 +230,9 @@ psf_status psf_causal_attn_bwd_saved(const psf_desc *desc, const void *Q, const 
  * block completes.  desc->n is the longest context (pos < n); positions must be fed in order
  * 0, 1, 2, ... after psf_decode_reset.
  *   state: device memory of psf_decode_state_bytes(desc) bytes, 256-byte aligned, owned by the
- *   caller: per unit the r^2 x (dv+1) fp32 state and the current block's keys, values and
- *   sketches; its size does not depend on n.
+ *   caller: per unit the fp32 state -- r (r + 1) / 2 rows of dv + 1 columns: phi'(x) = m (x) m is
+ *   symmetric in its two indices, so only the pairs a <= b' of Z are kept, the off-diagonal ones
+ *   doubled -- and the current block's keys, values and sketches; its size does not depend on n.
  * PSF_FEAT_SKETCH only (PSF_FEAT_EXACT returns PSF_ERR_UNSUPPORTED).  Nothing is allocated and
  * nothing synchronises; everything is enqueued on hip_stream.
  */

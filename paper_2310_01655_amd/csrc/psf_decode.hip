@@ -8,34 +8,69 @@
 // Section 3.1 and w_j = <q, k_j>^p (Section 3.2) or <m(q), m(k_j)>^2 (Section 3.1) inside the
 // current block.  When a block completes, its keys are folded into Z.
 //
+// phi'(x) = m(x) (x) m(x) is symmetric in its two indices, so Z[a][b'] = Z[b'][a] and only the
+// pairs a <= b' are kept, the off-diagonal ones doubled: S[a, b'] = Z[a][b'] + Z[b'][a] (b' > a),
+// S[a, a] = Z[a][a]; then phi'(q)^T Z = sum_{a <= b'} m(q)[a] m(q)[b'] S[a, b'] -- the same
+// numbers from Fs = mcols (mcols + 1) / 2 rows instead of mcols^2.  Pair (a, b') is row
+// tri_row(a) + b' - a.
+//
 // State per (batch, head) unit, all fp32, caller-owned:
-//   ZV [F][dv] and ZD [F]: the value columns and the "ones" column of Z (F = mcols^2 features),
+//   ZV [Fs][dv] and ZD [Fs]: the value columns and the "ones" column of S,
 //   kept apart so that rows of ZV are aligned and a step streams them with full-width loads;
+//   for bf16 storage also ZH [Fs][dv], ZV rounded to bf16 at every fold: the steps read ZH;
 //   then the current block's cache: CK [b][d] keys and CV [b][dv] values in the storage type
 //   of the call (fp32 or bf16), CM [b][mcols] sketches m(k) in fp32.  After the units come the scratch areas: m(q), m(k) of the new token [units][mcols]
 //   each and the partial sums of the state product [units][kSlices][dv + 1].
-// A step is bound by reading Z once (F * (dv + 1) * 4 bytes per unit) from HBM.
+// A step is bound by reading S once (Fs * (dv + 1) * 4 bytes per unit) from HBM.
 #include "psf_internal.h"
 
 namespace psf {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kSlices = 16;        // workgroups per unit in the state product
+constexpr int kSlices = 16;        // workgroups per unit in the state product (at most)
 
 struct DecodeLayout {
-    size_t zv, zd, ck, cv, cm, per_unit;     // float offsets inside one unit, floats per unit
+    size_t zv, zd, zh, ck, cv, cm, per_unit; // float offsets inside one unit, floats per unit
     size_t mq, mk, part, total;              // float offsets of the scratch areas, total floats
+    int shadow;                              // ZH present (see has_shadow)
+    int slices;                              // workgroups per unit in the state product
 };
+
+// bf16 storage: the steps read a bf16 copy ZH of ZV (rounded once per fold from the fp32 master,
+// as the forward kernels round their prefix states), half the bytes of a step.
+bool has_shadow(const Problem &pb) { return pb.bf16 && pb.dv % 8 == 0 && pb.dv / 8 <= kThreads; }
+
+// first row of the pairs (a, b' >= a) in the packed upper triangle of an m x m grid
+__host__ __device__ inline long long tri_row(int a, int m) { return (long long)a * m - (long long)a * (a - 1) / 2; }
+__host__ __device__ inline long long tri_count(int m) { return (long long)m * (m + 1) / 2; }
+
+// the pair of packed row t: a = the largest row index with tri_row(a) <= t (closed form in
+// fp32, then corrected by steps of one)
+__device__ __forceinline__ void tri_pair(long long t, int m, int &a, int &bp)
+{
+    const float s = 2.f * m + 1.f;
+    int aa = (int)((s - sqrtf(fmaxf(s * s - 8.f * (float)t, 0.f))) * 0.5f);
+    aa = max(0, min(aa, m - 1));
+    while (aa > 0 && tri_row(aa, m) > t) --aa;
+    while (aa + 1 < m && tri_row(aa + 1, m) <= t) ++aa;
+    a = aa;
+    bp = aa + (int)(t - tri_row(aa, m));
+}
 
 DecodeLayout decode_layout(const Problem &pb)
 {
     DecodeLayout L;
     auto up = [](size_t v) { return (v + 63) / 64 * 64; };            // 256-byte pieces
+    const size_t Fs = (size_t)tri_count(pb.mcols);
+    L.shadow = has_shadow(pb) ? 1 : 0;
+    // rows per slice: enough for every thread to keep eight 16-byte loads in flight
+    L.slices = L.shadow && Fs / kSlices < 256 ? kSlices / 2 : kSlices;
     L.zv = 0;
-    L.zd = up((size_t)pb.F * pb.dv);
+    L.zd = up(Fs * pb.dv);
+    L.zh = L.zd + up(Fs);
     const size_t per_float = pb.bf16 ? 2 : 1;                         // cached keys / values keep the storage type
-    L.ck = L.zd + up((size_t)pb.F);
+    L.ck = L.zh + up(L.shadow ? (Fs * pb.dv + 1) / 2 : 0);
     L.cv = L.ck + up(((size_t)pb.b * pb.d + per_float - 1) / per_float);
     L.cm = L.cv + up(((size_t)pb.b * pb.dv + per_float - 1) / per_float);
     L.per_unit = L.cm + up((size_t)pb.b * pb.mcols);
@@ -61,6 +96,161 @@ __device__ __forceinline__ float4 load4_f(const bf16_t *p)
                        __uint_as_float(w.y & 0xffff0000u));
 }
 
+// sixteen bytes of a state row as floats: four fp32 or eight bf16 columns
+template <typename ZT> struct ZRow;
+template <> struct ZRow<float> {
+    static constexpr int NV = 4;
+    float4 raw;
+    __device__ __forceinline__ void load(const float *p) { raw = *(const float4 *)p; }
+    __device__ __forceinline__ void zero() { raw = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ void fma(float ph, float *acc) const
+    {
+        acc[0] += ph * raw.x; acc[1] += ph * raw.y; acc[2] += ph * raw.z; acc[3] += ph * raw.w;
+    }
+    __device__ __forceinline__ float dot(const float *q) const
+    {
+        return q[0] * raw.x + q[1] * raw.y + q[2] * raw.z + q[3] * raw.w;
+    }
+};
+template <> struct ZRow<bf16_t> {
+    static constexpr int NV = 8;
+    uint4 raw;
+    __device__ __forceinline__ void load(const bf16_t *p) { raw = *(const uint4 *)p; }
+    __device__ __forceinline__ void zero() { raw = make_uint4(0u, 0u, 0u, 0u); }
+    __device__ __forceinline__ void fma(float ph, float *acc) const
+    {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += ph * __uint_as_float(w[i] << 16);
+            acc[2 * i + 1] += ph * __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    __device__ __forceinline__ float dot(const float *q) const
+    {
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        float sacc = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            sacc += q[2 * i] * __uint_as_float(w[i] << 16) + q[2 * i + 1] * __uint_as_float(w[i] & 0xffff0000u);
+        return sacc;
+    }
+};
+
+// sum over the nf rows of z [nf][dv] of phi[row] * z[row][.] into rowp[0 .. dv): NV columns per
+// thread (16-byte loads), consecutive lane groups on consecutive rows so that a wave reads
+// contiguous kilobytes, eight rows in flight per thread.  `scratch` (NV * kThreads floats) may
+// alias phi: it is written only after every thread has finished reading phi.
+template <typename ZT>
+__device__ __forceinline__ void state_rows(const ZT *__restrict__ z, const float *phi, int nf, int dv,
+                                           float *scratch, float *rowp)
+{
+    constexpr int NV = ZRow<ZT>::NV;
+    const int tid = threadIdx.x;
+    const int cn = dv / NV;
+    int cp = 1;
+    while (cp < cn) cp *= 2;
+    const int grp = kThreads / cp, cv = tid % cp, g = tid / cp;
+    float s0[NV], s1[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) s0[j] = s1[j] = 0.f;
+    if (cv < cn) {
+        const ZT *zc = z + cv * NV;
+        int ff = g;
+        for (; ff + 7 * grp < nf; ff += 8 * grp) {
+            ZRow<ZT> zr[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) zr[i].load(zc + (size_t)(ff + i * grp) * dv);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) zr[i].fma(phi[ff + i * grp], (i & 1) ? s1 : s0);
+        }
+        for (; ff < nf; ff += grp) {
+            ZRow<ZT> zr;
+            zr.load(zc + (size_t)ff * dv);
+            zr.fma(phi[ff], s0);
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NV; ++j) scratch[NV * tid + j] = s0[j] + s1[j];
+    __syncthreads();
+    if (tid < dv) {
+        const int cc = tid / NV, j = tid % NV;
+        float sacc = 0.f;
+        for (int q2 = 0; q2 < grp; ++q2) sacc += scratch[NV * (q2 * cp + cc) + j];
+        rowp[tid] = sacc;
+    }
+}
+
+// In-block share of a slice: rowp[0 .. dv) += sum_j w_j v_j and rowp[dv] += sum_j w_j over the
+// cached tokens j_beg .. j_end - 1, w_j = <qs, key_j>^pw.  A group of `lg` neighbouring lanes
+// owns a cached row: lane li reads sixteen bytes of the key row, the group adds up the dot
+// product with shuffles, and the same lane then weighs sixteen bytes of the value row -- no
+// LDS between the two; four rows in flight per thread.  Needs wa % NK == 0, dv % NV == 0 and
+// lg <= 64 (see cache_rows_ok).
+template <typename KT, typename VT>
+__device__ __forceinline__ void cache_rows(const KT *__restrict__ keys, int wa, const VT *__restrict__ vals,
+                                           int dv, const float *qs, int j_beg, int j_end, int pw, int lg,
+                                           float *scratch, float *red, float *rowp)
+{
+    constexpr int NK = ZRow<KT>::NV, NV = ZRow<VT>::NV, U = 4;
+    const int tid = threadIdx.x, kn = wa / NK, vn = dv / NV;
+    const int li = tid % lg, g = tid / lg, rows_per_pass = kThreads / lg;
+    float qreg[NK];
+#pragma unroll
+    for (int j = 0; j < NK; ++j) qreg[j] = li < kn ? qs[li * NK + j] : 0.f;
+    float acc[NV], wsum = 0.f;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) acc[j] = 0.f;
+    for (int j0 = j_beg; j0 < j_end; j0 += U * rows_per_pass) {     // uniform bounds: every lane shuffles
+        ZRow<KT> kr[U];
+        ZRow<VT> vr[U];
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            const int row = j0 + i * rows_per_pass + g;
+            kr[i].zero();
+            vr[i].zero();
+            if (row < j_end && li < kn) kr[i].load(keys + (size_t)row * wa + li * NK);
+            if (row < j_end && li < vn) vr[i].load(vals + (size_t)row * dv + li * NV);
+        }
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+            float sdot = kr[i].dot(qreg);
+            for (int off = 1; off < lg; off *= 2) sdot += __shfl_xor(sdot, off);
+            float wv = 1.f;
+            for (int e = 0; e < pw; ++e) wv *= sdot;
+            if (j0 + i * rows_per_pass + g >= j_end) wv = 0.f;
+            vr[i].fma(wv, acc);
+            if (li == 0) wsum += wv;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < NV; ++j) scratch[NV * tid + j] = acc[j];
+    red[tid] = wsum;
+    __syncthreads();
+    if (tid < dv) {
+        const int cc = tid / NV, j = tid % NV;
+        float sacc = 0.f;
+        for (int q2 = 0; q2 < rows_per_pass; ++q2) sacc += scratch[NV * (q2 * lg + cc) + j];
+        rowp[tid] += sacc;
+    }
+    if (tid == 0) {
+        float sacc = 0.f;
+        for (int q2 = 0; q2 < kThreads; ++q2) sacc += red[q2];
+        rowp[dv] += sacc;
+    }
+}
+
+// lane-group size for cache_rows, or 0 when the shapes do not fit it
+__device__ __forceinline__ int cache_rows_group(int wa, int nk, int dv, int nv)
+{
+    if (wa % nk != 0 || dv % nv != 0) return 0;
+    int lg = 1;
+    while (lg < wa / nk || lg < dv / nv) lg *= 2;
+    return lg <= 64 ? lg : 0;
+}
+
 __global__ __launch_bounds__(kThreads) void dec_zero_kernel(float *__restrict__ p, size_t count)
 {
     for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < count; i += (size_t)gridDim.x * kThreads)
@@ -68,9 +258,9 @@ __global__ __launch_bounds__(kThreads) void dec_zero_kernel(float *__restrict__ 
 }
 
 // part[u][s][c] = the share of slice s in row [N | S] of the new token:
-//   cross-block: sum over the features f of the slice of phi'(q)[f] ZV[f][c] (c < dv) and, at
-//   c = dv, of phi'(q)[f] ZD[f] (only once a block is complete: have_state); phi'(q) of the slice
-//   sits in LDS; thread (c, g) walks the rows g, g + groups, ... four at a time, so a wave reads
+//   cross-block: sum over the packed pairs f = (a, b') of the slice of m(q)[a] m(q)[b'] ZV[f][c]
+//   (c < dv) and, at c = dv, of the same times ZD[f] (only once a block is complete:
+//   have_state; F = the number of pairs); the products of the slice sit in LDS; thread (c, g) walks the rows g, g + groups, ... four at a time, so a wave reads
 //   whole contiguous rows of ZV;
 //   in-block: the slice's share of the `slot` tokens cached since the last block boundary,
 //   sum_j w_j [v_j | 1] with the weights of Section 3.2 (or 3.1).  The new token itself is not in
@@ -83,7 +273,7 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
                                                              int dv, int p, int mcols, long long F, int slot,
                                                              int have_state, int local_exact)
 {
-    constexpr int kMaxPer = 4096;                          // F / kSlices <= 65536 / 16
+    constexpr int kMaxPer = 4096;                          // pairs per slice: at most tri_count(256) / 16, and under 512 with eight slices
     __shared__ float mq[PSF_MAX_DIM], qs[PSF_MAX_DIM], phi[kMaxPer], red[kThreads], w[kThreads], rowp[PSF_MAX_DIM + 1];
     const int u = blockIdx.y, sl = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
     const float *su = state + (size_t)u * L.per_unit;
@@ -95,60 +285,30 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
     __syncthreads();
     const int dvp = pow2_at_least(dv, 32, kThreads), groups = kThreads / dvp;
     float *out = part + ((size_t)u * kSlices + sl) * kc;
+    const int slices = L.slices;
 
     if (have_state) {
-        const long long per = (F + kSlices - 1) / kSlices;
+        const long long per = (F + slices - 1) / slices;
         const long long f_beg = sl * per;
         const int nf = (int)max(0LL, min(F, f_beg + per) - f_beg);
         for (int ff = tid; ff < nf; ff += kThreads) {
-            const long long f = f_beg + ff;
-            phi[ff] = mq[f / mcols] * mq[f % mcols];
+            int a, bp;
+            tri_pair(f_beg + ff, mcols, a, bp);
+            phi[ff] = mq[a] * mq[bp];
         }
         __syncthreads();
         const float *zv = su + L.zv + (size_t)f_beg * dv;
         const float *zd = su + L.zd + f_beg;
-        if ((dv & 3) == 0 && dv <= 4 * kThreads) {
-            // four columns per thread (16-byte loads), consecutive lane groups on consecutive rows:
-            // a wave reads contiguous kilobytes; eight rows in flight per thread
-            const int c4n = dv / 4, c4p = pow2_at_least(c4n, 1, kThreads), grp4 = kThreads / c4p;
-            const int c4 = tid % c4p, g = tid / c4p;
-            float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0;
-            if (c4 < c4n) {
-                const float4 *z4 = (const float4 *)zv + c4;
-                int ff = g;
-                for (; ff + 7 * grp4 < nf; ff += 8 * grp4) {
-                    float4 zr[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) zr[i] = z4[(size_t)(ff + i * grp4) * c4n];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const float ph = phi[ff + i * grp4];
-                        float4 &acc4 = (i & 1) ? s1 : s0;
-                        acc4.x += ph * zr[i].x; acc4.y += ph * zr[i].y; acc4.z += ph * zr[i].z; acc4.w += ph * zr[i].w;
-                    }
-                }
-                for (; ff < nf; ff += grp4) {
-                    const float4 zr = z4[(size_t)ff * c4n];
-                    const float ph = phi[ff];
-                    s0.x += ph * zr.x; s0.y += ph * zr.y; s0.z += ph * zr.z; s0.w += ph * zr.w;
-                }
-            }
-            float *red4 = phi;                              // phi of the slice is no longer needed after this
-            // (the ones column below reads phi: do it first)
+        if (L.shadow || ((dv & 3) == 0 && dv <= 4 * kThreads)) {
+            // the ones column first: it reads phi, which state_rows then reuses as scratch
             float a1c = 0.f;
             for (int ff = tid; ff < nf; ff += kThreads) a1c += phi[ff] * zd[ff];
-            __syncthreads();
             red[tid] = a1c;
-            red4[4 * tid + 0] = s0.x + s1.x; red4[4 * tid + 1] = s0.y + s1.y;
-            red4[4 * tid + 2] = s0.z + s1.z; red4[4 * tid + 3] = s0.w + s1.w;
-            __syncthreads();
-            if (tid < dv) {
-                const int cc4 = tid / 4, j4 = tid % 4;
-                float sacc = 0.f;
-                for (int q2 = 0; q2 < grp4; ++q2) sacc += red4[4 * (q2 * c4p + cc4) + j4];
-                rowp[tid] = sacc;
-            }
-            if (tid == 0) {
+            if (L.shadow)
+                state_rows<bf16_t>((const bf16_t *)(su + L.zh) + (size_t)f_beg * dv, phi, nf, dv, phi, rowp);
+            else
+                state_rows<float>(zv, phi, nf, dv, phi, rowp);
+            if (tid == 0) {                                  // red is complete: state_rows has barriers
                 float sacc = 0.f;
                 for (int q2 = 0; q2 < kThreads; ++q2) sacc += red[q2];
                 rowp[dv] = sacc;
@@ -195,12 +355,20 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
     }
 
     // in-block: cached tokens j_beg .. j_end - 1 of this slice
-    const int per_j = (slot + kSlices - 1) / kSlices;
+    const int per_j = (slot + slices - 1) / slices;
     const int j_beg = min(slot, sl * per_j), j_end = min(slot, j_beg + per_j);
     const T *ckeys = (const T *)(su + L.ck);             // local_exact: the cached keys, storage type
     const float *mkeys = su + L.cm;                        // otherwise: their sketches
     const T *cvals = (const T *)(su + L.cv);
-    for (int j0 = j_beg; j0 < j_end; j0 += kThreads) {
+    const int lg = cache_rows_group(wa, local_exact ? ZRow<T>::NV : 4, dv, ZRow<T>::NV);
+    if (lg > 0) {
+        __syncthreads();                                   // phi (the scratch below) and red are free
+        if (local_exact)
+            cache_rows<T, T>(ckeys, wa, cvals, dv, qs, j_beg, j_end, p, lg, phi, red, rowp);
+        else
+            cache_rows<float, T>(mkeys, wa, cvals, dv, qs, j_beg, j_end, 2, lg, phi, red, rowp);
+    }
+    for (int j0 = j_beg; lg == 0 && j0 < j_end; j0 += kThreads) {
         const int nj = min(kThreads, j_end - j0);
         __syncthreads();
         // weights of the pass: four threads per key (consecutive lanes read consecutive pieces of
@@ -297,27 +465,36 @@ __global__ __launch_bounds__(kThreads) void dec_finish_kernel(const T *__restric
     }
     __syncthreads();
     float den = 1.f + w_self;
-    for (int sidx = 0; sidx < kSlices; ++sidx) den += part[((size_t)u * kSlices + sidx) * kc + dv];
+    for (int sidx = 0; sidx < L.slices; ++sidx) den += part[((size_t)u * kSlices + sidx) * kc + dv];
     for (int c = tid; c < dv; c += kThreads) {
         float acc = w_self * load_f(v, (size_t)u * dv + c);
-        for (int sidx = 0; sidx < kSlices; ++sidx) acc += part[((size_t)u * kSlices + sidx) * kc + c];
+        for (int sidx = 0; sidx < L.slices; ++sidx) acc += part[((size_t)u * kSlices + sidx) * kc + c];
         store_f(o, (size_t)u * dv + c, acc / den);
     }
 }
 
-// ZV[f][c] += sum over the b cached tokens of phi'(k_j)[f] v_j[c], ZD[f] += sum_j phi'(k_j)[f].
-// Workgroup = kFoldFeat features; thread (c, g) owns the PER = kFoldFeat / groups features
+// ZV[f][c] += sum over the b cached tokens of w_f m_j[a] m_j[b'] v_j[c] for the packed pair
+// f = (a, b'), w_f = 2 off the diagonal and 1 on it; ZD[f] += the same without v.
+// Workgroup = kFoldFeat pairs; thread (c, g) owns the PER = kFoldFeat / groups pairs
 // g * PER .. of column c (groups = 256 / columns per pass).
 constexpr int kFoldFeat = 64, kFoldTok = 32;
 template <typename T, int PER>
 __global__ __launch_bounds__(kThreads) void dec_fold_kernel(float *__restrict__ state, DecodeLayout L,
                                                             int dv, int b, int mcols, long long F)
 {
-    __shared__ float phi[kFoldTok][kFoldFeat + 1], vt[kFoldTok][PSF_MAX_DIM];
+    __shared__ float phi[kFoldTok][kFoldFeat + 1], vt[kFoldTok][PSF_MAX_DIM], pair_w[kFoldFeat];
+    __shared__ int pair_a[kFoldFeat], pair_b[kFoldFeat];
     constexpr int groups = kFoldFeat / PER, dvp = kThreads / groups;
     const int tid = threadIdx.x, u = blockIdx.y;
     const long long f0 = (long long)blockIdx.x * kFoldFeat;
     float *su = state + (size_t)u * L.per_unit;
+    if (tid < kFoldFeat) {
+        int a = 0, bp = 0;
+        if (f0 + tid < F) tri_pair(f0 + tid, mcols, a, bp);
+        pair_a[tid] = a;
+        pair_b[tid] = bp;
+        pair_w[tid] = f0 + tid < F ? (bp > a ? 2.f : 1.f) : 0.f;
+    }
     for (int c0 = 0; c0 < dv; c0 += dvp) {
         const int c = c0 + tid % dvp, g = tid / dvp;
         float acc[PER];
@@ -330,10 +507,9 @@ __global__ __launch_bounds__(kThreads) void dec_fold_kernel(float *__restrict__ 
             for (int idx = tid; idx < kFoldTok * kFoldFeat; idx += kThreads) {
                 const int jj = idx / kFoldFeat, ff = idx % kFoldFeat;
                 float v = 0.f;
-                if (jj < lim && f0 + ff < F) {
+                if (jj < lim) {
                     const float *m = su + L.cm + (size_t)(j0 + jj) * mcols;
-                    const long long f = f0 + ff;
-                    v = m[f / mcols] * m[f % mcols];
+                    v = pair_w[ff] * m[pair_a[ff]] * m[pair_b[ff]];
                 }
                 phi[jj][ff] = v;
             }
@@ -354,16 +530,22 @@ __global__ __launch_bounds__(kThreads) void dec_fold_kernel(float *__restrict__ 
         if (c < dv) {
 #pragma unroll
             for (int ff = 0; ff < PER; ++ff)
-                if (f0 + g * PER + ff < F) su[L.zv + (size_t)(f0 + g * PER + ff) * dv + c] += acc[ff];
+                if (f0 + g * PER + ff < F) {
+                    const size_t at = (size_t)(f0 + g * PER + ff) * dv + c;
+                    const float znew = su[L.zv + at] + acc[ff];
+                    su[L.zv + at] = znew;
+                    if (L.shadow) ((bf16_t *)(su + L.zh))[at] = f32_to_bf16(znew);
+                }
         }
         if (c0 == 0 && tid < kFoldFeat && f0 + tid < F) su[L.zd + f0 + tid] += dacc;
     }
 }
 
 // The same fold on MFMA for bf16 storage (phi'(k) and v as bf16 operands, fp32 accumulation, as
-// the forward state kernel does): Z[a][b'][c] += sum_j (m_j[a] m_j[b']) v_j[c].  Workgroup =
-// (NA consecutive sketch rows a, unit); wave w owns the 32 x 32 tiles w, w + 4, ... (SLOTS of
-// them) of each row's [mcols][dv] block.  64 tokens at a time are staged transposed
+// the forward state kernel does): S[a, b'][c] += w sum_j (m_j[a] m_j[b']) v_j[c] for b' >= a.
+// Workgroup = (NA consecutive sketch rows a, unit); wave w owns the 32 x 32 tiles w, w + 4, ...
+// (SLOTS of them) of each row's [mcols][dv] block; tiles whose 32 columns b' all lie below the
+// group's first row are skipped.  64 tokens at a time are staged transposed
 // ([column][token]) so that a lane's eight tokens of one column are neighbours; the fragments of
 // m_j[b'] and of v are shared by the NA rows.
 typedef __bf16 dec_bf16x8 __attribute__((ext_vector_type(8)));
@@ -407,6 +589,7 @@ __global__ __launch_bounds__(kThreads) void dec_fold_mfma_kernel(float *__restri
             const int ti = wave + 4 * sl;
             if (ti >= ntiles) break;
             const int bt = ti / tiles_c, ct = ti % tiles_c;
+            if (32 * bt + 31 < a0) continue;
 #pragma unroll
             for (int sstep = 0; sstep < TOK / 16; ++sstep) {
                 float mb[8];
@@ -436,17 +619,26 @@ __global__ __launch_bounds__(kThreads) void dec_fold_mfma_kernel(float *__restri
         const int ti = wave + 4 * sl;
         if (ti >= ntiles) break;
         const int bt = ti / tiles_c, ct = ti % tiles_c;
+        if (32 * bt + 31 < a0) continue;
 #pragma unroll
         for (int ai = 0; ai < NA; ++ai) {
+            const int a = a0 + ai;
+            const size_t row0 = (size_t)tri_row(a, mcols);
             // accumulator: lane x = column c, register v = row b' = 8 (v / 4) + 4 h + v % 4
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int bp = 32 * bt + 8 * (v / 4) + 4 * h + (v % 4);
-                su[L.zv + ((size_t)(a0 + ai) * mcols + bp) * dv + 32 * ct + x] += acc[sl][ai][v];
+                if (bp >= a) {
+                    const size_t at = (row0 + bp - a) * dv + 32 * ct + x;
+                    const float znew = su[L.zv + at] + (bp > a ? 2.f : 1.f) * acc[sl][ai][v];
+                    su[L.zv + at] = znew;
+                    if (L.shadow) ((bf16_t *)(su + L.zh))[at] = f32_to_bf16(znew);
+                }
             }
             if (ct == 0) {                                 // the "ones" column: lanes x = row b', both halves
                 const float tot = drow[sl][ai] + __shfl_xor(drow[sl][ai], 32);
-                if (h == 0) su[L.zd + (size_t)(a0 + ai) * mcols + 32 * bt + x] += tot;
+                const int bp = 32 * bt + x;
+                if (h == 0 && bp >= a) su[L.zd + row0 + bp - a] += (bp > a ? 2.f : 1.f) * tot;
             }
         }
     }
@@ -464,15 +656,16 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
     psf_status st = general_sketch_pair_f32(one, q, k, G, state + L.mq, state + L.mk, s);   // one launch for both
     if (st != PSF_OK) return st;
     const int have_state = pos >= pb.b ? 1 : 0;          // Z is zero during the first block
-    hipLaunchKernelGGL(dec_state_kernel<T>, dim3(kSlices, (unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q,
-                       state, state + L.mq, state + L.part, L, pb.d, pb.dv, pb.p, pb.mcols, pb.F, slot, have_state, le);
+    const long long Fs = tri_count(pb.mcols);
+    hipLaunchKernelGGL(dec_state_kernel<T>, dim3((unsigned)L.slices, (unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q,
+                       state, state + L.mq, state + L.part, L, pb.d, pb.dv, pb.p, pb.mcols, Fs, slot, have_state, le);
     PSF_LAUNCH_CHECK();
     hipLaunchKernelGGL(dec_finish_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q,
                        (const T *)k, (const T *)v, state, state + L.mq, state + L.mk, state + L.part, (T *)o, L, pb.d,
                        pb.dv, pb.p, pb.mcols, slot, le);
     PSF_LAUNCH_CHECK();
     if (slot == pb.b - 1) {                               // the block is complete: fold it into Z
-        const dim3 fgrid((unsigned)((pb.F + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
+        const dim3 fgrid((unsigned)((Fs + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
         if (pb.bf16 && pb.mcols % 32 == 0 && pb.mcols <= kFoldMfmaMaxM && pb.dv % 32 == 0 && pb.dv <= kFoldMfmaMaxDv) {
             if ((pb.mcols / 32) * (pb.dv / 32) <= 4)        // one tile per wave: eight sketch rows per workgroup
                 hipLaunchKernelGGL(dec_fold_mfma_kernel<1>, dim3((unsigned)pb.mcols / 8, (unsigned)pb.units),
@@ -481,13 +674,13 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
                 hipLaunchKernelGGL(dec_fold_mfma_kernel<2>, dim3((unsigned)pb.mcols / 4, (unsigned)pb.units),
                                    dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols);
         } else if (pb.dv <= 32)
-            hipLaunchKernelGGL((dec_fold_kernel<T, 8>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+            hipLaunchKernelGGL((dec_fold_kernel<T, 8>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
         else if (pb.dv <= 64)
-            hipLaunchKernelGGL((dec_fold_kernel<T, 16>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+            hipLaunchKernelGGL((dec_fold_kernel<T, 16>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
         else if (pb.dv <= 128)
-            hipLaunchKernelGGL((dec_fold_kernel<T, 32>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+            hipLaunchKernelGGL((dec_fold_kernel<T, 32>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
         else
-            hipLaunchKernelGGL((dec_fold_kernel<T, 64>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, pb.F);
+            hipLaunchKernelGGL((dec_fold_kernel<T, 64>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
         PSF_LAUNCH_CHECK();
     }
     return PSF_OK;

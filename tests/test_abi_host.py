@@ -147,10 +147,16 @@ def test_decode_entry_points_validate_on_the_host():
     ref = ctypes.byref(d)
     one = ctypes.c_void_p(256)   # never dereferenced: every call below fails validation first
     need = psf.decode_state_bytes(d)
-    # per unit: r^2 x (dv + 1) fp32 state and the block cache (keys and values in the storage
-    # type, sketches in fp32); no n in it
-    assert need >= 6 * ((1024 * 65 + 256 * 32) * 4 + 256 * (64 + 64) * 2)
-    assert need < 6 * (1024 * 65 + 256 * (64 + 64 + 32)) * 4 + (1 << 16)
+    # per unit: r (r + 1) / 2 x (dv + 1) fp32 state (the pairs a <= b' of the symmetric r x r
+    # feature grid), for bf16 storage its value columns once more in bf16, and the block cache
+    # (keys and values in the storage type, sketches in fp32); no n in it
+    pairs = 32 * 33 // 2
+    per_unit = (pairs * 65 + 256 * 32) * 4 + pairs * 64 * 2 + 256 * (64 + 64) * 2
+    assert need >= 6 * per_unit
+    assert need < 6 * per_unit + (1 << 16)
+    f32 = psf.make_desc(2, 3, 4096, 64, 4, 32, 256, "f32")
+    per_unit_f32 = (pairs * 65 + 256 * (32 + 64 + 64)) * 4
+    assert 6 * per_unit_f32 <= psf.decode_state_bytes(f32) < 6 * per_unit_f32 + (1 << 16)
     d2 = psf.make_desc(2, 3, 65536, 64, 4, 32, 256, "bf16")
     assert psf.decode_state_bytes(d2) == need
     assert L.psf_decode_reset(ref, None, need, None) == 1
