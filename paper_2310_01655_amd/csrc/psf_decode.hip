@@ -22,6 +22,8 @@
 //   of the call (fp32 or bf16), CM [b][mcols] sketches m(k) in fp32.  After the units come the scratch areas: m(q), m(k) of the new token [units][mcols]
 //   each and the partial sums of the state product [units][kSlices][dv + 1].
 // A step is bound by reading S once (Fs * (dv + 1) * 4 bytes per unit) from HBM.
+#include <type_traits>
+
 #include "psf_internal.h"
 
 namespace psf {
@@ -65,7 +67,12 @@ DecodeLayout decode_layout(const Problem &pb)
     const size_t Fs = (size_t)tri_count(pb.mcols);
     L.shadow = has_shadow(pb) ? 1 : 0;
     // rows per slice: enough for every thread to keep eight 16-byte loads in flight
-    L.slices = L.shadow && Fs / kSlices < 256 ? kSlices / 2 : kSlices;
+    // A workgroup costs about a microsecond to start and wind up, as much as streaming a few
+    // hundred kilobytes: as few slices as still give every CU about three workgroups, each
+    // with at least 256 rows (eight 16-byte loads in flight per thread).
+    const size_t want = (768 + (size_t)pb.units - 1) / (size_t)pb.units, most = Fs / 256 > 0 ? Fs / 256 : 1;
+    L.slices = (int)(want < most ? want : most);
+    if (L.slices > kSlices) L.slices = kSlices;
     L.zv = 0;
     L.zd = up(Fs * pb.dv);
     L.zh = L.zd + up(Fs);
@@ -137,112 +144,175 @@ template <> struct ZRow<bf16_t> {
     }
 };
 
-// sum over the nf rows of z [nf][dv] of phi[row] * z[row][.] into rowp[0 .. dv): NV columns per
-// thread (16-byte loads), consecutive lane groups on consecutive rows so that a wave reads
-// contiguous kilobytes, eight rows in flight per thread.  `scratch` (NV * kThreads floats) may
-// alias phi: it is written only after every thread has finished reading phi.
-template <typename ZT>
-__device__ __forceinline__ void state_rows(const ZT *__restrict__ z, const float *phi, int nf, int dv,
-                                           float *scratch, float *rowp)
+// sum of 256 floats in LDS by the first wave (call with every thread; result valid for tid 0)
+__device__ __forceinline__ float sum256(const float *red)
 {
-    constexpr int NV = ZRow<ZT>::NV;
     const int tid = threadIdx.x;
-    const int cn = dv / NV;
-    int cp = 1;
-    while (cp < cn) cp *= 2;
-    const int grp = kThreads / cp, cv = tid % cp, g = tid / cp;
-    float s0[NV], s1[NV];
+    float v = 0.f;
+    if (tid < 64) {
+        v = (red[tid] + red[tid + 64]) + (red[tid + 128] + red[tid + 192]);
 #pragma unroll
-    for (int j = 0; j < NV; ++j) s0[j] = s1[j] = 0.f;
-    if (cv < cn) {
-        const ZT *zc = z + cv * NV;
-        int ff = g;
-        for (; ff + 7 * grp < nf; ff += 8 * grp) {
-            ZRow<ZT> zr[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) zr[i].load(zc + (size_t)(ff + i * grp) * dv);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) zr[i].fma(phi[ff + i * grp], (i & 1) ? s1 : s0);
-        }
-        for (; ff < nf; ff += grp) {
-            ZRow<ZT> zr;
-            zr.load(zc + (size_t)ff * dv);
-            zr.fma(phi[ff], s0);
-        }
+        for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
     }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < NV; ++j) scratch[NV * tid + j] = s0[j] + s1[j];
-    __syncthreads();
-    if (tid < dv) {
-        const int cc = tid / NV, j = tid % NV;
-        float sacc = 0.f;
-        for (int q2 = 0; q2 < grp; ++q2) sacc += scratch[NV * (q2 * cp + cc) + j];
-        rowp[tid] = sacc;
-    }
+    return v;
 }
+
+// Sum over the nf rows of z [nf][dv] of phi[row] * z[row][.] into rowp[0 .. dv): NV columns per
+// thread (16-byte loads), consecutive lane groups on consecutive rows so that a wave reads
+// contiguous kilobytes, eight rows in flight per thread.  issue() starts the loads of the
+// first eight rows of every thread -- they do not depend on the query, so the kernel calls it
+// before anything else -- and finish() multiplies and goes on with the remaining rows.
+// `scratch` (NV * kThreads floats) may alias phi: it is written only after every thread has
+// finished reading phi.
+template <typename ZT>
+struct StateRows {
+    static constexpr int NV = ZRow<ZT>::NV;
+    const ZT *zc;
+    int nf, dv, cp, grp, g;
+    bool active, lane_on;
+    ZRow<ZT> first[8];
+
+    __device__ __forceinline__ void issue(const ZT *z, int nf_, int dv_)
+    {
+        const int tid = threadIdx.x, cn = dv_ / NV;
+        nf = nf_;
+        dv = dv_;
+        cp = 1;
+        while (cp < cn) cp *= 2;
+        grp = kThreads / cp;
+        g = tid / cp;
+        lane_on = tid % cp < cn;
+        zc = z + (tid % cp) * NV;
+        active = true;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            first[i].zero();
+            if (lane_on && g + i * grp < nf) first[i].load(zc + (size_t)(g + i * grp) * dv);
+        }
+    }
+
+    __device__ __forceinline__ void finish(const float *phi, float *scratch, float *rowp)
+    {
+        const int tid = threadIdx.x;
+        float s0[NV], s1[NV];
+#pragma unroll
+        for (int j = 0; j < NV; ++j) s0[j] = s1[j] = 0.f;
+        if (lane_on) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (g + i * grp < nf) first[i].fma(phi[g + i * grp], (i & 1) ? s1 : s0);
+            int ff = g + 8 * grp;
+            for (; ff + 7 * grp < nf; ff += 8 * grp) {
+                ZRow<ZT> zr[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) zr[i].load(zc + (size_t)(ff + i * grp) * dv);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) zr[i].fma(phi[ff + i * grp], (i & 1) ? s1 : s0);
+            }
+            for (; ff < nf; ff += grp) {
+                ZRow<ZT> zr;
+                zr.load(zc + (size_t)ff * dv);
+                zr.fma(phi[ff], s0);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NV; ++j) scratch[NV * tid + j] = s0[j] + s1[j];
+        __syncthreads();
+        if (tid < dv) {
+            const int cc = tid / NV, j = tid % NV;
+            float sacc = 0.f;
+            for (int q2 = 0; q2 < grp; ++q2) sacc += scratch[NV * (q2 * cp + cc) + j];
+            rowp[tid] = sacc;
+        }
+    }
+};
 
 // In-block share of a slice: rowp[0 .. dv) += sum_j w_j v_j and rowp[dv] += sum_j w_j over the
 // cached tokens j_beg .. j_end - 1, w_j = <qs, key_j>^pw.  A group of `lg` neighbouring lanes
 // owns a cached row: lane li reads sixteen bytes of the key row, the group adds up the dot
 // product with shuffles, and the same lane then weighs sixteen bytes of the value row -- no
-// LDS between the two; four rows in flight per thread.  Needs wa % NK == 0, dv % NV == 0 and
-// lg <= 64 (see cache_rows_ok).
+// LDS between the two; four rows in flight per thread, the first four started by issue()
+// before the query is known.  Needs wa % NK == 0, dv % NV == 0 and lg <= 64 (see
+// cache_rows_group).
 template <typename KT, typename VT>
-__device__ __forceinline__ void cache_rows(const KT *__restrict__ keys, int wa, const VT *__restrict__ vals,
-                                           int dv, const float *qs, int j_beg, int j_end, int pw, int lg,
-                                           float *scratch, float *red, float *rowp)
-{
-    constexpr int NK = ZRow<KT>::NV, NV = ZRow<VT>::NV, U = 4;
-    const int tid = threadIdx.x, kn = wa / NK, vn = dv / NV;
-    const int li = tid % lg, g = tid / lg, rows_per_pass = kThreads / lg;
-    float qreg[NK];
-#pragma unroll
-    for (int j = 0; j < NK; ++j) qreg[j] = li < kn ? qs[li * NK + j] : 0.f;
-    float acc[NV], wsum = 0.f;
-#pragma unroll
-    for (int j = 0; j < NV; ++j) acc[j] = 0.f;
-    for (int j0 = j_beg; j0 < j_end; j0 += U * rows_per_pass) {     // uniform bounds: every lane shuffles
-        ZRow<KT> kr[U];
-        ZRow<VT> vr[U];
+struct CacheRows {
+    static constexpr int NK = ZRow<KT>::NV, NV = ZRow<VT>::NV, U = 4;
+    const KT *keys;
+    const VT *vals;
+    int wa, dv, j_beg, j_end, lg, li, g, rows_per_pass;
+    ZRow<KT> k_first[U];
+    ZRow<VT> v_first[U];
+
+    __device__ __forceinline__ void load_rows(int j0, ZRow<KT> *kr, ZRow<VT> *vr) const
+    {
 #pragma unroll
         for (int i = 0; i < U; ++i) {
             const int row = j0 + i * rows_per_pass + g;
             kr[i].zero();
             vr[i].zero();
-            if (row < j_end && li < kn) kr[i].load(keys + (size_t)row * wa + li * NK);
-            if (row < j_end && li < vn) vr[i].load(vals + (size_t)row * dv + li * NV);
-        }
-#pragma unroll
-        for (int i = 0; i < U; ++i) {
-            float sdot = kr[i].dot(qreg);
-            for (int off = 1; off < lg; off *= 2) sdot += __shfl_xor(sdot, off);
-            float wv = 1.f;
-            for (int e = 0; e < pw; ++e) wv *= sdot;
-            if (j0 + i * rows_per_pass + g >= j_end) wv = 0.f;
-            vr[i].fma(wv, acc);
-            if (li == 0) wsum += wv;
+            if (row < j_end && li < wa / NK) kr[i].load(keys + (size_t)row * wa + li * NK);
+            if (row < j_end && li < dv / NV) vr[i].load(vals + (size_t)row * dv + li * NV);
         }
     }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < NV; ++j) scratch[NV * tid + j] = acc[j];
-    red[tid] = wsum;
-    __syncthreads();
-    if (tid < dv) {
-        const int cc = tid / NV, j = tid % NV;
-        float sacc = 0.f;
-        for (int q2 = 0; q2 < rows_per_pass; ++q2) sacc += scratch[NV * (q2 * lg + cc) + j];
-        rowp[tid] += sacc;
-    }
-    if (tid == 0) {
-        float sacc = 0.f;
-        for (int q2 = 0; q2 < kThreads; ++q2) sacc += red[q2];
-        rowp[dv] += sacc;
-    }
-}
 
-// lane-group size for cache_rows, or 0 when the shapes do not fit it
+    __device__ __forceinline__ void issue(const KT *keys_, int wa_, const VT *vals_, int dv_, int j_beg_,
+                                          int j_end_, int lg_)
+    {
+        const int tid = threadIdx.x;
+        keys = keys_; vals = vals_; wa = wa_; dv = dv_; j_beg = j_beg_; j_end = j_end_; lg = lg_;
+        li = tid % lg;
+        g = tid / lg;
+        rows_per_pass = kThreads / lg;
+        load_rows(j_beg, k_first, v_first);
+    }
+
+    __device__ __forceinline__ void finish(const float *qs, int pw, float *scratch, float *red, float *rowp)
+    {
+        const int tid = threadIdx.x;
+        float qreg[NK];
+#pragma unroll
+        for (int j = 0; j < NK; ++j) qreg[j] = li < wa / NK ? qs[li * NK + j] : 0.f;
+        float acc[NV], wsum = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) acc[j] = 0.f;
+        auto weigh = [&](int j0, const ZRow<KT> *kr, const ZRow<VT> *vr) {
+#pragma unroll
+            for (int i = 0; i < U; ++i) {
+                float sdot = kr[i].dot(qreg);
+                for (int off = 1; off < lg; off *= 2) sdot += __shfl_xor(sdot, off);
+                float wv = 1.f;
+                for (int e = 0; e < pw; ++e) wv *= sdot;
+                if (j0 + i * rows_per_pass + g >= j_end) wv = 0.f;
+                vr[i].fma(wv, acc);
+                if (li == 0) wsum += wv;
+            }
+        };
+        weigh(j_beg, k_first, v_first);
+        // uniform bounds: every lane takes part in the shuffles
+        for (int j0 = j_beg + U * rows_per_pass; j0 < j_end; j0 += U * rows_per_pass) {
+            ZRow<KT> kr[U];
+            ZRow<VT> vr[U];
+            load_rows(j0, kr, vr);
+            weigh(j0, kr, vr);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < NV; ++j) scratch[NV * tid + j] = acc[j];
+        red[tid] = wsum;
+        __syncthreads();
+        if (tid < dv) {
+            const int cc = tid / NV, j = tid % NV;
+            float sacc = 0.f;
+            for (int q2 = 0; q2 < rows_per_pass; ++q2) sacc += scratch[NV * (q2 * lg + cc) + j];
+            rowp[tid] += sacc;
+        }
+        const float tot = sum256(red);
+        if (tid == 0) rowp[dv] += tot;
+    }
+};
+
+// lane-group size for CacheRows, or 0 when the shapes do not fit it
 __device__ __forceinline__ int cache_rows_group(int wa, int nk, int dv, int nv)
 {
     if (wa % nk != 0 || dv % nv != 0) return 0;
@@ -259,169 +329,179 @@ __global__ __launch_bounds__(kThreads) void dec_zero_kernel(float *__restrict__ 
 
 // part[u][s][c] = the share of slice s in row [N | S] of the new token:
 //   cross-block: sum over the packed pairs f = (a, b') of the slice of m(q)[a] m(q)[b'] ZV[f][c]
-//   (c < dv) and, at c = dv, of the same times ZD[f] (only once a block is complete:
-//   have_state; F = the number of pairs); the products of the slice sit in LDS; thread (c, g) walks the rows g, g + groups, ... four at a time, so a wave reads
-//   whole contiguous rows of ZV;
+//   (c < dv; read from the bf16 copy when SHADOW) and, at c = dv, of the same times ZD[f] (only
+//   once a block is complete: have_state; F = the number of pairs); the products of the slice
+//   sit in LDS;
 //   in-block: the slice's share of the `slot` tokens cached since the last block boundary,
-//   sum_j w_j [v_j | 1] with the weights of Section 3.2 (or 3.1).  The new token itself is not in
-//   the cache yet: its own pair is added by dec_finish_kernel.
-template <typename T>
-__global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict__ q,
-                                                             const float *__restrict__ state,
+//   sum_j w_j [v_j | 1] with the weights of Section 3.2 (LE: keys in the storage type) or 3.1
+//   (their fp32 sketches).  The new token itself is not in the cache yet: its own pair is added
+//   by dec_finish_kernel.
+// The first loads of both parts are issued before the query is read, so that a workgroup waits
+// for memory once and not four times in a row.
+// FUSE (one slice per unit): the workgroup has the whole row, so it also does what
+// dec_finish_kernel does -- the new token's own pair, the division, the cache append -- and the
+// step is two launches.
+template <typename T, bool SHADOW, bool LE, bool FUSE>
+__global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict__ q, const T *__restrict__ k,
+                                                             const T *__restrict__ v, float *__restrict__ state,
                                                              const float *__restrict__ mq_new,
-                                                             float *__restrict__ part, DecodeLayout L, int d,
-                                                             int dv, int p, int mcols, long long F, int slot,
-                                                             int have_state, int local_exact)
+                                                             const float *__restrict__ mk_new,
+                                                             float *__restrict__ part, T *__restrict__ o,
+                                                             DecodeLayout L, int d, int dv, int p, int mcols,
+                                                             long long F, int slot, int have_state)
 {
+    using ZT = std::conditional_t<SHADOW, bf16_t, float>;
+    using KT = std::conditional_t<LE, T, float>;
     constexpr int kMaxPer = 4096;                          // pairs per slice: at most tri_count(256) / 16, and under 512 with eight slices
     __shared__ float mq[PSF_MAX_DIM], qs[PSF_MAX_DIM], phi[kMaxPer], red[kThreads], w[kThreads], rowp[PSF_MAX_DIM + 1];
     const int u = blockIdx.y, sl = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
-    const float *su = state + (size_t)u * L.per_unit;
-    for (int e = tid; e < mcols; e += kThreads) mq[e] = mq_new[(size_t)u * mcols + e];
-    const int wa = local_exact ? d : mcols;
-    for (int e = tid; e < wa; e += kThreads)
-        qs[e] = local_exact ? load_f(q, (size_t)u * d + e) : mq_new[(size_t)u * mcols + e];
+    float *su = state + (size_t)u * L.per_unit;
+    const int wa = LE ? d : mcols, slices = L.slices;
+    // this slice's pairs and cached tokens
+    const long long per = (F + slices - 1) / slices;
+    const long long f_beg = sl * per;
+    const int nf = have_state ? (int)max(0LL, min(F, f_beg + per) - f_beg) : 0;
+    const int per_j = (slot + slices - 1) / slices;
+    const int j_beg = min(slot, sl * per_j), j_end = min(slot, j_beg + per_j);
+    const float *zv = su + L.zv + (size_t)f_beg * dv;
+    const float *zd = su + L.zd + f_beg;
+    const ZT *zrows = SHADOW ? (const ZT *)((const bf16_t *)(su + L.zh) + (size_t)f_beg * dv) : (const ZT *)zv;
+    const KT *keys = LE ? (const KT *)(su + L.ck) : (const KT *)(su + L.cm);
+    const T *cvals = (const T *)(su + L.cv);
+    const bool zfast = dv % ZRow<ZT>::NV == 0 && dv / ZRow<ZT>::NV <= kThreads;
+    const int lg = cache_rows_group(wa, ZRow<KT>::NV, dv, ZRow<T>::NV);
+
+    // every load that does not depend on another one, oldest first (loads complete in order):
+    // the query (mcols, wa <= 256: one element per thread), the ones column, the first state
+    // rows, the first cached rows
+    static_assert(PSF_MAX_DIM <= kThreads, "one query element per thread");
+    const float mq_reg = tid < mcols ? mq_new[(size_t)u * mcols + tid] : 0.f;
+    const float qs_reg = tid < wa ? (LE ? load_f(q, (size_t)u * d + tid) : mq_new[(size_t)u * mcols + tid]) : 0.f;
+    const float zd0 = tid < nf ? zd[tid] : 0.f, zd1 = tid + kThreads < nf ? zd[tid + kThreads] : 0.f;
+    StateRows<ZT> sr;
+    CacheRows<KT, T> cr;
+    if (zfast && nf > 0) sr.issue(zrows, nf, dv);
+    if (lg > 0 && j_end > j_beg) cr.issue(keys, wa, cvals, dv, j_beg, j_end, lg);
+
+    if (tid < mcols) mq[tid] = mq_reg;
+    if (tid < wa) qs[tid] = qs_reg;
     for (int c = tid; c < kc; c += kThreads) rowp[c] = 0.f;
     __syncthreads();
     const int dvp = pow2_at_least(dv, 32, kThreads), groups = kThreads / dvp;
     float *out = part + ((size_t)u * kSlices + sl) * kc;
-    const int slices = L.slices;
 
-    if (have_state) {
-        const long long per = (F + slices - 1) / slices;
-        const long long f_beg = sl * per;
-        const int nf = (int)max(0LL, min(F, f_beg + per) - f_beg);
+    if (nf > 0) {
         for (int ff = tid; ff < nf; ff += kThreads) {
             int a, bp;
             tri_pair(f_beg + ff, mcols, a, bp);
             phi[ff] = mq[a] * mq[bp];
         }
         __syncthreads();
-        const float *zv = su + L.zv + (size_t)f_beg * dv;
-        const float *zd = su + L.zd + f_beg;
-        if (L.shadow || ((dv & 3) == 0 && dv <= 4 * kThreads)) {
-            // the ones column first: it reads phi, which state_rows then reuses as scratch
-            float a1c = 0.f;
-            for (int ff = tid; ff < nf; ff += kThreads) a1c += phi[ff] * zd[ff];
-            red[tid] = a1c;
-            if (L.shadow)
-                state_rows<bf16_t>((const bf16_t *)(su + L.zh) + (size_t)f_beg * dv, phi, nf, dv, phi, rowp);
-            else
-                state_rows<float>(zv, phi, nf, dv, phi, rowp);
-            if (tid == 0) {                                  // red is complete: state_rows has barriers
-                float sacc = 0.f;
-                for (int q2 = 0; q2 < kThreads; ++q2) sacc += red[q2];
-                rowp[dv] = sacc;
-            }
+        // the ones column first: it reads phi, which StateRows::finish then reuses as scratch
+        float a1c = 0.f;
+        if (tid < nf) a1c = phi[tid] * zd0;
+        if (tid + kThreads < nf) a1c += phi[tid + kThreads] * zd1;
+        for (int ff = tid + 2 * kThreads; ff < nf; ff += kThreads) a1c += phi[ff] * zd[ff];
+        red[tid] = a1c;
+        if (zfast) {
+            sr.finish(phi, phi, rowp);
         } else {
             for (int c0 = 0; c0 < dv; c0 += dvp) {
                 const int c = c0 + tid % dvp, g = tid / dvp;
-                float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
-                if (c < dv) {
-                    int ff = g;
-                    for (; ff + 7 * groups < nf; ff += 8 * groups) {          // eight rows in flight per thread
-                        const float z0 = zv[(size_t)ff * dv + c], z1 = zv[(size_t)(ff + groups) * dv + c];
-                        const float z2 = zv[(size_t)(ff + 2 * groups) * dv + c], z3 = zv[(size_t)(ff + 3 * groups) * dv + c];
-                        const float z4 = zv[(size_t)(ff + 4 * groups) * dv + c], z5 = zv[(size_t)(ff + 5 * groups) * dv + c];
-                        const float z6 = zv[(size_t)(ff + 6 * groups) * dv + c], z7 = zv[(size_t)(ff + 7 * groups) * dv + c];
-                        a0 += phi[ff] * z0 + phi[ff + 4 * groups] * z4;
-                        a1 += phi[ff + groups] * z1 + phi[ff + 5 * groups] * z5;
-                        a2 += phi[ff + 2 * groups] * z2 + phi[ff + 6 * groups] * z6;
-                        a3 += phi[ff + 3 * groups] * z3 + phi[ff + 7 * groups] * z7;
-                    }
-                    for (; ff < nf; ff += groups) a0 += phi[ff] * zv[(size_t)ff * dv + c];
-                }
+                float a0 = 0.f;
+                if (c < dv)
+                    for (int ff = g; ff < nf; ff += groups) a0 += phi[ff] * zv[(size_t)ff * dv + c];
                 __syncthreads();
-                red[tid] = (a0 + a1) + (a2 + a3);
+                w[tid] = a0;
+                __syncthreads();
+                if (tid < dvp && c0 + tid < dv) {
+                    float sacc = 0.f;
+                    for (int q2 = 0; q2 < groups; ++q2) sacc += w[q2 * dvp + tid];
+                    rowp[c0 + tid] = sacc;
+                }
+            }
+        }
+        __syncthreads();                                    // red complete in either branch
+        const float tot = sum256(red);
+        if (tid == 0) rowp[dv] = tot;
+    }
+
+    // in-block: cached tokens j_beg .. j_end - 1 of this slice
+    if (lg > 0) {
+        if (j_end > j_beg) {
+            __syncthreads();                               // phi (the scratch below) and red are free
+            cr.finish(qs, LE ? p : 2, phi, red, rowp);
+        }
+    } else {
+        for (int j0 = j_beg; j0 < j_end; j0 += kThreads) {
+            const int nj = min(kThreads, j_end - j0);
+            __syncthreads();
+            // weights of the pass: four threads per key, 64 keys at a time
+            for (int kk = 0; kk < nj; kk += kThreads / 4) {
+                const int kj = kk + (tid >> 2), part4 = tid & 3;
+                float sdot = 0.f;
+                if (kj < nj) {
+                    const size_t roff = (size_t)(j0 + kj) * wa;
+                    for (int e = part4; e < wa; e += 4) sdot += qs[e] * load_f(keys, roff + e);
+                }
+                sdot += __shfl_xor(sdot, 1);
+                sdot += __shfl_xor(sdot, 2);
+                if (part4 == 0 && kj < nj) {
+                    float wv = sdot * sdot;
+                    if (LE) {
+                        wv = 1.f;
+                        for (int e = 0; e < p; ++e) wv *= sdot;
+                    }
+                    w[kj] = wv;
+                }
+            }
+            __syncthreads();
+            for (int c0 = 0; c0 < dv; c0 += dvp) {            // values: thread (c, g) takes slots g, g + groups, ...
+                const int c = c0 + tid % dvp, g = tid / dvp;
+                float a = 0.f;
+                if (c < dv)
+                    for (int jj = g; jj < nj; jj += groups) a += w[jj] * load_f(cvals, (size_t)(j0 + jj) * dv + c);
+                __syncthreads();
+                red[tid] = a;
                 __syncthreads();
                 if (tid < dvp && c0 + tid < dv) {
                     float sacc = 0.f;
                     for (int q2 = 0; q2 < groups; ++q2) sacc += red[q2 * dvp + tid];
-                    rowp[c0 + tid] = sacc;
+                    rowp[c0 + tid] += sacc;
                 }
             }
-            // the "ones" column
-            float a = 0.f;
-            for (int ff = tid; ff < nf; ff += kThreads) a += phi[ff] * zd[ff];
-            __syncthreads();
-            red[tid] = a;
-            __syncthreads();
-            if (tid == 0) {
+            if (tid == 0) {                                   // the "ones" column: sum of the weights
                 float sacc = 0.f;
-                for (int q2 = 0; q2 < kThreads; ++q2) sacc += red[q2];
-                rowp[dv] = sacc;
+                for (int jj = 0; jj < nj; ++jj) sacc += w[jj];
+                rowp[dv] += sacc;
             }
-        }
-    }
-
-    // in-block: cached tokens j_beg .. j_end - 1 of this slice
-    const int per_j = (slot + slices - 1) / slices;
-    const int j_beg = min(slot, sl * per_j), j_end = min(slot, j_beg + per_j);
-    const T *ckeys = (const T *)(su + L.ck);             // local_exact: the cached keys, storage type
-    const float *mkeys = su + L.cm;                        // otherwise: their sketches
-    const T *cvals = (const T *)(su + L.cv);
-    const int lg = cache_rows_group(wa, local_exact ? ZRow<T>::NV : 4, dv, ZRow<T>::NV);
-    if (lg > 0) {
-        __syncthreads();                                   // phi (the scratch below) and red are free
-        if (local_exact)
-            cache_rows<T, T>(ckeys, wa, cvals, dv, qs, j_beg, j_end, p, lg, phi, red, rowp);
-        else
-            cache_rows<float, T>(mkeys, wa, cvals, dv, qs, j_beg, j_end, 2, lg, phi, red, rowp);
-    }
-    for (int j0 = j_beg; lg == 0 && j0 < j_end; j0 += kThreads) {
-        const int nj = min(kThreads, j_end - j0);
-        __syncthreads();
-        // weights of the pass: four threads per key (consecutive lanes read consecutive pieces of
-        // a cached row), 64 keys at a time
-        for (int kk = 0; kk < nj; kk += kThreads / 4) {
-            const int kj = kk + (tid >> 2), part4 = tid & 3;
-            float sdot = 0.f;
-            if (kj < nj) {
-                const size_t roff = (size_t)(j0 + kj) * wa;
-                if ((wa & 15) == 0) {
-                    for (int e = 4 * part4; e < wa; e += 16) {
-                        const float4 kv = local_exact ? load4_f(ckeys + roff + e) : load4_f(mkeys + roff + e);
-                        sdot += qs[e] * kv.x + qs[e + 1] * kv.y + qs[e + 2] * kv.z + qs[e + 3] * kv.w;
-                    }
-                } else {
-                    for (int e = part4; e < wa; e += 4)
-                        sdot += qs[e] * (local_exact ? load_f(ckeys, roff + e) : mkeys[roff + e]);
-                }
-            }
-            sdot += __shfl_xor(sdot, 1);
-            sdot += __shfl_xor(sdot, 2);
-            if (part4 == 0 && kj < nj) {
-                float wv = sdot * sdot;
-                if (local_exact) {
-                    wv = 1.f;
-                    for (int e = 0; e < p; ++e) wv *= sdot;
-                }
-                w[kj] = wv;
-            }
-        }
-        __syncthreads();
-        for (int c0 = 0; c0 < dv; c0 += dvp) {            // values: thread (c, g) takes slots g, g + groups, ...
-            const int c = c0 + tid % dvp, g = tid / dvp;
-            float a = 0.f;
-            if (c < dv)
-                for (int jj = g; jj < nj; jj += groups) a += w[jj] * load_f(cvals, (size_t)(j0 + jj) * dv + c);
-            __syncthreads();
-            red[tid] = a;
-            __syncthreads();
-            if (tid < dvp && c0 + tid < dv) {
-                float sacc = 0.f;
-                for (int q2 = 0; q2 < groups; ++q2) sacc += red[q2 * dvp + tid];
-                rowp[c0 + tid] += sacc;
-            }
-        }
-        if (tid == 0) {                                   // the "ones" column: sum of the weights
-            float sacc = 0.f;
-            for (int jj = 0; jj < nj; ++jj) sacc += w[jj];
-            rowp[dv] += sacc;
         }
     }
     __syncthreads();
-    for (int c = tid; c < kc; c += kThreads) out[c] = rowp[c];
+    if constexpr (!FUSE) {
+        for (int c = tid; c < kc; c += kThreads) out[c] = rowp[c];
+    } else {
+        // own pair <q, k>^p (or <m(q), m(k)>^2), then N / (1 + S) and the cache append
+        const float k_own = tid < wa ? (LE ? load_f(k, (size_t)u * d + tid) : mk_new[(size_t)u * mcols + tid]) : 0.f;
+        red[tid] = tid < wa ? qs[tid] * k_own : 0.f;
+        __syncthreads();
+        const float sdot = sum256(red);
+        if (tid == 0) {
+            float wv = 1.f;
+            for (int e = 0; e < (LE ? p : 2); ++e) wv *= sdot;
+            w[0] = wv;
+        }
+        __syncthreads();
+        const float w_self = w[0], den = 1.f + rowp[dv] + w_self;
+        T *ckeys = (T *)(su + L.ck), *cv_out = (T *)(su + L.cv);
+        for (int c = tid; c < dv; c += kThreads) {
+            const T vraw = v[(size_t)u * dv + c];
+            store_f(o, (size_t)u * dv + c, (rowp[c] + w_self * load_f(&vraw, 0)) / den);
+            cv_out[(size_t)slot * dv + c] = vraw;
+        }
+        for (int e = tid; e < d; e += kThreads) ckeys[(size_t)slot * d + e] = k[(size_t)u * d + e];
+        for (int e = tid; e < mcols; e += kThreads) su[L.cm + (size_t)slot * mcols + e] = mk_new[(size_t)u * mcols + e];
+    }
 }
 
 // The new token's key, value and m(k) go into cache slot `slot`; row = sum of the slices + the
@@ -657,13 +737,35 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
     if (st != PSF_OK) return st;
     const int have_state = pos >= pb.b ? 1 : 0;          // Z is zero during the first block
     const long long Fs = tri_count(pb.mcols);
-    hipLaunchKernelGGL(dec_state_kernel<T>, dim3((unsigned)L.slices, (unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q,
-                       state, state + L.mq, state + L.part, L, pb.d, pb.dv, pb.p, pb.mcols, Fs, slot, have_state, le);
+    const dim3 sgrid((unsigned)L.slices, (unsigned)pb.units);
+#define PSF_DEC_STATE(SH, LE_, FU)                                                                             \
+    hipLaunchKernelGGL((dec_state_kernel<T, SH, LE_, FU>), sgrid, dim3(kThreads), 0, s, (const T *)q,             \
+                       (const T *)k, (const T *)v, state, state + L.mq, state + L.mk, state + L.part, (T *)o, L, \
+                       pb.d, pb.dv, pb.p, pb.mcols, Fs, slot, have_state)
+#define PSF_DEC_STATE_LE(SH, FU) \
+    do {                         \
+        if (le)                  \
+            PSF_DEC_STATE(SH, true, FU); \
+        else                     \
+            PSF_DEC_STATE(SH, false, FU); \
+    } while (0)
+    const bool fuse = L.slices == 1;
+    if (L.shadow) {
+        if constexpr (std::is_same_v<T, bf16_t>) {
+            if (fuse) PSF_DEC_STATE_LE(true, true); else PSF_DEC_STATE_LE(true, false);
+        }
+    } else {
+        if (fuse) PSF_DEC_STATE_LE(false, true); else PSF_DEC_STATE_LE(false, false);
+    }
+#undef PSF_DEC_STATE_LE
+#undef PSF_DEC_STATE
     PSF_LAUNCH_CHECK();
-    hipLaunchKernelGGL(dec_finish_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q,
-                       (const T *)k, (const T *)v, state, state + L.mq, state + L.mk, state + L.part, (T *)o, L, pb.d,
-                       pb.dv, pb.p, pb.mcols, slot, le);
-    PSF_LAUNCH_CHECK();
+    if (!fuse) {
+        hipLaunchKernelGGL(dec_finish_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q,
+                           (const T *)k, (const T *)v, state, state + L.mq, state + L.mk, state + L.part, (T *)o, L,
+                           pb.d, pb.dv, pb.p, pb.mcols, slot, le);
+        PSF_LAUNCH_CHECK();
+    }
     if (slot == pb.b - 1) {                               // the block is complete: fold it into Z
         const dim3 fgrid((unsigned)((Fs + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
         if (pb.bf16 && pb.mcols % 32 == 0 && pb.mcols <= kFoldMfmaMaxM && pb.dv % 32 == 0 && pb.dv <= kFoldMfmaMaxDv) {

@@ -68,6 +68,13 @@ def test_decode_bf16_block_fold_on_mfma(n, d, r, b):
     decode_all(1, 2, n, d, d, 4, r, b, "bf16")
 
 
+@pytest.mark.parametrize("dtype,n,d,r,b", [("bf16", 48, 64, 32, 16), ("f32", 40, 16, 8, 8)])
+def test_decode_many_units_one_workgroup_per_unit(dtype, n, d, r, b):
+    # 768 units: the state product of a unit is not split into slices, and the same workgroup
+    # finishes the row (own pair, division, cache append): two launches per step
+    decode_all(64, 12, n, d, d, 4, r, b, dtype, per_head=False)
+
+
 def test_decode_equals_the_forward_entry_point():
     batch, heads, n, d, p, r, b = 1, 2, 128, 32, 4, 16, 32
     out = decode_all(batch, heads, n, d, d, p, r, b, "f32", seed=53)
