@@ -338,22 +338,38 @@ __global__ __launch_bounds__(kThreads) void dec_zero_kernel(float *__restrict__ 
 //   by dec_finish_kernel.
 // The first loads of both parts are issued before the query is read, so that a workgroup waits
 // for memory once and not four times in a row.
-// FUSE (one slice per unit): the workgroup has the whole row, so it also does what
-// dec_finish_kernel does -- the new token's own pair, the division, the cache append -- and the
-// step is two launches.
-template <typename T, bool SHADOW, bool LE, bool FUSE>
+// MODE 0: slices; dec_finish_kernel adds them up.  MODE 1 (one slice per unit): the workgroup
+// has the whole row, so it also does what dec_finish_kernel does -- the new token's own pair,
+// the division, the cache append.  MODE 2: it also computes m(q) and m(k) of the new token
+// itself (Algorithm 1 with the matrices of the unit's head), and the step is one launch.
+struct DecSketchArgs {
+    const void *G;           // sketch matrices, storage type
+    size_t g_len;            // entries per set
+    int heads, per_head, r;
+};
+
+template <typename T, bool SHADOW, bool LE, int MODE>
 __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict__ q, const T *__restrict__ k,
                                                              const T *__restrict__ v, float *__restrict__ state,
                                                              const float *__restrict__ mq_new,
                                                              const float *__restrict__ mk_new,
                                                              float *__restrict__ part, T *__restrict__ o,
                                                              DecodeLayout L, int d, int dv, int p, int mcols,
-                                                             long long F, int slot, int have_state)
+                                                             long long F, int slot, int have_state,
+                                                             DecSketchArgs sk)
 {
+    constexpr bool FUSE = MODE >= 1, SK = MODE == 2;
+    static_assert(kThreads == kSketchThreads, "sketch_row_lds assumes this workgroup size");
     using ZT = std::conditional_t<SHADOW, bf16_t, float>;
     using KT = std::conditional_t<LE, T, float>;
     constexpr int kMaxPer = 4096;                          // pairs per slice: at most tri_count(256) / 16, and under 512 with eight slices
-    __shared__ float mq[PSF_MAX_DIM], qs[PSF_MAX_DIM], phi[kMaxPer], red[kThreads], w[kThreads], rowp[PSF_MAX_DIM + 1];
+    __shared__ float mq[PSF_MAX_DIM], qs[PSF_MAX_DIM], red[kThreads], w[kThreads], rowp[PSF_MAX_DIM + 1];
+    __shared__ float xk[SK ? PSF_MAX_DIM : 1], mk_s[SK ? PSF_MAX_DIM : 1], xq[SK && !LE ? PSF_MAX_DIM : 1];
+    __shared__ union {
+        float phi[kMaxPer];          // products of the slice; later the scratch of the reductions
+        SketchScratch sketch;        // before that (MODE 2): intermediates of Algorithm 1
+    } big;
+    float *const phi = big.phi;
     const int u = blockIdx.y, sl = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
     float *su = state + (size_t)u * L.per_unit;
     const int wa = LE ? d : mcols, slices = L.slices;
@@ -375,17 +391,45 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
     // the query (mcols, wa <= 256: one element per thread), the ones column, the first state
     // rows, the first cached rows
     static_assert(PSF_MAX_DIM <= kThreads, "one query element per thread");
-    const float mq_reg = tid < mcols ? mq_new[(size_t)u * mcols + tid] : 0.f;
-    const float qs_reg = tid < wa ? (LE ? load_f(q, (size_t)u * d + tid) : mq_new[(size_t)u * mcols + tid]) : 0.f;
+    float mq_reg = 0.f, qs_reg = 0.f, xq_reg = 0.f, xk_reg = 0.f;
+    if constexpr (SK) {
+        if (tid < d) {
+            xq_reg = load_f(q, (size_t)u * d + tid);
+            xk_reg = load_f(k, (size_t)u * d + tid);
+        }
+    } else {
+        if (tid < mcols) mq_reg = mq_new[(size_t)u * mcols + tid];
+        if (tid < wa) qs_reg = LE ? load_f(q, (size_t)u * d + tid) : mq_new[(size_t)u * mcols + tid];
+    }
     const float zd0 = tid < nf ? zd[tid] : 0.f, zd1 = tid + kThreads < nf ? zd[tid + kThreads] : 0.f;
     StateRows<ZT> sr;
     CacheRows<KT, T> cr;
     if (zfast && nf > 0) sr.issue(zrows, nf, dv);
     if (lg > 0 && j_end > j_beg) cr.issue(keys, wa, cvals, dv, j_beg, j_end, lg);
 
-    if (tid < mcols) mq[tid] = mq_reg;
-    if (tid < wa) qs[tid] = qs_reg;
     for (int c = tid; c < kc; c += kThreads) rowp[c] = 0.f;
+    if constexpr (SK) {
+        // raw rows into LDS (q in qs when the in-block weights use it, else in xq), then
+        // Algorithm 1 for q and for k; the results leave the scratch before it is reused
+        float *const xq_s = LE ? qs : xq;
+        if (tid < d) {
+            xq_s[tid] = xq_reg;
+            xk[tid] = xk_reg;
+        }
+        __syncthreads();
+        const T *g_set = (const T *)sk.G + (sk.per_head ? (size_t)(u % sk.heads) * sk.g_len : 0);
+        const float *fin = sketch_row_lds(xq_s, g_set, d, sk.r, p, big.sketch);
+        if (tid < mcols) {
+            mq[tid] = fin[tid];
+            if (!LE) qs[tid] = fin[tid];
+        }
+        __syncthreads();
+        fin = sketch_row_lds(xk, g_set, d, sk.r, p, big.sketch);
+        if (tid < mcols) mk_s[tid] = fin[tid];
+    } else {
+        if (tid < mcols) mq[tid] = mq_reg;
+        if (tid < wa) qs[tid] = qs_reg;
+    }
     __syncthreads();
     const int dvp = pow2_at_least(dv, 32, kThreads), groups = kThreads / dvp;
     float *out = part + ((size_t)u * kSlices + sl) * kc;
@@ -482,7 +526,12 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
         for (int c = tid; c < kc; c += kThreads) out[c] = rowp[c];
     } else {
         // own pair <q, k>^p (or <m(q), m(k)>^2), then N / (1 + S) and the cache append
-        const float k_own = tid < wa ? (LE ? load_f(k, (size_t)u * d + tid) : mk_new[(size_t)u * mcols + tid]) : 0.f;
+        float k_own = 0.f;
+        if constexpr (SK) {
+            if (tid < wa) k_own = LE ? xk[tid] : mk_s[tid];
+        } else {
+            if (tid < wa) k_own = LE ? load_f(k, (size_t)u * d + tid) : mk_new[(size_t)u * mcols + tid];
+        }
         red[tid] = tid < wa ? qs[tid] * k_own : 0.f;
         __syncthreads();
         const float sdot = sum256(red);
@@ -500,7 +549,8 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
             cv_out[(size_t)slot * dv + c] = vraw;
         }
         for (int e = tid; e < d; e += kThreads) ckeys[(size_t)slot * d + e] = k[(size_t)u * d + e];
-        for (int e = tid; e < mcols; e += kThreads) su[L.cm + (size_t)slot * mcols + e] = mk_new[(size_t)u * mcols + e];
+        for (int e = tid; e < mcols; e += kThreads)
+            su[L.cm + (size_t)slot * mcols + e] = SK ? mk_s[e] : mk_new[(size_t)u * mcols + e];
     }
 }
 
@@ -632,17 +682,28 @@ typedef __bf16 dec_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float dec_f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kFoldMfmaTok = 64, kFoldMfmaMaxM = 64, kFoldMfmaMaxDv = 128;
 
-template <int SLOTS>
-__global__ __launch_bounds__(kThreads) void dec_fold_mfma_kernel(float *__restrict__ state, DecodeLayout L,
-                                                                 int dv, int b, int mcols)
+template <int MC, int DV>
+__global__ __launch_bounds__(kThreads, 2) void dec_fold_mfma_kernel(float *__restrict__ state, DecodeLayout L, int b)
 {
-    constexpr int TOK = kFoldMfmaTok, PITCH = TOK + 1;      // odd pitch: conflict-free column reads
+    constexpr int mcols = MC, dv = DV;
+    constexpr int SLOTS = (MC / 32) * (DV / 32) <= 4 ? 1 : 2;
+    // rows of 64 tokens: pitches of 68 floats / 72 bf16 keep every 16-byte read aligned and spread
+    // the 16 lanes of a read phase over all banks
+    constexpr int TOK = kFoldMfmaTok, PITCH = TOK + 4, PITCHV = TOK + 8;
     constexpr int NA = 8 / SLOTS;
-    __shared__ float mts[kFoldMfmaMaxM][PITCH], vts[kFoldMfmaMaxDv][PITCH];
+    __shared__ __attribute__((aligned(16))) float mts[MC][PITCH];
+    __shared__ __attribute__((aligned(16))) bf16_t vts[DV][PITCHV];
     const int a0 = blockIdx.x * NA, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int x = lane & 31, h = lane >> 5;
     float *su = state + (size_t)u * L.per_unit;
-    const int tiles_c = dv / 32, ntiles = (mcols / 32) * tiles_c;
+    constexpr int tiles_c = dv / 32, ntiles = (mcols / 32) * tiles_c;
+    // Tiles whose columns b' all lie below a0 are not needed.  One tile per wave: when at most
+    // half of them are left, two waves share a tile and split its NA rows.
+    const int first_tile = (a0 / 32) * tiles_c, nact = ntiles - first_tile;
+    const bool split = SLOTS == 1 && 2 * nact <= 4 && NA % 2 == 0;
+    const int ai_lo = split ? (wave / nact) % 2 * (NA / 2) : 0, ai_hi = split ? ai_lo + NA / 2 : NA;
+    // (split: waves 0 .. 2 nact - 1 work, the others have no tile)
+    auto tile_of = [&](int sl) { return split ? (wave < 2 * nact ? first_tile + wave % nact : ntiles) : wave + 4 * sl; };
     dec_f32x16 acc[SLOTS][NA];
     float drow[SLOTS][NA];
 #pragma unroll
@@ -653,39 +714,66 @@ __global__ __launch_bounds__(kThreads) void dec_fold_mfma_kernel(float *__restri
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[sl][ai][v] = 0.f;
         }
+    // A chunk of 64 tokens goes global -> registers (16-byte / 8-byte pieces of a cached row) ->
+    // LDS (transposed); the loads of the next chunk are in flight while this one is multiplied.
+    constexpr int MP = TOK * MC / 4 / kThreads, VP = TOK * DV / 4 / kThreads;
+    float4 m_pre[MP];
+    uint2 v_pre[VP];
+    const float *cm = su + L.cm;
+    const bf16_t *cvv = (const bf16_t *)(su + L.cv);
+    auto fetch = [&](int j0) {
+#pragma unroll
+        for (int i = 0; i < MP; ++i) {
+            const int idx = tid + i * kThreads, jj = idx / (MC / 4), c4 = idx % (MC / 4);
+            m_pre[i] = j0 + jj < b ? *(const float4 *)(cm + (size_t)(j0 + jj) * MC + 4 * c4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < VP; ++i) {
+            const int idx = tid + i * kThreads, jj = idx / (DV / 4), c4 = idx % (DV / 4);
+            v_pre[i] = j0 + jj < b ? *(const uint2 *)(cvv + (size_t)(j0 + jj) * DV + 4 * c4) : make_uint2(0u, 0u);
+        }
+    };
+    auto put = [&]() {
+#pragma unroll
+        for (int i = 0; i < MP; ++i) {
+            const int idx = tid + i * kThreads, jj = idx / (MC / 4), c4 = idx % (MC / 4);
+            mts[4 * c4 + 0][jj] = m_pre[i].x; mts[4 * c4 + 1][jj] = m_pre[i].y;
+            mts[4 * c4 + 2][jj] = m_pre[i].z; mts[4 * c4 + 3][jj] = m_pre[i].w;
+        }
+#pragma unroll
+        for (int i = 0; i < VP; ++i) {
+            const int idx = tid + i * kThreads, jj = idx / (DV / 4), c4 = idx % (DV / 4);
+            vts[4 * c4 + 0][jj] = (bf16_t)(v_pre[i].x & 0xffffu); vts[4 * c4 + 1][jj] = (bf16_t)(v_pre[i].x >> 16);
+            vts[4 * c4 + 2][jj] = (bf16_t)(v_pre[i].y & 0xffffu); vts[4 * c4 + 3][jj] = (bf16_t)(v_pre[i].y >> 16);
+        }
+    };
+    fetch(0);
     for (int j0 = 0; j0 < b; j0 += TOK) {
         __syncthreads();
-        for (int idx = tid; idx < TOK * mcols; idx += kThreads) {
-            const int jj = idx / mcols, col = idx % mcols;
-            mts[col][jj] = j0 + jj < b ? su[L.cm + (size_t)(j0 + jj) * mcols + col] : 0.f;
-        }
-        for (int idx = tid; idx < TOK * dv; idx += kThreads) {
-            const int jj = idx / dv, c = idx % dv;
-            vts[c][jj] = j0 + jj < b ? bf16_to_f32(((const bf16_t *)(su + L.cv))[(size_t)(j0 + jj) * dv + c]) : 0.f;
-        }
+        put();
         __syncthreads();
+        if (j0 + TOK < b) fetch(j0 + TOK);
 #pragma unroll
         for (int sl = 0; sl < SLOTS; ++sl) {
-            const int ti = wave + 4 * sl;
+            const int ti = tile_of(sl);
             if (ti >= ntiles) break;
             const int bt = ti / tiles_c, ct = ti % tiles_c;
             if (32 * bt + 31 < a0) continue;
 #pragma unroll
             for (int sstep = 0; sstep < TOK / 16; ++sstep) {
-                float mb[8];
-                dec_bf16x8 fb;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int tok = 16 * sstep + 8 * h + e;
-                    mb[e] = mts[32 * bt + x][tok];
-                    fb[e] = (__bf16)vts[32 * ct + x][tok];
-                }
+                const int tok = 16 * sstep + 8 * h;
+                const float4 mb0 = *(const float4 *)&mts[32 * bt + x][tok], mb1 = *(const float4 *)&mts[32 * bt + x][tok + 4];
+                const float mb[8] = {mb0.x, mb0.y, mb0.z, mb0.w, mb1.x, mb1.y, mb1.z, mb1.w};
+                const dec_bf16x8 fb = *(const dec_bf16x8 *)&vts[32 * ct + x][tok];
 #pragma unroll
                 for (int ai = 0; ai < NA; ++ai) {
+                    if (ai < ai_lo || ai >= ai_hi) continue;
+                    const float4 ma0 = *(const float4 *)&mts[a0 + ai][tok], ma1 = *(const float4 *)&mts[a0 + ai][tok + 4];
+                    const float ma[8] = {ma0.x, ma0.y, ma0.z, ma0.w, ma1.x, ma1.y, ma1.z, ma1.w};
                     dec_bf16x8 fa;
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const float pr = mts[a0 + ai][16 * sstep + 8 * h + e] * mb[e];
+                        const float pr = ma[e] * mb[e];
                         fa[e] = (__bf16)pr;
                         if (ct == 0) drow[sl][ai] += pr;
                     }
@@ -696,12 +784,13 @@ __global__ __launch_bounds__(kThreads) void dec_fold_mfma_kernel(float *__restri
     }
 #pragma unroll
     for (int sl = 0; sl < SLOTS; ++sl) {
-        const int ti = wave + 4 * sl;
+        const int ti = tile_of(sl);
         if (ti >= ntiles) break;
         const int bt = ti / tiles_c, ct = ti % tiles_c;
         if (32 * bt + 31 < a0) continue;
 #pragma unroll
         for (int ai = 0; ai < NA; ++ai) {
+            if (ai < ai_lo || ai >= ai_hi) continue;
             const int a = a0 + ai;
             const size_t row0 = (size_t)tri_row(a, mcols);
             // accumulator: lane x = column c, register v = row b' = 8 (v / 4) + 4 h + v % 4
@@ -730,34 +819,42 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
 {
     const DecodeLayout L = decode_layout(pb);
     const int slot = pos % pb.b, le = pb.local_exact ? 1 : 0;
-    // sketches of the new token: the general sketch kernel on [units, 1, d]
-    Problem one = pb;
-    one.n = 1;
-    psf_status st = general_sketch_pair_f32(one, q, k, G, state + L.mq, state + L.mk, s);   // one launch for both
-    if (st != PSF_OK) return st;
+    // one workgroup per unit: it finishes the row itself, and with the sketch of Algorithm 1
+    // (no networks) it also sketches the new token
+    const bool fuse = L.slices == 1;
+    const int mode = !fuse ? 0 : (pb.learned ? 1 : 2);
+    if (mode < 2) {
+        // sketches of the new token: the general sketch kernel on [units, 1, d]
+        Problem one = pb;
+        one.n = 1;
+        psf_status st = general_sketch_pair_f32(one, q, k, G, state + L.mq, state + L.mk, s);   // one launch for both
+        if (st != PSF_OK) return st;
+    }
     const int have_state = pos >= pb.b ? 1 : 0;          // Z is zero during the first block
     const long long Fs = tri_count(pb.mcols);
     const dim3 sgrid((unsigned)L.slices, (unsigned)pb.units);
-#define PSF_DEC_STATE(SH, LE_, FU)                                                                             \
-    hipLaunchKernelGGL((dec_state_kernel<T, SH, LE_, FU>), sgrid, dim3(kThreads), 0, s, (const T *)q,             \
+    const DecSketchArgs ska{G, pb.g_len, pb.heads, pb.per_head ? 1 : 0, pb.r};
+#define PSF_DEC_STATE(SH, LE_, MO)                                                                             \
+    hipLaunchKernelGGL((dec_state_kernel<T, SH, LE_, MO>), sgrid, dim3(kThreads), 0, s, (const T *)q,             \
                        (const T *)k, (const T *)v, state, state + L.mq, state + L.mk, state + L.part, (T *)o, L, \
-                       pb.d, pb.dv, pb.p, pb.mcols, Fs, slot, have_state)
-#define PSF_DEC_STATE_LE(SH, FU) \
-    do {                         \
-        if (le)                  \
-            PSF_DEC_STATE(SH, true, FU); \
-        else                     \
-            PSF_DEC_STATE(SH, false, FU); \
+                       pb.d, pb.dv, pb.p, pb.mcols, Fs, slot, have_state, ska)
+#define PSF_DEC_STATE_MODE(SH, LE_)      \
+    do {                                 \
+        if (mode == 0)                   \
+            PSF_DEC_STATE(SH, LE_, 0);   \
+        else if (mode == 1)              \
+            PSF_DEC_STATE(SH, LE_, 1);   \
+        else                             \
+            PSF_DEC_STATE(SH, LE_, 2);   \
     } while (0)
-    const bool fuse = L.slices == 1;
     if (L.shadow) {
         if constexpr (std::is_same_v<T, bf16_t>) {
-            if (fuse) PSF_DEC_STATE_LE(true, true); else PSF_DEC_STATE_LE(true, false);
+            if (le) PSF_DEC_STATE_MODE(true, true); else PSF_DEC_STATE_MODE(true, false);
         }
     } else {
-        if (fuse) PSF_DEC_STATE_LE(false, true); else PSF_DEC_STATE_LE(false, false);
+        if (le) PSF_DEC_STATE_MODE(false, true); else PSF_DEC_STATE_MODE(false, false);
     }
-#undef PSF_DEC_STATE_LE
+#undef PSF_DEC_STATE_MODE
 #undef PSF_DEC_STATE
     PSF_LAUNCH_CHECK();
     if (!fuse) {
@@ -769,12 +866,15 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
     if (slot == pb.b - 1) {                               // the block is complete: fold it into Z
         const dim3 fgrid((unsigned)((Fs + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
         if (pb.bf16 && pb.mcols % 32 == 0 && pb.mcols <= kFoldMfmaMaxM && pb.dv % 32 == 0 && pb.dv <= kFoldMfmaMaxDv) {
-            if ((pb.mcols / 32) * (pb.dv / 32) <= 4)        // one tile per wave: eight sketch rows per workgroup
-                hipLaunchKernelGGL(dec_fold_mfma_kernel<1>, dim3((unsigned)pb.mcols / 8, (unsigned)pb.units),
-                                   dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols);
-            else                                            // two tiles per wave: four rows
-                hipLaunchKernelGGL(dec_fold_mfma_kernel<2>, dim3((unsigned)pb.mcols / 4, (unsigned)pb.units),
-                                   dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols);
+            // one 32 x 32 tile per wave and eight sketch rows per workgroup, or two and four
+            const unsigned na = (pb.mcols / 32) * (pb.dv / 32) <= 4 ? 8 : 4;
+            const dim3 mgrid((unsigned)pb.mcols / na, (unsigned)pb.units);
+#define PSF_FOLD(MC_, DV_)                                                                                       \
+    if (pb.mcols == MC_ && pb.dv == DV_)                                                                          \
+    hipLaunchKernelGGL((dec_fold_mfma_kernel<MC_, DV_>), mgrid, dim3(kThreads), 0, s, state, L, pb.b)
+            PSF_FOLD(32, 32); PSF_FOLD(32, 64); PSF_FOLD(32, 96); PSF_FOLD(32, 128);
+            PSF_FOLD(64, 32); PSF_FOLD(64, 64); PSF_FOLD(64, 96); PSF_FOLD(64, 128);
+#undef PSF_FOLD
         } else if (pb.dv <= 32)
             hipLaunchKernelGGL((dec_fold_kernel<T, 8>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
         else if (pb.dv <= 64)

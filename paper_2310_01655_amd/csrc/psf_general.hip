@@ -42,9 +42,9 @@ __global__ __launch_bounds__(kThreads) void gen_sketch_kernel(
     const T *__restrict__ X2, float *__restrict__ M2_f32)
 {
     // X2 / M2_f32 (optional): a second set of `rows` rows sketched by the same launch (fp32 out only)
+    static_assert(kThreads == kSketchThreads, "sketch_row_lds assumes this workgroup size");
     __shared__ float xs[PSF_MAX_DIM];
-    __shared__ float lev[2][4][PSF_MAX_DIM];
-    __shared__ float pu[kThreads], pv[kThreads];
+    __shared__ SketchScratch scratch;
     const int tid = threadIdx.x;
     const int mcols = (p == 2) ? d : r;
     const long long total = X2 ? 2 * rows : rows;
@@ -58,56 +58,7 @@ __global__ __launch_bounds__(kThreads) void gen_sketch_kernel(
         const float *fin = xs;
         if (!exact && p > 2) {
             const int head = (int)((row / n) % heads);
-            const T *g_first = G + (per_head ? (size_t)head * g_len : 0);
-            const T *g_inner = g_first + (size_t)(p / 2) * d * r;
-            const float sc = sqrtf(1.0f / (float)r);
-            int cur = 0, count = p / 4;                       // degree-2 sketches of x
-            // all threads take part: thread (col, part) sums the rows e = part, part + nparts, ...
-            // of both projections; the partial sums are then added in a fixed order
-            const int nparts = kThreads / r > 0 ? kThreads / r : 1, part = tid / r, col = tid % r;
-            for (int j = 0; j < count; ++j) {
-                const T *ga = g_first + (size_t)(2 * j) * d * r;
-                const T *gb = ga + (size_t)d * r;
-                float u = 0.f, v = 0.f;
-                if (part < nparts && col < r) {
-                    for (int e = part; e < d; e += nparts) {
-                        u += xs[e] * load_f(ga, (size_t)e * r + col);
-                        v += xs[e] * load_f(gb, (size_t)e * r + col);
-                    }
-                }
-                __syncthreads();
-                pu[tid] = u;
-                pv[tid] = v;
-                __syncthreads();
-                if (tid < r) {
-                    float us = 0.f, vs = 0.f;
-                    for (int q2 = 0; q2 < nparts; ++q2) { us += pu[q2 * r + tid]; vs += pv[q2 * r + tid]; }
-                    lev[cur][j][tid] = sc * (us * vs);
-                }
-            }
-            __syncthreads();
-            size_t inner_at = 0;                              // r x r matrices, level by level
-            while (count > 1) {
-                const int next = count / 2;
-                if (tid < r) {
-                    for (int j = 0; j < next; ++j) {
-                        const T *ga = g_inner + (inner_at + 2 * j) * (size_t)r * r;
-                        const T *gb = ga + (size_t)r * r;
-                        const float *m1 = lev[cur][2 * j], *m2 = lev[cur][2 * j + 1];
-                        float u = 0.f, v = 0.f;
-                        for (int e = 0; e < r; ++e) {
-                            u += m1[e] * load_f(ga, (size_t)e * r + tid);
-                            v += m2[e] * load_f(gb, (size_t)e * r + tid);
-                        }
-                        lev[cur ^ 1][j][tid] = sc * (u * v);
-                    }
-                }
-                __syncthreads();
-                inner_at += 2 * (size_t)next;
-                count = next;
-                cur ^= 1;
-            }
-            fin = lev[cur][0];
+            fin = sketch_row_lds(xs, G + (per_head ? (size_t)head * g_len : 0), d, r, p, scratch);
         }
         if (!exact) {
             if (second) {

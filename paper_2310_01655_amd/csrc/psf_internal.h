@@ -117,5 +117,74 @@ __device__ __forceinline__ float load_f(const bf16_t *p, size_t i) { return bf16
 __device__ __forceinline__ void store_f(float *p, size_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void store_f(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
 
+// ---- Algorithm 1 for one row (device) -------------------------------------------------
+// m(x) = PolySketchWithNegativity(x, r, p / 2) of the row xs[0 .. d) held in LDS, computed by a
+// workgroup of kSketchThreads threads that all call this (it contains barriers); g_set is the
+// set of sketch matrices of the row's head (p / 2 of d x r, then the r x r ones level by
+// level).  Returns the LDS address of the r results (inside lev; xs itself for p == 2), valid
+// after the barrier this function ends with.  Thread (col, part) sums the input rows
+// e = part, part + nparts, ... of both projections of a node; the partial sums are then added
+// in a fixed order.
+constexpr int kSketchThreads = 256;
+struct SketchScratch {
+    float lev[2][4][PSF_MAX_DIM];
+    float pu[kSketchThreads], pv[kSketchThreads];
+};
+
+template <typename T>
+__device__ __forceinline__ const float *sketch_row_lds(const float *xs, const T *g_set, int d, int r, int p,
+                                                       SketchScratch &sc_lds)
+{
+    if (p <= 2) return xs;
+    const int tid = threadIdx.x;
+    const T *g_inner = g_set + (size_t)(p / 2) * d * r;
+    const float sc = sqrtf(1.0f / (float)r);
+    int cur = 0, count = p / 4;                       // degree-2 sketches of x
+    const int nparts = kSketchThreads / r > 0 ? kSketchThreads / r : 1, part = tid / r, col = tid % r;
+    for (int j = 0; j < count; ++j) {
+        const T *ga = g_set + (size_t)(2 * j) * d * r;
+        const T *gb = ga + (size_t)d * r;
+        float u = 0.f, v = 0.f;
+        if (part < nparts && col < r) {
+            for (int e = part; e < d; e += nparts) {
+                u += xs[e] * load_f(ga, (size_t)e * r + col);
+                v += xs[e] * load_f(gb, (size_t)e * r + col);
+            }
+        }
+        __syncthreads();
+        sc_lds.pu[tid] = u;
+        sc_lds.pv[tid] = v;
+        __syncthreads();
+        if (tid < r) {
+            float us = 0.f, vs = 0.f;
+            for (int q2 = 0; q2 < nparts; ++q2) { us += sc_lds.pu[q2 * r + tid]; vs += sc_lds.pv[q2 * r + tid]; }
+            sc_lds.lev[cur][j][tid] = sc * (us * vs);
+        }
+    }
+    __syncthreads();
+    size_t inner_at = 0;                              // r x r matrices, level by level
+    while (count > 1) {
+        const int next = count / 2;
+        if (tid < r) {
+            for (int j = 0; j < next; ++j) {
+                const T *ga = g_inner + (inner_at + 2 * j) * (size_t)r * r;
+                const T *gb = ga + (size_t)r * r;
+                const float *m1 = sc_lds.lev[cur][2 * j], *m2 = sc_lds.lev[cur][2 * j + 1];
+                float u = 0.f, v = 0.f;
+                for (int e = 0; e < r; ++e) {
+                    u += m1[e] * load_f(ga, (size_t)e * r + tid);
+                    v += m2[e] * load_f(gb, (size_t)e * r + tid);
+                }
+                sc_lds.lev[cur ^ 1][j][tid] = sc * (u * v);
+            }
+        }
+        __syncthreads();
+        inner_at += 2 * (size_t)next;
+        count = next;
+        cur ^= 1;
+    }
+    return sc_lds.lev[cur][0];
+}
+
 }  // namespace psf
 #endif
