@@ -247,6 +247,11 @@ def run_train(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     print(json.dumps(out))
 
 
+# HBM bytes of one dec_state_kernel launch at the serving shape, mid-block (rocprofv3 counters,
+# FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0; see profiles/decode_serving_kernel_trace.md)
+DECODE_MEASURED_TRAFFIC_BYTES = 3.13e8
+
+
 def run_decode(args, psf, inputs, torch):
     """Token-by-token evaluation at serving shape: 64 sequences x 12 heads, d = 64, r = 64,
     b = 1024 (the headline per-unit shape).  The first block and the first half of the second are
@@ -318,9 +323,11 @@ def run_decode(args, psf, inputs, torch):
                    "first_timed_position": first_timed, "state_bytes": psf.decode_state_bytes(desc),
                    "ms_mid_block_step": ms_mid, "ms_block_completion_step": ms_completion},
         "roofline": {"kernel": "dec_state_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "note": "whole step time against the bytes of the prefix states and of the block cache "
-                             "(each read once per step)"},
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": DECODE_MEASURED_TRAFFIC_BYTES,
+                     "note": "whole step time (the step is this one kernel, plus the block fold spread over "
+                             "the block) against the bytes of the prefix states and of the block cache, each "
+                             "read once per step; traffic: FETCH_SIZE + WRITE_SIZE counters of the kernel "
+                             "averaged over the mid-block positions (profiles/decode_serving_kernel_trace.md)"},
     }
     if not args.no_cpu_baseline:
         cores = min(os.cpu_count() or 1, 16)

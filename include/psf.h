@@ -232,7 +232,9 @@ psf_status psf_causal_attn_bwd_saved(const psf_desc *desc, const void *Q, const 
  *   state: device memory of psf_decode_state_bytes(desc) bytes, 256-byte aligned, owned by the
  *   caller: per unit the fp32 state -- r (r + 1) / 2 rows of dv + 1 columns: phi'(x) = m (x) m is
  *   symmetric in its two indices, so only the pairs a <= b' of Z are kept, the off-diagonal ones
- *   doubled -- and the current block's keys, values and sketches; its size does not depend on n.
+ *   doubled; for PSF_BF16 also a bf16 copy of its value columns, rounded from the fp32 state each
+ *   time a block is folded in, which is what the steps read -- and the current block's keys,
+ *   values and sketches; its size does not depend on n.
  * PSF_FEAT_SKETCH only (PSF_FEAT_EXACT returns PSF_ERR_UNSUPPORTED).  Nothing is allocated and
  * nothing synchronises; everything is enqueued on hip_stream.
  */
