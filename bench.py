@@ -258,7 +258,7 @@ def run_decode(args, psf, inputs, torch):
     fed untimed, so that the prefix state is populated and the timed steps sit around the middle
     of a block, where the in-block part of a step has its average cost."""
     import numpy as np
-    cfg = dict(batch=64, heads=12, n=32768, d=64, p=4, r=64, b=1024, dtype="bf16", per_head=False)
+    cfg = dict(batch=args.decode_batch, heads=12, n=32768, d=64, p=4, r=64, b=1024, dtype="bf16", per_head=False)
     dev = torch.device("cuda:0")
     U = cfg["batch"] * cfg["heads"]
     steps_total = 2 * cfg["b"]                              # two whole blocks of tokens are drawn
@@ -318,12 +318,13 @@ def run_decode(args, psf, inputs, torch):
         "metric": "causal_polysketch_attention_decode_tokens_per_s", "value": cfg["batch"] / (ms_per_step * 1e-3),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "decode_b64", "pass": "decode", "batch": cfg["batch"], "heads": cfg["heads"],
+        "config": {"workload": "decode_b%d" % cfg["batch"], "pass": "decode", "batch": cfg["batch"], "heads": cfg["heads"],
                    "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"], "storage": cfg["dtype"],
                    "first_timed_position": first_timed, "state_bytes": psf.decode_state_bytes(desc),
                    "ms_mid_block_step": ms_mid, "ms_block_completion_step": ms_completion},
         "roofline": {"kernel": "dec_state_kernel", "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": DECODE_MEASURED_TRAFFIC_BYTES,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": DECODE_MEASURED_TRAFFIC_BYTES if cfg["batch"] == 64 else None,
                      "note": "whole step time (the step is this one kernel, plus the block fold spread over "
                              "the block) against the bytes of the prefix states and of the block cache, each "
                              "read once per step; traffic: FETCH_SIZE + WRITE_SIZE counters of the kernel "
@@ -394,6 +395,8 @@ def main():
                     help="forward pass without the causal mask (psf_noncausal_attn_fwd)")
     ap.add_argument("--learned", action="store_true",
                     help="forward pass with learned sketches (Algorithm 2) instead of Gaussian ones")
+    ap.add_argument("--decode-batch", type=int, default=64,
+                    help="sequences decoded together by --pass decode (12 heads each)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also issue one 256 MiB device copy, so that a counter run can scale "
