@@ -480,6 +480,24 @@ struct StateStep {
     }
 };
 
+// LDS image of one staged chunk of the state kernel (TC tokens of m(k) and of v).  m sits there
+// as planes of four tokens, [R][4] fp32 each, as in global memory.  The reads of m_j[a] for the
+// DPP broadcast take the same few rows a from four planes at once; with R = 64 a plane is the
+// 1 KB that one wave copies, and 64 bytes of padding per plane put those reads into different
+// banks.
+template <int R, int D, int TC>
+struct StateLds {
+    static constexpr int PLANE = R * 16;                          // four tokens of every sketch column
+    static constexpr int PS = PLANE == 1024 ? PLANE + 64 : PLANE; // plane stride in LDS
+    static constexpr int M_LDS = (TC / 4) * PS;
+    static constexpr int BUF = (M_LDS + TC * D * 2 + 255) / 256 * 256;
+    // LDS offset of the 1 KB that wave w copies of the 4 KB piece q of m
+    static __device__ __forceinline__ uint32_t m_piece(int q, int w)
+    {
+        return PLANE == 1024 ? (uint32_t)((4 * q + w) * PS) : (uint32_t)(q * 4096 + w * 1024);
+    }
+};
+
 // SYM: Z[a][b'] = Z[b'][a] and the output kernel reads, for sketch row a, only the 16-wide
 // column ranges beta >= a / 16, so only those (a, beta) segments are computed: 16 (beta + 1)
 // rows a per range beta, R/16 * (R/16 + 1) / 2 * 16 segments in all (160 of 256 for R = 64).
@@ -496,8 +514,10 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
     constexpr int CT = D / 32;
     constexpr int NBUF = kStateRing;
     constexpr int STEPS = TC / 16;
-    constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2, BUF_BYTES = M_BYTES + V_BYTES;
-    constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
+    constexpr int PS = StateLds<R, D, TC>::PS;
+    constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2;
+    constexpr int M_LDS = StateLds<R, D, TC>::M_LDS, BUF_BYTES = StateLds<R, D, TC>::BUF;
+    constexpr int DMA_PER_CHUNK = (M_BYTES + V_BYTES) / 16 / kWg;
     constexpr int SEG = SYM ? 2 : 1;           // rows a per tile
     static_assert(M_BYTES % 4096 == 0 && V_BYTES % 4096 == 0, "whole 4 KB pieces");
     static_assert(NA <= 8, "DPP source lanes");
@@ -542,25 +562,26 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
         constexpr int SLOT = decltype(slot_tag)::value;
         const unsigned char *sm = (const unsigned char *)(gm + (size_t)chunk * TC * R);
         const unsigned char *sv = (const unsigned char *)(gv + (size_t)chunk * TC * D);
-        const uint32_t dst = lds0 + SLOT * BUF_BYTES + wave * 1024;
+        const uint32_t dst = lds0 + SLOT * BUF_BYTES;
 #pragma unroll
-        for (int q = 0; q < M_BYTES / 16 / kWg; ++q) dma16_sbase(sm + q * 4096, copy_off, dst + q * 4096);
+        for (int q = 0; q < M_BYTES / 16 / kWg; ++q)
+            dma16_sbase(sm + q * 4096, copy_off, dst + StateLds<R, D, TC>::m_piece(q, wave));
 #pragma unroll
         for (int q = 0; q < V_BYTES / 16 / kWg; ++q)
-            dma16_sbase(sv + q * 4096, copy_off, dst + M_BYTES + q * 4096);
+            dma16_sbase(sv + q * 4096, copy_off, dst + M_LDS + q * 4096 + wave * 1024);
     };
-    const unsigned char *lane_b = lds_base + ((h * 2 * R + bcol) * 16);
-    const unsigned char *lane_a = lds_base + (((h * 2 + q_src) * R + a_src) * 16);
-    const unsigned char *lane_v = lds_base + M_BYTES + ((h * D + x) * 16);
+    const unsigned char *lane_b = lds_base + (h * 2 * PS + bcol * 16);
+    const unsigned char *lane_a = lds_base + ((h * 2 + q_src) * PS + a_src * 16);
+    const unsigned char *lane_v = lds_base + M_LDS + ((h * D + x) * 16);
     auto load_ops = [&](auto slot_tag, auto step_tag) {
         constexpr int OFF = decltype(slot_tag)::value * BUF_BYTES;
         constexpr int S = decltype(step_tag)::value;          // octet 2 S + h
         StateOps<CT> o;
-        const f32x4 b_lo = *(const f32x4 *)(lane_b + OFF + S * 4 * R * 16);
-        const f32x4 b_hi = *(const f32x4 *)(lane_b + OFF + S * 4 * R * 16 + R * 16);
+        const f32x4 b_lo = *(const f32x4 *)(lane_b + OFF + S * 4 * PS);
+        const f32x4 b_hi = *(const f32x4 *)(lane_b + OFF + S * 4 * PS + PS);
 #pragma unroll
         for (int e = 0; e < 4; ++e) { o.bfv[e] = b_lo[e]; o.bfv[4 + e] = b_hi[e]; }
-        o.af = *(const f32x4 *)(lane_a + OFF + S * 4 * R * 16);
+        o.af = *(const f32x4 *)(lane_a + OFF + S * 4 * PS);
 #pragma unroll
         for (int ct = 0; ct < CT; ++ct) o.vf[ct] = *(const bf16x8 *)(lane_v + OFF + S * 2 * D * 16 + ct * 32 * 16);
         return o;
@@ -639,8 +660,8 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
                                                int units)
 {
     constexpr int NBUF = kStateRing;
-    constexpr int BUF_BYTES = TC * R * 4 + TC * D * 2;
-    constexpr int DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
+    constexpr int BUF_BYTES = StateLds<R, D, TC>::BUF, M_LDS = StateLds<R, D, TC>::M_LDS;
+    constexpr int DMA_PER_CHUNK = (TC * R * 4 + TC * D * 2) / 16 / kWg;
     constexpr int AG = NA * 4 / (R / 32);
     static_assert(!SYM || NA == 2, "tile deal of the symmetric variant");
     __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF * BUF_BYTES];
@@ -667,11 +688,12 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
             unsigned char *dst = lds + c * BUF_BYTES;
 #pragma unroll
             for (int q = 0; q < TC * R * 4 / 16 / kWg; ++q)
-                dma16(gm + (size_t)chunk * TC * R + (size_t)(q * kWg + tid) * 4, dst + (size_t)(q * kWg + wave * 64) * 16);
+                dma16(gm + (size_t)chunk * TC * R + (size_t)(q * kWg + tid) * 4,
+                      dst + StateLds<R, D, TC>::m_piece(q, wave));
 #pragma unroll
             for (int q = 0; q < TC * D * 2 / 16 / kWg; ++q)
                 dma16(gv + (size_t)chunk * TC * D + (size_t)(q * kWg + tid) * 8,
-                      dst + TC * R * 4 + (size_t)(q * kWg + wave * 64) * 16);
+                      dst + M_LDS + (size_t)(q * kWg + wave * 64) * 16);
         }
         wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
         __syncthreads();
