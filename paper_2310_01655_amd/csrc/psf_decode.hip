@@ -14,14 +14,17 @@
 // numbers from Fs = mcols (mcols + 1) / 2 rows instead of mcols^2.  Pair (a, b') is row
 // tri_row(a) + b' - a.
 //
-// State per (batch, head) unit, all fp32, caller-owned:
-//   ZV [Fs][dv] and ZD [Fs]: the value columns and the "ones" column of S,
-//   kept apart so that rows of ZV are aligned and a step streams them with full-width loads;
+// State per (batch, head) unit, caller-owned:
+//   ZV [Fs][dv] and ZD [Fs] in fp32: the value columns and the "ones" column of S, kept apart
+//   so that rows of ZV are aligned and a step streams them with full-width loads;
 //   for bf16 storage also ZH [Fs][dv], ZV rounded to bf16 at every fold: the steps read ZH;
 //   then the current block's cache: CK [b][d] keys and CV [b][dv] values in the storage type
-//   of the call (fp32 or bf16), CM [b][mcols] sketches m(k) in fp32.  After the units come the scratch areas: m(q), m(k) of the new token [units][mcols]
-//   each and the partial sums of the state product [units][kSlices][dv + 1].
-// A step is bound by reading S once (Fs * (dv + 1) * 4 bytes per unit) from HBM.
+//   of the call (fp32 or bf16), CM [b][mcols] sketches m(k) in fp32.
+// After the units come the scratch areas: m(q), m(k) of the new token [units][mcols] each and
+// the partial sums of the state product [units][kSlices][dv + 1] (used when a unit's product is
+// split over several workgroups).
+// A step is bound by reading the state once (Fs * (dv * s + 4) bytes per unit, s = 2 with the
+// bf16 copy, 4 without) and the cached keys and values of the current block.
 #include <type_traits>
 
 #include "psf_internal.h"
