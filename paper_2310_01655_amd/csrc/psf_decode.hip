@@ -34,6 +34,9 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kSlices = 16;        // workgroups per unit in the state product (at most)
+constexpr int kMaxPairsPerSlice = 4096;
+static_assert((size_t)PSF_MAX_DIM * (PSF_MAX_DIM + 1) / 2 <= (size_t)kSlices * kMaxPairsPerSlice,
+              "the largest state fits kSlices slices");
 
 struct DecodeLayout {
     size_t zv, zd, zh, ck, cv, cm, per_unit; // float offsets inside one unit, floats per unit
@@ -73,8 +76,11 @@ DecodeLayout decode_layout(const Problem &pb)
     // A workgroup costs about a microsecond to start and wind up, as much as streaming a few
     // hundred kilobytes: as few slices as still give every CU about three workgroups, each
     // with at least 256 rows (eight 16-byte loads in flight per thread).
+    // A slice's products m(q)[a] m(q)[b'] sit in LDS: at most kMaxPairsPerSlice of them.
     const size_t want = (768 + (size_t)pb.units - 1) / (size_t)pb.units, most = Fs / 256 > 0 ? Fs / 256 : 1;
+    const size_t least = (Fs + kMaxPairsPerSlice - 1) / kMaxPairsPerSlice;
     L.slices = (int)(want < most ? want : most);
+    if (L.slices < (int)least) L.slices = (int)least;
     if (L.slices > kSlices) L.slices = kSlices;
     L.zv = 0;
     L.zd = up(Fs * pb.dv);
@@ -365,7 +371,7 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
     static_assert(kThreads == kSketchThreads, "sketch_row_lds assumes this workgroup size");
     using ZT = std::conditional_t<SHADOW, bf16_t, float>;
     using KT = std::conditional_t<LE, T, float>;
-    constexpr int kMaxPer = 4096;                          // pairs per slice: at most tri_count(256) / 16, and under 512 with eight slices
+    constexpr int kMaxPer = kMaxPairsPerSlice;             // decode_layout keeps a slice within this
     __shared__ float mq[PSF_MAX_DIM], qs[PSF_MAX_DIM], red[kThreads], w[kThreads], rowp[PSF_MAX_DIM + 1];
     __shared__ float xk[SK ? PSF_MAX_DIM : 1], mk_s[SK ? PSF_MAX_DIM : 1], xq[SK && !LE ? PSF_MAX_DIM : 1];
     __shared__ union {

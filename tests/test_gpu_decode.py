@@ -75,6 +75,12 @@ def test_decode_many_units_one_workgroup_per_unit(dtype, n, d, r, b):
     decode_all(64, 12, n, d, d, 4, r, b, dtype, per_head=False)
 
 
+def test_decode_many_units_large_sketch_keeps_slices_within_lds():
+    # 384 units and r = 128 (8256 pairs): more pairs than one workgroup holds in LDS, so the
+    # unit count alone must not decide the number of slices
+    decode_all(32, 12, 24, 16, 16, 4, 128, 8, "f32", per_head=False)
+
+
 def test_decode_equals_the_forward_entry_point():
     batch, heads, n, d, p, r, b = 1, 2, 128, 32, 4, 16, 32
     out = decode_all(batch, heads, n, d, d, p, r, b, "f32", seed=53)
