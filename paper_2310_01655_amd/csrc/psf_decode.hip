@@ -376,7 +376,7 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
     __shared__ float xk[SK ? PSF_MAX_DIM : 1], mk_s[SK ? PSF_MAX_DIM : 1], xq[SK && !LE ? PSF_MAX_DIM : 1];
     __shared__ union {
         float phi[kMaxPer];          // products of the slice; later the scratch of the reductions
-        SketchScratch sketch;        // before that (MODE 2): intermediates of Algorithm 1
+        SketchScratchN<2> sketch;    // before that (MODE 2): intermediates of Algorithm 1 for q and k
     } big;
     float *const phi = big.phi;
     const int u = blockIdx.y, sl = blockIdx.x, tid = threadIdx.x, kc = dv + 1;
@@ -419,7 +419,7 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
     for (int c = tid; c < kc; c += kThreads) rowp[c] = 0.f;
     if constexpr (SK) {
         // raw rows into LDS (q in qs when the in-block weights use it, else in xq), then
-        // Algorithm 1 for q and for k; the results leave the scratch before it is reused
+        // Algorithm 1 for q and k together; the results leave the scratch before it is reused
         float *const xq_s = LE ? qs : xq;
         if (tid < d) {
             xq_s[tid] = xq_reg;
@@ -427,14 +427,14 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
         }
         __syncthreads();
         const T *g_set = (const T *)sk.G + (sk.per_head ? (size_t)(u % sk.heads) * sk.g_len : 0);
-        const float *fin = sketch_row_lds(xq_s, g_set, d, sk.r, p, big.sketch);
+        const float *const rows[2] = {xq_s, xk};
+        const float *fin[2];
+        sketch_rows_lds<T, 2>(rows, g_set, d, sk.r, p, big.sketch, fin);
         if (tid < mcols) {
-            mq[tid] = fin[tid];
-            if (!LE) qs[tid] = fin[tid];
+            mq[tid] = fin[0][tid];
+            if (!LE) qs[tid] = fin[0][tid];
+            mk_s[tid] = fin[1][tid];
         }
-        __syncthreads();
-        fin = sketch_row_lds(xk, g_set, d, sk.r, p, big.sketch);
-        if (tid < mcols) mk_s[tid] = fin[tid];
     } else {
         if (tid < mcols) mq[tid] = mq_reg;
         if (tid < wa) qs[tid] = qs_reg;

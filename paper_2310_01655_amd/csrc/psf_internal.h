@@ -117,25 +117,32 @@ __device__ __forceinline__ float load_f(const bf16_t *p, size_t i) { return bf16
 __device__ __forceinline__ void store_f(float *p, size_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void store_f(bf16_t *p, size_t i, float v) { p[i] = f32_to_bf16(v); }
 
-// ---- Algorithm 1 for one row (device) -------------------------------------------------
-// m(x) = PolySketchWithNegativity(x, r, p / 2) of the row xs[0 .. d) held in LDS, computed by a
-// workgroup of kSketchThreads threads that all call this (it contains barriers); g_set is the
-// set of sketch matrices of the row's head (p / 2 of d x r, then the r x r ones level by
-// level).  Returns the LDS address of the r results (inside lev; xs itself for p == 2), valid
+// ---- Algorithm 1 for a few rows (device) ----------------------------------------------
+// m(x) = PolySketchWithNegativity(x, r, p / 2) of NR rows xs[i][0 .. d) held in LDS, computed by
+// a workgroup of kSketchThreads threads that all call this (it contains barriers); the rows
+// share g_set, the set of sketch matrices of their head (p / 2 of d x r, then the r x r ones
+// level by level), so every matrix entry is loaded once for all of them.  fin[i] receives the
+// LDS address of the r results of row i (inside the scratch; xs[i] itself for p == 2), valid
 // after the barrier this function ends with.  Thread (col, part) sums the input rows
 // e = part, part + nparts, ... of both projections of a node; the partial sums are then added
 // in a fixed order.
 constexpr int kSketchThreads = 256;
-struct SketchScratch {
-    float lev[2][4][PSF_MAX_DIM];
-    float pu[kSketchThreads], pv[kSketchThreads];
+template <int NR>
+struct SketchScratchN {
+    float lev[NR][2][4][PSF_MAX_DIM];
+    float pu[NR][kSketchThreads], pv[NR][kSketchThreads];
 };
+typedef SketchScratchN<1> SketchScratch;
 
-template <typename T>
-__device__ __forceinline__ const float *sketch_row_lds(const float *xs, const T *g_set, int d, int r, int p,
-                                                       SketchScratch &sc_lds)
+template <typename T, int NR>
+__device__ __forceinline__ void sketch_rows_lds(const float *const (&xs)[NR], const T *g_set, int d, int r, int p,
+                                                SketchScratchN<NR> &sc_lds, const float *(&fin)[NR])
 {
-    if (p <= 2) return xs;
+    if (p <= 2) {
+#pragma unroll
+        for (int i = 0; i < NR; ++i) fin[i] = xs[i];
+        return;
+    }
     const int tid = threadIdx.x;
     const T *g_inner = g_set + (size_t)(p / 2) * d * r;
     const float sc = sqrtf(1.0f / (float)r);
@@ -144,21 +151,33 @@ __device__ __forceinline__ const float *sketch_row_lds(const float *xs, const T 
     for (int j = 0; j < count; ++j) {
         const T *ga = g_set + (size_t)(2 * j) * d * r;
         const T *gb = ga + (size_t)d * r;
-        float u = 0.f, v = 0.f;
+        float u[NR], v[NR];
+#pragma unroll
+        for (int i = 0; i < NR; ++i) u[i] = v[i] = 0.f;
         if (part < nparts && col < r) {
             for (int e = part; e < d; e += nparts) {
-                u += xs[e] * load_f(ga, (size_t)e * r + col);
-                v += xs[e] * load_f(gb, (size_t)e * r + col);
+                const float a = load_f(ga, (size_t)e * r + col), b = load_f(gb, (size_t)e * r + col);
+#pragma unroll
+                for (int i = 0; i < NR; ++i) {
+                    u[i] += xs[i][e] * a;
+                    v[i] += xs[i][e] * b;
+                }
             }
         }
         __syncthreads();
-        sc_lds.pu[tid] = u;
-        sc_lds.pv[tid] = v;
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+            sc_lds.pu[i][tid] = u[i];
+            sc_lds.pv[i][tid] = v[i];
+        }
         __syncthreads();
         if (tid < r) {
-            float us = 0.f, vs = 0.f;
-            for (int q2 = 0; q2 < nparts; ++q2) { us += sc_lds.pu[q2 * r + tid]; vs += sc_lds.pv[q2 * r + tid]; }
-            sc_lds.lev[cur][j][tid] = sc * (us * vs);
+#pragma unroll
+            for (int i = 0; i < NR; ++i) {
+                float us = 0.f, vs = 0.f;
+                for (int q2 = 0; q2 < nparts; ++q2) { us += sc_lds.pu[i][q2 * r + tid]; vs += sc_lds.pv[i][q2 * r + tid]; }
+                sc_lds.lev[i][cur][j][tid] = sc * (us * vs);
+            }
         }
     }
     __syncthreads();
@@ -169,13 +188,19 @@ __device__ __forceinline__ const float *sketch_row_lds(const float *xs, const T 
             for (int j = 0; j < next; ++j) {
                 const T *ga = g_inner + (inner_at + 2 * j) * (size_t)r * r;
                 const T *gb = ga + (size_t)r * r;
-                const float *m1 = sc_lds.lev[cur][2 * j], *m2 = sc_lds.lev[cur][2 * j + 1];
-                float u = 0.f, v = 0.f;
+                float u[NR], v[NR];
+#pragma unroll
+                for (int i = 0; i < NR; ++i) u[i] = v[i] = 0.f;
                 for (int e = 0; e < r; ++e) {
-                    u += m1[e] * load_f(ga, (size_t)e * r + tid);
-                    v += m2[e] * load_f(gb, (size_t)e * r + tid);
+                    const float a = load_f(ga, (size_t)e * r + tid), b = load_f(gb, (size_t)e * r + tid);
+#pragma unroll
+                    for (int i = 0; i < NR; ++i) {
+                        u[i] += sc_lds.lev[i][cur][2 * j][e] * a;
+                        v[i] += sc_lds.lev[i][cur][2 * j + 1][e] * b;
+                    }
                 }
-                sc_lds.lev[cur ^ 1][j][tid] = sc * (u * v);
+#pragma unroll
+                for (int i = 0; i < NR; ++i) sc_lds.lev[i][cur ^ 1][j][tid] = sc * (u[i] * v[i]);
             }
         }
         __syncthreads();
@@ -183,7 +208,18 @@ __device__ __forceinline__ const float *sketch_row_lds(const float *xs, const T 
         count = next;
         cur ^= 1;
     }
-    return sc_lds.lev[cur][0];
+#pragma unroll
+    for (int i = 0; i < NR; ++i) fin[i] = sc_lds.lev[i][cur][0];
+}
+
+template <typename T>
+__device__ __forceinline__ const float *sketch_row_lds(const float *xs, const T *g_set, int d, int r, int p,
+                                                       SketchScratch &sc_lds)
+{
+    const float *const rows[1] = {xs};
+    const float *fin[1];
+    sketch_rows_lds<T, 1>(rows, g_set, d, r, p, sc_lds, fin);
+    return fin[0];
 }
 
 }  // namespace psf
