@@ -3,8 +3,9 @@
  *
  * Entry points: psf_sketch, psf_causal_attn_fwd (the hot path), psf_noncausal_attn_fwd,
  * psf_causal_attn_bwd, psf_causal_attn_fwd_save + psf_causal_attn_bwd_saved (forward and
- * backward without a second forward pass), psf_decode_step (token by token), the *_timed
- * variants for benchmarking, and the host-only sizing / selection queries.
+ * backward without a second forward pass), psf_decode_step (token by token) with
+ * psf_decode_prefill (its state after a prompt), the *_timed variants for benchmarking, and the
+ * host-only sizing / selection queries.
  *
  * Method: PolySketchFormer (arXiv 2310.01655).  Every query/key row x is mapped to
  *   m(x)    = PolySketchWithNegativity(x, r, p/2)            (Algorithm 1)
@@ -243,6 +244,25 @@ psf_status psf_decode_reset(const psf_desc *desc, void *state, size_t state_byte
 psf_status psf_decode_step(const psf_desc *desc, const void *q, const void *k, const void *v,
                            const void *G, int32_t pos, void *state, size_t state_bytes, void *o,
                            void *hip_stream);
+
+/*
+ * Hand-over from a prompt to token-by-token evaluation.  psf_decode_prefill leaves `state` as
+ * if the first n_prompt positions had gone through psf_decode_step one by one (the state is
+ * reset first; the next call is psf_decode_step with pos = n_prompt): the keys of the completed
+ * blocks folded into the prefix state of Section 3.1, the rest of the prompt in the block
+ * cache.  It produces no output rows: those of the prompt are what psf_causal_attn_fwd
+ * returns for it.
+ *   K [batch, heads, n_prompt, d], V [batch, heads, n_prompt, dv]: device, desc->dtype;
+ *   0 <= n_prompt <= desc->n (else PSF_ERR_SHAPE); G as for psf_decode_step.
+ *   workspace: psf_decode_prefill_workspace_bytes(desc, n_prompt) bytes of device memory,
+ *   256-byte aligned; zero (null allowed) for the sketches of Algorithm 1, the fp32 sketches of
+ *   all prompt keys for learned sketches.
+ * Nothing is allocated and nothing synchronises; everything is enqueued on hip_stream.
+ */
+size_t psf_decode_prefill_workspace_bytes(const psf_desc *desc, int32_t n_prompt);
+psf_status psf_decode_prefill(const psf_desc *desc, const void *K, const void *V, const void *G,
+                              int32_t n_prompt, void *state, size_t state_bytes, void *workspace,
+                              size_t workspace_bytes, void *hip_stream);
 
 const char *psf_status_string(psf_status status);
 

@@ -24,7 +24,7 @@ EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_le
            "psf_noncausal_attn_fwd_timed", "psf_fwd_save_bytes", "psf_causal_attn_fwd_save",
            "psf_causal_attn_bwd_saved", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
            "psf_causal_attn_bwd_timed", "psf_decode_state_bytes", "psf_decode_reset",
-           "psf_decode_step")
+           "psf_decode_step", "psf_decode_prefill_workspace_bytes", "psf_decode_prefill")
 
 
 class PsfDesc(ctypes.Structure):
@@ -100,6 +100,10 @@ def lib():
         L.psf_decode_reset.argtypes = [dp, vp, ctypes.c_size_t, vp]
         L.psf_decode_step.restype = ctypes.c_int
         L.psf_decode_step.argtypes = [dp, vp, vp, vp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp, vp]
+        L.psf_decode_prefill_workspace_bytes.restype = ctypes.c_size_t
+        L.psf_decode_prefill_workspace_bytes.argtypes = [dp, ctypes.c_int32]
+        L.psf_decode_prefill.restype = ctypes.c_int
+        L.psf_decode_prefill.argtypes = [dp, vp, vp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
         L.psf_stage_name.restype = ctypes.c_char_p
         L.psf_stage_name.argtypes = [ctypes.c_int, ctypes.c_int32]
         L.psf_status_string.restype = ctypes.c_char_p
@@ -392,6 +396,23 @@ def decode_new_state(desc, device="cuda", stream=None):
     if st != PSF_OK:
         raise PsfError(st, "psf_decode_reset")
     return state
+
+
+def psf_decode_prefill(desc, K, V, G, state, stream=None):
+    """State after the prompt K, V ([batch, heads, n_prompt, d | dv]); next: psf_decode_step at pos = n_prompt."""
+    B, H, d, dv = desc.batch, desc.heads, desc.d, desc.dv
+    n_prompt = int(K.shape[2])
+    need = lib().psf_decode_prefill_workspace_bytes(ctypes.byref(desc), n_prompt)
+    ws = torch.empty(max(need, 1), dtype=torch.uint8, device=K.device)
+    gs = _g_shape(desc)
+    st = lib().psf_decode_prefill(
+        ctypes.byref(desc), _dev_ptr(K, desc, (B, H, n_prompt, d), "K"), _dev_ptr(V, desc, (B, H, n_prompt, dv), "V"),
+        _dev_ptr(G, desc, gs, "G") if gs else None, n_prompt, ctypes.c_void_p(state.data_ptr()),
+        ctypes.c_size_t(state.numel()), ctypes.c_void_p(ws.data_ptr()) if need else None, ctypes.c_size_t(need),
+        _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_decode_prefill")
+    return ws      # alive until the caller has synchronised
 
 
 def psf_decode_step(desc, q, k, v, G, pos, state, o=None, stream=None):

@@ -392,6 +392,29 @@ psf_status psf_decode_step(const psf_desc *desc, const void *q, const void *k, c
     return decode_step(pb, q, k, v, G, pos, state, o, (hipStream_t)hip_stream);
 }
 
+size_t psf_decode_prefill_workspace_bytes(const psf_desc *desc, int32_t n_prompt)
+{
+    Problem pb;
+    if (make_problem(desc, &pb) != PSF_OK || !decode_supported(pb) || n_prompt < 0 || n_prompt > pb.n) return 0;
+    return decode_prefill_workspace_bytes(pb, n_prompt);
+}
+
+psf_status psf_decode_prefill(const psf_desc *desc, const void *K, const void *V, const void *G,
+                              int32_t n_prompt, void *state, size_t state_bytes, void *workspace,
+                              size_t workspace_bytes, void *hip_stream)
+{
+    Problem pb;
+    psf_status st = decode_check(desc, &pb, state, state_bytes);
+    if (st != PSF_OK) return st;
+    if (n_prompt < 0 || n_prompt > pb.n) return PSF_ERR_SHAPE;
+    if (n_prompt > 0 && (!K || !V)) return PSF_ERR_NULL;
+    if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
+    const size_t need = decode_prefill_workspace_bytes(pb, n_prompt);
+    if (need > 0 && !workspace) return PSF_ERR_NULL;
+    if (workspace_bytes < need || (need > 0 && ((uintptr_t)workspace & 255u) != 0)) return PSF_ERR_WORKSPACE;
+    return decode_prefill(pb, K, V, G, n_prompt, state, workspace, (hipStream_t)hip_stream);
+}
+
 const char *psf_stage_name(int path, int32_t stage)
 {
     static const char *bwd[] = {"sketches", "forward_rows", "reverse_states", "query_side",

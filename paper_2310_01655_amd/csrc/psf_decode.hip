@@ -822,6 +822,79 @@ __global__ __launch_bounds__(kThreads, 2) void dec_fold_mfma_kernel(float *__res
     }
 }
 
+// Prompt tokens pos0 + j (j < count) of every unit go into cache slots j: keys and values as
+// they are, m(k) from Algorithm 1 (two tokens at a time share the matrices) or, HAVE_M, from
+// the rows M_all [units][n_prompt][mcols] computed beforehand (learned sketches).
+constexpr int kPrefillTokens = 8;
+template <typename T, bool HAVE_M>
+__global__ __launch_bounds__(kThreads) void dec_prefill_kernel(const T *__restrict__ K, const T *__restrict__ V,
+                                                               const float *__restrict__ M_all,
+                                                               float *__restrict__ state, DecodeLayout L, int d,
+                                                               int dv, int p, int mcols, int n_prompt, int pos0,
+                                                               int count, DecSketchArgs sk)
+{
+    static_assert(kThreads == kSketchThreads, "sketch_rows_lds assumes this workgroup size");
+    __shared__ float xs[2][PSF_MAX_DIM];
+    __shared__ SketchScratchN<HAVE_M ? 1 : 2> scratch;
+    const int u = blockIdx.y, tid = threadIdx.x;
+    float *su = state + (size_t)u * L.per_unit;
+    T *ckeys = (T *)(su + L.ck), *cvals = (T *)(su + L.cv);
+    const T *g_set = (const T *)sk.G + (sk.per_head ? (size_t)(u % sk.heads) * sk.g_len : 0);
+    // kPrefillTokens tokens per workgroup, two at a time (a workgroup per pair would spend most
+    // of its time starting up)
+    for (int j0 = kPrefillTokens * blockIdx.x; j0 < min(count, kPrefillTokens * ((int)blockIdx.x + 1)); j0 += 2) {
+        const int nrow = min(2, count - j0);
+        for (int i = 0; i < nrow; ++i) {
+            const size_t row = (size_t)u * n_prompt + pos0 + j0 + i;
+            for (int e = tid; e < d; e += kThreads) ckeys[(size_t)(j0 + i) * d + e] = K[row * d + e];
+            for (int c = tid; c < dv; c += kThreads) cvals[(size_t)(j0 + i) * dv + c] = V[row * dv + c];
+            if (HAVE_M)
+                for (int e = tid; e < mcols; e += kThreads)
+                    su[L.cm + (size_t)(j0 + i) * mcols + e] = M_all[row * mcols + e];
+        }
+        if constexpr (!HAVE_M) {
+            __syncthreads();                               // the previous pair's results have been read
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+                if (tid < d) xs[i][tid] = i < nrow ? load_f(K, ((size_t)u * n_prompt + pos0 + j0 + i) * d + tid) : 0.f;
+            __syncthreads();
+            const float *const rows[2] = {xs[0], xs[1]};
+            const float *fin[2];
+            sketch_rows_lds<T, 2>(rows, g_set, d, sk.r, p, scratch, fin);
+            for (int i = 0; i < nrow; ++i)
+                if (tid < mcols) su[L.cm + (size_t)(j0 + i) * mcols + tid] = fin[i][tid];
+        }
+    }
+}
+
+// Folds the b tokens in the block cache into the state (the block is complete).
+template <typename T>
+psf_status launch_fold(const Problem &pb, const DecodeLayout &L, float *state, hipStream_t s)
+{
+    const long long Fs = tri_count(pb.mcols);
+    const dim3 fgrid((unsigned)((Fs + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
+    if (pb.bf16 && pb.mcols % 32 == 0 && pb.mcols <= kFoldMfmaMaxM && pb.dv % 32 == 0 && pb.dv <= kFoldMfmaMaxDv) {
+        // one 32 x 32 tile per wave and eight sketch rows per workgroup, or two and four
+        const unsigned na = (pb.mcols / 32) * (pb.dv / 32) <= 4 ? 8 : 4;
+        const dim3 mgrid((unsigned)pb.mcols / na, (unsigned)pb.units);
+#define PSF_FOLD(MC_, DV_)                                                                                       \
+    if (pb.mcols == MC_ && pb.dv == DV_)                                                                          \
+    hipLaunchKernelGGL((dec_fold_mfma_kernel<MC_, DV_>), mgrid, dim3(kThreads), 0, s, state, L, pb.b)
+        PSF_FOLD(32, 32); PSF_FOLD(32, 64); PSF_FOLD(32, 96); PSF_FOLD(32, 128);
+        PSF_FOLD(64, 32); PSF_FOLD(64, 64); PSF_FOLD(64, 96); PSF_FOLD(64, 128);
+#undef PSF_FOLD
+    } else if (pb.dv <= 32)
+        hipLaunchKernelGGL((dec_fold_kernel<T, 8>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
+    else if (pb.dv <= 64)
+        hipLaunchKernelGGL((dec_fold_kernel<T, 16>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
+    else if (pb.dv <= 128)
+        hipLaunchKernelGGL((dec_fold_kernel<T, 32>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
+    else
+        hipLaunchKernelGGL((dec_fold_kernel<T, 64>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
+    PSF_LAUNCH_CHECK();
+    return PSF_OK;
+}
+
 template <typename T>
 psf_status step_launch(const Problem &pb, const void *q, const void *k, const void *v, const void *G, int pos,
                        float *state, void *o, hipStream_t s)
@@ -872,28 +945,7 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
                            pb.d, pb.dv, pb.p, pb.mcols, slot, le);
         PSF_LAUNCH_CHECK();
     }
-    if (slot == pb.b - 1) {                               // the block is complete: fold it into Z
-        const dim3 fgrid((unsigned)((Fs + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
-        if (pb.bf16 && pb.mcols % 32 == 0 && pb.mcols <= kFoldMfmaMaxM && pb.dv % 32 == 0 && pb.dv <= kFoldMfmaMaxDv) {
-            // one 32 x 32 tile per wave and eight sketch rows per workgroup, or two and four
-            const unsigned na = (pb.mcols / 32) * (pb.dv / 32) <= 4 ? 8 : 4;
-            const dim3 mgrid((unsigned)pb.mcols / na, (unsigned)pb.units);
-#define PSF_FOLD(MC_, DV_)                                                                                       \
-    if (pb.mcols == MC_ && pb.dv == DV_)                                                                          \
-    hipLaunchKernelGGL((dec_fold_mfma_kernel<MC_, DV_>), mgrid, dim3(kThreads), 0, s, state, L, pb.b)
-            PSF_FOLD(32, 32); PSF_FOLD(32, 64); PSF_FOLD(32, 96); PSF_FOLD(32, 128);
-            PSF_FOLD(64, 32); PSF_FOLD(64, 64); PSF_FOLD(64, 96); PSF_FOLD(64, 128);
-#undef PSF_FOLD
-        } else if (pb.dv <= 32)
-            hipLaunchKernelGGL((dec_fold_kernel<T, 8>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
-        else if (pb.dv <= 64)
-            hipLaunchKernelGGL((dec_fold_kernel<T, 16>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
-        else if (pb.dv <= 128)
-            hipLaunchKernelGGL((dec_fold_kernel<T, 32>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
-        else
-            hipLaunchKernelGGL((dec_fold_kernel<T, 64>), fgrid, dim3(kThreads), 0, s, state, L, pb.dv, pb.b, pb.mcols, Fs);
-        PSF_LAUNCH_CHECK();
-    }
+    if (slot == pb.b - 1) return launch_fold<T>(pb, L, state, s);   // the block is complete: fold it into Z
     return PSF_OK;
 }
 
@@ -909,6 +961,53 @@ psf_status decode_reset(const Problem &pb, void *state, hipStream_t s)
     hipLaunchKernelGGL(dec_zero_kernel, dim3(2048), dim3(kThreads), 0, s, (float *)state, count);
     PSF_LAUNCH_CHECK();
     return PSF_OK;
+}
+
+size_t decode_prefill_workspace_bytes(const Problem &pb, int n_prompt)
+{
+    // learned sketches: m(k) of every prompt row, from the general sketch kernel
+    return pb.learned && pb.p > 2 ? (size_t)pb.units * (size_t)n_prompt * pb.mcols * sizeof(float) : 0;
+}
+
+template <typename T>
+static psf_status prefill_launch(const Problem &pb, const void *K, const void *V, const void *G, int n_prompt,
+                                 float *state, void *ws, hipStream_t s)
+{
+    const DecodeLayout L = decode_layout(pb);
+    psf_status st = decode_reset(pb, state, s);
+    if (st != PSF_OK) return st;
+    const bool have_m = decode_prefill_workspace_bytes(pb, n_prompt) > 0;
+    if (have_m && n_prompt > 0) {
+        Problem all = pb;
+        all.n = n_prompt;
+        st = general_sketch_f32(all, K, G, (float *)ws, s);
+        if (st != PSF_OK) return st;
+    }
+    const DecSketchArgs ska{G, pb.g_len, pb.heads, pb.per_head ? 1 : 0, pb.r};
+    for (int pos0 = 0; pos0 < n_prompt; pos0 += pb.b) {
+        const int count = n_prompt - pos0 < pb.b ? n_prompt - pos0 : pb.b;
+        const dim3 grid((unsigned)((count + kPrefillTokens - 1) / kPrefillTokens), (unsigned)pb.units);
+        if (have_m)
+            hipLaunchKernelGGL((dec_prefill_kernel<T, true>), grid, dim3(kThreads), 0, s, (const T *)K, (const T *)V,
+                               (const float *)ws, state, L, pb.d, pb.dv, pb.p, pb.mcols, n_prompt, pos0, count, ska);
+        else
+            hipLaunchKernelGGL((dec_prefill_kernel<T, false>), grid, dim3(kThreads), 0, s, (const T *)K, (const T *)V,
+                               (const float *)nullptr, state, L, pb.d, pb.dv, pb.p, pb.mcols, n_prompt, pos0, count,
+                               ska);
+        PSF_LAUNCH_CHECK();
+        if (count == pb.b) {
+            st = launch_fold<T>(pb, L, state, s);
+            if (st != PSF_OK) return st;
+        }
+    }
+    return PSF_OK;
+}
+
+psf_status decode_prefill(const Problem &pb, const void *K, const void *V, const void *G, int n_prompt, void *state,
+                          void *ws, hipStream_t s)
+{
+    return pb.bf16 ? prefill_launch<bf16_t>(pb, K, V, G, n_prompt, (float *)state, ws, s)
+                   : prefill_launch<float>(pb, K, V, G, n_prompt, (float *)state, ws, s);
 }
 
 psf_status decode_step(const Problem &pb, const void *q, const void *k, const void *v, const void *G, int pos,

@@ -78,6 +78,11 @@ size_t decode_state_bytes(const Problem &pb);
 psf_status decode_reset(const Problem &pb, void *state, hipStream_t s);
 psf_status decode_step(const Problem &pb, const void *q, const void *k, const void *v, const void *G,
                        int pos, void *state, void *o, hipStream_t s);
+// State after the first n_prompt tokens (K, V: [units][n_prompt][d | dv]), as if they had been fed
+// one by one; ws: decode_prefill_workspace_bytes.
+size_t decode_prefill_workspace_bytes(const Problem &pb, int n_prompt);
+psf_status decode_prefill(const Problem &pb, const void *K, const void *V, const void *G, int n_prompt,
+                          void *state, void *ws, hipStream_t s);
 
 // bf16 MFMA path.
 size_t mfma_workspace_bytes(const Problem &pb);

@@ -175,6 +175,25 @@ def test_decode_entry_points_validate_on_the_host():
     exact = psf.make_desc(1, 1, 64, 8, 4, 1, 8, "f32", feat=psf.FEAT_EXACT)
     assert psf.decode_state_bytes(exact) == 0
     assert L.psf_decode_step(ctypes.byref(exact), *args, 0, one, 1 << 40, one, None) == 3
+    # hand-over from a prompt: no workspace for the sketches of Algorithm 1, the fp32 sketches of
+    # every prompt key for learned ones; every failure below is found before any launch
+    assert L.psf_decode_prefill_workspace_bytes(ref, 1000) == 0
+    assert L.psf_decode_prefill_workspace_bytes(ref, 4097) == 0
+    assert L.psf_decode_prefill(ref, one, one, one, -1, one, need, None, 0, None) == 2
+    assert L.psf_decode_prefill(ref, one, one, one, 4097, one, need, None, 0, None) == 2
+    assert L.psf_decode_prefill(ref, None, one, one, 5, one, need, None, 0, None) == 1
+    assert L.psf_decode_prefill(ref, one, None, one, 5, one, need, None, 0, None) == 1
+    assert L.psf_decode_prefill(ref, one, one, None, 5, one, need, None, 0, None) == 1
+    assert L.psf_decode_prefill(ref, one, one, one, 5, None, need, None, 0, None) == 1
+    assert L.psf_decode_prefill(ref, one, one, one, 5, one, need - 1, None, 0, None) == 4
+    lrn = psf.make_desc(2, 3, 4096, 64, 4, 32, 256, "bf16", learned=True)
+    lref, lneed = ctypes.byref(lrn), psf.decode_state_bytes(lrn)
+    want_ws = 6 * 1000 * 32 * 4
+    assert L.psf_decode_prefill_workspace_bytes(lref, 1000) == want_ws
+    assert L.psf_decode_prefill(lref, one, one, one, 1000, one, lneed, None, want_ws, None) == 1
+    assert L.psf_decode_prefill(lref, one, one, one, 1000, one, lneed, one, want_ws - 1, None) == 4
+    assert L.psf_decode_prefill(lref, one, one, one, 1000, one, lneed, ctypes.c_void_p(264), want_ws, None) == 4
+    assert L.psf_decode_prefill(ctypes.byref(exact), one, one, one, 5, one, 1 << 40, None, 0, None) == 3
 
 
 def test_status_strings_and_stage_names():

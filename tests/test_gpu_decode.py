@@ -81,6 +81,70 @@ def test_decode_many_units_large_sketch_keeps_slices_within_lds():
     decode_all(32, 12, 24, 16, 16, 4, 128, 8, "f32", per_head=False)
 
 
+def prefill_then_decode(batch, heads, n, n_prompt, d, dv, p, r, b, dtype, local=psf.LOCAL_EXACT, learned=False,
+                        per_head=True, seed=57):
+    """psf_decode_prefill on the first n_prompt tokens, then steps n_prompt .. n - 1: every
+    decoded row against the float64 oracle's row of the whole sequence."""
+    q, k, v = inputs.make_qkv(batch, heads, n, d, dv=dv, seed=seed, dtype=dtype)
+    if learned:
+        G = inputs.make_learned_params(heads, d, r, p, per_head=per_head, seed=3, dtype=dtype)
+    else:
+        G = inputs.make_sketch_matrices(heads, d, r, p, per_head=per_head, seed=0, dtype=dtype) if p > 2 else None
+    desc = psf.make_desc(batch, heads, n, d, p, r, b, dtype, dv=dv, local=local, per_head=per_head, learned=learned)
+    dev = torch.device("cuda:0")
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    Gd = G.to(dev) if G is not None else None
+    state = psf.decode_new_state(desc, dev)
+    state.fill_(0x7f)                                       # prefill must not rely on an earlier reset
+    ws = psf.psf_decode_prefill(desc, kd[:, :, :n_prompt].contiguous(), vd[:, :, :n_prompt].contiguous(), Gd, state)
+    out = torch.empty(batch, heads, n - n_prompt, dv, dtype=q.dtype, device=dev)
+    for pos in range(n_prompt, n):
+        o = psf.psf_decode_step(desc, qd[:, :, pos:pos + 1].contiguous(), kd[:, :, pos:pos + 1].contiguous(),
+                                vd[:, :, pos:pos + 1].contiguous(), Gd, pos, state)
+        out[:, :, pos - n_prompt] = o[:, :, 0]
+    torch.cuda.synchronize()
+    del ws
+    rows = list(range(n_prompt, n))
+    want = np.empty((batch, heads, len(rows), dv))
+    olocal = oracle.LOCAL_EXACT if local == psf.LOCAL_EXACT else oracle.LOCAL_SKETCH
+    for bi in range(batch):
+        for h in range(heads):
+            Gh = None if G is None else as_f64(G[h if G.shape[0] > 1 else 0])
+            want[bi, h] = oracle.attn_def(as_f64(q[bi, h]), as_f64(k[bi, h]), as_f64(v[bi, h]), Gh, p, r, b,
+                                          local=olocal, rows=rows, learned=learned)
+    res = assert_close(out.float().cpu().numpy(), want, dtype, "prefill %d of %d, b=%d" % (n_prompt, n, b))
+    print("prefill", (n, n_prompt, d, dv, p, r, b, dtype, learned), res)
+
+
+@pytest.mark.parametrize("n,n_prompt,b", [
+    (96, 0, 32),        # empty prompt: the same as a reset
+    (96, 20, 32),       # inside the first block: cache only
+    (96, 64, 32),       # exactly two blocks: two folds, empty cache
+    (96, 75, 32),       # two folds and a tail in the cache
+    (40, 39, 8),        # almost everything, odd tail
+])
+def test_decode_prefill_then_steps_fp32(n, n_prompt, b):
+    prefill_then_decode(1, 2, n, n_prompt, 24, 40, 4, 12, b, "f32")
+
+
+@pytest.mark.parametrize("p,local", [(2, psf.LOCAL_EXACT), (8, psf.LOCAL_EXACT), (4, psf.LOCAL_SKETCH)])
+def test_decode_prefill_other_degrees_and_in_block_rule(p, local):
+    prefill_then_decode(1, 2, 64, 37, 16, 16, p, 8, 16, "f32", local=local)
+
+
+def test_decode_prefill_bf16_mfma_fold_many_units():
+    # 768 units (the step kernel's one-workgroup mode), blocks folded by the MFMA kernel
+    prefill_then_decode(64, 12, 64, 50, 64, 64, 4, 32, 16, "bf16", per_head=False)
+
+
+def test_decode_prefill_headline_unit_shape_bf16():
+    prefill_then_decode(1, 3, 768, 600, 64, 64, 4, 64, 256, "bf16")
+
+
+def test_decode_prefill_learned_sketches():
+    prefill_then_decode(1, 2, 48, 29, 16, 16, 4, 8, 16, "f32", learned=True)
+
+
 def test_decode_equals_the_forward_entry_point():
     batch, heads, n, d, p, r, b = 1, 2, 128, 32, 4, 16, 32
     out = decode_all(batch, heads, n, d, d, p, r, b, "f32", seed=53)
