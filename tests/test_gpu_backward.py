@@ -192,3 +192,23 @@ def test_saved_forward_is_refused_where_the_general_kernels_run():
     G = inputs.make_sketch_matrices(1, 64, 16, 4, seed=0, dtype="f32")
     with pytest.raises(psf.PsfError):
         psf.psf_causal_attn_fwd_save(desc, q.cuda(), k.cuda(), v.cuda(), G.cuda())
+
+
+@pytest.mark.parametrize("dtype,d,r,b,n", [("f32", 16, 8, 16, 64), ("bf16", 64, 64, 256, 512)])
+def test_autograd_function_matches_the_oracle_gradient(dtype, d, r, b, n):
+    # torch.autograd glue over the two entry points (general fp32 path; MFMA path with the saved
+    # forward state): loss = <O, W> with a fixed W, gradients against the float64 oracle
+    from paper_2310_01655_amd.autograd import causal_polysketch_attention
+    batch, heads, p = 1, 2, 4
+    q, k, v = inputs.make_qkv(batch, heads, n, d, seed=61, dtype=dtype)
+    G = inputs.make_sketch_matrices(heads, d, r, p, per_head=True, seed=0, dtype=dtype)
+    W = inputs.make_dout(batch, heads, n, d, seed=62, dtype=dtype)
+    qd, kd, vd = (t.cuda().requires_grad_(True) for t in (q, k, v))
+    O = causal_polysketch_attention(qd, kd, vd, G.cuda(), p, r, b, per_head=True)
+    (O.float() * W.cuda().float()).sum().backward()
+    torch.cuda.synchronize()
+    for h in range(heads):
+        dq, dk, dvv = oracle.attn_bwd(as_f64(q[0, h]), as_f64(k[0, h]), as_f64(v[0, h]), as_f64(G[h]),
+                                      as_f64(W[0, h]), p, r, b)
+        for name, got, want in (("dQ", qd.grad, dq), ("dK", kd.grad, dk), ("dV", vd.grad, dvv)):
+            assert_close_scaled(got[0, h].float().cpu().numpy(), want, dtype, "autograd %s head %d" % (name, h))
