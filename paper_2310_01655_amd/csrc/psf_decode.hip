@@ -682,47 +682,52 @@ __global__ __launch_bounds__(kThreads) void dec_fold_kernel(float *__restrict__ 
 
 // The same fold on MFMA for bf16 storage (phi'(k) and v as bf16 operands, fp32 accumulation, as
 // the forward state kernel does): S[a, b'][c] += w sum_j (m_j[a] m_j[b']) v_j[c] for b' >= a.
-// Workgroup = (NA consecutive sketch rows a, unit); wave w owns the 32 x 32 tiles w, w + 4, ...
-// (SLOTS of them) of each row's [mcols][dv] block; tiles whose 32 columns b' all lie below the
-// group's first row are skipped.  64 tokens at a time are staged transposed
-// ([column][token]) so that a lane's eight tokens of one column are neighbours; the fragments of
-// m_j[b'] and of v are shared by the NA rows.
+// Workgroup = (NA consecutive sketch rows a, unit).  An item is (row a, 32-wide range of b'):
+// the fragment m_j[a] m_j[b'] generated for it feeds one MFMA per 32-wide tile of value columns.
+// Ranges whose columns b' all lie below the group's first row are skipped; the remaining items
+// are dealt evenly to the four waves, a wave's items sharing one range (and with it the
+// fragments of m_j[b'] and of v).  64 tokens at a time are staged transposed ([column][token])
+// so that a lane's eight tokens of one column are neighbours.
 typedef __bf16 dec_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float dec_f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kFoldMfmaTok = 64, kFoldMfmaMaxM = 64, kFoldMfmaMaxDv = 128;
 
 template <int MC, int DV>
+struct FoldShape {
+    static constexpr int NB = MC / 32, TC = DV / 32;
+    static constexpr int IPW = 8 / TC < 4 ? 8 / TC : 4;      // items per wave, at most (accumulators: IPW * TC tiles)
+    static constexpr int NA = 4 * IPW / NB;                  // sketch rows per workgroup
+};
+
+template <int MC, int DV>
 __global__ __launch_bounds__(kThreads, 2) void dec_fold_mfma_kernel(float *__restrict__ state, DecodeLayout L, int b)
 {
     constexpr int mcols = MC, dv = DV;
-    constexpr int SLOTS = (MC / 32) * (DV / 32) <= 4 ? 1 : 2;
+    constexpr int NB = FoldShape<MC, DV>::NB, TC = FoldShape<MC, DV>::TC, IPW = FoldShape<MC, DV>::IPW;
+    constexpr int NA = FoldShape<MC, DV>::NA;
     // rows of 64 tokens: pitches of 68 floats / 72 bf16 keep every 16-byte read aligned and spread
     // the 16 lanes of a read phase over all banks
     constexpr int TOK = kFoldMfmaTok, PITCH = TOK + 4, PITCHV = TOK + 8;
-    constexpr int NA = 8 / SLOTS;
     __shared__ __attribute__((aligned(16))) float mts[MC][PITCH];
     __shared__ __attribute__((aligned(16))) bf16_t vts[DV][PITCHV];
-    const int a0 = blockIdx.x * NA, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int a0 = blockIdx.x * NA, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int x = lane & 31, h = lane >> 5;
     float *su = state + (size_t)u * L.per_unit;
-    constexpr int tiles_c = dv / 32, ntiles = (mcols / 32) * tiles_c;
-    // Tiles whose columns b' all lie below a0 are not needed.  One tile per wave: when at most
-    // half of them are left, two waves share a tile and split its NA rows.
-    const int first_tile = (a0 / 32) * tiles_c, nact = ntiles - first_tile;
-    const bool split = SLOTS == 1 && 2 * nact <= 4 && NA % 2 == 0;
-    const int ai_lo = split ? (wave / nact) % 2 * (NA / 2) : 0, ai_hi = split ? ai_lo + NA / 2 : NA;
-    // (split: waves 0 .. 2 nact - 1 work, the others have no tile)
-    auto tile_of = [&](int sl) { return split ? (wave < 2 * nact ? first_tile + wave % nact : ntiles) : wave + 4 * sl; };
-    dec_f32x16 acc[SLOTS][NA];
-    float drow[SLOTS][NA];
+    // this wave's items: rows a0 + row0 .. + rpw - 1 of range bt
+    const int bt_min = a0 / 32, nb_act = NB - bt_min;
+    const int rpw = NA * nb_act / 4;                         // 1 .. IPW
+    const int bt = bt_min + (wave * rpw) / NA, row0 = (wave * rpw) % NA;
+    dec_f32x16 acc[IPW][TC];
+    float drow[IPW];
 #pragma unroll
-    for (int sl = 0; sl < SLOTS; ++sl)
+    for (int k = 0; k < IPW; ++k) {
+        drow[k] = 0.f;
 #pragma unroll
-        for (int ai = 0; ai < NA; ++ai) {
-            drow[sl][ai] = 0.f;
+        for (int ct = 0; ct < TC; ++ct)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[sl][ai][v] = 0.f;
-        }
+            for (int v = 0; v < 16; ++v) acc[k][ct][v] = 0.f;
+    }
     // A chunk of 64 tokens goes global -> registers (16-byte / 8-byte pieces of a cached row) ->
     // LDS (transposed); the loads of the next chunk are in flight while this one is multiplied.
     constexpr int MP = TOK * MC / 4 / kThreads, VP = TOK * DV / 4 / kThreads;
@@ -763,62 +768,55 @@ __global__ __launch_bounds__(kThreads, 2) void dec_fold_mfma_kernel(float *__res
         __syncthreads();
         if (j0 + TOK < b) fetch(j0 + TOK);
 #pragma unroll
-        for (int sl = 0; sl < SLOTS; ++sl) {
-            const int ti = tile_of(sl);
-            if (ti >= ntiles) break;
-            const int bt = ti / tiles_c, ct = ti % tiles_c;
-            if (32 * bt + 31 < a0) continue;
+        for (int sstep = 0; sstep < TOK / 16; ++sstep) {
+            const int tok = 16 * sstep + 8 * h;
+            const float4 mb0 = *(const float4 *)&mts[32 * bt + x][tok], mb1 = *(const float4 *)&mts[32 * bt + x][tok + 4];
+            const float mb[8] = {mb0.x, mb0.y, mb0.z, mb0.w, mb1.x, mb1.y, mb1.z, mb1.w};
+            dec_bf16x8 fb[TC];
 #pragma unroll
-            for (int sstep = 0; sstep < TOK / 16; ++sstep) {
-                const int tok = 16 * sstep + 8 * h;
-                const float4 mb0 = *(const float4 *)&mts[32 * bt + x][tok], mb1 = *(const float4 *)&mts[32 * bt + x][tok + 4];
-                const float mb[8] = {mb0.x, mb0.y, mb0.z, mb0.w, mb1.x, mb1.y, mb1.z, mb1.w};
-                const dec_bf16x8 fb = *(const dec_bf16x8 *)&vts[32 * ct + x][tok];
+            for (int ct = 0; ct < TC; ++ct) fb[ct] = *(const dec_bf16x8 *)&vts[32 * ct + x][tok];
 #pragma unroll
-                for (int ai = 0; ai < NA; ++ai) {
-                    if (ai < ai_lo || ai >= ai_hi) continue;
-                    const float4 ma0 = *(const float4 *)&mts[a0 + ai][tok], ma1 = *(const float4 *)&mts[a0 + ai][tok + 4];
-                    const float ma[8] = {ma0.x, ma0.y, ma0.z, ma0.w, ma1.x, ma1.y, ma1.z, ma1.w};
-                    dec_bf16x8 fa;
+            for (int k = 0; k < IPW; ++k) {
+                if (k >= rpw) break;                        // wave-uniform
+                const int a = a0 + row0 + k;
+                const float4 ma0 = *(const float4 *)&mts[a][tok], ma1 = *(const float4 *)&mts[a][tok + 4];
+                const float ma[8] = {ma0.x, ma0.y, ma0.z, ma0.w, ma1.x, ma1.y, ma1.z, ma1.w};
+                dec_bf16x8 fa;
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const float pr = ma[e] * mb[e];
-                        fa[e] = (__bf16)pr;
-                        if (ct == 0) drow[sl][ai] += pr;
-                    }
-                    acc[sl][ai] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb, acc[sl][ai], 0, 0, 0);
+                for (int e = 0; e < 8; ++e) {
+                    const float pr = ma[e] * mb[e];
+                    fa[e] = (__bf16)pr;
+                    drow[k] += pr;
                 }
+#pragma unroll
+                for (int ct = 0; ct < TC; ++ct)
+                    acc[k][ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, fb[ct], acc[k][ct], 0, 0, 0);
             }
         }
     }
 #pragma unroll
-    for (int sl = 0; sl < SLOTS; ++sl) {
-        const int ti = tile_of(sl);
-        if (ti >= ntiles) break;
-        const int bt = ti / tiles_c, ct = ti % tiles_c;
-        if (32 * bt + 31 < a0) continue;
+    for (int k = 0; k < IPW; ++k) {
+        if (k >= rpw) break;
+        const int a = a0 + row0 + k;
+        const size_t rowbase = (size_t)tri_row(a, mcols);
 #pragma unroll
-        for (int ai = 0; ai < NA; ++ai) {
-            if (ai < ai_lo || ai >= ai_hi) continue;
-            const int a = a0 + ai;
-            const size_t row0 = (size_t)tri_row(a, mcols);
+        for (int ct = 0; ct < TC; ++ct) {
             // accumulator: lane x = column c, register v = row b' = 8 (v / 4) + 4 h + v % 4
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int bp = 32 * bt + 8 * (v / 4) + 4 * h + (v % 4);
                 if (bp >= a) {
-                    const size_t at = (row0 + bp - a) * dv + 32 * ct + x;
-                    const float znew = su[L.zv + at] + (bp > a ? 2.f : 1.f) * acc[sl][ai][v];
+                    const size_t at = (rowbase + bp - a) * dv + 32 * ct + x;
+                    const float znew = su[L.zv + at] + (bp > a ? 2.f : 1.f) * acc[k][ct][v];
                     su[L.zv + at] = znew;
                     if (L.shadow) ((bf16_t *)(su + L.zh))[at] = f32_to_bf16(znew);
                 }
             }
-            if (ct == 0) {                                 // the "ones" column: lanes x = row b', both halves
-                const float tot = drow[sl][ai] + __shfl_xor(drow[sl][ai], 32);
-                const int bp = 32 * bt + x;
-                if (h == 0 && bp >= a) su[L.zd + row0 + bp - a] += (bp > a ? 2.f : 1.f) * tot;
-            }
         }
+        // the "ones" column: lanes x = row b', both halves
+        const float tot = drow[k] + __shfl_xor(drow[k], 32);
+        const int bp = 32 * bt + x;
+        if (h == 0 && bp >= a) su[L.zd + rowbase + bp - a] += (bp > a ? 2.f : 1.f) * tot;
     }
 }
 
@@ -874,12 +872,10 @@ psf_status launch_fold(const Problem &pb, const DecodeLayout &L, float *state, h
     const long long Fs = tri_count(pb.mcols);
     const dim3 fgrid((unsigned)((Fs + kFoldFeat - 1) / kFoldFeat), (unsigned)pb.units);
     if (pb.bf16 && pb.mcols % 32 == 0 && pb.mcols <= kFoldMfmaMaxM && pb.dv % 32 == 0 && pb.dv <= kFoldMfmaMaxDv) {
-        // one 32 x 32 tile per wave and eight sketch rows per workgroup, or two and four
-        const unsigned na = (pb.mcols / 32) * (pb.dv / 32) <= 4 ? 8 : 4;
-        const dim3 mgrid((unsigned)pb.mcols / na, (unsigned)pb.units);
 #define PSF_FOLD(MC_, DV_)                                                                                       \
     if (pb.mcols == MC_ && pb.dv == DV_)                                                                          \
-    hipLaunchKernelGGL((dec_fold_mfma_kernel<MC_, DV_>), mgrid, dim3(kThreads), 0, s, state, L, pb.b)
+    hipLaunchKernelGGL((dec_fold_mfma_kernel<MC_, DV_>), dim3(MC_ / FoldShape<MC_, DV_>::NA, (unsigned)pb.units),  \
+                       dim3(kThreads), 0, s, state, L, pb.b)
         PSF_FOLD(32, 32); PSF_FOLD(32, 64); PSF_FOLD(32, 96); PSF_FOLD(32, 128);
         PSF_FOLD(64, 32); PSF_FOLD(64, 64); PSF_FOLD(64, 96); PSF_FOLD(64, 128);
 #undef PSF_FOLD

@@ -68,6 +68,13 @@ def test_decode_bf16_block_fold_on_mfma(n, d, r, b):
     decode_all(1, 2, n, d, d, 4, r, b, "bf16")
 
 
+@pytest.mark.parametrize("r,dv", [(64, 32), (64, 96), (64, 128), (32, 32), (32, 96)])
+def test_decode_bf16_block_fold_every_tile_shape(r, dv):
+    # the MFMA fold is instantiated per (sketch size, value width): one, two, three or four
+    # 32-wide value tiles per fragment, one or two 32-wide ranges of sketch columns
+    decode_all(1, 2, 192, 64, dv, 4, r, 64, "bf16", steps=150)
+
+
 @pytest.mark.parametrize("dtype,n,d,r,b", [("bf16", 48, 64, 32, 16), ("f32", 40, 16, 8, 8)])
 def test_decode_many_units_one_workgroup_per_unit(dtype, n, d, r, b):
     # 768 units: the state product of a unit is not split into slices, and the same workgroup
