@@ -710,7 +710,14 @@ __global__ __launch_bounds__(kThreads, 2) void dec_fold_mfma_kernel(float *__res
     constexpr int TOK = kFoldMfmaTok, PITCH = TOK + 4, PITCHV = TOK + 8;
     __shared__ __attribute__((aligned(16))) float mts[MC][PITCH];
     __shared__ __attribute__((aligned(16))) bf16_t vts[DV][PITCHV];
-    const int a0 = blockIdx.x * NA, u = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+    // The MC / NA workgroups of a unit all stream the unit's block cache.  Consecutive workgroup
+    // ids go to different XCDs, so give each XCD a contiguous range of (unit, row group) pairs:
+    // the groups of a unit then share one L2 and run at about the same time.
+    constexpr int GROUPS = MC / NA;
+    int wg = blockIdx.x;
+    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    const int u = wg / GROUPS, a0 = (wg % GROUPS) * NA;
+    const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int x = lane & 31, h = lane >> 5;
     float *su = state + (size_t)u * L.per_unit;
@@ -874,7 +881,7 @@ psf_status launch_fold(const Problem &pb, const DecodeLayout &L, float *state, h
     if (pb.bf16 && pb.mcols % 32 == 0 && pb.mcols <= kFoldMfmaMaxM && pb.dv % 32 == 0 && pb.dv <= kFoldMfmaMaxDv) {
 #define PSF_FOLD(MC_, DV_)                                                                                       \
     if (pb.mcols == MC_ && pb.dv == DV_)                                                                          \
-    hipLaunchKernelGGL((dec_fold_mfma_kernel<MC_, DV_>), dim3(MC_ / FoldShape<MC_, DV_>::NA, (unsigned)pb.units),  \
+    hipLaunchKernelGGL((dec_fold_mfma_kernel<MC_, DV_>), dim3((unsigned)(MC_ / FoldShape<MC_, DV_>::NA * pb.units)), \
                        dim3(kThreads), 0, s, state, L, pb.b)
         PSF_FOLD(32, 32); PSF_FOLD(32, 64); PSF_FOLD(32, 96); PSF_FOLD(32, 128);
         PSF_FOLD(64, 32); PSF_FOLD(64, 64); PSF_FOLD(64, 96); PSF_FOLD(64, 128);
