@@ -152,6 +152,22 @@ def test_decode_prefill_learned_sketches():
     prefill_then_decode(1, 2, 48, 29, 16, 16, 4, 8, 16, "f32", learned=True)
 
 
+@pytest.mark.parametrize("batch,heads,n,d,r,b,dtype,local,learned", [
+    # the step kernel's variants: storage type x bf16 copy of the state x in-block rule x
+    # (slices + finish kernel | one workgroup | one workgroup that also sketches)
+    (1, 2, 128, 64, 64, 32, "bf16", psf.LOCAL_SKETCH, False),      # slices, weights from the sketches, bf16 copy
+    (64, 12, 48, 64, 32, 16, "bf16", psf.LOCAL_SKETCH, False),     # 768 units: one launch, weights from the sketches
+    (1, 2, 128, 64, 64, 32, "f32", psf.LOCAL_SKETCH, False),       # slices, fp32 state only
+    (1, 2, 96, 64, 64, 32, "bf16", psf.LOCAL_EXACT, True),         # learned sketches, slices + finish kernel
+    (1, 2, 96, 64, 64, 32, "f32", psf.LOCAL_EXACT, True),
+    (32, 24, 32, 16, 8, 8, "f32", psf.LOCAL_EXACT, True),          # learned sketches, 768 units: finish inside
+    # (fp32 storage: with 4 x 10^5 bf16 outputs of magnitude up to 4 the largest rounding error
+    # alone reaches the 2e-2 bound)
+])
+def test_decode_step_kernel_variants(batch, heads, n, d, r, b, dtype, local, learned):
+    prefill_then_decode(batch, heads, n, 0, d, d, 4, r, b, dtype, local=local, learned=learned, per_head=False)
+
+
 def test_decode_equals_the_forward_entry_point():
     batch, heads, n, d, p, r, b = 1, 2, 128, 32, 4, 16, 32
     out = decode_all(batch, heads, n, d, d, p, r, b, "f32", seed=53)
