@@ -174,3 +174,35 @@ def test_in_block_sketch_rule_path_selection():
     assert psf.kernel_path(psf.make_desc(1, 2, 1024, 128, 4, 32, 256, "bf16", local=psf.LOCAL_SKETCH)) == 0
     assert psf.kernel_path(psf.make_desc(1, 2, 1024, 64, 4, 32, 256, "bf16", local=psf.LOCAL_SKETCH, learned=True)) == 0
     assert psf.kernel_path(psf.make_desc(1, 2, 1024, 128, 4, 64, 256, "bf16", local=psf.LOCAL_SKETCH)) == 1
+
+
+def test_forward_replays_from_a_captured_graph():
+    # The library only enqueues kernels on the caller's stream (no allocation, no memset, no
+    # synchronisation), so a call can be captured into a HIP graph: several replays, with eager
+    # work and synchronisations between them, must reproduce the eager result bit for bit.
+    cfg = mk(1, 2, 1024, 64, 4, 64, 256)
+    q, k, v, G = draw(cfg)
+    dev = torch.device("cuda:0")
+    qd, kd, vd, Gd = q.to(dev), k.to(dev), v.to(dev), G.to(dev)
+    desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"], "bf16",
+                         per_head=cfg["per_head"])
+    ws = psf.alloc_workspace(desc, dev)
+    eager = psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd, workspace=ws).clone()
+    torch.cuda.synchronize()
+    O = torch.empty_like(eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws)       # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        psf.psf_causal_attn_fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws)
+    for rep in range(4):
+        O.fill_(float("nan"))
+        ws.random_(0, 255)                                   # eager work that dirties everything the graph rewrites
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O, eager), "replay %d differs from the eager call" % rep
