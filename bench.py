@@ -2,8 +2,12 @@
 
 Default: the forward hot path; a step = one full pass (sketch of Q and K, block prefix states,
 fused output) over one synthetic batch.  `--pass bwd` times the backward entry point instead
-(a step = gradients with respect to Q, K, V, forward quantities recomputed inside).  Prints ONE
-JSON line ("Measurement").
+(a step = gradients with respect to Q, K, V, forward quantities recomputed inside);
+`--pass train` the forward that keeps its state plus the backward that uses it; `--pass decode`
+the token-by-token entry point at a serving shape.  Prints ONE JSON line: metric, value, unit,
+the step time, the workload, and two objects -- `roofline` (the dominant kernel's algorithmic
+flops or bytes over its HIP-event time against the MI355X peak) and `cpu_baseline` (the float64
+oracle timed on the host cores on a bounded sample of the same workload).
 """
 import argparse
 import json
@@ -415,7 +419,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (units = batch x heads would shard with "
-                 "no communication, see DESIGN.md); run with --gpus 1")
+                 "no communication); run with --gpus 1")
 
     import torch
     from paper_2310_01655_amd import binding as psf
