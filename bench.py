@@ -158,7 +158,8 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     dev = torch.device("cuda:0")
     dO = inputs.make_dout(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], seed=1000 + idx, dtype=cfg["dtype"])
     desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
-                         cfg["dtype"], per_head=cfg["per_head"])
+                         cfg["dtype"], per_head=cfg["per_head"],
+                         local=psf.LOCAL_SKETCH if args.local_sketch else psf.LOCAL_EXACT)
     qd, kd, vd, Gd, dOd = (x.to(dev) for x in (q, k, v, G, dO))
     ws = psf.alloc_bwd_workspace(desc, dev)
     stream = torch.cuda.current_stream()
@@ -189,6 +190,7 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if mfma else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "pass": "bwd", "batch": cfg["batch"], "heads": cfg["heads"],
                    "n": cfg["n"], "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
+                   "in_block": "sketch" if args.local_sketch else "exact",
                    "storage": cfg["dtype"], "kernel_path": "mfma_bf16" if mfma else "general_fp32"},
         "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
         "tflops": fl["total"] / (ms_per_step * 1e-3) / 1e12,
@@ -196,7 +198,7 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
                      "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
                      "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc}},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.local_sketch:   # the oracle driver used here: exact in-block weights
         out["cpu_baseline"] = cpu_baseline_bwd(cfg, q, k, v, G, dO)
     print(json.dumps(out))
 

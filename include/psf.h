@@ -183,8 +183,9 @@ psf_status psf_noncausal_attn_fwd_timed(const psf_desc *desc, const void *Q, con
  *   quantities are recomputed inside; nothing has to be kept from the forward call.
  * Supported: PSF_FEAT_SKETCH with either in-block rule, every p, r, d, dv, b and dtype the
  * descriptor check admits (fp32 arithmetic).  PSF_FEAT_EXACT returns PSF_ERR_UNSUPPORTED.
- * Kernels: bf16 storage with d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0, PSF_LOCAL_EXACT and
- * random sketches runs on MFMA (psf_bwd_kernel_path == 3; bf16 operands, fp32 accumulation, g and
+ * Kernels: bf16 storage with d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0, random sketches and
+ * PSF_LOCAL_EXACT (or PSF_LOCAL_SKETCH with r = 64) runs on MFMA (psf_bwd_kernel_path == 3;
+ * bf16 operands, fp32 accumulation, g and
  * the in-block weights rounded to bf16 like the forward pass rounds its weights); everything
  * else runs the general fp32 kernels (== 2).  -1: invalid descriptor or unsupported.
  * The _timed variant reports per-stage milliseconds like psf_causal_attn_fwd_timed, stage

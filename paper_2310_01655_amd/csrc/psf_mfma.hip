@@ -1780,9 +1780,19 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         constexpr bool LS_OK = (32 * TT * R * 2) % (16 * kWg) == 0;    // whole copies of a key tile of m(K) rows
         if (!noncausal && !pb.local_exact) {
             if constexpr (LS_OK) {
-                if (pb.learned || Den) return PSF_ERR_UNSUPPORTED;  // (not routed here: see select_path)
-                hipLaunchKernelGGL((k_out<R, D, P, TT, false, false, true>), dim3(grid), dim3(kWg), 0, s, w.MQ,
-                                   w.MKrm, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b, pb.t);
+                if (pb.learned) return PSF_ERR_UNSUPPORTED;         // (not routed here: see select_path)
+                const bf16_t *mk_rows = MK_rm ? MK_rm : w.MKrm;
+                if (Den) {
+                    // the backward pass's forward: only where the backward kernels exist
+                    if constexpr (D == 64 && R == 64 && P == 4)
+                        hipLaunchKernelGGL((k_out<R, D, P, TT, true, false, true>), dim3(grid), dim3(kWg), 0, s, w.MQ,
+                                           mk_rows, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b, pb.t);
+                    else
+                        return PSF_ERR_UNSUPPORTED;
+                } else {
+                    hipLaunchKernelGGL((k_out<R, D, P, TT, false, false, true>), dim3(grid), dim3(kWg), 0, s, w.MQ,
+                                       mk_rows, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b, pb.t);
+                }
             } else {
                 return PSF_ERR_UNSUPPORTED;
             }
@@ -1812,8 +1822,9 @@ size_t mfma_workspace_bytes(const Problem &pb) { return carve(pb, nullptr).total
 
 bool mfma_bwd_supported(const Problem &pb)
 {
+    // in-block weights from the sketches (Section 3.1): r = d only
     return pb.d == 64 && pb.dv == 64 && pb.p == 4 && (pb.r == 32 || pb.r == 64) && pb.b % 256 == 0 &&
-           !pb.learned && !pb.exact_feat && pb.local_exact;
+           !pb.learned && !pb.exact_feat && (pb.local_exact || pb.r == 64);
 }
 
 size_t mfma_bwd_workspace_bytes(const Problem &pb) { return carve_bwd(pb, nullptr).total; }

@@ -205,12 +205,12 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
 }
 
 // ---- through Algorithm 1 (p = 4), one 32-token tile of a wave --------------------------------
-// dx = dXacc + sqrt(1/r) [(dm * (x G2)) G1^T + (dm * (x G1)) G2^T].  lds: the transposed sketch
+// dx = dXacc (if ADD_BASE) + sqrt(1/r) [(dm * (x G2)) G1^T + (dm * (x G1)) G2^T].  lds: the transposed sketch
 // matrices as the forward sketch kernel stages them (for the recomputed projections); go: G1,
 // G2 as given, rows [d][r] padded to GP (for the transposed products, whose A fragments are read
 // in accumulator order).  dm: lane = token, register = sketch column, as the accumulators of
 // the cross-block kernel leave it.
-template <int D, int R>
+template <int D, int R, bool ADD_BASE = true>
 __device__ __forceinline__ void sketch_grad_tile(const SketchLds<D, R> &lds, const bf16_t *go,
                                                  const bf16_t *__restrict__ X, const f32x16 *dm,
                                                  const float *__restrict__ dXacc, bf16_t *__restrict__ dX,
@@ -257,9 +257,12 @@ __device__ __forceinline__ void sketch_grad_tile(const SketchLds<D, R> &lds, con
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
             const size_t off = row * D + 32 * dt + 8 * gq + 4 * h;
-            const f32x4 base = *(const f32x4 *)&dXacc[off];
-            const f32x4 q4 = {acc[4 * gq] + base[0], acc[4 * gq + 1] + base[1], acc[4 * gq + 2] + base[2],
-                              acc[4 * gq + 3] + base[3]};
+            f32x4 q4 = {acc[4 * gq], acc[4 * gq + 1], acc[4 * gq + 2], acc[4 * gq + 3]};
+            if constexpr (ADD_BASE) {
+                const f32x4 base = *(const f32x4 *)&dXacc[off];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) q4[j] += base[j];
+            }
             *(bf16x4 *)&dX[off] = cvt4(q4);
         }
     }
@@ -367,7 +370,10 @@ struct Cross {
 // coefficient 1.  Blocks without a cross-block term have dm = 0.  dm stays in registers and goes
 // straight through Algorithm 1 (sketch_grad_tile): dX = bf16(dXacc + J_m(x)^T dm), with dXacc the
 // in-block part, for the rows X (Q or K) of the workgroup.
-template <int R, int D, bool QSIDE, int TT>
+// LS (in-block rule of Section 3.1, R == D): the in-block weights are functions of the sketches
+// too, so dXacc holds the in-block part of dm ([rows][R] fp32), which joins dm before the sketch:
+// dX = bf16(J_m(x)^T (dm + dXacc)).
+template <int R, int D, bool QSIDE, int TT, bool LS = false>
 __global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M, const bf16_t *__restrict__ Vec,
                                                   const float *__restrict__ Cc, const bf16_t *__restrict__ ZT,
                                                   const bf16_t *__restrict__ Shi, const bf16_t *__restrict__ Slo,
@@ -445,9 +451,25 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M,
     const size_t goff = per_head ? (size_t)(u % heads) * g_len : 0;
     sketch_grad_stage<D, R>(lds, go, Gt + goff, G + goff);
     __syncthreads();
+    if constexpr (LS) {
+        static_assert(R == D, "the in-block kernels leave dm in the layout of a gradient row");
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int at = 0; at < AT; ++at)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    // register v of out[tt][at]: sketch column 32 at + 8 (v / 4) + 4 h + v % 4
+                    const f32x4 a4 = *(const f32x4 *)&dXacc[(urow + i0 + wave * 32 * TT + 32 * tt + x) * R + 32 * at +
+                                                            8 * gq + 4 * h];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) out[tt][at][4 * gq + j] += a4[j];
+                }
+    }
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt)
-        sketch_grad_tile<D, R>(lds, go, Xrows, out[tt], dXacc, dX, urow + i0 + wave * 32 * TT + 32 * tt + x, x, h);
+        sketch_grad_tile<D, R, !LS>(lds, go, Xrows, out[tt], dXacc, dX, urow + i0 + wave * 32 * TT + 32 * tt + x, x,
+                                    h);
 }
 
 // ---- dV: cross-block part = phi'(k_j)^T R_l (value columns) ----------------------------------
@@ -841,6 +863,10 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     MfmaWs f = carve(pb, w.fwd);
     const size_t rows = (size_t)pb.units * pb.n;
     const bf16_t *q = (const bf16_t *)Q, *k = (const bf16_t *)K, *v = (const bf16_t *)V;
+    // in-block rule of Section 3.1 (r = d = 64 only): the in-block kernels take the sketches
+    // m(Q), m(K) in place of Q, K with exponent 2 and leave the in-block part of dm
+    const bool ls = !pb.local_exact;
+    if (ls && R != D) return PSF_ERR_UNSUPPORTED;
     psf_status st;
     if (saved) {
         const MfmaSaved sv = carve_saved(pb, saved);
@@ -854,6 +880,7 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
         if (st != PSF_OK) return st;
     }
     if (tm) tm->mark();
+    const bf16_t *rq = ls ? f.MQ : q, *rk = ls ? w.MK : k;  // the rows the in-block weights are made of
     // g, c, layouts
     hipLaunchKernelGGL((k_bwd_prep<D>), dim3((unsigned)(rows / 32)), dim3(kWg), 0, s, (const bf16_t *)dO, w.O,
                        w.Den, w.G_rm, w.G8, w.G8r, w.Cc, pb.n, pb.b, pb.t);
@@ -861,18 +888,18 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     {
         const size_t octets = rows / 8;
         const unsigned grid = (unsigned)((octets * D + kWg - 1) / kWg);
-        hipLaunchKernelGGL((k_v_octets<D>), dim3(grid), dim3(kWg), 0, s, q, w.Q8, octets);
+        hipLaunchKernelGGL((k_v_octets<D>), dim3(grid), dim3(kWg), 0, s, rq, w.Q8, octets);
         PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_v_octets<D>), dim3(grid), dim3(kWg), 0, s, k, w.K8, octets);
+        hipLaunchKernelGGL((k_v_octets<D>), dim3(grid), dim3(kWg), 0, s, rk, w.K8, octets);
         PSF_LAUNCH_CHECK();
         const size_t pieces = rows * D / 8;
         const unsigned gridp = (unsigned)((pieces + kWg - 1) / kWg);
-        const bf16_t *src[4] = {q, k, v, w.G_rm};
+        const bf16_t *src[4] = {rq, rk, v, w.G_rm};
         bf16_t *dstf[4] = {w.QF, w.KF, w.VF, w.GF};
         for (int i = 0; i < 4; ++i) {
-            // the copy of g that only feeds dW = <g, v> + c carries the factor p of d(s^p) = p s^(p-1) ds
+            // the copy of g that only feeds dW = <g, v> + c carries the factor e of d(s^e) = e s^(e-1) ds
             hipLaunchKernelGGL(k_bwd_row_tiles, dim3(gridp), dim3(kWg), 0, s, src[i], dstf[i], pieces,
-                               i == 3 ? (float)P : 1.0f);
+                               i == 3 ? (ls ? 2.0f : (float)P) : 1.0f);
             PSF_LAUNCH_CHECK();
         }
     }
@@ -897,8 +924,12 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     // in-block parts
     {
         const unsigned grid = (unsigned)(rows / (32 * NWL));
-        hipLaunchKernelGGL((k_bwd_local_q<P, NWL>), dim3(grid), dim3(64 * NWL), 0, s, q, w.KF, w.VF, w.K8, w.G_rm, w.Cc,
-                           w.dQacc, pb.n, pb.b);
+        if (ls)
+            hipLaunchKernelGGL((k_bwd_local_q<2, NWL>), dim3(grid), dim3(64 * NWL), 0, s, rq, w.KF, w.VF, w.K8, w.G_rm,
+                               w.Cc, w.dQacc, pb.n, pb.b);
+        else
+            hipLaunchKernelGGL((k_bwd_local_q<P, NWL>), dim3(grid), dim3(64 * NWL), 0, s, q, w.KF, w.VF, w.K8, w.G_rm,
+                               w.Cc, w.dQacc, pb.n, pb.b);
         PSF_LAUNCH_CHECK();
     }
     {
@@ -906,8 +937,12 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
         const unsigned gridc = (unsigned)(rows / (128 * TT)), grid = (unsigned)(rows / (32 * NWL));
         hipLaunchKernelGGL((k_bwd_dvc<R, D, TT>), dim3(gridc), dim3(kWg), 0, s, w.MK, w.Rg, w.dVc, pb.n, pb.b, pb.t);
         PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_bwd_local_k<P, NWL>), dim3(grid), dim3(64 * NWL), 0, s, w.QF, k, v, w.Q8, w.GF, w.G8, w.Cc,
-                           w.dVc, w.dKacc, (bf16_t *)dV, pb.n, pb.b);
+        if (ls)
+            hipLaunchKernelGGL((k_bwd_local_k<2, NWL>), dim3(grid), dim3(64 * NWL), 0, s, w.QF, rk, v, w.Q8, w.GF, w.G8,
+                               w.Cc, w.dVc, w.dKacc, (bf16_t *)dV, pb.n, pb.b);
+        else
+            hipLaunchKernelGGL((k_bwd_local_k<P, NWL>), dim3(grid), dim3(64 * NWL), 0, s, w.QF, k, v, w.Q8, w.GF, w.G8,
+                               w.Cc, w.dVc, w.dKacc, (bf16_t *)dV, pb.n, pb.b);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
@@ -915,14 +950,28 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     {
         const unsigned grid = (unsigned)(rows / (128 * TT));
         const int ph = pb.per_head ? 1 : 0;
-        hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm, w.Cc, w.ZT, f.Shi,
-                           f.Slo, q, f.Gt, (const bf16_t *)G, w.dQacc, (bf16_t *)dQ, pb.n, pb.b, pb.t, pb.heads, ph,
-                           pb.g_len);
-        PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_bwd_dm<R, D, false, TT>), dim3(grid), dim3(kWg), 0, s, w.MK, v, w.Cc, w.RT, w.Rchi,
-                           w.Rclo, k, f.Gt, (const bf16_t *)G, w.dKacc, (bf16_t *)dK, pb.n, pb.b, pb.t, pb.heads, ph,
-                           pb.g_len);
-        PSF_LAUNCH_CHECK();
+        if constexpr (R == D) {
+            if (ls) {
+                hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT, true>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm, w.Cc,
+                                   w.ZT, f.Shi, f.Slo, q, f.Gt, (const bf16_t *)G, w.dQacc, (bf16_t *)dQ, pb.n, pb.b,
+                                   pb.t, pb.heads, ph, pb.g_len);
+                PSF_LAUNCH_CHECK();
+                hipLaunchKernelGGL((k_bwd_dm<R, D, false, TT, true>), dim3(grid), dim3(kWg), 0, s, w.MK, v, w.Cc, w.RT,
+                                   w.Rchi, w.Rclo, k, f.Gt, (const bf16_t *)G, w.dKacc, (bf16_t *)dK, pb.n, pb.b, pb.t,
+                                   pb.heads, ph, pb.g_len);
+                PSF_LAUNCH_CHECK();
+            }
+        }
+        if (!ls) {
+            hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm, w.Cc, w.ZT, f.Shi,
+                               f.Slo, q, f.Gt, (const bf16_t *)G, w.dQacc, (bf16_t *)dQ, pb.n, pb.b, pb.t, pb.heads, ph,
+                               pb.g_len);
+            PSF_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_bwd_dm<R, D, false, TT>), dim3(grid), dim3(kWg), 0, s, w.MK, v, w.Cc, w.RT, w.Rchi,
+                               w.Rclo, k, f.Gt, (const bf16_t *)G, w.dKacc, (bf16_t *)dK, pb.n, pb.b, pb.t, pb.heads, ph,
+                               pb.g_len);
+            PSF_LAUNCH_CHECK();
+        }
     }
     if (tm) tm->mark();
     return PSF_OK;

@@ -102,6 +102,17 @@ def test_backward_mfma_path_full_parity(heads, n, r, b, per_head):
     run_case(1, heads, n, 64, 64, 4, r, b, "bf16", per_head=per_head, seed=43)
 
 
+@pytest.mark.parametrize("heads,n,b,per_head", [(2, 1024, 256, True), (3, 1536, 512, False), (1, 512, 512, False)])
+def test_backward_mfma_path_in_block_weights_from_the_sketches(heads, n, b, per_head):
+    # Section 3.1's in-block rule on the MFMA kernels (r = d = 64): the in-block kernels work on
+    # m(Q), m(K) and their result joins dm before the sketch gradient; r = 32 stays on the
+    # general kernels
+    desc = psf.make_desc(1, heads, n, 64, 4, 64, b, "bf16", per_head=per_head, local=psf.LOCAL_SKETCH)
+    assert psf.bwd_kernel_path(desc) == 3
+    assert psf.bwd_kernel_path(psf.make_desc(1, heads, n, 64, 4, 32, b, "bf16", local=psf.LOCAL_SKETCH)) == 2
+    run_case(1, heads, n, 64, 64, 4, 64, b, "bf16", local=psf.LOCAL_SKETCH, per_head=per_head, seed=45)
+
+
 def test_backward_mfma_path_is_deterministic_and_matches_general_kernels():
     """The MFMA kernels against the general fp32 kernels of the same library on a shape both
     accept (b % 256 != 0 sends the same problem down the general path)."""
@@ -162,8 +173,8 @@ def test_backward_config3_full_size_sampled_rows_and_identities():
               assert_close_scaled(gv[tail0:], wV[tail0:], "bf16", "dV"))
 
 
-@pytest.mark.parametrize("r,b", [(64, 256), (32, 512)])
-def test_saved_forward_gives_the_same_output_and_gradients(r, b):
+@pytest.mark.parametrize("r,b,local", [(64, 256, psf.LOCAL_EXACT), (32, 512, psf.LOCAL_EXACT), (64, 256, psf.LOCAL_SKETCH)])
+def test_saved_forward_gives_the_same_output_and_gradients(r, b, local):
     """psf_causal_attn_fwd_save + psf_causal_attn_bwd_saved against the plain forward and the
     plain (recomputing) backward of the same library: identical bits, since the same kernels run
     on the same data; the plain calls are the ones checked against the oracle above."""
@@ -171,7 +182,7 @@ def test_saved_forward_gives_the_same_output_and_gradients(r, b):
     q, k, v = inputs.make_qkv(batch, heads, n, d, seed=53, dtype="bf16")
     dO = inputs.make_dout(batch, heads, n, d, seed=53, dtype="bf16")
     G = inputs.make_sketch_matrices(heads, d, r, p, per_head=True, seed=0, dtype="bf16")
-    desc = psf.make_desc(batch, heads, n, d, p, r, b, "bf16", per_head=True)
+    desc = psf.make_desc(batch, heads, n, d, p, r, b, "bf16", per_head=True, local=local)
     assert psf.bwd_kernel_path(desc) == 3 and psf.fwd_save_bytes(desc) > psf.workspace_bytes(desc)
     dev = torch.device("cuda:0")
     qd, kd, vd, Gd, dOd = (x.to(dev) for x in (q, k, v, G, dO))
