@@ -86,7 +86,8 @@ psf_status psf_check_desc(const psf_desc *desc);
 
 /* Which kernels the descriptor selects: 1 = bf16 MFMA path (FEAT_SKETCH, bf16, p in {4,8},
  * r in {32,64}, d = dv in {64,128}, b % 256 == 0; LOCAL_EXACT, or LOCAL_SKETCH with Gaussian
- * sketches unless d = 128 and r = 32), 0 = general fp32 path
+ * sketches unless d = 128 and r = 32; also p = 2 with d = dv = 64, where m(x) = x and r is
+ * ignored), 0 = general fp32 path
  * (everything else the descriptor check admits), -1 = invalid descriptor. */
 int psf_kernel_path(const psf_desc *desc);
 

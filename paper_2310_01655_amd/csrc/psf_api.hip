@@ -62,7 +62,9 @@ int select_path(const Problem &pb)
     // learned sketches included; the in-block rule of Section 3.1 (weights from the sketches) with
     // Gaussian sketches, except d = 128 with r = 32 (a key tile of m(K) rows is half a copy there)
     const bool local_ok = pb.local_exact || (!pb.learned && !(pb.d == 128 && pb.r == 32));
-    return (pb.bf16 && !pb.exact_feat && local_ok && shapes) ? 1 : 0;
+    // p = 2 (m(x) = x, the sketch size is d): d = dv = 64, either in-block rule (they coincide)
+    const bool base_case = pb.p == 2 && pb.d == 64 && pb.dv == 64 && pb.b % 256 == 0;
+    return (pb.bf16 && !pb.exact_feat && ((local_ok && shapes) || base_case)) ? 1 : 0;
 }
 
 psf_status StageTimer::begin(hipStream_t s)

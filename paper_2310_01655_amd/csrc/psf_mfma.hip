@@ -88,8 +88,8 @@ __device__ __forceinline__ float row_bcast(float v)
 
 __device__ __forceinline__ float pow_p(float x, int p)
 {
-    x *= x;                 // p is 4 or 8 here
-    x *= x;
+    x *= x;                 // p is 2, 4 or 8 here
+    if (p >= 4) x *= x;
     if (p == 8) x *= x;
     return x;
 }
@@ -1151,8 +1151,9 @@ __global__ __launch_bounds__(kWg) void k_m_to_bf16(const float *__restrict__ M, 
 
 // One workgroup per part of `tokens` consecutive tokens of one unit: m(K) rows -> token octets
 // [n/8][2][R][4] fp32, and the part's S = m^T m (R x R, fp32) for the denominator scan.
-template <int R>
-__global__ __launch_bounds__(kWg) void k_m_to_octets_and_partials(const float *__restrict__ M,
+// (MT: fp32 rows from the general sketch kernel, or bf16 rows that are the sketch already, p = 2.)
+template <int R, typename MT = float>
+__global__ __launch_bounds__(kWg) void k_m_to_octets_and_partials(const MT *__restrict__ M,
                                                                   float *__restrict__ MK8,
                                                                   float *__restrict__ Spart, int tokens)
 {
@@ -1167,18 +1168,19 @@ __global__ __launch_bounds__(kWg) void k_m_to_octets_and_partials(const float *_
         __syncthreads();
         for (int idx = tid; idx < TCH * R; idx += kWg) {
             const int tk = idx / R, c = idx % R;
-            const float v = M[(row0 + t0 + tk) * R + c];
+            const float v = load_f(M, (row0 + t0 + tk) * R + c);
             ms[tk][c] = v;
             const size_t tok = row0 + t0 + tk;            // octet layout: ((tok/8 * 2 + (tok%8)/4) * R + c) * 4 + tok%4
             MK8[((tok / 8 * 2 + (tok % 8) / 4) * R + c) * 4 + tok % 4] = v;
         }
         __syncthreads();
+        // entry e = q * kWg + tid of S: column c = tid % R for every q, row a = q * (kWg / R) + tid / R
+        // (the same row for the whole wave: a broadcast read)
+        const int c = tid % R, a0 = tid / R;
+        for (int tk = 0; tk < TCH; ++tk) {
+            const float mc = ms[tk][c];
 #pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            const int e = q * kWg + tid, a = e / R, c = e % R;
-            float sacc = 0.f;
-            for (int tk = 0; tk < TCH; ++tk) sacc += ms[tk][a] * ms[tk][c];
-            acc[q] += sacc;
+            for (int q = 0; q < PER; ++q) acc[q] += ms[tk][q * (kWg / R) + a0] * mc;
         }
     }
     float *out = Spart + (size_t)blockIdx.x * R * R;
@@ -1629,7 +1631,7 @@ MfmaWs carve(const Problem &pb, void *ws)
     char *base = (char *)ws;
     auto take = [&](size_t bytes) { char *p = base + off; off += align_up(bytes, 256); return p; };
     w.Gt = (bf16_t *)take(pb.learned ? 0 : sets * pb.g_len * 2);
-    w.MQ = (bf16_t *)take(rows * R * 2);
+    w.MQ = (bf16_t *)take(pb.p == 2 ? 0 : rows * R * 2);     // p = 2: m(Q) = Q itself
     w.MK8 = (float *)take(rows * R * 4);
     w.V8 = (bf16_t *)take(rows * D * 2);
     w.Zg = (bf16_t *)take((size_t)pb.units * tb * R * R * D * 2);
@@ -1745,6 +1747,15 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
                                dim3(kWg), 0, s, w.M32, w.MK8, w.Spart, part_tokens(pb));
             PSF_LAUNCH_CHECK();
         }
+    } else if constexpr (P == 2) {
+        // base case of Algorithm 1: m(x) = x (r = d).  The query rows serve as m(Q) as they are;
+        // the key rows are put into the state kernel's layout (and their m^T m partials formed).
+        static_assert(R == D, "p = 2: the sketch is the row itself");
+        const size_t rows = (size_t)pb.units * pb.n;
+        w.MQ = (bf16_t *)Q;
+        hipLaunchKernelGGL((k_m_to_octets_and_partials<R, bf16_t>), dim3((unsigned)(rows / part_tokens(pb))),
+                           dim3(kWg), 0, s, (const bf16_t *)K, w.MK8, w.Spart, part_tokens(pb));
+        PSF_LAUNCH_CHECK();
     } else {
         st = launch_transpose_g(pb, G, w.Gt, s);
         if (st != PSF_OK) return st;
@@ -1818,7 +1829,19 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
 
 }  // namespace
 
-size_t mfma_workspace_bytes(const Problem &pb) { return carve(pb, nullptr).total; }
+// p = 2: m(x) = x, so the sketch size is d whatever the descriptor says, and the two in-block
+// rules coincide (<m(q), m(k)>^2 = <q, k>^2).
+static Problem base_case_problem(const Problem &pb0)
+{
+    Problem pb = pb0;
+    if (pb.p == 2) {
+        pb.r = pb.mcols;
+        pb.local_exact = true;
+    }
+    return pb;
+}
+
+size_t mfma_workspace_bytes(const Problem &pb) { return carve(base_case_problem(pb), nullptr).total; }
 
 bool mfma_bwd_supported(const Problem &pb)
 {
@@ -1849,6 +1872,7 @@ psf_status mfma_attn_fwd_save(const Problem &pb, const void *Q, const void *K, c
 
 #define PSF_DISPATCH(CALL)                                                   \
     do {                                                                     \
+        if (pb.d == 64 && pb.p == 2) return CALL(64, 64, 2);                 \
         if (pb.d == 64 && pb.r == 64 && pb.p == 4) return CALL(64, 64, 4);   \
         if (pb.d == 64 && pb.r == 32 && pb.p == 4) return CALL(64, 32, 4);   \
         if (pb.d == 64 && pb.r == 64 && pb.p == 8) return CALL(64, 64, 8);   \
@@ -1860,9 +1884,10 @@ psf_status mfma_attn_fwd_save(const Problem &pb, const void *Q, const void *K, c
         return PSF_ERR_UNSUPPORTED;                                          \
     } while (0)
 
-psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
+psf_status mfma_attn(const Problem &pb0, const void *Q, const void *K, const void *V, const void *G,
                      void *O, void *ws, hipStream_t s, StageTimer *tm)
 {
+    const Problem pb = base_case_problem(pb0);
 #define PSF_AT(D_, R_, P_) (attn_impl<D_, R_, P_>(pb, Q, K, V, G, O, ws, s, tm))
     PSF_DISPATCH(PSF_AT);
 #undef PSF_AT
@@ -1873,7 +1898,7 @@ psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void
 // its in-block phase.
 static Problem noncausal_problem(const Problem &pb0)
 {
-    Problem pb = pb0;
+    Problem pb = base_case_problem(pb0);
     pb.b = pb0.n;
     pb.t = 2;
     return pb;

@@ -176,6 +176,23 @@ def test_in_block_sketch_rule_path_selection():
     assert psf.kernel_path(psf.make_desc(1, 2, 1024, 128, 4, 64, 256, "bf16", local=psf.LOCAL_SKETCH)) == 1
 
 
+@pytest.mark.parametrize("b,local", [(256, psf.LOCAL_EXACT), (512, psf.LOCAL_SKETCH), (1024, psf.LOCAL_EXACT)])
+def test_base_case_degree_two_on_the_mfma_path(b, local):
+    # p = 2: m(x) = x (Algorithm 1's base case), 64^2 = 4096 features, no randomness; the two
+    # in-block rules coincide.  Full parity against the definition, which is exact degree-2
+    # polynomial attention.
+    cfg = mk(1, 2, 1024, 64, 2, 64, b)
+    q, k, v = inputs.make_qkv(1, 2, 1024, 64, seed=19, dtype="bf16")
+    got, desc = gpu_attn(cfg, q, k, v, None, local=local)
+    assert psf.kernel_path(desc) == 1
+    want = oracle_attn(cfg, q, k, v, None)
+    print("p=2", (b, local), assert_close(got.numpy(), want, "bf16", "p=2 b=%d" % b))
+    desc_r = psf.make_desc(1, 2, 1024, 64, 2, 16, b, "bf16", local=local)      # r is ignored for p = 2
+    O2 = psf.psf_causal_attn_fwd(desc_r, q.cuda(), k.cuda(), v.cuda(), None)
+    torch.cuda.synchronize()
+    assert torch.equal(O2.float().cpu(), got)
+
+
 def test_forward_replays_from_a_captured_graph():
     # The library only enqueues kernels on the caller's stream (no allocation, no memset, no
     # synchronisation), so a call can be captured into a HIP graph: several replays, with eager
