@@ -135,3 +135,28 @@ def test_largest_admitted_dimensions():
     G = inputs.make_sketch_matrices(1, 256, 256, 4, seed=0, dtype="f32")
     got, _ = gpu_attn(cfg, q, k, v, G)
     assert_close(got.numpy(), oracle_attn(cfg, q, k, v, G), "f32", "d = dv = r = 256")
+
+
+@pytest.mark.parametrize("dtype,d,r,b,n", [("f32", 16, 8, 16, 64), ("bf16", 64, 64, 256, 512), ("bf16", 64, 32, 256, 512)])
+def test_degenerate_all_zero_queries_and_keys(dtype, d, r, b, n):
+    # q = k = 0: every weight is 0, so o = 0 / (1 + 0) = 0 and every gradient is 0 -- on the
+    # general and on the MFMA kernels, forward, backward and token by token; nothing may turn
+    # into a NaN on the way (the 1 + keeps the denominator away from 0)
+    batch, heads, p = 1, 2, 4
+    dev = torch.device("cuda:0")
+    td = inputs.torch_dtype(dtype)
+    z = torch.zeros(batch, heads, n, d, dtype=td, device=dev)
+    _, _, v = inputs.make_qkv(batch, heads, n, d, seed=71, dtype=dtype)
+    dO = inputs.make_dout(batch, heads, n, d, seed=72, dtype=dtype)
+    G = inputs.make_sketch_matrices(heads, d, r, p, per_head=True, seed=0, dtype=dtype)
+    desc = psf.make_desc(batch, heads, n, d, p, r, b, dtype, per_head=True)
+    O = psf.psf_causal_attn_fwd(desc, z, z, v.to(dev), G.to(dev))
+    dQ, dK, dV = psf.psf_causal_attn_bwd(desc, z, z, v.to(dev), G.to(dev), dO.to(dev))
+    state = psf.decode_new_state(desc, dev)
+    rows = []
+    for pos in range(b + 3):
+        rows.append(psf.psf_decode_step(desc, z[:, :, pos:pos + 1].contiguous(), z[:, :, pos:pos + 1].contiguous(),
+                                        v.to(dev)[:, :, pos:pos + 1].contiguous(), G.to(dev), pos, state).clone())
+    torch.cuda.synchronize()
+    for name, t in (("O", O), ("dQ", dQ), ("dK", dK), ("dV", dV), ("decoded rows", torch.cat(rows, 2))):
+        assert torch.count_nonzero(t).item() == 0 and torch.isfinite(t.float()).all(), name
