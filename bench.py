@@ -283,6 +283,7 @@ def run_decode(args, psf, inputs, torch):
     # steps one by one
     n_prompt = untimed - args.warmup
     kp, vp = kd[:, :, :n_prompt].contiguous(), vd[:, :, :n_prompt].contiguous()
+    ws = psf.psf_decode_prefill(desc, kp, vp, Gd, state, stream=stream)      # once untimed (kernels load on first use)
     torch.cuda.synchronize()
     tp = time.perf_counter()
     ws = psf.psf_decode_prefill(desc, kp, vp, Gd, state, stream=stream)

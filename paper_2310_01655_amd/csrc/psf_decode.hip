@@ -872,6 +872,50 @@ __global__ __launch_bounds__(kThreads) void dec_prefill_kernel(const T *__restri
     }
 }
 
+// The state after the complete blocks of a prompt, taken from the forward path's state kernel:
+// Zg [units][a][b'/8][c][8] bf16 holds sum_j phi'(k_j) v_j^T with this file's convention already
+// applied (b' > a doubled, b' < a zero); Spart [units][parts][r][r] fp32 the partial m^T m.
+// ZV (and its bf16 copy) take the pairs a <= b' of Zg, ZD the weighted sums of the partials.
+__global__ __launch_bounds__(kThreads) void dec_import_state_kernel(const bf16_t *__restrict__ Zg,
+                                                                    const float *__restrict__ Spart,
+                                                                    float *__restrict__ state, DecodeLayout L,
+                                                                    int dv, int mcols, long long pairs, int parts)
+{
+    const int u = blockIdx.y;
+    float *su = state + (size_t)u * L.per_unit;
+    const bf16_t *zu = Zg + (size_t)u * mcols * mcols * dv;
+    const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
+    if (idx < pairs * dv) {
+        const long long pair = idx / dv;
+        const int c = (int)(idx % dv);
+        int a, bp;
+        tri_pair(pair, mcols, a, bp);
+        const bf16_t raw = zu[(((size_t)a * (mcols / 8) + bp / 8) * dv + c) * 8 + bp % 8];
+        su[L.zv + idx] = bf16_to_f32(raw);
+        if (L.shadow) ((bf16_t *)(su + L.zh))[idx] = raw;
+    }
+    if (idx < pairs) {
+        int a, bp;
+        tri_pair(idx, mcols, a, bp);
+        const float *sp = Spart + (size_t)u * parts * mcols * mcols + (size_t)a * mcols + bp;
+        float sacc = 0.f;
+        for (int q2 = 0; q2 < parts; ++q2) sacc += sp[(size_t)q2 * mcols * mcols];
+        su[L.zd + idx] = (bp > a ? 2.f : 1.f) * sacc;
+    }
+}
+
+// 16-byte copies of the first n_full rows of every unit out of [units][n_prompt][w] (bf16)
+__global__ __launch_bounds__(kThreads) void dec_gather_prefix_kernel(const bf16_t *__restrict__ src,
+                                                                     bf16_t *__restrict__ dst, int w, int n_prompt,
+                                                                     int n_full, size_t pieces)
+{
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;       // piece of 8 elements
+    if (i >= pieces) return;
+    const size_t per_unit = (size_t)n_full * w / 8;
+    const size_t u = i / per_unit, r8 = i % per_unit;
+    *(uint4 *)(dst + i * 8) = *(const uint4 *)(src + (u * n_prompt * w) + r8 * 8);
+}
+
 // Folds the b tokens in the block cache into the state (the block is complete).
 template <typename T>
 psf_status launch_fold(const Problem &pb, const DecodeLayout &L, float *state, hipStream_t s)
@@ -966,10 +1010,24 @@ psf_status decode_reset(const Problem &pb, void *state, hipStream_t s)
     return PSF_OK;
 }
 
+// The complete blocks of a prompt go through the forward path's kernels where those exist
+// (bf16, the MFMA shapes, sketches of Algorithm 1): their total state is imported, and only the
+// tokens after the last block boundary are written into the cache one block at a time.
+static int prefill_fast_tokens(const Problem &pb, int n_prompt)
+{
+    const int n_full = n_prompt / pb.b * pb.b;
+    return n_full > 0 && pb.mcols % 8 == 0 && mfma_total_state_supported(pb, n_full) ? n_full : 0;
+}
+
 size_t decode_prefill_workspace_bytes(const Problem &pb, int n_prompt)
 {
     // learned sketches: m(k) of every prompt row, from the general sketch kernel
-    return pb.learned && pb.p > 2 ? (size_t)pb.units * (size_t)n_prompt * pb.mcols * sizeof(float) : 0;
+    if (pb.learned && pb.p > 2) return (size_t)pb.units * (size_t)n_prompt * pb.mcols * sizeof(float);
+    const int n_full = prefill_fast_tokens(pb, n_prompt);
+    if (n_full == 0) return 0;
+    // contiguous copies of the prefix of K and V when the prompt has a tail, then the kernels' own
+    const size_t copy = n_full == n_prompt ? 0 : align_up((size_t)pb.units * n_full * pb.d * 2, 256);
+    return 2 * copy + mfma_total_state_workspace_bytes(pb, n_full);
 }
 
 template <typename T>
@@ -979,7 +1037,40 @@ static psf_status prefill_launch(const Problem &pb, const void *K, const void *V
     const DecodeLayout L = decode_layout(pb);
     psf_status st = decode_reset(pb, state, s);
     if (st != PSF_OK) return st;
-    const bool have_m = decode_prefill_workspace_bytes(pb, n_prompt) > 0;
+    int first = 0;                                         // prompt tokens before this one are in the state already
+    if constexpr (std::is_same_v<T, bf16_t>) {
+        const int n_full = prefill_fast_tokens(pb, n_prompt);
+        if (n_full > 0 && !pb.learned) {
+            const bf16_t *kc = (const bf16_t *)K, *vc = (const bf16_t *)V;
+            char *wsp = (char *)ws;
+            if (n_full != n_prompt) {
+                const size_t copy = align_up((size_t)pb.units * n_full * pb.d * 2, 256);
+                const size_t pieces = (size_t)pb.units * n_full * pb.d / 8;
+                const unsigned grid = (unsigned)((pieces + kThreads - 1) / kThreads);
+                hipLaunchKernelGGL(dec_gather_prefix_kernel, dim3(grid), dim3(kThreads), 0, s, (const bf16_t *)K,
+                                   (bf16_t *)wsp, pb.d, n_prompt, n_full, pieces);
+                PSF_LAUNCH_CHECK();
+                hipLaunchKernelGGL(dec_gather_prefix_kernel, dim3(grid), dim3(kThreads), 0, s, (const bf16_t *)V,
+                                   (bf16_t *)(wsp + copy), pb.dv, n_prompt, n_full, pieces);
+                PSF_LAUNCH_CHECK();
+                kc = (const bf16_t *)wsp;
+                vc = (const bf16_t *)(wsp + copy);
+                wsp += 2 * copy;
+            }
+            const void *zg = nullptr;
+            const float *spart = nullptr;
+            int parts = 0;
+            st = mfma_total_state(pb, n_full, kc, vc, G, wsp, s, &zg, &spart, &parts);
+            if (st != PSF_OK) return st;
+            const long long pairs = tri_count(pb.mcols);
+            const dim3 grid((unsigned)((pairs * pb.dv + kThreads - 1) / kThreads), (unsigned)pb.units);
+            hipLaunchKernelGGL(dec_import_state_kernel, grid, dim3(kThreads), 0, s, (const bf16_t *)zg, spart, state, L,
+                               pb.dv, pb.mcols, pairs, parts);
+            PSF_LAUNCH_CHECK();
+            first = n_full;
+        }
+    }
+    const bool have_m = pb.learned && pb.p > 2;
     if (have_m && n_prompt > 0) {
         Problem all = pb;
         all.n = n_prompt;
@@ -987,7 +1078,7 @@ static psf_status prefill_launch(const Problem &pb, const void *K, const void *V
         if (st != PSF_OK) return st;
     }
     const DecSketchArgs ska{G, pb.g_len, pb.heads, pb.per_head ? 1 : 0, pb.r};
-    for (int pos0 = 0; pos0 < n_prompt; pos0 += pb.b) {
+    for (int pos0 = first; pos0 < n_prompt; pos0 += pb.b) {
         const int count = n_prompt - pos0 < pb.b ? n_prompt - pos0 : pb.b;
         const dim3 grid((unsigned)((count + kPrefillTokens - 1) / kPrefillTokens), (unsigned)pb.units);
         if (have_m)

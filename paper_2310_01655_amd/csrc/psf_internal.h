@@ -88,6 +88,13 @@ psf_status decode_prefill(const Problem &pb, const void *K, const void *V, const
 size_t mfma_workspace_bytes(const Problem &pb);
 psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void *V,
                      const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);
+// Sum over n_tok tokens per unit (K, V contiguous [units][n_tok][d]) of phi'(k) v^T, in the output
+// kernel's state layout ([a][b'/8][c][8] bf16; b' > a doubled, b' < a zero), and the fp32
+// partial sums of m(k)^T m(k) ([units][parts][r][r]); for the decode hand-over.
+bool mfma_total_state_supported(const Problem &pb, int n_tok);
+size_t mfma_total_state_workspace_bytes(const Problem &pb, int n_tok);
+psf_status mfma_total_state(const Problem &pb, int n_tok, const void *K, const void *V, const void *G, void *ws,
+                            hipStream_t s, const void **Zg, const float **Spart, int *parts_per_unit);
 size_t mfma_noncausal_workspace_bytes(const Problem &pb);
 psf_status mfma_attn_noncausal(const Problem &pb, const void *Q, const void *K, const void *V,
                                const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);

@@ -1893,6 +1893,92 @@ psf_status mfma_attn(const Problem &pb0, const void *Q, const void *K, const voi
 #undef PSF_AT
 }
 
+// ---- total state of a run of tokens (for the hand-over from a prompt to token-by-token
+// evaluation): Z = sum_j phi'(k_j) v_j^T over the n_tok tokens of every unit, from the sketch,
+// layout and state kernels of the forward path run on one "block" of n_tok tokens (as the
+// non-causal entry point does).  Zg: [units][a][b'/8][c][8] bf16 with the symmetry weights of
+// k_state (b' > a doubled, b' < a zero); Spart: [units][parts][r][r] fp32 partial m^T m.
+struct TotalWs {
+    bf16_t *Gt; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart;
+    size_t total;
+};
+
+static Problem total_problem(const Problem &pb0, int n_tok)
+{
+    Problem pb = pb0;
+    pb.n = n_tok;
+    pb.b = n_tok;
+    pb.t = 2;
+    pb.local_exact = true;
+    return pb;
+}
+
+static TotalWs carve_total(const Problem &pb, void *ws)
+{
+    TotalWs w;
+    const size_t rows = (size_t)pb.units * pb.n, R = pb.r, D = pb.d;
+    const size_t sets = pb.per_head ? pb.heads : 1, parts = rows / (size_t)part_tokens(pb);
+    size_t off = 0;
+    char *base = (char *)ws;
+    auto take = [&](size_t bytes) { char *q = base + off; off += align_up(bytes, 256); return q; };
+    w.Gt = (bf16_t *)take(sets * pb.g_len * 2);
+    w.MK8 = (float *)take(rows * R * 4);
+    w.V8 = (bf16_t *)take(rows * D * 2);
+    w.Zg = (bf16_t *)take((size_t)pb.units * R * R * D * 2);
+    w.Spart = (float *)take(parts * R * R * 4);
+    w.total = off;
+    return w;
+}
+
+bool mfma_total_state_supported(const Problem &pb, int n_tok)
+{
+    return pb.bf16 && !pb.learned && !pb.exact_feat && pb.d == pb.dv && (pb.d == 64 || pb.d == 128) &&
+           (pb.r == 32 || pb.r == 64) && (pb.p == 4 || pb.p == 8) && n_tok >= 256 && n_tok % 256 == 0;
+}
+
+size_t mfma_total_state_workspace_bytes(const Problem &pb, int n_tok)
+{
+    return carve_total(total_problem(pb, n_tok), nullptr).total;
+}
+
+namespace {
+template <int D, int R, int P>
+psf_status total_state_impl(const Problem &pb, const void *K, const void *V, const void *G, const TotalWs &w,
+                            hipStream_t s)
+{
+    psf_status st = launch_transpose_g(pb, G, w.Gt, s);
+    if (st != PSF_OK) return st;
+    st = launch_sketch<D, R, P>(pb, K, w.Gt, false, nullptr, w.MK8, w.Spart, sketch_tiles_per_wg(pb.b), s);
+    if (st != PSF_OK) return st;
+    const size_t octets = (size_t)pb.units * pb.n / 8;
+    hipLaunchKernelGGL((k_v_octets<D>), dim3((unsigned)((octets * D + kWg - 1) / kWg)), dim3(kWg), 0, s,
+                       (const bf16_t *)V, w.V8, octets);
+    PSF_LAUNCH_CHECK();
+    return launch_state<D, R>(pb, w.MK8, w.V8, w.Zg, s);
+}
+}  // namespace
+
+psf_status mfma_total_state(const Problem &pb0, int n_tok, const void *K, const void *V, const void *G, void *ws,
+                            hipStream_t s, const void **Zg, const float **Spart, int *parts_per_unit)
+{
+    const Problem pb = total_problem(pb0, n_tok);
+    const TotalWs w = carve_total(pb, ws);
+    *Zg = w.Zg;
+    *Spart = w.Spart;
+    *parts_per_unit = pb.n / part_tokens(pb);
+#define PSF_AT(D_, R_, P_) (total_state_impl<D_, R_, P_>(pb, K, V, G, w, s))
+    if (pb.d == 64 && pb.r == 64 && pb.p == 4) return PSF_AT(64, 64, 4);
+    if (pb.d == 64 && pb.r == 32 && pb.p == 4) return PSF_AT(64, 32, 4);
+    if (pb.d == 64 && pb.r == 64 && pb.p == 8) return PSF_AT(64, 64, 8);
+    if (pb.d == 64 && pb.r == 32 && pb.p == 8) return PSF_AT(64, 32, 8);
+    if (pb.d == 128 && pb.r == 64 && pb.p == 4) return PSF_AT(128, 64, 4);
+    if (pb.d == 128 && pb.r == 32 && pb.p == 4) return PSF_AT(128, 32, 4);
+    if (pb.d == 128 && pb.r == 64 && pb.p == 8) return PSF_AT(128, 64, 8);
+    if (pb.d == 128 && pb.r == 32 && pb.p == 8) return PSF_AT(128, 32, 8);
+#undef PSF_AT
+    return PSF_ERR_UNSUPPORTED;
+}
+
 // Non-causal attention (Section 2.2) = the causal kernels on one "block" of all n tokens whose
 // state every token reads: the state kernel accumulates that block, the output kernel skips
 // its in-block phase.

@@ -175,9 +175,20 @@ def test_decode_entry_points_validate_on_the_host():
     exact = psf.make_desc(1, 1, 64, 8, 4, 1, 8, "f32", feat=psf.FEAT_EXACT)
     assert psf.decode_state_bytes(exact) == 0
     assert L.psf_decode_step(ctypes.byref(exact), *args, 0, one, 1 << 40, one, None) == 3
-    # hand-over from a prompt: no workspace for the sketches of Algorithm 1, the fp32 sketches of
-    # every prompt key for learned ones; every failure below is found before any launch
-    assert L.psf_decode_prefill_workspace_bytes(ref, 1000) == 0
+    # hand-over from a prompt: no workspace while the prompt is shorter than a block; with complete
+    # blocks on the MFMA shapes the forward kernels' buffers (sketches, value octets, one state,
+    # the prefix of K and V when a tail follows); the fp32 sketches of every prompt key for
+    # learned sketches; every failure below is found before any launch
+    assert L.psf_decode_prefill_workspace_bytes(ref, 200) == 0
+    units, n_full = 6, 768
+    fast = L.psf_decode_prefill_workspace_bytes(ref, 1000)
+    assert fast >= units * n_full * (32 * 4 + 64 * 2 + 2 * 64 * 2) + units * 32 * 32 * 64 * 2
+    assert fast < units * n_full * (32 * 4 + 64 * 2 + 2 * 64 * 2) + units * 32 * 32 * 64 * 2 + (1 << 20)
+    assert L.psf_decode_prefill_workspace_bytes(ref, 768) < fast      # no tail: K and V are used in place
+    assert L.psf_decode_prefill(ref, one, one, one, 1000, one, need, None, fast, None) == 1
+    assert L.psf_decode_prefill(ref, one, one, one, 1000, one, need, one, fast - 1, None) == 4
+    f32d = psf.make_desc(2, 3, 4096, 64, 4, 32, 256, "f32")
+    assert L.psf_decode_prefill_workspace_bytes(ctypes.byref(f32d), 1000) == 0    # general kernels only
     assert L.psf_decode_prefill_workspace_bytes(ref, 4097) == 0
     assert L.psf_decode_prefill(ref, one, one, one, -1, one, need, None, 0, None) == 2
     assert L.psf_decode_prefill(ref, one, one, one, 4097, one, need, None, 0, None) == 2

@@ -148,6 +148,19 @@ def test_decode_prefill_headline_unit_shape_bf16():
     prefill_then_decode(1, 3, 768, 600, 64, 64, 4, 64, 256, "bf16")
 
 
+@pytest.mark.parametrize("heads,n,n_prompt,d,p,r,b,per_head", [
+    (2, 768, 512, 64, 4, 32, 256, True),      # complete blocks only: K and V used in place
+    (3, 1024, 700, 64, 4, 32, 256, False),    # two blocks through the forward kernels, a tail through the cache
+    (2, 768, 600, 128, 8, 64, 256, True),     # d = 128, two-level sketch
+    (2, 1024, 1023, 64, 4, 64, 512, False),   # one block, then all but one token of the next
+])
+def test_decode_prefill_through_the_forward_state_kernel(heads, n, n_prompt, d, p, r, b, per_head):
+    # bf16 on the MFMA shapes: the state of the prompt's complete blocks is the forward path's
+    # total state (bf16, as the forward pass stores its prefix states), imported into the packed
+    # fp32 / bf16 decode state; the rows decoded afterwards against the oracle
+    prefill_then_decode(1, heads, n, n_prompt, d, d, p, r, b, "bf16", per_head=per_head)
+
+
 def test_decode_prefill_learned_sketches():
     prefill_then_decode(1, 2, 48, 29, 16, 16, 4, 8, 16, "f32", learned=True)
 
