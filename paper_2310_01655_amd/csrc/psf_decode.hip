@@ -885,14 +885,24 @@ __global__ __launch_bounds__(kThreads) void dec_import_state_kernel(const bf16_t
     float *su = state + (size_t)u * L.per_unit;
     const bf16_t *zu = Zg + (size_t)u * mcols * mcols * dv;
     const long long idx = (long long)blockIdx.x * kThreads + threadIdx.x;
-    if (idx < pairs * dv) {
-        const long long pair = idx / dv;
-        const int c = (int)(idx % dv);
-        int a, bp;
-        tri_pair(pair, mcols, a, bp);
-        const bf16_t raw = zu[(((size_t)a * (mcols / 8) + bp / 8) * dv + c) * 8 + bp % 8];
-        su[L.zv + idx] = bf16_to_f32(raw);
-        if (L.shadow) ((bf16_t *)(su + L.zh))[idx] = raw;
+    // one 16-byte piece of Zg per thread: row a, eight columns b' = 8 o .., value column c
+    // (consecutive threads: consecutive c, so reads and the stores of a row are contiguous)
+    if (idx < (long long)mcols * (mcols / 8) * dv) {
+        const int c = (int)(idx % dv), o = (int)((idx / dv) % (mcols / 8)), a = (int)(idx / dv / (mcols / 8));
+        if (8 * o + 7 >= a) {
+            const uint4 raw = *(const uint4 *)(zu + (size_t)idx * 8);
+            const uint32_t wds[4] = {raw.x, raw.y, raw.z, raw.w};
+            const size_t row0 = (size_t)tri_row(a, mcols);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int bp = 8 * o + e;
+                if (bp < a) continue;
+                const bf16_t h16 = (bf16_t)((e & 1) ? wds[e / 2] >> 16 : wds[e / 2] & 0xffffu);
+                const size_t at = (row0 + bp - a) * dv + c;
+                su[L.zv + at] = bf16_to_f32(h16);
+                if (L.shadow) ((bf16_t *)(su + L.zh))[at] = h16;
+            }
+        }
     }
     if (idx < pairs) {
         int a, bp;
@@ -1063,7 +1073,8 @@ static psf_status prefill_launch(const Problem &pb, const void *K, const void *V
             st = mfma_total_state(pb, n_full, kc, vc, G, wsp, s, &zg, &spart, &parts);
             if (st != PSF_OK) return st;
             const long long pairs = tri_count(pb.mcols);
-            const dim3 grid((unsigned)((pairs * pb.dv + kThreads - 1) / kThreads), (unsigned)pb.units);
+            const long long pieces = (long long)pb.mcols * (pb.mcols / 8) * pb.dv;      // >= pairs
+            const dim3 grid((unsigned)((pieces + kThreads - 1) / kThreads), (unsigned)pb.units);
             hipLaunchKernelGGL(dec_import_state_kernel, grid, dim3(kThreads), 0, s, (const bf16_t *)zg, spart, state, L,
                                pb.dv, pb.mcols, pairs, parts);
             PSF_LAUNCH_CHECK();
