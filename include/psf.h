@@ -258,7 +258,7 @@ psf_status psf_decode_step(const psf_desc *desc, const void *q, const void *k, c
  *   0 <= n_prompt <= desc->n (else PSF_ERR_SHAPE); G as for psf_decode_step.
  *   workspace: psf_decode_prefill_workspace_bytes(desc, n_prompt) bytes of device memory,
  *   256-byte aligned (null allowed when that is zero).  Where psf_kernel_path(desc) == 1 with
- *   the sketches of Algorithm 1 and p in {4, 8}, the complete blocks of the prompt go through
+ *   p in {4, 8} (learned sketches: p = 4 and d = 64), the complete blocks of the prompt go through
  *   the forward path's sketch and state kernels (their buffers are the workspace) and the
  *   state starts from their bf16 result, as the forward pass's own prefix states do; learned
  *   sketches need the fp32 sketches of all prompt keys; otherwise the workspace is empty and

@@ -836,8 +836,9 @@ __global__ __launch_bounds__(kThreads) void dec_prefill_kernel(const T *__restri
                                                                const float *__restrict__ M_all,
                                                                float *__restrict__ state, DecodeLayout L, int d,
                                                                int dv, int p, int mcols, int n_prompt, int pos0,
-                                                               int count, DecSketchArgs sk)
+                                                               int count, int m_first, int m_rows, DecSketchArgs sk)
 {
+    // M_all: [units][m_rows][mcols], the sketches of prompt rows m_first .. m_first + m_rows - 1
     static_assert(kThreads == kSketchThreads, "sketch_rows_lds assumes this workgroup size");
     __shared__ float xs[2][PSF_MAX_DIM];
     __shared__ SketchScratchN<HAVE_M ? 1 : 2> scratch;
@@ -855,7 +856,8 @@ __global__ __launch_bounds__(kThreads) void dec_prefill_kernel(const T *__restri
             for (int c = tid; c < dv; c += kThreads) cvals[(size_t)(j0 + i) * dv + c] = V[row * dv + c];
             if (HAVE_M)
                 for (int e = tid; e < mcols; e += kThreads)
-                    su[L.cm + (size_t)(j0 + i) * mcols + e] = M_all[row * mcols + e];
+                    su[L.cm + (size_t)(j0 + i) * mcols + e] =
+                        M_all[((size_t)u * m_rows + (pos0 + j0 + i - m_first)) * mcols + e];
         }
         if constexpr (!HAVE_M) {
             __syncthreads();                               // the previous pair's results have been read
@@ -914,16 +916,17 @@ __global__ __launch_bounds__(kThreads) void dec_import_state_kernel(const bf16_t
     }
 }
 
-// 16-byte copies of the first n_full rows of every unit out of [units][n_prompt][w] (bf16)
-__global__ __launch_bounds__(kThreads) void dec_gather_prefix_kernel(const bf16_t *__restrict__ src,
-                                                                     bf16_t *__restrict__ dst, int w, int n_prompt,
-                                                                     int n_full, size_t pieces)
+// 16-byte copies of rows first .. first + rows - 1 of every unit out of [units][n_prompt][w] (bf16)
+// into [units][rows][w]
+__global__ __launch_bounds__(kThreads) void dec_gather_rows_kernel(const bf16_t *__restrict__ src,
+                                                                   bf16_t *__restrict__ dst, int w, int n_prompt,
+                                                                   int first, int rows, size_t pieces)
 {
     const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;       // piece of 8 elements
     if (i >= pieces) return;
-    const size_t per_unit = (size_t)n_full * w / 8;
+    const size_t per_unit = (size_t)rows * w / 8;
     const size_t u = i / per_unit, r8 = i % per_unit;
-    *(uint4 *)(dst + i * 8) = *(const uint4 *)(src + (u * n_prompt * w) + r8 * 8);
+    *(uint4 *)(dst + i * 8) = *(const uint4 *)(src + (u * n_prompt + first) * w + r8 * 8);
 }
 
 // Folds the b tokens in the block cache into the state (the block is complete).
@@ -1029,16 +1032,32 @@ static int prefill_fast_tokens(const Problem &pb, int n_prompt)
     return n_full > 0 && pb.mcols % 8 == 0 && mfma_total_state_supported(pb, n_full) ? n_full : 0;
 }
 
-size_t decode_prefill_workspace_bytes(const Problem &pb, int n_prompt)
+// Workspace of a hand-over, in this order: the fp32 sketches of the prompt keys that go through
+// the cache (learned sketches only: all of them, or those after the last block boundary when
+// the forward kernels take the complete blocks), a contiguous copy of those keys (same case),
+// contiguous copies of the complete blocks of K and V (when a tail follows them), the forward
+// kernels' own buffers.
+struct PrefillPlan {
+    int n_full, m_rows;                   // tokens through the forward kernels; sketched rows per unit
+    size_t m_bytes, ktail_bytes, copy_bytes, total;
+};
+
+static PrefillPlan prefill_plan(const Problem &pb, int n_prompt)
 {
-    // learned sketches: m(k) of every prompt row, from the general sketch kernel
-    if (pb.learned && pb.p > 2) return (size_t)pb.units * (size_t)n_prompt * pb.mcols * sizeof(float);
-    const int n_full = prefill_fast_tokens(pb, n_prompt);
-    if (n_full == 0) return 0;
-    // contiguous copies of the prefix of K and V when the prompt has a tail, then the kernels' own
-    const size_t copy = n_full == n_prompt ? 0 : align_up((size_t)pb.units * n_full * pb.d * 2, 256);
-    return 2 * copy + mfma_total_state_workspace_bytes(pb, n_full);
+    PrefillPlan pl;
+    const bool learned = pb.learned && pb.p > 2;
+    pl.n_full = prefill_fast_tokens(pb, n_prompt);
+    const int tail = n_prompt - pl.n_full;
+    pl.m_rows = learned ? tail : 0;
+    pl.m_bytes = align_up((size_t)pb.units * pl.m_rows * pb.mcols * sizeof(float), 256);
+    pl.ktail_bytes = learned && pl.n_full > 0 ? align_up((size_t)pb.units * tail * pb.d * 2, 256) : 0;
+    pl.copy_bytes = pl.n_full > 0 && tail > 0 ? align_up((size_t)pb.units * pl.n_full * pb.d * 2, 256) : 0;
+    pl.total = pl.m_bytes + pl.ktail_bytes + 2 * pl.copy_bytes +
+               (pl.n_full > 0 ? mfma_total_state_workspace_bytes(pb, pl.n_full) : 0);
+    return pl;
 }
+
+size_t decode_prefill_workspace_bytes(const Problem &pb, int n_prompt) { return prefill_plan(pb, n_prompt).total; }
 
 template <typename T>
 static psf_status prefill_launch(const Problem &pb, const void *K, const void *V, const void *G, int n_prompt,
@@ -1047,30 +1066,29 @@ static psf_status prefill_launch(const Problem &pb, const void *K, const void *V
     const DecodeLayout L = decode_layout(pb);
     psf_status st = decode_reset(pb, state, s);
     if (st != PSF_OK) return st;
-    int first = 0;                                         // prompt tokens before this one are in the state already
+    const PrefillPlan pl = prefill_plan(pb, n_prompt);
+    const int first = pl.n_full, tail = n_prompt - first;  // prompt tokens before `first` go through the forward kernels
+    float *m_tail = (float *)ws;
+    char *ktail = (char *)ws + pl.m_bytes, *wsp = ktail + pl.ktail_bytes;
     if constexpr (std::is_same_v<T, bf16_t>) {
-        const int n_full = prefill_fast_tokens(pb, n_prompt);
-        if (n_full > 0 && !pb.learned) {
+        if (first > 0) {
             const bf16_t *kc = (const bf16_t *)K, *vc = (const bf16_t *)V;
-            char *wsp = (char *)ws;
-            if (n_full != n_prompt) {
-                const size_t copy = align_up((size_t)pb.units * n_full * pb.d * 2, 256);
-                const size_t pieces = (size_t)pb.units * n_full * pb.d / 8;
+            if (tail > 0) {
+                const size_t pieces = (size_t)pb.units * first * pb.d / 8;
                 const unsigned grid = (unsigned)((pieces + kThreads - 1) / kThreads);
-                hipLaunchKernelGGL(dec_gather_prefix_kernel, dim3(grid), dim3(kThreads), 0, s, (const bf16_t *)K,
-                                   (bf16_t *)wsp, pb.d, n_prompt, n_full, pieces);
+                hipLaunchKernelGGL(dec_gather_rows_kernel, dim3(grid), dim3(kThreads), 0, s, (const bf16_t *)K,
+                                   (bf16_t *)wsp, pb.d, n_prompt, 0, first, pieces);
                 PSF_LAUNCH_CHECK();
-                hipLaunchKernelGGL(dec_gather_prefix_kernel, dim3(grid), dim3(kThreads), 0, s, (const bf16_t *)V,
-                                   (bf16_t *)(wsp + copy), pb.dv, n_prompt, n_full, pieces);
+                hipLaunchKernelGGL(dec_gather_rows_kernel, dim3(grid), dim3(kThreads), 0, s, (const bf16_t *)V,
+                                   (bf16_t *)(wsp + pl.copy_bytes), pb.dv, n_prompt, 0, first, pieces);
                 PSF_LAUNCH_CHECK();
                 kc = (const bf16_t *)wsp;
-                vc = (const bf16_t *)(wsp + copy);
-                wsp += 2 * copy;
+                vc = (const bf16_t *)(wsp + pl.copy_bytes);
             }
             const void *zg = nullptr;
             const float *spart = nullptr;
             int parts = 0;
-            st = mfma_total_state(pb, n_full, kc, vc, G, wsp, s, &zg, &spart, &parts);
+            st = mfma_total_state(pb, first, kc, vc, G, wsp + 2 * pl.copy_bytes, s, &zg, &spart, &parts);
             if (st != PSF_OK) return st;
             const long long pairs = tri_count(pb.mcols);
             const long long pieces = (long long)pb.mcols * (pb.mcols / 8) * pb.dv;      // >= pairs
@@ -1078,14 +1096,25 @@ static psf_status prefill_launch(const Problem &pb, const void *K, const void *V
             hipLaunchKernelGGL(dec_import_state_kernel, grid, dim3(kThreads), 0, s, (const bf16_t *)zg, spart, state, L,
                                pb.dv, pb.mcols, pairs, parts);
             PSF_LAUNCH_CHECK();
-            first = n_full;
         }
     }
-    const bool have_m = pb.learned && pb.p > 2;
-    if (have_m && n_prompt > 0) {
-        Problem all = pb;
-        all.n = n_prompt;
-        st = general_sketch_f32(all, K, G, (float *)ws, s);
+    const bool have_m = pl.m_rows > 0;
+    if (have_m) {
+        // learned sketches of the rows that go through the cache: rows first .. n_prompt - 1 of every unit
+        const void *krows = K;
+        if constexpr (std::is_same_v<T, bf16_t>) {
+            if (first > 0) {
+                const size_t pieces = (size_t)pb.units * tail * pb.d / 8;
+                hipLaunchKernelGGL(dec_gather_rows_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads)),
+                                   dim3(kThreads), 0, s, (const bf16_t *)K, (bf16_t *)ktail, pb.d, n_prompt, first, tail,
+                                   pieces);
+                PSF_LAUNCH_CHECK();
+                krows = ktail;
+            }
+        }
+        Problem part = pb;
+        part.n = tail;
+        st = general_sketch_f32(part, krows, G, m_tail, s);
         if (st != PSF_OK) return st;
     }
     const DecSketchArgs ska{G, pb.g_len, pb.heads, pb.per_head ? 1 : 0, pb.r};
@@ -1094,11 +1123,12 @@ static psf_status prefill_launch(const Problem &pb, const void *K, const void *V
         const dim3 grid((unsigned)((count + kPrefillTokens - 1) / kPrefillTokens), (unsigned)pb.units);
         if (have_m)
             hipLaunchKernelGGL((dec_prefill_kernel<T, true>), grid, dim3(kThreads), 0, s, (const T *)K, (const T *)V,
-                               (const float *)ws, state, L, pb.d, pb.dv, pb.p, pb.mcols, n_prompt, pos0, count, ska);
+                               (const float *)m_tail, state, L, pb.d, pb.dv, pb.p, pb.mcols, n_prompt, pos0, count,
+                               first, tail, ska);
         else
             hipLaunchKernelGGL((dec_prefill_kernel<T, false>), grid, dim3(kThreads), 0, s, (const T *)K, (const T *)V,
                                (const float *)nullptr, state, L, pb.d, pb.dv, pb.p, pb.mcols, n_prompt, pos0, count,
-                               ska);
+                               first, tail, ska);
         PSF_LAUNCH_CHECK();
         if (count == pb.b) {
             st = launch_fold<T>(pb, L, state, s);

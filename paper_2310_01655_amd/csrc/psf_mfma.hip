@@ -1900,6 +1900,7 @@ psf_status mfma_attn(const Problem &pb0, const void *Q, const void *K, const voi
 // k_state (b' > a doubled, b' < a zero); Spart: [units][parts][r][r] fp32 partial m^T m.
 struct TotalWs {
     bf16_t *Gt; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart;
+    bf16_t *LW; float *C1, *LVp;                 // learned sketches: arranged weights (see k_learned_prep)
     size_t total;
 };
 
@@ -1921,19 +1922,25 @@ static TotalWs carve_total(const Problem &pb, void *ws)
     size_t off = 0;
     char *base = (char *)ws;
     auto take = [&](size_t bytes) { char *q = base + off; off += align_up(bytes, 256); return q; };
-    w.Gt = (bf16_t *)take(sets * pb.g_len * 2);
+    w.Gt = (bf16_t *)take(pb.learned ? 0 : sets * pb.g_len * 2);
     w.MK8 = (float *)take(rows * R * 4);
     w.V8 = (bf16_t *)take(rows * D * 2);
     w.Zg = (bf16_t *)take((size_t)pb.units * R * R * D * 2);
     w.Spart = (float *)take(parts * R * R * 4);
+    const size_t nch = R / 4;
+    w.LW = (bf16_t *)take(pb.learned ? sets * 4 * nch * kLsSlotBytes : 0);
+    w.C1 = (float *)take(pb.learned ? sets * 2 * nch * 32 * 4 : 0);
+    w.LVp = (float *)take(pb.learned ? sets * 2 * nch * 2 * R * 4 : 0);
     w.total = off;
     return w;
 }
 
 bool mfma_total_state_supported(const Problem &pb, int n_tok)
 {
-    return pb.bf16 && !pb.learned && !pb.exact_feat && pb.d == pb.dv && (pb.d == 64 || pb.d == 128) &&
-           (pb.r == 32 || pb.r == 64) && (pb.p == 4 || pb.p == 8) && n_tok >= 256 && n_tok % 256 == 0;
+    const bool shapes = pb.bf16 && !pb.exact_feat && pb.d == pb.dv && (pb.d == 64 || pb.d == 128) &&
+                        (pb.r == 32 || pb.r == 64) && n_tok >= 256 && n_tok % 256 == 0;
+    // learned sketches: the MFMA sketch kernel exists for degree 4 and d = 64
+    return shapes && (pb.learned ? pb.p == 4 && pb.d == 64 : pb.p == 4 || pb.p == 8);
 }
 
 size_t mfma_total_state_workspace_bytes(const Problem &pb, int n_tok)
@@ -1946,10 +1953,26 @@ template <int D, int R, int P>
 psf_status total_state_impl(const Problem &pb, const void *K, const void *V, const void *G, const TotalWs &w,
                             hipStream_t s)
 {
-    psf_status st = launch_transpose_g(pb, G, w.Gt, s);
-    if (st != PSF_OK) return st;
-    st = launch_sketch<D, R, P>(pb, K, w.Gt, false, nullptr, w.MK8, w.Spart, sketch_tiles_per_wg(pb.b), s);
-    if (st != PSF_OK) return st;
+    psf_status st;
+    if (pb.learned) {
+        if constexpr (P == 4 && D == 64) {
+            const int sets = pb.per_head ? pb.heads : 1;
+            hipLaunchKernelGGL((k_learned_prep<R>), dim3(4 * (R / 4), sets), dim3(kWg), 0, s, (const bf16_t *)G,
+                               pb.g_len, w.LW, w.C1, w.LVp);
+            PSF_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_learned_sketch<R, false, 1>), dim3((unsigned)((size_t)pb.units * pb.n / 256)),
+                               dim3(512), 0, s, (const bf16_t *)K, w.LW, w.C1, w.LVp, nullptr, w.MK8, w.Spart, pb.n,
+                               pb.heads, pb.per_head ? 1 : 0);
+            PSF_LAUNCH_CHECK();
+        } else {
+            return PSF_ERR_UNSUPPORTED;
+        }
+    } else {
+        st = launch_transpose_g(pb, G, w.Gt, s);
+        if (st != PSF_OK) return st;
+        st = launch_sketch<D, R, P>(pb, K, w.Gt, false, nullptr, w.MK8, w.Spart, sketch_tiles_per_wg(pb.b), s);
+        if (st != PSF_OK) return st;
+    }
     const size_t octets = (size_t)pb.units * pb.n / 8;
     hipLaunchKernelGGL((k_v_octets<D>), dim3((unsigned)((octets * D + kWg - 1) / kWg)), dim3(kWg), 0, s,
                        (const bf16_t *)V, w.V8, octets);

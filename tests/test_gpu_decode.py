@@ -165,6 +165,13 @@ def test_decode_prefill_learned_sketches():
     prefill_then_decode(1, 2, 48, 29, 16, 16, 4, 8, 16, "f32", learned=True)
 
 
+@pytest.mark.parametrize("n,n_prompt,r,b,per_head", [(768, 600, 64, 256, True), (768, 512, 32, 256, False)])
+def test_decode_prefill_learned_sketches_through_the_forward_kernels(n, n_prompt, r, b, per_head):
+    # bf16, d = 64, degree 4: the complete blocks through the MFMA learned-sketch kernel and the
+    # state kernel, the tail through the general sketch kernel and the cache
+    prefill_then_decode(1, 2, n, n_prompt, 64, 64, 4, r, b, "bf16", learned=True, per_head=per_head)
+
+
 @pytest.mark.parametrize("batch,heads,n,d,r,b,dtype,local,learned", [
     # the step kernel's variants: storage type x bf16 copy of the state x in-block rule x
     # (slices + finish kernel | one workgroup | one workgroup that also sketches)
