@@ -351,6 +351,8 @@ __global__ __launch_bounds__(kThreads) void dec_zero_kernel(float *__restrict__ 
 // has the whole row, so it also does what dec_finish_kernel does -- the new token's own pair,
 // the division, the cache append.  MODE 2: it also computes m(q) and m(k) of the new token
 // itself (Algorithm 1 with the matrices of the unit's head), and the step is one launch.
+// MODE 3: slices as in MODE 0, but every slice sketches the token itself (slice 0 leaves the
+// sketches in mq_out / mk_out for dec_finish_kernel): two launches instead of three.
 struct DecSketchArgs {
     const void *G;           // sketch matrices, storage type
     size_t g_len;            // entries per set
@@ -362,12 +364,13 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
                                                              const T *__restrict__ v, float *__restrict__ state,
                                                              const float *__restrict__ mq_new,
                                                              const float *__restrict__ mk_new,
+                                                             float *__restrict__ mq_out, float *__restrict__ mk_out,
                                                              float *__restrict__ part, T *__restrict__ o,
                                                              DecodeLayout L, int d, int dv, int p, int mcols,
                                                              long long F, int slot, int have_state,
                                                              DecSketchArgs sk)
 {
-    constexpr bool FUSE = MODE >= 1, SK = MODE == 2;
+    constexpr bool FUSE = MODE == 1 || MODE == 2, SK = MODE >= 2;
     static_assert(kThreads == kSketchThreads, "sketch_row_lds assumes this workgroup size");
     using ZT = std::conditional_t<SHADOW, bf16_t, float>;
     using KT = std::conditional_t<LE, T, float>;
@@ -434,6 +437,12 @@ __global__ __launch_bounds__(kThreads) void dec_state_kernel(const T *__restrict
             mq[tid] = fin[0][tid];
             if (!LE) qs[tid] = fin[0][tid];
             mk_s[tid] = fin[1][tid];
+            if constexpr (MODE == 3) {
+                if (sl == 0) {                             // for dec_finish_kernel
+                    mq_out[(size_t)u * mcols + tid] = fin[0][tid];
+                    mk_out[(size_t)u * mcols + tid] = fin[1][tid];
+                }
+            }
         }
     } else {
         if (tid < mcols) mq[tid] = mq_reg;
@@ -964,7 +973,9 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
     // one workgroup per unit: it finishes the row itself, and with the sketch of Algorithm 1
     // (no networks) it also sketches the new token
     const bool fuse = L.slices == 1;
-    const int mode = !fuse ? 0 : (pb.learned ? 1 : 2);
+    // learned sketches come from the general sketch kernel (modes 0, 1); those of Algorithm 1 are
+    // computed inside the step kernel (modes 2, 3)
+    const int mode = pb.learned ? (fuse ? 1 : 0) : (fuse ? 2 : 3);
     if (mode < 2) {
         // sketches of the new token: the general sketch kernel on [units, 1, d]
         Problem one = pb;
@@ -978,16 +989,18 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
     const DecSketchArgs ska{G, pb.g_len, pb.heads, pb.per_head ? 1 : 0, pb.r};
 #define PSF_DEC_STATE(SH, LE_, MO)                                                                             \
     hipLaunchKernelGGL((dec_state_kernel<T, SH, LE_, MO>), sgrid, dim3(kThreads), 0, s, (const T *)q,             \
-                       (const T *)k, (const T *)v, state, state + L.mq, state + L.mk, state + L.part, (T *)o, L, \
-                       pb.d, pb.dv, pb.p, pb.mcols, Fs, slot, have_state, ska)
+                       (const T *)k, (const T *)v, state, state + L.mq, state + L.mk, state + L.mq, state + L.mk, \
+                       state + L.part, (T *)o, L, pb.d, pb.dv, pb.p, pb.mcols, Fs, slot, have_state, ska)
 #define PSF_DEC_STATE_MODE(SH, LE_)      \
     do {                                 \
         if (mode == 0)                   \
             PSF_DEC_STATE(SH, LE_, 0);   \
         else if (mode == 1)              \
             PSF_DEC_STATE(SH, LE_, 1);   \
-        else                             \
+        else if (mode == 2)              \
             PSF_DEC_STATE(SH, LE_, 2);   \
+        else                             \
+            PSF_DEC_STATE(SH, LE_, 3);   \
     } while (0)
     if (L.shadow) {
         if constexpr (std::is_same_v<T, bf16_t>) {
@@ -999,7 +1012,7 @@ psf_status step_launch(const Problem &pb, const void *q, const void *k, const vo
 #undef PSF_DEC_STATE_MODE
 #undef PSF_DEC_STATE
     PSF_LAUNCH_CHECK();
-    if (!fuse) {
+    if (!fuse) {                                          // modes 0 and 3: the slices are added up here
         hipLaunchKernelGGL(dec_finish_kernel<T>, dim3((unsigned)pb.units), dim3(kThreads), 0, s, (const T *)q,
                            (const T *)k, (const T *)v, state, state + L.mq, state + L.mk, state + L.part, (T *)o, L,
                            pb.d, pb.dv, pb.p, pb.mcols, slot, le);
