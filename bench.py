@@ -516,6 +516,14 @@ def main():
                            "traffic": None if (args.noncausal or args.learned or args.local_sketch)
                            else MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
                            "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc if nm in fl}}
+    elif cfg["p"] == 4 and not args.learned:
+        # general fp32 kernels (plain vector arithmetic): the whole step against the fp32 vector peak
+        total = stage_flops(cfg, noncausal=args.noncausal, local_sketch=args.local_sketch)["total"]
+        achieved = total / (ms_per_step * 1e-3) / 1e12
+        out["tflops"] = achieved
+        out["roofline"] = {"kernel": "whole step", "bound": "alu", "achieved": achieved,
+                           "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": None}
     if not args.no_cpu_baseline and not args.learned and not args.local_sketch:   # oracle drivers used here: Gaussian sketches, exact in-block
         out["cpu_baseline"] = cpu_baseline_noncausal(cfg, q, k, v, G) if args.noncausal else cpu_baseline(cfg, q, k, v, G)
     print(json.dumps(out))
