@@ -50,7 +50,9 @@ typedef enum {
     PSF_ERR_UNSUPPORTED = 3, /* p not in {2,4,8,16}, feature count above PSF_MAX_FEATURES,
                                 unknown enum value, sizes beyond the stated limits          */
     PSF_ERR_WORKSPACE = 4,   /* workspace smaller than psf_workspace_bytes()                */
-    PSF_ERR_HIP = 5          /* a HIP call or kernel launch failed                          */
+    PSF_ERR_HIP = 5,         /* a HIP call or kernel launch failed                          */
+    PSF_ERR_ALIGNMENT = 6    /* a tensor is not 16-byte aligned where the bf16 MFMA kernels,
+                                which move 16-byte pieces, would run (psf_kernel_path == 1)  */
 } psf_status;
 
 typedef enum { PSF_F32 = 0, PSF_BF16 = 1 } psf_dtype;   /* storage type of Q, K, V, G, M, Phi, O */
@@ -130,7 +132,9 @@ psf_status psf_sketch(const psf_desc *desc, const void *X, const void *G,
  *   O    [batch, heads, n, dv]: device output in desc->dtype
  *   workspace: device scratch of at least psf_workspace_bytes(desc) bytes, 256-byte aligned;
  *              contents on entry are irrelevant, contents on return unspecified.
- * Accumulation is fp32 throughout; on the MFMA path the operands of the contractions
+ * Where psf_kernel_path(desc) == 1 the tensors must be 16-byte aligned (PSF_ERR_ALIGNMENT
+ * otherwise; the same holds for the non-causal, backward, saved-state and prompt entry points
+ * when they run the bf16 MFMA kernels).  Accumulation is fp32 throughout; on the MFMA path the operands of the contractions
  * (m(x), phi', Z_l, in-block weights) are rounded to bf16.
  */
 psf_status psf_causal_attn_fwd(const psf_desc *desc, const void *Q, const void *K, const void *V,

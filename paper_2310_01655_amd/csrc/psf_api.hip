@@ -1,6 +1,7 @@
 // libpsf entry points: descriptor validation, path selection, workspace sizing, dispatch.
 // The operations themselves are defined in include/psf.h (with their citations of
 // PolySketchFormer, arXiv 2310.01655); nothing here computes.
+#include <initializer_list>
 #include "psf_internal.h"
 
 namespace psf {
@@ -97,6 +98,14 @@ psf_status StageTimer::finish(float *ms, int cap, int *written)
     return st;
 }
 
+// The bf16 MFMA kernels read and write the caller's tensors in 16-byte pieces.
+static bool aligned16(std::initializer_list<const void *> tensors)
+{
+    for (const void *p : tensors)
+        if (((uintptr_t)p & 15u) != 0) return false;
+    return true;
+}
+
 static psf_status run_attn(const psf_desc *desc, const void *Q, const void *K, const void *V,
                            const void *G, void *O, void *ws, size_t ws_bytes, void *stream,
                            StageTimer *tm)
@@ -110,6 +119,7 @@ static psf_status run_attn(const psf_desc *desc, const void *Q, const void *K, c
     if (need > 0 && !ws) return PSF_ERR_NULL;
     if (ws_bytes < need) return PSF_ERR_WORKSPACE;
     if (((uintptr_t)ws & 255u) != 0) return PSF_ERR_WORKSPACE;
+    if (select_path(pb) == 1 && !aligned16({Q, K, V, G, O})) return PSF_ERR_ALIGNMENT;
     hipStream_t s = (hipStream_t)stream;
     return select_path(pb) == 1 ? mfma_attn(pb, Q, K, V, G, O, ws, s, tm)
                                 : general_attn(pb, Q, K, V, G, O, ws, s, tm);
@@ -127,6 +137,7 @@ static psf_status run_noncausal(const psf_desc *desc, const void *Q, const void 
     if (need > 0 && !ws) return PSF_ERR_NULL;
     if (ws_bytes < need) return PSF_ERR_WORKSPACE;
     if (((uintptr_t)ws & 255u) != 0) return PSF_ERR_WORKSPACE;
+    if (select_path(pb) == 1 && !aligned16({Q, K, V, G, O})) return PSF_ERR_ALIGNMENT;
     hipStream_t s = (hipStream_t)stream;
     return select_path(pb) == 1 ? mfma_attn_noncausal(pb, Q, K, V, G, O, ws, s, tm)
                                 : general_attn(pb, Q, K, V, G, O, ws, s, tm, true);
@@ -150,6 +161,7 @@ static psf_status run_bwd(const psf_desc *desc, const void *Q, const void *K, co
     if (!ws) return PSF_ERR_NULL;
     if (ws_bytes < need) return PSF_ERR_WORKSPACE;
     if (((uintptr_t)ws & 255u) != 0) return PSF_ERR_WORKSPACE;
+    if (mfma && !aligned16({Q, K, V, G, dO, dQ, dK, dV})) return PSF_ERR_ALIGNMENT;
     if (mfma) return mfma_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm);
     return general_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm);
 }
@@ -294,6 +306,7 @@ psf_status psf_causal_attn_fwd_save(const psf_desc *desc, const void *Q, const v
     if (!Q || !K || !V || !O || !save) return PSF_ERR_NULL;
     if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
     if (save_bytes < mfma_fwd_save_bytes(pb) || ((uintptr_t)save & 255u) != 0) return PSF_ERR_WORKSPACE;
+    if (!aligned16({Q, K, V, G, O})) return PSF_ERR_ALIGNMENT;
     return mfma_attn_fwd_save(pb, Q, K, V, G, O, save, (hipStream_t)hip_stream, nullptr);
 }
 
@@ -310,6 +323,7 @@ psf_status psf_causal_attn_bwd_saved(const psf_desc *desc, const void *Q, const 
     if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
     if (save_bytes < mfma_fwd_save_bytes(pb) || ((uintptr_t)save & 255u) != 0) return PSF_ERR_WORKSPACE;
     if (workspace_bytes < mfma_bwd_workspace_bytes(pb) || ((uintptr_t)workspace & 255u) != 0) return PSF_ERR_WORKSPACE;
+    if (!aligned16({Q, K, V, G, O, dO, dQ, dK, dV})) return PSF_ERR_ALIGNMENT;
     return mfma_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, workspace, (hipStream_t)hip_stream, nullptr, save, O);
 }
 
@@ -414,6 +428,8 @@ psf_status psf_decode_prefill(const psf_desc *desc, const void *K, const void *V
     const size_t need = decode_prefill_workspace_bytes(pb, n_prompt);
     if (need > 0 && !workspace) return PSF_ERR_NULL;
     if (workspace_bytes < need || (need > 0 && ((uintptr_t)workspace & 255u) != 0)) return PSF_ERR_WORKSPACE;
+    // (complete blocks of the prompt may go through the forward pass's MFMA kernels)
+    if (select_path(pb) == 1 && !aligned16({K, V, G})) return PSF_ERR_ALIGNMENT;
     return decode_prefill(pb, K, V, G, n_prompt, state, workspace, (hipStream_t)hip_stream);
 }
 
@@ -442,6 +458,7 @@ const char *psf_status_string(psf_status status)
     case PSF_ERR_SHAPE: return "invalid shape (non-positive size or n not a multiple of b)";
     case PSF_ERR_UNSUPPORTED: return "unsupported parameter";
     case PSF_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case PSF_ERR_ALIGNMENT: return "tensor not 16-byte aligned for the bf16 MFMA kernels";
     case PSF_ERR_HIP: return "HIP call or kernel launch failed";
     }
     return "unknown status";

@@ -211,9 +211,39 @@ def test_decode_entry_points_validate_on_the_host():
     assert L.psf_decode_prefill(ctypes.byref(exact), one, one, one, 5, one, 1 << 40, None, 0, None) == 3
 
 
+def test_misaligned_tensors_are_rejected_on_the_mfma_paths_before_any_launch():
+    """The bf16 MFMA kernels move 16-byte pieces: a tensor that is not 16-byte aligned gives
+    PSF_ERR_ALIGNMENT (6).  Every call below has exactly one misaligned tensor, so each returns
+    from validation; none reaches a launch."""
+    L = psf.lib()
+    d = psf.make_desc(1, 2, 1024, 64, 4, 64, 256, "bf16")
+    assert psf.kernel_path(d) == 1 and psf.bwd_kernel_path(d) == 3
+    ref = ctypes.byref(d)
+    ok, odd, big = ctypes.c_void_p(256), ctypes.c_void_p(258), 1 << 40
+    for hole in range(5):                                                    # Q, K, V, G, O
+        a = [ok] * 5
+        a[hole] = odd
+        assert L.psf_causal_attn_fwd(ref, *a, ok, big, None) == 6, hole
+        assert L.psf_noncausal_attn_fwd(ref, *a, ok, big, None) == 6, hole
+        assert L.psf_causal_attn_fwd_save(ref, *a, ok, big, None) == 6, hole
+    for hole in range(8):                                                    # Q, K, V, G, dO, dQ, dK, dV
+        a = [ok] * 8
+        a[hole] = odd
+        assert L.psf_causal_attn_bwd(ref, *a, ok, big, None) == 6, hole
+    for hole in range(3):                                                    # K, V, G of a prompt
+        a = [ok] * 3
+        a[hole] = odd
+        assert L.psf_decode_prefill(ref, *a, 512, ok, big, ok, big, None) == 6, hole
+    # the general fp32 kernels read element by element: no such requirement (NULL check comes first)
+    g = psf.make_desc(1, 1, 64, 16, 4, 8, 16, "f32")
+    assert psf.kernel_path(g) == 0
+    assert L.psf_causal_attn_fwd(ctypes.byref(g), odd, odd, odd, odd, None, ok, big, None) == 1
+    assert psf.status_string(6)
+
+
 def test_status_strings_and_stage_names():
     assert psf.status_string(0) == "ok"
-    assert all(psf.status_string(c) for c in range(6))
+    assert all(psf.status_string(c) for c in range(7))
     assert psf.lib().psf_stage_name(0, 0) == b"sketch_q"
     assert psf.lib().psf_stage_name(1, 3) == b"output"
 
