@@ -504,7 +504,11 @@ struct StateLds {
 // A 32-row MFMA tile is two segments that share beta (lanes x < 16 and x >= 16 of the A operand
 // carry different rows a), a wave owns NA = 2 tiles = four consecutive rows a of one beta, and
 // the waves are numbered range by range: beta = 0 first (4 waves), then 1 (8 waves), ...
-template <int R, int D, int NA, bool SYM, int TC>
+// NG = 2: eight waves, two per SIMD.  Waves w and w + 4 own the same tiles and take the even and
+// the odd 16-token steps, so the vector instructions that generate one wave's next fragment
+// run under the other wave's MFMAs; at a block boundary the two exchange partial sums through
+// LDS so that each holds (and stores) the whole of one of the two tiles.
+template <int R, int D, int NA, bool SYM, int TC, int NG>
 __device__ __forceinline__ void state_body(const float *__restrict__ M8, const bf16_t *__restrict__ V8,
                                            bf16_t *__restrict__ Zg, int n, int b, int t, int u, int grp,
                                            unsigned char *lds_base)
@@ -513,18 +517,19 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
     constexpr int AG = NA * 4 / NB;            // sketch rows a per workgroup (!SYM)
     constexpr int CT = D / 32;
     constexpr int NBUF = kStateRing;
-    constexpr int STEPS = TC / 16;
+    constexpr int STEPS = TC / 16 / NG;        // steps of one wave per chunk
     constexpr int PS = StateLds<R, D, TC>::PS;
     constexpr int M_BYTES = TC * R * 4, V_BYTES = TC * D * 2;
     constexpr int M_LDS = StateLds<R, D, TC>::M_LDS, BUF_BYTES = StateLds<R, D, TC>::BUF;
-    constexpr int DMA_PER_CHUNK = (M_BYTES + V_BYTES) / 16 / kWg;
+    constexpr int DMA_PER_CHUNK = (M_BYTES + V_BYTES) / 16 / (kWg * NG);
     constexpr int SEG = SYM ? 2 : 1;           // rows a per tile
-    static_assert(M_BYTES % 4096 == 0 && V_BYTES % 4096 == 0, "whole 4 KB pieces");
+    static_assert(M_BYTES % (4096 * NG) == 0 && V_BYTES % (4096 * NG) == 0, "whole 4 KB pieces per wave group");
     static_assert(NA <= 8, "DPP source lanes");
     static_assert(STEPS % 2 == 0, "operand ping-pong");
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
+    const int wave = wave8 & 3, wg2 = NG == 1 ? 0 : wave8 >> 2;  // tile owner; step parity (NG = 2)
     const int x = lane & 31, h = lane >> 5, n16 = lane & 15;
     // tiles of this wave: tile i holds the sketch rows a0 + i * SEG + (0..SEG-1); bcol is the
     // column b' of lane x
@@ -556,26 +561,32 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
 
     // Ring slots are compile-time constants (the chunk loop dispatches on the slot), so every
     // LDS address below is a per-lane base plus an immediate and the copies take a scalar base.
-    const uint32_t copy_off = (uint32_t)tid * 16;             // lane's byte offset inside a 4 KB piece
+    const uint32_t copy_off = (uint32_t)(tid & 255) * 16;     // lane's byte offset inside a 4 KB piece
     const uint32_t lds0 = lds_address(lds_base);
     auto stage = [&](auto slot_tag, int chunk) {              // straight copies: global layout == LDS layout
         constexpr int SLOT = decltype(slot_tag)::value;
         const unsigned char *sm = (const unsigned char *)(gm + (size_t)chunk * TC * R);
         const unsigned char *sv = (const unsigned char *)(gv + (size_t)chunk * TC * D);
         const uint32_t dst = lds0 + SLOT * BUF_BYTES;
+        // (the wave groups share the pieces: group g copies pieces g, g + NG, ...)
 #pragma unroll
-        for (int q = 0; q < M_BYTES / 16 / kWg; ++q)
+        for (int qq = 0; qq < M_BYTES / 4096 / NG; ++qq) {
+            const int q = qq * NG + wg2;
             dma16_sbase(sm + q * 4096, copy_off, dst + StateLds<R, D, TC>::m_piece(q, wave));
+        }
 #pragma unroll
-        for (int q = 0; q < V_BYTES / 16 / kWg; ++q)
+        for (int qq = 0; qq < V_BYTES / 4096 / NG; ++qq) {
+            const int q = qq * NG + wg2;
             dma16_sbase(sv + q * 4096, copy_off, dst + M_LDS + q * 4096 + wave * 1024);
+        }
     };
-    const unsigned char *lane_b = lds_base + (h * 2 * PS + bcol * 16);
-    const unsigned char *lane_a = lds_base + ((h * 2 + q_src) * PS + a_src * 16);
-    const unsigned char *lane_v = lds_base + M_LDS + ((h * D + x) * 16);
+    // step S of this wave is step NG * S + wg2 of the chunk: the parity sits in the lane bases
+    const unsigned char *lane_b = lds_base + (h * 2 * PS + bcol * 16) + wg2 * 4 * PS;
+    const unsigned char *lane_a = lds_base + ((h * 2 + q_src) * PS + a_src * 16) + wg2 * 4 * PS;
+    const unsigned char *lane_v = lds_base + M_LDS + ((h * D + x) * 16) + wg2 * 2 * D * 16;
     auto load_ops = [&](auto slot_tag, auto step_tag) {
         constexpr int OFF = decltype(slot_tag)::value * BUF_BYTES;
-        constexpr int S = decltype(step_tag)::value;          // octet 2 S + h
+        constexpr int S = decltype(step_tag)::value * NG;     // octet 2 (S + wg2) + h
         StateOps<CT> o;
         const f32x4 b_lo = *(const f32x4 *)(lane_b + OFF + S * 4 * PS);
         const f32x4 b_hi = *(const f32x4 *)(lane_b + OFF + S * 4 * PS + PS);
@@ -587,12 +598,54 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
         return o;
     };
     auto snapshot = [&](int l) {
+        if constexpr (NG == 2) {
+            // The two waves of a tile pair exchange partial sums through LDS, one value-column
+            // tile per round: the wave of the even steps ends up with the whole of tile 0 and
+            // keeps its running prefix, the other one with tile 1; each stores its tile below
+            // and restarts the other tile from zero.  Buffer behind the ring:
+            // [group][wave][register quad][lane] x 16 bytes.
+            static_assert(NA == 2, "one tile per wave group");
+            f32x4 *xb = (f32x4 *)(lds_base + NBUF * BUF_BYTES);
+            f32x4 *mine = xb + ((wg2 * 4 + wave) * 4) * 64 + lane;
+            const f32x4 *theirs = xb + (((wg2 ^ 1) * 4 + wave) * 4) * 64 + lane;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                // (the tile this wave gives away: index 1 - wg2)
+                auto put = [&](const f32x16 &t) {
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4)
+                        mine[v4 * 64] = f32x4{t[4 * v4], t[4 * v4 + 1], t[4 * v4 + 2], t[4 * v4 + 3]};
+                };
+                if (wg2) put(acc[0][ct]);
+                else put(acc[1][ct]);
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                asm volatile("" ::: "memory");
+                auto take = [&](f32x16 &keep, f32x16 &given) {
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        const f32x4 q = theirs[v4 * 64];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) keep[4 * v4 + j] += q[j];
+                    }
+                    given = f32x16{0};
+                };
+                if (wg2) take(acc[1][ct], acc[0][ct]);
+                else take(acc[0][ct], acc[1][ct]);
+                if (ct + 1 < CT) {
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+                }
+            }
+        }
         // Z_{l+1} = sum over blocks 0..l, stored [a][b'/8][c][8] bf16.  Z[a][b'] = Z[b'][a]
         // (phi' = m (x) m), so the output kernel only contracts b' >= a: entries with b' > a are
         // stored doubled, b' < a as zero.
         bf16_t *z = Zg + ((size_t)u * (t - 1) + l) * R * R * D;
 #pragma unroll
-        for (int i = 0; i < NA; ++i)
+        for (int i = 0; i < NA; ++i) {
+            if (NG == 2 && i != wg2) continue;             // wave-uniform: the tile this wave holds in full
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
@@ -608,6 +661,7 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
                     }
                     *(bf16x4 *)&z[(((size_t)a * (R / 8) + bq0 / 8) * D + 32 * ct + x) * 8 + 4 * h] = cvt4(q4);
                 }
+        }
     };
 
     StateOps<CT> ops[2];
@@ -653,18 +707,18 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
 // TC tokens per staged chunk, kStateRing chunks per workgroup (one less in flight to cover the
 // memory latency); OCC workgroups per CU: grids that exceed one workgroup per CU run two per CU
 // with half-size chunks.
-template <int R, int D, int NA, bool SYM, int TC, int OCC>
-__global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8,
-                                               const bf16_t *__restrict__ V8,
-                                               bf16_t *__restrict__ Zg, int n, int b, int t,
-                                               int units)
+template <int R, int D, int NA, bool SYM, int TC, int NG>
+__device__ __forceinline__ void state_workgroup(const float *__restrict__ M8, const bf16_t *__restrict__ V8,
+                                                bf16_t *__restrict__ Zg, int n, int b, int t, int units)
 {
     constexpr int NBUF = kStateRing;
     constexpr int BUF_BYTES = StateLds<R, D, TC>::BUF, M_LDS = StateLds<R, D, TC>::M_LDS;
-    constexpr int DMA_PER_CHUNK = (TC * R * 4 + TC * D * 2) / 16 / kWg;
+    constexpr int NTHR = kWg * NG;
+    constexpr int DMA_PER_CHUNK = (TC * R * 4 + TC * D * 2) / 16 / NTHR;
     constexpr int AG = NA * 4 / (R / 32);
     static_assert(!SYM || NA == 2, "tile deal of the symmetric variant");
-    __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF * BUF_BYTES];
+    // NG = 2: 32 KB behind the ring for the exchange of partial sums at block boundaries
+    __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF * BUF_BYTES + (NG == 2 ? 8 * 16 * 64 * 4 : 0)];
 
     // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
     // contiguous range of (unit, group) pairs; the groups of one unit then share one L2.
@@ -678,7 +732,8 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
     // indices past the end are clamped: the copies are redundant but keep the in-flight count,
     // and with it the waits, the same in every iteration.
     {
-        const int tid = threadIdx.x, wave = tid >> 6;
+        const int tid = threadIdx.x & 255, wave = tid >> 6;
+        const int wg2 = NG == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 8);
         const int chunks = (t - 1) * (b / TC);
         const float *gm = M8 + (size_t)u * n * R;
         const bf16_t *gv = V8 + (size_t)u * n * D;
@@ -687,18 +742,41 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
             const int chunk = min(c, chunks - 1);
             unsigned char *dst = lds + c * BUF_BYTES;
 #pragma unroll
-            for (int q = 0; q < TC * R * 4 / 16 / kWg; ++q)
+            for (int qq = 0; qq < TC * R * 4 / 4096 / NG; ++qq) {
+                const int q = qq * NG + wg2;
                 dma16(gm + (size_t)chunk * TC * R + (size_t)(q * kWg + tid) * 4,
                       dst + StateLds<R, D, TC>::m_piece(q, wave));
+            }
 #pragma unroll
-            for (int q = 0; q < TC * D * 2 / 16 / kWg; ++q)
+            for (int qq = 0; qq < TC * D * 2 / 4096 / NG; ++qq) {
+                const int q = qq * NG + wg2;
                 dma16(gv + (size_t)chunk * TC * D + (size_t)(q * kWg + tid) * 8,
                       dst + M_LDS + (size_t)(q * kWg + wave * 64) * 16);
+            }
         }
         wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
         __syncthreads();
     }
-    state_body<R, D, NA, SYM, TC>(M8, V8, Zg, n, b, t, u, grp, lds);
+    state_body<R, D, NA, SYM, TC, NG>(M8, V8, Zg, n, b, t, u, grp, lds);
+}
+
+template <int R, int D, int NA, bool SYM, int TC, int OCC>
+__global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8,
+                                               const bf16_t *__restrict__ V8,
+                                               bf16_t *__restrict__ Zg, int n, int b, int t,
+                                               int units)
+{
+    state_workgroup<R, D, NA, SYM, TC, 1>(M8, V8, Zg, n, b, t, units);
+}
+
+// The symmetric deal with eight waves, two per SIMD (see state_body), one workgroup per CU.
+template <int R, int D, int TC>
+__global__ __launch_bounds__(2 * kWg, 1) void k_state_two_waves(const float *__restrict__ M8,
+                                                                 const bf16_t *__restrict__ V8,
+                                                                 bf16_t *__restrict__ Zg, int n, int b, int t,
+                                                                 int units)
+{
+    state_workgroup<R, D, 2, true, TC, 2>(M8, V8, Zg, n, b, t, units);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1684,7 +1762,13 @@ psf_status launch_state(const Problem &pb, const float *M8, const bf16_t *V8, bf
     const unsigned grid_sym = (unsigned)(pb.units * GROUPS);
     if (D == 64 && (R == 64 || grid_sym > 512)) {
         if constexpr (D == 64) {
-            if (grid_sym <= 256)
+            // One block only (no mask, or the prompt of a decode): eight waves, two per SIMD,
+            // 8 % faster per token; with a snapshot every block the exchange and the stalled
+            // ring after the stores cost more than that.
+            if (grid_sym <= 256 && pb.t == 2)
+                hipLaunchKernelGGL((k_state_two_waves<R, D, 64>), dim3(grid_sym), dim3(2 * kWg), 0, s, M8, V8, Zg,
+                                   pb.n, pb.b, pb.t, pb.units);
+            else if (grid_sym <= 256)
                 hipLaunchKernelGGL((k_state<R, D, 2, true, 64, 1>), dim3(grid_sym), dim3(kWg), 0, s, M8, V8, Zg,
                                    pb.n, pb.b, pb.t, pb.units);
             else
