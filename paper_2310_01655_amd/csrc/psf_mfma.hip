@@ -16,7 +16,8 @@
 //                  written to memory.  A bf16 snapshot Z_{l+1} is stored after each block, so
 //                  the exclusive scan over blocks (Section 3.1) costs nothing extra.  Z is
 //                  symmetric in its two sketch indices; for d = 64 only the half the output
-//                  kernel reads is computed.
+//                  kernel reads is computed.  k_state_two_waves: the same with two waves per
+//                  SIMD that split the token steps, for calls with a single block per unit.
 //   k_out          per 256-token tile: exact in-block weights lt((Q_l K_l^T)^p) [V_l | 1]
 //                  (Section 3.2) kept in registers, plus phi'(Q_l) Z_l with phi'(q_i) expanded
 //                  in registers as the MFMA operand, then the division by 1 + denominator
