@@ -30,7 +30,7 @@ def draw_desc(seed, max_width=40, max_r=24, degrees=(2, 4, 8), max_blocks=6, max
              local=int(rng.choice([psf.LOCAL_EXACT, psf.LOCAL_SKETCH])),
              per_head=bool(rng.integers(0, 2)))
     # one case in four with learned sketches (Algorithm 2); p = 2 has no sketch to learn
-    c["learned"] = bool(learned_too and c["p"] > 2 and rng.integers(0, 4) == 0)
+    c["learned"] = bool(learned_too and 2 < c["p"] <= 8 and rng.integers(0, 4) == 0)
     if c["learned"]:
         c["r"] = min(c["r"], 12)                 # hidden width 8 r: keeps the oracle's network loops short
     return c
@@ -133,3 +133,22 @@ def test_decode_random_descriptor(seed):
     if rows:
         want = oracle_rows(c, q, k, v, G, rows=rows)
         print(c, n_prompt, assert_close(out.float().cpu().numpy(), want, c["dtype"], "decode %s" % c))
+
+
+@pytest.mark.parametrize("seed", range(5000, 5024))
+def test_sketch_entry_point_random_descriptor(seed):
+    """psf_sketch on a random descriptor: m(x) of Algorithm 1 (or Algorithm 2) and its self tensor
+    product phi'(x) = m(x) (x) m(x), row by row."""
+    c = draw_desc(seed, degrees=(2, 4, 8, 16), max_blocks=3)
+    q, _, _, G, desc = draw_inputs(c, seed)
+    dev = torch.device("cuda:0")
+    M, Phi = psf.psf_sketch(desc, q.to(dev), G.to(dev) if G is not None else None, want_m=True, want_phi=True)
+    torch.cuda.synchronize()
+    for bi in range(c["batch"]):
+        for h in range(c["heads"]):
+            g = None if G is None else as_f64(G[h if G.shape[0] > 1 else 0])
+            x = as_f64(q[bi, h])
+            m = oracle.sketch_learned(x, g, c["r"], c["p"]) if c["learned"] else oracle.sketch(x, g, c["r"], c["p"])
+            assert_close_scaled(M[bi, h].float().cpu().numpy(), m, c["dtype"], "m %s" % c)
+            assert_close_scaled(Phi[bi, h].float().cpu().numpy(), oracle.self_tensor(m), c["dtype"], "phi' %s" % c)
+    print(c)
