@@ -1766,10 +1766,12 @@ psf_status launch_state(const Problem &pb, const float *M8, const bf16_t *V8, bf
             // One block only (no mask, or the prompt of a decode): eight waves, two per SIMD,
             // 8 % faster per token; with a snapshot every block the exchange and the stalled
             // ring after the stores cost more than that.
-            if (grid_sym <= 256 && pb.t == 2)
-                hipLaunchKernelGGL((k_state_two_waves<R, D, 64>), dim3(grid_sym), dim3(2 * kWg), 0, s, M8, V8, Zg,
-                                   pb.n, pb.b, pb.t, pb.units);
-            else if (grid_sym <= 256)
+            // (r = 32 reaches this branch with large grids only.)
+            if (R == 64 && grid_sym <= 256 && pb.t == 2) {
+                if constexpr (R == 64)
+                    hipLaunchKernelGGL((k_state_two_waves<R, D, 64>), dim3(grid_sym), dim3(2 * kWg), 0, s, M8, V8,
+                                       Zg, pb.n, pb.b, pb.t, pb.units);
+            } else if (grid_sym <= 256)
                 hipLaunchKernelGGL((k_state<R, D, 2, true, 64, 1>), dim3(grid_sym), dim3(kWg), 0, s, M8, V8, Zg,
                                    pb.n, pb.b, pb.t, pb.units);
             else
