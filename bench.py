@@ -46,7 +46,9 @@ def stage_flops(cfg, learned=False, noncausal=False, local_sketch=False):
     noncausal: one state over all n keys, applied to all n queries, no in-block pairs."""
     U = cfg["batch"] * cfg["heads"]
     n, d, r, b, p = cfg["n"], cfg["d"], cfg["r"], cfg["b"], cfg["p"]
-    sketch = 2 * (8 * n * d * r if p == 4 else 16 * n * d * r + 8 * n * r * r)   # Q and K
+    # Algorithm 1 on both sides: p/2 projections of 2 d r flops per row for Q and for K (8 n d r
+    # at p = 4), plus the two r x r projections per side of the second level at p = 8
+    sketch = 8 * n * d * r if p == 4 else 16 * n * d * r + 8 * n * r * r
     if learned:          # p - 2 networks per row: four dense layers each (Appendix D)
         net = lambda win: 2 * (win * 8 * r + 24 * r * r)
         sketch = 2 * n * ((p // 2) * net(d) + max(p // 2 - 2, 0) * net(r))
@@ -98,15 +100,15 @@ def bwd_stage_flops(cfg):
     n, d, r, b, p = cfg["n"], cfg["d"], cfg["r"], cfg["b"], cfg["p"]
     F, kc = r * r, d + 1
     pairs = n * (b + 1) // 2
-    sketch = 8 * n * d * r if p == 4 else 16 * n * d * r + 8 * n * r * r      # one side: Q or K
+    sketch = 8 * n * d * r if p == 4 else 16 * n * d * r + 8 * n * r * r      # Algorithm 1 for Q and K
     cross = 2 * (n - b) * F * kc                                             # one state-sized contraction
     f = {
-        "sketches": U * 2 * sketch,
+        "sketches": U * sketch,
         "forward_rows": U * (2 * cross + pairs * 2 * (d + kc)),              # H_l, phi^T Z_l, in-block rows
         "reverse_states": U * cross,
         "query_side": U * (cross + 4 * (n - b) * F + pairs * 2 * (kc + 2 * d)),
         "key_side": U * (2 * cross + 4 * (n - b) * F + pairs * 2 * (kc + 2 * d + d)),
-        "sketch_gradient": U * 2 * 2 * sketch,                               # recompute + transposed products
+        "sketch_gradient": U * 2 * sketch,                                   # recompute + transposed products
     }
     f["total"] = sum(f.values())
     return f
@@ -125,7 +127,7 @@ def bwd_stage_flops_mfma(cfg):
         "mirror_states": U * cross,
         "in_block_and_dv": U * (pairs * 2 * 7 * d + cross),                  # 3 + 4 tile products per pair; phi'(K)^T R_l
         # dm(q), dm(k) with their S / Rc terms; projections again + transposed products
-        "cross_block_and_sketch_gradient": U * (2 * cross + 8 * (n - b) * F + 2 * 16 * n * d * r),
+        "cross_block_and_sketch_gradient": U * (2 * cross + 8 * (n - b) * F + 16 * n * d * r),
     }
     f["total"] = sum(f.values())
     return f
@@ -334,7 +336,7 @@ def run_decode(args, psf, inputs, torch):
     out = {
         "metric": "causal_polysketch_attention_decode_tokens_per_s", "value": cfg["batch"] / (ms_per_step * 1e-3),
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg["dtype"], "data": "synthetic",
         "config": {"workload": "decode_b%d" % cfg["batch"], "pass": "decode", "batch": cfg["batch"], "heads": cfg["heads"],
                    "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"], "storage": cfg["dtype"],
                    "first_timed_position": first_timed, "state_bytes": psf.decode_state_bytes(desc),

@@ -261,12 +261,14 @@ psf_status psf_decode_step(const psf_desc *desc, const void *q, const void *k, c
  *   K [batch, heads, n_prompt, d], V [batch, heads, n_prompt, dv]: device, desc->dtype;
  *   0 <= n_prompt <= desc->n (else PSF_ERR_SHAPE); G as for psf_decode_step.
  *   workspace: psf_decode_prefill_workspace_bytes(desc, n_prompt) bytes of device memory,
- *   256-byte aligned (null allowed when that is zero).  Where psf_kernel_path(desc) == 1 with
- *   p in {4, 8} (learned sketches: p = 4 and d = 64), the complete blocks of the prompt go through
- *   the forward path's sketch and state kernels (their buffers are the workspace) and the
- *   state starts from their bf16 result, as the forward pass's own prefix states do; learned
- *   sketches need the fp32 sketches of all prompt keys; otherwise the workspace is empty and
- *   the prompt is folded block by block.
+ *   256-byte aligned (null allowed when that is zero).  For bf16 storage with d = dv in
+ *   {64, 128}, r in {32, 64}, p in {4, 8} (learned sketches: p = 4 and d = 64) and at least one
+ *   complete block whose tokens are a multiple of 256 -- whatever b % 256 and the in-block rule
+ *   are -- the complete blocks of the prompt go through the forward path's sketch and state
+ *   kernels (their buffers are the workspace; K, V and G must then be 16-byte aligned, else
+ *   PSF_ERR_ALIGNMENT) and the state starts from their bf16 result, as the forward pass's own
+ *   prefix states do; learned sketches need the fp32 sketches of all prompt keys; otherwise
+ *   the workspace is empty and the prompt is folded block by block.
  * Nothing is allocated and nothing synchronises; everything is enqueued on hip_stream.
  */
 size_t psf_decode_prefill_workspace_bytes(const psf_desc *desc, int32_t n_prompt);

@@ -49,7 +49,9 @@ psf_status make_problem(const psf_desc *desc, Problem *out)
         pb.F = (long long)pb.mcols * pb.mcols;
         if (pb.F > PSF_MAX_FEATURES) return PSF_ERR_UNSUPPORTED;
     }
-    pb.learned = desc->learned != 0;
+    // p = 2 is the base case m(x) = x of both algorithms: no network is applied, so a request
+    // for learned sketches of that degree is the plain one
+    pb.learned = desc->learned != 0 && desc->p > 2;
     pb.g_len = (pb.exact_feat || desc->p == 2) ? 0
                : pb.learned ? psf_learned_len(desc->d, pb.r, desc->p) : psf_g_len(desc->d, pb.r, desc->p);
     *out = pb;
@@ -70,9 +72,18 @@ int select_path(const Problem &pb)
 
 psf_status StageTimer::begin(hipStream_t s)
 {
-    on = true; stream = s; count = 0;
-    for (int i = 0; i <= kMax; ++i) PSF_HIP_TRY(hipEventCreate(&ev[i]));
-    PSF_HIP_TRY(hipEventRecord(ev[0], stream));
+    on = false; stream = s; count = 0;
+    for (int i = 0; i <= kMax; ++i) {
+        if (hipEventCreate(&ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);   // nothing is left behind
+            return PSF_ERR_HIP;
+        }
+    }
+    if (hipEventRecord(ev[0], stream) != hipSuccess) {
+        for (int j = 0; j <= kMax; ++j) (void)hipEventDestroy(ev[j]);
+        return PSF_ERR_HIP;
+    }
+    on = true;
     return PSF_OK;
 }
 
@@ -428,8 +439,9 @@ psf_status psf_decode_prefill(const psf_desc *desc, const void *K, const void *V
     const size_t need = decode_prefill_workspace_bytes(pb, n_prompt);
     if (need > 0 && !workspace) return PSF_ERR_NULL;
     if (workspace_bytes < need || (need > 0 && ((uintptr_t)workspace & 255u) != 0)) return PSF_ERR_WORKSPACE;
-    // (complete blocks of the prompt may go through the forward pass's MFMA kernels)
-    if (select_path(pb) == 1 && !aligned16({K, V, G})) return PSF_ERR_ALIGNMENT;
+    // (the hand-over has its own rule for when the forward pass's MFMA kernels take the complete
+    // blocks of the prompt: it does not depend on b % 256 or on the in-block rule)
+    if (decode_prefill_uses_mfma(pb, n_prompt) && !aligned16({K, V, G})) return PSF_ERR_ALIGNMENT;
     return decode_prefill(pb, K, V, G, n_prompt, state, workspace, (hipStream_t)hip_stream);
 }
 

@@ -1072,6 +1072,8 @@ static PrefillPlan prefill_plan(const Problem &pb, int n_prompt)
 
 size_t decode_prefill_workspace_bytes(const Problem &pb, int n_prompt) { return prefill_plan(pb, n_prompt).total; }
 
+bool decode_prefill_uses_mfma(const Problem &pb, int n_prompt) { return prefill_fast_tokens(pb, n_prompt) > 0; }
+
 template <typename T>
 static psf_status prefill_launch(const Problem &pb, const void *K, const void *V, const void *G, int n_prompt,
                                  float *state, void *ws, hipStream_t s)

@@ -81,6 +81,9 @@ psf_status decode_step(const Problem &pb, const void *q, const void *k, const vo
 // State after the first n_prompt tokens (K, V: [units][n_prompt][d | dv]), as if they had been fed
 // one by one; ws: decode_prefill_workspace_bytes.
 size_t decode_prefill_workspace_bytes(const Problem &pb, int n_prompt);
+// true when the complete blocks of the prompt go through the forward path's bf16 MFMA kernels
+// (which move the caller's K, V, G in 16-byte pieces)
+bool decode_prefill_uses_mfma(const Problem &pb, int n_prompt);
 psf_status decode_prefill(const Problem &pb, const void *K, const void *V, const void *G, int n_prompt,
                           void *state, void *ws, hipStream_t s);
 

@@ -234,6 +234,15 @@ def test_misaligned_tensors_are_rejected_on_the_mfma_paths_before_any_launch():
         a = [ok] * 3
         a[hole] = odd
         assert L.psf_decode_prefill(ref, *a, 512, ok, big, ok, big, None) == 6, hole
+    # the hand-over takes the MFMA kernels for complete blocks whatever b % 256 and the in-block
+    # rule are, i.e. also where the forward call itself runs the general kernels
+    for dd in (psf.make_desc(1, 2, 1024, 64, 4, 64, 128, "bf16"),
+               psf.make_desc(1, 2, 1024, 128, 4, 32, 256, "bf16", local=psf.LOCAL_SKETCH)):
+        assert psf.kernel_path(dd) == 0
+        for hole in range(3):
+            a = [ok] * 3
+            a[hole] = odd
+            assert L.psf_decode_prefill(ctypes.byref(dd), *a, 512, ok, big, ok, big, None) == 6, hole
     # the general fp32 kernels read element by element: no such requirement (NULL check comes first)
     g = psf.make_desc(1, 1, 64, 16, 4, 8, 16, "f32")
     assert psf.kernel_path(g) == 0

@@ -191,6 +191,15 @@ def test_base_case_degree_two_on_the_mfma_path(b, local):
     O2 = psf.psf_causal_attn_fwd(desc_r, q.cuda(), k.cuda(), v.cuda(), None)
     torch.cuda.synchronize()
     assert torch.equal(O2.float().cpu(), got)
+    # learned sketches of degree 2 are the same base case (no network is applied): bit-equal
+    desc_l = psf.make_desc(1, 2, 1024, 64, 2, 64, b, "bf16", local=local, learned=True)
+    assert psf.kernel_path(desc_l) == 1
+    O3 = psf.psf_causal_attn_fwd(desc_l, q.cuda(), k.cuda(), v.cuda(), None)
+    O4 = psf.psf_noncausal_attn_fwd(desc_l, q.cuda(), k.cuda(), v.cuda(), None)
+    O5 = psf.psf_noncausal_attn_fwd(desc, q.cuda(), k.cuda(), v.cuda(), None)
+    torch.cuda.synchronize()
+    assert torch.equal(O3.float().cpu(), got)
+    assert torch.equal(O4, O5)
 
 
 def test_forward_replays_from_a_captured_graph():
