@@ -165,6 +165,8 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     qd, kd, vd, Gd, dOd = (x.to(dev) for x in (q, k, v, G, dO))
     ws = psf.alloc_bwd_workspace(desc, dev)
     stream = torch.cuda.current_stream()
+    ramp_steps = ramp(lambda: psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream),
+                      args.ramp_ms, torch)
     for _ in range(args.warmup):
         psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream)
     torch.cuda.synchronize()
@@ -188,7 +190,8 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     out = {
         "metric": "causal_polysketch_attention_bwd_tokens_per_s",
         "value": cfg["batch"] * cfg["n"] * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "ramp_steps": ramp_steps,
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if mfma else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "pass": "bwd", "batch": cfg["batch"], "heads": cfg["heads"],
                    "n": cfg["n"], "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
@@ -225,6 +228,7 @@ def run_train(args, cfg, psf, inputs, torch, q, k, v, G, idx):
         psf.psf_causal_attn_fwd_save(desc, qd, kd, vd, Gd, O=O, save=save, stream=stream)
         psf.psf_causal_attn_bwd_saved(desc, qd, kd, vd, Gd, O, dOd, save, workspace=ws, stream=stream, out=grads)
 
+    ramp_steps = ramp(step, args.ramp_ms, torch)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -240,7 +244,8 @@ def run_train(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     out = {
         "metric": "causal_polysketch_attention_fwd_bwd_tokens_per_s",
         "value": cfg["batch"] * cfg["n"] * args.steps / elapsed, "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "ramp_steps": ramp_steps,
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "pass": "train (forward with saved states + backward)",
                    "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"], "d": cfg["d"], "p": cfg["p"],
@@ -366,6 +371,55 @@ def run_decode(args, psf, inputs, torch):
     print(json.dumps(out))
 
 
+def ramp(step, ramp_ms, torch):
+    """Runs `step` untimed until ramp_ms of wall time have passed; returns the count."""
+    count = 0
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < ramp_ms:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+        count += 8
+    return count
+
+
+def event_times(step, steps, torch, stream):
+    """Sorted per-step milliseconds of `steps` calls, each between two events on `stream`."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    ev[0].record(stream)
+    for i in range(steps):
+        step()
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    return sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+
+
+def context_peaks(psf, torch, stream):
+    """What this GPU sustains on two plain loops, measured in this run (context for the roofline
+    fractions, which keep the published peaks as divisors): a pure bf16 MFMA loop on all compute
+    units and a 256 MiB device-to-device copy (read + write bytes)."""
+    dev = torch.device("cuda:0")
+    wgs, iters = 2048, 4096
+    sink = torch.empty(wgs * 256, dtype=torch.float32, device=dev)
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    best = {"mfma": 0.0, "copy": 0.0}
+    for _ in range(3):
+        e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        e0.record(stream)
+        flops = psf.psf_probe_mfma_loop(wgs, iters, sink, stream=stream)
+        e1.record(stream)
+        dst.copy_(src)
+        e2.record(stream)
+        torch.cuda.synchronize()
+        best["mfma"] = max(best["mfma"], flops / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+        best["copy"] = max(best["copy"], 2 * src.numel() / (e1.elapsed_time(e2) * 1e-3) / 1e9)
+    return {"mfma_bf16_loop_tflops": best["mfma"], "published_mfma_bf16_tflops": MFMA_BF16_PEAK_TFLOPS,
+            "device_copy_gbs": best["copy"], "published_hbm_gbs": HBM_PEAK_GBS,
+            "note": "best of 3; the MFMA loop holds the chip at full matrix load for ~10 ms, where its clock "
+                    "settles below the boost clock the published peak assumes"}
+
+
 def cpu_baseline(cfg, q, k, v, G, rows_per_unit=16384):
     """The float64 oracle, as it stands, on a bounded sample: `cores` units, a uniform random
     sample of rows of each.  The full-unit time is estimated as sketch time + row time * n/rows
@@ -418,6 +472,11 @@ def main():
     ap.add_argument("--decode-batch", type=int, default=64,
                     help="sequences decoded together by --pass decode (12 heads each)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-context-peaks", action="store_true",
+                    help="skip the MFMA-loop and device-copy measurements printed as context")
+    ap.add_argument("--ramp-ms", type=float, default=400.0,
+                    help="untimed steps run for this long before the warm-up steps, so that the clock has "
+                         "settled (reported as ramp_steps; 0 disables)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also issue one 256 MiB device copy, so that a counter run can scale "
                          "FETCH_SIZE / WRITE_SIZE by a transfer of known size")
@@ -474,16 +533,22 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    step = lambda: fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
+    # Untimed ramp: the GPU clock takes a few hundred milliseconds of load to settle after the
+    # idle time of start-up (uploads, allocation); the same steps, counted and reported.
+    ramp_steps = ramp(step, args.ramp_ms, torch)
     for _ in range(args.warmup):
-        fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        fwd(desc, qd, kd, vd, Gd, O=O, workspace=ws, stream=stream)
+        step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
     tokens = cfg["batch"] * cfg["n"]
+    # the same K steps once more, each bracketed by events on the launch stream: median
+    per_step = event_times(step, args.steps, torch, stream)
 
     # per-kernel durations: HIP events recorded by the library on the launch stream
     reps = max(3, min(args.steps, 10))
@@ -498,7 +563,9 @@ def main():
         "metric": ("noncausal" if args.noncausal else "causal") + "_polysketch_attention_fwd_tokens_per_s",
         "value": tokens * args.steps / elapsed,
         "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "ms_per_step_median": per_step[len(per_step) // 2],
+        "ms_per_step_min": per_step[0], "ramp_steps": ramp_steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if path == 1 else "f32", "data": "synthetic",
         "config": {"workload": args.workload, "sketch": "learned" if args.learned else "gaussian",
                    "mask": "none" if args.noncausal else "causal",
@@ -526,6 +593,8 @@ def main():
         out["roofline"] = {"kernel": "whole step", "bound": "alu", "achieved": achieved,
                            "peak": FP32_VALU_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": achieved / FP32_VALU_PEAK_TFLOPS, "traffic": None}
+    if not args.no_context_peaks:
+        out["context_peaks"] = context_peaks(psf, torch, stream)
     if not args.no_cpu_baseline and not args.learned and not args.local_sketch:   # oracle drivers used here: Gaussian sketches, exact in-block
         out["cpu_baseline"] = cpu_baseline_noncausal(cfg, q, k, v, G) if args.noncausal else cpu_baseline(cfg, q, k, v, G)
     print(json.dumps(out))

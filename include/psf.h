@@ -276,6 +276,16 @@ psf_status psf_decode_prefill(const psf_desc *desc, const void *K, const void *V
                               int32_t n_prompt, void *state, size_t state_bytes, void *workspace,
                               size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Measurement aid (not part of the attention path): launches `workgroups` workgroups of four
+ * wavefronts, each wavefront issuing iters x 8 independent v_mfma_f32_32x32x16_bf16 on non-zero
+ * operands, i.e. workgroups x 4 x iters x 8 x 32768 flops in all.  A benchmark times it with
+ * events on `hip_stream` to print the rate the matrix cores of this GPU sustain under load
+ * beside the published peak.  sink: device memory of at least workgroups x 256 floats (written).
+ * Nothing is allocated and nothing synchronises.
+ */
+psf_status psf_probe_mfma_loop(int32_t workgroups, int32_t iters, void *sink, void *hip_stream);
+
 const char *psf_status_string(psf_status status);
 
 #ifdef __cplusplus

@@ -24,7 +24,7 @@ EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_le
            "psf_noncausal_attn_fwd_timed", "psf_fwd_save_bytes", "psf_causal_attn_fwd_save",
            "psf_causal_attn_bwd_saved", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
            "psf_causal_attn_bwd_timed", "psf_decode_state_bytes", "psf_decode_reset",
-           "psf_decode_step", "psf_decode_prefill_workspace_bytes", "psf_decode_prefill")
+           "psf_decode_step", "psf_decode_prefill_workspace_bytes", "psf_decode_prefill", "psf_probe_mfma_loop")
 
 
 class PsfDesc(ctypes.Structure):
@@ -104,6 +104,8 @@ def lib():
         L.psf_decode_prefill_workspace_bytes.argtypes = [dp, ctypes.c_int32]
         L.psf_decode_prefill.restype = ctypes.c_int
         L.psf_decode_prefill.argtypes = [dp, vp, vp, vp, ctypes.c_int32, vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+        L.psf_probe_mfma_loop.restype = ctypes.c_int
+        L.psf_probe_mfma_loop.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp]
         L.psf_stage_name.restype = ctypes.c_char_p
         L.psf_stage_name.argtypes = [ctypes.c_int, ctypes.c_int32]
         L.psf_status_string.restype = ctypes.c_char_p
@@ -429,3 +431,14 @@ def psf_decode_step(desc, q, k, v, G, pos, state, o=None, stream=None):
     if st != PSF_OK:
         raise PsfError(st, "psf_decode_step")
     return o
+
+
+def psf_probe_mfma_loop(workgroups, iters, sink, stream=None):
+    """Pure MFMA loop (measurement aid): workgroups x 4 waves x iters x 8 MFMAs of 32768 flops.
+    Returns the flop count of the launch."""
+    if not sink.is_cuda or sink.dtype != torch.float32 or sink.numel() < workgroups * 256:
+        raise ValueError("sink must be a float32 GPU tensor of at least workgroups * 256 entries")
+    st = lib().psf_probe_mfma_loop(int(workgroups), int(iters), ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_probe_mfma_loop")
+    return workgroups * 4 * iters * 8 * 32768

@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpsf.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["psf_mfma.hip", "psf_api.hip", "psf_general.hip", "psf_backward.hip", "psf_decode.hip"]
+SOURCES = ["psf_mfma.hip", "psf_api.hip", "psf_general.hip", "psf_backward.hip", "psf_decode.hip", "psf_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # packed fp32 VALU forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
