@@ -27,10 +27,12 @@ _lp = ctypes.POINTER(ctypes.c_long)
 def lib():
     global _lib
     if _lib is None:
-        path = _build.LIB
-        if (not os.path.exists(path)
-                or os.path.getmtime(path) < os.path.getmtime(_build.SRC)):
-            _build.build()
+        path = os.environ.get("PSF_ORACLE_LIB")      # another build of the same source (sanitizers)
+        if not path:
+            path = _build.LIB
+            if (not os.path.exists(path)
+                    or os.path.getmtime(path) < os.path.getmtime(_build.SRC)):
+                _build.build()
         L = ctypes.CDLL(path)
         L.psf_oracle_num_g_first.restype = ctypes.c_long
         L.psf_oracle_num_g_first.argtypes = [ctypes.c_long]

@@ -19,5 +19,19 @@ def build(force: bool = True) -> str:
     return LIB
 
 
+SAN_LIB = os.path.join(HERE, "libpsf_oracle_san.so")
+
+
+def build_sanitized() -> str:
+    """The same source under AddressSanitizer and UndefinedBehaviorSanitizer (host code only),
+    for the test that runs the pin suite's cases through it.  A process that loads it needs
+    the sanitizer runtime first in LD_PRELOAD (gcc -print-file-name=libasan.so)."""
+    cmd = ["gcc", "-O1", "-g", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-Wall", "-Wextra",
+           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+           SRC, "-o", SAN_LIB, "-lm"]
+    subprocess.run(cmd, check=True)
+    return SAN_LIB
+
+
 if __name__ == "__main__":
     print(build())
