@@ -142,6 +142,25 @@ psf_status psf_causal_attn_fwd(const psf_desc *desc, const void *Q, const void *
                                void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * psf_causal_attn_fwd_static -- the same call for callers that cannot allocate device memory or
+ * pass a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The workspace is an array of PSF_STATIC_SCRATCH_BYTES bytes that lives in the
+ * library's device image (one copy per GPU, held until the process ends); the call allocates and
+ * frees nothing and runs the same kernels as psf_causal_attn_fwd, so the output is the same bit
+ * for bit.  Inputs and output are still the caller's.
+ *   Problems with psf_workspace_bytes(desc) > PSF_STATIC_SCRATCH_BYTES are rejected with
+ *   PSF_ERR_WORKSPACE before anything is launched (use psf_causal_attn_fwd for those).
+ *   All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ *   (different streams, or different host threads) race and give unspecified results;
+ *   calls on one stream are ordered and safe.  Nothing in the array has to survive between
+ *   calls and nothing needs clearing.  The first call on a device looks the array's address up
+ *   (once per device, with that device current); later calls only enqueue kernels.
+ */
+#define PSF_STATIC_SCRATCH_BYTES (32u << 20)
+psf_status psf_causal_attn_fwd_static(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                      const void *G, void *O, void *hip_stream);
+
+/*
  * Same call, but brackets each kernel with HIP events on `hip_stream`, waits for the stream
  * and reports per-stage milliseconds: stage_ms[i], stage names via psf_stage_name(path, i).
  * n_stages is the capacity of stage_ms; returns the stage count in *n_written.  Creates and

@@ -19,7 +19,7 @@ LOCAL_EXACT, LOCAL_SKETCH = 0, 1
 
 EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_len", "psf_learned_len",
            "psf_sketch",
-           "psf_causal_attn_fwd", "psf_causal_attn_fwd_timed", "psf_stage_name",
+           "psf_causal_attn_fwd", "psf_causal_attn_fwd_static", "psf_causal_attn_fwd_timed", "psf_stage_name",
            "psf_status_string", "psf_noncausal_workspace_bytes", "psf_noncausal_attn_fwd",
            "psf_noncausal_attn_fwd_timed", "psf_fwd_save_bytes", "psf_causal_attn_fwd_save",
            "psf_causal_attn_bwd_saved", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
@@ -67,6 +67,8 @@ def lib():
         L.psf_sketch.argtypes = [dp, vp, vp, vp, vp, vp]
         L.psf_causal_attn_fwd.restype = ctypes.c_int
         L.psf_causal_attn_fwd.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.psf_causal_attn_fwd_static.restype = ctypes.c_int
+        L.psf_causal_attn_fwd_static.argtypes = [dp, vp, vp, vp, vp, vp, vp]
         L.psf_causal_attn_fwd_timed.restype = ctypes.c_int
         L.psf_causal_attn_fwd_timed.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp,
                                                 ctypes.POINTER(ctypes.c_float), ctypes.c_int32,
@@ -228,6 +230,23 @@ def psf_causal_attn_fwd(desc, Q, K, V, G, O=None, workspace=None, stream=None):
     st = lib().psf_causal_attn_fwd(ctypes.byref(desc), *ptrs, _stream_ptr(stream))
     if st != PSF_OK:
         raise PsfError(st, "psf_causal_attn_fwd")
+    return O
+
+
+STATIC_SCRATCH_BYTES = 32 << 20      # PSF_STATIC_SCRATCH_BYTES of include/psf.h
+
+
+def psf_causal_attn_fwd_static(desc, Q, K, V, G, O, stream=None):
+    """The forward call on the library's own static device scratch: no workspace argument and
+    no allocation anywhere (O is the caller's, so this wrapper allocates nothing either)."""
+    B, H, n, d, dv = desc.batch, desc.heads, desc.n, desc.d, desc.dv
+    gs = _g_shape(desc)
+    st = lib().psf_causal_attn_fwd_static(
+        ctypes.byref(desc), _dev_ptr(Q, desc, (B, H, n, d), "Q"), _dev_ptr(K, desc, (B, H, n, d), "K"),
+        _dev_ptr(V, desc, (B, H, n, dv), "V"), _dev_ptr(G, desc, gs, "G") if gs else None,
+        _dev_ptr(O, desc, (B, H, n, dv), "O"), _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_fwd_static")
     return O
 
 

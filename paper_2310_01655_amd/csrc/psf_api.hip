@@ -2,6 +2,7 @@
 // The operations themselves are defined in include/psf.h (with their citations of
 // PolySketchFormer, arXiv 2310.01655); nothing here computes.
 #include <initializer_list>
+#include <mutex>
 #include "psf_internal.h"
 
 namespace psf {
@@ -177,6 +178,33 @@ static psf_status run_bwd(const psf_desc *desc, const void *Q, const void *K, co
     return general_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm);
 }
 
+// ---- scratch of the entry point that allocates nothing ------------------------------------
+// One array per GPU the library runs on, held until the process ends.  In host code the
+// array's name is only a handle for the symbol, never a device address: the address on the
+// current device is asked for once per device and kept; kernels and everything else only
+// ever see that pointer.
+static __device__ __align__(256) unsigned char scratch[PSF_STATIC_SCRATCH_BYTES];
+
+static const int kMaxDevices = 64;
+static std::mutex scratch_mutex;
+static void *scratch_ptr[kMaxDevices];            // per device; null until its first call
+
+static psf_status static_scratch(void **out)
+{
+    int dev = -1;
+    PSF_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return PSF_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        PSF_HIP_TRY(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));   // with `dev` current
+        if (!ptr || ((uintptr_t)ptr & 255u) != 0) return PSF_ERR_HIP;
+        scratch_ptr[dev] = ptr;
+    }
+    *out = scratch_ptr[dev];
+    return PSF_OK;
+}
+
 }  // namespace psf
 
 using namespace psf;
@@ -243,6 +271,23 @@ psf_status psf_causal_attn_fwd(const psf_desc *desc, const void *Q, const void *
                                void *hip_stream)
 {
     return run_attn(desc, Q, K, V, G, O, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+psf_status psf_causal_attn_fwd_static(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                      const void *G, void *O, void *hip_stream)
+{
+    // sizes first: nothing is touched for a problem that does not fit
+    Problem pb;
+    psf_status st = make_problem(desc, &pb);
+    if (st != PSF_OK) return st;
+    const size_t need = psf_workspace_bytes(desc);
+    if (need > (size_t)PSF_STATIC_SCRATCH_BYTES) return PSF_ERR_WORKSPACE;
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != PSF_OK) return st;
+    // every kernel of the forward path writes what it later reads, so the previous call's
+    // contents need no clearing
+    return run_attn(desc, Q, K, V, G, O, ws, (size_t)PSF_STATIC_SCRATCH_BYTES, hip_stream, nullptr);
 }
 
 psf_status psf_causal_attn_fwd_timed(const psf_desc *desc, const void *Q, const void *K,
