@@ -68,6 +68,10 @@ def lib():
         L.psf_oracle_attn_bwd_rows.restype = ctypes.c_int
         L.psf_oracle_attn_bwd_rows.argtypes = ([_dp] * 5 + [ctypes.c_long] * 6 + [ctypes.c_int] * 2
                                                + [_lp, ctypes.c_long] + [_dp] * 3)
+        L.psf_oracle_sketch_learned_bwd.restype = ctypes.c_int
+        L.psf_oracle_sketch_learned_bwd.argtypes = [_dp] + [ctypes.c_long] * 4 + [_dp] * 4
+        L.psf_oracle_attn_bwd_learned.restype = ctypes.c_int
+        L.psf_oracle_attn_bwd_learned.argtypes = ([_dp] * 5 + [ctypes.c_long] * 6 + [ctypes.c_int] + [_dp] * 4)
         L.psf_oracle_attn_bwd_batch.restype = ctypes.c_int
         L.psf_oracle_attn_bwd_batch.argtypes = ([_dp] * 4 + [ctypes.c_long] * 2 + [_dp]
                                                 + [ctypes.c_long] * 7 + [ctypes.c_int] * 2
@@ -224,6 +228,36 @@ def sketch_bwd(X, G, r, p, dM):
     if rc:
         raise ValueError("psf_oracle_sketch_bwd failed: %d" % rc)
     return dX
+
+
+def sketch_learned_bwd(X, params, r, p, dM):
+    """((d m / d x)^T dM, (d m / d params)^T dM) for the learned sketch m of `sketch_learned`
+    (gradient of Algorithm 2 with respect to the input rows and to the networks' parameters)."""
+    X, dM = _f64(X), _f64(dM)
+    k, d = X.shape
+    P = _f64(params).reshape(-1) if p > 2 else np.zeros(1)
+    dX = np.empty((k, d))
+    dP = np.zeros(max(learned_len(d, r, p), 1))
+    rc = lib().psf_oracle_sketch_learned_bwd(_ptr(X), k, d, r, p, _ptr(P), _ptr(dM), _ptr(dX), _ptr(dP))
+    if rc:
+        raise ValueError("psf_oracle_sketch_learned_bwd failed: %d" % rc)
+    return dX, dP[:learned_len(d, r, p)]
+
+
+def attn_bwd_learned(Q, K, V, params, dO, p, r, b, local=LOCAL_EXACT):
+    """Gradient of `attn_def(..., learned=True)` (all rows) with respect to Q, K, V and the
+    parameters of the learned sketch, for dL/dO = dO; one unit."""
+    Q, K, V, dO = _f64(Q), _f64(K), _f64(V), _f64(dO)
+    n, d = Q.shape
+    dv = V.shape[1]
+    P = _f64(params).reshape(-1) if p > 2 else np.zeros(1)
+    dQ, dK, dV = np.empty((n, d)), np.empty((n, d)), np.empty((n, dv))
+    dP = np.zeros(max(learned_len(d, r, p), 1))
+    rc = lib().psf_oracle_attn_bwd_learned(_ptr(Q), _ptr(K), _ptr(V), _ptr(P), _ptr(dO), n, d, dv, r, p, b,
+                                           local, _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dP))
+    if rc:
+        raise ValueError("psf_oracle_attn_bwd_learned failed: %d" % rc)
+    return dQ, dK, dV, dP[:learned_len(d, r, p)]
 
 
 def attn_noncausal(Q, K, V, G, p, r, feat=FEAT_SKETCH, explicit_features=False, learned=False):

@@ -26,6 +26,8 @@
  *   oracle_lpswn,            Algorithm 2 (learnable sketches, Appendix D): the recursion of
  *   psf_oracle_sketch_learned  Algorithm 1 with each projection M G replaced by a dense network
  *                            f(M) and sqrt(r) tanh(sqrt(1/r) .) around the Hadamard product
+ *   oracle_lpswn_bwd,        gradient of Algorithm 2 with respect to the input rows and to the
+ *   oracle_learned_net_bwd   networks' parameters (chain rule through layer norm, gelu, tanh)
  *   oracle_pswn_bwd,         gradient of the same definition (Section 3 with the weights of
  *   psf_oracle_attn_bwd      Sections 3.1/3.2, sketch of Algorithm 1) with respect to Q, K, V:
  *                            the chain rule written out pair by pair; the paper trains
@@ -493,6 +495,194 @@ int psf_oracle_sketch_bwd(const double *X, long k, long d, long r, long p,
     return oracle_pswn_bwd(X, k, d, r, p / 2, &gf, &gi, dM, dX);
 }
 
+/* ---- gradient of Algorithm 2 --------------------------------------------------------
+ * The learned sketch is trained, so both gradients are needed: with respect to the input rows
+ * and with respect to the parameters of the networks.  Everything below is the chain rule
+ * through oracle_learned_net / oracle_lpswn, row by row.
+ *
+ * d gelu(x) / dx for the tanh form: with c = sqrt(2/pi), t = tanh(c (x + 0.044715 x^3)):
+ * 0.5 (1 + t) + 0.5 x (1 - t^2) c (1 + 3 * 0.044715 x^2). */
+static double gelu_tanh_grad(double x)
+{
+    const double c = 0.7978845608028654;
+    double t = tanh(c * (x + 0.044715 * x * x * x));
+    return 0.5 * (1.0 + t) + 0.5 * x * (1.0 - t * t) * c * (1.0 + 3.0 * 0.044715 * x * x);
+}
+
+/* y = (x - mean) inv g + b with inv = 1 / sqrt(var + eps), biased variance.  Given dy: adds
+ * dg += dy * xhat, db += dy, and writes dx = inv (dxh - mean(dxh) - xhat mean(dxh * xhat)) with
+ * dxh = dy * g (the eps sits inside the square root, so the formula is exact for it too). */
+static void layer_norm_bwd(const double *x, long m, const double *g, const double *dy,
+                           double *dg, double *db, double *dx)
+{
+    double mean = 0.0, var = 0.0;
+    for (long e = 0; e < m; ++e) mean += x[e];
+    mean /= (double)m;
+    for (long e = 0; e < m; ++e) var += (x[e] - mean) * (x[e] - mean);
+    var /= (double)m;
+    double inv = 1.0 / sqrt(var + 1e-6);
+    double s1 = 0.0, s2 = 0.0;
+    for (long e = 0; e < m; ++e) {
+        double xh = (x[e] - mean) * inv, dxh = dy[e] * g[e];
+        s1 += dxh;
+        s2 += dxh * xh;
+        dg[e] += dy[e] * xh;
+        db[e] += dy[e];
+    }
+    s1 /= (double)m;
+    s2 /= (double)m;
+    for (long e = 0; e < m; ++e) {
+        double xh = (x[e] - mean) * inv;
+        dx[e] = inv * (dy[e] * g[e] - s1 - xh * s2);
+    }
+}
+
+/* One network f (see oracle_learned_net): given dF = dL/df (k x r), adds dL/dA into dA (k x win)
+ * and dL/dparams into dP, which has the layout of the network's own parameter block
+ * [g1, b1, W1, g2, b2, W2, W3, W4].  The forward values of a row are recomputed first. */
+static int oracle_learned_net_bwd(const double *A, long k, long win, long r, const double *P,
+                                  const double *dF, double *dA, double *dP)
+{
+    long hid = 8 * r;
+    const double *g1 = P, *b1 = g1 + win, *W1 = b1 + win;
+    const double *g2 = W1 + win * hid, *b2 = g2 + hid, *W2 = b2 + hid;
+    const double *W3 = W2 + hid * r, *W4 = W3 + r * hid;
+    double *dg1 = dP, *db1 = dg1 + win, *dW1 = db1 + win;
+    double *dg2 = dW1 + win * hid, *db2 = dg2 + hid, *dW2 = db2 + hid;
+    double *dW3 = dW2 + hid * r, *dW4 = dW3 + r * hid;
+    long big = win > hid ? win : hid;
+    double *buf = (double *)malloc(sizeof(double) * (size_t)(2 * win + 8 * hid + 2 * r + 2 * big));
+    if (!buf) return 2;
+    double *u0 = buf, *du0 = u0 + win, *s1 = du0 + win, *h1 = s1 + hid, *v = h1 + hid, *s3 = v + hid,
+           *h3 = s3 + hid, *dh = h3 + hid, *dv = dh + hid, *ds = dv + hid, *h2 = ds + hid, *dh2 = h2 + r,
+           *da = dh2 + r;
+    (void)big;
+    for (long i = 0; i < k; ++i) {
+        const double *a = A + i * win, *df = dF + i * r;
+        /* forward, keeping what the reverse pass needs */
+        layer_norm(a, win, g1, b1, u0);
+        for (long c = 0; c < hid; ++c) {
+            double t = 0.0;
+            for (long e = 0; e < win; ++e) t += u0[e] * W1[e * hid + c];
+            s1[c] = t;
+            h1[c] = gelu_tanh(t);
+        }
+        layer_norm(h1, hid, g2, b2, v);
+        for (long c = 0; c < r; ++c) {
+            double t = 0.0;
+            for (long e = 0; e < hid; ++e) t += v[e] * W2[e * r + c];
+            h2[c] = t;
+        }
+        for (long c = 0; c < hid; ++c) {
+            double t = 0.0;
+            for (long e = 0; e < r; ++e) t += h2[e] * W3[e * hid + c];
+            s3[c] = t;
+            h3[c] = gelu_tanh(t);
+        }
+        /* f = h3 W4 */
+        for (long e = 0; e < hid; ++e) {
+            double t = 0.0;
+            for (long c = 0; c < r; ++c) {
+                t += df[c] * W4[e * r + c];
+                dW4[e * r + c] += h3[e] * df[c];
+            }
+            ds[e] = t * gelu_tanh_grad(s3[e]);            /* dL/ds3 */
+        }
+        /* s3 = h2 W3 */
+        for (long e = 0; e < r; ++e) {
+            double t = 0.0;
+            for (long c = 0; c < hid; ++c) {
+                t += ds[c] * W3[e * hid + c];
+                dW3[e * hid + c] += h2[e] * ds[c];
+            }
+            dh2[e] = t;
+        }
+        /* h2 = v W2 */
+        for (long e = 0; e < hid; ++e) {
+            double t = 0.0;
+            for (long c = 0; c < r; ++c) {
+                t += dh2[c] * W2[e * r + c];
+                dW2[e * r + c] += v[e] * dh2[c];
+            }
+            dv[e] = t;
+        }
+        /* v = LayerNorm(h1) */
+        layer_norm_bwd(h1, hid, g2, dv, dg2, db2, dh);
+        /* h1 = gelu(s1), s1 = u0 W1 */
+        for (long c = 0; c < hid; ++c) ds[c] = dh[c] * gelu_tanh_grad(s1[c]);
+        for (long e = 0; e < win; ++e) {
+            double t = 0.0;
+            for (long c = 0; c < hid; ++c) {
+                t += ds[c] * W1[e * hid + c];
+                dW1[e * hid + c] += u0[e] * ds[c];
+            }
+            du0[e] = t;
+        }
+        /* u0 = LayerNorm(a) */
+        layer_norm_bwd(a, win, g1, du0, dg1, db1, da);
+        for (long e = 0; e < win; ++e) dA[i * win + e] += da[e];
+    }
+    free(buf);
+    return 0;
+}
+
+/* Reverse of oracle_lpswn.  The node's output is sqrt(r) tanh(F1 * F2 / sqrt(r)), so with
+ * t = tanh(F1 F2 / sqrt(r)):  dF1 = dOut (1 - t^2) F2,  dF2 = dOut (1 - t^2) F1 (the two
+ * sqrt(r) cancel); each network is then differentiated with respect to its input M1 / M2 and
+ * its parameters, and the subtrees in turn.  *params walks the parameter blob exactly as in
+ * the forward recursion; dP0 is the gradient blob (same layout), P0 the start of the blob. */
+static int oracle_lpswn_bwd(const double *A, long k, long m, long r, long deg, const double **params,
+                            const double *P0, double *dP0, const double *dOut, double *dA)
+{
+    if (deg == 1) {
+        for (long i = 0; i < k * m; ++i) dA[i] += dOut[i];
+        return 0;
+    }
+    const double *p_left = *params;
+    double *M1 = oracle_lpswn(A, k, m, r, deg / 2, params);
+    const double *p_right = *params;
+    double *M2 = oracle_lpswn(A, k, m, r, deg / 2, params);
+    long win = (deg / 2 == 1) ? m : r;
+    const double *p_f1 = *params;
+    double *F1 = M1 ? oracle_learned_net(M1, k, win, r, params) : NULL;
+    const double *p_f2 = *params;
+    double *F2 = M2 ? oracle_learned_net(M2, k, win, r, params) : NULL;
+    double *dF1 = (double *)malloc(sizeof(double) * (size_t)k * (size_t)r);
+    double *dF2 = (double *)malloc(sizeof(double) * (size_t)k * (size_t)r);
+    double *dM1 = (double *)calloc((size_t)k * (size_t)win, sizeof(double));
+    double *dM2 = (double *)calloc((size_t)k * (size_t)win, sizeof(double));
+    int err = (!M1 || !M2 || !F1 || !F2 || !dF1 || !dF2 || !dM1 || !dM2) ? 2 : 0;
+    if (!err) {
+        double sr = sqrt((double)r);
+        for (long i = 0; i < k * r; ++i) {
+            double t = tanh(F1[i] * F2[i] / sr);
+            double dz = dOut[i] * (1.0 - t * t);
+            dF1[i] = dz * F2[i];
+            dF2[i] = dz * F1[i];
+        }
+        err = oracle_learned_net_bwd(M1, k, win, r, p_f1, dF1, dM1, dP0 + (p_f1 - P0));
+        if (!err) err = oracle_learned_net_bwd(M2, k, win, r, p_f2, dF2, dM2, dP0 + (p_f2 - P0));
+        const double *pp = p_left;
+        if (!err) err = oracle_lpswn_bwd(A, k, m, r, deg / 2, &pp, P0, dP0, dM1, dA);
+        pp = p_right;
+        if (!err) err = oracle_lpswn_bwd(A, k, m, r, deg / 2, &pp, P0, dP0, dM2, dA);
+    }
+    free(M1); free(M2); free(F1); free(F2); free(dF1); free(dF2); free(dM1); free(dM2);
+    return err;
+}
+
+/* dX (k x d, overwritten) = (d m / d x)^T dM and, added into dParams (psf_oracle_learned_len
+ * entries, NOT cleared here so that several calls can accumulate), (d m / d params)^T dM, for
+ * m = LearnablePolysketchWithNegativity(x, r, p/2) as in psf_oracle_sketch_learned. */
+int psf_oracle_sketch_learned_bwd(const double *X, long k, long d, long r, long p,
+                                  const double *params, const double *dM, double *dX, double *dParams)
+{
+    if (!is_pow2(p) || p < 2 || k < 0 || d <= 0 || r <= 0) return 1;
+    for (long i = 0; i < k * d; ++i) dX[i] = 0.0;
+    const double *pp = params;
+    return oracle_lpswn_bwd(X, k, d, r, p / 2, &pp, params, dParams, dM, dX);
+}
+
 /* ---- gradient of the definition -----------------------------------------------------
  * L is any scalar with dL/dO = dO (n x dv).  With N_i = sum_{j<=i} w_ij v_j,
  * D_i = 1 + sum_{j<=i} w_ij, o_i = N_i / D_i:
@@ -505,7 +695,7 @@ int psf_oracle_sketch_bwd(const double *X, long k, long d, long r, long p,
 static int oracle_attn_bwd_rows(const double *Q, const double *K, const double *V, const double *G,
                                 const double *dO, long n, long d, long dv, long r, long p, long b,
                                 int feat, int local, const long *rows, long nrows,
-                                double *dQ, double *dK, double *dV)
+                                double *dQ, double *dK, double *dV, int learned, double *dP)
 {
     if (n <= 0 || b <= 0 || n % b != 0 || !is_pow2(p) || p < 2) return 1;
     long mcols = (p == 2) ? d : r;
@@ -521,8 +711,8 @@ static int oracle_attn_bwd_rows(const double *Q, const double *K, const double *
         dmq = (double *)calloc((size_t)n * (size_t)mcols, sizeof(double));
         dmk = (double *)calloc((size_t)n * (size_t)mcols, sizeof(double));
         if (!mq || !mk || !dmq || !dmk) err = 2;
-        if (!err) err = psf_oracle_sketch(Q, n, d, r, p, G, mq);
-        if (!err) err = psf_oracle_sketch(K, n, d, r, p, G, mk);
+        if (!err) err = learned ? psf_oracle_sketch_learned(Q, n, d, r, p, G, mq) : psf_oracle_sketch(Q, n, d, r, p, G, mq);
+        if (!err) err = learned ? psf_oracle_sketch_learned(K, n, d, r, p, G, mk) : psf_oracle_sketch(K, n, d, r, p, G, mk);
     }
     if (!err) {
         for (long i = 0; i < n * d; ++i) dQ[i] = dK[i] = 0.0;
@@ -568,9 +758,13 @@ static int oracle_attn_bwd_rows(const double *Q, const double *K, const double *
             }
         }
         if (sketch && !err) {
-            err = psf_oracle_sketch_bwd(Q, n, d, r, p, G, dmq, tmp);
+            /* learned sketches: the same networks serve the query and the key rows, so their
+             * parameter gradients add up */
+            err = learned ? psf_oracle_sketch_learned_bwd(Q, n, d, r, p, G, dmq, tmp, dP)
+                          : psf_oracle_sketch_bwd(Q, n, d, r, p, G, dmq, tmp);
             for (long i = 0; i < n * d && !err; ++i) dQ[i] += tmp[i];
-            if (!err) err = psf_oracle_sketch_bwd(K, n, d, r, p, G, dmk, tmp);
+            if (!err) err = learned ? psf_oracle_sketch_learned_bwd(K, n, d, r, p, G, dmk, tmp, dP)
+                                    : psf_oracle_sketch_bwd(K, n, d, r, p, G, dmk, tmp);
             for (long i = 0; i < n * d && !err; ++i) dK[i] += tmp[i];
         }
     }
@@ -582,7 +776,21 @@ int psf_oracle_attn_bwd(const double *Q, const double *K, const double *V, const
                         const double *dO, long n, long d, long dv, long r, long p, long b,
                         int feat, int local, double *dQ, double *dK, double *dV)
 {
-    return oracle_attn_bwd_rows(Q, K, V, G, dO, n, d, dv, r, p, b, feat, local, NULL, 0, dQ, dK, dV);
+    return oracle_attn_bwd_rows(Q, K, V, G, dO, n, d, dv, r, p, b, feat, local, NULL, 0, dQ, dK, dV, 0, NULL);
+}
+
+/* The same gradient with learned sketches (Algorithm 2) in place of Algorithm 1: params holds
+ * the networks' parameters (psf_oracle_learned_len entries); dParams (same length, overwritten)
+ * receives dL/dparams, the sum of the query-side and key-side contributions.  Sketch features
+ * only; p in {2, 4, 8, 16} (p = 2: no networks, dParams untouched). */
+int psf_oracle_attn_bwd_learned(const double *Q, const double *K, const double *V, const double *params,
+                                const double *dO, long n, long d, long dv, long r, long p, long b,
+                                int local, double *dQ, double *dK, double *dV, double *dParams)
+{
+    long len = psf_oracle_learned_len(d, r, p);
+    for (long i = 0; i < len; ++i) dParams[i] = 0.0;
+    return oracle_attn_bwd_rows(Q, K, V, params, dO, n, d, dv, r, p, b, FEAT_SKETCH, local, NULL, 0,
+                                dQ, dK, dV, 1, dParams);
 }
 
 /* The same sums restricted to the listed query rows i (each listed once): row i of dQ is complete
@@ -595,7 +803,7 @@ int psf_oracle_attn_bwd_rows(const double *Q, const double *K, const double *V, 
                              double *dQ, double *dK, double *dV)
 {
     if (!rows || nrows < 0) return 1;
-    return oracle_attn_bwd_rows(Q, K, V, G, dO, n, d, dv, r, p, b, feat, local, rows, nrows, dQ, dK, dV);
+    return oracle_attn_bwd_rows(Q, K, V, G, dO, n, d, dv, r, p, b, feat, local, rows, nrows, dQ, dK, dV, 0, NULL);
 }
 
 /* ---- drivers over (batch, head) units ---------------------------------------------

@@ -39,6 +39,8 @@ for p in (2, 4, 8, 16):
             M = oracle.sketch_learned(Q, P, r, p)
             assert np.isfinite(M).all() and np.abs(M).max() <= np.sqrt(r) + 1e-12
             oracle.attn_def(Q, K, V, P, p, r, b, learned=True)
+            oracle.sketch_learned_bwd(Q, P, r, p, rng.standard_normal((n, r)))
+            oracle.attn_bwd_learned(Q, K, V, P, dO, p, r, b)
 Qb, Kb, Vb = rng.standard_normal((2, 3, 8, 4)), rng.standard_normal((2, 3, 8, 4)), rng.standard_normal((2, 3, 8, 3))
 Gb = rng.standard_normal((3, oracle.g_len(4, 4, 4)))
 O, _ = oracle.attn_def_batch(Qb, Kb, Vb, Gb, 4, 4, 2, max_threads=3)
