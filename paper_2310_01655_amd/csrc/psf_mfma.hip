@@ -33,6 +33,7 @@
 //   A[i][k]: lane x = i, half h supplies k = 8h..8h+7 (8 bf16 per lane)
 //   B[k][j]: lane x = j, half h supplies k = 8h..8h+7
 //   D[i][j]: lane x = j, register v holds row i = 8*(v/4) + 4*h + (v%4)
+#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -389,34 +390,229 @@ __global__ __launch_bounds__(kWg) void k_v_octets(const bf16_t *__restrict__ V,
     *(uint4 *)&V8[idx * 8] = pk;
 }
 
+// ------------------------------------------------------------------------------------
+// Everything the state and output kernels need (degree 4, Gaussian sketches).  A workgroup
+// takes one role on one part of the rows (a part = 128 * tiles_per_wg tokens of one unit):
+// 0 = sketch of the query rows (m(Q) as bf16 rows), 1 = sketch of the key rows (m(K) as fp32
+// token octets + the part's S = m^T m), 2 = the value rows as token octets.  The sketch
+// matrices are read as given, [d][r] row-major, and transposed on their way into LDS (once per
+// workgroup), so no transposed copy is needed.
+// ------------------------------------------------------------------------------------
+template <int D, int R>
+struct PrepLds {
+    SketchLds<D, R> g;
+    union {
+        float red[4][32][33];                        // key role: S partial reduction
+        bf16_t qtile[4][32][R + 8];                  // query role: row-major store staging
+    } u;
+};
+
+template <int D, int R>
+__device__ __forceinline__ void stage_g_transposing(bf16_t *dst, const bf16_t *g)
+{
+    // g is [D][R] row-major; dst[c * PITCH + e] = g[e][c]
+    constexpr int PITCH = SketchLds<D, R>::kPitch;
+    constexpr int VEC = R / 8;
+    for (int idx = threadIdx.x; idx < D * VEC; idx += kWg) {
+        const int e = idx / VEC, part = idx % VEC;
+        const uint4 raw = *(const uint4 *)&g[(size_t)e * R + 8 * part];
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            dst[(8 * part + i) * PITCH + e] = (bf16_t)(w[i / 2] >> (16 * (i % 2)));
+    }
+}
+
+template <int D, int R, bool QSIDE>
+__device__ __forceinline__ void prep_sketch_role(PrepLds<D, R> &lds, const bf16_t *__restrict__ X,
+                                                 const bf16_t *__restrict__ g, size_t tok_wg0, int tiles_per_wg,
+                                                 bf16_t *__restrict__ M_rm, float *__restrict__ M8,
+                                                 float *__restrict__ Spart_out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int x = lane & 31, h = lane >> 5;
+    const float scale = sqrtf(1.0f / (float)R);
+    constexpr int KS = D / 16, NT = R / 32;
+
+    f32x16 sacc[QSIDE ? 1 : NT][QSIDE ? 1 : NT];
+    if (!QSIDE) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) sacc[i][j] = f32x16{0};
+    }
+    // first tile's operands are on their way while the matrices are staged
+    bf16x8 xfr[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[(tok_wg0 + wave * 32 + x) * D + 16 * s + 8 * h];
+    stage_g_transposing<D, R>(lds.g.gt[0], g);
+    stage_g_transposing<D, R>(lds.g.gt[1], g + (size_t)D * R);
+    __syncthreads();
+
+#pragma unroll 1
+    for (int tile = 0; tile < tiles_per_wg; ++tile) {
+        const size_t row0 = tok_wg0 + (size_t)tile * 128 + wave * 32;   // this wave's 32 tokens
+        f32x16 a0[NT], a1[NT], m[NT];
+        project<D, R, KS, QSIDE>(lds.g.gt[0], xfr, a0, x, h);
+        project<D, R, KS, QSIDE>(lds.g.gt[1], xfr, a1, x, h);
+        // Operands of the next tile (the last tile loads its own rows again: no branch here).
+        // A conditional block between the MFMAs above and the first read of their results
+        // made the compiler count the wait states of the skipped loads: on the path that skips
+        // them the last accumulator registers were read before the matrix pipe had written
+        // them.  Straight-line code gets the full wait.
+        {
+            const size_t nrow = row0 + (tile + 1 < tiles_per_wg ? 128 : 0);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[(nrow + x) * D + 16 * s + 8 * h];
+        }
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) m[ct] = scale * (a0[ct] * a1[ct]);
+
+        if (QSIDE) {
+            // lane = token x, register v = sketch column 32ct + 8(v/4) + 4h + v%4; through LDS so
+            // that the row-major store is 16 contiguous bytes per lane
+            bf16_t *qt = lds.u.qtile[wave][0];
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int c0 = 32 * ct + 8 * gq + 4 * h;
+                    f32x4 q4 = {m[ct][4 * gq], m[ct][4 * gq + 1], m[ct][4 * gq + 2], m[ct][4 * gq + 3]};
+                    *(bf16x4 *)&qt[x * (R + 8) + c0] = cvt4(q4);
+                }
+            __builtin_amdgcn_s_waitcnt((0x3F & 0xF) | (0x7 << 4) | (0x0 << 8) | ((0x3F >> 4) << 14));   // own LDS writes
+#pragma unroll
+            for (int i = 0; i < 32 * R / 8 / 64; ++i) {
+                const int w = i * 64 + lane, tok = w / (R / 8), part = w % (R / 8);
+                *(uint4 *)&M_rm[(row0 + tok) * R + 8 * part] = *(const uint4 *)&qt[tok * (R + 8) + 8 * part];
+            }
+        } else {
+            // lane = sketch column 32ct + x, register v = token 8(v/4) + 4h + v%4
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int c = 32 * ct + x;
+                    f32x4 q4 = {m[ct][4 * gq], m[ct][4 * gq + 1], m[ct][4 * gq + 2], m[ct][4 * gq + 3]};
+                    const size_t oct = (row0 >> 3) + gq;
+                    *(f32x4 *)&M8[((oct * 2 + h) * R + c) * 4] = q4;
+                    if (M_rm)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            M_rm[(row0 + 8 * gq + 4 * h + j) * R + c] = f32_to_bf16(q4[j]);
+                }
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp) {              // S += M^T M over these 32 tokens
+                bf16x8 f[NT];
+#pragma unroll
+                for (int ct = 0; ct < NT; ++ct) f[ct] = cvt8_from16(m[ct], 8 * sp);
+#pragma unroll
+                for (int i = 0; i < NT; ++i)
+#pragma unroll
+                    for (int j = 0; j < NT; ++j) sacc[i][j] = mfma32(f[i], f[j], sacc[i][j]);
+            }
+        }
+    }
+
+    if (!QSIDE) {
+#pragma unroll
+        for (int i = 0; i < NT; ++i)
+#pragma unroll
+            for (int j = 0; j < NT; ++j) {
+                __syncthreads();
+#pragma unroll
+                for (int v = 0; v < 16; ++v) lds.u.red[wave][8 * (v / 4) + 4 * h + (v % 4)][x] = sacc[i][j][v];
+                __syncthreads();
+                for (int idx = threadIdx.x; idx < 32 * 32; idx += kWg) {
+                    const int a = idx / 32, c = idx % 32;
+                    Spart_out[(size_t)(32 * i + a) * R + 32 * j + c] =
+                        lds.u.red[0][a][c] + lds.u.red[1][a][c] + lds.u.red[2][a][c] + lds.u.red[3][a][c];
+                }
+            }
+    }
+}
+
+// KEYS = false: roles 0 and 2 alternate (few registers, four workgroups per CU); KEYS = true: role 1
+// alone (its S accumulators make it the register-heavy one; as one launch with the others it
+// would pull them down to its occupancy).
+template <int D, int R, bool KEYS>
+__global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                              const bf16_t *__restrict__ V, const bf16_t *__restrict__ G,
+                                              int n, int heads, int per_head, size_t g_len, int tiles_per_wg,
+                                              bf16_t *__restrict__ MQ, float *__restrict__ MK8,
+                                              bf16_t *__restrict__ MK_rm, float *__restrict__ Spart,
+                                              bf16_t *__restrict__ V8, int with_q)
+{
+    // (with_q == 0: the query rows are sketched elsewhere; every workgroup takes role 2)
+    __shared__ __attribute__((aligned(16))) PrepLds<D, R> lds;
+    const int role = KEYS ? 1 : (with_q ? 2 * (int)(blockIdx.x % 2) : 2);
+    const size_t part = (KEYS || !with_q) ? blockIdx.x : blockIdx.x / 2;
+    const size_t tok_wg0 = part * (size_t)tiles_per_wg * 128;           // first row of the part (all units)
+    if (!KEYS && role == 2) {
+        // value rows -> token octets [rows/8][D][8]: one 16-byte store per thread and step
+        // (UN outputs per thread and step, all their loads issued before the first is used: the
+        // role is bound by memory latency otherwise)
+        constexpr int UN = 4;
+        const size_t first = tok_wg0 / 8 * D, count = (size_t)tiles_per_wg * 16 * D;   // count % (UN * kWg) == 0
+        static_assert((16 * D) % (UN * kWg) == 0, "whole steps per 128-token tile");
+        for (size_t i0 = threadIdx.x; i0 < count; i0 += UN * kWg) {
+            uint16_t tmp[UN][8];
+#pragma unroll
+            for (int q = 0; q < UN; ++q) {
+                const size_t idx = first + i0 + (size_t)q * kWg, oct = idx / D;
+                const int c = (int)(idx % D);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) tmp[q][j] = V[(oct * 8 + j) * D + c];
+            }
+#pragma unroll
+            for (int q = 0; q < UN; ++q) {
+                const size_t idx = first + i0 + (size_t)q * kWg;
+                uint4 pk;
+                pk.x = tmp[q][0] | ((uint32_t)tmp[q][1] << 16);
+                pk.y = tmp[q][2] | ((uint32_t)tmp[q][3] << 16);
+                pk.z = tmp[q][4] | ((uint32_t)tmp[q][5] << 16);
+                pk.w = tmp[q][6] | ((uint32_t)tmp[q][7] << 16);
+                *(uint4 *)&V8[idx * 8] = pk;
+            }
+        }
+        return;
+    }
+    const int u = (int)(tok_wg0 / n);
+    const bf16_t *g = G + (per_head ? (size_t)(u % heads) * g_len : 0);
+    if constexpr (!KEYS)
+        prep_sketch_role<D, R, true>(lds, Q, g, tok_wg0, tiles_per_wg, MQ, nullptr, nullptr);
+    else
+        prep_sketch_role<D, R, false>(lds, K, g, tok_wg0, tiles_per_wg, MK_rm, MK8, Spart + part * R * R);
+}
+
 // Prefix over the sketch kernel's per-workgroup partials of S, snapshotted at block boundaries
 // and written as MFMA A-operands [R/8][R][8] bf16, split into hi + lo so that the denominator
 // keeps ~16 mantissa bits.  Slot l holds sum over blocks 0..l, which is what block l+1 needs.
+// (u, blk): unit and which 256 of its R * R entries this workgroup scans
 template <int R>
-__global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spart,
-                                                  bf16_t *__restrict__ Shi, bf16_t *__restrict__ Slo,
-                                                  int t, int parts_per_block, int parts_per_unit)
+__device__ __forceinline__ void den_scan_workgroup(const float *__restrict__ Spart, bf16_t *__restrict__ Shi,
+                                                   bf16_t *__restrict__ Slo, int t, int parts_per_block,
+                                                   int parts_per_unit, int u, int blk)
 {
-    const int u = blockIdx.y;
     // one entry of S per thread, threads in the order of the output layout [b'/8][a][8] so that
     // a wave's 2-byte stores are contiguous (its reads are 32-byte pieces)
-    const int dst = blockIdx.x * kWg + threadIdx.x;
+    const int dst = blk * kWg + threadIdx.x;
     if (dst >= R * R) return;
     const int a = (dst / 8) % R, bq = (dst / (8 * R)) * 8 + dst % 8;
     const int e = a * R + bq;
     const float *src = Spart + (size_t)u * parts_per_unit * R * R + e;
     const int total = (t - 1) * parts_per_block;
     float run = 0.f;
-    for (int w0 = 0; w0 < total; w0 += 8) {
-        float v[8];
+    constexpr int FLY = 8;                        // loads in flight per thread (32 measured slower)
+    for (int w0 = 0; w0 < total; w0 += FLY) {
+        float v[FLY];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = (w0 + i < total) ? src[(size_t)(w0 + i) * R * R] : 0.f;
+        for (int i = 0; i < FLY; ++i) v[i] = (w0 + i < total) ? src[(size_t)(w0 + i) * R * R] : 0.f;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
+        for (int i = 0; i < FLY; ++i) {
             const int w = w0 + i;
-            if (w >= total) break;
-            run += v[i];
-            if ((w + 1) % parts_per_block == 0) {
+            run += v[i];                          // zero past the end
+            if (w < total && (w + 1) % parts_per_block == 0) {
                 const int l = w / parts_per_block;
                 const size_t base = ((size_t)u * (t - 1) + l) * R * R;
                 const bf16_t hi = f32_to_bf16(run);
@@ -425,6 +621,14 @@ __global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spar
             }
         }
     }
+}
+
+template <int R>
+__global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spart,
+                                                  bf16_t *__restrict__ Shi, bf16_t *__restrict__ Slo,
+                                                  int t, int parts_per_block, int parts_per_unit)
+{
+    den_scan_workgroup<R>(Spart, Shi, Slo, t, parts_per_block, parts_per_unit, blockIdx.y, blockIdx.x);
 }
 
 // ------------------------------------------------------------------------------------
@@ -708,9 +912,17 @@ __device__ __forceinline__ void state_body(const float *__restrict__ M8, const b
 // TC tokens per staged chunk, kStateRing chunks per workgroup (one less in flight to cover the
 // memory latency); OCC workgroups per CU: grids that exceed one workgroup per CU run two per CU
 // with half-size chunks.
+// LDS of one state workgroup: the ring, and for NG = 2 the 32 KB behind it for the exchange of
+// partial sums at block boundaries.
+template <int R, int D, int TC, int NG>
+constexpr int state_lds_bytes() { return kStateRing * StateLds<R, D, TC>::BUF + (NG == 2 ? 8 * 16 * 64 * 4 : 0); }
+
+// lds: state_lds_bytes() of workgroup memory, 16-byte aligned; (bid, nblk): this workgroup's
+// index among the nblk state workgroups of the launch (dispatch order).
 template <int R, int D, int NA, bool SYM, int TC, int NG>
 __device__ __forceinline__ void state_workgroup(const float *__restrict__ M8, const bf16_t *__restrict__ V8,
-                                                bf16_t *__restrict__ Zg, int n, int b, int t, int units)
+                                                bf16_t *__restrict__ Zg, int n, int b, int t, int units,
+                                                unsigned char *lds, int bid, int nblk)
 {
     constexpr int NBUF = kStateRing;
     constexpr int BUF_BYTES = StateLds<R, D, TC>::BUF, M_LDS = StateLds<R, D, TC>::M_LDS;
@@ -718,13 +930,11 @@ __device__ __forceinline__ void state_workgroup(const float *__restrict__ M8, co
     constexpr int DMA_PER_CHUNK = (TC * R * 4 + TC * D * 2) / 16 / NTHR;
     constexpr int AG = NA * 4 / (R / 32);
     static_assert(!SYM || NA == 2, "tile deal of the symmetric variant");
-    // NG = 2: 32 KB behind the ring for the exchange of partial sums at block boundaries
-    __shared__ __attribute__((aligned(16))) unsigned char lds[NBUF * BUF_BYTES + (NG == 2 ? 8 * 16 * 64 * 4 : 0)];
 
     // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
     // contiguous range of (unit, group) pairs; the groups of one unit then share one L2.
-    int wg = blockIdx.x;
-    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    int wg = bid;
+    if ((nblk & 7) == 0) wg = (bid & 7) * (nblk >> 3) + (bid >> 3);
     constexpr int GROUPS = SYM ? (R / 16) * (R / 16 + 1) / 2 : R / AG;   // workgroups per unit
     const int u = wg / GROUPS, grp = wg % GROUPS;
     if (u >= units || t < 2) return;
@@ -767,7 +977,8 @@ __global__ __launch_bounds__(kWg, OCC) void k_state(const float *__restrict__ M8
                                                bf16_t *__restrict__ Zg, int n, int b, int t,
                                                int units)
 {
-    state_workgroup<R, D, NA, SYM, TC, 1>(M8, V8, Zg, n, b, t, units);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[state_lds_bytes<R, D, TC, 1>()];
+    state_workgroup<R, D, NA, SYM, TC, 1>(M8, V8, Zg, n, b, t, units, lds, blockIdx.x, gridDim.x);
 }
 
 // The symmetric deal with eight waves, two per SIMD (see state_body), one workgroup per CU.
@@ -777,7 +988,8 @@ __global__ __launch_bounds__(2 * kWg, 1) void k_state_two_waves(const float *__r
                                                                  bf16_t *__restrict__ Zg, int n, int b, int t,
                                                                  int units)
 {
-    state_workgroup<R, D, 2, true, TC, 2>(M8, V8, Zg, n, b, t, units);
+    __shared__ __attribute__((aligned(16))) unsigned char lds[state_lds_bytes<R, D, TC, 2>()];
+    state_workgroup<R, D, 2, true, TC, 2>(M8, V8, Zg, n, b, t, units, lds, blockIdx.x, gridDim.x);
 }
 
 // ------------------------------------------------------------------------------------
@@ -791,15 +1003,38 @@ __global__ __launch_bounds__(2 * kWg, 1) void k_state_two_waves(const float *__r
 // one state of its unit (slot 0; the caller passes b = n, t = 2).
 // LS (Section 3.1, in-block rule (L R^T)^2): the in-block weights are <m(q_i), m(k_j)>^2 like the
 // cross-block ones; Q, K then point to the bf16 rows of m(Q), m(K) (width R instead of D).
-template <int R, int D, int P, int TT, bool DEN, bool NONCAUSAL = false, bool LS = false>
-__global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
-                                                const bf16_t *__restrict__ V8,
-                                                const bf16_t *__restrict__ MQ,
-                                                const bf16_t *__restrict__ Zg,
-                                                const bf16_t *__restrict__ Shi,
-                                                const bf16_t *__restrict__ Slo, bf16_t *__restrict__ O,
-                                                float *__restrict__ Den, int n, int b, int t)
+// PART splits the work of a token tile over two launches: 0 = everything (one launch);
+// 1 = the in-block part only, its unnormalised rows and weight sums left in Pnum / Pden (it
+// needs neither the sketches nor the states, so it can run beside the state kernel);
+// 2 = the cross-block part, started from what PART 1 left, then the division.
+// Pnum / Pden layout (private to these two parts, which share this code): per 32-token tile of
+// a wave the accumulator registers as they are, [tile][value-column tile][register quad][lane]
+// x 16 bytes, and the partial weight sums of the 64 lanes (two per token), so that the second
+// launch continues exactly where one launch would be: the results are the same bit for bit.
+constexpr int kKeyTilesInFlight = 4;
+template <int R, int D, int TT, bool LS, int PART>
+constexpr int out_lds_bytes()
 {
+    constexpr int KD = LS ? R : D, TOK_WAVE = 32 * TT, TOK_WG = 4 * TOK_WAVE;
+    constexpr int KV = TOK_WAVE * KD * 2 + TOK_WAVE * D * 2;
+    constexpr int ZA = 16384 / (R * D);
+    constexpr int CROSS = 2 * (ZA * R * D * 2 + ZA * TOK_WG * 4);
+    constexpr int INB = kKeyTilesInFlight * KV;
+    return PART == 1 ? INB : (PART == 2 ? CROSS : (CROSS > INB ? CROSS : INB));
+}
+
+// stage: out_lds_bytes() of workgroup memory, 16-byte aligned; (bid, nblk): this workgroup's
+// index among the nblk output workgroups of the launch (dispatch order).
+template <int R, int D, int P, int TT, bool DEN, bool NONCAUSAL, bool LS, int PART>
+__device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                              const bf16_t *__restrict__ V8, const bf16_t *__restrict__ MQ,
+                                              const bf16_t *__restrict__ Zg, const bf16_t *__restrict__ Shi,
+                                              const bf16_t *__restrict__ Slo, bf16_t *__restrict__ O,
+                                              float *__restrict__ Den, float *__restrict__ Pnum,
+                                              float *__restrict__ Pden, int n, int b, int t,
+                                              unsigned char *stage, int bid, int nblk)
+{
+    static_assert(PART == 0 || (!NONCAUSAL && !DEN), "the split serves the causal forward call");
     constexpr int KD = LS ? R : D;                        // row width of the in-block score operands
     constexpr int CT = D / 32, KS = KD / 16, RS = R / 16, AT = R / 32;
     constexpr int TOK_WAVE = 32 * TT, TOK_WG = 4 * TOK_WAVE;
@@ -807,16 +1042,13 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
     constexpr int SUBS = KEYT / 32, IPT = SUBS * TT;      // 32x32 items per staged tile and wave
     constexpr int K_BYTES = KEYT * KD * 2, V_BYTES = KEYT * D * 2;
     constexpr int KV_BYTES = K_BYTES + V_BYTES;           // staged K tile + V tile (16 KB)
-    constexpr int NKV = 4;                                // key tiles in flight
+    constexpr int NKV = kKeyTilesInFlight;                // key tiles in flight
     constexpr int DMA_KV = KV_BYTES / 16 / kWg;           // copies per thread and tile
     constexpr int ZA = 16384 / (R * D);                   // sketch rows a per staged Z chunk
     constexpr int Z_PER_A = R * D;                        // bf16 elements of Z for one a
     constexpr int Z_CHUNK_BYTES = ZA * Z_PER_A * 2;       // 32 KB
     constexpr int MQ_CHUNK_BYTES = ZA * TOK_WG * 4;       // m_i[a] of the chunk, fp32 [ZA][TOK_WG]
-    constexpr int CROSS_BYTES = 2 * (Z_CHUNK_BYTES + MQ_CHUNK_BYTES);
-    constexpr int STAGE_BYTES = CROSS_BYTES > NKV * KV_BYTES ? CROSS_BYTES : NKV * KV_BYTES;
     static_assert(K_BYTES % (16 * kWg) == 0 && V_BYTES % (16 * kWg) == 0, "whole copies");
-    __shared__ __attribute__((aligned(16))) unsigned char stage[STAGE_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
@@ -825,8 +1057,8 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
     // XCD-aware order: consecutive workgroup ids go to different XCDs, so give each XCD a
     // contiguous range of tiles; the workgroups that stream the same Z_l (same unit, same
     // block) then share one L2 and run at about the same time.
-    int wg = blockIdx.x;
-    if ((gridDim.x & 7) == 0) wg = (blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3);
+    int wg = bid;
+    if ((nblk & 7) == 0) wg = (bid & 7) * (nblk >> 3) + (bid >> 3);
     const int u = wg / tiles_per_unit;
     // late tiles of a unit first: they carry the cross-block term
     const int tile = tiles_per_unit - 1 - (wg % tiles_per_unit);
@@ -837,15 +1069,34 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
 
     f32x16 out[TT][CT];
     float den[TT];
+    // rows of the workgroup's 32-token tiles in Pnum / Pden
+    const size_t ptile0 = (urow + tok_w0) / 32;
+    if constexpr (PART == 2) {
+        // start from the in-block part (the loads land while the denominators and the first
+        // chunk of the state are on their way)
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) {
-        den[tt] = 0.f;
+        for (int tt = 0; tt < TT; ++tt) {
+            den[tt] = Pden[(ptile0 + tt) * 64 + lane];
 #pragma unroll
-        for (int ct = 0; ct < CT; ++ct) out[tt][ct] = f32x16{0};
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const f32x4 q4 = *(const f32x4 *)&Pnum[(((ptile0 + tt) * CT + ct) * 4 + gq) * 256 + lane * 4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) out[tt][ct][4 * gq + j] = q4[j];
+                }
+        }
+    } else {
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            den[tt] = 0.f;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) out[tt][ct] = f32x16{0};
+        }
     }
 
     // ---------------- in-block exact weights (Section 3.2) ----------------
-    if constexpr (!NONCAUSAL) {
+    if constexpr (!NONCAUSAL && PART != 2) {
         bf16x8 qfr[TT][KS];
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt)
@@ -1021,6 +1272,22 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
         }
         wait_vmem_le<0>();                                // drain the clamped copies
         __syncthreads();
+    }
+
+    if constexpr (PART == 1) {
+        // leave the unnormalised rows and the weight sums for the second launch
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            Pden[(ptile0 + tt) * 64 + lane] = den[tt];      // per lane: the two halves of a wave hold different keys
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq)
+                    *(f32x4 *)&Pnum[(((ptile0 + tt) * CT + ct) * 4 + gq) * 256 + lane * 4] =
+                        f32x4{out[tt][ct][4 * gq], out[tt][ct][4 * gq + 1], out[tt][ct][4 * gq + 2],
+                              out[tt][ct][4 * gq + 3]};
+        }
+        return;
     }
 
     // ---------------- cross-block term phi'(Q_l) Z_l (Section 3.1) ----------------
@@ -1209,6 +1476,79 @@ __global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, co
                             out[tt][ct][4 * gq + 2] * inv, out[tt][ct][4 * gq + 3] * inv};
                 *(bf16x4 *)&O[row * D + 32 * ct + 8 * gq + 4 * h] = cvt4(q4);
             }
+    }
+}
+
+template <int R, int D, int P, int TT, bool DEN, bool NONCAUSAL = false, bool LS = false, int PART = 0>
+__global__ __launch_bounds__(kWg, 2) void k_out(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                const bf16_t *__restrict__ V8,
+                                                const bf16_t *__restrict__ MQ,
+                                                const bf16_t *__restrict__ Zg,
+                                                const bf16_t *__restrict__ Shi,
+                                                const bf16_t *__restrict__ Slo, bf16_t *__restrict__ O,
+                                                float *__restrict__ Den, float *__restrict__ Pnum,
+                                                float *__restrict__ Pden, int n, int b, int t)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char stage[out_lds_bytes<R, D, TT, LS, PART>()];
+    out_workgroup<R, D, P, TT, DEN, NONCAUSAL, LS, PART>(Q, K, V8, MQ, Zg, Shi, Slo, O, Den, Pnum, Pden, n, b, t,
+                                                         stage, blockIdx.x, gridDim.x);
+}
+
+// The state kernel in one launch with everything that does not depend on its results: the
+// in-block part of the output kernel (reads Q, K, V only), the sketch of the query rows and the
+// scan of the denominator partials (both first needed by the cross-block part afterwards).
+// They stall on different things: a state workgroup is one wave per SIMD that waits on its LDS
+// operands between MFMAs, the in-block part is bound by the vector work on its score tiles, the
+// query sketch by memory.  Side by side on a CU each fills what the others leave idle.  The
+// first n_state workgroups (dispatched first: one per CU as long as there are at most as many
+// as CUs) run the state kernel in its two-per-CU form, the next n_den the scan, and the rest
+// alternate: `ratio` 128 * TT token tiles of the in-block part, then one part of the sketch.
+struct BesideStates {
+    const bf16_t *Q, *K, *G;                   // rows as given; sketch matrices [d][r] row-major
+    float *Pnum, *Pden;                        // in-block part out
+    bf16_t *MQ;                                // query sketch out
+    const float *Spart;                        // scan in
+    bf16_t *Shi, *Slo;                         // scan out
+    int heads, per_head, tiles_per_wg, parts_per_block, parts_per_unit;
+    int n_state, n_den, n_tiles, ratio;        // workgroups per role; in-block tiles between two sketch parts
+    size_t g_len;
+};
+
+template <int R, int D, int P, int TT>
+__global__ __launch_bounds__(kWg, 2) void k_state_and_in_block(const float *__restrict__ M8,
+                                                               const bf16_t *__restrict__ V8,
+                                                               bf16_t *__restrict__ Zg, int units, int n, int b,
+                                                               int t, BesideStates a)
+{
+    constexpr int TC = 32;
+    constexpr int S_BYTES = state_lds_bytes<R, D, TC, 1>(), O_BYTES = out_lds_bytes<R, D, TT, false, 1>();
+    constexpr int BYTES = S_BYTES > O_BYTES ? S_BYTES : O_BYTES;
+    static_assert(sizeof(PrepLds<D, R>) <= BYTES, "the sketch role fits the same allocation");
+    __shared__ __attribute__((aligned(16))) unsigned char lds[BYTES];
+    int bid = blockIdx.x;
+    if (bid < a.n_state) {
+        state_workgroup<R, D, 2, true, TC, 1>(M8, V8, Zg, n, b, t, units, lds, bid, a.n_state);
+        return;
+    }
+    bid -= a.n_state;
+    if (bid < a.n_den) {
+        constexpr int PER_UNIT = R * R / kWg;
+        den_scan_workgroup<R>(a.Spart, a.Shi, a.Slo, t, a.parts_per_block, a.parts_per_unit, bid / PER_UNIT,
+                              bid % PER_UNIT);
+        return;
+    }
+    bid -= a.n_den;
+    const int period = a.ratio + 1;
+    if (bid % period == a.ratio) {
+        const size_t tok_wg0 = (size_t)(bid / period) * a.tiles_per_wg * 128;
+        const int u = (int)(tok_wg0 / n);
+        const bf16_t *g = a.G + (a.per_head ? (size_t)(u % a.heads) * a.g_len : 0);
+        prep_sketch_role<D, R, true>(*reinterpret_cast<PrepLds<D, R> *>(lds), a.Q, g, tok_wg0, a.tiles_per_wg, a.MQ,
+                                     nullptr, nullptr);
+    } else {
+        out_workgroup<R, D, P, TT, false, false, false, 1>(a.Q, a.K, V8, nullptr, nullptr, nullptr, nullptr, nullptr,
+                                                           nullptr, a.Pnum, a.Pden, n, b, t, lds,
+                                                           (bid / period) * a.ratio + bid % period, a.n_tiles);
     }
 }
 
@@ -1680,6 +2020,7 @@ int sketch_tiles_per_wg(int b);
 
 struct MfmaWs {
     bf16_t *Gt; bf16_t *MQ; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
+    float *Pnum, *Pden;                          // in-block part of the rows (two-launch output, see k_out)
     float *M32;                                  // learned sketches only: m(x) as fp32 rows
     bf16_t *MKrm;                                // m(K) as bf16 rows: in-block rule of Section 3.1 only
     bf16_t *LW; float *C1, *LVp;                 // learned sketches on MFMA: arranged weights
@@ -1700,6 +2041,15 @@ int sketch_tiles_per_wg(int b)
     return tiles;
 }
 
+// The causal call with exact in-block weights at d = r = 64 runs the in-block part of the output
+// beside the state kernel when the state kernel leaves room for it: at most one state
+// workgroup per CU (ten per unit) and at least one prefix state to compute.
+constexpr int kComputeUnits = 256;
+bool in_block_beside_states(const Problem &pb)
+{
+    return pb.d == 64 && pb.r == 64 && pb.local_exact && pb.t >= 2 && pb.units * 10 <= kComputeUnits;
+}
+
 MfmaWs carve(const Problem &pb, void *ws)
 {
     MfmaWs w;
@@ -1718,6 +2068,8 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.Shi = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
     w.Slo = (bf16_t *)take((size_t)pb.units * tb * R * R * 2);
     w.MKrm = (bf16_t *)take(pb.local_exact ? 0 : rows * R * 2);
+    w.Pnum = (float *)take(in_block_beside_states(pb) ? rows * D * 4 : 0);
+    w.Pden = (float *)take(in_block_beside_states(pb) ? rows * 2 * 4 : 0);
     const bool fast_learned = learned_on_mfma(pb);
     w.M32 = (float *)take(pb.learned && !fast_learned ? rows * R * 4 : 0);
     const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
@@ -1799,6 +2151,11 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     MfmaWs w = carve(pb, ws);
     const int tiles = sketch_tiles_per_wg(pb.b);
     psf_status st;
+    bool v_done = false;                         // value octets already written by the sketch launch
+    // the state kernel's launch also runs the in-block part of the output, the denominator scan
+    // and, with Gaussian sketches of degree 4, the sketch of the query rows
+    const bool beside = D == 64 && R == 64 && P != 2 && in_block_beside_states(pb) && !noncausal && !Den;
+    const bool q_beside = beside && P == 4 && !pb.learned;
     if (pb.learned) {
         const size_t rows = (size_t)pb.units * pb.n, count = rows * R;
         bool fast = false;
@@ -1843,6 +2200,23 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         hipLaunchKernelGGL((k_m_to_octets_and_partials<R, bf16_t>), dim3((unsigned)(rows / part_tokens(pb))),
                            dim3(kWg), 0, s, (const bf16_t *)K, w.MK8, w.Spart, part_tokens(pb));
         PSF_LAUNCH_CHECK();
+    } else if constexpr (P == 4) {
+        // degree 4 with Gaussian sketches: query sketch + value layout in one launch, key sketch
+        const unsigned parts = (unsigned)((size_t)pb.units * pb.n / (128 * (size_t)tiles));
+        if (Den || MK_rm) {                      // the backward pass reads the transposed matrices
+            st = launch_transpose_g(pb, G, w.Gt, s);
+            if (st != PSF_OK) return st;
+        }
+        hipLaunchKernelGGL((k_prep<D, R, false>), dim3(q_beside ? parts : 2 * parts), dim3(kWg), 0, s,
+                           (const bf16_t *)Q, (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                           pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8,
+                           MK_rm ? MK_rm : (pb.local_exact ? nullptr : w.MKrm), w.Spart, w.V8, q_beside ? 0 : 1);
+        PSF_LAUNCH_CHECK();
+        hipLaunchKernelGGL((k_prep<D, R, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
+                           (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles,
+                           w.MQ, w.MK8, MK_rm ? MK_rm : (pb.local_exact ? nullptr : w.MKrm), w.Spart, w.V8, 1);
+        PSF_LAUNCH_CHECK();
+        v_done = true;
     } else {
         st = launch_transpose_g(pb, G, w.Gt, s);
         if (st != PSF_OK) return st;
@@ -1852,19 +2226,47 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
                                     w.Spart, tiles, s);
         if (st != PSF_OK) return st;
     }
-    {
+    if (!v_done) {
         const size_t octets = (size_t)pb.units * pb.n / 8;
         hipLaunchKernelGGL((k_v_octets<D>), dim3((unsigned)((octets * D + kWg - 1) / kWg)), dim3(kWg), 0,
                            s, (const bf16_t *)V, w.V8, octets);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
-    if (pb.t > 1) {
+    if (pb.t > 1 && !beside) {
         hipLaunchKernelGGL((k_den_scan<R>), dim3(R * R / kWg, pb.units), dim3(kWg), 0, s, w.Spart, w.Shi,
                            w.Slo, pb.t, pb.b / part_tokens(pb), pb.n / part_tokens(pb));
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
+    if constexpr (D == 64 && R == 64 && P != 2) {
+        if (beside) {
+            constexpr int TT = 2;
+            const int n_tiles = pb.units * (pb.n / (128 * TT));
+            const int n_q = q_beside ? (int)((size_t)pb.units * pb.n / (128 * (size_t)tiles)) : 0;
+            BesideStates a;
+            a.Q = (const bf16_t *)Q; a.K = (const bf16_t *)K; a.G = (const bf16_t *)G;
+            a.Pnum = w.Pnum; a.Pden = w.Pden; a.MQ = w.MQ;
+            a.Spart = w.Spart; a.Shi = w.Shi; a.Slo = w.Slo;
+            a.heads = pb.heads; a.per_head = pb.per_head ? 1 : 0; a.tiles_per_wg = tiles;
+            a.parts_per_block = pb.b / part_tokens(pb); a.parts_per_unit = pb.n / part_tokens(pb);
+            a.n_state = pb.units * 10; a.n_den = pb.units * (R * R / kWg);
+            a.n_tiles = n_tiles;
+            a.ratio = n_q > 0 ? n_tiles / n_q : n_tiles;       // tiles between two sketch parts (exact: both tile n)
+            a.g_len = pb.g_len;
+            hipLaunchKernelGGL((k_state_and_in_block<R, D, P, TT>),
+                               dim3((unsigned)(a.n_state + a.n_den + n_tiles + n_q)), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+                               pb.units, pb.n, pb.b, pb.t, a);
+            PSF_LAUNCH_CHECK();
+            if (tm) tm->mark();
+            hipLaunchKernelGGL((k_out<R, D, P, TT, false, false, false, 2>), dim3((unsigned)n_tiles), dim3(kWg), 0, s,
+                               (const bf16_t *)Q, (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O,
+                               nullptr, w.Pnum, w.Pden, pb.n, pb.b, pb.t);
+            PSF_LAUNCH_CHECK();
+            if (tm) tm->mark();
+            return PSF_OK;
+        }
+    }
     if (pb.t > 1) {
         st = launch_state<D, R>(pb, w.MK8, w.V8, w.Zg, s);
         if (st != PSF_OK) return st;
@@ -1884,28 +2286,28 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
                     // the backward pass's forward: only where the backward kernels exist
                     if constexpr (D == 64 && R == 64 && P == 4)
                         hipLaunchKernelGGL((k_out<R, D, P, TT, true, false, true>), dim3(grid), dim3(kWg), 0, s, w.MQ,
-                                           mk_rows, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b, pb.t);
+                                           mk_rows, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, nullptr, nullptr, pb.n, pb.b, pb.t);
                     else
                         return PSF_ERR_UNSUPPORTED;
                 } else {
                     hipLaunchKernelGGL((k_out<R, D, P, TT, false, false, true>), dim3(grid), dim3(kWg), 0, s, w.MQ,
-                                       mk_rows, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b, pb.t);
+                                       mk_rows, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, nullptr, nullptr, pb.n, pb.b, pb.t);
                 }
             } else {
                 return PSF_ERR_UNSUPPORTED;
             }
         } else if (noncausal)
             hipLaunchKernelGGL((k_out<R, D, P, TT, false, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
-                               (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b,
-                               pb.t);
+                               (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, nullptr, nullptr, pb.n,
+                               pb.b, pb.t);
         else if (Den)
             hipLaunchKernelGGL((k_out<R, D, P, TT, true>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
-                               (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b,
-                               pb.t);
+                               (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, nullptr, nullptr, pb.n,
+                               pb.b, pb.t);
         else
             hipLaunchKernelGGL((k_out<R, D, P, TT, false>), dim3(grid), dim3(kWg), 0, s, (const bf16_t *)Q,
-                               (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, pb.n, pb.b,
-                               pb.t);
+                               (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O, Den, nullptr, nullptr, pb.n,
+                               pb.b, pb.t);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();
