@@ -559,6 +559,18 @@ def main():
             acc[nm] = acc.get(nm, 0.0) + ms / reps
     fl = stage_flops(cfg, learned=args.learned, noncausal=args.noncausal,
                      local_sketch=args.local_sketch) if path == 1 else None
+    beside = 0 if args.noncausal else psf.fwd_beside_states(desc)
+    if fl and beside & 1:
+        # the launch of the state kernel also ran the in-block part of the output (and the query
+        # sketch): count those flops where their time is
+        U, n, d, b, r = cfg["batch"] * cfg["heads"], cfg["n"], cfg["d"], cfg["b"], cfg["r"]
+        moved = U * n * (b + 1) * (2 * d + 1)
+        fl["output"] -= moved
+        fl["block_states_scan"] += moved
+        if beside & 2:
+            q_sketch = U * 4 * n * d * r
+            fl["sketch_and_layouts"] -= q_sketch
+            fl["block_states_scan"] += q_sketch
     out = {
         "metric": ("noncausal" if args.noncausal else "causal") + "_polysketch_attention_fwd_tokens_per_s",
         "value": tokens * args.steps / elapsed,
@@ -574,6 +586,9 @@ def main():
                    "kernel_path": "mfma_bf16" if path == 1 else "general_fp32"},
         "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
     }
+    if beside & 1:
+        out["stage_note"] = ("block_states_scan = one launch: state kernel + in-block part of the output + denominator "
+                             "scan" + (" + query sketch" if beside & 2 else "") + "; output = cross-block part + division")
     if fl:
         out["tflops"] = fl["total"] / (ms_per_step * 1e-3) / 1e12
         out["pct_mfma_peak"] = 100.0 * out["tflops"] / MFMA_BF16_PEAK_TFLOPS

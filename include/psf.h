@@ -93,6 +93,13 @@ psf_status psf_check_desc(const psf_desc *desc);
  * (everything else the descriptor check admits), -1 = invalid descriptor. */
 int psf_kernel_path(const psf_desc *desc);
 
+/* Which work psf_causal_attn_fwd runs inside the launch of its state kernel (the stage that
+ * psf_stage_name(1, 2) calls "block_states_scan"), for a benchmark that splits flops by stage:
+ * bit 0: the in-block part of the output (Section 3.2; the "output" stage is then the
+ * cross-block part and the division only) and the scan of the denominator partials; bit 1: the
+ * sketch of the query rows (Algorithm 1).  0 where none of this applies.  Host only. */
+int psf_fwd_beside_states(const psf_desc *desc);
+
 /* Bytes of device workspace psf_causal_attn_fwd needs for this descriptor (0 if invalid).
  * Holds the sketches m(Q), m(K), the block prefix states Z_l (Section 3.1) and staging. */
 size_t psf_workspace_bytes(const psf_desc *desc);

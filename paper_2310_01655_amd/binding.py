@@ -17,7 +17,7 @@ F32, BF16 = 0, 1
 FEAT_SKETCH, FEAT_EXACT = 0, 1
 LOCAL_EXACT, LOCAL_SKETCH = 0, 1
 
-EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_workspace_bytes", "psf_g_len", "psf_learned_len",
+EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_fwd_beside_states", "psf_workspace_bytes", "psf_g_len", "psf_learned_len",
            "psf_sketch",
            "psf_causal_attn_fwd", "psf_causal_attn_fwd_static", "psf_causal_attn_fwd_timed", "psf_stage_name",
            "psf_status_string", "psf_noncausal_workspace_bytes", "psf_noncausal_attn_fwd",
@@ -57,6 +57,8 @@ def lib():
         L.psf_check_desc.argtypes = [dp]
         L.psf_kernel_path.restype = ctypes.c_int
         L.psf_kernel_path.argtypes = [dp]
+        L.psf_fwd_beside_states.restype = ctypes.c_int
+        L.psf_fwd_beside_states.argtypes = [dp]
         L.psf_workspace_bytes.restype = ctypes.c_size_t
         L.psf_workspace_bytes.argtypes = [dp]
         L.psf_g_len.restype = ctypes.c_size_t
@@ -133,6 +135,11 @@ def check_desc(desc):
 
 def kernel_path(desc):
     return lib().psf_kernel_path(ctypes.byref(desc))
+
+
+def fwd_beside_states(desc):
+    """Bit 0: in-block part + denominator scan run in the state kernel's launch; bit 1: the query sketch too."""
+    return lib().psf_fwd_beside_states(ctypes.byref(desc))
 
 
 def workspace_bytes(desc):

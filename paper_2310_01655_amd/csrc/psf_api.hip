@@ -224,6 +224,13 @@ int psf_kernel_path(const psf_desc *desc)
     return select_path(pb);
 }
 
+int psf_fwd_beside_states(const psf_desc *desc)
+{
+    Problem pb;
+    if (make_problem(desc, &pb) != PSF_OK || select_path(pb) != 1) return 0;
+    return mfma_beside_states(pb);
+}
+
 size_t psf_g_len(int32_t d, int32_t r, int32_t p)
 {
     if (d <= 0 || r <= 0 || p < 4) return 0;

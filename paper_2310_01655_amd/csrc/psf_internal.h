@@ -89,6 +89,7 @@ psf_status decode_prefill(const Problem &pb, const void *K, const void *V, const
 
 // bf16 MFMA path.
 size_t mfma_workspace_bytes(const Problem &pb);
+int mfma_beside_states(const Problem &pb);
 psf_status mfma_attn(const Problem &pb, const void *Q, const void *K, const void *V,
                      const void *G, void *O, void *ws, hipStream_t s, StageTimer *tm);
 // Sum over n_tok tokens per unit (K, V contiguous [units][n_tok][d]) of phi'(k) v^T, in the output

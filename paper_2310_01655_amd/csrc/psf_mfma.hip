@@ -532,16 +532,129 @@ __device__ __forceinline__ void prep_sketch_role(PrepLds<D, R> &lds, const bf16_
     }
 }
 
+// Key rows for the half-precision state kernel: m(K) as fp16 token octets [rows/8][R][8],
+// multiplied by a power of two alpha chosen per part so that every |alpha m| < 1 (alpha itself
+// goes to scale_out; powers of two keep the scaling exact and the state kernel divides it out
+// again), and the part's S = m^T m from the unscaled values.  fp16 carries more mantissa than the
+// bf16 the products are rounded to elsewhere, but only 5 exponent bits: the scale is what keeps
+// rows of any norm inside them.  Two passes over the part: the largest |m| first (nothing is
+// stored), then the same sketches again (the rows come from the L2 the second time).
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+template <int D, int R>
+__device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf16_t *__restrict__ X,
+                                                   const bf16_t *__restrict__ g, size_t tok_wg0, int tiles_per_wg,
+                                                   _Float16 *__restrict__ MKh, float *__restrict__ scale_out,
+                                                   float *__restrict__ Spart_out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int x = lane & 31, h = lane >> 5;
+    const float scale = sqrtf(1.0f / (float)R);
+    constexpr int KS = D / 16, NT = R / 32;
+    stage_g_transposing<D, R>(lds.g.gt[0], g);
+    stage_g_transposing<D, R>(lds.g.gt[1], g + (size_t)D * R);
+    __syncthreads();
+
+    auto sketch_tile = [&](int tile, f32x16 *m) {
+        const size_t row0 = tok_wg0 + (size_t)tile * 128 + wave * 32;
+        bf16x8 xfr[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[(row0 + x) * D + 16 * s + 8 * h];
+        f32x16 a0[NT], a1[NT];
+        project<D, R, KS, false>(lds.g.gt[0], xfr, a0, x, h);
+        project<D, R, KS, false>(lds.g.gt[1], xfr, a1, x, h);
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct) m[ct] = scale * (a0[ct] * a1[ct]);
+    };
+
+    float mx = 0.f;
+#pragma unroll 1
+    for (int tile = 0; tile < tiles_per_wg; ++tile) {
+        f32x16 m[NT];
+        sketch_tile(tile, m);
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, fabsf(m[ct][v]));
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    if (lane == 0) lds.u.red[wave][0][0] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(lds.u.red[0][0][0], lds.u.red[1][0][0]), fmaxf(lds.u.red[2][0][0], lds.u.red[3][0][0]));
+    // mx = f 2^e with f in [0.5, 1)  ->  alpha = 2^-e (1 for a part of zeros; the exponent is kept
+    // inside the normal range of fp32)
+    // (the exponent of alpha is kept within +-40, so that its square and the ratio of two squares
+    // stay finite in fp32; rows beyond 2^40 times the unit scale are not a case to serve)
+    const int ebits = min(max((int)((__float_as_uint(mx) >> 23) & 0xffu), 126 - 40), 126 + 40);
+    const float alpha = mx > 0.f ? __uint_as_float((uint32_t)(253 - ebits) << 23) : 1.0f;
+    if (threadIdx.x == 0) *scale_out = alpha;
+
+    f32x16 sacc[NT][NT];
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) sacc[i][j] = f32x16{0};
+#pragma unroll 1
+    for (int tile = 0; tile < tiles_per_wg; ++tile) {
+        const size_t row0 = tok_wg0 + (size_t)tile * 128 + wave * 32;
+        f32x16 m[NT];
+        sketch_tile(tile, m);
+        // lane = sketch column 32ct + x, register v = token 8(v/4) + 4h + v%4: half an octet per
+        // register quad, 8 bytes per lane
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int c = 32 * ct + x;
+                const size_t oct = (row0 >> 3) + gq;
+                f16x4 q4 = {(_Float16)(alpha * m[ct][4 * gq]), (_Float16)(alpha * m[ct][4 * gq + 1]),
+                            (_Float16)(alpha * m[ct][4 * gq + 2]), (_Float16)(alpha * m[ct][4 * gq + 3])};
+                *(f16x4 *)&MKh[(oct * R + c) * 8 + 4 * h] = q4;
+            }
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {              // S += M^T M over these 32 tokens
+            bf16x8 f[NT];
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) f[ct] = cvt8_from16(m[ct], 8 * sp);
+#pragma unroll
+            for (int i = 0; i < NT; ++i)
+#pragma unroll
+                for (int j = 0; j < NT; ++j) sacc[i][j] = mfma32(f[i], f[j], sacc[i][j]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            __syncthreads();
+#pragma unroll
+            for (int v = 0; v < 16; ++v) lds.u.red[wave][8 * (v / 4) + 4 * h + (v % 4)][x] = sacc[i][j][v];
+            __syncthreads();
+            for (int idx = threadIdx.x; idx < 32 * 32; idx += kWg) {
+                const int a = idx / 32, c = idx % 32;
+                Spart_out[(size_t)(32 * i + a) * R + 32 * j + c] =
+                    lds.u.red[0][a][c] + lds.u.red[1][a][c] + lds.u.red[2][a][c] + lds.u.red[3][a][c];
+            }
+        }
+}
+
 // KEYS = false: roles 0 and 2 alternate (few registers, four workgroups per CU); KEYS = true: role 1
 // alone (its S accumulators make it the register-heavy one; as one launch with the others it
 // would pull them down to its occupancy).
-template <int D, int R, bool KEYS>
+// F16: for the half-precision state kernel -- role 1 writes fp16 key sketches and their scale
+// (prep_keys_f16_role; MK8 then points to them, Kscale gets one float per part), role 2 also
+// writes the value rows as fp16 token octets (V8h; magnitudes beyond the fp16 range saturate).
+template <int D, int R, bool KEYS, bool F16 = false>
 __global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                               const bf16_t *__restrict__ V, const bf16_t *__restrict__ G,
                                               int n, int heads, int per_head, size_t g_len, int tiles_per_wg,
                                               bf16_t *__restrict__ MQ, float *__restrict__ MK8,
                                               bf16_t *__restrict__ MK_rm, float *__restrict__ Spart,
-                                              bf16_t *__restrict__ V8, int with_q)
+                                              bf16_t *__restrict__ V8, int with_q,
+                                              float *__restrict__ Kscale, _Float16 *__restrict__ V8h)
 {
     // (with_q == 0: the query rows are sketched elsewhere; every workgroup takes role 2)
     __shared__ __attribute__((aligned(16))) PrepLds<D, R> lds;
@@ -573,6 +686,13 @@ __global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__rest
                 pk.z = tmp[q][4] | ((uint32_t)tmp[q][5] << 16);
                 pk.w = tmp[q][6] | ((uint32_t)tmp[q][7] << 16);
                 *(uint4 *)&V8[idx * 8] = pk;
+                if constexpr (F16) {
+                    f16x8 hv;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        hv[j] = (_Float16)fminf(fmaxf(bf16_to_f32(tmp[q][j]), -65504.f), 65504.f);
+                    *(f16x8 *)&V8h[idx * 8] = hv;
+                }
             }
         }
         return;
@@ -581,6 +701,9 @@ __global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__rest
     const bf16_t *g = G + (per_head ? (size_t)(u % heads) * g_len : 0);
     if constexpr (!KEYS)
         prep_sketch_role<D, R, true>(lds, Q, g, tok_wg0, tiles_per_wg, MQ, nullptr, nullptr);
+    else if constexpr (F16)
+        prep_keys_f16_role<D, R>(lds, K, g, tok_wg0, tiles_per_wg, (_Float16 *)MK8, Kscale + part,
+                                 Spart + part * R * R);
     else
         prep_sketch_role<D, R, false>(lds, K, g, tok_wg0, tiles_per_wg, MK_rm, MK8, Spart + part * R * R);
 }
@@ -969,6 +1092,174 @@ __device__ __forceinline__ void state_workgroup(const float *__restrict__ M8, co
         __syncthreads();
     }
     state_body<R, D, NA, SYM, TC, NG>(M8, V8, Zg, n, b, t, u, grp, lds);
+}
+
+// ------------------------------------------------------------------------------------
+// The running prefix state in half precision (r = d = 64, the symmetric deal of state_body with
+// NA = 2): m(K) and V arrive as fp16 token octets ([rows/8][64][8], one 1 KB plane per octet), so
+// a fragment of phi'(k)^T is four packed multiplies of two LDS operands -- m_j[b'] of the lane's
+// column and m_j[a] of its segment's row, each 8 tokens in 16 bytes -- instead of eight
+// multiplies and four conversions, and a 64-token chunk is 16 KB of LDS instead of 25.  fp16 has
+// three more mantissa bits than the bf16 the same products are rounded to elsewhere; its
+// narrow exponent is handled by the per-part scale of the key sketches (prep_keys_f16_role):
+// the accumulators hold C Z with C = alpha^2 of the current part and are multiplied by the
+// ratio (a power of two: exact) when the scale changes; the snapshots store Z itself, bf16,
+// with the symmetry weights, exactly as state_body does.
+//   lds: kStateRing * 16 KB + 1 KB (the unit's scales); (bid, nblk) as for state_workgroup.
+// ------------------------------------------------------------------------------------
+constexpr int kStateF16Chunk = 64, kStateF16Buf = 2 * kStateF16Chunk * 64 * 2;
+constexpr int kStateF16Lds = kStateRing * kStateF16Buf + 1024;
+
+struct StateOpsF16 {
+    f16x8 bfv, av[2], vf[2];
+};
+
+template <int R, int D>
+__device__ __forceinline__ void state_f16_workgroup(const _Float16 *__restrict__ MKh, const _Float16 *__restrict__ V8h,
+                                                    const float *__restrict__ Kscale, bf16_t *__restrict__ Zg,
+                                                    int n, int b, int t, int units, int part_tokens,
+                                                    unsigned char *lds_base, int bid, int nblk)
+{
+    static_assert(R == 64 && D == 64, "planes of 1 KB, ten workgroups per unit");
+    constexpr int TC = kStateF16Chunk, NBUF = kStateRing, CT = 2, NA = 2, SEG = 2, STEPS = TC / 16;
+    constexpr int M_BYTES = TC * R * 2, BUF_BYTES = kStateF16Buf, DMA_PER_CHUNK = BUF_BYTES / 16 / kWg;
+    constexpr int GROUPS = 10;
+    int wg = bid;
+    if ((nblk & 7) == 0) wg = (bid & 7) * (nblk >> 3) + (bid >> 3);
+    const int u = wg / GROUPS, grp = wg % GROUPS;
+    if (u >= units || t < 2) return;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int x = lane & 31, h = lane >> 5;
+    int beta = 0, wv = grp * 4 + wave;
+    while (wv >= 4 * (beta + 1)) { wv -= 4 * (beta + 1); ++beta; }
+    const int a0 = wv * NA * SEG, bcol = 16 * beta + (x & 15);
+
+    // the scales of this unit's parts, squared (phi' = m (x) m carries alpha twice)
+    float *cs = (float *)(lds_base + NBUF * BUF_BYTES);
+    const int parts = n / part_tokens;
+    for (int i = tid; i < parts && i < 256; i += kWg) {
+        const float al = Kscale[(size_t)u * parts + i];
+        cs[i] = al * al;
+    }
+    wait_all_memory();
+
+    const unsigned char *gm = (const unsigned char *)(MKh + (size_t)u * n * R);
+    const unsigned char *gv = (const unsigned char *)(V8h + (size_t)u * n * D);
+    const int chunks = (t - 1) * (b / TC), chunks_per_block = b / TC;
+    const uint32_t copy_off = (uint32_t)tid * 16;
+    const uint32_t lds0 = lds_address(lds_base);
+    auto stage = [&](int slot, int chunk) {          // straight copies: global layout == LDS layout
+        const unsigned char *sm = gm + (size_t)chunk * M_BYTES, *sv = gv + (size_t)chunk * M_BYTES;
+        const uint32_t dst = lds0 + slot * BUF_BYTES + wave * 1024;
+#pragma unroll
+        for (int q = 0; q < M_BYTES / 4096; ++q) dma16_sbase(sm + q * 4096, copy_off, dst + q * 4096);
+#pragma unroll
+        for (int q = 0; q < M_BYTES / 4096; ++q) dma16_sbase(sv + q * 4096, copy_off, dst + M_BYTES + q * 4096);
+    };
+#pragma unroll
+    for (int c = 0; c < NBUF - 1; ++c) stage(c, min(c, chunks - 1));
+    wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
+    __syncthreads();
+
+    const unsigned char *lane_b = lds_base + h * 1024 + bcol * 16;
+    const unsigned char *lane_a = lds_base + h * 1024 + (a0 + ((lane >> 4) & 1)) * 16;
+    const unsigned char *lane_v = lds_base + M_BYTES + h * 1024 + x * 16;
+    auto load_ops = [&](auto slot_tag, auto step_tag) {
+        constexpr int OFF = decltype(slot_tag)::value * BUF_BYTES + decltype(step_tag)::value * 2048;
+        StateOpsF16 o;
+        o.bfv = *(const f16x8 *)(lane_b + OFF);
+#pragma unroll
+        for (int i = 0; i < NA; ++i) o.av[i] = *(const f16x8 *)(lane_a + OFF + i * SEG * 16);
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) o.vf[ct] = *(const f16x8 *)(lane_v + OFF + ct * 512);
+        return o;
+    };
+
+    f32x16 acc[NA][CT];
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+#pragma unroll
+        for (int j = 0; j < CT; ++j) acc[i][j] = f32x16{0};
+    float C = cs[0];
+
+    auto snapshot = [&](int l) {
+        bf16_t *z = Zg + ((size_t)u * (t - 1) + l) * R * R * D;
+        const float invC = 1.0f / C;
+#pragma unroll
+        for (int i = 0; i < NA; ++i)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int a = a0 + i * SEG + gq / 2;
+                    const int bq0 = 16 * beta + 8 * (gq % 2) + 4 * h;
+                    f32x4 q4;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float wsym = bq0 + j > a ? 2.f : (bq0 + j == a ? 1.f : 0.f);
+                        q4[j] = acc[i][ct][4 * gq + j] * (wsym * invC);
+                    }
+                    *(bf16x4 *)&z[(((size_t)a * (R / 8) + bq0 / 8) * D + 32 * ct + x) * 8 + 4 * h] = cvt4(q4);
+                }
+    };
+
+    StateOpsF16 ops[2];
+    ops[0] = load_ops(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{});
+    f16x8 frag = ops[0].bfv * ops[0].av[0];
+    auto run_chunk = [&](auto slot_tag, int chunk) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        stage((SLOT + NBUF - 1) % NBUF, min(chunk + NBUF - 1, chunks - 1));
+        static_for<STEPS>([&](auto s_tag) {
+            constexpr int sidx = decltype(s_tag)::value;
+            if (sidx == STEPS - 1) {
+                wait_vmem_le<(NBUF - 2) * DMA_PER_CHUNK>();
+                __builtin_amdgcn_s_barrier();
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (sidx + 1 < STEPS)
+                ops[(sidx + 1) & 1] = load_ops(slot_tag, std::integral_constant<int, sidx + 1>{});
+            else
+                ops[(sidx + 1) & 1] = load_ops(std::integral_constant<int, (SLOT + 1) % NBUF>{},
+                                               std::integral_constant<int, 0>{});
+            __builtin_amdgcn_sched_group_barrier(0x100, 1 + NA + CT, 0);      // LDS reads first
+            const StateOpsF16 &cur = ops[sidx & 1], &nxt = ops[(sidx + 1) & 1];
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct)
+                    acc[i][ct] = __builtin_amdgcn_mfma_f32_32x32x16_f16(frag, cur.vf[ct], acc[i][ct], 0, 0, 0);
+                frag = i + 1 < NA ? cur.bfv * cur.av[i + 1] : nxt.bfv * nxt.av[0];
+#pragma unroll
+                for (int ct = 0; ct < CT; ++ct) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4 / CT, 0);
+                }
+            }
+        });
+    };
+    int chunk = 0;
+#pragma unroll 1
+    for (int l = 0; l < t - 1; ++l) {
+#pragma unroll 1
+        for (int cb = 0; cb < chunks_per_block; cb += NBUF, chunk += NBUF) {
+            // a new part starts here when its first token does (parts are multiples of 256 tokens)
+            if ((chunk * TC) % part_tokens == 0) {
+                const float c = cs[min((chunk * TC) / part_tokens, 255)];
+                if (c != C) {                             // wave-uniform
+                    const float ratio = c / C;            // powers of two: exact
+#pragma unroll
+                    for (int i = 0; i < NA; ++i)
+#pragma unroll
+                        for (int j = 0; j < CT; ++j) acc[i][j] = acc[i][j] * ratio;
+                    C = c;
+                }
+            }
+            static_for<NBUF>([&](auto slot_tag) { run_chunk(slot_tag, chunk + decltype(slot_tag)::value); });
+        }
+        snapshot(l);
+    }
 }
 
 template <int R, int D, int NA, bool SYM, int TC, int OCC>
@@ -1512,22 +1803,31 @@ struct BesideStates {
     int heads, per_head, tiles_per_wg, parts_per_block, parts_per_unit;
     int n_state, n_den, n_tiles, ratio;        // workgroups per role; in-block tiles between two sketch parts
     size_t g_len;
+    const _Float16 *V8h;                       // half-precision state kernel: value octets, key scales
+    const float *Kscale;
+    int part_tokens;
 };
 
-template <int R, int D, int P, int TT>
+// F16: the state role runs state_f16_workgroup (M8 then holds the fp16 key sketches).
+template <int R, int D, int P, int TT, bool F16>
 __global__ __launch_bounds__(kWg, 2) void k_state_and_in_block(const float *__restrict__ M8,
                                                                const bf16_t *__restrict__ V8,
                                                                bf16_t *__restrict__ Zg, int units, int n, int b,
                                                                int t, BesideStates a)
 {
     constexpr int TC = 32;
-    constexpr int S_BYTES = state_lds_bytes<R, D, TC, 1>(), O_BYTES = out_lds_bytes<R, D, TT, false, 1>();
+    constexpr int S_BYTES = F16 ? kStateF16Lds : state_lds_bytes<R, D, TC, 1>();
+    constexpr int O_BYTES = out_lds_bytes<R, D, TT, false, 1>();
     constexpr int BYTES = S_BYTES > O_BYTES ? S_BYTES : O_BYTES;
     static_assert(sizeof(PrepLds<D, R>) <= BYTES, "the sketch role fits the same allocation");
     __shared__ __attribute__((aligned(16))) unsigned char lds[BYTES];
     int bid = blockIdx.x;
     if (bid < a.n_state) {
-        state_workgroup<R, D, 2, true, TC, 1>(M8, V8, Zg, n, b, t, units, lds, bid, a.n_state);
+        if constexpr (F16)
+            state_f16_workgroup<R, D>((const _Float16 *)M8, a.V8h, a.Kscale, Zg, n, b, t, units, a.part_tokens, lds, bid,
+                                      a.n_state);
+        else
+            state_workgroup<R, D, 2, true, TC, 1>(M8, V8, Zg, n, b, t, units, lds, bid, a.n_state);
         return;
     }
     bid -= a.n_state;
@@ -2021,6 +2321,7 @@ int sketch_tiles_per_wg(int b);
 struct MfmaWs {
     bf16_t *Gt; bf16_t *MQ; float *MK8; bf16_t *V8; bf16_t *Zg; float *Spart; bf16_t *Shi, *Slo;
     float *Pnum, *Pden;                          // in-block part of the rows (two-launch output, see k_out)
+    _Float16 *V8h; float *Kscale;                // half-precision state kernel: value octets, key scales per part
     float *M32;                                  // learned sketches only: m(x) as fp32 rows
     bf16_t *MKrm;                                // m(K) as bf16 rows: in-block rule of Section 3.1 only
     bf16_t *LW; float *C1, *LVp;                 // learned sketches on MFMA: arranged weights
@@ -2047,7 +2348,9 @@ int sketch_tiles_per_wg(int b)
 constexpr int kComputeUnits = 256;
 bool in_block_beside_states(const Problem &pb)
 {
-    return pb.d == 64 && pb.r == 64 && pb.local_exact && pb.t >= 2 && pb.units * 10 <= kComputeUnits;
+    // (and at most 256 sketch parts per unit: the half-precision state kernel keeps their scales in LDS)
+    return pb.d == 64 && pb.r == 64 && pb.local_exact && pb.t >= 2 && pb.units * 10 <= kComputeUnits &&
+           pb.n / 256 <= 256;
 }
 
 MfmaWs carve(const Problem &pb, void *ws)
@@ -2070,6 +2373,8 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.MKrm = (bf16_t *)take(pb.local_exact ? 0 : rows * R * 2);
     w.Pnum = (float *)take(in_block_beside_states(pb) ? rows * D * 4 : 0);
     w.Pden = (float *)take(in_block_beside_states(pb) ? rows * 2 * 4 : 0);
+    w.V8h = (_Float16 *)take(in_block_beside_states(pb) ? rows * D * 2 : 0);
+    w.Kscale = (float *)take(in_block_beside_states(pb) ? parts * 4 : 0);
     const bool fast_learned = learned_on_mfma(pb);
     w.M32 = (float *)take(pb.learned && !fast_learned ? rows * R * 4 : 0);
     const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
@@ -2207,15 +2512,31 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
             st = launch_transpose_g(pb, G, w.Gt, s);
             if (st != PSF_OK) return st;
         }
-        hipLaunchKernelGGL((k_prep<D, R, false>), dim3(q_beside ? parts : 2 * parts), dim3(kWg), 0, s,
-                           (const bf16_t *)Q, (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
-                           pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8,
-                           MK_rm ? MK_rm : (pb.local_exact ? nullptr : w.MKrm), w.Spart, w.V8, q_beside ? 0 : 1);
-        PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_prep<D, R, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q, (const bf16_t *)K,
-                           (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.g_len, tiles,
-                           w.MQ, w.MK8, MK_rm ? MK_rm : (pb.local_exact ? nullptr : w.MKrm), w.Spart, w.V8, 1);
-        PSF_LAUNCH_CHECK();
+        bf16_t *mk_rows = MK_rm ? MK_rm : (pb.local_exact ? nullptr : w.MKrm);
+        if (q_beside) {
+            // the state kernel of this path works in half precision: fp16 value octets and key sketches
+            hipLaunchKernelGGL((k_prep<D, R, false, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                               (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                               pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 0, w.Kscale,
+                               w.V8h);
+            PSF_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_prep<D, R, true, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                               (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                               pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1, w.Kscale,
+                               w.V8h);
+            PSF_LAUNCH_CHECK();
+        } else {
+            hipLaunchKernelGGL((k_prep<D, R, false>), dim3(2 * parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                               (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                               pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1, nullptr,
+                               nullptr);
+            PSF_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_prep<D, R, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                               (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                               pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1, nullptr,
+                               nullptr);
+            PSF_LAUNCH_CHECK();
+        }
         v_done = true;
     } else {
         st = launch_transpose_g(pb, G, w.Gt, s);
@@ -2254,9 +2575,14 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
             a.n_tiles = n_tiles;
             a.ratio = n_q > 0 ? n_tiles / n_q : n_tiles;       // tiles between two sketch parts (exact: both tile n)
             a.g_len = pb.g_len;
-            hipLaunchKernelGGL((k_state_and_in_block<R, D, P, TT>),
-                               dim3((unsigned)(a.n_state + a.n_den + n_tiles + n_q)), dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
-                               pb.units, pb.n, pb.b, pb.t, a);
+            a.V8h = w.V8h; a.Kscale = w.Kscale; a.part_tokens = part_tokens(pb);
+            const dim3 grid((unsigned)(a.n_state + a.n_den + n_tiles + n_q));
+            if (q_beside)
+                hipLaunchKernelGGL((k_state_and_in_block<R, D, P, TT, true>), grid, dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+                                   pb.units, pb.n, pb.b, pb.t, a);
+            else
+                hipLaunchKernelGGL((k_state_and_in_block<R, D, P, TT, false>), grid, dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
+                                   pb.units, pb.n, pb.b, pb.t, a);
             PSF_LAUNCH_CHECK();
             if (tm) tm->mark();
             hipLaunchKernelGGL((k_out<R, D, P, TT, false, false, false, 2>), dim3((unsigned)n_tiles), dim3(kWg), 0, s,
@@ -2331,6 +2657,15 @@ static Problem base_case_problem(const Problem &pb0)
 }
 
 size_t mfma_workspace_bytes(const Problem &pb) { return carve(base_case_problem(pb), nullptr).total; }
+
+// What the forward call runs inside the state kernel's launch (see k_state_and_in_block):
+// bit 0: the in-block part of the output and the denominator scan; bit 1: the query sketch.
+int mfma_beside_states(const Problem &pb0)
+{
+    const Problem pb = base_case_problem(pb0);
+    if (!(pb.d == 64 && pb.r == 64 && pb.p != 2 && in_block_beside_states(pb))) return 0;
+    return 1 | (pb.p == 4 && !pb.learned ? 2 : 0);
+}
 
 bool mfma_bwd_supported(const Problem &pb)
 {

@@ -8,7 +8,7 @@ import torch
 import oracle
 from paper_2310_01655_amd import binding as psf
 from paper_2310_01655_amd import inputs
-from parity import as_f64, assert_close, errors, gpu_attn, oracle_attn, oracle_units_rows, probe_rows
+from parity import as_f64, assert_close, assert_close_scaled, errors, gpu_attn, oracle_attn, oracle_units_rows, probe_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -232,3 +232,25 @@ def test_forward_replays_from_a_captured_graph():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(O, eager), "replay %d differs from the eager call" % rep
+
+
+@pytest.mark.parametrize("k_scales,v_scale", [((8.0, 8.0), 1.0), ((1 / 16, 1 / 16), 64.0), ((8.0, 0.25), 1.0),
+                                               ((0.25, 1.0, 16.0, 0.5), 1 / 256)])
+def test_rows_of_other_norms_through_the_half_precision_state_kernel(k_scales, v_scale):
+    """The state kernel of the d = r = 64 path multiplies fp16 operands; what keeps key rows of
+    any norm inside fp16's exponent range is a power-of-two scale per 256..1024-token part of the
+    key sketches, divided out again exactly.  Key rows of norm 8 (what layer normalisation gives
+    at d = 64), of norm 1/16, and norms that change from block to block (so that the running
+    accumulators are rescaled on the way), with values far from unit scale, against the oracle."""
+    cfg = mk(1, 2, 2048, 64, 4, 64, 512)
+    q, k, v, G = draw(cfg, seed=43)
+    seg = cfg["n"] // len(k_scales)
+    k = k.float()
+    for i, sc in enumerate(k_scales):
+        k[:, :, i * seg:(i + 1) * seg] *= sc
+    k = k.to(torch.bfloat16)
+    v = (v.float() * v_scale).to(torch.bfloat16)
+    got, desc = gpu_attn(cfg, q, k, v, G)
+    assert psf.kernel_path(desc) == 1
+    want = oracle_attn(cfg, q, k, v, G)
+    print("norms", k_scales, v_scale, assert_close_scaled(got.numpy(), want, "bf16", "k x %s, v x %s" % (k_scales, v_scale)))
