@@ -235,7 +235,9 @@ psf_status psf_causal_attn_bwd_timed(const psf_desc *desc, const void *Q, const 
 
 /*
  * Forward + backward without running the forward pass twice (for callers that train).
- * psf_causal_attn_fwd_save computes the same O as psf_causal_attn_fwd and leaves in `save`
+ * psf_causal_attn_fwd_save computes the O of psf_causal_attn_fwd (the same function; where the
+ * plain call forms the products of its prefix states in half precision the two agree within
+ * the rounding of the storage type, not bit for bit) and leaves in `save`
  * (caller memory, psf_fwd_save_bytes(desc) bytes, 256-byte aligned) what the backward pass would
  * otherwise recompute: the sketches, the block states and the denominators.
  * psf_causal_attn_bwd_saved takes that buffer untouched since, the same Q, K, V, G and the O the

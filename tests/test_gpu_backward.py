@@ -10,7 +10,7 @@ import torch
 import oracle
 from paper_2310_01655_amd import binding as psf
 from paper_2310_01655_amd import inputs
-from parity import as_f64, assert_close_scaled
+from parity import as_f64, assert_close, assert_close_scaled
 
 pytestmark = pytest.mark.gpu
 
@@ -176,8 +176,11 @@ def test_backward_config3_full_size_sampled_rows_and_identities():
 @pytest.mark.parametrize("r,b,local", [(64, 256, psf.LOCAL_EXACT), (32, 512, psf.LOCAL_EXACT), (64, 256, psf.LOCAL_SKETCH)])
 def test_saved_forward_gives_the_same_output_and_gradients(r, b, local):
     """psf_causal_attn_fwd_save + psf_causal_attn_bwd_saved against the plain forward and the
-    plain (recomputing) backward of the same library: identical bits, since the same kernels run
-    on the same data; the plain calls are the ones checked against the oracle above."""
+    plain (recomputing) backward of the same library.  The gradients are identical bits: the
+    recomputing backward runs the very forward kernels the saving call runs, on the same data.
+    The plain forward call may take other kernels for the prefix states (half-precision products
+    where the in-block part runs beside them), so its output agrees within the rounding of the
+    storage type, not bit for bit; the plain calls are the ones checked against the oracle above."""
     batch, heads, n, d, p = 1, 3, 1024, 64, 4
     q, k, v = inputs.make_qkv(batch, heads, n, d, seed=53, dtype="bf16")
     dO = inputs.make_dout(batch, heads, n, d, seed=53, dtype="bf16")
@@ -191,7 +194,7 @@ def test_saved_forward_gives_the_same_output_and_gradients(r, b, local):
     g1 = psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd)
     g2 = psf.psf_causal_attn_bwd_saved(desc, qd, kd, vd, Gd, O2, dOd, save)
     torch.cuda.synchronize()
-    assert torch.equal(O1, O2)
+    assert_close(O2.float().cpu().numpy(), O1.float().cpu().numpy(), "bf16", "saving forward against plain forward")
     for a, c in zip(g1, g2):
         assert torch.equal(a, c)
 
