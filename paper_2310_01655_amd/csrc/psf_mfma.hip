@@ -533,12 +533,11 @@ __device__ __forceinline__ void prep_sketch_role(PrepLds<D, R> &lds, const bf16_
 }
 
 // Key rows for the half-precision state kernel: m(K) as fp16 token octets [rows/8][R][8],
-// multiplied by a power of two alpha chosen per part so that every |alpha m| < 1 (alpha itself
-// goes to scale_out; powers of two keep the scaling exact and the state kernel divides it out
-// again), and the part's S = m^T m from the unscaled values.  fp16 carries more mantissa than the
-// bf16 the products are rounded to elsewhere, but only 5 exponent bits: the scale is what keeps
-// rows of any norm inside them.  Two passes over the part: the largest |m| first (nothing is
-// stored), then the same sketches again (the rows come from the L2 the second time).
+// multiplied by a power of two alpha chosen per 128-token tile so that every |alpha m| < 1
+// (alpha itself goes to scale_out, one float per tile; powers of two keep the scaling exact and
+// the state kernel divides it out again), and the part's S = m^T m from the unscaled values.
+// fp16 carries more mantissa than the bf16 the products are rounded to elsewhere, but only 5
+// exponent bits: the scale is what keeps rows of any norm inside them.
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
@@ -569,39 +568,34 @@ __device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf1
         for (int ct = 0; ct < NT; ++ct) m[ct] = scale * (a0[ct] * a1[ct]);
     };
 
-    float mx = 0.f;
-#pragma unroll 1
-    for (int tile = 0; tile < tiles_per_wg; ++tile) {
-        f32x16 m[NT];
-        sketch_tile(tile, m);
-#pragma unroll
-        for (int ct = 0; ct < NT; ++ct)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, fabsf(m[ct][v]));
-    }
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-    if (lane == 0) lds.u.red[wave][0][0] = mx;
-    __syncthreads();
-    mx = fmaxf(fmaxf(lds.u.red[0][0][0], lds.u.red[1][0][0]), fmaxf(lds.u.red[2][0][0], lds.u.red[3][0][0]));
-    // mx = f 2^e with f in [0.5, 1)  ->  alpha = 2^-e (1 for a part of zeros; the exponent is kept
-    // inside the normal range of fp32)
-    // (the exponent of alpha is kept within +-40, so that its square and the ratio of two squares
-    // stay finite in fp32; rows beyond 2^40 times the unit scale are not a case to serve)
-    const int ebits = min(max((int)((__float_as_uint(mx) >> 23) & 0xffu), 126 - 40), 126 + 40);
-    const float alpha = mx > 0.f ? __uint_as_float((uint32_t)(253 - ebits) << 23) : 1.0f;
-    if (threadIdx.x == 0) *scale_out = alpha;
-
     f32x16 sacc[NT][NT];
 #pragma unroll
     for (int i = 0; i < NT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j) sacc[i][j] = f32x16{0};
+    float *tile_max = &lds.u.red[0][0][0];                 // [2][4]: the four waves' maxima, two tiles in flight
 #pragma unroll 1
     for (int tile = 0; tile < tiles_per_wg; ++tile) {
         const size_t row0 = tok_wg0 + (size_t)tile * 128 + wave * 32;
         f32x16 m[NT];
         sketch_tile(tile, m);
+        float mx = 0.f;
+#pragma unroll
+        for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, fabsf(m[ct][v]));
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        if (lane == 0) tile_max[(tile & 1) * 4 + wave] = mx;
+        __syncthreads();                                   // (the slot is written again two tiles later: one barrier per tile)
+        const float *tm = tile_max + (tile & 1) * 4;
+        mx = fmaxf(fmaxf(tm[0], tm[1]), fmaxf(tm[2], tm[3]));
+        // mx = f 2^e with f in [0.5, 1)  ->  alpha = 2^-e (1 for a tile of zeros).  The exponent of
+        // alpha is kept within +-40, so that its square and the ratio of two squares stay finite
+        // in fp32; rows beyond 2^40 times the unit scale are not a case to serve.
+        const int ebits = min(max((int)((__float_as_uint(mx) >> 23) & 0xffu), 126 - 40), 126 + 40);
+        const float alpha = mx > 0.f ? __uint_as_float((uint32_t)(253 - ebits) << 23) : 1.0f;
+        if (threadIdx.x == 0) scale_out[tile] = alpha;
         // lane = sketch column 32ct + x, register v = token 8(v/4) + 4h + v%4: half an octet per
         // register quad, 8 bytes per lane
 #pragma unroll
@@ -645,7 +639,7 @@ __device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf1
 // alone (its S accumulators make it the register-heavy one; as one launch with the others it
 // would pull them down to its occupancy).
 // F16: for the half-precision state kernel -- role 1 writes fp16 key sketches and their scale
-// (prep_keys_f16_role; MK8 then points to them, Kscale gets one float per part), role 2 also
+// (prep_keys_f16_role; MK8 then points to them, Kscale gets one float per 128-token tile), role 2 also
 // writes the value rows as fp16 token octets (V8h; magnitudes beyond the fp16 range saturate).
 template <int D, int R, bool KEYS, bool F16 = false>
 __global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
@@ -702,7 +696,7 @@ __global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__rest
     if constexpr (!KEYS)
         prep_sketch_role<D, R, true>(lds, Q, g, tok_wg0, tiles_per_wg, MQ, nullptr, nullptr);
     else if constexpr (F16)
-        prep_keys_f16_role<D, R>(lds, K, g, tok_wg0, tiles_per_wg, (_Float16 *)MK8, Kscale + part,
+        prep_keys_f16_role<D, R>(lds, K, g, tok_wg0, tiles_per_wg, (_Float16 *)MK8, Kscale + part * tiles_per_wg,
                                  Spart + part * R * R);
     else
         prep_sketch_role<D, R, false>(lds, K, g, tok_wg0, tiles_per_wg, MK_rm, MK8, Spart + part * R * R);
@@ -1101,14 +1095,16 @@ __device__ __forceinline__ void state_workgroup(const float *__restrict__ M8, co
 // column and m_j[a] of its segment's row, each 8 tokens in 16 bytes -- instead of eight
 // multiplies and four conversions, and a 64-token chunk is 16 KB of LDS instead of 25.  fp16 has
 // three more mantissa bits than the bf16 the same products are rounded to elsewhere; its
-// narrow exponent is handled by the per-part scale of the key sketches (prep_keys_f16_role):
-// the accumulators hold C Z with C = alpha^2 of the current part and are multiplied by the
-// ratio (a power of two: exact) when the scale changes; the snapshots store Z itself, bf16,
-// with the symmetry weights, exactly as state_body does.
-//   lds: kStateRing * 16 KB + 1 KB (the unit's scales); (bid, nblk) as for state_workgroup.
+// narrow exponent is handled by the scale of the key sketches, one power of two per 128-token
+// tile (prep_keys_f16_role): the accumulators hold C Z with C = alpha^2 of the current tile and
+// are multiplied by the ratio (a power of two: exact) when the scale changes; the snapshots
+// store Z itself, bf16, with the symmetry weights, exactly as state_body does.
+//   lds: kStateRing * 16 KB + 2 KB (the unit's scales, at most 512 tiles); (bid, nblk) as for
+//   state_workgroup.
 // ------------------------------------------------------------------------------------
 constexpr int kStateF16Chunk = 64, kStateF16Buf = 2 * kStateF16Chunk * 64 * 2;
-constexpr int kStateF16Lds = kStateRing * kStateF16Buf + 1024;
+constexpr int kStateF16Tiles = 512;             // 128-token tiles per unit, at most
+constexpr int kStateF16Lds = kStateRing * kStateF16Buf + kStateF16Tiles * 4;
 
 struct StateOpsF16 {
     f16x8 bfv, av[2], vf[2];
@@ -1117,7 +1113,7 @@ struct StateOpsF16 {
 template <int R, int D>
 __device__ __forceinline__ void state_f16_workgroup(const _Float16 *__restrict__ MKh, const _Float16 *__restrict__ V8h,
                                                     const float *__restrict__ Kscale, bf16_t *__restrict__ Zg,
-                                                    int n, int b, int t, int units, int part_tokens,
+                                                    int n, int b, int t, int units,
                                                     unsigned char *lds_base, int bid, int nblk)
 {
     static_assert(R == 64 && D == 64, "planes of 1 KB, ten workgroups per unit");
@@ -1136,11 +1132,11 @@ __device__ __forceinline__ void state_f16_workgroup(const _Float16 *__restrict__
     while (wv >= 4 * (beta + 1)) { wv -= 4 * (beta + 1); ++beta; }
     const int a0 = wv * NA * SEG, bcol = 16 * beta + (x & 15);
 
-    // the scales of this unit's parts, squared (phi' = m (x) m carries alpha twice)
+    // the scales of this unit's 128-token tiles, squared (phi' = m (x) m carries alpha twice)
     float *cs = (float *)(lds_base + NBUF * BUF_BYTES);
-    const int parts = n / part_tokens;
-    for (int i = tid; i < parts && i < 256; i += kWg) {
-        const float al = Kscale[(size_t)u * parts + i];
+    const int tiles = n / 128;
+    for (int i = tid; i < tiles && i < kStateF16Tiles; i += kWg) {
+        const float al = Kscale[(size_t)u * tiles + i];
         cs[i] = al * al;
     }
     wait_all_memory();
@@ -1244,19 +1240,21 @@ __device__ __forceinline__ void state_f16_workgroup(const _Float16 *__restrict__
     for (int l = 0; l < t - 1; ++l) {
 #pragma unroll 1
         for (int cb = 0; cb < chunks_per_block; cb += NBUF, chunk += NBUF) {
-            // a new part starts here when its first token does (parts are multiples of 256 tokens)
-            if ((chunk * TC) % part_tokens == 0) {
-                const float c = cs[min((chunk * TC) / part_tokens, 255)];
-                if (c != C) {                             // wave-uniform
-                    const float ratio = c / C;            // powers of two: exact
+            static_for<NBUF>([&](auto slot_tag) {
+                constexpr int SLOT = decltype(slot_tag)::value;
+                if constexpr (SLOT % 2 == 0) {            // a 128-token tile starts: two chunks
+                    const float c = cs[min((chunk + SLOT) / 2, kStateF16Tiles - 1)];
+                    if (c != C) {                         // wave-uniform
+                        const float ratio = c / C;        // powers of two: exact
 #pragma unroll
-                    for (int i = 0; i < NA; ++i)
+                        for (int i = 0; i < NA; ++i)
 #pragma unroll
-                        for (int j = 0; j < CT; ++j) acc[i][j] = acc[i][j] * ratio;
-                    C = c;
+                            for (int j = 0; j < CT; ++j) acc[i][j] = acc[i][j] * ratio;
+                        C = c;
+                    }
                 }
-            }
-            static_for<NBUF>([&](auto slot_tag) { run_chunk(slot_tag, chunk + decltype(slot_tag)::value); });
+                run_chunk(slot_tag, chunk + SLOT);
+            });
         }
         snapshot(l);
     }
@@ -1804,8 +1802,7 @@ struct BesideStates {
     int n_state, n_den, n_tiles, ratio;        // workgroups per role; in-block tiles between two sketch parts
     size_t g_len;
     const _Float16 *V8h;                       // half-precision state kernel: value octets, key scales
-    const float *Kscale;
-    int part_tokens;
+    const float *Kscale;                       // one per 128-token tile
 };
 
 // F16: the state role runs state_f16_workgroup (M8 then holds the fp16 key sketches).
@@ -1824,8 +1821,7 @@ __global__ __launch_bounds__(kWg, 2) void k_state_and_in_block(const float *__re
     int bid = blockIdx.x;
     if (bid < a.n_state) {
         if constexpr (F16)
-            state_f16_workgroup<R, D>((const _Float16 *)M8, a.V8h, a.Kscale, Zg, n, b, t, units, a.part_tokens, lds, bid,
-                                      a.n_state);
+            state_f16_workgroup<R, D>((const _Float16 *)M8, a.V8h, a.Kscale, Zg, n, b, t, units, lds, bid, a.n_state);
         else
             state_workgroup<R, D, 2, true, TC, 1>(M8, V8, Zg, n, b, t, units, lds, bid, a.n_state);
         return;
@@ -2348,9 +2344,9 @@ int sketch_tiles_per_wg(int b)
 constexpr int kComputeUnits = 256;
 bool in_block_beside_states(const Problem &pb)
 {
-    // (and at most 256 sketch parts per unit: the half-precision state kernel keeps their scales in LDS)
+    // (and at most 512 tiles of 128 tokens per unit: the half-precision state kernel keeps their scales in LDS)
     return pb.d == 64 && pb.r == 64 && pb.local_exact && pb.t >= 2 && pb.units * 10 <= kComputeUnits &&
-           pb.n / 256 <= 256;
+           pb.n / 128 <= 512;
 }
 
 MfmaWs carve(const Problem &pb, void *ws)
@@ -2374,7 +2370,7 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.Pnum = (float *)take(in_block_beside_states(pb) ? rows * D * 4 : 0);
     w.Pden = (float *)take(in_block_beside_states(pb) ? rows * 2 * 4 : 0);
     w.V8h = (_Float16 *)take(in_block_beside_states(pb) ? rows * D * 2 : 0);
-    w.Kscale = (float *)take(in_block_beside_states(pb) ? parts * 4 : 0);
+    w.Kscale = (float *)take(in_block_beside_states(pb) ? rows / 128 * 4 : 0);
     const bool fast_learned = learned_on_mfma(pb);
     w.M32 = (float *)take(pb.learned && !fast_learned ? rows * R * 4 : 0);
     const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
@@ -2575,7 +2571,7 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
             a.n_tiles = n_tiles;
             a.ratio = n_q > 0 ? n_tiles / n_q : n_tiles;       // tiles between two sketch parts (exact: both tile n)
             a.g_len = pb.g_len;
-            a.V8h = w.V8h; a.Kscale = w.Kscale; a.part_tokens = part_tokens(pb);
+            a.V8h = w.V8h; a.Kscale = w.Kscale;
             const dim3 grid((unsigned)(a.n_state + a.n_den + n_tiles + n_q));
             if (q_beside)
                 hipLaunchKernelGGL((k_state_and_in_block<R, D, P, TT, true>), grid, dim3(kWg), 0, s, w.MK8, w.V8, w.Zg,
