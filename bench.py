@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # runs summarised in profiles/ (scaled by the copy calibration described there).  bench.py
 # cannot collect counters itself; workloads without a committed counter run report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("config3", "output"): 1.236e9,
-    ("config3", "block_states_scan"): 0.537e9,
+    ("config3", "output"): 0.689e9,                 # k_out, cross-block part: 588 MB read + 101 MB written
+    ("config3", "block_states_scan"): 1.566e9,      # k_state_and_in_block: 1002 MB read + 564 MB written
 }
 
 
@@ -593,13 +593,23 @@ def main():
         out["tflops"] = fl["total"] / (ms_per_step * 1e-3) / 1e12
         out["pct_mfma_peak"] = 100.0 * out["tflops"] / MFMA_BF16_PEAK_TFLOPS
         dom = max((nm for nm in acc if nm in fl), key=lambda nm: acc[nm])
-        achieved = fl[dom] / (acc[dom] * 1e-3) / 1e12
-        out["roofline"] = {"kernel": dom, "bound": "mfma", "achieved": achieved,
+        # The event-timed calls wait for the stream after every call, and the kernels of a call
+        # that starts on an idle GPU run a few per cent faster than in the back-to-back steps of
+        # the timed region (their sum is below the step time although nothing lies between
+        # them): the stage times are stretched to add up to the measured step.
+        stretch = max(1.0, ms_per_step / sum(acc.values()))
+        achieved = fl[dom] / (acc[dom] * stretch * 1e-3) / 1e12
+        kernel_of = {"sketch_and_layouts": "k_prep / k_sketch", "block_states_scan": "k_state", "output": "k_out"}
+        if beside & 1:
+            kernel_of.update({"block_states_scan": "k_state_and_in_block", "output": "k_out (cross-block part)"})
+        out["roofline"] = {"kernel": dom, "kernel_name": kernel_of.get(dom, dom), "bound": "mfma", "achieved": achieved,
+                           "duration_ms": acc[dom] * stretch, "stage_stretch": stretch,
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
                            "traffic": None if (args.noncausal or args.learned or args.local_sketch)
                            else MEASURED_TRAFFIC_BYTES.get((args.workload, dom)),
-                           "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc if nm in fl}}
+                           "per_stage_tflops": {nm: fl[nm] / (acc[nm] * stretch * 1e-3) / 1e12
+                                                for nm in acc if nm in fl and acc[nm] > 0.02}}
     elif cfg["p"] == 4 and not args.learned:
         # general fp32 kernels (plain vector arithmetic): the whole step against the fp32 vector peak
         total = stage_flops(cfg, noncausal=args.noncausal, local_sketch=args.local_sketch)["total"]

@@ -2,13 +2,17 @@
 // block lower-triangular algorithm of PolySketchFormer (arXiv 2310.01655, Sections 3.1, 3.2).
 //
 // Kernels (R = sketch size r, D = head size d = dv, b = block size, t = n/b):
-//   k_transpose_g  sketch matrices transposed once (operand-friendly for the sketch kernel).
-//   k_sketch       Algorithm 1 on bf16 MFMA.  m(Q) is stored row-major bf16; m(K) is stored as
-//                  fp32 "token octets" [n/8][2][R][4] so that the state kernel can stage it into
-//                  LDS with straight copies.  The K side also accumulates S = m(K)^T m(K) per
-//                  workgroup (R x R): the "ones" column of H_l = phi'(K_l)^T [V_l | 1], because
-//                  phi' = m (x) m (Algorithm 1).
-//   k_v_octets     V -> [n/8][D][8] bf16 (same octet layout).
+//   k_prep         degree 4 with Gaussian sketches: Algorithm 1 on bf16 MFMA for the query rows
+//                  (m(Q) row-major bf16), for the key rows (m(K) as "token octets", see below, and
+//                  the partial sums S = m(K)^T m(K) per workgroup: the "ones" column of
+//                  H_l = phi'(K_l)^T [V_l | 1], because phi' = m (x) m) and V -> [n/8][D][8] bf16,
+//                  as roles of two launches (queries + values at four workgroups per CU, keys
+//                  at two); the sketch matrices are transposed on their way into LDS.  m(K) is
+//                  stored as fp32 octets [n/8][2][R][4], or, for the half-precision state
+//                  kernel, as fp16 octets [n/8][R][8] scaled by a power of two per 128 tokens.
+//   k_transpose_g, k_sketch, k_v_octets
+//                  the same steps as separate launches: degree 8 (two levels, the first level's
+//                  accumulators are the second level's operands) and the backward pass.
 //   k_den_scan     prefix of the S partials over blocks, stored as bf16 hi + lo MFMA operands.
 //   k_state        running prefix state Z = sum phi'(k_j) v_j^T kept in MFMA accumulators while
 //                  one workgroup walks the blocks in order; phi'(k_j) = m_j (x) m_j is expanded
@@ -22,7 +26,15 @@
 //                  (Section 3.2) kept in registers, plus phi'(Q_l) Z_l with phi'(q_i) expanded
 //                  in registers as the MFMA operand, then the division by 1 + denominator
 //                  (Section 3).  NONCAUSAL instantiation (Section 2.2): no in-block phase, one
-//                  state for all tokens.
+//                  state for all tokens.  PART = 1 / 2: the in-block part alone (fp32 rows and
+//                  row sums left in the workspace) and the cross-block part that finishes them.
+//   k_state_and_in_block
+//                  d = r = 64, exact in-block weights, at most one state workgroup per CU: one
+//                  launch whose workgroups take one of four roles by index -- the state kernel
+//                  (in half precision when k_prep left fp16 sketches: state_f16_workgroup),
+//                  the denominator scan, the in-block part of the output (k_out's PART 1) and
+//                  the query sketch -- so that the in-block tiles fill the SIMD slots the
+//                  state workgroups (one wave per SIMD) leave empty; k_out PART 2 follows.
 //   k_learned_prep, k_learned_sketch
 //                  Algorithm 2 (learned sketches) of degree 4 with d = 64 on MFMA; other learned
 //                  cases take m(x) from the general fp32 kernel through k_m_to_bf16 /
@@ -2342,6 +2354,10 @@ int sketch_tiles_per_wg(int b)
 // beside the state kernel when the state kernel leaves room for it: at most one state
 // workgroup per CU (ten per unit) and at least one prefix state to compute.
 constexpr int kComputeUnits = 256;
+// From this many rows per tensor on, the sketches and layouts are HBM-bound whatever the number
+// of launches, and the separate kernels (matrices transposed once, straight copies into LDS)
+// move the bytes 5 to 13 % faster than k_prep's roles; below, fewer launches win.
+constexpr size_t kPrepMaxRows = (size_t)1 << 22;
 bool in_block_beside_states(const Problem &pb)
 {
     // (and at most 512 tiles of 128 tokens per unit: the half-precision state kernel keeps their scales in LDS)
@@ -2501,7 +2517,8 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         hipLaunchKernelGGL((k_m_to_octets_and_partials<R, bf16_t>), dim3((unsigned)(rows / part_tokens(pb))),
                            dim3(kWg), 0, s, (const bf16_t *)K, w.MK8, w.Spart, part_tokens(pb));
         PSF_LAUNCH_CHECK();
-    } else if constexpr (P == 4) {
+    } else if (P == 4 && (q_beside || (size_t)pb.units * pb.n < kPrepMaxRows)) {
+      if constexpr (P == 4) {
         // degree 4 with Gaussian sketches: query sketch + value layout in one launch, key sketch
         const unsigned parts = (unsigned)((size_t)pb.units * pb.n / (128 * (size_t)tiles));
         if (Den || MK_rm) {                      // the backward pass reads the transposed matrices
@@ -2534,6 +2551,7 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
             PSF_LAUNCH_CHECK();
         }
         v_done = true;
+      }
     } else {
         st = launch_transpose_g(pb, G, w.Gt, s);
         if (st != PSF_OK) return st;
