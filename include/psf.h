@@ -213,7 +213,9 @@ psf_status psf_noncausal_attn_fwd_timed(const psf_desc *desc, const void *Q, con
  *   workspace: at least psf_bwd_workspace_bytes(desc) bytes, 256-byte aligned.  The forward
  *   quantities are recomputed inside; nothing has to be kept from the forward call.
  * Supported: PSF_FEAT_SKETCH with either in-block rule, every p, r, d, dv, b and dtype the
- * descriptor check admits (fp32 arithmetic).  PSF_FEAT_EXACT returns PSF_ERR_UNSUPPORTED.
+ * descriptor check admits (fp32 arithmetic), Gaussian or learned sketches (with learned ones G
+ * holds the networks' parameters and this call treats them as constants; see
+ * psf_causal_attn_bwd_learned).  PSF_FEAT_EXACT returns PSF_ERR_UNSUPPORTED.
  * Kernels: bf16 storage with d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0, random sketches and
  * PSF_LOCAL_EXACT (or PSF_LOCAL_SKETCH with r = 64) runs on MFMA (psf_bwd_kernel_path == 3;
  * bf16 operands, fp32 accumulation, g and
@@ -232,6 +234,24 @@ psf_status psf_causal_attn_bwd_timed(const psf_desc *desc, const void *Q, const 
                                      void *dK, void *dV, void *workspace, size_t workspace_bytes,
                                      void *hip_stream, float *stage_ms, int32_t n_stages,
                                      int32_t *n_written);
+
+/*
+ * psf_causal_attn_bwd_learned -- psf_causal_attn_bwd for desc->learned = 1 that also returns the
+ * gradient with respect to the parameters of the learned sketch (Algorithm 2, Appendix D: the
+ * networks are trained with the model, Section 2.3): the chain rule through
+ * sqrt(r) tanh(f1(M1) * f2(M2) / sqrt(r)) at every node and through every network layer by
+ * layer (dense layers, tanh-form gelu, layer normalisation), summed over the query and the key
+ * rows that share a parameter set.
+ *   dG [sets, psf_learned_len(d, r, p)] fp32 (device): overwritten, in G's parameter order;
+ *   sets = heads when desc->sketch_per_head, else 1.  Everything else as for psf_causal_attn_bwd;
+ *   workspace: psf_bwd_workspace_bytes(desc) (it includes the staging of the parameter sums).
+ * The sums over rows run in a fixed order (no atomics).  General fp32 kernels
+ * (psf_bwd_kernel_path == 2).  PSF_ERR_UNSUPPORTED unless desc->learned (and p > 2);
+ * PSF_ERR_NULL without dG.
+ */
+psf_status psf_causal_attn_bwd_learned(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                       const void *G, const void *dO, void *dQ, void *dK, void *dV,
+                                       float *dG, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Forward + backward without running the forward pass twice (for callers that train).

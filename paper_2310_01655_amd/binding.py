@@ -23,6 +23,7 @@ EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_fwd_beside_states", "psf_wo
            "psf_status_string", "psf_noncausal_workspace_bytes", "psf_noncausal_attn_fwd",
            "psf_noncausal_attn_fwd_timed", "psf_fwd_save_bytes", "psf_causal_attn_fwd_save",
            "psf_causal_attn_bwd_saved", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
+           "psf_causal_attn_bwd_learned",
            "psf_causal_attn_bwd_timed", "psf_decode_state_bytes", "psf_decode_reset",
            "psf_decode_step", "psf_decode_prefill_workspace_bytes", "psf_decode_prefill", "psf_probe_mfma_loop")
 
@@ -93,6 +94,8 @@ def lib():
         L.psf_bwd_workspace_bytes.argtypes = [dp]
         L.psf_causal_attn_bwd.restype = ctypes.c_int
         L.psf_causal_attn_bwd.argtypes = [dp] + [vp] * 9 + [ctypes.c_size_t, vp]
+        L.psf_causal_attn_bwd_learned.restype = ctypes.c_int
+        L.psf_causal_attn_bwd_learned.argtypes = [dp] + [vp] * 10 + [ctypes.c_size_t, vp]
         L.psf_causal_attn_bwd_timed.restype = ctypes.c_int
         L.psf_causal_attn_bwd_timed.argtypes = [dp] + [vp] * 9 + [ctypes.c_size_t, vp,
                                                                   ctypes.POINTER(ctypes.c_float),
@@ -377,7 +380,9 @@ def _bwd_args(desc, Q, K, V, G, dO, workspace):
             ctypes.c_void_p(dQ.data_ptr()), ctypes.c_void_p(dK.data_ptr()),
             ctypes.c_void_p(dV.data_ptr()),
             ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel())]
-    return (dQ, dK, dV), ptrs
+    # the workspace is handed back so that the caller holds it until the call is enqueued: a
+    # tensor allocated in between must not be given the same memory
+    return (dQ, dK, dV), ptrs, workspace
 
 
 def psf_causal_attn_bwd(desc, Q, K, V, G, dO, workspace=None, stream=None):
@@ -385,11 +390,27 @@ def psf_causal_attn_bwd(desc, Q, K, V, G, dO, workspace=None, stream=None):
     st = check_desc(desc)
     if st != PSF_OK:
         raise PsfError(st, "psf_causal_attn_bwd")
-    grads, ptrs = _bwd_args(desc, Q, K, V, G, dO, workspace)
+    grads, ptrs, workspace = _bwd_args(desc, Q, K, V, G, dO, workspace)
     st = lib().psf_causal_attn_bwd(ctypes.byref(desc), *ptrs, _stream_ptr(stream))
     if st != PSF_OK:
         raise PsfError(st, "psf_causal_attn_bwd")
     return grads
+
+
+def psf_causal_attn_bwd_learned(desc, Q, K, V, G, dO, workspace=None, stream=None):
+    """Learned sketches: gradient with respect to Q, K, V and to the networks' parameters;
+    returns (dQ, dK, dV, dG) with dG fp32 of G's shape."""
+    st = check_desc(desc)
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_bwd_learned")
+    grads, ptrs, workspace = _bwd_args(desc, Q, K, V, G, dO, workspace)
+    gs = _g_shape(desc)
+    dG = torch.empty(gs if gs else (1,), dtype=torch.float32, device=Q.device)
+    ptrs = ptrs[:8] + [ctypes.c_void_p(dG.data_ptr())] + ptrs[8:]
+    st = lib().psf_causal_attn_bwd_learned(ctypes.byref(desc), *ptrs, _stream_ptr(stream))
+    if st != PSF_OK:
+        raise PsfError(st, "psf_causal_attn_bwd_learned")
+    return grads + (dG,)
 
 
 def psf_causal_attn_bwd_timed(desc, Q, K, V, G, dO, workspace=None, stream=None):
@@ -397,7 +418,7 @@ def psf_causal_attn_bwd_timed(desc, Q, K, V, G, dO, workspace=None, stream=None)
     st = check_desc(desc)
     if st != PSF_OK:
         raise PsfError(st, "psf_causal_attn_bwd_timed")
-    grads, ptrs = _bwd_args(desc, Q, K, V, G, dO, workspace)
+    grads, ptrs, workspace = _bwd_args(desc, Q, K, V, G, dO, workspace)
     ms = (ctypes.c_float * 16)()
     written = ctypes.c_int32(0)
     st = lib().psf_causal_attn_bwd_timed(ctypes.byref(desc), *ptrs, _stream_ptr(stream), ms, 16,

@@ -160,7 +160,7 @@ static bool bwd_on_mfma(const Problem &pb) { return select_path(pb) == 1 && mfma
 
 static psf_status run_bwd(const psf_desc *desc, const void *Q, const void *K, const void *V,
                           const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
-                          size_t ws_bytes, void *stream, StageTimer *tm)
+                          size_t ws_bytes, void *stream, StageTimer *tm, float *dG = nullptr)
 {
     Problem pb;
     psf_status st = make_problem(desc, &pb);
@@ -175,7 +175,8 @@ static psf_status run_bwd(const psf_desc *desc, const void *Q, const void *K, co
     if (((uintptr_t)ws & 255u) != 0) return PSF_ERR_WORKSPACE;
     if (mfma && !aligned16({Q, K, V, G, dO, dQ, dK, dV})) return PSF_ERR_ALIGNMENT;
     if (mfma) return mfma_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm);
-    return general_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm);
+    if (dG && !pb.learned) return PSF_ERR_UNSUPPORTED;
+    return general_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm, dG);
 }
 
 // ---- scratch of the entry point that allocates nothing ------------------------------------
@@ -409,6 +410,14 @@ psf_status psf_causal_attn_bwd(const psf_desc *desc, const void *Q, const void *
                                void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     return run_bwd(desc, Q, K, V, G, dO, dQ, dK, dV, workspace, workspace_bytes, hip_stream, nullptr);
+}
+
+psf_status psf_causal_attn_bwd_learned(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                       const void *G, const void *dO, void *dQ, void *dK, void *dV,
+                                       float *dG, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!dG) return PSF_ERR_NULL;
+    return run_bwd(desc, Q, K, V, G, dO, dQ, dK, dV, workspace, workspace_bytes, hip_stream, nullptr, dG);
 }
 
 psf_status psf_causal_attn_bwd_timed(const psf_desc *desc, const void *Q, const void *K,

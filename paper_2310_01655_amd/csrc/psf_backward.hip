@@ -14,7 +14,8 @@
 //   finally dQ += J^T dm(Q), dK += J^T dm(K) through Algorithm 1.
 // These are plain fp32 LDS-staged kernels for every descriptor with sketch features (any d, dv,
 // r <= 256, p in {2,4,8,16}, either in-block rule, fp32 or bf16 storage).  The sketch matrices
-// are constants.
+// are constants.  With learned sketches (Algorithm 2) the last step goes through the networks
+// instead and can also return the gradient with respect to their parameters.
 #include "psf_internal.h"
 
 namespace psf {
@@ -635,8 +636,430 @@ __global__ __launch_bounds__(kThreads) void bwd_sketch_kernel(
     }
 }
 
+// ---- gradient through Algorithm 2 (learned sketches, Appendix D) ---------------------------
+// One network is LN -> W1 (win x 8r) -> gelu -> LN -> W2 (8r x r) -> W3 (r x 8r) -> gelu -> W4 (8r x r)
+// (the reading stated in include/psf.h); a node returns sqrt(r) tanh(f1(M1) * f2(M2) / sqrt(r)).
+// A workgroup takes one row: it runs the networks forward (twice: once for the values every node
+// needs, once more per network for the quantities its reverse pass reads), walks back from the
+// root, and leaves, per network, the input and the output gradient of every dense layer (and
+// the two products a layer normalisation's scale and bias need) in a staging buffer; the
+// parameter gradients are then sums over rows of outer products of those, formed by
+// bwd_param_gemm / bwd_param_colsum in a fixed order (chunk by chunk, rows in order: no atomics).
+constexpr int kMaxHidden = 8 * PSF_MAX_DIM;
+
+__device__ __forceinline__ float gelu_tanh_f(float x)
+{
+    return 0.5f * x * (1.0f + tanhf(0.7978845608028654f * (x + 0.044715f * x * x * x)));
+}
+
+__device__ __forceinline__ float gelu_tanh_grad_f(float x)
+{
+    const float c = 0.7978845608028654f, k = 0.044715f;
+    const float th = tanhf(c * (x + k * x * x * x));
+    return 0.5f * (1.0f + th) + 0.5f * x * (1.0f - th * th) * c * (1.0f + 3.0f * k * x * x);
+}
+
+// sum of v over the workgroup, the same value in every thread; red: 4 floats of LDS
+__device__ __forceinline__ float wg_sum(float v, float *red)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
+// Staging of one network for a chunk of RC rows: offsets (in floats) of its arrays, each [RC][width].
+struct NetStage {
+    size_t A1, LG1, LB1;                 // width win: layer-norm-1 output; d(out) * xhat; d(out)
+    size_t D1, A2, LG2, LB2, D3, A4;     // width 8r: d(pre-gelu 1); LN-2 output; its two products; d(pre-gelu 3); gelu 3
+    size_t D2, A3, D4;                   // width r: d(W2 output); W2 output; d(network output)
+    size_t end;
+};
+
+__host__ __device__ inline NetStage net_stage(size_t base, size_t RC, int win, int r)
+{
+    const size_t hid = 8 * (size_t)r;
+    NetStage L;
+    size_t o = base;
+    L.A1 = o; o += RC * win;
+    L.LG1 = o; o += RC * win;
+    L.LB1 = o; o += RC * win;
+    L.D1 = o; o += RC * hid;
+    L.A2 = o; o += RC * hid;
+    L.LG2 = o; o += RC * hid;
+    L.LB2 = o; o += RC * hid;
+    L.D3 = o; o += RC * hid;
+    L.A4 = o; o += RC * hid;
+    L.D2 = o; o += RC * r;
+    L.A3 = o; o += RC * r;
+    L.D4 = o; o += RC * r;
+    L.end = o;
+    return L;
+}
+
+__host__ __device__ inline size_t learned_net_len(int win, int r)
+{
+    const size_t hid = 8 * (size_t)r;
+    return 2 * (size_t)win + (size_t)win * hid + 2 * hid + hid * r + (size_t)r * hid + hid * r;
+}
+
+// input width of network k (Appendix D order: the p/2 networks on x, then the ones on sketches)
+__host__ __device__ inline int learned_net_win(int k, int d, int r, int p) { return k < p / 2 ? d : r; }
+
+struct LearnedLds {
+    float a1[kMaxHidden], xh2[kMaxHidden], a3[kMaxHidden], s1[kMaxHidden];
+    float xh1[PSF_MAX_DIM], u[PSF_MAX_DIM], u2[PSF_MAX_DIM], du2[PSF_MAX_DIM], tw[PSF_MAX_DIM];
+    float red[4];
+};
+
+// out[c] = sum_e x[e] W[e * cols + c]; x, out in LDS
+template <typename T>
+__device__ void wgl_dense(const float *x, int rows, const T *W, int cols, float *out)
+{
+    for (int c = threadIdx.x; c < cols; c += kThreads) {
+        float a = 0.f;
+        for (int e = 0; e < rows; ++e) a += x[e] * load_f(W, (size_t)e * cols + c);
+        out[c] = a;
+    }
+    __syncthreads();
+}
+
+// out[e] = sum_c x[c] W[e * cols + c] (the product with the transposed matrix): one wave per row e
+template <typename T>
+__device__ void wgl_dense_t(const float *x, const T *W, int rows, int cols, float *out)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int e = wave; e < rows; e += kThreads / 64) {
+        float a = 0.f;
+        for (int c = lane; c < cols; c += 64) a += x[c] * load_f(W, (size_t)e * cols + c);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+        if (lane == 0) out[e] = a;
+    }
+    __syncthreads();
+}
+
+// xhat = (x - mean) / sqrt(var + eps) into xh, xhat * g + b into out (LDS, may alias x); returns 1 / sigma
+template <typename T>
+__device__ float wgl_layer_norm(const float *x, int m, const T *g, const T *b, float *xh, float *out, float *red)
+{
+    float a = 0.f;
+    for (int e = threadIdx.x; e < m; e += kThreads) a += x[e];
+    const float mean = wg_sum(a, red) / (float)m;
+    a = 0.f;
+    for (int e = threadIdx.x; e < m; e += kThreads) a += (x[e] - mean) * (x[e] - mean);
+    const float inv = rsqrtf(wg_sum(a, red) / (float)m + 1e-6f);
+    for (int e = threadIdx.x; e < m; e += kThreads) {
+        const float xv = (x[e] - mean) * inv;
+        xh[e] = xv;
+        out[e] = xv * load_f(g, e) + load_f(b, e);
+    }
+    __syncthreads();
+    return inv;
+}
+
+// dy (LDS, m entries: the gradient of the normalisation's output) -> gradient of its input, in
+// place; lg / lb (staging rows, or null) receive dy * xhat and dy
+template <typename T>
+__device__ void wgl_layer_norm_bwd(float *dy, const float *xh, int m, const T *g, float inv, float *lg, float *lb,
+                                   float *red)
+{
+    float a = 0.f, c = 0.f;
+    for (int e = threadIdx.x; e < m; e += kThreads) {
+        const float v = dy[e];
+        if (lg) { lg[e] = v * xh[e]; lb[e] = v; }
+        const float dx = v * load_f(g, e);
+        dy[e] = dx;
+        a += dx;
+        c += dx * xh[e];
+    }
+    const float m1 = wg_sum(a, red) / (float)m, m2 = wg_sum(c, red) / (float)m;
+    for (int e = threadIdx.x; e < m; e += kThreads) dy[e] = inv * (dy[e] - m1 - xh[e] * m2);
+    __syncthreads();
+}
+
+template <typename T>
+struct NetParams {
+    const T *g1, *b1, *W1, *g2, *b2, *W2, *W3, *W4;
+    __device__ NetParams(const T *P, int win, int r)
+    {
+        const size_t hid = 8 * (size_t)r;
+        g1 = P; b1 = g1 + win; W1 = b1 + win;
+        g2 = W1 + (size_t)win * hid; b2 = g2 + hid; W2 = b2 + hid;
+        W3 = W2 + hid * r; W4 = W3 + (size_t)r * hid;
+    }
+};
+
+// out = f(inp) for one network; with KEEP the quantities the reverse pass reads stay in L
+// (a1, xh1, xh2, a3, u2; inv[0], inv[1]) and, where st is given, its layer inputs go to staging.
+template <typename T, bool KEEP>
+__device__ void wgl_net_fwd(const float *inp, int win, int r, const T *P, float *out, LearnedLds &L, float *inv,
+                            float *st, const NetStage &ns, size_t li)
+{
+    const int hid = 8 * r, tid = threadIdx.x;
+    const NetParams<T> np(P, win, r);
+    const float i1 = wgl_layer_norm(inp, win, np.g1, np.b1, L.xh1, L.u, L.red);
+    wgl_dense(L.u, win, np.W1, hid, L.a1);
+    for (int c = tid; c < hid; c += kThreads) L.s1[c] = gelu_tanh_f(L.a1[c]);
+    __syncthreads();
+    const float i2 = wgl_layer_norm(L.s1, hid, np.g2, np.b2, L.xh2, L.s1, L.red);      // s1 = LN-2 output
+    wgl_dense(L.s1, hid, np.W2, r, L.u2);
+    if (KEEP && st) {
+        for (int e = tid; e < win; e += kThreads) st[ns.A1 + li * win + e] = L.u[e];
+        for (int c = tid; c < hid; c += kThreads) st[ns.A2 + li * hid + c] = L.s1[c];
+        for (int e = tid; e < r; e += kThreads) st[ns.A3 + li * r + e] = L.u2[e];
+    }
+    wgl_dense(L.u2, r, np.W3, hid, L.a3);
+    for (int c = tid; c < hid; c += kThreads) {
+        const float hv = gelu_tanh_f(L.a3[c]);
+        L.s1[c] = hv;
+        if (KEEP && st) st[ns.A4 + li * hid + c] = hv;
+    }
+    __syncthreads();
+    if (!KEEP) wgl_dense(L.s1, hid, np.W4, r, out);
+    if (KEEP) { inv[0] = i1; inv[1] = i2; }
+}
+
+// Reverse pass of one network for the row whose forward quantities wgl_net_fwd<KEEP> left in L:
+// df (LDS, r) = gradient of its output; dinp (LDS, win) += gradient of its input.
+template <typename T>
+__device__ void wgl_net_bwd(const float *df, int win, int r, const T *P, float *dinp, LearnedLds &L,
+                            const float *inv, float *st, const NetStage &ns, size_t li)
+{
+    const int hid = 8 * r, tid = threadIdx.x;
+    const NetParams<T> np(P, win, r);
+    if (st)
+        for (int e = tid; e < r; e += kThreads) st[ns.D4 + li * r + e] = df[e];
+    wgl_dense_t(df, np.W4, hid, r, L.s1);                          // d(gelu 3 output)
+    for (int c = tid; c < hid; c += kThreads) {
+        const float v = L.s1[c] * gelu_tanh_grad_f(L.a3[c]);
+        L.s1[c] = v;
+        if (st) st[ns.D3 + li * hid + c] = v;
+    }
+    __syncthreads();
+    wgl_dense_t(L.s1, np.W3, r, hid, L.du2);
+    if (st)
+        for (int e = tid; e < r; e += kThreads) st[ns.D2 + li * r + e] = L.du2[e];
+    wgl_dense_t(L.du2, np.W2, hid, r, L.s1);                       // d(LN-2 output)
+    wgl_layer_norm_bwd(L.s1, L.xh2, hid, np.g2, inv[1], st ? st + ns.LG2 + li * hid : nullptr,
+                       st ? st + ns.LB2 + li * hid : nullptr, L.red);
+    for (int c = tid; c < hid; c += kThreads) {
+        const float v = L.s1[c] * gelu_tanh_grad_f(L.a1[c]);
+        L.s1[c] = v;
+        if (st) st[ns.D1 + li * hid + c] = v;
+    }
+    __syncthreads();
+    wgl_dense_t(L.s1, np.W1, win, hid, L.tw);                      // d(LN-1 output)
+    wgl_layer_norm_bwd(L.tw, L.xh1, win, np.g1, inv[0], st ? st + ns.LG1 + li * win : nullptr,
+                       st ? st + ns.LB1 + li * win : nullptr, L.red);
+    for (int e = tid; e < win; e += kThreads) dinp[e] += L.tw[e];
+    __syncthreads();
+}
+
+// Rows row0 .. row0 + gridDim.x - 1 (one per workgroup, all of one parameter set P0): dX = direct
+// + (d m / d x)^T dM; stage (or null): the chunk's staging, RC rows per array.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void bwd_sketch_learned_kernel(
+    const T *__restrict__ X, const T *__restrict__ P0, const float *__restrict__ dM,
+    const float *__restrict__ direct, T *__restrict__ dX, long long row0, int RC, int d, int r, int p,
+    float *__restrict__ stage)
+{
+    __shared__ LearnedLds L;
+    __shared__ float xs[PSF_MAX_DIM], dxs[PSF_MAX_DIM], df[PSF_MAX_DIM];
+    __shared__ float f[6][PSF_MAX_DIM], mn[2][PSF_MAX_DIM], tn[2][PSF_MAX_DIM], dmn[2][PSF_MAX_DIM];
+    const int tid = threadIdx.x;
+    const size_t li = blockIdx.x, row = (size_t)row0 + li;
+    const float sr = sqrtf((float)r);
+    if (tid < d) { xs[tid] = load_f(X, row * d + tid); dxs[tid] = direct[row * d + tid]; }
+    if (tid < r) { dmn[0][tid] = 0.f; dmn[1][tid] = 0.f; }
+    __syncthreads();
+    float inv[2];
+    // staging layout and parameter offset of network k
+    auto locate = [&](int k, NetStage &ns, size_t &p_at) {
+        size_t base = 0;
+        p_at = 0;
+        for (int j = 0;; ++j) {
+            const int win = learned_net_win(j, d, r, p);
+            ns = net_stage(base, (size_t)RC, win, r);
+            if (j == k) return;
+            base = ns.end;
+            p_at += learned_net_len(win, r);
+        }
+    };
+    auto value = [&](int k, const float *inp, int win) {
+        NetStage ns;
+        size_t p_at;
+        locate(k, ns, p_at);
+        wgl_net_fwd<T, false>(inp, win, r, P0 + p_at, f[k], L, inv, nullptr, ns, li);
+    };
+    // values of every network and node
+    for (int k = 0; k < p / 2; ++k) value(k, xs, d);
+    if (p == 8) {
+        if (tid < r) {
+            for (int j = 0; j < 2; ++j) {
+                const float th = tanhf(f[2 * j][tid] * f[2 * j + 1][tid] / sr);
+                tn[j][tid] = th;
+                mn[j][tid] = sr * th;
+            }
+        }
+        __syncthreads();
+        value(4, mn[0], r);
+        value(5, mn[1], r);
+    }
+    // the root, then down
+    const int ra = p == 8 ? 4 : 0, rb = ra + 1;
+    float dz = 0.f;
+    if (tid < r) {
+        const float th = tanhf(f[ra][tid] * f[rb][tid] / sr);
+        dz = dM[row * r + tid] * (1.0f - th * th);
+    }
+    auto through = [&](int k, const float *inp, int win, float factor_of, float *dinp) {
+        // df = dz * (value of the sibling network)
+        if (tid < r) df[tid] = dz * factor_of;
+        __syncthreads();
+        NetStage ns;
+        size_t p_at;
+        locate(k, ns, p_at);
+        wgl_net_fwd<T, true>(inp, win, r, P0 + p_at, nullptr, L, inv, stage, ns, li);
+        wgl_net_bwd<T>(df, win, r, P0 + p_at, dinp, L, inv, stage, ns, li);
+    };
+    if (p == 8) {
+        through(4, mn[0], r, tid < r ? f[5][tid] : 0.f, dmn[0]);
+        through(5, mn[1], r, tid < r ? f[4][tid] : 0.f, dmn[1]);
+        for (int j = 0; j < 2; ++j) {
+            if (tid < r) dz = dmn[j][tid] * (1.0f - tn[j][tid] * tn[j][tid]);
+            through(2 * j, xs, d, tid < r ? f[2 * j + 1][tid] : 0.f, dxs);
+            through(2 * j + 1, xs, d, tid < r ? f[2 * j][tid] : 0.f, dxs);
+        }
+    } else {
+        through(0, xs, d, tid < r ? f[1][tid] : 0.f, dxs);
+        through(1, xs, d, tid < r ? f[0][tid] : 0.f, dxs);
+    }
+    if (tid < d) store_f(dX, row * d + tid, dxs[tid]);
+}
+
+// dW[m][c] += sum over the chunk's rows of A[row][m] * D[row][c]  (A: [nrows][mw], D: [nrows][cw])
+__global__ __launch_bounds__(kThreads) void bwd_param_gemm(const float *__restrict__ A, int mw,
+                                                           const float *__restrict__ D, int cw, int nrows,
+                                                           float *__restrict__ dW)
+{
+    __shared__ float As[32][16], Ds[32][64];
+    const int tid = threadIdx.x, tc = tid & 63, tg = tid >> 6;
+    const int c0 = blockIdx.x * 64, m0 = blockIdx.y * 16;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int r0 = 0; r0 < nrows; r0 += 32) {
+        __syncthreads();
+        for (int idx = tid; idx < 32 * 16; idx += kThreads) {
+            const int rr = idx / 16, mm = idx % 16;
+            As[rr][mm] = (r0 + rr < nrows && m0 + mm < mw) ? A[(size_t)(r0 + rr) * mw + m0 + mm] : 0.f;
+        }
+        for (int idx = tid; idx < 32 * 64; idx += kThreads) {
+            const int rr = idx / 64, cc = idx % 64;
+            Ds[rr][cc] = (r0 + rr < nrows && c0 + cc < cw) ? D[(size_t)(r0 + rr) * cw + c0 + cc] : 0.f;
+        }
+        __syncthreads();
+        for (int rr = 0; rr < 32; ++rr) {
+            const float dv = Ds[rr][tc];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] += As[rr][tg * 4 + j] * dv;
+        }
+    }
+    if (c0 + tc < cw)
+        for (int j = 0; j < 4; ++j)
+            if (m0 + tg * 4 + j < mw) dW[(size_t)(m0 + tg * 4 + j) * cw + c0 + tc] += acc[j];
+}
+
+// out[c] += sum over the chunk's rows of X[row][c]
+__global__ __launch_bounds__(kThreads) void bwd_param_colsum(const float *__restrict__ X, int w, int nrows,
+                                                             float *__restrict__ out)
+{
+    const int c = blockIdx.x * kThreads + threadIdx.x;
+    if (c >= w) return;
+    float a = 0.f;
+    for (int rr = 0; rr < nrows; ++rr) a += X[(size_t)rr * w + c];
+    out[c] += a;
+}
+
+__global__ __launch_bounds__(kThreads) void bwd_fill_kernel(float *__restrict__ p, size_t count)
+{
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < count) p[i] = 0.f;
+}
+
+// staging floats per row over all networks of one set
+size_t learned_stage_floats_per_row(const Problem &pb)
+{
+    size_t at = 0;
+    for (int k = 0; k < pb.p - 2; ++k) at = net_stage(at, 1, learned_net_win(k, pb.d, pb.r, pb.p), pb.r).end;
+    return at;
+}
+
+// rows per chunk: at most 128 MB of staging, at most 4096 rows, at least 64
+int learned_chunk_rows(const Problem &pb)
+{
+    const size_t per_row = learned_stage_floats_per_row(pb) * 4;
+    size_t rc = ((size_t)128 << 20) / (per_row ? per_row : 1);
+    if (rc > 4096) rc = 4096;
+    if (rc < 64) rc = 64;
+    const size_t seg = pb.per_head ? (size_t)pb.n : (size_t)pb.units * pb.n;
+    return (int)(rc < seg ? rc : seg);
+}
+
+// dX = direct + J^T dM through Algorithm 2 for every row of X; dG (or null) += the parameter gradient
+template <typename T>
+psf_status learned_sketch_bwd(const Problem &pb, const void *X, const void *G, const float *dM,
+                              const float *direct, void *dX, float *dG, float *stage, hipStream_t s)
+{
+    const int RC = learned_chunk_rows(pb), nets = pb.p - 2, r = pb.r, hid = 8 * pb.r;
+    const size_t rows = (size_t)pb.units * pb.n;
+    const size_t seg_rows = pb.per_head ? (size_t)pb.n : rows;
+    for (size_t seg0 = 0; seg0 < rows; seg0 += seg_rows) {
+        const size_t set = pb.per_head ? (seg0 / pb.n) % pb.heads : 0;
+        const T *P0 = (const T *)G + set * pb.g_len;
+        for (size_t c0 = 0; c0 < seg_rows; c0 += RC) {
+            const int nrows = (int)(seg_rows - c0 < (size_t)RC ? seg_rows - c0 : (size_t)RC);
+            hipLaunchKernelGGL(bwd_sketch_learned_kernel<T>, dim3(nrows), dim3(kThreads), 0, s, (const T *)X, P0, dM,
+                               direct, (T *)dX, (long long)(seg0 + c0), RC, pb.d, r, pb.p, dG ? stage : nullptr);
+            PSF_LAUNCH_CHECK();
+            if (!dG) continue;
+            size_t base = 0, p_at = 0;
+            for (int k = 0; k < nets; ++k) {
+                const int win = learned_net_win(k, pb.d, r, pb.p);
+                const NetStage ns = net_stage(base, (size_t)RC, win, r);
+                base = ns.end;
+                float *g = dG + set * pb.g_len + p_at;
+                float *g1 = g, *b1 = g1 + win, *W1 = b1 + win;
+                float *g2 = W1 + (size_t)win * hid, *b2 = g2 + hid, *W2 = b2 + hid;
+                float *W3 = W2 + (size_t)hid * r, *W4 = W3 + (size_t)r * hid;
+                p_at += learned_net_len(win, r);
+                auto gemm = [&](size_t a_off, int mw, size_t d_off, int cw, float *dW) {
+                    hipLaunchKernelGGL(bwd_param_gemm, dim3((cw + 63) / 64, (mw + 15) / 16), dim3(kThreads), 0, s,
+                                       stage + a_off, mw, stage + d_off, cw, nrows, dW);
+                };
+                auto colsum = [&](size_t x_off, int w, float *out) {
+                    hipLaunchKernelGGL(bwd_param_colsum, dim3((w + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
+                                       stage + x_off, w, nrows, out);
+                };
+                colsum(ns.LG1, win, g1);
+                colsum(ns.LB1, win, b1);
+                gemm(ns.A1, win, ns.D1, hid, W1);
+                colsum(ns.LG2, hid, g2);
+                colsum(ns.LB2, hid, b2);
+                gemm(ns.A2, hid, ns.D2, r, W2);
+                gemm(ns.A3, r, ns.D3, hid, W3);
+                gemm(ns.A4, hid, ns.D4, r, W4);
+                PSF_LAUNCH_CHECK();
+            }
+        }
+    }
+    return PSF_OK;
+}
+
 struct BwdWs {
     float *MQ, *MK, *CV, *GC, *Z, *RB, *dMQ, *dMK, *dQd, *dKd;
+    float *LS;                                   // learned sketches: staging of one chunk of rows
     size_t total;
 };
 
@@ -657,13 +1080,14 @@ BwdWs carve_bwd(const Problem &pb, void *ws)
     w.dMK = take(rows * pb.mcols);
     w.dQd = take(rows * pb.d);
     w.dKd = take(rows * pb.d);
+    w.LS = take(pb.learned ? (size_t)learned_chunk_rows(pb) * learned_stage_floats_per_row(pb) : 0);
     w.total = off;
     return w;
 }
 
 template <typename T>
 psf_status bwd_launch(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
-                      const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s,
+                      const void *dO, void *dQ, void *dK, void *dV, float *dG, void *ws, hipStream_t s,
                       StageTimer *tm)
 {
     BwdWs w = carve_bwd(pb, ws);
@@ -731,6 +1155,20 @@ psf_status bwd_launch(const Problem &pb, const void *Q, const void *K, const voi
     PSF_LAUNCH_CHECK();
     if (tm) tm->mark();                                   // stage: key side
 
+    if (pb.learned) {
+        if (dG) {
+            const size_t count = (size_t)(pb.per_head ? pb.heads : 1) * pb.g_len;
+            hipLaunchKernelGGL(bwd_fill_kernel, dim3((unsigned)((count + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                               s, dG, count);
+            PSF_LAUNCH_CHECK();
+        }
+        st = learned_sketch_bwd<T>(pb, Q, G, w.dMQ, w.dQd, dQ, dG, w.LS, s);
+        if (st != PSF_OK) return st;
+        st = learned_sketch_bwd<T>(pb, K, G, w.dMK, w.dKd, dK, dG, w.LS, s);
+        if (st != PSF_OK) return st;
+        if (tm) tm->mark();                               // stage: sketch gradient
+        return PSF_OK;
+    }
     const int grid = (int)(rows < 65536 ? rows : 65536);
     hipLaunchKernelGGL(bwd_sketch_kernel<T>, dim3(grid), dim3(kThreads), 0, s, (const T *)Q, (const T *)G,
                        w.dMQ, w.dQd, (T *)dQ, (long long)rows, pb.n, pb.heads, pb.per_head ? 1 : 0, pb.d,
@@ -748,19 +1186,19 @@ psf_status bwd_launch(const Problem &pb, const void *Q, const void *K, const voi
 
 bool general_bwd_supported(const Problem &pb)
 {
-    // explicit x^{(x)p} features and learned sketches have no backward here; the feature staging assumes F and a
+    // explicit x^{(x)p} features have no backward here; the feature staging assumes F and a
     // block fit the chunked LDS loops (any size) and the 32-bit feature index of one pass
-    return !pb.exact_feat && !pb.learned && pb.F <= PSF_MAX_FEATURES;
+    return !pb.exact_feat && pb.F <= PSF_MAX_FEATURES;
 }
 
 size_t general_bwd_workspace_bytes(const Problem &pb) { return carve_bwd(pb, nullptr).total; }
 
 psf_status general_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V,
                             const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
-                            hipStream_t s, StageTimer *tm)
+                            hipStream_t s, StageTimer *tm, float *dG)
 {
-    return pb.bf16 ? bwd_launch<bf16_t>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm)
-                   : bwd_launch<float>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm);
+    return pb.bf16 ? bwd_launch<bf16_t>(pb, Q, K, V, G, dO, dQ, dK, dV, dG, ws, s, tm)
+                   : bwd_launch<float>(pb, Q, K, V, G, dO, dQ, dK, dV, dG, ws, s, tm);
 }
 
 }  // namespace psf

@@ -53,12 +53,13 @@ psf_status general_sketch_f32(const Problem &pb, const void *X, const void *G, f
 psf_status general_sketch_pair_f32(const Problem &pb, const void *X, const void *X2, const void *G,
                                    float *M_f32, float *M2_f32, hipStream_t s);
 
-// Backward pass (general fp32 kernels; sketch features only).
+// Backward pass (general fp32 kernels; sketch features only).  dG: with learned sketches,
+// the gradient with respect to the networks' parameters (fp32 [sets][g_len], overwritten), or null.
 bool general_bwd_supported(const Problem &pb);
 size_t general_bwd_workspace_bytes(const Problem &pb);
 psf_status general_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V,
                             const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
-                            hipStream_t s, StageTimer *tm);
+                            hipStream_t s, StageTimer *tm, float *dG = nullptr);
 
 // Backward pass on MFMA (bf16, d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0, random sketches).
 bool mfma_bwd_supported(const Problem &pb);

@@ -132,8 +132,6 @@ def test_decode_with_learned_sketches():
     assert_close(out.cpu().numpy(), oracle_rows(q, k, v, P, p, r, b), "f32", "decode learned")
 
 
-def test_learned_backward_and_degree_16_are_refused():
-    desc = psf.make_desc(1, 1, 64, 16, 4, 8, 16, "f32", learned=True)
-    assert psf.bwd_workspace_bytes(desc) == 0
+def test_degree_16_and_exact_features_are_refused():
     assert psf.check_desc(psf.make_desc(1, 1, 64, 16, 16, 8, 16, "f32", learned=True)) == 3
     assert psf.check_desc(psf.make_desc(1, 1, 64, 4, 4, 8, 16, "f32", learned=True, feat=psf.FEAT_EXACT)) == 3

@@ -1,0 +1,113 @@
+"""GPU parity of the backward pass through learned sketches (Algorithm 2, Appendix D) against the
+float64 gradient oracle, through the C ABI: gradients with respect to Q, K, V and to the
+networks' parameters (psf_causal_attn_bwd_learned), and the row gradients alone
+(psf_causal_attn_bwd with desc.learned).  The oracle takes the storage-rounded inputs and
+parameters upcast to float64 and works one unit at a time; the parameter gradient of a set is the
+sum over the units that share it.  Tolerances as for the other gradients: relative Frobenius
+error and max-abs error relative to the largest entry, 1e-4 (fp32 storage) / 2e-2 (bf16)."""
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2310_01655_amd import binding as psf
+from paper_2310_01655_amd import inputs
+from parity import as_f64, assert_close_scaled
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_grads(q, k, v, P, dO, p, r, b, local):
+    B, H = q.shape[:2]
+    units = [(bi, h) for bi in range(B) for h in range(H)]
+
+    def one(u):
+        bi, h = u
+        return oracle.attn_bwd_learned(as_f64(q[bi, h]), as_f64(k[bi, h]), as_f64(v[bi, h]),
+                                       as_f64(P[h if P.shape[0] > 1 else 0]), as_f64(dO[bi, h]), p, r, b, local=local)
+
+    with ThreadPoolExecutor(min(len(units), 8)) as ex:
+        parts = list(ex.map(one, units))
+    wQ, wK, wV = (np.empty(tuple(t.shape)) for t in (q, k, v))
+    wP = np.zeros(tuple(P.shape))
+    for (bi, h), (dq, dk, dv, dp) in zip(units, parts):
+        wQ[bi, h], wK[bi, h], wV[bi, h] = dq, dk, dv
+        wP[h if P.shape[0] > 1 else 0] += dp
+    return wQ, wK, wV, wP
+
+
+def run_case(batch, heads, n, d, dv, p, r, b, dtype, local=psf.LOCAL_EXACT, per_head=True, seed=71):
+    q, k, v = inputs.make_qkv(batch, heads, n, d, dv=dv, seed=seed, dtype=dtype)
+    dO = inputs.make_dout(batch, heads, n, dv, seed=seed, dtype=dtype)
+    P = inputs.make_learned_params(heads, d, r, p, per_head=per_head, seed=3, dtype=dtype)
+    desc = psf.make_desc(batch, heads, n, d, p, r, b, dtype, dv=dv, local=local, per_head=per_head, learned=True)
+    assert psf.bwd_kernel_path(desc) == 2
+    dev = torch.device("cuda:0")
+    args = [x.to(dev) for x in (q, k, v, P, dO)]
+    dQ, dK, dV, dG = psf.psf_causal_attn_bwd_learned(desc, *args)
+    torch.cuda.synchronize()
+    assert dG.dtype == torch.float32 and tuple(dG.shape) == tuple(P.shape)
+    wQ, wK, wV, wP = oracle_grads(q, k, v, P, dO, p, r, b,
+                                  oracle.LOCAL_EXACT if local == psf.LOCAL_EXACT else oracle.LOCAL_SKETCH)
+    what = "n=%d d=%d p=%d r=%d b=%d %s" % (n, d, p, r, b, dtype)
+    res = {}
+    for name, got, want in (("dQ", dQ, wQ), ("dK", dK, wK), ("dV", dV, wV)):
+        res[name] = assert_close_scaled(got.float().cpu().numpy(), want, dtype, name + " " + what)
+    # the parameter gradient is accumulated and returned in fp32 whatever the storage type: what
+    # separates it from the oracle is the fp32 arithmetic of the row kernels
+    for s in range(P.shape[0]):
+        res["dG%d" % s] = assert_close_scaled(dG[s].cpu().numpy(), wP[s], "f32", "dG set %d %s" % (s, what))
+    print(what, {k2: ("%.2e" % v2[0], "%.2e" % v2[1]) for k2, v2 in res.items()})
+    return desc, args, (dQ, dK, dV, dG)
+
+
+@pytest.mark.parametrize("n,d,dv,p,r,b,per_head", [
+    (96, 24, 16, 4, 8, 32, True),      # three blocks, dv != d, a set per head
+    (96, 24, 24, 4, 8, 32, False),     # one shared set: its gradient sums over all units
+    (64, 16, 16, 8, 8, 16, True),      # degree 8: six networks, two of them on sketches
+    (64, 20, 12, 4, 12, 64, True),     # single block, sizes that are no powers of two
+])
+def test_learned_backward_fp32(n, d, dv, p, r, b, per_head):
+    run_case(2, 2, n, d, dv, p, r, b, "f32", per_head=per_head)
+
+
+@pytest.mark.parametrize("p", [4, 8])
+def test_learned_backward_in_block_weights_from_the_sketches(p):
+    run_case(1, 2, 64, 16, 16, p, 8, 16, "f32", local=psf.LOCAL_SKETCH)
+
+
+def test_learned_backward_bf16_storage():
+    run_case(1, 2, 128, 32, 32, 4, 16, 32, "bf16")
+
+
+def test_learned_backward_widest_networks():
+    # d = r = 256: 2048 hidden units, the largest the row kernel's workgroup memory is sized for
+    run_case(1, 1, 32, 256, 64, 4, 256, 16, "f32")
+
+
+def test_learned_backward_several_chunks_of_rows():
+    # 6144 rows share one parameter set: the staging holds 4096 rows, so the sums over rows run
+    # in two chunks that do not end on unit boundaries
+    run_case(2, 3, 1024, 16, 16, 4, 8, 256, "f32", per_head=False)
+
+
+def test_rows_only_call_gives_the_same_row_gradients_and_repeats_bit_for_bit():
+    desc, args, (dQ, dK, dV, dG) = run_case(1, 2, 64, 16, 16, 4, 8, 16, "f32")
+    rQ, rK, rV = psf.psf_causal_attn_bwd(desc, *args)
+    again = psf.psf_causal_attn_bwd_learned(desc, *args)
+    torch.cuda.synchronize()
+    for a, c in ((rQ, dQ), (rK, dK), (rV, dV)):
+        assert torch.equal(a, c)
+    for a, c in zip(again, (dQ, dK, dV, dG)):
+        assert torch.equal(a, c)               # fixed summation order: no atomics
+
+
+def test_parameter_gradient_is_refused_for_gaussian_sketches():
+    desc = psf.make_desc(1, 1, 64, 16, 4, 8, 16, "f32")
+    q, k, v = inputs.make_qkv(1, 1, 64, 16, seed=1, dtype="f32")
+    dO = inputs.make_dout(1, 1, 64, 16, seed=1, dtype="f32")
+    G = inputs.make_sketch_matrices(1, 16, 8, 4, per_head=False, seed=0, dtype="f32")
+    with pytest.raises(psf.PsfError):
+        psf.psf_causal_attn_bwd_learned(desc, *[x.cuda() for x in (q, k, v, G, dO)])
