@@ -1307,11 +1307,12 @@ __global__ __launch_bounds__(2 * kWg, 1) void k_state_two_waves(const float *__r
 // PART splits the work of a token tile over two launches: 0 = everything (one launch);
 // 1 = the in-block part only, its unnormalised rows and weight sums left in Pnum / Pden (it
 // needs neither the sketches nor the states, so it can run beside the state kernel);
-// 2 = the cross-block part, started from what PART 1 left, then the division.
+// 2 = the cross-block part, to which what PART 1 left is added at the end (so that its load is
+// not in the way of the first chunk of the state), then the division.
 // Pnum / Pden layout (private to these two parts, which share this code): per 32-token tile of
 // a wave the accumulator registers as they are, [tile][value-column tile][register quad][lane]
-// x 16 bytes, and the partial weight sums of the 64 lanes (two per token), so that the second
-// launch continues exactly where one launch would be: the results are the same bit for bit.
+// x 16 bytes, and the partial weight sums of the 64 lanes (two per token).  The two launches add
+// the same terms as one launch in another order: equal within fp32 rounding, not bit for bit.
 constexpr int kKeyTilesInFlight = 4;
 template <int R, int D, int TT, bool LS, int PART>
 constexpr int out_lds_bytes()
@@ -1373,19 +1374,11 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
     // rows of the workgroup's 32-token tiles in Pnum / Pden
     const size_t ptile0 = (urow + tok_w0) / 32;
     if constexpr (PART == 2) {
-        // start from the in-block part (the loads land while the denominators and the first
-        // chunk of the state are on their way)
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
             den[tt] = Pden[(ptile0 + tt) * 64 + lane];
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
-#pragma unroll
-                for (int gq = 0; gq < 4; ++gq) {
-                    const f32x4 q4 = *(const f32x4 *)&Pnum[(((ptile0 + tt) * CT + ct) * 4 + gq) * 256 + lane * 4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) out[tt][ct][4 * gq + j] = q4[j];
-                }
+            for (int ct = 0; ct < CT; ++ct) out[tt][ct] = f32x16{0};
         }
     } else {
 #pragma unroll
@@ -1602,36 +1595,6 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
             for (int s = 0; s < RS; ++s)
                 mfr[tt][s] = *(const bf16x8 *)&MQ[(urow + tok_w0 + 32 * tt + x) * R + 16 * s + 8 * h];
 
-        // denominator: m_i^T S m_i with S = prefix of m_j m_j^T, hi + lo operands
-        {
-            const size_t sbase = ((size_t)u * (t - 1) + (NONCAUSAL ? 0 : l - 1)) * R * R;
-#pragma unroll
-            for (int at = 0; at < AT; ++at) {
-                f32x16 td[TT];
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt) td[tt] = f32x16{0};
-#pragma unroll
-                for (int s = 0; s < RS; ++s) {
-                    const size_t off = sbase + ((size_t)(2 * s + h) * R + 32 * at + x) * 8;
-                    const bf16x8 s_hi = *(const bf16x8 *)&Shi[off], s_lo = *(const bf16x8 *)&Slo[off];
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) {
-                        td[tt] = mfma32(s_hi, mfr[tt][s], td[tt]);
-                        td[tt] = mfma32(s_lo, mfr[tt][s], td[tt]);
-                    }
-                }
-#pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-#pragma unroll
-                    for (int gq = 0; gq < 4; ++gq) {
-                        const bf16x4 m4 = *(const bf16x4 *)&MQ[(urow + tok_w0 + 32 * tt + x) * R + 32 * at +
-                                                               8 * gq + 4 * h];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) den[tt] += (float)m4[j] * td[tt][4 * gq + j];
-                    }
-            }
-        }
-
         // numerator: phi'(q_i)^T Z_l with phi'(q_i) = m_i (x) m_i expanded in registers.  For
         // sketch row a and 16-wide step s the B operand is B[k = b'][j = token] = m_i[a] * m_i[b']
         // (12 VALU operations per fragment, each feeding CT MFMAs that accumulate straight into
@@ -1694,6 +1657,48 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
         };
         for (int k = 0; k < z_ncopy(0); ++k) stage_z_k(0, 0, k);
         load_mq(0);
+        // denominator: m_i^T S m_i with S = prefix of m_j m_j^T, hi + lo operands
+        {
+            const size_t sbase = ((size_t)u * (t - 1) + (NONCAUSAL ? 0 : l - 1)) * R * R;
+#pragma unroll
+            for (int at = 0; at < AT; ++at) {
+                f32x16 td[TT];
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) td[tt] = f32x16{0};
+#pragma unroll
+                for (int s = 0; s < RS; ++s) {
+                    const size_t off = sbase + ((size_t)(2 * s + h) * R + 32 * at + x) * 8;
+                    const bf16x8 s_hi = *(const bf16x8 *)&Shi[off], s_lo = *(const bf16x8 *)&Slo[off];
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) {
+                        td[tt] = mfma32(s_hi, mfr[tt][s], td[tt]);
+                        td[tt] = mfma32(s_lo, mfr[tt][s], td[tt]);
+                    }
+                }
+                // m_i[a] for the rows a = 32 at + 8 gq + 4 h + j this lane holds of td: they sit in
+                // the B operands already, half of them in the other half-wave (one swap per pair)
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        const uint4 w = __builtin_bit_cast(uint4, mfr[tt][2 * at + s2]);
+                        const auto s0 = __builtin_amdgcn_permlane32_swap(w.x, w.z, false, false);
+                        const auto s1 = __builtin_amdgcn_permlane32_swap(w.y, w.w, false, false);
+                        // lane h = 0: s0[0], s1[0] = elements 0..3, s0[1], s1[1] = elements 8..11 of the 16;
+                        // lane h = 1: elements 4..7 and 12..15
+                        const uint32_t pr[4] = {s0[0], s1[0], s0[1], s1[1]};
+#pragma unroll
+                        for (int g2 = 0; g2 < 2; ++g2)
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) {
+                                const uint32_t word = pr[2 * g2 + j / 2];
+                                const float mv = __uint_as_float((j & 1) ? (word & 0xffff0000u) : (word << 16));
+                                den[tt] += mv * td[tt][4 * (2 * s2 + g2) + j];
+                            }
+                    }
+            }
+        }
+
         store_mq(0);
         wait_all_memory();
         __syncthreads();
@@ -1762,6 +1767,19 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
         }
     }
 
+    if constexpr (PART == 2) {
+        // the in-block part, left by the first launch
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const f32x4 q4 = *(const f32x4 *)&Pnum[(((ptile0 + tt) * CT + ct) * 4 + gq) * 256 + lane * 4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) out[tt][ct][4 * gq + j] += q4[j];
+                }
+    }
     // ---------------- normalise and store (Section 3: divide by 1 + sum of weights) ----------------
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
