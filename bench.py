@@ -469,6 +469,9 @@ def main():
                     help="forward pass without the causal mask (psf_noncausal_attn_fwd)")
     ap.add_argument("--learned", action="store_true",
                     help="forward pass with learned sketches (Algorithm 2) instead of Gaussian ones")
+    ap.add_argument("--degree", type=int, default=None, choices=[2, 4, 8],
+                    help="degree p of the polynomial in place of the workload's (a variant of the workload, "
+                         "not the quoted configuration)")
     ap.add_argument("--decode-batch", type=int, default=64,
                     help="sequences decoded together by --pass decode (12 heads each)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -498,7 +501,9 @@ def main():
         args.workload = "config3"
     if args.workload not in wl:
         sys.exit("unknown workload %s; choose from %s" % (args.workload, ", ".join(sorted(wl))))
-    cfg = wl[args.workload]
+    cfg = dict(wl[args.workload])
+    if args.degree is not None:
+        cfg["p"] = args.degree
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     idx = int(args.workload[6:]) if args.workload.startswith("config") else 4

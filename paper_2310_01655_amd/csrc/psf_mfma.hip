@@ -36,7 +36,7 @@
 //                  the query sketch -- so that the in-block tiles fill the SIMD slots the
 //                  state workgroups (one wave per SIMD) leave empty; k_out PART 2 follows.
 //   k_learned_prep, k_learned_sketch
-//                  Algorithm 2 (learned sketches) of degree 4 with d = 64 on MFMA; other learned
+//                  Algorithm 2 (learned sketches) of degree 4 and 8 with d = 64 on MFMA; other learned
 //                  cases take m(x) from the general fp32 kernel through k_m_to_bf16 /
 //                  k_m_to_octets_and_partials.
 //   psf_mfma_bwd.inl (included below): the backward pass for d = 64, p = 4.
@@ -1934,8 +1934,9 @@ __global__ __launch_bounds__(kWg) void k_m_to_octets_and_partials(const MT *__re
 }
 
 // ------------------------------------------------------------------------------------
-// Learned sketch of degree 4 on MFMA (Algorithm 2 with p = 4, d = 64): m(x) =
-// sqrt(r) tanh(f1(x) * f2(x) / sqrt(r)), f = the four-layer network of Appendix D.
+// Learned sketches on MFMA (Algorithm 2 with d = 64; degree 4: m(x) =
+// sqrt(r) tanh(f1(x) * f2(x) / sqrt(r)), degree 8: the same node once more on two such sketches),
+// f = the four-layer network of Appendix D.
 // Everything is "transposed": accumulators hold [feature][token] (lane = token), so a layer's
 // output registers are the next layer's B operand after a bf16 conversion; the weights are
 // the A operands, pre-arranged by k_learned_prep so that every fragment is one 16-byte read
@@ -1962,49 +1963,101 @@ __device__ __forceinline__ float tanh_fast(float y)
     return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
-// Parameter blob of one network (input width 64): g1, b1, W1 [64][8R], g2, b2, W2 [8R][R],
-// W3 [R][8R], W4 [8R][R].
+// Operand type of the network layers.  Degree 4 keeps bf16; degree 8 stacks two levels of
+// networks and the rounding of every layer's operands to 8 mantissa bits adds up to the whole
+// tolerance of the path there, so its weights and activations are fp16 (11 bits; the weights
+// are bf16 values, exact in fp16 unless below 2^-14; activations are layer-normalised rows and
+// gelu outputs, far inside +-65504 for any network with O(1)-scaled weights -- beyond that
+// range they would overflow).
+template <bool HALF>
+struct LsOp;
+template <>
+struct LsOp<false> {
+    typedef bf16x8 v8;
+    typedef __bf16 elem;
+    __device__ static __forceinline__ v8 cvt(f32x8 x) { return cvt8(x); }
+    __device__ static __forceinline__ f32x16 mfma(v8 a, v8 b, f32x16 c) { return mfma32(a, b, c); }
+    __device__ static __forceinline__ uint16_t bits(float v) { return f32_to_bf16(v); }
+    __device__ static __forceinline__ float rounded(float v) { return bf16_to_f32(f32_to_bf16(v)); }
+};
+template <>
+struct LsOp<true> {
+    typedef f16x8 v8;
+    typedef _Float16 elem;
+    __device__ static __forceinline__ v8 cvt(f32x8 x) { return __builtin_convertvector(x, f16x8); }
+    __device__ static __forceinline__ f32x16 mfma(v8 a, v8 b, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    __device__ static __forceinline__ uint16_t bits(float v) { return __builtin_bit_cast(uint16_t, (_Float16)v); }
+    __device__ static __forceinline__ float rounded(float v) { return (float)(_Float16)v; }
+};
+template <class Op>
+__device__ __forceinline__ typename Op::v8 ls_cvt_from16(const f32x16 &v, int first)
+{
+    f32x8 t;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t[e] = v[first + e];
+    return Op::cvt(t);
+}
+
+// Parameter blob of one network of input width win (64 for the networks on x, R for the two
+// second-level ones of degree 8): g1, b1, W1 [win][8R], g2, b2, W2 [8R][R], W3 [R][8R], W4 [8R][R].
 template <int R>
 struct LearnedNet {
     static constexpr int HID = 8 * R, NCH = HID / 32, D = 64;
-    static constexpr size_t LEN = 2 * D + (size_t)D * HID + 2 * HID + 3 * (size_t)HID * R;
-    const bf16_t *g1, *b1, *W1, *g2, *b2, *W2, *W3, *W4;
-    __device__ explicit LearnedNet(const bf16_t *P)
+    __host__ __device__ static constexpr size_t len(int win)
     {
-        g1 = P; b1 = g1 + D; W1 = b1 + D; g2 = W1 + (size_t)D * HID; b2 = g2 + HID; W2 = b2 + HID;
+        return 2 * (size_t)win + (size_t)win * HID + 2 * HID + 3 * (size_t)HID * R;
+    }
+    // offset of network `net` in a parameter set of degree p (Appendix D order: the p / 2 networks
+    // on x, then the ones on sketches) and its input width
+    __host__ __device__ static constexpr int win_of(int net, int p) { return net < p / 2 ? D : R; }
+    __host__ __device__ static constexpr size_t offset_of(int net, int p)
+    {
+        return net < p / 2 ? net * len(D) : (p / 2) * len(D) + (net - p / 2) * len(R);
+    }
+    const bf16_t *g1, *b1, *W1, *g2, *b2, *W2, *W3, *W4;
+    __device__ LearnedNet(const bf16_t *P, int win)
+    {
+        g1 = P; b1 = g1 + win; W1 = b1 + win; g2 = W1 + (size_t)win * HID; b2 = g2 + HID; W2 = b2 + HID;
         W3 = W2 + (size_t)HID * R; W4 = W3 + (size_t)R * HID;
     }
 };
 
-// Slot (net, phase, chunk) of the weight stream of one parameter set; grid (4 * NCH, sets).
+// Slot (net, phase, chunk) of the weight stream of one parameter set; grid (2 * (P - 2) * NCH, sets).
 //   phase 0: [0, 4 KB)  W1' fragments: k-step s < 4, hidden row i, half h, e: k = 16 s + 8 h + e,
-//                       value bf16(g1[k] W1[k][32 ch + i])
+//                       value bf16(g1[k] W1[k][32 ch + i]); for the networks on sketches (degree 8)
+//                       k runs in accumulator row order like W3's feature below, zero past R
 //            [4 KB, ..) W2' fragments: out tile ot, k-step s < 2, out row i, half h, e:
 //                       hidden = 32 ch + 16 s + 8 (e / 4) + 4 h + e % 4 (accumulator row order),
 //                       value bf16(g2[hidden] W2[hidden][32 ot + i])
 //   phase 1: [0, 4 KB)  W3 fragments: k-step t < R / 16, hidden row i, half h, e:
 //                       feature = 32 (t / 2) + 16 (t % 2) + 8 (e / 4) + 4 h + e % 4
 //            [4 KB, ..) W4 fragments, arranged like W2' without the scale.
-template <int R>
+template <int R, int P_DEG = 4>
 __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__ P, size_t p_len,
                                                       bf16_t *__restrict__ LW, float *__restrict__ C1,
                                                       float *__restrict__ LVp)
 {
     using Net = LearnedNet<R>;
-    constexpr int NCH = Net::NCH, HID = Net::HID, D = Net::D;
+    using Op = LsOp<P_DEG == 8>;
+    constexpr int NCH = Net::NCH, HID = Net::HID, D = Net::D, NETS = P_DEG - 2;
     __shared__ float red[2][kWg];
     const int q = blockIdx.x, set = blockIdx.y, tid = threadIdx.x;
     const int net = q / (2 * NCH), phase = (q / NCH) % 2, ch = q % NCH;
-    const Net nt(P + (size_t)set * p_len + (size_t)net * Net::LEN);
-    bf16_t *slot = LW + ((size_t)set * 4 * NCH + q) * (kLsSlotBytes / 2);
+    const int win = Net::win_of(net, P_DEG);
+    const bool on_sketch = net >= P_DEG / 2;
+    const Net nt(P + (size_t)set * p_len + Net::offset_of(net, P_DEG), win);
+    bf16_t *slot = LW + ((size_t)set * 2 * NETS * NCH + q) * (kLsSlotBytes / 2);
     for (int idx = tid; idx < kLsSlotBytes / 2; idx += kWg) {
         float v = 0.f;
         const int part = idx / 2048, r2 = idx % 2048;
         const int i = (r2 % 512) / 16, h = (r2 / 8) % 2, e = r2 % 8, blk = r2 / 512;
         const int perm = 8 * (e / 4) + 4 * h + e % 4;           // accumulator row order inside 16
         if (phase == 0 && part == 0) {
-            const int k = 16 * blk + 8 * h + e;
-            v = bf16_to_f32(nt.g1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + 32 * ch + i]);
+            const int k = on_sketch ? 32 * (blk / 2) + 16 * (blk % 2) + perm : 16 * blk + 8 * h + e;
+            if (k < win) v = bf16_to_f32(nt.g1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + 32 * ch + i]);
         } else if (phase == 0) {
             if (blk < 2 * (R / 32)) {
                 const int ot = blk / 2, sstep = blk % 2, hid = 32 * ch + 16 * sstep + perm;
@@ -2021,23 +2074,23 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
                 v = bf16_to_f32(nt.W4[(size_t)hid * R + 32 * ot + i]);
             }
         }
-        slot[idx] = f32_to_bf16(v);
+        slot[idx] = Op::bits(v);
     }
     if (phase != 0) return;
     // constants of the folded layer normalisations for the 32 hidden units of this chunk:
     //   C1 [set][net][NCH][32] fp32: c1 = sum_k b1[k] W1[k][.]  (the accumulators of the input layer start there)
-    //   LVp [set][net][NCH][2][R] fp32: this chunk's part of s2 = sum_hid bf16(g2 W2), c2 = sum_hid b2 W2
+    //   LVp [set][net][NCH][2][R] fp32: this chunk's part of s2 = sum_hid (g2 W2 as stored), c2 = sum_hid b2 W2
     {
         const int i = tid & 31, kp = tid >> 5, hid = 32 * ch + i;
         float c1 = 0.f;
         for (int k = 8 * kp; k < 8 * kp + 8; ++k)
-            c1 += bf16_to_f32(nt.b1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + hid]);
+            if (k < win) c1 += bf16_to_f32(nt.b1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + hid]);
         red[0][tid] = c1;
         __syncthreads();
         if (tid < 32) {
             c1 = 0.f;
             for (int kk = 0; kk < D / 8; ++kk) c1 += red[0][32 * kk + tid];
-            C1[(((size_t)set * 2 + net) * NCH + ch) * 32 + tid] = c1;
+            C1[(((size_t)set * NETS + net) * NCH + ch) * 32 + tid] = c1;
         }
         __syncthreads();
     }
@@ -2048,7 +2101,7 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
         for (int hh = 0; hh < PER; ++hh) {
             const int hid = 32 * ch + hp * PER + hh;
             const float w = bf16_to_f32(nt.W2[(size_t)hid * R + out]);
-            s2 += bf16_to_f32(f32_to_bf16(bf16_to_f32(nt.g2[hid]) * w));
+            s2 += Op::rounded(bf16_to_f32(nt.g2[hid]) * w);
             c2 += bf16_to_f32(nt.b2[hid]) * w;
         }
         red[0][tid] = s2;
@@ -2057,7 +2110,7 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
         if (tid < R) {
             s2 = c2 = 0.f;
             for (int g = 0; g < GR; ++g) { s2 += red[0][g * R + tid]; c2 += red[1][g * R + tid]; }
-            float *o = LVp + (((size_t)set * 2 + net) * NCH + ch) * 2 * R;
+            float *o = LVp + (((size_t)set * NETS + net) * NCH + ch) * 2 * R;
             o[tid] = s2;
             o[R + tid] = c2;
         }
@@ -2069,7 +2122,10 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
 //   key side: the last layer runs with the operand roles swapped, so that lanes hold sketch
 //   columns and registers tokens; writes the token octets [rows/8][2][R][4] fp32 and the
 //   workgroup's S = m^T m (R x R fp32, from the bf16 m like the random-sketch kernel does).
-template <int R, bool QSIDE, int TT>
+// P_DEG = 8: three nodes -- networks 0, 1 and 2, 3 on x, then 4 on the first node's sketch and 5
+// on the second's (their inputs are the accumulator registers of the nodes, normalised in place:
+// no layout change, their first-layer weights are arranged in that register order).
+template <int R, bool QSIDE, int TT, int P_DEG = 4>
 __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__restrict__ X,
                                                                 const bf16_t *__restrict__ LW,
                                                                 const float *__restrict__ C1,
@@ -2080,14 +2136,17 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
                                                                 int per_head)
 {
     using Net = LearnedNet<R>;
+    using Op = LsOp<P_DEG == 8>;
+    typedef typename Op::v8 op8;
     constexpr int NCH = Net::NCH, HID = Net::HID, D = 64, OT = R / 32, KS = D / 16, RS = R / 16;
     constexpr int NW = 8 / TT, NTHR = 64 * NW;             // waves, threads
-    constexpr int QN = 4 * NCH;                            // slots of the weight stream
+    constexpr int NETS = P_DEG - 2;
+    constexpr int QN = 2 * NETS * NCH;                     // slots of the weight stream
     constexpr int DMA = kLsSlotBytes / 16 / NTHR;          // copies per thread and slot
     static_assert(NW * 32 * 32 * 4 <= kLsRing * kLsSlotBytes, "the reduction of S reuses the ring");
     __shared__ __attribute__((aligned(16))) unsigned char ring[kLsRing * kLsSlotBytes];
-    __shared__ __attribute__((aligned(16))) float c1s[2 * NCH * 32];
-    __shared__ __attribute__((aligned(16))) float lv[2 * 2 * R];
+    __shared__ __attribute__((aligned(16))) float c1s[NETS * NCH * 32];
+    __shared__ __attribute__((aligned(16))) float lv[NETS * 2 * R];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -2106,17 +2165,17 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
     };
 #pragma unroll
     for (int q = 0; q < kLsRing - 1; ++q) stage(q);
-    for (int idx = tid; idx < 2 * NCH * 32; idx += NTHR) c1s[idx] = C1[(size_t)set * 2 * NCH * 32 + idx];
-    for (int idx = tid; idx < 2 * 2 * R; idx += NTHR) {    // s2, c2: sum of the per-chunk parts
+    for (int idx = tid; idx < NETS * NCH * 32; idx += NTHR) c1s[idx] = C1[(size_t)set * NETS * NCH * 32 + idx];
+    for (int idx = tid; idx < NETS * 2 * R; idx += NTHR) { // s2, c2: sum of the per-chunk parts
         const int net = idx / (2 * R), rest = idx % (2 * R);
-        const float *src = LVp + ((size_t)set * 2 + net) * NCH * 2 * R + rest;
+        const float *src = LVp + ((size_t)set * NETS + net) * NCH * 2 * R + rest;
         float acc = 0.f;
         for (int ch = 0; ch < NCH; ++ch) acc += src[(size_t)ch * 2 * R];
         lv[idx] = acc;
     }
 
     // B operands of the first layer: the rows of X, normalised (zero mean, unit variance)
-    bf16x8 xfr[TT][KS];
+    op8 xfr[TT][KS];
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         const size_t row = row0 + wave * (32 * TT) + 32 * tt + x;
@@ -2139,13 +2198,47 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
 #pragma unroll
         for (int s = 0; s < KS; ++s)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) xfr[tt][s][e] = (__bf16)((xv[s][e] - mean) * inv);
+            for (int e = 0; e < 8; ++e) xfr[tt][s][e] = (typename Op::elem)((xv[s][e] - mean) * inv);
     }
 
+    // a node's sketch (accumulator registers, lane = token) -> normalised B operands of the
+    // network that takes it as input; steps past R / 16 are zero (so are their weights)
+    auto normalised = [&](const f32x16 (&mv)[TT][OT], op8 (&dst)[TT][KS]) {
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            float sum = 0.f, sq = 0.f;
+#pragma unroll
+            for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    sum += mv[tt][ot][v];
+                    sq += mv[tt][ot][v] * mv[tt][ot][v];
+                }
+            sum += __shfl_xor(sum, 32);
+            sq += __shfl_xor(sq, 32);
+            const float mean = sum * (1.0f / R), var = sq * (1.0f / R) - mean * mean;
+            const float inv = rsqrtf(fmaxf(var, 0.f) + 1e-6f);
+#pragma unroll
+            for (int t = 0; t < KS; ++t) {
+                if (t < RS) {
+                    f32x8 nv;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) nv[e] = (mv[tt][t / 2][8 * (t % 2) + e] - mean) * inv;
+                    dst[tt][t] = Op::cvt(nv);
+                } else {
+                    dst[tt][t] = op8{0};
+                }
+            }
+        }
+    };
+    static_assert(RS <= KS, "a sketch is no wider than a row");
+
     f32x16 f1[TT][OT];
+    f32x16 node_a[P_DEG == 8 ? TT : 1][P_DEG == 8 ? OT : 1];   // degree 8: the first node's sketch
+    op8 xin_b[P_DEG == 8 ? TT : 1][KS];                     // degree 8: input of network 5
     int q = 0;
 #pragma unroll 1
-    for (int net = 0; net < 2; ++net) {
+    for (int net = 0; net < NETS; ++net) {
         // ---- layers 1 and 2: P2 = gelu(LN(x) W1) (g2 . W2), with the sums for the second LN ----
         f32x16 acc2[TT][OT];
         float sh[TT], sqh[TT];
@@ -2161,9 +2254,9 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
             __syncthreads();                               // slot q has landed for everybody; slot q-1 is free
             stage(q + kLsRing - 1);
             const unsigned char *sl = ring + (q % kLsRing) * kLsSlotBytes;
-            bf16x8 a1[KS], a2[OT][2];
+            op8 a1[KS], a2[OT][2];
 #pragma unroll
-            for (int s = 0; s < KS; ++s) a1[s] = *(const bf16x8 *)(sl + ((s * 32 + x) * 2 + h) * 16);
+            for (int s = 0; s < KS; ++s) a1[s] = *(const op8 *)(sl + ((s * 32 + x) * 2 + h) * 16);
             f32x16 init;                                   // b1 W1 of this chunk's hidden rows
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
@@ -2175,12 +2268,12 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
             for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
-                    a2[ot][s] = *(const bf16x8 *)(sl + 4096 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
+                    a2[ot][s] = *(const op8 *)(sl + 4096 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 f32x16 acc = init;
 #pragma unroll
-                for (int s = 0; s < KS; ++s) acc = mfma32(a1[s], xfr[tt][s], acc);
+                for (int s = 0; s < KS; ++s) acc = Op::mfma(a1[s], xfr[tt][s], acc);   // (xfr: this network's input)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const float hv = gelu_fast(acc[v]);
@@ -2188,16 +2281,16 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
                     sqh[tt] += hv * hv;
                     acc[v] = hv;
                 }
-                const bf16x8 hf0 = cvt8_from16(acc, 0), hf1 = cvt8_from16(acc, 8);
+                const op8 hf0 = ls_cvt_from16<Op>(acc, 0), hf1 = ls_cvt_from16<Op>(acc, 8);
 #pragma unroll
                 for (int ot = 0; ot < OT; ++ot) {
-                    acc2[tt][ot] = mfma32(a2[ot][0], hf0, acc2[tt][ot]);
-                    acc2[tt][ot] = mfma32(a2[ot][1], hf1, acc2[tt][ot]);
+                    acc2[tt][ot] = Op::mfma(a2[ot][0], hf0, acc2[tt][ot]);
+                    acc2[tt][ot] = Op::mfma(a2[ot][1], hf1, acc2[tt][ot]);
                 }
             }
         }
         // ---- second layer normalisation applied to the accumulated product ----
-        bf16x8 h2f[TT][RS];
+        op8 h2f[TT][RS];
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
             const float s_all = sh[tt] + __shfl_xor(sh[tt], 32), q_all = sqh[tt] + __shfl_xor(sqh[tt], 32);
@@ -2213,8 +2306,8 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
                     for (int j2 = 0; j2 < 4; ++j2)
                         acc2[tt][ot][4 * g4 + j2] = (acc2[tt][ot][4 * g4 + j2] - mean * s2[j2]) * inv + c2[j2];
                 }
-                h2f[tt][2 * ot] = cvt8_from16(acc2[tt][ot], 0);
-                h2f[tt][2 * ot + 1] = cvt8_from16(acc2[tt][ot], 8);
+                h2f[tt][2 * ot] = ls_cvt_from16<Op>(acc2[tt][ot], 0);
+                h2f[tt][2 * ot + 1] = ls_cvt_from16<Op>(acc2[tt][ot], 8);
             }
         }
         // ---- layers 3 and 4: out = gelu(h2 W3) W4 ----
@@ -2229,35 +2322,35 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
             __syncthreads();
             stage(q + kLsRing - 1);
             const unsigned char *sl = ring + (q % kLsRing) * kLsSlotBytes;
-            bf16x8 a3[RS], a4[OT][2];
+            op8 a3[RS], a4[OT][2];
 #pragma unroll
-            for (int t = 0; t < RS; ++t) a3[t] = *(const bf16x8 *)(sl + ((t * 32 + x) * 2 + h) * 16);
+            for (int t = 0; t < RS; ++t) a3[t] = *(const op8 *)(sl + ((t * 32 + x) * 2 + h) * 16);
 #pragma unroll
             for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
-                    a4[ot][s] = *(const bf16x8 *)(sl + 4096 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
+                    a4[ot][s] = *(const op8 *)(sl + 4096 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 f32x16 acc = {0};
 #pragma unroll
-                for (int t = 0; t < RS; ++t) acc = mfma32(a3[t], h2f[tt][t], acc);
+                for (int t = 0; t < RS; ++t) acc = Op::mfma(a3[t], h2f[tt][t], acc);
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[v] = gelu_fast(acc[v]);
-                const bf16x8 hf0 = cvt8_from16(acc, 0), hf1 = cvt8_from16(acc, 8);
+                const op8 hf0 = ls_cvt_from16<Op>(acc, 0), hf1 = ls_cvt_from16<Op>(acc, 8);
 #pragma unroll
                 for (int ot = 0; ot < OT; ++ot) {
-                    if (QSIDE) {                           // [feature][token]
-                        out[tt][ot] = mfma32(a4[ot][0], hf0, out[tt][ot]);
-                        out[tt][ot] = mfma32(a4[ot][1], hf1, out[tt][ot]);
+                    if (QSIDE || net < NETS - 2) {         // [feature][token]
+                        out[tt][ot] = Op::mfma(a4[ot][0], hf0, out[tt][ot]);
+                        out[tt][ot] = Op::mfma(a4[ot][1], hf1, out[tt][ot]);
                     } else {                               // [token][feature]: lanes = sketch columns
-                        out[tt][ot] = mfma32(hf0, a4[ot][0], out[tt][ot]);
-                        out[tt][ot] = mfma32(hf1, a4[ot][1], out[tt][ot]);
+                        out[tt][ot] = Op::mfma(hf0, a4[ot][0], out[tt][ot]);
+                        out[tt][ot] = Op::mfma(hf1, a4[ot][1], out[tt][ot]);
                     }
                 }
             }
         }
-        if (net == 0) {
+        if ((net & 1) == 0) {
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
@@ -2270,6 +2363,22 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
                 for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) f1[tt][ot][v] = sr * tanh_fast(f1[tt][ot][v] * out[tt][ot][v] * isr);
+        }
+        if constexpr (P_DEG == 8) {
+            if (net == 1) {                                // first node done: keep it, x is still the input
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                    for (int ot = 0; ot < OT; ++ot) node_a[tt][ot] = f1[tt][ot];
+            } else if (net == 3) {                         // both nodes: they are the inputs from here on
+                normalised(f1, xin_b);
+                normalised(node_a, xfr);
+            } else if (net == 4) {
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) xfr[tt][s] = xin_b[tt][s];
+            }
         }
     }
     wait_vmem_le<0>();                                     // drain the clamped copies
@@ -2354,9 +2463,12 @@ struct MfmaWs {
     size_t total;
 };
 
-// Degree-4 learned sketches with d = 64 run on MFMA when a 256-token workgroup stays inside
-// one block; everything else goes through the general fp32 sketch kernel.
-bool learned_on_mfma(const Problem &pb) { return pb.learned && pb.p == 4 && pb.d == 64 && pb.b % 256 == 0; }
+// Learned sketches of degree 4 and 8 with d = 64 run on MFMA when a 256-token workgroup stays
+// inside one block; everything else goes through the general fp32 sketch kernel.
+bool learned_on_mfma(const Problem &pb)
+{
+    return pb.learned && (pb.p == 4 || pb.p == 8) && pb.d == 64 && pb.b % 256 == 0;
+}
 
 // tokens per partial S = m^T m handed to the denominator scan
 int part_tokens(const Problem &pb) { return learned_on_mfma(pb) ? 256 : 128 * sketch_tiles_per_wg(pb.b); }
@@ -2408,9 +2520,10 @@ MfmaWs carve(const Problem &pb, void *ws)
     const bool fast_learned = learned_on_mfma(pb);
     w.M32 = (float *)take(pb.learned && !fast_learned ? rows * R * 4 : 0);
     const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
-    w.LW = (bf16_t *)take(fast_learned ? sets * 4 * nch * kLsSlotBytes : 0);
-    w.C1 = (float *)take(fast_learned ? sets * 2 * nch * 32 * 4 : 0);
-    w.LVp = (float *)take(fast_learned ? sets * 2 * nch * 2 * R * 4 : 0);
+    const size_t nets = pb.p > 2 ? pb.p - 2 : 0;         // networks per set
+    w.LW = (bf16_t *)take(fast_learned ? sets * 2 * nets * nch * kLsSlotBytes : 0);
+    w.C1 = (float *)take(fast_learned ? sets * nets * nch * 32 * 4 : 0);
+    w.LVp = (float *)take(fast_learned ? sets * nets * nch * 2 * R * 4 : 0);
     w.total = off;
     return w;
 }
@@ -2494,20 +2607,20 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     if (pb.learned) {
         const size_t rows = (size_t)pb.units * pb.n, count = rows * R;
         bool fast = false;
-        if constexpr (P == 4 && D == 64) {
+        if constexpr ((P == 4 || P == 8) && D == 64) {
             if (learned_on_mfma(pb)) {
                 fast = true;
                 const int sets = pb.per_head ? pb.heads : 1;
                 const unsigned grid = (unsigned)(rows / 256);
-                hipLaunchKernelGGL((k_learned_prep<R>), dim3(4 * (R / 4), sets), dim3(kWg), 0, s,
+                hipLaunchKernelGGL((k_learned_prep<R, P>), dim3(2 * (P - 2) * (R / 4), sets), dim3(kWg), 0, s,
                                    (const bf16_t *)G, pb.g_len, w.LW, w.C1, w.LVp);
                 PSF_LAUNCH_CHECK();
                 constexpr int TT = 1;                       // 8 waves of one tile: two waves per SIMD
-                hipLaunchKernelGGL((k_learned_sketch<R, true, TT>), dim3(grid), dim3(512 / TT), 0, s,
+                hipLaunchKernelGGL((k_learned_sketch<R, true, TT, P>), dim3(grid), dim3(512 / TT), 0, s,
                                    (const bf16_t *)Q, w.LW, w.C1, w.LVp, w.MQ, nullptr, nullptr, pb.n, pb.heads,
                                    pb.per_head ? 1 : 0);
                 PSF_LAUNCH_CHECK();
-                hipLaunchKernelGGL((k_learned_sketch<R, false, TT>), dim3(grid), dim3(512 / TT), 0, s,
+                hipLaunchKernelGGL((k_learned_sketch<R, false, TT, P>), dim3(grid), dim3(512 / TT), 0, s,
                                    (const bf16_t *)K, w.LW, w.C1, w.LVp, nullptr, w.MK8, w.Spart, pb.n, pb.heads,
                                    pb.per_head ? 1 : 0);
                 PSF_LAUNCH_CHECK();

@@ -63,7 +63,8 @@ def test_attention_general_path_learned_fp32(p, local):
     print("general learned", p, assert_close(O.cpu().numpy(), want, "f32", "general learned p=%d" % p))
 
 
-@pytest.mark.parametrize("d,p,r,b", [(64, 4, 64, 256), (64, 4, 32, 256), (128, 4, 64, 256), (64, 8, 32, 512)])
+@pytest.mark.parametrize("d,p,r,b", [(64, 4, 64, 256), (64, 4, 32, 256), (128, 4, 64, 256), (64, 8, 32, 512),
+                                     (64, 8, 64, 256), (128, 8, 32, 256)])
 def test_attention_mfma_path_learned_bf16(d, p, r, b):
     q, k, v, P, desc = case(1, 2, 1024, d, p, r, b, "bf16")
     assert psf.kernel_path(desc) == 1
@@ -85,6 +86,19 @@ def test_attention_mfma_learned_kernel_sets_and_blocks(per_head, heads, n, b, r)
     want = oracle_rows(q, k, v, P, 4, r, b)
     print("mfma learned sets", (per_head, heads, n, b, r),
           assert_close(O.float().cpu().numpy(), want, "bf16", "mfma learned sets"))
+
+
+@pytest.mark.parametrize("per_head,heads,n,b,r", [(False, 3, 1024, 512, 64), (True, 3, 1536, 768, 32)])
+def test_attention_mfma_learned_kernel_degree_8(per_head, heads, n, b, r):
+    """Degree 8, d = 64: six networks per set on the MFMA network kernel (two of them take the
+    first-level sketches as input), shared and per-head parameters, several workgroups per block."""
+    q, k, v, P, desc = case(2, heads, n, 64, 8, r, b, "bf16", per_head=per_head, seed=69)
+    assert psf.kernel_path(desc) == 1
+    O = psf.psf_causal_attn_fwd(desc, q.cuda(), k.cuda(), v.cuda(), P.cuda())
+    torch.cuda.synchronize()
+    want = oracle_rows(q, k, v, P, 8, r, b)
+    print("mfma learned degree 8", (per_head, heads, n, b, r),
+          assert_close(O.float().cpu().numpy(), want, "bf16", "mfma learned degree 8"))
 
 
 def test_config3_shape_learned_sampled_rows():
