@@ -1313,6 +1313,17 @@ __global__ __launch_bounds__(2 * kWg, 1) void k_state_two_waves(const float *__r
 // a wave the accumulator registers as they are, [tile][value-column tile][register quad][lane]
 // x 16 bytes, and the partial weight sums of the 64 lanes (two per token).  The two launches add
 // the same terms as one launch in another order: equal within fp32 rounding, not bit for bit.
+// The half-precision state kernel as a launch of its own (any number of units; two workgroups per CU).
+template <int R, int D>
+__global__ __launch_bounds__(kWg, 2) void k_state_f16(const _Float16 *__restrict__ MKh,
+                                                      const _Float16 *__restrict__ V8h,
+                                                      const float *__restrict__ Kscale, bf16_t *__restrict__ Zg,
+                                                      int n, int b, int t, int units)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char lds[kStateF16Lds];
+    state_f16_workgroup<R, D>(MKh, V8h, Kscale, Zg, n, b, t, units, lds, blockIdx.x, gridDim.x);
+}
+
 constexpr int kKeyTilesInFlight = 4;
 template <int R, int D, int TT, bool LS, int PART>
 constexpr int out_lds_bytes()
@@ -2495,6 +2506,15 @@ bool in_block_beside_states(const Problem &pb)
            pb.n / 128 <= 512;
 }
 
+// The causal call with Gaussian sketches of degree 4, exact in-block weights and r = d = 64 forms its
+// prefix states from fp16 products (fp16 key sketches with a scale per 128-token tile, fp16 values),
+// beside the in-block part where that applies, else as a launch of its own.
+bool half_precision_states(const Problem &pb)
+{
+    return pb.d == 64 && pb.r == 64 && pb.p == 4 && !pb.learned && pb.local_exact && pb.t >= 2 &&
+           pb.b % 256 == 0 && pb.n / 128 <= kStateF16Tiles;
+}
+
 MfmaWs carve(const Problem &pb, void *ws)
 {
     MfmaWs w;
@@ -2515,8 +2535,8 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.MKrm = (bf16_t *)take(pb.local_exact ? 0 : rows * R * 2);
     w.Pnum = (float *)take(in_block_beside_states(pb) ? rows * D * 4 : 0);
     w.Pden = (float *)take(in_block_beside_states(pb) ? rows * 2 * 4 : 0);
-    w.V8h = (_Float16 *)take(in_block_beside_states(pb) ? rows * D * 2 : 0);
-    w.Kscale = (float *)take(in_block_beside_states(pb) ? rows / 128 * 4 : 0);
+    w.V8h = (_Float16 *)take(half_precision_states(pb) ? rows * D * 2 : 0);
+    w.Kscale = (float *)take(half_precision_states(pb) ? rows / 128 * 4 : 0);
     const bool fast_learned = learned_on_mfma(pb);
     w.M32 = (float *)take(pb.learned && !fast_learned ? rows * R * 4 : 0);
     const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
@@ -2604,6 +2624,9 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     // and, with Gaussian sketches of degree 4, the sketch of the query rows
     const bool beside = D == 64 && R == 64 && P != 2 && in_block_beside_states(pb) && !noncausal && !Den;
     const bool q_beside = beside && P == 4 && !pb.learned;
+    // the same state kernel without the fused launch (more state workgroups than CUs)
+    const bool f16_alone = D == 64 && R == 64 && P == 4 && half_precision_states(pb) && !beside && !noncausal && !Den &&
+                           !MK_rm;
     if (pb.learned) {
         const size_t rows = (size_t)pb.units * pb.n, count = rows * R;
         bool fast = false;
@@ -2648,7 +2671,7 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
         hipLaunchKernelGGL((k_m_to_octets_and_partials<R, bf16_t>), dim3((unsigned)(rows / part_tokens(pb))),
                            dim3(kWg), 0, s, (const bf16_t *)K, w.MK8, w.Spart, part_tokens(pb));
         PSF_LAUNCH_CHECK();
-    } else if (P == 4 && (q_beside || (size_t)pb.units * pb.n < kPrepMaxRows)) {
+    } else if (P == 4 && (q_beside || f16_alone || (size_t)pb.units * pb.n < kPrepMaxRows)) {
       if constexpr (P == 4) {
         // degree 4 with Gaussian sketches: query sketch + value layout in one launch, key sketch
         const unsigned parts = (unsigned)((size_t)pb.units * pb.n / (128 * (size_t)tiles));
@@ -2657,7 +2680,18 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
             if (st != PSF_OK) return st;
         }
         bf16_t *mk_rows = MK_rm ? MK_rm : (pb.local_exact ? nullptr : w.MKrm);
-        if (q_beside) {
+        if (f16_alone) {
+            hipLaunchKernelGGL((k_prep<D, R, false, true>), dim3(2 * parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                               (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                               pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1, w.Kscale,
+                               w.V8h);
+            PSF_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_prep<D, R, true, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                               (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                               pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1, w.Kscale,
+                               w.V8h);
+            PSF_LAUNCH_CHECK();
+        } else if (q_beside) {
             // the state kernel of this path works in half precision: fp16 value octets and key sketches
             hipLaunchKernelGGL((k_prep<D, R, false, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
                                (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
@@ -2738,7 +2772,13 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
             return PSF_OK;
         }
     }
-    if (pb.t > 1) {
+    if (f16_alone) {
+        if constexpr (D == 64 && R == 64) {
+            hipLaunchKernelGGL((k_state_f16<R, D>), dim3((unsigned)(pb.units * 10)), dim3(kWg), 0, s,
+                               (const _Float16 *)w.MK8, w.V8h, w.Kscale, w.Zg, pb.n, pb.b, pb.t, pb.units);
+            PSF_LAUNCH_CHECK();
+        }
+    } else if (pb.t > 1) {
         st = launch_state<D, R>(pb, w.MK8, w.V8, w.Zg, s);
         if (st != PSF_OK) return st;
     }
