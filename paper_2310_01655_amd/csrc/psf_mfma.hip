@@ -36,7 +36,7 @@
 //                  the query sketch -- so that the in-block tiles fill the SIMD slots the
 //                  state workgroups (one wave per SIMD) leave empty; k_out PART 2 follows.
 //   k_learned_prep, k_learned_sketch
-//                  Algorithm 2 (learned sketches) of degree 4 and 8 with d = 64 on MFMA; other learned
+//                  Algorithm 2 (learned sketches) of degree 4 and 8 with d = 64 or 128 on MFMA; other learned
 //                  cases take m(x) from the general fp32 kernel through k_m_to_bf16 /
 //                  k_m_to_octets_and_partials.
 //   psf_mfma_bwd.inl (included below): the backward pass for d = 64, p = 4.
@@ -1945,7 +1945,7 @@ __global__ __launch_bounds__(kWg) void k_m_to_octets_and_partials(const MT *__re
 }
 
 // ------------------------------------------------------------------------------------
-// Learned sketches on MFMA (Algorithm 2 with d = 64; degree 4: m(x) =
+// Learned sketches on MFMA (Algorithm 2 with d = 64 or 128; degree 4: m(x) =
 // sqrt(r) tanh(f1(x) * f2(x) / sqrt(r)), degree 8: the same node once more on two such sketches),
 // f = the four-layer network of Appendix D.
 // Everything is "transposed": accumulators hold [feature][token] (lane = token), so a layer's
@@ -1958,7 +1958,9 @@ __global__ __launch_bounds__(kWg) void k_m_to_octets_and_partials(const MT *__re
 // chunks, together with the sums of h and h^2.  Hidden width 8r is walked in chunks of 32;
 // the weights of a chunk (8 KB) stream through a ring of LDS slots.
 // ------------------------------------------------------------------------------------
-constexpr int kLsSlotBytes = 8192;     // one chunk: [W1' | W2'] or [W3 | W4], second part at +4096
+constexpr int kLsSlotBytes = 8192;     // one chunk at d = 64: [W1' | W2'] or [W3 | W4], second part at +4096
+// d = 128: W1' is eight 1 KB k-steps, so the second part sits at +8192 and a slot is 16 KB
+__host__ __device__ constexpr int ls_slot_bytes(int d) { return d == 64 ? kLsSlotBytes : 2 * kLsSlotBytes; }
 constexpr int kLsRing = 4;
 
 __device__ __forceinline__ float gelu_fast(float x)
@@ -2014,9 +2016,9 @@ __device__ __forceinline__ typename Op::v8 ls_cvt_from16(const f32x16 &v, int fi
 
 // Parameter blob of one network of input width win (64 for the networks on x, R for the two
 // second-level ones of degree 8): g1, b1, W1 [win][8R], g2, b2, W2 [8R][R], W3 [R][8R], W4 [8R][R].
-template <int R>
+template <int R, int D_IN = 64>
 struct LearnedNet {
-    static constexpr int HID = 8 * R, NCH = HID / 32, D = 64;
+    static constexpr int HID = 8 * R, NCH = HID / 32, D = D_IN;
     __host__ __device__ static constexpr size_t len(int win)
     {
         return 2 * (size_t)win + (size_t)win * HID + 2 * HID + 3 * (size_t)HID * R;
@@ -2046,29 +2048,30 @@ struct LearnedNet {
 //   phase 1: [0, 4 KB)  W3 fragments: k-step t < R / 16, hidden row i, half h, e:
 //                       feature = 32 (t / 2) + 16 (t % 2) + 8 (e / 4) + 4 h + e % 4
 //            [4 KB, ..) W4 fragments, arranged like W2' without the scale.
-template <int R, int P_DEG = 4>
+template <int R, int P_DEG = 4, int D_IN = 64>
 __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__ P, size_t p_len,
                                                       bf16_t *__restrict__ LW, float *__restrict__ C1,
                                                       float *__restrict__ LVp)
 {
-    using Net = LearnedNet<R>;
+    using Net = LearnedNet<R, D_IN>;
     using Op = LsOp<P_DEG == 8>;
     constexpr int NCH = Net::NCH, HID = Net::HID, D = Net::D, NETS = P_DEG - 2;
+    constexpr int SLOT = ls_slot_bytes(D), PART_ELEMS = SLOT / 4;      // bf16 / fp16 entries of one half of a slot
     __shared__ float red[2][kWg];
     const int q = blockIdx.x, set = blockIdx.y, tid = threadIdx.x;
     const int net = q / (2 * NCH), phase = (q / NCH) % 2, ch = q % NCH;
     const int win = Net::win_of(net, P_DEG);
     const bool on_sketch = net >= P_DEG / 2;
     const Net nt(P + (size_t)set * p_len + Net::offset_of(net, P_DEG), win);
-    bf16_t *slot = LW + ((size_t)set * 2 * NETS * NCH + q) * (kLsSlotBytes / 2);
-    for (int idx = tid; idx < kLsSlotBytes / 2; idx += kWg) {
+    bf16_t *slot = LW + ((size_t)set * 2 * NETS * NCH + q) * (SLOT / 2);
+    for (int idx = tid; idx < SLOT / 2; idx += kWg) {
         float v = 0.f;
-        const int part = idx / 2048, r2 = idx % 2048;
+        const int part = idx / PART_ELEMS, r2 = idx % PART_ELEMS;
         const int i = (r2 % 512) / 16, h = (r2 / 8) % 2, e = r2 % 8, blk = r2 / 512;
         const int perm = 8 * (e / 4) + 4 * h + e % 4;           // accumulator row order inside 16
         if (phase == 0 && part == 0) {
             const int k = on_sketch ? 32 * (blk / 2) + 16 * (blk % 2) + perm : 16 * blk + 8 * h + e;
-            if (k < win) v = bf16_to_f32(nt.g1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + 32 * ch + i]);
+            if (k < win && blk < D / 16) v = bf16_to_f32(nt.g1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + 32 * ch + i]);
         } else if (phase == 0) {
             if (blk < 2 * (R / 32)) {
                 const int ot = blk / 2, sstep = blk % 2, hid = 32 * ch + 16 * sstep + perm;
@@ -2094,13 +2097,13 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
     {
         const int i = tid & 31, kp = tid >> 5, hid = 32 * ch + i;
         float c1 = 0.f;
-        for (int k = 8 * kp; k < 8 * kp + 8; ++k)
+        for (int k = (D / 8) * kp; k < (D / 8) * (kp + 1); ++k)
             if (k < win) c1 += bf16_to_f32(nt.b1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + hid]);
         red[0][tid] = c1;
         __syncthreads();
         if (tid < 32) {
             c1 = 0.f;
-            for (int kk = 0; kk < D / 8; ++kk) c1 += red[0][32 * kk + tid];
+            for (int kk = 0; kk < kWg / 32; ++kk) c1 += red[0][32 * kk + tid];
             C1[(((size_t)set * NETS + net) * NCH + ch) * 32 + tid] = c1;
         }
         __syncthreads();
@@ -2136,7 +2139,7 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
 // P_DEG = 8: three nodes -- networks 0, 1 and 2, 3 on x, then 4 on the first node's sketch and 5
 // on the second's (their inputs are the accumulator registers of the nodes, normalised in place:
 // no layout change, their first-layer weights are arranged in that register order).
-template <int R, bool QSIDE, int TT, int P_DEG = 4>
+template <int R, bool QSIDE, int TT, int P_DEG = 4, int D_IN = 64>
 __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__restrict__ X,
                                                                 const bf16_t *__restrict__ LW,
                                                                 const float *__restrict__ C1,
@@ -2146,16 +2149,17 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
                                                                 float *__restrict__ Spart, int n, int heads,
                                                                 int per_head)
 {
-    using Net = LearnedNet<R>;
+    using Net = LearnedNet<R, D_IN>;
     using Op = LsOp<P_DEG == 8>;
     typedef typename Op::v8 op8;
-    constexpr int NCH = Net::NCH, HID = Net::HID, D = 64, OT = R / 32, KS = D / 16, RS = R / 16;
+    constexpr int NCH = Net::NCH, HID = Net::HID, D = D_IN, OT = R / 32, KS = D / 16, RS = R / 16;
+    constexpr int SLOT = ls_slot_bytes(D), PART1 = SLOT / 2;  // bytes of a slot; offset of its second part
     constexpr int NW = 8 / TT, NTHR = 64 * NW;             // waves, threads
     constexpr int NETS = P_DEG - 2;
     constexpr int QN = 2 * NETS * NCH;                     // slots of the weight stream
-    constexpr int DMA = kLsSlotBytes / 16 / NTHR;          // copies per thread and slot
-    static_assert(NW * 32 * 32 * 4 <= kLsRing * kLsSlotBytes, "the reduction of S reuses the ring");
-    __shared__ __attribute__((aligned(16))) unsigned char ring[kLsRing * kLsSlotBytes];
+    constexpr int DMA = SLOT / 16 / NTHR;          // copies per thread and slot
+    static_assert(NW * 32 * 32 * 4 <= kLsRing * SLOT, "the reduction of S reuses the ring");
+    __shared__ __attribute__((aligned(16))) unsigned char ring[kLsRing * SLOT];
     __shared__ __attribute__((aligned(16))) float c1s[NETS * NCH * 32];
     __shared__ __attribute__((aligned(16))) float lv[NETS * 2 * R];
 
@@ -2164,14 +2168,14 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
     const int x = lane & 31, h = lane >> 5;
     const size_t row0 = (size_t)blockIdx.x * 256;
     const int set = per_head ? (int)((row0 / n) % heads) : 0;
-    const unsigned char *stream = (const unsigned char *)(LW + (size_t)set * QN * (kLsSlotBytes / 2));
+    const unsigned char *stream = (const unsigned char *)(LW + (size_t)set * QN * (SLOT / 2));
     const uint32_t ring0 = lds_address(ring);
     auto stage = [&](int q) {
         const int qc = min(q, QN - 1);                     // clamped: keeps the copy count uniform
-        const uint32_t dst = ring0 + (q % kLsRing) * kLsSlotBytes + wave * 1024;
+        const uint32_t dst = ring0 + (q % kLsRing) * SLOT + wave * 1024;
 #pragma unroll
         for (int c = 0; c < DMA; ++c)
-            dma16_sbase(stream + (size_t)qc * kLsSlotBytes + c * (NTHR * 16), (uint32_t)tid * 16,
+            dma16_sbase(stream + (size_t)qc * SLOT + c * (NTHR * 16), (uint32_t)tid * 16,
                         dst + c * (NTHR * 16));
     };
 #pragma unroll
@@ -2264,7 +2268,7 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
             wait_vmem_le<(kLsRing - 2) * DMA>();
             __syncthreads();                               // slot q has landed for everybody; slot q-1 is free
             stage(q + kLsRing - 1);
-            const unsigned char *sl = ring + (q % kLsRing) * kLsSlotBytes;
+            const unsigned char *sl = ring + (q % kLsRing) * SLOT;
             op8 a1[KS], a2[OT][2];
 #pragma unroll
             for (int s = 0; s < KS; ++s) a1[s] = *(const op8 *)(sl + ((s * 32 + x) * 2 + h) * 16);
@@ -2279,7 +2283,7 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
             for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
-                    a2[ot][s] = *(const op8 *)(sl + 4096 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
+                    a2[ot][s] = *(const op8 *)(sl + PART1 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 f32x16 acc = init;
@@ -2332,7 +2336,7 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
             wait_vmem_le<(kLsRing - 2) * DMA>();
             __syncthreads();
             stage(q + kLsRing - 1);
-            const unsigned char *sl = ring + (q % kLsRing) * kLsSlotBytes;
+            const unsigned char *sl = ring + (q % kLsRing) * SLOT;
             op8 a3[RS], a4[OT][2];
 #pragma unroll
             for (int t = 0; t < RS; ++t) a3[t] = *(const op8 *)(sl + ((t * 32 + x) * 2 + h) * 16);
@@ -2340,7 +2344,7 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
             for (int ot = 0; ot < OT; ++ot)
 #pragma unroll
                 for (int s = 0; s < 2; ++s)
-                    a4[ot][s] = *(const op8 *)(sl + 4096 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
+                    a4[ot][s] = *(const op8 *)(sl + PART1 + (((ot * 2 + s) * 32 + x) * 2 + h) * 16);
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 f32x16 acc = {0};
@@ -2474,11 +2478,11 @@ struct MfmaWs {
     size_t total;
 };
 
-// Learned sketches of degree 4 and 8 with d = 64 run on MFMA when a 256-token workgroup stays
+// Learned sketches of degree 4 and 8 with d = 64 or 128 run on MFMA when a 256-token workgroup stays
 // inside one block; everything else goes through the general fp32 sketch kernel.
 bool learned_on_mfma(const Problem &pb)
 {
-    return pb.learned && (pb.p == 4 || pb.p == 8) && pb.d == 64 && pb.b % 256 == 0;
+    return pb.learned && (pb.p == 4 || pb.p == 8) && (pb.d == 64 || pb.d == 128) && pb.b % 256 == 0;
 }
 
 // tokens per partial S = m^T m handed to the denominator scan
@@ -2541,7 +2545,7 @@ MfmaWs carve(const Problem &pb, void *ws)
     w.M32 = (float *)take(pb.learned && !fast_learned ? rows * R * 4 : 0);
     const size_t nch = R / 4;                            // hidden chunks of 32 (8 R wide)
     const size_t nets = pb.p > 2 ? pb.p - 2 : 0;         // networks per set
-    w.LW = (bf16_t *)take(fast_learned ? sets * 2 * nets * nch * kLsSlotBytes : 0);
+    w.LW = (bf16_t *)take(fast_learned ? sets * 2 * nets * nch * ls_slot_bytes(pb.d) : 0);
     w.C1 = (float *)take(fast_learned ? sets * nets * nch * 32 * 4 : 0);
     w.LVp = (float *)take(fast_learned ? sets * nets * nch * 2 * R * 4 : 0);
     w.total = off;
@@ -2630,20 +2634,20 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     if (pb.learned) {
         const size_t rows = (size_t)pb.units * pb.n, count = rows * R;
         bool fast = false;
-        if constexpr ((P == 4 || P == 8) && D == 64) {
+        if constexpr (P == 4 || P == 8) {
             if (learned_on_mfma(pb)) {
                 fast = true;
                 const int sets = pb.per_head ? pb.heads : 1;
                 const unsigned grid = (unsigned)(rows / 256);
-                hipLaunchKernelGGL((k_learned_prep<R, P>), dim3(2 * (P - 2) * (R / 4), sets), dim3(kWg), 0, s,
+                hipLaunchKernelGGL((k_learned_prep<R, P, D>), dim3(2 * (P - 2) * (R / 4), sets), dim3(kWg), 0, s,
                                    (const bf16_t *)G, pb.g_len, w.LW, w.C1, w.LVp);
                 PSF_LAUNCH_CHECK();
                 constexpr int TT = 1;                       // 8 waves of one tile: two waves per SIMD
-                hipLaunchKernelGGL((k_learned_sketch<R, true, TT, P>), dim3(grid), dim3(512 / TT), 0, s,
+                hipLaunchKernelGGL((k_learned_sketch<R, true, TT, P, D>), dim3(grid), dim3(512 / TT), 0, s,
                                    (const bf16_t *)Q, w.LW, w.C1, w.LVp, w.MQ, nullptr, nullptr, pb.n, pb.heads,
                                    pb.per_head ? 1 : 0);
                 PSF_LAUNCH_CHECK();
-                hipLaunchKernelGGL((k_learned_sketch<R, false, TT, P>), dim3(grid), dim3(512 / TT), 0, s,
+                hipLaunchKernelGGL((k_learned_sketch<R, false, TT, P, D>), dim3(grid), dim3(512 / TT), 0, s,
                                    (const bf16_t *)K, w.LW, w.C1, w.LVp, nullptr, w.MK8, w.Spart, pb.n, pb.heads,
                                    pb.per_head ? 1 : 0);
                 PSF_LAUNCH_CHECK();
