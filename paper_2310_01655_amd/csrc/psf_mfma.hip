@@ -721,14 +721,20 @@ __global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__rest
 template <int R>
 __device__ __forceinline__ void den_scan_workgroup(const float *__restrict__ Spart, bf16_t *__restrict__ Shi,
                                                    bf16_t *__restrict__ Slo, int t, int parts_per_block,
-                                                   int parts_per_unit, int u, int blk)
+                                                   int parts_per_unit, int u, int blk, bf16_t *xch)
 {
-    // one entry of S per thread, threads in the order of the output layout [b'/8][a][8] so that
-    // a wave's 2-byte stores are contiguous (its reads are 32-byte pieces)
-    const int dst = blk * kWg + threadIdx.x;
-    if (dst >= R * R) return;
-    const int a = (dst / 8) % R, bq = (dst / (8 * R)) * 8 + dst % 8;
-    const int e = a * R + bq;
+    // One entry of S per thread, threads in the order of the partials (row-major [a][b']): a wave
+    // reads 256 contiguous bytes of every partial.  At a block boundary the 256 results change
+    // places through LDS (xch: 2 * kWg entries) so that they leave in the order of the output
+    // layout [b'/8][a][8]: pieces of kWg / R rows x 8 columns, 16 bytes per row.
+    static_assert(kWg % R == 0 && (R * R) % kWg == 0, "whole rows per workgroup");
+    constexpr int ROWS = kWg / R;
+    const int tid = threadIdx.x;
+    const int e = blk * kWg + tid;
+    const int a0 = blk * ROWS;
+    const int within = tid % (ROWS * 8), oa = a0 + within / 8, obq = 8 * (tid / (ROWS * 8)) + within % 8;
+    const int from = (oa - a0) * R + obq;                 // the thread that holds entry (oa, obq)
+    const int dst = ((obq / 8) * R + oa) * 8 + obq % 8;
     const float *src = Spart + (size_t)u * parts_per_unit * R * R + e;
     const int total = (t - 1) * parts_per_block;
     float run = 0.f;
@@ -741,12 +747,16 @@ __device__ __forceinline__ void den_scan_workgroup(const float *__restrict__ Spa
         for (int i = 0; i < FLY; ++i) {
             const int w = w0 + i;
             run += v[i];                          // zero past the end
-            if (w < total && (w + 1) % parts_per_block == 0) {
+            if (w < total && (w + 1) % parts_per_block == 0) {       // the same for every thread
                 const int l = w / parts_per_block;
                 const size_t base = ((size_t)u * (t - 1) + l) * R * R;
                 const bf16_t hi = f32_to_bf16(run);
-                Shi[base + dst] = hi;
-                Slo[base + dst] = f32_to_bf16(run - bf16_to_f32(hi));
+                xch[tid] = hi;
+                xch[kWg + tid] = f32_to_bf16(run - bf16_to_f32(hi));
+                __syncthreads();
+                Shi[base + dst] = xch[from];
+                Slo[base + dst] = xch[kWg + from];
+                __syncthreads();
             }
         }
     }
@@ -757,7 +767,8 @@ __global__ __launch_bounds__(kWg) void k_den_scan(const float *__restrict__ Spar
                                                   bf16_t *__restrict__ Shi, bf16_t *__restrict__ Slo,
                                                   int t, int parts_per_block, int parts_per_unit)
 {
-    den_scan_workgroup<R>(Spart, Shi, Slo, t, parts_per_block, parts_per_unit, blockIdx.y, blockIdx.x);
+    __shared__ bf16_t xch[2 * kWg];
+    den_scan_workgroup<R>(Spart, Shi, Slo, t, parts_per_block, parts_per_unit, blockIdx.y, blockIdx.x, xch);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1871,7 +1882,7 @@ __global__ __launch_bounds__(kWg, 2) void k_state_and_in_block(const float *__re
     if (bid < a.n_den) {
         constexpr int PER_UNIT = R * R / kWg;
         den_scan_workgroup<R>(a.Spart, a.Shi, a.Slo, t, a.parts_per_block, a.parts_per_unit, bid / PER_UNIT,
-                              bid % PER_UNIT);
+                              bid % PER_UNIT, (bf16_t *)lds);
         return;
     }
     bid -= a.n_den;
