@@ -558,7 +558,7 @@ template <int D, int R>
 __device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf16_t *__restrict__ X,
                                                    const bf16_t *__restrict__ g, size_t tok_wg0, int tiles_per_wg,
                                                    _Float16 *__restrict__ MKh, float *__restrict__ scale_out,
-                                                   float *__restrict__ Spart_out)
+                                                   float *__restrict__ Spart_out, bf16_t *__restrict__ M_rm)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int x = lane & 31, h = lane >> 5;
@@ -619,6 +619,10 @@ __device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf1
                 f16x4 q4 = {(_Float16)(alpha * m[ct][4 * gq]), (_Float16)(alpha * m[ct][4 * gq + 1]),
                             (_Float16)(alpha * m[ct][4 * gq + 2]), (_Float16)(alpha * m[ct][4 * gq + 3])};
                 *(f16x4 *)&MKh[(oct * R + c) * 8 + 4 * h] = q4;
+                if (M_rm)                                  // unscaled bf16 rows as well (the backward pass reads them)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        M_rm[(row0 + 8 * gq + 4 * h + j) * R + c] = f32_to_bf16(m[ct][4 * gq + j]);
             }
 #pragma unroll
         for (int sp = 0; sp < 2; ++sp) {              // S += M^T M over these 32 tokens
@@ -709,7 +713,7 @@ __global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__rest
         prep_sketch_role<D, R, true>(lds, Q, g, tok_wg0, tiles_per_wg, MQ, nullptr, nullptr);
     else if constexpr (F16)
         prep_keys_f16_role<D, R>(lds, K, g, tok_wg0, tiles_per_wg, (_Float16 *)MK8, Kscale + part * tiles_per_wg,
-                                 Spart + part * R * R);
+                                 Spart + part * R * R, MK_rm);
     else
         prep_sketch_role<D, R, false>(lds, K, g, tok_wg0, tiles_per_wg, MK_rm, MK8, Spart + part * R * R);
 }
@@ -1358,7 +1362,7 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
                                               float *__restrict__ Pden, int n, int b, int t,
                                               unsigned char *stage, int bid, int nblk)
 {
-    static_assert(PART == 0 || (!NONCAUSAL && !DEN), "the split serves the causal forward call");
+    static_assert(PART == 0 || (!NONCAUSAL && (PART == 2 || !DEN)), "the split serves the causal forward call");
     constexpr int KD = LS ? R : D;                        // row width of the in-block score operands
     constexpr int CT = D / 32, KS = KD / 16, RS = R / 16, AT = R / 32;
     constexpr int TOK_WAVE = 32 * TT, TOK_WG = 4 * TOK_WAVE;
@@ -2637,7 +2641,9 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     bool v_done = false;                         // value octets already written by the sketch launch
     // the state kernel's launch also runs the in-block part of the output, the denominator scan
     // and, with Gaussian sketches of degree 4, the sketch of the query rows
-    const bool beside = D == 64 && R == 64 && P != 2 && in_block_beside_states(pb) && !noncausal && !Den;
+    // (the backward pass's forward, which also wants the denominators: Gaussian sketches of degree 4 only)
+    const bool beside = D == 64 && R == 64 && P != 2 && in_block_beside_states(pb) && !noncausal &&
+                        (!Den || (P == 4 && !pb.learned));
     const bool q_beside = beside && P == 4 && !pb.learned;
     // the same state kernel without the fused launch (more state workgroups than CUs)
     const bool f16_alone = D == 64 && R == 64 && P == 4 && half_precision_states(pb) && !beside && !noncausal && !Den &&
@@ -2779,9 +2785,14 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
                                    pb.units, pb.n, pb.b, pb.t, a);
             PSF_LAUNCH_CHECK();
             if (tm) tm->mark();
-            hipLaunchKernelGGL((k_out<R, D, P, TT, false, false, false, 2>), dim3((unsigned)n_tiles), dim3(kWg), 0, s,
-                               (const bf16_t *)Q, (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O,
-                               nullptr, w.Pnum, w.Pden, pb.n, pb.b, pb.t);
+            if (Den)
+                hipLaunchKernelGGL((k_out<R, D, P, TT, true, false, false, 2>), dim3((unsigned)n_tiles), dim3(kWg), 0, s,
+                                   (const bf16_t *)Q, (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O,
+                                   Den, w.Pnum, w.Pden, pb.n, pb.b, pb.t);
+            else
+                hipLaunchKernelGGL((k_out<R, D, P, TT, false, false, false, 2>), dim3((unsigned)n_tiles), dim3(kWg), 0, s,
+                                   (const bf16_t *)Q, (const bf16_t *)K, w.V8, w.MQ, w.Zg, w.Shi, w.Slo, (bf16_t *)O,
+                                   nullptr, w.Pnum, w.Pden, pb.n, pb.b, pb.t);
             PSF_LAUNCH_CHECK();
             if (tm) tm->mark();
             return PSF_OK;
