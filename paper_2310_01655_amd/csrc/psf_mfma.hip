@@ -415,8 +415,9 @@ struct PrepLds {
     SketchLds<D, R> g;
     union {
         float red[4][32][33];                        // key role: S partial reduction
-        bf16_t qtile[4][32][R + 8];                  // query role: row-major store staging
+        bf16_t qtile[4][32][R + 8];                  // row-major store staging (query role; bf16 rows of m(K))
     } u;
+    float tmax[8];                                   // fp16 key role: the four waves' maxima, two tiles in flight
 };
 
 template <int D, int R>
@@ -585,7 +586,7 @@ __device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf1
     for (int i = 0; i < NT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j) sacc[i][j] = f32x16{0};
-    float *tile_max = &lds.u.red[0][0][0];                 // [2][4]: the four waves' maxima, two tiles in flight
+    float *tile_max = lds.tmax;                            // [2][4]
 #pragma unroll 1
     for (int tile = 0; tile < tiles_per_wg; ++tile) {
         const size_t row0 = tok_wg0 + (size_t)tile * 128 + wave * 32;
@@ -619,11 +620,23 @@ __device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf1
                 f16x4 q4 = {(_Float16)(alpha * m[ct][4 * gq]), (_Float16)(alpha * m[ct][4 * gq + 1]),
                             (_Float16)(alpha * m[ct][4 * gq + 2]), (_Float16)(alpha * m[ct][4 * gq + 3])};
                 *(f16x4 *)&MKh[(oct * R + c) * 8 + 4 * h] = q4;
-                if (M_rm)                                  // unscaled bf16 rows as well (the backward pass reads them)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        M_rm[(row0 + 8 * gq + 4 * h + j) * R + c] = f32_to_bf16(m[ct][4 * gq + j]);
             }
+        if (M_rm) {
+            // unscaled bf16 rows as well (the backward pass reads them): through LDS, so that the
+            // row-major store is 16 contiguous bytes per lane
+            bf16_t *qt = lds.u.qtile[wave][0];
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    qt[(8 * (v / 4) + 4 * h + v % 4) * (R + 8) + 32 * ct + x] = f32_to_bf16(m[ct][v]);
+            __builtin_amdgcn_s_waitcnt((0x3F & 0xF) | (0x7 << 4) | (0x0 << 8) | ((0x3F >> 4) << 14));   // own LDS writes
+#pragma unroll
+            for (int i = 0; i < 32 * R / 8 / 64; ++i) {
+                const int w = i * 64 + lane, tok = w / (R / 8), part = w % (R / 8);
+                *(uint4 *)&M_rm[(row0 + tok) * R + 8 * part] = *(const uint4 *)&qt[tok * (R + 8) + 8 * part];
+            }
+        }
 #pragma unroll
         for (int sp = 0; sp < 2; ++sp) {              // S += M^T M over these 32 tokens
             bf16x8 f[NT];
