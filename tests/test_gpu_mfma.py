@@ -254,3 +254,23 @@ def test_rows_of_other_norms_through_the_half_precision_state_kernel(k_scales, v
     assert psf.kernel_path(desc) == 1
     want = oracle_attn(cfg, q, k, v, G)
     print("norms", k_scales, v_scale, assert_close_scaled(got.numpy(), want, "bf16", "k x %s, v x %s" % (k_scales, v_scale)))
+
+
+@pytest.mark.parametrize("k_scales,v_scale", [((8.0, 0.25), 1.0), ((0.25, 1.0, 16.0, 0.5), 1 / 256)])
+def test_rows_of_other_norms_through_the_half_precision_state_launch(k_scales, v_scale):
+    """The same with more units than the fused launch takes (27 units x 10 state workgroups > 256
+    CUs): the half-precision state kernel then runs as a launch of its own, two workgroups per
+    CU, and the output kernel is the one-launch form."""
+    cfg = mk(3, 9, 1024, 64, 4, 64, 256)
+    q, k, v, G = draw(cfg, seed=47)
+    seg = cfg["n"] // len(k_scales)
+    k = k.float()
+    for i, sc in enumerate(k_scales):
+        k[:, :, i * seg:(i + 1) * seg] *= sc
+    k = k.to(torch.bfloat16)
+    v = (v.float() * v_scale).to(torch.bfloat16)
+    got, desc = gpu_attn(cfg, q, k, v, G)
+    assert psf.kernel_path(desc) == 1 and psf.fwd_beside_states(desc) == 0
+    want = oracle_attn(cfg, q, k, v, G)
+    print("norms, own launch", k_scales, v_scale,
+          assert_close_scaled(got.numpy(), want, "bf16", "k x %s, v x %s" % (k_scales, v_scale)))
