@@ -555,7 +555,9 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 
-template <int D, int R>
+// ROWS: also leave the unscaled sketch as bf16 rows in M_rm (a separate instantiation: the code
+// for it costs the plain one a third workgroup per CU in registers).
+template <int D, int R, bool ROWS>
 __device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf16_t *__restrict__ X,
                                                    const bf16_t *__restrict__ g, size_t tok_wg0, int tiles_per_wg,
                                                    _Float16 *__restrict__ MKh, float *__restrict__ scale_out,
@@ -621,7 +623,7 @@ __device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf1
                             (_Float16)(alpha * m[ct][4 * gq + 2]), (_Float16)(alpha * m[ct][4 * gq + 3])};
                 *(f16x4 *)&MKh[(oct * R + c) * 8 + 4 * h] = q4;
             }
-        if (M_rm) {
+        if constexpr (ROWS) {
             // unscaled bf16 rows as well (the backward pass reads them): through LDS, so that the
             // row-major store is 16 contiguous bytes per lane
             bf16_t *qt = lds.u.qtile[wave][0];
@@ -670,7 +672,7 @@ __device__ __forceinline__ void prep_keys_f16_role(PrepLds<D, R> &lds, const bf1
 // F16: for the half-precision state kernel -- role 1 writes fp16 key sketches and their scale
 // (prep_keys_f16_role; MK8 then points to them, Kscale gets one float per 128-token tile), role 2 also
 // writes the value rows as fp16 token octets (V8h; magnitudes beyond the fp16 range saturate).
-template <int D, int R, bool KEYS, bool F16 = false>
+template <int D, int R, bool KEYS, bool F16 = false, bool ROWS = false>
 __global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                               const bf16_t *__restrict__ V, const bf16_t *__restrict__ G,
                                               int n, int heads, int per_head, size_t g_len, int tiles_per_wg,
@@ -725,8 +727,8 @@ __global__ __launch_bounds__(kWg, KEYS ? 2 : 4) void k_prep(const bf16_t *__rest
     if constexpr (!KEYS)
         prep_sketch_role<D, R, true>(lds, Q, g, tok_wg0, tiles_per_wg, MQ, nullptr, nullptr);
     else if constexpr (F16)
-        prep_keys_f16_role<D, R>(lds, K, g, tok_wg0, tiles_per_wg, (_Float16 *)MK8, Kscale + part * tiles_per_wg,
-                                 Spart + part * R * R, MK_rm);
+        prep_keys_f16_role<D, R, ROWS>(lds, K, g, tok_wg0, tiles_per_wg, (_Float16 *)MK8, Kscale + part * tiles_per_wg,
+                                       Spart + part * R * R, MK_rm);
     else
         prep_sketch_role<D, R, false>(lds, K, g, tok_wg0, tiles_per_wg, MK_rm, MK8, Spart + part * R * R);
 }
@@ -2732,10 +2734,16 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
                                pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 0, w.Kscale,
                                w.V8h);
             PSF_LAUNCH_CHECK();
-            hipLaunchKernelGGL((k_prep<D, R, true, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
-                               (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
-                               pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1, w.Kscale,
-                               w.V8h);
+            if (mk_rows)
+                hipLaunchKernelGGL((k_prep<D, R, true, true, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                                   (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                                   pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1,
+                                   w.Kscale, w.V8h);
+            else
+                hipLaunchKernelGGL((k_prep<D, R, true, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                                   (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                                   pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1,
+                                   w.Kscale, w.V8h);
             PSF_LAUNCH_CHECK();
         } else {
             hipLaunchKernelGGL((k_prep<D, R, false>), dim3(2 * parts), dim3(kWg), 0, s, (const bf16_t *)Q,
