@@ -2545,8 +2545,9 @@ bool in_block_beside_states(const Problem &pb)
 // beside the in-block part where that applies, else as a launch of its own.
 bool half_precision_states(const Problem &pb)
 {
-    return pb.d == 64 && pb.r == 64 && pb.p == 4 && !pb.learned && pb.local_exact && pb.t >= 2 &&
-           pb.b % 256 == 0 && pb.n / 128 <= kStateF16Tiles;
+    // (either in-block rule: with Section 3.1's the key role also leaves the bf16 rows of m(K))
+    return pb.d == 64 && pb.r == 64 && pb.p == 4 && !pb.learned && pb.t >= 2 && pb.b % 256 == 0 &&
+           pb.n / 128 <= kStateF16Tiles;
 }
 
 MfmaWs carve(const Problem &pb, void *ws)
@@ -2722,10 +2723,16 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
                                pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1, w.Kscale,
                                w.V8h);
             PSF_LAUNCH_CHECK();
-            hipLaunchKernelGGL((k_prep<D, R, true, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
-                               (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
-                               pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1, w.Kscale,
-                               w.V8h);
+            if (mk_rows)
+                hipLaunchKernelGGL((k_prep<D, R, true, true, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                                   (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                                   pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1,
+                                   w.Kscale, w.V8h);
+            else
+                hipLaunchKernelGGL((k_prep<D, R, true, true>), dim3(parts), dim3(kWg), 0, s, (const bf16_t *)Q,
+                                   (const bf16_t *)K, (const bf16_t *)V, (const bf16_t *)G, pb.n, pb.heads,
+                                   pb.per_head ? 1 : 0, pb.g_len, tiles, w.MQ, w.MK8, mk_rows, w.Spart, w.V8, 1,
+                                   w.Kscale, w.V8h);
             PSF_LAUNCH_CHECK();
         } else if (q_beside) {
             // the state kernel of this path works in half precision: fp16 value octets and key sketches
