@@ -92,7 +92,7 @@ def cpu_baseline_noncausal(cfg, q, k, v, G):
             "seconds_measured": dt}
 
 
-def bwd_stage_flops(cfg):
+def bwd_stage_flops(cfg, learned=False):
     """Algorithmic flops of one backward step (multiply-add = 2) by stage of
     psf_causal_attn_bwd.  F = r^2 features, kc = dv + 1 columns, pairs = causal pairs inside
     blocks; states cover n - b tokens (first / last block excluded as in the forward count)."""
@@ -110,6 +110,15 @@ def bwd_stage_flops(cfg):
         "key_side": U * (2 * cross + 4 * (n - b) * F + pairs * 2 * (kc + 2 * d + d)),
         "sketch_gradient": U * 2 * sketch,                                   # recompute + transposed products
     }
+    if learned:
+        # Algorithm 2: p - 2 networks per row and side; forward once in the sketch stage; in the
+        # gradient stage the values again, a second forward per network, the products with the
+        # transposed matrices (one forward's worth) and the outer products of the parameter
+        # gradient (one more)
+        net = lambda win: 2 * (win * 8 * r + 24 * r * r)
+        nets = 2 * n * ((p // 2) * net(d) + max(p // 2 - 2, 0) * net(r))
+        f["sketches"] = U * nets
+        f["sketch_gradient"] = U * 4 * nets
     f["total"] = sum(f.values())
     return f
 
@@ -160,19 +169,20 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     dev = torch.device("cuda:0")
     dO = inputs.make_dout(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], seed=1000 + idx, dtype=cfg["dtype"])
     desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
-                         cfg["dtype"], per_head=cfg["per_head"],
+                         cfg["dtype"], per_head=cfg["per_head"], learned=args.learned,
                          local=psf.LOCAL_SKETCH if args.local_sketch else psf.LOCAL_EXACT)
     qd, kd, vd, Gd, dOd = (x.to(dev) for x in (q, k, v, G, dO))
     ws = psf.alloc_bwd_workspace(desc, dev)
     stream = torch.cuda.current_stream()
-    ramp_steps = ramp(lambda: psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream),
-                      args.ramp_ms, torch)
+    # learned sketches: the call that also returns the gradient of the networks' parameters
+    step = psf.psf_causal_attn_bwd_learned if args.learned else psf.psf_causal_attn_bwd
+    ramp_steps = ramp(lambda: step(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream), args.ramp_ms, torch)
     for _ in range(args.warmup):
-        psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream)
+        step(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        psf.psf_causal_attn_bwd(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream)
+        step(desc, qd, kd, vd, Gd, dOd, workspace=ws, stream=stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
@@ -183,7 +193,7 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
         for nm, ms in st.items():
             acc[nm] = acc.get(nm, 0.0) + ms / reps
     mfma = psf.bwd_kernel_path(desc) == 3
-    fl = bwd_stage_flops_mfma(cfg) if mfma else bwd_stage_flops(cfg)
+    fl = bwd_stage_flops_mfma(cfg) if mfma else bwd_stage_flops(cfg, learned=args.learned)
     dom = max(acc, key=lambda nm: acc[nm])
     achieved = fl[dom] / (acc[dom] * 1e-3) / 1e12
     peak = MFMA_BF16_PEAK_TFLOPS if mfma else FP32_VALU_PEAK_TFLOPS
@@ -196,6 +206,7 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
         "config": {"workload": args.workload, "pass": "bwd", "batch": cfg["batch"], "heads": cfg["heads"],
                    "n": cfg["n"], "d": cfg["d"], "p": cfg["p"], "r": cfg["r"], "b": cfg["b"],
                    "in_block": "sketch" if args.local_sketch else "exact",
+                   "sketch": "learned" if args.learned else "gaussian",
                    "storage": cfg["dtype"], "kernel_path": "mfma_bf16" if mfma else "general_fp32"},
         "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
         "tflops": fl["total"] / (ms_per_step * 1e-3) / 1e12,
@@ -203,7 +214,10 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
                      "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
                      "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc}},
     }
-    if not args.no_cpu_baseline and not args.local_sketch:   # the oracle driver used here: exact in-block weights
+    if args.learned:
+        out["stage_note"] = ("stage_ms from the timed call, which leaves out the parameter sums; "
+                             "ms_per_step is the whole call with them")
+    if not args.no_cpu_baseline and not args.local_sketch and not args.learned:   # the oracle driver used here: Gaussian sketches, exact in-block weights
         out["cpu_baseline"] = cpu_baseline_bwd(cfg, q, k, v, G, dO)
     print(json.dumps(out))
 

@@ -940,24 +940,31 @@ __global__ __launch_bounds__(kThreads) void bwd_sketch_learned_kernel(
     if (tid < d) store_f(dX, row * d + tid, dxs[tid]);
 }
 
-// dW[m][c] += sum over the chunk's rows of A[row][m] * D[row][c]  (A: [nrows][mw], D: [nrows][cw])
+// The sums over rows run in slices of kSliceRows rows (blockIdx.z): a slice leaves its part of
+// every parameter in its own copy of the network's blob, bwd_param_reduce then adds the slices to
+// the gradient in order.  (The outputs are small and the sums long: without slices a launch has
+// a handful of workgroups.)
+constexpr int kSliceRows = 256, kMaxSlices = 16;
+
+// part[z][m][c] = sum over the rows of slice z of A[row][m] * D[row][c]  (A: [nrows][mw], D: [nrows][cw])
 __global__ __launch_bounds__(kThreads) void bwd_param_gemm(const float *__restrict__ A, int mw,
                                                            const float *__restrict__ D, int cw, int nrows,
-                                                           float *__restrict__ dW)
+                                                           float *__restrict__ part, size_t slice_stride)
 {
     __shared__ float As[32][16], Ds[32][64];
     const int tid = threadIdx.x, tc = tid & 63, tg = tid >> 6;
     const int c0 = blockIdx.x * 64, m0 = blockIdx.y * 16;
+    const int row_lo = blockIdx.z * kSliceRows, row_hi = min(nrows, row_lo + kSliceRows);
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int r0 = 0; r0 < nrows; r0 += 32) {
+    for (int r0 = row_lo; r0 < row_hi; r0 += 32) {
         __syncthreads();
         for (int idx = tid; idx < 32 * 16; idx += kThreads) {
             const int rr = idx / 16, mm = idx % 16;
-            As[rr][mm] = (r0 + rr < nrows && m0 + mm < mw) ? A[(size_t)(r0 + rr) * mw + m0 + mm] : 0.f;
+            As[rr][mm] = (r0 + rr < row_hi && m0 + mm < mw) ? A[(size_t)(r0 + rr) * mw + m0 + mm] : 0.f;
         }
         for (int idx = tid; idx < 32 * 64; idx += kThreads) {
             const int rr = idx / 64, cc = idx % 64;
-            Ds[rr][cc] = (r0 + rr < nrows && c0 + cc < cw) ? D[(size_t)(r0 + rr) * cw + c0 + cc] : 0.f;
+            Ds[rr][cc] = (r0 + rr < row_hi && c0 + cc < cw) ? D[(size_t)(r0 + rr) * cw + c0 + cc] : 0.f;
         }
         __syncthreads();
         for (int rr = 0; rr < 32; ++rr) {
@@ -966,20 +973,33 @@ __global__ __launch_bounds__(kThreads) void bwd_param_gemm(const float *__restri
             for (int j = 0; j < 4; ++j) acc[j] += As[rr][tg * 4 + j] * dv;
         }
     }
+    float *out = part + (size_t)blockIdx.z * slice_stride;
     if (c0 + tc < cw)
         for (int j = 0; j < 4; ++j)
-            if (m0 + tg * 4 + j < mw) dW[(size_t)(m0 + tg * 4 + j) * cw + c0 + tc] += acc[j];
+            if (m0 + tg * 4 + j < mw) out[(size_t)(m0 + tg * 4 + j) * cw + c0 + tc] = acc[j];
 }
 
-// out[c] += sum over the chunk's rows of X[row][c]
+// part[z][c] = sum over the rows of slice z of X[row][c]
 __global__ __launch_bounds__(kThreads) void bwd_param_colsum(const float *__restrict__ X, int w, int nrows,
-                                                             float *__restrict__ out)
+                                                             float *__restrict__ part, size_t slice_stride)
 {
     const int c = blockIdx.x * kThreads + threadIdx.x;
     if (c >= w) return;
+    const int row_lo = blockIdx.z * kSliceRows, row_hi = min(nrows, row_lo + kSliceRows);
     float a = 0.f;
-    for (int rr = 0; rr < nrows; ++rr) a += X[(size_t)rr * w + c];
-    out[c] += a;
+    for (int rr = row_lo; rr < row_hi; ++rr) a += X[(size_t)rr * w + c];
+    part[(size_t)blockIdx.z * slice_stride + c] = a;
+}
+
+// g[i] += part[0][i] + part[1][i] + ... in that order
+__global__ __launch_bounds__(kThreads) void bwd_param_reduce(const float *__restrict__ part, size_t count,
+                                                             int slices, size_t slice_stride, float *__restrict__ g)
+{
+    const size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i >= count) return;
+    float a = g[i];
+    for (int z = 0; z < slices; ++z) a += part[(size_t)z * slice_stride + i];
+    g[i] = a;
 }
 
 __global__ __launch_bounds__(kThreads) void bwd_fill_kernel(float *__restrict__ p, size_t count)
@@ -1010,9 +1030,10 @@ int learned_chunk_rows(const Problem &pb)
 // dX = direct + J^T dM through Algorithm 2 for every row of X; dG (or null) += the parameter gradient
 template <typename T>
 psf_status learned_sketch_bwd(const Problem &pb, const void *X, const void *G, const float *dM,
-                              const float *direct, void *dX, float *dG, float *stage, hipStream_t s)
+                              const float *direct, void *dX, float *dG, float *stage, float *part, hipStream_t s)
 {
     const int RC = learned_chunk_rows(pb), nets = pb.p - 2, r = pb.r, hid = 8 * pb.r;
+    const size_t slice_stride = learned_net_len(pb.d > r ? pb.d : r, r);      // the longest network blob
     const size_t rows = (size_t)pb.units * pb.n;
     const size_t seg_rows = pb.per_head ? (size_t)pb.n : rows;
     for (size_t seg0 = 0; seg0 < rows; seg0 += seg_rows) {
@@ -1029,18 +1050,19 @@ psf_status learned_sketch_bwd(const Problem &pb, const void *X, const void *G, c
                 const int win = learned_net_win(k, pb.d, r, pb.p);
                 const NetStage ns = net_stage(base, (size_t)RC, win, r);
                 base = ns.end;
-                float *g = dG + set * pb.g_len + p_at;
+                float *g = part;                               // slice 0 of this network's blob
                 float *g1 = g, *b1 = g1 + win, *W1 = b1 + win;
                 float *g2 = W1 + (size_t)win * hid, *b2 = g2 + hid, *W2 = b2 + hid;
                 float *W3 = W2 + (size_t)hid * r, *W4 = W3 + (size_t)r * hid;
-                p_at += learned_net_len(win, r);
+                const size_t net_len = learned_net_len(win, r);
+                const int slices = (nrows + kSliceRows - 1) / kSliceRows;      // <= kMaxSlices: RC <= 4096
                 auto gemm = [&](size_t a_off, int mw, size_t d_off, int cw, float *dW) {
-                    hipLaunchKernelGGL(bwd_param_gemm, dim3((cw + 63) / 64, (mw + 15) / 16), dim3(kThreads), 0, s,
-                                       stage + a_off, mw, stage + d_off, cw, nrows, dW);
+                    hipLaunchKernelGGL(bwd_param_gemm, dim3((cw + 63) / 64, (mw + 15) / 16, slices), dim3(kThreads), 0,
+                                       s, stage + a_off, mw, stage + d_off, cw, nrows, dW, slice_stride);
                 };
                 auto colsum = [&](size_t x_off, int w, float *out) {
-                    hipLaunchKernelGGL(bwd_param_colsum, dim3((w + kThreads - 1) / kThreads), dim3(kThreads), 0, s,
-                                       stage + x_off, w, nrows, out);
+                    hipLaunchKernelGGL(bwd_param_colsum, dim3((w + kThreads - 1) / kThreads, 1, slices), dim3(kThreads),
+                                       0, s, stage + x_off, w, nrows, out, slice_stride);
                 };
                 colsum(ns.LG1, win, g1);
                 colsum(ns.LB1, win, b1);
@@ -1050,6 +1072,10 @@ psf_status learned_sketch_bwd(const Problem &pb, const void *X, const void *G, c
                 gemm(ns.A2, hid, ns.D2, r, W2);
                 gemm(ns.A3, r, ns.D3, hid, W3);
                 gemm(ns.A4, hid, ns.D4, r, W4);
+                hipLaunchKernelGGL(bwd_param_reduce, dim3((unsigned)((net_len + kThreads - 1) / kThreads)),
+                                   dim3(kThreads), 0, s, part, net_len, slices, slice_stride,
+                                   dG + set * pb.g_len + p_at);
+                p_at += net_len;
                 PSF_LAUNCH_CHECK();
             }
         }
@@ -1059,7 +1085,7 @@ psf_status learned_sketch_bwd(const Problem &pb, const void *X, const void *G, c
 
 struct BwdWs {
     float *MQ, *MK, *CV, *GC, *Z, *RB, *dMQ, *dMK, *dQd, *dKd;
-    float *LS;                                   // learned sketches: staging of one chunk of rows
+    float *LS, *LP;                              // learned sketches: staging of one chunk of rows; slices of one network's sums
     size_t total;
 };
 
@@ -1081,6 +1107,7 @@ BwdWs carve_bwd(const Problem &pb, void *ws)
     w.dQd = take(rows * pb.d);
     w.dKd = take(rows * pb.d);
     w.LS = take(pb.learned ? (size_t)learned_chunk_rows(pb) * learned_stage_floats_per_row(pb) : 0);
+    w.LP = take(pb.learned ? (size_t)kMaxSlices * learned_net_len(pb.d > pb.r ? pb.d : pb.r, pb.r) : 0);
     w.total = off;
     return w;
 }
@@ -1162,9 +1189,9 @@ psf_status bwd_launch(const Problem &pb, const void *Q, const void *K, const voi
                                s, dG, count);
             PSF_LAUNCH_CHECK();
         }
-        st = learned_sketch_bwd<T>(pb, Q, G, w.dMQ, w.dQd, dQ, dG, w.LS, s);
+        st = learned_sketch_bwd<T>(pb, Q, G, w.dMQ, w.dQd, dQ, dG, w.LS, w.LP, s);
         if (st != PSF_OK) return st;
-        st = learned_sketch_bwd<T>(pb, K, G, w.dMK, w.dKd, dK, dG, w.LS, s);
+        st = learned_sketch_bwd<T>(pb, K, G, w.dMK, w.dKd, dK, dG, w.LS, w.LP, s);
         if (st != PSF_OK) return st;
         if (tm) tm->mark();                               // stage: sketch gradient
         return PSF_OK;
