@@ -110,6 +110,33 @@ def test_backward_random_descriptor(seed):
     print(c)
 
 
+@pytest.mark.parametrize("seed", range(3500, 3516))
+def test_learned_backward_random_descriptor(seed):
+    """Learned sketches (Algorithm 2): gradients with respect to Q, K, V and to the networks'
+    parameters; the oracle works unit by unit, the parameter gradient of a set is the sum over the
+    units that use it."""
+    c = draw_desc(seed, max_width=24, max_r=12, degrees=(4, 8), max_blocks=3, max_b=24)
+    c["learned"] = True
+    q, k, v, G, desc = draw_inputs(c, seed)
+    dO = inputs.make_dout(c["batch"], c["heads"], c["n"], c["dv"], seed=seed, dtype=c["dtype"])
+    dQ, dK, dV, dG = psf.psf_causal_attn_bwd_learned(desc, *on_gpu(q, k, v, G, dO))
+    torch.cuda.synchronize()
+    wQ, wK, wV = (np.empty(tuple(t.shape)) for t in (q, k, v))
+    wG = np.zeros(tuple(G.shape))
+    for bi in range(c["batch"]):
+        for h in range(c["heads"]):
+            s = h if G.shape[0] > 1 else 0
+            wQ[bi, h], wK[bi, h], wV[bi, h], dp = oracle.attn_bwd_learned(
+                as_f64(q[bi, h]), as_f64(k[bi, h]), as_f64(v[bi, h]), as_f64(G[s]), as_f64(dO[bi, h]), c["p"],
+                c["r"], c["b"], local=oracle_local(c))
+            wG[s] += dp
+    for name, got, want in (("dQ", dQ, wQ), ("dK", dK, wK), ("dV", dV, wV)):
+        assert_close_scaled(got.float().cpu().numpy(), want, c["dtype"], "%s %s" % (name, c))
+    for s in range(G.shape[0]):
+        assert_close_scaled(dG[s].cpu().numpy(), wG[s], "f32", "dG set %d %s" % (s, c))
+    print(c)
+
+
 @pytest.mark.parametrize("seed", range(4000, 4024))
 def test_decode_random_descriptor(seed):
     """Prompt of a random length through psf_decode_prefill, the rest token by token: every
