@@ -174,8 +174,8 @@ static psf_status run_bwd(const psf_desc *desc, const void *Q, const void *K, co
     if (ws_bytes < need) return PSF_ERR_WORKSPACE;
     if (((uintptr_t)ws & 255u) != 0) return PSF_ERR_WORKSPACE;
     if (mfma && !aligned16({Q, K, V, G, dO, dQ, dK, dV})) return PSF_ERR_ALIGNMENT;
-    if (mfma) return mfma_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm);
     if (dG && !pb.learned) return PSF_ERR_UNSUPPORTED;
+    if (mfma) return mfma_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm, nullptr, nullptr, dG);
     return general_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, ws, (hipStream_t)stream, tm, dG);
 }
 
@@ -356,7 +356,7 @@ psf_status psf_noncausal_attn_fwd_timed(const psf_desc *desc, const void *Q, con
 size_t psf_fwd_save_bytes(const psf_desc *desc)
 {
     Problem pb;
-    if (make_problem(desc, &pb) != PSF_OK || !general_bwd_supported(pb) || !bwd_on_mfma(pb)) return 0;
+    if (make_problem(desc, &pb) != PSF_OK || !general_bwd_supported(pb) || !bwd_on_mfma(pb) || pb.learned) return 0;
     return mfma_fwd_save_bytes(pb);
 }
 
@@ -366,7 +366,7 @@ psf_status psf_causal_attn_fwd_save(const psf_desc *desc, const void *Q, const v
     Problem pb;
     psf_status st = make_problem(desc, &pb);
     if (st != PSF_OK) return st;
-    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb)) return PSF_ERR_UNSUPPORTED;
+    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb) || pb.learned) return PSF_ERR_UNSUPPORTED;
     if (!Q || !K || !V || !O || !save) return PSF_ERR_NULL;
     if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
     if (save_bytes < mfma_fwd_save_bytes(pb) || ((uintptr_t)save & 255u) != 0) return PSF_ERR_WORKSPACE;
@@ -382,7 +382,7 @@ psf_status psf_causal_attn_bwd_saved(const psf_desc *desc, const void *Q, const 
     Problem pb;
     psf_status st = make_problem(desc, &pb);
     if (st != PSF_OK) return st;
-    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb)) return PSF_ERR_UNSUPPORTED;
+    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb) || pb.learned) return PSF_ERR_UNSUPPORTED;
     if (!Q || !K || !V || !O || !dO || !dQ || !dK || !dV || !save || !workspace) return PSF_ERR_NULL;
     if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
     if (save_bytes < mfma_fwd_save_bytes(pb) || ((uintptr_t)save & 255u) != 0) return PSF_ERR_WORKSPACE;
@@ -511,6 +511,7 @@ const char *psf_stage_name(int path, int32_t stage)
     static const char *bwd[] = {"sketches", "forward_rows", "reverse_states", "query_side",
                                 "key_side", "sketch_gradient"};
     if (path == 2 && stage >= 0 && stage < 6) return bwd[stage];
+    // (learned sketches: the last stage also holds the networks' reverse pass and the parameter sums)
     static const char *bwd_mfma[] = {"forward_again", "g_c_and_layouts", "mirror_states", "in_block_and_dv",
                                      "cross_block_and_sketch_gradient"};
     if (path == 3 && stage >= 0 && stage < 5) return bwd_mfma[stage];

@@ -61,14 +61,17 @@ psf_status general_attn_bwd(const Problem &pb, const void *Q, const void *K, con
                             const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
                             hipStream_t s, StageTimer *tm, float *dG = nullptr);
 
-// Backward pass on MFMA (bf16, d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0, random sketches).
+// Backward pass on MFMA (bf16, d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0; random sketches
+// with either in-block rule (Section 3.1's for r = 64), learned sketches with exact in-block weights).
 bool mfma_bwd_supported(const Problem &pb);
 size_t mfma_bwd_workspace_bytes(const Problem &pb);
 // saved / O_saved: what mfma_attn_fwd_save left and the output it wrote (skips the forward pass
-// inside), or null.
+// inside; random sketches only), or null.  dG (learned sketches only): fp32 [sets][g_len], the
+// gradient of the network parameters, or null to treat them as constants.
 psf_status mfma_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                          const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s,
-                         StageTimer *tm, void *saved = nullptr, const void *O_saved = nullptr);
+                         StageTimer *tm, void *saved = nullptr, const void *O_saved = nullptr,
+                         float *dG = nullptr);
 size_t mfma_fwd_save_bytes(const Problem &pb);
 psf_status mfma_attn_fwd_save(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                               void *O, void *saved, hipStream_t s, StageTimer *tm);

@@ -2006,12 +2006,14 @@ __device__ __forceinline__ float tanh_fast(float y)
     return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
-// Operand type of the network layers.  Degree 4 keeps bf16; degree 8 stacks two levels of
-// networks and the rounding of every layer's operands to 8 mantissa bits adds up to the whole
-// tolerance of the path there, so its weights and activations are fp16 (11 bits; the weights
-// are bf16 values, exact in fp16 unless below 2^-14; activations are layer-normalised rows and
-// gelu outputs, far inside +-65504 for any network with O(1)-scaled weights -- beyond that
-// range they would overflow).
+// Operand type of the network layers: fp16.  With bf16 operands the rounding of every layer's
+// inputs to 8 mantissa bits adds up: at degree 8 (two levels of networks) to the whole tolerance
+// of the path, at degree 4 to two thirds of it once the gradients go through the same sketches.
+// fp16 has 11 bits; the weights are bf16 values, exact in fp16 unless below 2^-14; activations
+// are layer-normalised rows and gelu outputs, far inside +-65504 for any network with
+// O(1)-scaled weights -- beyond that range they would overflow.  (LsOp<false> keeps the bf16
+// variant of the same code.)
+constexpr bool kLsHalf = true;
 template <bool HALF>
 struct LsOp;
 template <>
@@ -2084,7 +2086,7 @@ __global__ __launch_bounds__(kWg) void k_learned_prep(const bf16_t *__restrict__
                                                       float *__restrict__ LVp)
 {
     using Net = LearnedNet<R, D_IN>;
-    using Op = LsOp<P_DEG == 8>;
+    using Op = LsOp<kLsHalf>;
     constexpr int NCH = Net::NCH, HID = Net::HID, D = Net::D, NETS = P_DEG - 2;
     constexpr int SLOT = ls_slot_bytes(D), PART_ELEMS = SLOT / 4;      // bf16 / fp16 entries of one half of a slot
     __shared__ float red[2][kWg];
@@ -2180,7 +2182,7 @@ __global__ __launch_bounds__(512 / TT, 1) void k_learned_sketch(const bf16_t *__
                                                                 int per_head)
 {
     using Net = LearnedNet<R, D_IN>;
-    using Op = LsOp<P_DEG == 8>;
+    using Op = LsOp<kLsHalf>;
     typedef typename Op::v8 op8;
     constexpr int NCH = Net::NCH, HID = Net::HID, D = D_IN, OT = R / 32, KS = D / 16, RS = R / 16;
     constexpr int SLOT = ls_slot_bytes(D), PART1 = SLOT / 2;  // bytes of a slot; offset of its second part
@@ -2879,6 +2881,7 @@ psf_status attn_impl(const Problem &pb, const void *Q, const void *K, const void
     return PSF_OK;
 }
 
+#include "psf_mfma_learned_bwd.inl"
 #include "psf_mfma_bwd.inl"
 
 }  // namespace
@@ -2909,18 +2912,20 @@ int mfma_beside_states(const Problem &pb0)
 bool mfma_bwd_supported(const Problem &pb)
 {
     // in-block weights from the sketches (Section 3.1): r = d only
+    // learned sketches (the networks' reverse pass on MFMA): exact in-block weights only
     return pb.d == 64 && pb.dv == 64 && pb.p == 4 && (pb.r == 32 || pb.r == 64) && pb.b % 256 == 0 &&
-           !pb.learned && !pb.exact_feat && (pb.local_exact || pb.r == 64);
+           !pb.exact_feat && (pb.local_exact || (pb.r == 64 && !pb.learned));
 }
 
 size_t mfma_bwd_workspace_bytes(const Problem &pb) { return carve_bwd(pb, nullptr).total; }
 
 psf_status mfma_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                          const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm,
-                         void *saved, const void *O_saved)
+                         void *saved, const void *O_saved, float *dG)
 {
-    if (pb.r == 64) return attn_bwd_impl<64>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm, saved, O_saved);
-    return attn_bwd_impl<32>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm, saved, O_saved);
+    if (dG && !pb.learned) return PSF_ERR_UNSUPPORTED;
+    if (pb.r == 64) return attn_bwd_impl<64>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm, saved, O_saved, dG);
+    return attn_bwd_impl<32>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm, saved, O_saved, dG);
 }
 
 size_t mfma_fwd_save_bytes(const Problem &pb) { return carve_saved(pb, nullptr).total; }

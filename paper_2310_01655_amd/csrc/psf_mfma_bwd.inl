@@ -373,14 +373,15 @@ struct Cross {
 // LS (in-block rule of Section 3.1, R == D): the in-block weights are functions of the sketches
 // too, so dXacc holds the in-block part of dm ([rows][R] fp32), which joins dm before the sketch:
 // dX = bf16(J_m(x)^T (dm + dXacc)).
-template <int R, int D, bool QSIDE, int TT, bool LS = false>
+// RAW (learned sketches): dm itself is the result, fp32 rows [rows][R] in dMout (no sketch matrices).
+template <int R, int D, bool QSIDE, int TT, bool LS = false, bool RAW = false>
 __global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M, const bf16_t *__restrict__ Vec,
                                                   const float *__restrict__ Cc, const bf16_t *__restrict__ ZT,
                                                   const bf16_t *__restrict__ Shi, const bf16_t *__restrict__ Slo,
                                                   const bf16_t *__restrict__ Xrows, const bf16_t *__restrict__ Gt,
                                                   const bf16_t *__restrict__ G, const float *__restrict__ dXacc,
                                                   bf16_t *__restrict__ dX, int n, int b, int t, int heads,
-                                                  int per_head, size_t g_len)
+                                                  int per_head, size_t g_len, float *__restrict__ dMout = nullptr)
 {
     using X = Cross<R, D, R, false, TT>;
     static_assert(sizeof(SketchLds<D, R>) + 2 * D * (R + 8) * 2 <= X::LDS_BYTES, "the sketch matrices reuse the stage");
@@ -444,6 +445,20 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M,
                 for (int v = 0; v < 16; ++v) out[tt][at][v] += 2.0f * coef * td[tt][v];   // the state operand is stored doubled
             }
         }
+    }
+    if constexpr (RAW) {
+        // register v of out[tt][at]: sketch column 32 at + 8 (v / 4) + 4 h + v % 4
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+            for (int at = 0; at < AT; ++at)
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const f32x4 o4 = {out[tt][at][4 * gq], out[tt][at][4 * gq + 1], out[tt][at][4 * gq + 2],
+                                      out[tt][at][4 * gq + 3]};
+                    *(f32x4 *)&dMout[(urow + i0 + wave * 32 * TT + 32 * tt + x) * R + 32 * at + 8 * gq + 4 * h] = o4;
+                }
+        return;
     }
     // through the sketch; the stage is free again (the contraction ends with a barrier)
     SketchLds<D, R> &lds = *(SketchLds<D, R> *)stage;
@@ -787,6 +802,11 @@ struct MfmaBwdWs {
     void *fwd;                                               // the forward workspace
     bf16_t *O, *MK, *G_rm, *G8, *G8r, *Q8, *K8, *QF, *KF, *VF, *GF, *Rg, *ZT, *RT, *Rchi, *Rclo;
     float *Den, *Cc, *M8r, *ScPart, *dVc, *dQacc, *dKacc;
+    // learned sketches: backward weight stream, what the row kernel leaves for the parameter
+    // kernel (one side at a time), its workgroup sums, the per-unit parameter sums of both sides
+    bf16_t *LB;
+    LbStage sg;
+    float *GB1, *part;
     size_t total;
 };
 
@@ -822,6 +842,22 @@ MfmaBwdWs carve_bwd(const Problem &pb, void *ws)
     w.dVc = (float *)take(rows * D * 4);
     w.dQacc = (float *)take(rows * D * 4);
     w.dKacc = (float *)take(rows * D * 4);
+    if (pb.learned) {
+        const size_t sets = pb.per_head ? pb.heads : 1, nch = R / 4;
+        w.LB = (bf16_t *)take(sets * 4 * nch * kLbSlot);
+        w.sg.rows = rows;
+        w.sg.XnR = (bf16_t *)take(rows * D * 2);
+        w.sg.XnT = (bf16_t *)take(rows * D * 2);
+        w.sg.A2R = (bf16_t *)take(2 * rows * R * 2);
+        w.sg.A2T = (bf16_t *)take(2 * rows * R * 2);
+        w.sg.DOR = (bf16_t *)take(2 * rows * R * 2);
+        w.sg.DOT = (bf16_t *)take(2 * rows * R * 2);
+        w.sg.DAR = (bf16_t *)take(2 * rows * R * 2);
+        w.sg.DAT = (bf16_t *)take(2 * rows * R * 2);
+        w.sg.ST = (float *)take(2 * 4 * rows * 4);
+        w.GB1 = (float *)take(rows / 256 * 2 * 2 * D * 4);
+        w.part = (float *)take(2 * (size_t)pb.units * pb.g_len * 4);
+    }
     w.total = off;
     return w;
 }
@@ -855,7 +891,7 @@ MfmaSaved carve_saved(const Problem &pb, void *ptr)
 template <int R>
 psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                          const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm,
-                         void *saved = nullptr, const void *O_saved = nullptr)
+                         void *saved = nullptr, const void *O_saved = nullptr, float *dG = nullptr)
 {
     constexpr int D = 64, P = 4, TT = 2;
     constexpr int NWL = 4;                                  // waves per in-block workgroup: 256 own rows share a streamed tile
@@ -867,6 +903,7 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     // m(Q), m(K) in place of Q, K with exponent 2 and leave the in-block part of dm
     const bool ls = !pb.local_exact;
     if (ls && R != D) return PSF_ERR_UNSUPPORTED;
+    if (pb.learned && (ls || saved)) return PSF_ERR_UNSUPPORTED;
     psf_status st;
     if (saved) {
         const MfmaSaved sv = carve_saved(pb, saved);
@@ -878,6 +915,14 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
         // forward pass again: O, the denominators, m(Q), m(K), the states Z_l and S_l
         st = attn_impl<D, R, P>(pb, Q, K, V, G, w.O, w.fwd, s, nullptr, w.Den, w.MK);
         if (st != PSF_OK) return st;
+        if (pb.learned) {
+            // (the learned key-side sketch kernel writes the state kernel's octets only)
+            if (!learned_on_mfma(pb)) return PSF_ERR_UNSUPPORTED;
+            const size_t count4 = rows * R / 4;
+            hipLaunchKernelGGL((k_octets_to_rows<R>), dim3((unsigned)((count4 + kWg - 1) / kWg)), dim3(kWg), 0, s,
+                               f.MK8, w.MK, count4);
+            PSF_LAUNCH_CHECK();
+        }
     }
     if (tm) tm->mark();
     const bf16_t *rq = ls ? f.MQ : q, *rk = ls ? w.MK : k;  // the rows the in-block weights are made of
@@ -962,7 +1007,50 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
                 PSF_LAUNCH_CHECK();
             }
         }
-        if (!ls) {
+        if (pb.learned) {
+            // dm as fp32 rows (in the buffer of the mirror-state octets, consumed by now), then
+            // through the networks: one side after the other, the staging buffers serve both
+            const int sets = pb.per_head ? pb.heads : 1;
+            const unsigned grid_rows = (unsigned)(rows / 256);
+            const unsigned grid_par = (unsigned)(pb.units * 2 * (R / 4 / 4));
+            hipLaunchKernelGGL((k_learned_bwd_prep<R>), dim3(4 * (R / 4), sets), dim3(kWg), 0, s, (const bf16_t *)G,
+                               pb.g_len, w.LB);
+            PSF_LAUNCH_CHECK();
+            for (int side = 0; side < 2; ++side) {
+                if (side == 0)
+                    hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT, false, true>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm,
+                                       w.Cc, w.ZT, f.Shi, f.Slo, q, nullptr, nullptr, nullptr, nullptr, pb.n, pb.b, pb.t,
+                                       pb.heads, ph, pb.g_len, w.M8r);
+                else
+                    hipLaunchKernelGGL((k_bwd_dm<R, D, false, TT, false, true>), dim3(grid), dim3(kWg), 0, s, w.MK, v,
+                                       w.Cc, w.RT, w.Rchi, w.Rclo, k, nullptr, nullptr, nullptr, nullptr, pb.n, pb.b, pb.t,
+                                       pb.heads, ph, pb.g_len, w.M8r);
+                PSF_LAUNCH_CHECK();
+                const bf16_t *xr = side == 0 ? q : k;
+                const float *base = side == 0 ? w.dQacc : w.dKacc;
+                bf16_t *dx = (bf16_t *)(side == 0 ? dQ : dK);
+                if (dG) {
+                    hipLaunchKernelGGL((k_learned_bwd_rows<R, true>), dim3(grid_rows), dim3(512), 0, s, xr, w.M8r, base,
+                                       f.LW, f.C1, f.LVp, w.LB, (const bf16_t *)G, pb.g_len, dx, w.sg, w.GB1, pb.n,
+                                       pb.heads, ph);
+                    PSF_LAUNCH_CHECK();
+                    hipLaunchKernelGGL((k_learned_bwd_params<R>), dim3(grid_par), dim3(kWg), 0, s, w.sg,
+                                       (const bf16_t *)G, pb.g_len, f.C1, w.GB1,
+                                       w.part + (size_t)side * pb.units * pb.g_len, pb.g_len, pb.n, pb.heads, ph);
+                    PSF_LAUNCH_CHECK();
+                } else {
+                    hipLaunchKernelGGL((k_learned_bwd_rows<R, false>), dim3(grid_rows), dim3(512), 0, s, xr, w.M8r, base,
+                                       f.LW, f.C1, f.LVp, w.LB, (const bf16_t *)G, pb.g_len, dx, w.sg, w.GB1, pb.n,
+                                       pb.heads, ph);
+                    PSF_LAUNCH_CHECK();
+                }
+            }
+            if (dG) {
+                hipLaunchKernelGGL(k_learned_bwd_reduce, dim3((unsigned)((pb.g_len + kWg - 1) / kWg), sets), dim3(kWg), 0, s,
+                                   w.part, dG, pb.g_len, pb.units, pb.heads, ph);
+                PSF_LAUNCH_CHECK();
+            }
+        } else if (!ls) {
             hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm, w.Cc, w.ZT, f.Shi,
                                f.Slo, q, f.Gt, (const bf16_t *)G, w.dQacc, (bf16_t *)dQ, pb.n, pb.b, pb.t, pb.heads, ph,
                                pb.g_len);

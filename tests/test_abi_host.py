@@ -113,12 +113,25 @@ def test_backward_kernel_path_and_mfma_workspace():
     assert psf.bwd_kernel_path(psf.make_desc(1, 1, 1024, 64, 4, 16, 128, "f32")) == 2
     assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 128, 4, 64, 256, "bf16")) == 2     # d = 128: general kernels
     assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 8, 64, 256, "bf16")) == 2      # p = 8
+    # learned sketches of degree 4 with exact in-block weights: the MFMA kernels; other degrees,
+    # the in-block rule of Section 3.1 and fp32 storage: the general ones
     learned = psf.make_desc(1, 2, 1024, 64, 4, 64, 256, "bf16", learned=True)
-    assert psf.bwd_kernel_path(learned) == 2                                               # learned sketches
-    # the general workspace plus the staging the parameter sums read (here 2048 rows of 2 networks)
     plain = psf.make_desc(1, 2, 1024, 64, 4, 64, 256, "bf16")
+    assert psf.bwd_kernel_path(learned) == 3
+    rows = 2 * 1024
+    # the Gaussian-sketch workspace + staged r-wide vectors of both networks (rows and tiles) + the
+    # per-unit parameter sums of both sides
+    assert psf.bwd_workspace_bytes(learned) >= (psf.bwd_workspace_bytes(plain) + 2 * rows * 64 * 2 + 12 * rows * 64 * 2
+                                                + 2 * 2 * psf.lib().psf_learned_len(64, 64, 4) * 4)
+    assert psf.fwd_save_bytes(learned) == 0                                                # recomputing call only
+    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 8, 64, 256, "bf16", learned=True)) == 2
+    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 4, 64, 256, "bf16", learned=True,
+                                             local=psf.LOCAL_SKETCH)) == 2
+    learned_general = psf.make_desc(1, 2, 1024, 64, 4, 64, 256, "f32", learned=True)
     plain_general = psf.make_desc(1, 2, 1024, 64, 4, 64, 256, "f32")
-    assert psf.bwd_workspace_bytes(learned) >= psf.bwd_workspace_bytes(plain_general) + 2048 * 2 * (3 * 64 + 6 * 512 + 3 * 64) * 4
+    assert psf.bwd_kernel_path(learned_general) == 2
+    # the general workspace plus the staging the parameter sums read (here 2048 rows of 2 networks)
+    assert psf.bwd_workspace_bytes(learned_general) >= psf.bwd_workspace_bytes(plain_general) + 2048 * 2 * (3 * 64 + 6 * 512 + 3 * 64) * 4
     assert psf.bwd_kernel_path(plain) == 3
     assert psf.lib().psf_stage_name(3, 0) == b"forward_again"
     assert psf.lib().psf_stage_name(3, 4) == b"cross_block_and_sketch_gradient"

@@ -38,12 +38,12 @@ def oracle_grads(q, k, v, P, dO, p, r, b, local):
     return wQ, wK, wV, wP
 
 
-def run_case(batch, heads, n, d, dv, p, r, b, dtype, local=psf.LOCAL_EXACT, per_head=True, seed=71):
+def run_case(batch, heads, n, d, dv, p, r, b, dtype, local=psf.LOCAL_EXACT, per_head=True, seed=71, path=2):
     q, k, v = inputs.make_qkv(batch, heads, n, d, dv=dv, seed=seed, dtype=dtype)
     dO = inputs.make_dout(batch, heads, n, dv, seed=seed, dtype=dtype)
     P = inputs.make_learned_params(heads, d, r, p, per_head=per_head, seed=3, dtype=dtype)
     desc = psf.make_desc(batch, heads, n, d, p, r, b, dtype, dv=dv, local=local, per_head=per_head, learned=True)
-    assert psf.bwd_kernel_path(desc) == 2
+    assert psf.bwd_kernel_path(desc) == path
     dev = torch.device("cuda:0")
     args = [x.to(dev) for x in (q, k, v, P, dO)]
     dQ, dK, dV, dG = psf.psf_causal_attn_bwd_learned(desc, *args)
@@ -55,10 +55,12 @@ def run_case(batch, heads, n, d, dv, p, r, b, dtype, local=psf.LOCAL_EXACT, per_
     res = {}
     for name, got, want in (("dQ", dQ, wQ), ("dK", dK, wK), ("dV", dV, wV)):
         res[name] = assert_close_scaled(got.float().cpu().numpy(), want, dtype, name + " " + what)
-    # the parameter gradient is accumulated and returned in fp32 whatever the storage type: what
-    # separates it from the oracle is the fp32 arithmetic of the row kernels
+    # the parameter gradient is accumulated and returned in fp32 whatever the storage type: on the
+    # general path what separates it from the oracle is the fp32 arithmetic of the row kernels; the
+    # MFMA kernels (path 3) form it from bf16 operands like every other product of that path
     for s in range(P.shape[0]):
-        res["dG%d" % s] = assert_close_scaled(dG[s].cpu().numpy(), wP[s], "f32", "dG set %d %s" % (s, what))
+        res["dG%d" % s] = assert_close_scaled(dG[s].cpu().numpy(), wP[s], "f32" if path == 2 else "bf16",
+                                              "dG set %d %s" % (s, what))
     print(what, {k2: ("%.2e" % v2[0], "%.2e" % v2[1]) for k2, v2 in res.items()})
     return desc, args, (dQ, dK, dV, dG)
 
@@ -91,6 +93,32 @@ def test_learned_backward_several_chunks_of_rows():
     # 6144 rows share one parameter set: the staging holds 4096 rows, so the sums over rows run
     # in two chunks that do not end on unit boundaries
     run_case(2, 3, 1024, 16, 16, 4, 8, 256, "f32", per_head=False)
+
+
+@pytest.mark.parametrize("batch,heads,n,r,b,per_head", [
+    (1, 2, 512, 32, 256, True),        # two blocks, a set per head, 16 hidden chunks of 32 per network
+    (2, 2, 512, 64, 256, False),       # one shared set: sums over four units; r = d = 64
+    (1, 1, 256, 64, 256, True),        # a single block: no cross-block term at all
+    (1, 3, 768, 32, 256, True),        # three blocks, a unit count the XCD-aware order does not apply to
+])
+def test_learned_backward_mfma(batch, heads, n, r, b, per_head):
+    run_case(batch, heads, n, 64, 64, 4, r, b, "bf16", per_head=per_head, path=3)
+
+
+def test_learned_backward_mfma_eight_units():
+    # eight units: the parameter kernel's XCD-aware workgroup order
+    run_case(4, 2, 256, 64, 64, 4, 32, 256, "bf16", per_head=True, path=3)
+
+
+def test_learned_backward_mfma_rows_only_and_repeat():
+    desc, args, (dQ, dK, dV, dG) = run_case(1, 2, 512, 64, 64, 4, 64, 256, "bf16", path=3)
+    rQ, rK, rV = psf.psf_causal_attn_bwd(desc, *args)
+    again = psf.psf_causal_attn_bwd_learned(desc, *args)
+    torch.cuda.synchronize()
+    for a, c in ((rQ, dQ), (rK, dK), (rV, dV)):
+        assert torch.equal(a, c)
+    for a, c in zip(again, (dQ, dK, dV, dG)):
+        assert torch.equal(a, c)               # fixed summation order: no atomics
 
 
 def test_rows_only_call_gives_the_same_row_gradients_and_repeats_bit_for_bit():
