@@ -123,7 +123,7 @@ def bwd_stage_flops(cfg, learned=False):
     return f
 
 
-def bwd_stage_flops_mfma(cfg):
+def bwd_stage_flops_mfma(cfg, learned=False):
     """The same count by stage of the MFMA backward kernels (d = dv, p = 4)."""
     U = cfg["batch"] * cfg["heads"]
     n, d, r, b = cfg["n"], cfg["d"], cfg["r"], cfg["b"]
@@ -131,13 +131,19 @@ def bwd_stage_flops_mfma(cfg):
     pairs = n * (b + 1) // 2
     cross = 2 * (n - b) * F * kc
     f = {
-        "forward_again": stage_flops(cfg)["total"],
+        "forward_again": stage_flops(cfg, learned=learned)["total"],
         "g_c_and_layouts": U * 4 * n * d,
         "mirror_states": U * cross,
         "in_block_and_dv": U * (pairs * 2 * 7 * d + cross),                  # 3 + 4 tile products per pair; phi'(K)^T R_l
         # dm(q), dm(k) with their S / Rc terms; projections again + transposed products
         "cross_block_and_sketch_gradient": U * (2 * cross + 8 * (n - b) * F + 16 * n * d * r),
     }
+    if learned:
+        # in place of Algorithm 1's reverse: the two networks of every row and side forward again,
+        # their pre-activations per hidden chunk once more, the products with the transposed
+        # matrices and the outer products of the parameter gradient (one forward's worth each)
+        nets = 2 * n * 2 * 2 * (d * 8 * r + 24 * r * r)
+        f["cross_block_and_sketch_gradient"] = U * (2 * cross + 8 * (n - b) * F + 4 * nets)
     f["total"] = sum(f.values())
     return f
 
@@ -193,7 +199,7 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
         for nm, ms in st.items():
             acc[nm] = acc.get(nm, 0.0) + ms / reps
     mfma = psf.bwd_kernel_path(desc) == 3
-    fl = bwd_stage_flops_mfma(cfg) if mfma else bwd_stage_flops(cfg, learned=args.learned)
+    fl = bwd_stage_flops_mfma(cfg, learned=args.learned) if mfma else bwd_stage_flops(cfg, learned=args.learned)
     dom = max(acc, key=lambda nm: acc[nm])
     achieved = fl[dom] / (acc[dom] * 1e-3) / 1e12
     peak = MFMA_BF16_PEAK_TFLOPS if mfma else FP32_VALU_PEAK_TFLOPS

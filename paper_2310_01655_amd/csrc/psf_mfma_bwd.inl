@@ -856,7 +856,7 @@ MfmaBwdWs carve_bwd(const Problem &pb, void *ws)
         w.sg.DAT = (bf16_t *)take(2 * rows * R * 2);
         w.sg.ST = (float *)take(2 * 4 * rows * 4);
         w.GB1 = (float *)take(rows / 256 * 2 * 2 * D * 4);
-        w.part = (float *)take(2 * (size_t)pb.units * pb.g_len * 4);
+        w.part = (float *)take(2 * (size_t)pb.units * learned_bwd_slices(pb) * pb.g_len * 4);
     }
     w.total = off;
     return w;
@@ -1012,7 +1012,8 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
             // through the networks: one side after the other, the staging buffers serve both
             const int sets = pb.per_head ? pb.heads : 1;
             const unsigned grid_rows = (unsigned)(rows / 256);
-            const unsigned grid_par = (unsigned)(pb.units * 2 * (R / 4 / 4));
+            const int per_unit = learned_bwd_slices(pb), slice_rows = pb.n / per_unit;
+            const unsigned grid_par = (unsigned)(pb.units * per_unit * 2 * (R / 4 / 4));
             hipLaunchKernelGGL((k_learned_bwd_prep<R>), dim3(4 * (R / 4), sets), dim3(kWg), 0, s, (const bf16_t *)G,
                                pb.g_len, w.LB);
             PSF_LAUNCH_CHECK();
@@ -1034,9 +1035,14 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
                                        f.LW, f.C1, f.LVp, w.LB, (const bf16_t *)G, pb.g_len, dx, w.sg, w.GB1, pb.n,
                                        pb.heads, ph);
                     PSF_LAUNCH_CHECK();
-                    hipLaunchKernelGGL((k_learned_bwd_params<R>), dim3(grid_par), dim3(kWg), 0, s, w.sg,
-                                       (const bf16_t *)G, pb.g_len, f.C1, w.GB1,
-                                       w.part + (size_t)side * pb.units * pb.g_len, pb.g_len, pb.n, pb.heads, ph);
+                    float *part = w.part + (size_t)side * pb.units * per_unit * pb.g_len;
+                    hipLaunchKernelGGL((k_learned_bwd_params<R, 0>), dim3(grid_par), dim3(kWg), 0, s, w.sg,
+                                       (const bf16_t *)G, pb.g_len, f.C1, w.GB1, part, pb.g_len, pb.n, slice_rows,
+                                       pb.heads, ph);
+                    PSF_LAUNCH_CHECK();
+                    hipLaunchKernelGGL((k_learned_bwd_params<R, 1>), dim3(grid_par), dim3(kWg), 0, s, w.sg,
+                                       (const bf16_t *)G, pb.g_len, f.C1, w.GB1, part, pb.g_len, pb.n, slice_rows,
+                                       pb.heads, ph);
                     PSF_LAUNCH_CHECK();
                 } else {
                     hipLaunchKernelGGL((k_learned_bwd_rows<R, false>), dim3(grid_rows), dim3(512), 0, s, xr, w.M8r, base,
@@ -1047,7 +1053,7 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
             }
             if (dG) {
                 hipLaunchKernelGGL(k_learned_bwd_reduce, dim3((unsigned)((pb.g_len + kWg - 1) / kWg), sets), dim3(kWg), 0, s,
-                                   w.part, dG, pb.g_len, pb.units, pb.heads, ph);
+                                   w.part, dG, pb.g_len, pb.units, learned_bwd_slices(pb), pb.heads, ph);
                 PSF_LAUNCH_CHECK();
             }
         } else if (!ls) {

@@ -26,13 +26,13 @@
 //                         the sums for dg1 / db1 per workgroup, and, for the parameter kernel, the
 //                         r-wide vectors of every row (x^, a2, df, da2 as bf16 rows and as
 //                         [tile of 32 rows][feature][32] tiles, mean / 1/sigma of h1, m1, m2).
-//   k_learned_bwd_params  workgroup = 4 waves = 4 hidden chunks of one network for all rows of one
-//                         unit, lane = hidden unit: recomputes a1, a3 of its 32 hidden units with the
-//                         operand roles swapped ("[row][hidden]" accumulators), forms h1, h^, da1, h3,
-//                         da3 there, and contracts over the rows on MFMA with the staged tiles as
-//                         the other operand; the sums over the whole unit stay in accumulators and
+//   k_learned_bwd_params  workgroup = 4 waves = 4 hidden chunks of one network for a slice of the rows
+//                         of one unit, lane = hidden unit: recomputes a1 (or a3) of its 32 hidden units
+//                         with the operand roles swapped ("[row][hidden]" accumulators), forms h1, h^,
+//                         da1 (h3, da3) there, and contracts over the rows on MFMA with the staged
+//                         tiles as the other operand; the sums over the slice stay in accumulators and
 //                         are written once, in the layout of the parameter blob.
-//   k_learned_bwd_reduce  adds the per-unit parts in a fixed order (no atomics: a repeated call
+//   k_learned_bwd_reduce  adds the per-slice parts in a fixed order (no atomics: a repeated call
 //                         returns the same bits).
 
 constexpr int kLbSlot = 16384;          // backward weight slot of one hidden chunk: three parts of 4 KB + padding
@@ -518,60 +518,73 @@ __global__ __launch_bounds__(512, 1) void k_learned_bwd_rows(const bf16_t *__res
     }
 }
 
-// Parameter sums of one unit (rows [u n, (u + 1) n)) for the 4 hidden chunks (one per wave) of
-// group cg of network net; lane = hidden unit 32 ch + x.  part: fp32 copy of the parameter blob
-// per unit, every entry of networks 0 and 1 written exactly once over the launch (g1 / b1 from
-// the row kernel's workgroup sums GB1 by the first wave of group 0).
-template <int R>
-__global__ __launch_bounds__(kWg, 1) void k_learned_bwd_params(LbStage sg, const bf16_t *__restrict__ P, size_t p_len,
+// Parameter sums over one slice (slice_rows consecutive rows of one unit, a multiple of 256) for
+// the 4 hidden chunks (one per wave) of group cg of network net; lane = hidden unit 32 ch + x.
+// HALF 0: layers 1 and 2 (W1, g2, b2, W2; its first workgroup of a network also sums g1 / b1 from
+// the row kernel's workgroup sums GB1), HALF 1: layers 3 and 4 (W3, W4): two sets of
+// accumulators that do not share a register budget.  part: fp32 copy of the parameter blob per
+// slice, every entry of networks 0 and 1 written exactly once over the launch.
+template <int R, int HALF>
+__global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const bf16_t *__restrict__ P, size_t p_len,
                                                               const float *__restrict__ C1,
                                                               const float *__restrict__ GB1, float *__restrict__ part,
-                                                              size_t blob_len, int n, int heads, int per_head)
+                                                              size_t blob_len, int n, int slice_rows, int heads,
+                                                              int per_head)
 {
     using Net = LearnedNet<R, 64>;
     constexpr int NCH = Net::NCH, HID = Net::HID, D = 64, OT = R / 32, KS = D / 16, RS = R / 16, DT = D / 32;
-    constexpr int CG = NCH / 4, JOBS = 2 * CG;             // workgroups per unit
+    constexpr int CG = NCH / 4, JOBS = 2 * CG;             // workgroups per slice
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int x = lane & 31, h = lane >> 5;
-    // the workgroups of one unit read the same staged rows: keep them on one XCD (one L2)
+    // the workgroups of one slice read the same staged rows: keep them on one XCD (one L2)
     int wg = blockIdx.x;
     const int total = gridDim.x;
     if ((total / JOBS) % 8 == 0) {
         const int xcd = wg & 7, idx = wg >> 3;
         wg = ((idx / JOBS) * 8 + xcd) * JOBS + idx % JOBS;
     }
-    const int u = wg / JOBS, net = (wg % JOBS) / CG, cg = wg % CG;
+    const int slice = wg / JOBS, net = (wg % JOBS) / CG, cg = wg % CG;
+    const int per_unit = n / slice_rows;
+    const int u = slice / per_unit;
+    const size_t first = (size_t)u * n + (size_t)(slice % per_unit) * slice_rows;
     const int ch = cg * 4 + wave, hid = 32 * ch + x;
     const int set = per_head ? u % heads : 0;
     const Net nt(P + (size_t)set * p_len + Net::offset_of(net, 4), 64);
 
     // this chunk's weights as B operands (lane = hidden unit, 8 consecutive contraction indices)
-    bf16x8 w1f[KS], w2f[RS], w3f[RS], w4f[RS];
+    bf16x8 wa[HALF == 0 ? KS : RS], wb[RS];                // HALF 0: g1 . W1, W2;  HALF 1: W3, W4
+    if constexpr (HALF == 0) {
 #pragma unroll
-    for (int s = 0; s < KS; ++s)
+        for (int s = 0; s < KS; ++s)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int k = 16 * s + 8 * h + e;
-            w1f[s][e] = (__bf16)(bf16_to_f32(nt.g1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + hid]));
-        }
+            for (int e = 0; e < 8; ++e) {
+                const int k = 16 * s + 8 * h + e;
+                wa[s][e] = (__bf16)(bf16_to_f32(nt.g1[k]) * bf16_to_f32(nt.W1[(size_t)k * HID + hid]));
+            }
+    }
 #pragma unroll
     for (int t = 0; t < RS; ++t)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int k = 16 * t + 8 * h + e;
-            w2f[t][e] = __builtin_bit_cast(__bf16, nt.W2[(size_t)hid * R + k]);
-            w3f[t][e] = __builtin_bit_cast(__bf16, nt.W3[(size_t)k * HID + hid]);
-            w4f[t][e] = __builtin_bit_cast(__bf16, nt.W4[(size_t)hid * R + k]);
+            if constexpr (HALF == 0) {
+                wb[t][e] = __builtin_bit_cast(__bf16, nt.W2[(size_t)hid * R + k]);
+            } else {
+                wa[t][e] = __builtin_bit_cast(__bf16, nt.W3[(size_t)k * HID + hid]);
+                wb[t][e] = __builtin_bit_cast(__bf16, nt.W4[(size_t)hid * R + k]);
+            }
         }
     const float c1 = C1[(((size_t)set * 2 + net) * NCH + ch) * 32 + x];
     const float g2h = bf16_to_f32(nt.g2[hid]);
 
-    f32x16 aW1[DT], aW2[OT], aW3[OT], aW4[OT];
+    // HALF 0: accA = dW1 (DT tiles), accB = dW2;  HALF 1: accA = dW3, accB = dW4
+    constexpr int NA = HALF == 0 ? DT : OT;
+    f32x16 accA[NA], accB[OT];
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) aW1[dt] = f32x16{0};
+    for (int i = 0; i < NA; ++i) accA[i] = f32x16{0};
 #pragma unroll
-    for (int ot = 0; ot < OT; ++ot) aW2[ot] = aW3[ot] = aW4[ot] = f32x16{0};
+    for (int ot = 0; ot < OT; ++ot) accB[ot] = f32x16{0};
     float sg2 = 0.f, sb2 = 0.f, sda1 = 0.f, sda2[OT];
 #pragma unroll
     for (int ot = 0; ot < OT; ++ot) sda2[ot] = 0.f;
@@ -591,121 +604,142 @@ __global__ __launch_bounds__(kWg, 1) void k_learned_bwd_params(LbStage sg, const
     };
 
 #pragma unroll 1
-    for (int tl = 0; tl < n / 32; ++tl) {
-        const size_t r0 = (size_t)u * n + 32 * (size_t)tl, tile = r0 / 32, rw = r0 + x;
+    for (int tl = 0; tl < slice_rows / 32; ++tl) {
+        const size_t r0 = first + 32 * (size_t)tl, tile = r0 / 32, rw = r0 + x;
         // register v of a "[row][hidden]" accumulator: row 8 (v / 4) + 4 h + v % 4 of the tile
-        // ---- layers 1 and 2 ----
-        f32x16 a1, du2 = {0};
+        if constexpr (HALF == 0) {
+            f32x16 a1, du2 = {0};
 #pragma unroll
-        for (int v = 0; v < 16; ++v) a1[v] = c1;
+            for (int v = 0; v < 16; ++v) a1[v] = c1;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) a1 = mfma32(*(const bf16x8 *)&sg.XnR[rw * D + 16 * s + 8 * h], w1f[s], a1);
+            for (int s = 0; s < KS; ++s) a1 = mfma32(*(const bf16x8 *)&sg.XnR[rw * D + 16 * s + 8 * h], wa[s], a1);
 #pragma unroll
-        for (int t = 0; t < RS; ++t) du2 = mfma32(*(const bf16x8 *)&DAR[rw * R + 16 * t + 8 * h], w2f[t], du2);
-        f32x16 hh;
+            for (int t = 0; t < RS; ++t) du2 = mfma32(*(const bf16x8 *)&DAR[rw * R + 16 * t + 8 * h], wb[t], du2);
+            f32x16 hh;
 #pragma unroll
-        for (int g4 = 0; g4 < 4; ++g4) {
-            const f32x4 mu = *(const f32x4 *)&ST[0 * sg.rows + r0 + 8 * g4 + 4 * h];
-            const f32x4 iv = *(const f32x4 *)&ST[1 * sg.rows + r0 + 8 * g4 + 4 * h];
-            const f32x4 m1 = *(const f32x4 *)&ST[2 * sg.rows + r0 + 8 * g4 + 4 * h];
-            const f32x4 m2 = *(const f32x4 *)&ST[3 * sg.rows + r0 + 8 * g4 + 4 * h];
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const f32x4 mu = *(const f32x4 *)&ST[0 * sg.rows + r0 + 8 * g4 + 4 * h];
+                const f32x4 iv = *(const f32x4 *)&ST[1 * sg.rows + r0 + 8 * g4 + 4 * h];
+                const f32x4 m1 = *(const f32x4 *)&ST[2 * sg.rows + r0 + 8 * g4 + 4 * h];
+                const f32x4 m2 = *(const f32x4 *)&ST[3 * sg.rows + r0 + 8 * g4 + 4 * h];
 #pragma unroll
-            for (int j2 = 0; j2 < 4; ++j2) {
-                const int v = 4 * g4 + j2;
+                for (int j2 = 0; j2 < 4; ++j2) {
+                    const int v = 4 * g4 + j2;
+                    float y, dy;
+                    gelu_and_slope(a1[v], y, dy);
+                    const float hv = (y - mu[j2]) * iv[j2];
+                    sg2 += du2[v] * hv;
+                    sb2 += du2[v];
+                    const float d = iv[j2] * (g2h * du2[v] - m1[j2] - hv * m2[j2]) * dy;
+                    sda1 += d;
+                    hh[v] = hv;
+                    a1[v] = d;                              // da1
+                }
+            }
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const bf16x8 da1f = cvt8_from16(a1, 8 * s2), hhf = cvt8_from16(hh, 8 * s2);
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) accA[dt] = mfma32(frag_t(sg.XnT, tile, D, 32 * dt + x, s2), da1f, accA[dt]);
+#pragma unroll
+                for (int ot = 0; ot < OT; ++ot) {
+                    const bf16x8 dat = frag_t(DAT, tile, R, 32 * ot + x, s2);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) sda2[ot] += (float)dat[e];
+                    accB[ot] = mfma32(hhf, dat, accB[ot]);
+                }
+            }
+        } else {
+            f32x16 a3 = {0}, dh3 = {0};
+#pragma unroll
+            for (int t = 0; t < RS; ++t) {
+                a3 = mfma32(*(const bf16x8 *)&A2R[rw * R + 16 * t + 8 * h], wa[t], a3);
+                dh3 = mfma32(*(const bf16x8 *)&DOR[rw * R + 16 * t + 8 * h], wb[t], dh3);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
                 float y, dy;
-                gelu_and_slope(a1[v], y, dy);
-                const float hv = (y - mu[j2]) * iv[j2];
-                sg2 += du2[v] * hv;
-                sb2 += du2[v];
-                const float d = iv[j2] * (g2h * du2[v] - m1[j2] - hv * m2[j2]) * dy;
-                sda1 += d;
-                hh[v] = hv;
-                a1[v] = d;                                  // da1
+                gelu_and_slope(a3[v], y, dy);
+                a3[v] = y;                                  // h3
+                dh3[v] *= dy;                               // da3
             }
-        }
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            const bf16x8 da1f = cvt8_from16(a1, 8 * s2), hhf = cvt8_from16(hh, 8 * s2);
+            for (int s2 = 0; s2 < 2; ++s2) {
+                const bf16x8 h3f = cvt8_from16(a3, 8 * s2), da3f = cvt8_from16(dh3, 8 * s2);
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) aW1[dt] = mfma32(frag_t(sg.XnT, tile, D, 32 * dt + x, s2), da1f, aW1[dt]);
-#pragma unroll
-            for (int ot = 0; ot < OT; ++ot) {
-                const bf16x8 dat = frag_t(DAT, tile, R, 32 * ot + x, s2);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) sda2[ot] += (float)dat[e];
-                aW2[ot] = mfma32(hhf, dat, aW2[ot]);
-            }
-        }
-        // ---- layers 3 and 4 ----
-        f32x16 a3 = {0}, dh3 = {0};
-#pragma unroll
-        for (int t = 0; t < RS; ++t) {
-            a3 = mfma32(*(const bf16x8 *)&A2R[rw * R + 16 * t + 8 * h], w3f[t], a3);
-            dh3 = mfma32(*(const bf16x8 *)&DOR[rw * R + 16 * t + 8 * h], w4f[t], dh3);
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            float y, dy;
-            gelu_and_slope(a3[v], y, dy);
-            a3[v] = y;                                      // h3
-            dh3[v] *= dy;                                   // da3
-        }
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            const bf16x8 h3f = cvt8_from16(a3, 8 * s2), da3f = cvt8_from16(dh3, 8 * s2);
-#pragma unroll
-            for (int ot = 0; ot < OT; ++ot) {
-                aW3[ot] = mfma32(frag_t(A2T, tile, R, 32 * ot + x, s2), da3f, aW3[ot]);
-                aW4[ot] = mfma32(h3f, frag_t(DOT, tile, R, 32 * ot + x, s2), aW4[ot]);
+                for (int ot = 0; ot < OT; ++ot) {
+                    accA[ot] = mfma32(frag_t(A2T, tile, R, 32 * ot + x, s2), da3f, accA[ot]);
+                    accB[ot] = mfma32(h3f, frag_t(DOT, tile, R, 32 * ot + x, s2), accB[ot]);
+                }
             }
         }
     }
 
-    // ---- write this chunk's part of the unit's sums (blob layout, fp32) ----
+    // ---- write this chunk's part of the slice's sums (blob layout, fp32) ----
     // register v of an accumulator: row i = 8 (v / 4) + 4 h + v % 4, lane x = column
-    float *out = part + (size_t)u * blob_len + Net::offset_of(net, 4);
+    float *out = part + (size_t)slice * blob_len + Net::offset_of(net, 4);
     float *oW1 = out + 2 * D, *og2 = oW1 + (size_t)D * HID, *ob2 = og2 + HID, *oW2 = ob2 + HID;
     float *oW3 = oW2 + (size_t)HID * R, *oW4 = oW3 + (size_t)R * HID;
-    sda1 += __shfl_xor(sda1, 32);
-    sg2 += __shfl_xor(sg2, 32);
-    sb2 += __shfl_xor(sb2, 32);
-    if (h == 0) {
-        og2[hid] = sg2;
-        ob2[hid] = sb2;
-    }
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int k = 32 * dt + 8 * (v / 4) + 4 * h + v % 4;            // dW1[k][hid], u1 = g1 x^ + b1
-            oW1[(size_t)k * HID + hid] = bf16_to_f32(nt.g1[k]) * aW1[dt][v] + bf16_to_f32(nt.b1[k]) * sda1;
+    if constexpr (HALF == 0) {
+        sda1 += __shfl_xor(sda1, 32);
+        sg2 += __shfl_xor(sg2, 32);
+        sb2 += __shfl_xor(sb2, 32);
+        if (h == 0) {
+            og2[hid] = sg2;
+            ob2[hid] = sb2;
         }
 #pragma unroll
-    for (int ot = 0; ot < OT; ++ot) {
-        const float s2all = sda2[ot] + __shfl_xor(sda2[ot], 32);
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int i = 8 * (v / 4) + 4 * h + v % 4, hr = 32 * ch + i;
-            // dW2[hr][o], u2 = g2 h^ + b2;  dW4[hr][o];  dW3[f][hid], f = 32 ot + i
-            oW2[(size_t)hr * R + 32 * ot + x] = bf16_to_f32(nt.g2[hr]) * aW2[ot][v] + bf16_to_f32(nt.b2[hr]) * s2all;
-            oW4[(size_t)hr * R + 32 * ot + x] = aW4[ot][v];
-            oW3[(size_t)(32 * ot + i) * HID + hid] = aW3[ot][v];
+            for (int v = 0; v < 16; ++v) {
+                const int k = 32 * dt + 8 * (v / 4) + 4 * h + v % 4;        // dW1[k][hid], u1 = g1 x^ + b1
+                oW1[(size_t)k * HID + hid] = bf16_to_f32(nt.g1[k]) * accA[dt][v] + bf16_to_f32(nt.b1[k]) * sda1;
+            }
+#pragma unroll
+        for (int ot = 0; ot < OT; ++ot) {
+            const float s2all = sda2[ot] + __shfl_xor(sda2[ot], 32);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int hr = 32 * ch + 8 * (v / 4) + 4 * h + v % 4;       // dW2[hr][o], u2 = g2 h^ + b2
+                oW2[(size_t)hr * R + 32 * ot + x] = bf16_to_f32(nt.g2[hr]) * accB[ot][v] + bf16_to_f32(nt.b2[hr]) * s2all;
+            }
         }
-    }
-    if (cg == 0 && wave == 0) {
-        // dg1, db1: the row kernel's workgroup sums over this unit, in order
-        const size_t wg0 = (size_t)u * n / 256;
-        for (int idx = lane; idx < 2 * D; idx += 64) {
-            float sum = 0.f;
-            for (int k = 0; k < n / 256; ++k) sum += GB1[((wg0 + k) * 2 + net) * 2 * D + idx];
-            out[idx] = sum;
+        if (cg == 0 && wave == 0) {
+            // dg1, db1: the row kernel's workgroup sums over this slice, in order
+            const size_t wg0 = first / 256;
+            for (int idx = lane; idx < 2 * D; idx += 64) {
+                float sum = 0.f;
+                for (int k = 0; k < slice_rows / 256; ++k) sum += GB1[((wg0 + k) * 2 + net) * 2 * D + idx];
+                out[idx] = sum;
+            }
         }
+    } else {
+#pragma unroll
+        for (int ot = 0; ot < OT; ++ot)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = 8 * (v / 4) + 4 * h + v % 4;
+                oW4[(size_t)(32 * ch + i) * R + 32 * ot + x] = accB[ot][v];      // dW4[hidden][o]
+                oW3[(size_t)(32 * ot + i) * HID + hid] = accA[ot][v];            // dW3[f][hid]
+            }
     }
 }
 
-// dG[set][idx] = sum over the sides (query rows, key rows) and the units of the set, in order.
+// Slices per unit for the parameter kernel: enough workgroups to fill the GPU several times over,
+// slices of at least 512 rows that are multiples of 256.
+int learned_bwd_slices(const Problem &pb)
+{
+    const int jobs = 2 * (pb.r / 4 / 4);
+    int k = 1;
+    while ((long long)pb.units * k * jobs < 2048 && pb.n / (2 * k) >= 512 && pb.n % (2 * k * 256) == 0) k *= 2;
+    return k;
+}
+
+// dG[set][idx] = sum over the sides (query rows, key rows) and the slices of the units of the
+// set, in order.  part: [side][unit][slice of the unit][blob].
 __global__ __launch_bounds__(kWg) void k_learned_bwd_reduce(const float *__restrict__ part, float *__restrict__ dG,
-                                                            size_t blob_len, int units, int heads, int per_head)
+                                                            size_t blob_len, int units, int per_unit, int heads,
+                                                            int per_head)
 {
     const size_t idx = (size_t)blockIdx.x * kWg + threadIdx.x;
     const int set = blockIdx.y;
@@ -713,7 +747,9 @@ __global__ __launch_bounds__(kWg) void k_learned_bwd_reduce(const float *__restr
     const int step = per_head ? heads : 1;
     float sum = 0.f;
     for (int side = 0; side < 2; ++side)
-        for (int u = per_head ? set : 0; u < units; u += step) sum += part[((size_t)side * units + u) * blob_len + idx];
+        for (int u = per_head ? set : 0; u < units; u += step)
+            for (int k = 0; k < per_unit; ++k)
+                sum += part[(((size_t)side * units + u) * per_unit + k) * blob_len + idx];
     dG[(size_t)set * blob_len + idx] = sum;
 }
 
