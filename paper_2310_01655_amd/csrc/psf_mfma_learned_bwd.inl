@@ -603,18 +603,64 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
         return f;
     };
 
-#pragma unroll 1
-    for (int tl = 0; tl < slice_rows / 32; ++tl) {
+    // operands of one tile of 32 rows: row fragments (lane = row) of two staged vectors and the
+    // transposed tiles (lane = feature) of two; the next tile's are loaded under the current one's arithmetic
+    struct Tile {
+        bf16x8 ra[HALF == 0 ? KS : RS], rb[RS];            // HALF 0: x^, da2;  HALF 1: a2, df
+        bf16x8 ta[NA][2], tb[OT][2];                       // HALF 0: x^ tiles, da2 tiles;  HALF 1: a2 tiles, df tiles
+    };
+    // (HALF 0 is short of registers: there only the row fragments, which the tile's first products
+    // wait for, come a tile ahead; the transposed tiles are asked for at the top of their own tile
+    // and used at its end)
+    auto load_tile = [&](int tl, Tile &o, bool rows_part, bool tiles_part) {
         const size_t r0 = first + 32 * (size_t)tl, tile = r0 / 32, rw = r0 + x;
+        if constexpr (HALF == 0) {
+            if (rows_part) {
+#pragma unroll
+                for (int s = 0; s < KS; ++s) o.ra[s] = *(const bf16x8 *)&sg.XnR[rw * D + 16 * s + 8 * h];
+#pragma unroll
+                for (int t = 0; t < RS; ++t) o.rb[t] = *(const bf16x8 *)&DAR[rw * R + 16 * t + 8 * h];
+            }
+            if (tiles_part)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) o.ta[dt][s2] = frag_t(sg.XnT, tile, D, 32 * dt + x, s2);
+#pragma unroll
+                for (int ot = 0; ot < OT; ++ot) o.tb[ot][s2] = frag_t(DAT, tile, R, 32 * ot + x, s2);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < RS; ++t) {
+                o.ra[t] = *(const bf16x8 *)&A2R[rw * R + 16 * t + 8 * h];
+                o.rb[t] = *(const bf16x8 *)&DOR[rw * R + 16 * t + 8 * h];
+            }
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int ot = 0; ot < OT; ++ot) {
+                    o.ta[ot][s2] = frag_t(A2T, tile, R, 32 * ot + x, s2);
+                    o.tb[ot][s2] = frag_t(DOT, tile, R, 32 * ot + x, s2);
+                }
+        }
+    };
+    Tile cur, nxt;
+    const int n_tiles = slice_rows / 32;
+    load_tile(0, cur, true, HALF == 1);
+#pragma unroll 1
+    for (int tl = 0; tl < n_tiles; ++tl) {
+        const size_t r0 = first + 32 * (size_t)tl;
+        if constexpr (HALF == 0) load_tile(tl, cur, false, true);
+        if (tl + 1 < n_tiles) load_tile(tl + 1, nxt, true, HALF == 1);
         // register v of a "[row][hidden]" accumulator: row 8 (v / 4) + 4 h + v % 4 of the tile
         if constexpr (HALF == 0) {
             f32x16 a1, du2 = {0};
 #pragma unroll
             for (int v = 0; v < 16; ++v) a1[v] = c1;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) a1 = mfma32(*(const bf16x8 *)&sg.XnR[rw * D + 16 * s + 8 * h], wa[s], a1);
+            for (int s = 0; s < KS; ++s) a1 = mfma32(cur.ra[s], wa[s], a1);
 #pragma unroll
-            for (int t = 0; t < RS; ++t) du2 = mfma32(*(const bf16x8 *)&DAR[rw * R + 16 * t + 8 * h], wb[t], du2);
+            for (int t = 0; t < RS; ++t) du2 = mfma32(cur.rb[t], wb[t], du2);
             f32x16 hh;
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
@@ -640,21 +686,20 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
             for (int s2 = 0; s2 < 2; ++s2) {
                 const bf16x8 da1f = cvt8_from16(a1, 8 * s2), hhf = cvt8_from16(hh, 8 * s2);
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) accA[dt] = mfma32(frag_t(sg.XnT, tile, D, 32 * dt + x, s2), da1f, accA[dt]);
+                for (int dt = 0; dt < DT; ++dt) accA[dt] = mfma32(cur.ta[dt][s2], da1f, accA[dt]);
 #pragma unroll
                 for (int ot = 0; ot < OT; ++ot) {
-                    const bf16x8 dat = frag_t(DAT, tile, R, 32 * ot + x, s2);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) sda2[ot] += (float)dat[e];
-                    accB[ot] = mfma32(hhf, dat, accB[ot]);
+                    for (int e = 0; e < 8; ++e) sda2[ot] += (float)cur.tb[ot][s2][e];
+                    accB[ot] = mfma32(hhf, cur.tb[ot][s2], accB[ot]);
                 }
             }
         } else {
             f32x16 a3 = {0}, dh3 = {0};
 #pragma unroll
             for (int t = 0; t < RS; ++t) {
-                a3 = mfma32(*(const bf16x8 *)&A2R[rw * R + 16 * t + 8 * h], wa[t], a3);
-                dh3 = mfma32(*(const bf16x8 *)&DOR[rw * R + 16 * t + 8 * h], wb[t], dh3);
+                a3 = mfma32(cur.ra[t], wa[t], a3);
+                dh3 = mfma32(cur.rb[t], wb[t], dh3);
             }
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
@@ -668,10 +713,18 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
                 const bf16x8 h3f = cvt8_from16(a3, 8 * s2), da3f = cvt8_from16(dh3, 8 * s2);
 #pragma unroll
                 for (int ot = 0; ot < OT; ++ot) {
-                    accA[ot] = mfma32(frag_t(A2T, tile, R, 32 * ot + x, s2), da3f, accA[ot]);
-                    accB[ot] = mfma32(h3f, frag_t(DOT, tile, R, 32 * ot + x, s2), accB[ot]);
+                    accA[ot] = mfma32(cur.ta[ot][s2], da3f, accA[ot]);
+                    accB[ot] = mfma32(h3f, cur.tb[ot][s2], accB[ot]);
                 }
             }
+        }
+        if constexpr (HALF == 0) {
+#pragma unroll
+            for (int s = 0; s < KS; ++s) cur.ra[s] = nxt.ra[s];
+#pragma unroll
+            for (int t = 0; t < RS; ++t) cur.rb[t] = nxt.rb[t];
+        } else {
+            cur = nxt;
         }
     }
 
