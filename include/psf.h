@@ -216,11 +216,12 @@ psf_status psf_noncausal_attn_fwd_timed(const psf_desc *desc, const void *Q, con
  * descriptor check admits (fp32 arithmetic), Gaussian or learned sketches (with learned ones G
  * holds the networks' parameters and this call treats them as constants; see
  * psf_causal_attn_bwd_learned).  PSF_FEAT_EXACT returns PSF_ERR_UNSUPPORTED.
- * Kernels: bf16 storage with d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0, random sketches and
- * PSF_LOCAL_EXACT (or PSF_LOCAL_SKETCH with r = 64) runs on MFMA (psf_bwd_kernel_path == 3;
- * bf16 operands, fp32 accumulation, g and
- * the in-block weights rounded to bf16 like the forward pass rounds its weights); everything
- * else runs the general fp32 kernels (== 2).  -1: invalid descriptor or unsupported.
+ * Kernels: bf16 storage with d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0 and PSF_LOCAL_EXACT
+ * (random or learned sketches) or PSF_LOCAL_SKETCH (random sketches, r = 64) runs on MFMA
+ * (psf_bwd_kernel_path == 3; bf16 operands, fp32 accumulation, g and
+ * the in-block weights rounded to bf16 like the forward pass rounds its weights; the learned
+ * networks' layers take fp16 activations like the forward kernel, their gradients bf16);
+ * everything else runs the general fp32 kernels (== 2).  -1: invalid descriptor or unsupported.
  * The _timed variant reports per-stage milliseconds like psf_causal_attn_fwd_timed, stage
  * names via psf_stage_name(psf_bwd_kernel_path(desc), i).
  */
@@ -245,9 +246,10 @@ psf_status psf_causal_attn_bwd_timed(const psf_desc *desc, const void *Q, const 
  *   dG [sets, psf_learned_len(d, r, p)] fp32 (device): overwritten, in G's parameter order;
  *   sets = heads when desc->sketch_per_head, else 1.  Everything else as for psf_causal_attn_bwd;
  *   workspace: psf_bwd_workspace_bytes(desc) (it includes the staging of the parameter sums).
- * The sums over rows run in a fixed order (no atomics).  General fp32 kernels
- * (psf_bwd_kernel_path == 2).  PSF_ERR_UNSUPPORTED unless desc->learned (and p > 2);
- * PSF_ERR_NULL without dG.
+ * The sums over rows run in a fixed order (no atomics: a repeated call returns the same bits).
+ * Kernels as psf_bwd_kernel_path says: MFMA (== 3: the sums are then formed from bf16 operands,
+ * fp32 accumulation) or the general fp32 ones (== 2).  PSF_ERR_UNSUPPORTED unless desc->learned
+ * (and p > 2); PSF_ERR_NULL without dG.
  */
 psf_status psf_causal_attn_bwd_learned(const psf_desc *desc, const void *Q, const void *K, const void *V,
                                        const void *G, const void *dO, void *dQ, void *dK, void *dV,
@@ -263,8 +265,9 @@ psf_status psf_causal_attn_bwd_learned(const psf_desc *desc, const void *Q, cons
  * psf_causal_attn_bwd_saved takes that buffer untouched since, the same Q, K, V, G and the O the
  * forward call wrote, and returns the same gradients as psf_causal_attn_bwd (bit for bit).
  * workspace: psf_bwd_workspace_bytes(desc) as for psf_causal_attn_bwd.  Available where
- * psf_bwd_kernel_path(desc) == 3; elsewhere psf_fwd_save_bytes is 0 and both calls return
- * PSF_ERR_UNSUPPORTED (use psf_causal_attn_fwd / psf_causal_attn_bwd there).
+ * psf_bwd_kernel_path(desc) == 3 with random sketches; elsewhere (learned sketches included)
+ * psf_fwd_save_bytes is 0 and both calls return PSF_ERR_UNSUPPORTED (use psf_causal_attn_fwd /
+ * psf_causal_attn_bwd there).
  */
 size_t psf_fwd_save_bytes(const psf_desc *desc);
 psf_status psf_causal_attn_fwd_save(const psf_desc *desc, const void *Q, const void *K, const void *V,
