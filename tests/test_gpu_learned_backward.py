@@ -121,6 +121,59 @@ def test_learned_backward_mfma_rows_only_and_repeat():
         assert torch.equal(a, c)               # fixed summation order: no atomics
 
 
+def test_learned_backward_mfma_config3_size_against_the_oracle_on_a_prefix():
+    """The launch configuration `bench.py --pass bwd --learned` times (config 3's shapes: 2 x 12
+    units of 32768 tokens, a parameter set per head).  dL/dO is zero from row T = 2048 on, so by
+    causality the gradient is that of the T-token prefix problem: rows below T of dQ, dK, dV and
+    the parameter gradient equal the oracle's on the prefix (two parameter sets = four units are
+    checked), every row from T on is exactly zero.  A second call with 2 dL/dO returns twice the
+    first (every step of the reverse pass is linear in dL/dO), and <dV, V> = <dO, O> per unit
+    (the output is linear in V)."""
+    cfg, q, k, v, _ = inputs.make_config(3)
+    B, H, n, d, r, b = cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["r"], cfg["b"]
+    T = 2 * b
+    P = inputs.make_learned_params(H, d, r, 4, per_head=True, seed=3, dtype="bf16")
+    dO = inputs.make_dout(B, H, n, d, seed=1003, dtype="bf16")
+    dO[:, :, T:] = 0
+    desc = psf.make_desc(B, H, n, d, 4, r, b, "bf16", per_head=True, learned=True)
+    assert psf.bwd_kernel_path(desc) == 3
+    dev = torch.device("cuda:0")
+    qd, kd, vd, Pd, dOd = (x.to(dev) for x in (q, k, v, P, dO))
+    ws = psf.alloc_bwd_workspace(desc, dev)
+    dQ, dK, dV, dG = psf.psf_causal_attn_bwd_learned(desc, qd, kd, vd, Pd, dOd, workspace=ws)
+    dQ2, dK2, dV2, dG2 = psf.psf_causal_attn_bwd_learned(desc, qd, kd, vd, Pd, 2 * dOd, workspace=ws)
+    O = psf.psf_causal_attn_fwd(desc, qd, kd, vd, Pd)
+    torch.cuda.synchronize()
+    for a in (dQ, dK, dV):
+        assert torch.isfinite(a.float()).all()
+        assert not a[:, :, T:].any()
+    for a, c in ((dQ, dQ2), (dK, dK2), (dV, dV2), (dG, dG2)):
+        assert torch.allclose(2 * a.float(), c.float(), rtol=1e-5, atol=0)
+    f = lambda t: t.float()
+    lv, lo = (f(dV) * f(vd)).sum((-1, -2)), (f(dOd) * f(O)).sum((-1, -2))
+    scale_v = (f(dOd) * f(O)).sum(-1).abs().sum(-1)
+    assert ((lv - lo).abs() <= 2e-2 * scale_v).all(), ((lv - lo).abs() / scale_v).max()
+    sets = [0, 7]
+    units = [(bi, h) for h in sets for bi in range(B)]
+
+    def one(u):
+        bi, h = u
+        return oracle.attn_bwd_learned(as_f64(q[bi, h, :T]), as_f64(k[bi, h, :T]), as_f64(v[bi, h, :T]), as_f64(P[h]),
+                                       as_f64(dO[bi, h, :T]), 4, r, b, local=oracle.LOCAL_EXACT)
+
+    with ThreadPoolExecutor(len(units)) as ex:
+        parts = list(ex.map(one, units))
+    wP = {h: 0.0 for h in sets}
+    for (bi, h), (wq, wk, wv, wp) in zip(units, parts):
+        wP[h] = wP[h] + wp
+        print("config 3 learned bwd", (bi, h),
+              assert_close_scaled(dQ[bi, h, :T].float().cpu().numpy(), wq, "bf16", "dQ"),
+              assert_close_scaled(dK[bi, h, :T].float().cpu().numpy(), wk, "bf16", "dK"),
+              assert_close_scaled(dV[bi, h, :T].float().cpu().numpy(), wv, "bf16", "dV"))
+    for h in sets:
+        print("set", h, assert_close_scaled(dG[h].cpu().numpy(), wP[h], "bf16", "dG set %d" % h))
+
+
 def test_rows_only_call_gives_the_same_row_gradients_and_repeats_bit_for_bit():
     desc, args, (dQ, dK, dV, dG) = run_case(1, 2, 64, 16, 16, 4, 8, 16, "f32")
     rQ, rK, rV = psf.psf_causal_attn_bwd(desc, *args)
