@@ -185,6 +185,32 @@ def test_rows_only_call_gives_the_same_row_gradients_and_repeats_bit_for_bit():
         assert torch.equal(a, c)               # fixed summation order: no atomics
 
 
+@pytest.mark.parametrize("dtype,d,r,b,n", [("f32", 16, 8, 16, 64), ("bf16", 64, 32, 256, 512)])
+def test_autograd_function_trains_the_learned_sketches(dtype, d, r, b, n):
+    # torch.autograd glue (marshalling only): with parameters that require a gradient the
+    # backward is psf_causal_attn_bwd_learned (general kernels / MFMA kernels), bit for bit
+    from paper_2310_01655_amd.autograd import causal_polysketch_attention
+    batch, heads, p = 1, 2, 4
+    q, k, v = inputs.make_qkv(batch, heads, n, d, seed=61, dtype=dtype)
+    P = inputs.make_learned_params(heads, d, r, p, per_head=True, seed=3, dtype=dtype)
+    W = inputs.make_dout(batch, heads, n, d, seed=62, dtype=dtype)
+    qd, kd, vd, Pd = (t.cuda().requires_grad_(True) for t in (q, k, v, P))
+    O = causal_polysketch_attention(qd, kd, vd, Pd, p, r, b, per_head=True, learned=True)
+    (O.float() * W.cuda().float()).sum().backward()
+    desc = psf.make_desc(batch, heads, n, d, p, r, b, dtype, per_head=True, learned=True)
+    dQ, dK, dV, dG = psf.psf_causal_attn_bwd_learned(desc, qd.detach(), kd.detach(), vd.detach(), Pd.detach(),
+                                                     W.cuda())
+    torch.cuda.synchronize()
+    for got, want in ((qd.grad, dQ), (kd.grad, dK), (vd.grad, dV), (Pd.grad, dG.to(Pd.dtype))):
+        assert torch.equal(got, want)
+    # constants: no parameter gradient is asked for, the rows-only call runs
+    q2, k2, v2 = (t.cuda().requires_grad_(True) for t in (q, k, v))
+    O2 = causal_polysketch_attention(q2, k2, v2, P.cuda(), p, r, b, per_head=True, learned=True)
+    (O2.float() * W.cuda().float()).sum().backward()
+    torch.cuda.synchronize()
+    assert torch.equal(q2.grad, dQ) and torch.equal(k2.grad, dK) and torch.equal(v2.grad, dV)
+
+
 def test_parameter_gradient_is_refused_for_gaussian_sketches():
     desc = psf.make_desc(1, 1, 64, 16, 4, 8, 16, "f32")
     q, k, v = inputs.make_qkv(1, 1, 64, 16, seed=1, dtype="f32")
