@@ -1211,6 +1211,25 @@ psf_status bwd_launch(const Problem &pb, const void *Q, const void *K, const voi
 
 }  // namespace
 
+// Algorithm 1's reverse alone: dX = direct + J_m(X)^T dM for rows of X (storage type of pb), with
+// dM [rows][mcols] and direct [rows][d] fp32.
+psf_status general_sketch_bwd(const Problem &pb, const void *X, const void *G, const float *dM,
+                              const float *direct, void *dX, hipStream_t s)
+{
+    const size_t rows = (size_t)pb.units * pb.n;
+    const int grid = (int)(rows < 65536 ? rows : 65536);
+    if (pb.bf16)
+        hipLaunchKernelGGL(bwd_sketch_kernel<bf16_t>, dim3(grid), dim3(kThreads), 0, s, (const bf16_t *)X,
+                           (const bf16_t *)G, dM, direct, (bf16_t *)dX, (long long)rows, pb.n, pb.heads,
+                           pb.per_head ? 1 : 0, pb.d, pb.r, pb.p, pb.g_len);
+    else
+        hipLaunchKernelGGL(bwd_sketch_kernel<float>, dim3(grid), dim3(kThreads), 0, s, (const float *)X,
+                           (const float *)G, dM, direct, (float *)dX, (long long)rows, pb.n, pb.heads,
+                           pb.per_head ? 1 : 0, pb.d, pb.r, pb.p, pb.g_len);
+    PSF_LAUNCH_CHECK();
+    return PSF_OK;
+}
+
 bool general_bwd_supported(const Problem &pb)
 {
     // explicit x^{(x)p} features have no backward here; the feature staging assumes F and a

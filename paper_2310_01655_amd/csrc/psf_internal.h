@@ -61,6 +61,9 @@ psf_status general_attn_bwd(const Problem &pb, const void *Q, const void *K, con
                             const void *G, const void *dO, void *dQ, void *dK, void *dV, void *ws,
                             hipStream_t s, StageTimer *tm, float *dG = nullptr);
 
+psf_status general_sketch_bwd(const Problem &pb, const void *X, const void *G, const float *dM,
+                              const float *direct, void *dX, hipStream_t s);
+
 // Backward pass on MFMA (bf16, d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0; random sketches
 // with either in-block rule (Section 3.1's for r = 64), learned sketches with exact in-block weights).
 bool mfma_bwd_supported(const Problem &pb);

@@ -2911,21 +2911,37 @@ int mfma_beside_states(const Problem &pb0)
 
 bool mfma_bwd_supported(const Problem &pb)
 {
-    // in-block weights from the sketches (Section 3.1): r = d only
-    // learned sketches (the networks' reverse pass on MFMA): exact in-block weights only
-    return pb.d == 64 && pb.dv == 64 && pb.p == 4 && (pb.r == 32 || pb.r == 64) && pb.b % 256 == 0 &&
-           !pb.exact_feat && (pb.local_exact || (pb.r == 64 && !pb.learned));
+    // in-block weights from the sketches (Section 3.1): d = r = 64, degree 4 only;
+    // learned sketches (the networks' reverse pass on MFMA): d = 64, degree 4, exact in-block weights
+    const bool base = pb.d == 64 && pb.p == 4;
+    return (pb.d == 64 || pb.d == 128) && pb.dv == pb.d && (pb.p == 4 || pb.p == 8) && (pb.r == 32 || pb.r == 64) &&
+           pb.b % 256 == 0 && !pb.exact_feat && (!pb.learned || base) &&
+           (pb.local_exact || (base && pb.r == 64 && !pb.learned));
 }
 
 size_t mfma_bwd_workspace_bytes(const Problem &pb) { return carve_bwd(pb, nullptr).total; }
+
+#define PSF_BWD_DISPATCH(CALL)                                               \
+    do {                                                                     \
+        if (pb.d == 64 && pb.r == 64 && pb.p == 4) return CALL(64, 64, 4);   \
+        if (pb.d == 64 && pb.r == 32 && pb.p == 4) return CALL(64, 32, 4);   \
+        if (pb.d == 64 && pb.r == 64 && pb.p == 8) return CALL(64, 64, 8);   \
+        if (pb.d == 64 && pb.r == 32 && pb.p == 8) return CALL(64, 32, 8);   \
+        if (pb.d == 128 && pb.r == 64 && pb.p == 4) return CALL(128, 64, 4); \
+        if (pb.d == 128 && pb.r == 32 && pb.p == 4) return CALL(128, 32, 4); \
+        if (pb.d == 128 && pb.r == 64 && pb.p == 8) return CALL(128, 64, 8); \
+        if (pb.d == 128 && pb.r == 32 && pb.p == 8) return CALL(128, 32, 8); \
+        return PSF_ERR_UNSUPPORTED;                                          \
+    } while (0)
 
 psf_status mfma_attn_bwd(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                          const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm,
                          void *saved, const void *O_saved, float *dG)
 {
     if (dG && !pb.learned) return PSF_ERR_UNSUPPORTED;
-    if (pb.r == 64) return attn_bwd_impl<64>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm, saved, O_saved, dG);
-    return attn_bwd_impl<32>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm, saved, O_saved, dG);
+#define PSF_AT(D_, R_, P_) (attn_bwd_impl<R_, D_, P_>(pb, Q, K, V, G, dO, dQ, dK, dV, ws, s, tm, saved, O_saved, dG))
+    PSF_BWD_DISPATCH(PSF_AT);
+#undef PSF_AT
 }
 
 size_t mfma_fwd_save_bytes(const Problem &pb) { return carve_saved(pb, nullptr).total; }
@@ -2934,8 +2950,9 @@ psf_status mfma_attn_fwd_save(const Problem &pb, const void *Q, const void *K, c
                               void *O, void *saved, hipStream_t s, StageTimer *tm)
 {
     const MfmaSaved sv = carve_saved(pb, saved);
-    if (pb.r == 64) return attn_impl<64, 64, 4>(pb, Q, K, V, G, O, sv.fwd, s, tm, sv.Den, sv.MK);
-    return attn_impl<64, 32, 4>(pb, Q, K, V, G, O, sv.fwd, s, tm, sv.Den, sv.MK);
+#define PSF_AT(D_, R_, P_) (attn_impl<D_, R_, P_>(pb, Q, K, V, G, O, sv.fwd, s, tm, sv.Den, sv.MK))
+    PSF_BWD_DISPATCH(PSF_AT);
+#undef PSF_AT
 }
 
 #define PSF_DISPATCH(CALL)                                                   \

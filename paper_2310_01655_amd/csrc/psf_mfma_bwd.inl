@@ -34,19 +34,25 @@ __global__ __launch_bounds__(kWg) void k_bwd_prep(const bf16_t *__restrict__ dO,
                                                   bf16_t *__restrict__ G8, bf16_t *__restrict__ G8r,
                                                   float *__restrict__ Cc, int n, int b, int t)
 {
-    static_assert(D == 64, "one lane per value column");
+    static_assert(D % 64 == 0, "D / 64 value columns per lane");
+    constexpr int CL = D / 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t oct = (size_t)blockIdx.x * 4 + wave, row0 = oct * 8;
-    uint16_t gb[8];
+    uint16_t gb[CL][8];
     float dot[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const float d_o = bf16_to_f32(dO[(row0 + j) * D + lane]);
-        const float o = bf16_to_f32(O[(row0 + j) * D + lane]);
         const float inv = 1.0f / Den[row0 + j];
-        gb[j] = f32_to_bf16(d_o * inv);
-        dot[j] = d_o * o * inv;
-        G_rm[(row0 + j) * D + lane] = gb[j];
+        dot[j] = 0.f;
+#pragma unroll
+        for (int cl = 0; cl < CL; ++cl) {
+            const int col = 64 * cl + lane;
+            const float d_o = bf16_to_f32(dO[(row0 + j) * D + col]);
+            const float o = bf16_to_f32(O[(row0 + j) * D + col]);
+            gb[cl][j] = f32_to_bf16(d_o * inv);
+            dot[j] += d_o * o * inv;
+            G_rm[(row0 + j) * D + col] = gb[cl][j];
+        }
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -54,15 +60,19 @@ __global__ __launch_bounds__(kWg) void k_bwd_prep(const bf16_t *__restrict__ dO,
         for (int m = 32; m >= 1; m >>= 1) dot[j] += __shfl_xor(dot[j], m);
         if (lane == j) Cc[row0 + j] = -dot[j];
     }
-    uint4 pk;
-    pk.x = gb[0] | ((uint32_t)gb[1] << 16);
-    pk.y = gb[2] | ((uint32_t)gb[3] << 16);
-    pk.z = gb[4] | ((uint32_t)gb[5] << 16);
-    pk.w = gb[6] | ((uint32_t)gb[7] << 16);
-    *(uint4 *)&G8[(oct * D + lane) * 8] = pk;
     const size_t u = row0 / n, pos = row0 % n;
     const size_t rpos = (size_t)(t - 1 - (int)(pos / b)) * b + pos % b;
-    *(uint4 *)&G8r[(((u * n + rpos) >> 3) * D + lane) * 8] = pk;
+#pragma unroll
+    for (int cl = 0; cl < CL; ++cl) {
+        const int col = 64 * cl + lane;
+        uint4 pk;
+        pk.x = gb[cl][0] | ((uint32_t)gb[cl][1] << 16);
+        pk.y = gb[cl][2] | ((uint32_t)gb[cl][3] << 16);
+        pk.z = gb[cl][4] | ((uint32_t)gb[cl][5] << 16);
+        pk.w = gb[cl][6] | ((uint32_t)gb[cl][7] << 16);
+        *(uint4 *)&G8[(oct * D + col) * 8] = pk;
+        *(uint4 *)&G8r[(((u * n + rpos) >> 3) * D + col) * 8] = pk;
+    }
 }
 
 // ---- m(Q) octets in reverse block order and the c-weighted partial sums --------------------
@@ -384,7 +394,7 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dm(const bf16_t *__restrict__ M,
                                                   int per_head, size_t g_len, float *__restrict__ dMout = nullptr)
 {
     using X = Cross<R, D, R, false, TT>;
-    static_assert(sizeof(SketchLds<D, R>) + 2 * D * (R + 8) * 2 <= X::LDS_BYTES, "the sketch matrices reuse the stage");
+    static_assert(RAW || sizeof(SketchLds<D, R>) + 2 * D * (R + 8) * 2 <= X::LDS_BYTES, "the sketch matrices reuse the stage");
     constexpr int AT = R / 32, RS = R / 16, VS = D / 16, TOK_WG = 128 * TT;
     __shared__ __attribute__((aligned(16))) unsigned char stage[X::LDS_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
@@ -542,41 +552,42 @@ __global__ __launch_bounds__(kWg, 2) void k_bwd_dvc(const bf16_t *__restrict__ M
 // registers = streamed rows), are turned into bf16 B operands with one half-wave swap per
 // register pair (as in the forward output kernel) and contracted with the octets.
 constexpr int kLocT = 64;                                   // streamed rows per tile
-constexpr int kLocRows = kLocT * 64 * 2;                    // bytes of one [D/8][64][8] / [8][D][8] array, D = 64
+// bytes of one [D/8][64][8] / [8][D][8] array
+__host__ __device__ constexpr int loc_rows_bytes(int d) { return kLocT * d * 2; }
 
-// X [rows][64] bf16 -> XF [rows/64][8][64][8]: per 64-row tile the layout the in-block kernels keep
-// in LDS (16-byte A fragments with contraction over the 64 columns), so that staging a tile is
-// a straight, fully coalesced copy.
+// X [rows][D] bf16 -> XF [rows/64][D/8][64][8]: per 64-row tile the layout the in-block kernels keep
+// in LDS (16-byte A fragments with contraction over the D columns), so that staging a tile is
+// a straight, fully coalesced copy.  d8 = D / 8.
 // scale: a power of two (exact in bf16) the copy is multiplied by; 1 for a plain re-layout.
 __global__ __launch_bounds__(kWg) void k_bwd_row_tiles(const bf16_t *__restrict__ X, bf16_t *__restrict__ XF,
-                                                       size_t pieces, float scale)
+                                                       size_t pieces, float scale, int d8)
 {
     const size_t idx = (size_t)blockIdx.x * kWg + threadIdx.x;         // (tile, row, column octet)
     if (idx >= pieces) return;
-    const size_t tile = idx / 512;
-    const int key = (int)(idx % 512) / 8, doct = (int)(idx % 8);
+    const size_t per_tile = (size_t)kLocT * d8, tile = idx / per_tile;
+    const int key = (int)(idx % per_tile) / d8, doct = (int)(idx % d8);
     bf16x8 v = *(const bf16x8 *)&X[idx * 8];
     if (scale != 1.0f) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = (__bf16)((float)v[e] * scale);
     }
-    *(bf16x8 *)&XF[((tile * 8 + doct) * kLocT + key) * 8] = v;
+    *(bf16x8 *)&XF[((tile * d8 + doct) * kLocT + key) * 8] = v;
 }
 // tile of rows [j0, j0 + 64) of XF -> LDS, straight copy
-template <int NTHR>
+template <int NTHR, int D>
 __device__ __forceinline__ void loc_stage_rows(const bf16_t *XF, size_t j0, unsigned char *dst, int tid, int wave)
 {
 #pragma unroll
-    for (int q = 0; q < kLocRows / 16 / NTHR; ++q)
-        dma16(XF + j0 * 64 + (size_t)(q * NTHR + tid) * 8, dst + (size_t)(q * NTHR + wave * 64) * 16);
+    for (int q = 0; q < loc_rows_bytes(D) / 16 / NTHR; ++q)
+        dma16(XF + j0 * D + (size_t)(q * NTHR + tid) * 8, dst + (size_t)(q * NTHR + wave * 64) * 16);
 }
-// octets of rows [j0, j0 + 64) of X8 ([rows/8][64][8]) -> LDS, straight copy
-template <int NTHR>
+// octets of rows [j0, j0 + 64) of X8 ([rows/8][D][8]) -> LDS, straight copy
+template <int NTHR, int D>
 __device__ __forceinline__ void loc_stage_octets(const bf16_t *X8, size_t j0, unsigned char *dst, int tid, int wave)
 {
 #pragma unroll
-    for (int q = 0; q < kLocRows / 16 / NTHR; ++q)
-        dma16(X8 + j0 * 64 + (size_t)(q * NTHR + tid) * 8, dst + (size_t)(q * NTHR + wave * 64) * 16);
+    for (int q = 0; q < loc_rows_bytes(D) / 16 / NTHR; ++q)
+        dma16(X8 + j0 * D + (size_t)(q * NTHR + tid) * 8, dst + (size_t)(q * NTHR + wave * 64) * 16);
 }
 // 16 fp32 (lane = own row, register v = streamed row 8 (v / 4) + 4 h + v % 4) -> two bf16 B
 // fragments whose 8 entries are the streamed rows 16 sp + 8 h + e
@@ -594,13 +605,13 @@ __device__ __forceinline__ void loc_pack(const f32x16 &w, bf16x8 (&pw)[2])
 
 // dQ (in-block): own rows = queries, streamed = keys of the same block up to the diagonal.
 //   dq_i = sum_{j <= i} (<g_i, v_j> + c_i) p <q_i, k_j>^(p-1) k_j          -> dQacc fp32 rows
-template <int P, int NW>
-__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void k_bwd_local_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ KF,
+template <int P, int NW, int D = 64>
+__global__ __launch_bounds__(64 * NW, D == 64 ? 512 / (64 * NW) : 1) void k_bwd_local_q(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ KF,
                                                        const bf16_t *__restrict__ VF, const bf16_t *__restrict__ K8,
                                                        const bf16_t *__restrict__ G_rm, const float *__restrict__ Cc,
                                                        float *__restrict__ dQacc, int n, int b)
 {
-    constexpr int D = 64, KS = 4, CT = 2, BUF = 3 * kLocRows, NTHR = 64 * NW, OWN = 32 * NW;
+    constexpr int KS = D / 16, CT = D / 32, kLocRows = loc_rows_bytes(D), BUF = 3 * kLocRows, NTHR = 64 * NW, OWN = 32 * NW;
     __shared__ __attribute__((aligned(16))) unsigned char stage[2 * BUF];
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -622,14 +633,16 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void k_bwd_local_q(const 
         for (int e = 0; e < 8; ++e) gfr[s][e] = (__bf16)((float)gfr[s][e] * (float)P);   // p of p s^(p-1), exact (power of two)
     }
     const float c_me = (float)P * Cc[urow + tok];
-    f32x16 dq[CT] = {f32x16{0}, f32x16{0}};
+    f32x16 dq[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) dq[ct] = f32x16{0};
     const int ntiles = (i0 + OWN - jb) / kLocT;
     auto stage_tile = [&](int kt) {
         unsigned char *dst = stage + (kt & 1) * BUF;
         const size_t j0 = urow + jb + (size_t)kt * kLocT;
-        loc_stage_rows<NTHR>(KF, j0, dst, tid, wave);
-        loc_stage_rows<NTHR>(VF, j0, dst + kLocRows, tid, wave);
-        loc_stage_octets<NTHR>(K8, j0, dst + 2 * kLocRows, tid, wave);
+        loc_stage_rows<NTHR, D>(KF, j0, dst, tid, wave);
+        loc_stage_rows<NTHR, D>(VF, j0, dst + kLocRows, tid, wave);
+        loc_stage_octets<NTHR, D>(K8, j0, dst + 2 * kLocRows, tid, wave);
     };
     stage_tile(0);
 #pragma unroll 1
@@ -691,15 +704,15 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void k_bwd_local_q(const 
 //   dk_j = sum_{i >= j} (<g_i, v_j> + c_i) p <q_i, k_j>^(p-1) q_i   -> dKacc fp32 rows
 //          (GF, the streamed rows of g for the first product, and the staged c carry the factor p)
 //   dv_j = sum_{i >= j} <q_i, k_j>^p g_i + dVc_j                     -> dV bf16 rows
-template <int P, int NW>
-__global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void k_bwd_local_k(const bf16_t *__restrict__ QF, const bf16_t *__restrict__ K,
+template <int P, int NW, int D = 64>
+__global__ __launch_bounds__(64 * NW, D == 64 ? 512 / (64 * NW) : 1) void k_bwd_local_k(const bf16_t *__restrict__ QF, const bf16_t *__restrict__ K,
                                                        const bf16_t *__restrict__ V, const bf16_t *__restrict__ Q8,
                                                        const bf16_t *__restrict__ GF, const bf16_t *__restrict__ G8,
                                                        const float *__restrict__ Cc, const float *__restrict__ dVc,
                                                        float *__restrict__ dKacc, bf16_t *__restrict__ dV, int n,
                                                        int b)
 {
-    constexpr int D = 64, KS = 4, CT = 2, BUF = 4 * kLocRows + kLocT * 4, NTHR = 64 * NW, OWN = 32 * NW;
+    constexpr int KS = D / 16, CT = D / 32, kLocRows = loc_rows_bytes(D), BUF = 4 * kLocRows + kLocT * 4, NTHR = 64 * NW, OWN = 32 * NW;
     __shared__ __attribute__((aligned(16))) unsigned char stage[2 * BUF];
     const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -716,15 +729,17 @@ __global__ __launch_bounds__(64 * NW, 512 / (64 * NW)) void k_bwd_local_k(const 
         kfr[s] = *(const bf16x8 *)&K[(urow + key) * D + 16 * s + 8 * h];
         vfr[s] = *(const bf16x8 *)&V[(urow + key) * D + 16 * s + 8 * h];
     }
-    f32x16 dk[CT] = {f32x16{0}, f32x16{0}}, dv[CT] = {f32x16{0}, f32x16{0}};
+    f32x16 dk[CT], dv[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct) dk[ct] = dv[ct] = f32x16{0};
     const int first = (j0 - jb) / kLocT, ntiles = b / kLocT;
     auto stage_tile = [&](int qt) {
         unsigned char *dst = stage + (qt & 1) * BUF;
         const size_t t0 = urow + jb + (size_t)qt * kLocT;
-        loc_stage_rows<NTHR>(QF, t0, dst, tid, wave);
-        loc_stage_rows<NTHR>(GF, t0, dst + kLocRows, tid, wave);
-        loc_stage_octets<NTHR>(Q8, t0, dst + 2 * kLocRows, tid, wave);
-        loc_stage_octets<NTHR>(G8, t0, dst + 3 * kLocRows, tid, wave);
+        loc_stage_rows<NTHR, D>(QF, t0, dst, tid, wave);
+        loc_stage_rows<NTHR, D>(GF, t0, dst + kLocRows, tid, wave);
+        loc_stage_octets<NTHR, D>(Q8, t0, dst + 2 * kLocRows, tid, wave);
+        loc_stage_octets<NTHR, D>(G8, t0, dst + 3 * kLocRows, tid, wave);
         if (tid < kLocT) ((float *)(dst + 4 * kLocRows))[tid] = (float)P * Cc[t0 + tid];
     };
     stage_tile(first);
@@ -888,12 +903,12 @@ MfmaSaved carve_saved(const Problem &pb, void *ptr)
 
 // saved / O_saved: null = run the forward pass again inside; otherwise what psf_causal_attn_fwd_save
 // left and the output it wrote.
-template <int R>
+template <int R, int D, int P>
 psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                          const void *dO, void *dQ, void *dK, void *dV, void *ws, hipStream_t s, StageTimer *tm,
                          void *saved = nullptr, const void *O_saved = nullptr, float *dG = nullptr)
 {
-    constexpr int D = 64, P = 4, TT = 2;
+    constexpr int TT = D == 64 ? 2 : 1;                     // 32-token tiles per wave in the cross-block kernels
     constexpr int NWL = 4;                                  // waves per in-block workgroup: 256 own rows share a streamed tile
     MfmaBwdWs w = carve_bwd(pb, ws);
     MfmaWs f = carve(pb, w.fwd);
@@ -902,7 +917,8 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     // in-block rule of Section 3.1 (r = d = 64 only): the in-block kernels take the sketches
     // m(Q), m(K) in place of Q, K with exponent 2 and leave the in-block part of dm
     const bool ls = !pb.local_exact;
-    if (ls && R != D) return PSF_ERR_UNSUPPORTED;
+    if (ls && !(R == D && P == 4)) return PSF_ERR_UNSUPPORTED;
+    if (pb.learned && !(D == 64 && P == 4)) return PSF_ERR_UNSUPPORTED;
     if (pb.learned && (ls || saved)) return PSF_ERR_UNSUPPORTED;
     psf_status st;
     if (saved) {
@@ -944,7 +960,7 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
         for (int i = 0; i < 4; ++i) {
             // the copy of g that only feeds dW = <g, v> + c carries the factor e of d(s^e) = e s^(e-1) ds
             hipLaunchKernelGGL(k_bwd_row_tiles, dim3(gridp), dim3(kWg), 0, s, src[i], dstf[i], pieces,
-                               i == 3 ? (ls ? 2.0f : (float)P) : 1.0f);
+                               i == 3 ? (ls ? 2.0f : (float)P) : 1.0f, D / 8);
             PSF_LAUNCH_CHECK();
         }
     }
@@ -969,33 +985,43 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     // in-block parts
     {
         const unsigned grid = (unsigned)(rows / (32 * NWL));
-        if (ls)
-            hipLaunchKernelGGL((k_bwd_local_q<2, NWL>), dim3(grid), dim3(64 * NWL), 0, s, rq, w.KF, w.VF, w.K8, w.G_rm,
+        if constexpr (R == D && P == 4) {
+            if (ls) {
+                hipLaunchKernelGGL((k_bwd_local_q<2, NWL, D>), dim3(grid), dim3(64 * NWL), 0, s, rq, w.KF, w.VF, w.K8,
+                                   w.G_rm, w.Cc, w.dQacc, pb.n, pb.b);
+                PSF_LAUNCH_CHECK();
+            }
+        }
+        if (!ls) {
+            hipLaunchKernelGGL((k_bwd_local_q<P, NWL, D>), dim3(grid), dim3(64 * NWL), 0, s, q, w.KF, w.VF, w.K8, w.G_rm,
                                w.Cc, w.dQacc, pb.n, pb.b);
-        else
-            hipLaunchKernelGGL((k_bwd_local_q<P, NWL>), dim3(grid), dim3(64 * NWL), 0, s, q, w.KF, w.VF, w.K8, w.G_rm,
-                               w.Cc, w.dQacc, pb.n, pb.b);
-        PSF_LAUNCH_CHECK();
+            PSF_LAUNCH_CHECK();
+        }
     }
     {
         // dV: the cross-block part first, the in-block kernel adds to it
         const unsigned gridc = (unsigned)(rows / (128 * TT)), grid = (unsigned)(rows / (32 * NWL));
         hipLaunchKernelGGL((k_bwd_dvc<R, D, TT>), dim3(gridc), dim3(kWg), 0, s, w.MK, w.Rg, w.dVc, pb.n, pb.b, pb.t);
         PSF_LAUNCH_CHECK();
-        if (ls)
-            hipLaunchKernelGGL((k_bwd_local_k<2, NWL>), dim3(grid), dim3(64 * NWL), 0, s, w.QF, rk, v, w.Q8, w.GF, w.G8,
+        if constexpr (R == D && P == 4) {
+            if (ls) {
+                hipLaunchKernelGGL((k_bwd_local_k<2, NWL, D>), dim3(grid), dim3(64 * NWL), 0, s, w.QF, rk, v, w.Q8, w.GF,
+                                   w.G8, w.Cc, w.dVc, w.dKacc, (bf16_t *)dV, pb.n, pb.b);
+                PSF_LAUNCH_CHECK();
+            }
+        }
+        if (!ls) {
+            hipLaunchKernelGGL((k_bwd_local_k<P, NWL, D>), dim3(grid), dim3(64 * NWL), 0, s, w.QF, k, v, w.Q8, w.GF, w.G8,
                                w.Cc, w.dVc, w.dKacc, (bf16_t *)dV, pb.n, pb.b);
-        else
-            hipLaunchKernelGGL((k_bwd_local_k<P, NWL>), dim3(grid), dim3(64 * NWL), 0, s, w.QF, k, v, w.Q8, w.GF, w.G8,
-                               w.Cc, w.dVc, w.dKacc, (bf16_t *)dV, pb.n, pb.b);
-        PSF_LAUNCH_CHECK();
+            PSF_LAUNCH_CHECK();
+        }
     }
     if (tm) tm->mark();
     // cross-block parts of dm(q), dm(k), then through the sketch together with the in-block parts
     {
         const unsigned grid = (unsigned)(rows / (128 * TT));
         const int ph = pb.per_head ? 1 : 0;
-        if constexpr (R == D) {
+        if constexpr (R == D && P == 4) {
             if (ls) {
                 hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT, true>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm, w.Cc,
                                    w.ZT, f.Shi, f.Slo, q, f.Gt, (const bf16_t *)G, w.dQacc, (bf16_t *)dQ, pb.n, pb.b,
@@ -1007,6 +1033,8 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
                 PSF_LAUNCH_CHECK();
             }
         }
+        constexpr bool FUSED = D == 64 && P == 4;           // Algorithm 1's reverse inside k_bwd_dm
+        if constexpr (FUSED) {
         if (pb.learned) {
             // dm as fp32 rows (in the buffer of the mirror-state octets, consumed by now), then
             // through the networks: one side after the other, the staging buffers serve both
@@ -1065,6 +1093,24 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
                                w.Rclo, k, f.Gt, (const bf16_t *)G, w.dKacc, (bf16_t *)dK, pb.n, pb.b, pb.t, pb.heads, ph,
                                pb.g_len);
             PSF_LAUNCH_CHECK();
+        }
+        } else {
+            // d = 128 or degree 8: dm as fp32 rows (in the buffer of the mirror-state octets, consumed
+            // by now), then Algorithm 1's reverse as a pass of its own, one side after the other
+            for (int side = 0; side < 2; ++side) {
+                if (side == 0)
+                    hipLaunchKernelGGL((k_bwd_dm<R, D, true, TT, false, true>), dim3(grid), dim3(kWg), 0, s, f.MQ, w.G_rm,
+                                       w.Cc, w.ZT, f.Shi, f.Slo, q, nullptr, nullptr, nullptr, nullptr, pb.n, pb.b, pb.t,
+                                       pb.heads, ph, pb.g_len, w.M8r);
+                else
+                    hipLaunchKernelGGL((k_bwd_dm<R, D, false, TT, false, true>), dim3(grid), dim3(kWg), 0, s, w.MK, v,
+                                       w.Cc, w.RT, w.Rchi, w.Rclo, k, nullptr, nullptr, nullptr, nullptr, pb.n, pb.b, pb.t,
+                                       pb.heads, ph, pb.g_len, w.M8r);
+                PSF_LAUNCH_CHECK();
+                st = general_sketch_bwd(pb, side == 0 ? Q : K, G, w.M8r, side == 0 ? w.dQacc : w.dKacc,
+                                        side == 0 ? dQ : dK, s);
+                if (st != PSF_OK) return st;
+            }
         }
     }
     if (tm) tm->mark();

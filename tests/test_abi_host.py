@@ -111,8 +111,11 @@ def test_backward_kernel_path_and_mfma_workspace():
     # forward workspace + two more sets of state snapshots + the fp32 gradient accumulators
     assert psf.bwd_workspace_bytes(mf) >= psf.workspace_bytes(mf) + 2 * snaps * 64 * 64 * 64 * 2 + 5 * rows * 64 * 4
     assert psf.bwd_kernel_path(psf.make_desc(1, 1, 1024, 64, 4, 16, 128, "f32")) == 2
-    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 128, 4, 64, 256, "bf16")) == 2     # d = 128: general kernels
-    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 8, 64, 256, "bf16")) == 2      # p = 8
+    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 128, 4, 64, 256, "bf16")) == 3     # d = 128
+    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 8, 64, 256, "bf16")) == 3      # p = 8
+    assert psf.bwd_kernel_path(psf.make_desc(1, 16, 16384, 128, 8, 64, 512, "bf16")) == 3   # config 5
+    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 128, 8, 64, 256, "bf16", local=psf.LOCAL_SKETCH)) == 2
+    assert psf.bwd_kernel_path(psf.make_desc(1, 2, 1024, 64, 16, 64, 256, "bf16")) == 2     # p = 16
     # learned sketches of degree 4 with exact in-block weights: the MFMA kernels; other degrees,
     # the in-block rule of Section 3.1 and fp32 storage: the general ones
     learned = psf.make_desc(1, 2, 1024, 64, 4, 64, 256, "bf16", learned=True)

@@ -102,6 +102,20 @@ def test_backward_mfma_path_full_parity(heads, n, r, b, per_head):
     run_case(1, heads, n, 64, 64, 4, r, b, "bf16", per_head=per_head, seed=43)
 
 
+@pytest.mark.parametrize("heads,n,d,p,r,b,per_head", [
+    (2, 1024, 128, 8, 64, 256, True),    # config 5's head width and degree: four blocks
+    (2, 1024, 128, 8, 32, 512, False),
+    (1, 512, 128, 8, 64, 512, True),     # single block: in-block pairs only, s^7 slopes
+    (2, 1024, 64, 8, 64, 256, True),     # degree 8 at d = 64
+    (2, 768, 128, 4, 64, 256, False),    # d = 128 with degree 4
+    (3, 1536, 128, 8, 64, 768, True),    # block size that is no power of two
+])
+def test_backward_mfma_path_wide_heads_and_degree_eight(heads, n, d, p, r, b, per_head):
+    desc = psf.make_desc(1, heads, n, d, p, r, b, "bf16", per_head=per_head)
+    assert psf.bwd_kernel_path(desc) == 3
+    run_case(1, heads, n, d, d, p, r, b, "bf16", per_head=per_head, seed=49)
+
+
 @pytest.mark.parametrize("heads,n,b,per_head", [(2, 1024, 256, True), (3, 1536, 512, False), (1, 512, 512, False)])
 def test_backward_mfma_path_in_block_weights_from_the_sketches(heads, n, b, per_head):
     # Section 3.1's in-block rule on the MFMA kernels (r = d = 64): the in-block kernels work on
