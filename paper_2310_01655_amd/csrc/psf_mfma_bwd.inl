@@ -292,6 +292,153 @@ __device__ __forceinline__ void sketch_grad_stage(SketchLds<D, R> &lds, bf16_t *
     }
 }
 
+// ---- through Algorithm 1 as a pass of its own (d = 128 or degree 8) ---------------------------
+// dX = bf16(dXacc + J_m(x)^T dm) for 128 rows per workgroup (one 32-row tile per wave, lane = row), dm
+// given as fp32 rows.  Degree 4: sketch_grad_tile.  Degree 8, with u_k = x G_k (k < 4),
+// n1 = s u0 * u1, n2 = s u2 * u3, w1 = n1 G4, w2 = n2 G5, m = s w1 * w2, s = sqrt(1/r):
+//     dw1 = s dm * w2, dw2 = s dm * w1;  dn1 = dw1 G4^T, dn2 = dw2 G5^T;
+//     du0 = s dn1 * u1, du1 = s dn1 * u0, du2 = s dn2 * u3, du3 = s dn2 * u2;  dx = sum_k du_k G_k^T.
+// The matrices go through LDS in phases (two transposed ones for the projections, two as given
+// for the transposed products at a time), as in the forward sketch kernel.
+template <int D, int R, int P>
+__global__ __launch_bounds__(kWg, 1) void k_bwd_sketch_rows(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Gt,
+                                                           const bf16_t *__restrict__ G, const float *__restrict__ dM,
+                                                           const float *__restrict__ dXacc, bf16_t *__restrict__ dX,
+                                                           int n, int heads, int per_head, size_t g_len)
+{
+    constexpr int KS = D / 16, NT = R / 32, RS = R / 16, DT = D / 32, GP = R + 8;
+    __shared__ __attribute__((aligned(16))) SketchLds<D, R> lds;
+    __shared__ __attribute__((aligned(16))) bf16_t go[2 * D * GP];
+    const int tid = threadIdx.x, lane = tid & 63, x = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const size_t row0 = (size_t)blockIdx.x * 128, row = row0 + wave * 32 + x;
+    const size_t goff = per_head ? (size_t)((row0 / n) % heads) * g_len : 0;
+    const bf16_t *gt = Gt + goff, *g = G + goff;
+    // dm of the tile: lane = row, register v of tile ct = sketch column 32 ct + 8 (v / 4) + 4 h + v % 4
+    f32x16 dm[NT];
+#pragma unroll
+    for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const f32x4 d4 = *(const f32x4 *)&dM[row * R + 32 * ct + 8 * gq + 4 * h];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dm[ct][4 * gq + j] = d4[j];
+        }
+    if constexpr (P == 4) {
+        sketch_grad_stage<D, R>(lds, go, gt, g);
+        __syncthreads();
+        sketch_grad_tile<D, R, true>(lds, go, X, dm, dXacc, dX, row, x, h);
+    } else {
+        static_assert(P == 8, "degree 4 or 8");
+        const float scale = sqrtf(1.0f / (float)R);
+        // rows [0, nrows) of a matrix given as [nrows][R] -> go[which] with rows padded to GP
+        auto stage_rows = [&](int which, const bf16_t *src, int nrows) {
+            for (int idx = tid; idx < nrows * (R / 8); idx += kWg) {
+                const int e = idx / (R / 8), part = idx % (R / 8);
+                *(uint4 *)&go[(which * D + e) * GP + 8 * part] = *(const uint4 *)&src[(size_t)e * R + 8 * part];
+            }
+        };
+        // out[i][row] = sum_k M[i][k] v[k][row], M as given ([.][R], staged by stage_rows), v as B
+        // fragments in accumulator order (entries e of step ks: k = 16 ks + 8 (e / 4) + 4 h + e % 4)
+        auto times_rows = [&](int which, int tile, const bf16x8 *v, f32x16 acc) {
+#pragma unroll
+            for (int ks = 0; ks < RS; ++ks) {
+                const int off = (which * D + 32 * tile + x) * GP + 16 * ks + 4 * h;
+                const bf16x4 lo = *(const bf16x4 *)&go[off], hi = *(const bf16x4 *)&go[off + 8];
+                bf16x8 f;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { f[e] = lo[e]; f[4 + e] = hi[e]; }
+                acc = mfma32(f, v[ks], acc);
+            }
+            return acc;
+        };
+        auto to_frags = [&](const f32x16 (&a)[NT], bf16x8 (&f)[RS]) {
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+                for (int q2 = 0; q2 < 2; ++q2) f[2 * ct + q2] = cvt8_from16(a[ct], 8 * q2);
+        };
+        bf16x8 xfr[KS];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
+        f32x16 u[4][NT];
+        bf16x8 nfr[2][RS];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            __syncthreads();
+            stage_gt<D, R, D>(lds.gt[0], gt + (size_t)(2 * half) * D * R);
+            stage_gt<D, R, D>(lds.gt[1], gt + (size_t)(2 * half + 1) * D * R);
+            __syncthreads();
+            project<D, R, KS, true>(lds.gt[0], xfr, u[2 * half], x, h);
+            project<D, R, KS, true>(lds.gt[1], xfr, u[2 * half + 1], x, h);
+            f32x16 nn[NT];
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) nn[ct] = scale * (u[2 * half][ct] * u[2 * half + 1][ct]);
+            to_frags(nn, nfr[half]);
+        }
+        __syncthreads();
+        const size_t inner = (size_t)4 * D * R;
+        stage_gt<D, R, R>(lds.gt[0], gt + inner);
+        stage_gt<D, R, R>(lds.gt[1], gt + inner + (size_t)R * R);
+        stage_rows(0, g + inner, R);
+        stage_rows(1, g + inner + (size_t)R * R, R);
+        __syncthreads();
+        bf16x8 duf[4][RS];
+        {
+            f32x16 w1[NT], w2[NT];
+            project_inner<D, R, true>(lds.gt[0], nfr[0], w1, x, h);
+            project_inner<D, R, true>(lds.gt[1], nfr[1], w2, x, h);
+            f32x16 d1[NT], d2[NT];
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                d1[ct] = scale * (dm[ct] * w2[ct]);
+                d2[ct] = scale * (dm[ct] * w1[ct]);
+            }
+            bf16x8 dw1[RS], dw2[RS];
+            to_frags(d1, dw1);
+            to_frags(d2, dw2);
+            f32x16 t0[NT], t1[NT];
+#pragma unroll
+            for (int ct = 0; ct < NT; ++ct) {
+                const f32x16 dn1 = times_rows(0, ct, dw1, f32x16{0}), dn2 = times_rows(1, ct, dw2, f32x16{0});
+                t0[ct] = scale * (dn1 * u[1][ct]);
+                t1[ct] = scale * (dn1 * u[0][ct]);
+                d1[ct] = scale * (dn2 * u[3][ct]);
+                d2[ct] = scale * (dn2 * u[2][ct]);
+            }
+            to_frags(t0, duf[0]);
+            to_frags(t1, duf[1]);
+            to_frags(d1, duf[2]);
+            to_frags(d2, duf[3]);
+        }
+        f32x16 dx[DT];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) dx[dt] = f32x16{0};
+#pragma unroll
+        for (int pair = 0; pair < 2; ++pair) {
+            __syncthreads();
+            stage_rows(0, g + (size_t)(2 * pair) * D * R, D);
+            stage_rows(1, g + (size_t)(2 * pair + 1) * D * R, D);
+            __syncthreads();
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                dx[dt] = times_rows(0, dt, duf[2 * pair], dx[dt]);
+                dx[dt] = times_rows(1, dt, duf[2 * pair + 1], dx[dt]);
+            }
+        }
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const size_t off = row * D + 32 * dt + 8 * gq + 4 * h;
+                const f32x4 base = *(const f32x4 *)&dXacc[off];
+                const f32x4 q4 = {dx[dt][4 * gq] + base[0], dx[dt][4 * gq + 1] + base[1], dx[dt][4 * gq + 2] + base[2],
+                                  dx[dt][4 * gq + 3] + base[3]};
+                *(bf16x4 *)&dX[off] = cvt4(q4);
+            }
+    }
+}
+
 // ---- generic cross-block contraction ---------------------------------------------------------
 // out^T[o][token] += sum_{a < NS} sum_{k < NV} (sc_token[a] * vec_token[k]) * Z[a][k][o],  Z stored
 // [NS][NV/8][NO][8] bf16 (k octets innermost: 16-byte A fragments with rows o).  The B operand
@@ -1107,9 +1254,10 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
                                        w.Cc, w.RT, w.Rchi, w.Rclo, k, nullptr, nullptr, nullptr, nullptr, pb.n, pb.b, pb.t,
                                        pb.heads, ph, pb.g_len, w.M8r);
                 PSF_LAUNCH_CHECK();
-                st = general_sketch_bwd(pb, side == 0 ? Q : K, G, w.M8r, side == 0 ? w.dQacc : w.dKacc,
-                                        side == 0 ? dQ : dK, s);
-                if (st != PSF_OK) return st;
+                hipLaunchKernelGGL((k_bwd_sketch_rows<D, R, P>), dim3((unsigned)(rows / 128)), dim3(kWg), 0, s,
+                                   side == 0 ? q : k, f.Gt, (const bf16_t *)G, w.M8r, side == 0 ? w.dQacc : w.dKacc,
+                                   (bf16_t *)(side == 0 ? dQ : dK), pb.n, pb.heads, ph, pb.g_len);
+                PSF_LAUNCH_CHECK();
             }
         }
     }
