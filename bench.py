@@ -126,17 +126,18 @@ def bwd_stage_flops(cfg, learned=False):
 def bwd_stage_flops_mfma(cfg, learned=False):
     """The same count by stage of the MFMA backward kernels (d = dv, p = 4)."""
     U = cfg["batch"] * cfg["heads"]
-    n, d, r, b = cfg["n"], cfg["d"], cfg["r"], cfg["b"]
+    n, d, r, b, p = cfg["n"], cfg["d"], cfg["r"], cfg["b"], cfg["p"]
     F, kc = r * r, d + 1
     pairs = n * (b + 1) // 2
     cross = 2 * (n - b) * F * kc
+    sketch = 8 * n * d * r if p == 4 else 16 * n * d * r + 8 * n * r * r      # Algorithm 1 for Q and K
     f = {
         "forward_again": stage_flops(cfg, learned=learned)["total"],
         "g_c_and_layouts": U * 4 * n * d,
         "mirror_states": U * cross,
         "in_block_and_dv": U * (pairs * 2 * 7 * d + cross),                  # 3 + 4 tile products per pair; phi'(K)^T R_l
         # dm(q), dm(k) with their S / Rc terms; projections again + transposed products
-        "cross_block_and_sketch_gradient": U * (2 * cross + 8 * (n - b) * F + 16 * n * d * r),
+        "cross_block_and_sketch_gradient": U * (2 * cross + 8 * (n - b) * F + 2 * sketch),
     }
     if learned:
         # in place of Algorithm 1's reverse: the two networks of every row and side forward again,

@@ -152,32 +152,35 @@ __global__ __launch_bounds__(kWg) void k_bwd_qoct(const bf16_t *__restrict__ MQ,
 //      b' < a zero).  Out: ZT [snap][b][c/8][e][8] = 2 Z[e][b][c], twice the full symmetric state
 //      (so only the diagonal needs arithmetic) with the value column as the contraction octet and
 //      the free sketch index e as the row of an MFMA A operand.  Workgroup = (octet of b, snapshot).
-template <int R, int D>
+// DC value columns per workgroup (blockIdx.z picks the range): D = 128 goes in two halves so that
+// two workgroups fit a CU.
+template <int R, int D, int DC = D>
 __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__ Zs, bf16_t *__restrict__ ZT)
 {
+    static_assert(DC >= 64 && D % DC == 0, "the swizzle needs eight column octets");
     // [b % 8][e][c], the 16-byte column c / 8 of row e stored at (c / 8) ^ (e % 8): the final
     // reads walk e with a fixed column and would otherwise all hit the same banks
-    __shared__ __attribute__((aligned(16))) bf16_t F[8][R][D];
+    __shared__ __attribute__((aligned(16))) bf16_t F[8][R][DC];
     auto at = [&](int b8, int e, int c) -> bf16_t & { return F[b8][e][(((c >> 3) ^ (e & 7)) << 3) + (c & 7)]; };
-    const int tid = threadIdx.x, ob = blockIdx.x;
+    const int tid = threadIdx.x, ob = blockIdx.x, c0 = blockIdx.z * DC;
     const bf16_t *src = Zs + (size_t)blockIdx.y * R * R * D;
     bf16_t *dst = ZT + (size_t)blockIdx.y * R * R * D;
     auto twice = [](uint32_t bits) { return f32_to_bf16(2.0f * bf16_to_f32((bf16_t)bits)); };
     // 16-byte pieces of the source, all loads of a thread issued before their use:
-    //   pieces [0, 8 ob D): rows e < 8 ob, octet ob (b > e there: 2 Z[e][b][c] = Zs[e][b][c])
+    //   pieces [0, 8 ob DC): rows e < 8 ob, octet ob (b > e there: 2 Z[e][b][c] = Zs[e][b][c])
     //   the rest: rows a of this octet, column octets ob2 >= ob
-    constexpr int PIECES = 8 * D * (R / 8) / kWg;
-    const int n_a = 8 * ob * D, per_a = (R / 8 - ob) * D;
+    constexpr int PIECES = 8 * DC * (R / 8) / kWg;
+    const int n_a = 8 * ob * DC, per_a = (R / 8 - ob) * DC;
     uint4 pk[PIECES];
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) {
         const int idx = tid + i * kWg;
         size_t off;
         if (idx < n_a) {
-            off = ((size_t)(idx / D) * (R / 8) + ob) * D + idx % D;
+            off = ((size_t)(idx / DC) * (R / 8) + ob) * D + c0 + idx % DC;
         } else {
             const int k2 = idx - n_a, a8 = k2 / per_a, rem = k2 % per_a;
-            off = ((size_t)(8 * ob + a8) * (R / 8) + ob + rem / D) * D + rem % D;
+            off = ((size_t)(8 * ob + a8) * (R / 8) + ob + rem / DC) * D + c0 + rem % DC;
         }
         pk[i] = *(const uint4 *)&src[off * 8];
     }
@@ -186,11 +189,11 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
         const int idx = tid + i * kWg;
         const uint32_t w[4] = {pk[i].x, pk[i].y, pk[i].z, pk[i].w};
         if (idx < n_a) {
-            const int e = idx / D, c = idx % D;
+            const int e = idx / DC, c = idx % DC;
 #pragma unroll
             for (int j = 0; j < 8; ++j) at(j, e, c) = (bf16_t)((w[j / 2] >> (16 * (j % 2))) & 0xffffu);
         } else {
-            const int k2 = idx - n_a, a8 = k2 / per_a, rem = k2 % per_a, ob2 = ob + rem / D, c = rem % D;
+            const int k2 = idx - n_a, a8 = k2 / per_a, rem = k2 % per_a, ob2 = ob + rem / DC, c = rem % DC;
             const int a = 8 * ob + a8;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -209,8 +212,8 @@ __global__ __launch_bounds__(kWg) void k_bwd_relayout(const bf16_t *__restrict__
 #pragma unroll
     for (int i = 0; i < PIECES; ++i) {
         const int idx = tid + i * kWg;
-        const int b8 = idx / ((D / 8) * R), c8 = (idx / R) % (D / 8), e = idx % R;
-        *(uint4 *)&dst[((((size_t)(8 * ob + b8)) * (D / 8) + c8) * R + e) * 8] = *(const uint4 *)&F[b8][e][8 * (c8 ^ (e & 7))];
+        const int b8 = idx / ((DC / 8) * R), c8 = (idx / R) % (DC / 8), e = idx % R;
+        *(uint4 *)&dst[((((size_t)(8 * ob + b8)) * (D / 8) + c0 / 8 + c8) * R + e) * 8] = *(const uint4 *)&F[b8][e][8 * (c8 ^ (e & 7))];
     }
 }
 
@@ -1122,10 +1125,11 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
         hipLaunchKernelGGL((k_den_scan<R>), dim3(R * R / kWg, pb.units), dim3(kWg), 0, s, w.ScPart, w.Rchi, w.Rclo,
                            pb.t, pb.b / 256, pb.n / 256);
         PSF_LAUNCH_CHECK();
-        const dim3 grid(R / 8, (unsigned)((size_t)pb.units * (pb.t - 1)));
-        hipLaunchKernelGGL((k_bwd_relayout<R, D>), grid, dim3(kWg), 0, s, f.Zg, w.ZT);
+        constexpr int DC = 64;                              // value columns per re-layout workgroup
+        const dim3 grid(R / 8, (unsigned)((size_t)pb.units * (pb.t - 1)), D / DC);
+        hipLaunchKernelGGL((k_bwd_relayout<R, D, DC>), grid, dim3(kWg), 0, s, f.Zg, w.ZT);
         PSF_LAUNCH_CHECK();
-        hipLaunchKernelGGL((k_bwd_relayout<R, D>), grid, dim3(kWg), 0, s, w.Rg, w.RT);
+        hipLaunchKernelGGL((k_bwd_relayout<R, D, DC>), grid, dim3(kWg), 0, s, w.Rg, w.RT);
         PSF_LAUNCH_CHECK();
     }
     if (tm) tm->mark();

@@ -187,15 +187,16 @@ def test_backward_config3_full_size_sampled_rows_and_identities():
               assert_close_scaled(gv[tail0:], wV[tail0:], "bf16", "dV"))
 
 
-@pytest.mark.parametrize("r,b,local", [(64, 256, psf.LOCAL_EXACT), (32, 512, psf.LOCAL_EXACT), (64, 256, psf.LOCAL_SKETCH)])
-def test_saved_forward_gives_the_same_output_and_gradients(r, b, local):
+@pytest.mark.parametrize("d,p,r,b,local", [(64, 4, 64, 256, psf.LOCAL_EXACT), (64, 4, 32, 512, psf.LOCAL_EXACT),
+                                           (64, 4, 64, 256, psf.LOCAL_SKETCH), (128, 8, 64, 512, psf.LOCAL_EXACT)])
+def test_saved_forward_gives_the_same_output_and_gradients(d, p, r, b, local):
     """psf_causal_attn_fwd_save + psf_causal_attn_bwd_saved against the plain forward and the
     plain (recomputing) backward of the same library.  The gradients are identical bits: the
     recomputing backward runs the very forward kernels the saving call runs, on the same data.
     The plain forward call may take other kernels for the prefix states (half-precision products
     where the in-block part runs beside them), so its output agrees within the rounding of the
     storage type, not bit for bit; the plain calls are the ones checked against the oracle above."""
-    batch, heads, n, d, p = 1, 3, 1024, 64, 4
+    batch, heads, n = 1, 3, 1024
     q, k, v = inputs.make_qkv(batch, heads, n, d, seed=53, dtype="bf16")
     dO = inputs.make_dout(batch, heads, n, d, seed=53, dtype="bf16")
     G = inputs.make_sketch_matrices(heads, d, r, p, per_head=True, seed=0, dtype="bf16")
