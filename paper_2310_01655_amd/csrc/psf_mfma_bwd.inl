@@ -304,7 +304,7 @@ __device__ __forceinline__ void sketch_grad_stage(SketchLds<D, R> &lds, bf16_t *
 // The matrices go through LDS in phases (two transposed ones for the projections, two as given
 // for the transposed products at a time), as in the forward sketch kernel.
 template <int D, int R, int P>
-__global__ __launch_bounds__(kWg, 1) void k_bwd_sketch_rows(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Gt,
+__global__ __launch_bounds__(kWg, 2) void k_bwd_sketch_rows(const bf16_t *__restrict__ X, const bf16_t *__restrict__ Gt,
                                                            const bf16_t *__restrict__ G, const float *__restrict__ dM,
                                                            const float *__restrict__ dXacc, bf16_t *__restrict__ dX,
                                                            int n, int heads, int per_head, size_t g_len)
@@ -364,7 +364,8 @@ __global__ __launch_bounds__(kWg, 1) void k_bwd_sketch_rows(const bf16_t *__rest
         bf16x8 xfr[KS];
 #pragma unroll
         for (int s = 0; s < KS; ++s) xfr[s] = *(const bf16x8 *)&X[row * D + 16 * s + 8 * h];
-        f32x16 u[4][NT];
+        // the projections are kept as bf16 (like every operand of the products they enter): half the registers
+        bf16x8 ub[4][RS];
         bf16x8 nfr[2][RS];
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
@@ -372,13 +373,17 @@ __global__ __launch_bounds__(kWg, 1) void k_bwd_sketch_rows(const bf16_t *__rest
             stage_gt<D, R, D>(lds.gt[0], gt + (size_t)(2 * half) * D * R);
             stage_gt<D, R, D>(lds.gt[1], gt + (size_t)(2 * half + 1) * D * R);
             __syncthreads();
-            project<D, R, KS, true>(lds.gt[0], xfr, u[2 * half], x, h);
-            project<D, R, KS, true>(lds.gt[1], xfr, u[2 * half + 1], x, h);
+            f32x16 ua[NT], uc[NT];
+            project<D, R, KS, true>(lds.gt[0], xfr, ua, x, h);
+            project<D, R, KS, true>(lds.gt[1], xfr, uc, x, h);
             f32x16 nn[NT];
 #pragma unroll
-            for (int ct = 0; ct < NT; ++ct) nn[ct] = scale * (u[2 * half][ct] * u[2 * half + 1][ct]);
+            for (int ct = 0; ct < NT; ++ct) nn[ct] = scale * (ua[ct] * uc[ct]);
             to_frags(nn, nfr[half]);
+            to_frags(ua, ub[2 * half]);
+            to_frags(uc, ub[2 * half + 1]);
         }
+        auto u_at = [&](int k, int ct, int v) { return (float)ub[k][2 * ct + v / 8][v % 8]; };
         __syncthreads();
         const size_t inner = (size_t)4 * D * R;
         stage_gt<D, R, R>(lds.gt[0], gt + inner);
@@ -404,10 +409,13 @@ __global__ __launch_bounds__(kWg, 1) void k_bwd_sketch_rows(const bf16_t *__rest
 #pragma unroll
             for (int ct = 0; ct < NT; ++ct) {
                 const f32x16 dn1 = times_rows(0, ct, dw1, f32x16{0}), dn2 = times_rows(1, ct, dw2, f32x16{0});
-                t0[ct] = scale * (dn1 * u[1][ct]);
-                t1[ct] = scale * (dn1 * u[0][ct]);
-                d1[ct] = scale * (dn2 * u[3][ct]);
-                d2[ct] = scale * (dn2 * u[2][ct]);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    t0[ct][v] = scale * dn1[v] * u_at(1, ct, v);
+                    t1[ct][v] = scale * dn1[v] * u_at(0, ct, v);
+                    d1[ct][v] = scale * dn2[v] * u_at(3, ct, v);
+                    d2[ct][v] = scale * dn2[v] * u_at(2, ct, v);
+                }
             }
             to_frags(t0, duf[0]);
             to_frags(t1, duf[1]);
