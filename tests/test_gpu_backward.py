@@ -136,9 +136,10 @@ def test_backward_mfma_path_is_deterministic_and_matches_general_kernels():
         assert torch.equal(x, y)
 
 
-def test_backward_config3_full_size_sampled_rows_and_identities():
-    """The workload `bench.py --pass bwd` times (config 3: 2 x 12 units of 32768 tokens, MFMA
-    kernels).  Element-wise against the oracle where it can afford the sums: dQ on probe rows
+@pytest.mark.parametrize("idx,units", [(3, [(0, 0), (1, 7)]), (5, [(0, 0), (0, 9)])])
+def test_backward_config3_full_size_sampled_rows_and_identities(idx, units):
+    """The workloads `bench.py --pass bwd` times (config 3: 2 x 12 units of 32768 tokens; config 5:
+    16 units of 16384 tokens with d = 128 and degree 8; MFMA kernels).  Element-wise against the oracle where it can afford the sums: dQ on probe rows
     spread over the sequence, dK and dV on the last block plus the end of the block before it
     (those rows see in-block pairs and one later block's cross-block pairs), for two units.
     Over all tokens of every unit, two identities that hold at any size: the weights are
@@ -146,9 +147,9 @@ def test_backward_config3_full_size_sampled_rows_and_identities():
     (= p sum w dw, Euler); the output is linear in V, so <dV, V> = <dO, O>."""
     from concurrent.futures import ThreadPoolExecutor
     from parity import probe_rows
-    cfg, q, k, v, G = inputs.make_config(3)
+    cfg, q, k, v, G = inputs.make_config(idx)
     n, b, r, p, heads = cfg["n"], cfg["b"], cfg["r"], cfg["p"], cfg["heads"]
-    dO = inputs.make_dout(cfg["batch"], heads, n, cfg["d"], seed=1003, dtype="bf16")
+    dO = inputs.make_dout(cfg["batch"], heads, n, cfg["d"], seed=1000 + idx, dtype="bf16")
     desc = psf.make_desc(cfg["batch"], heads, n, cfg["d"], p, r, b, "bf16", per_head=cfg["per_head"])
     assert psf.bwd_kernel_path(desc) == 3
     dev = torch.device("cuda:0")
@@ -169,7 +170,6 @@ def test_backward_config3_full_size_sampled_rows_and_identities():
     tail0 = n - b - 128
     probe = [x for x in probe_rows(n, b, extra=12) if x < tail0]
     rows = probe + list(range(tail0, n))
-    units = [(0, 0), (1, 7)]
 
     def one(unit):
         bi, h = unit
@@ -181,7 +181,7 @@ def test_backward_config3_full_size_sampled_rows_and_identities():
         want = list(ex.map(one, units))
     for (bi, h), (wQ, wK, wV) in zip(units, want):
         gq, gk, gv = (x[bi, h].float().cpu().numpy() for x in (dQ, dK, dV))
-        print("config 3 bwd", (bi, h),
+        print("config %d bwd" % idx, (bi, h),
               assert_close_scaled(gq[rows], wQ[rows], "bf16", "dQ"),
               assert_close_scaled(gk[tail0:], wK[tail0:], "bf16", "dK"),
               assert_close_scaled(gv[tail0:], wV[tail0:], "bf16", "dV"))
