@@ -216,8 +216,9 @@ psf_status psf_noncausal_attn_fwd_timed(const psf_desc *desc, const void *Q, con
  * descriptor check admits (fp32 arithmetic), Gaussian or learned sketches (with learned ones G
  * holds the networks' parameters and this call treats them as constants; see
  * psf_causal_attn_bwd_learned).  PSF_FEAT_EXACT returns PSF_ERR_UNSUPPORTED.
- * Kernels: bf16 storage with d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0 and PSF_LOCAL_EXACT
- * (random or learned sketches) or PSF_LOCAL_SKETCH (random sketches, r = 64) runs on MFMA
+ * Kernels: bf16 storage with d = dv in {64, 128}, p in {4, 8}, r in {32, 64}, b % 256 == 0 and
+ * PSF_LOCAL_EXACT (random sketches; learned ones for d = 64, p = 4) or PSF_LOCAL_SKETCH (random
+ * sketches, d = r = 64, p = 4) runs on MFMA
  * (psf_bwd_kernel_path == 3; bf16 operands, fp32 accumulation, g and
  * the in-block weights rounded to bf16 like the forward pass rounds its weights; the learned
  * networks' layers take fp16 activations like the forward kernel, their gradients bf16);

@@ -64,8 +64,8 @@ psf_status general_attn_bwd(const Problem &pb, const void *Q, const void *K, con
 psf_status general_sketch_bwd(const Problem &pb, const void *X, const void *G, const float *dM,
                               const float *direct, void *dX, hipStream_t s);
 
-// Backward pass on MFMA (bf16, d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0; random sketches
-// with either in-block rule (Section 3.1's for r = 64), learned sketches with exact in-block weights).
+// Backward pass on MFMA (bf16, d = dv in {64, 128}, p in {4, 8}, r in {32, 64}, b % 256 == 0, exact
+// in-block weights; for d = 64 and p = 4 also Section 3.1's in-block rule (r = 64) and learned sketches).
 bool mfma_bwd_supported(const Problem &pb);
 size_t mfma_bwd_workspace_bytes(const Problem &pb);
 // saved / O_saved: what mfma_attn_fwd_save left and the output it wrote (skips the forward pass

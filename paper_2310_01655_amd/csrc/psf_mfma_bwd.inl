@@ -1,4 +1,4 @@
-// Backward pass on MFMA (bf16 storage, d = dv = 64, p = 4, r in {32, 64}, b % 256 == 0).
+// Backward pass on MFMA (bf16 storage, d = dv in {64, 128}, p in {4, 8}, r in {32, 64}, b % 256 == 0).
 // Included inside the anonymous namespace of psf_mfma.hip, after the forward kernels it reuses.
 //
 // Gradient of the forward function of Sections 3, 3.1, 3.2 (the paper prints no formula; this is
@@ -13,7 +13,8 @@
 //     dm(k_j)[e] = 2 sum_{b,c} R_l[e,b,c] m(k_j)[b] v_j[c]  +  2 (Rc_l m(k_j))[e]
 //     dV_j      +=   phi'(k_j)^T R_l            (the forward cross-block product with R in place of Z)
 // where S_l / Rc_l are the ones-column parts of the states.  Finally dq_i += J_m(q_i)^T dm(q_i)
-// through Algorithm 1 (p = 4: m = sqrt(1/r) (x G1) * (x G2)).
+// through Algorithm 1 (p = 4: m = sqrt(1/r) (x G1) * (x G2), inside k_bwd_dm at d = 64; d = 128 and
+// p = 8 (one more level of the recursion): k_bwd_sketch_rows).
 
 template <int E>
 __device__ __forceinline__ float pow_n(float x)
