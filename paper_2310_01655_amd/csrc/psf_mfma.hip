@@ -2609,6 +2609,9 @@ psf_status launch_sketch(const Problem &pb, const void *X, const bf16_t *Gt, boo
     return PSF_OK;
 }
 
+// The symmetric deal of the state kernel at d = 128, r = 64: ten workgroups per unit instead of
+// sixteen with the same work each (config 5: 0.285 -> 0.254 ms for the state stage).
+constexpr bool kSymWide = true;
 // Running prefix states of (M8, V8) for every unit, snapshots into Zg.
 template <int D, int R>
 psf_status launch_state(const Problem &pb, const float *M8, const bf16_t *V8, bf16_t *Zg, hipStream_t s)
@@ -2635,6 +2638,10 @@ psf_status launch_state(const Problem &pb, const float *M8, const bf16_t *V8, bf
                 hipLaunchKernelGGL((k_state<R, D, 2, true, 32, 2>), dim3(grid_sym), dim3(kWg), 0, s, M8, V8, Zg,
                                    pb.n, pb.b, pb.t, pb.units);
         }
+    } else if (D == 128 && R == 64 && kSymWide) {
+        if constexpr (D == 128 && R == 64)
+            hipLaunchKernelGGL((k_state<R, D, 2, true, 64, 1>), dim3(grid_sym), dim3(kWg), 0, s, M8, V8, Zg, pb.n, pb.b,
+                               pb.t, pb.units);
     } else if constexpr (!(D == 64 && R == 64)) {
         constexpr int NA = (D == 64) ? 4 : 2;
         constexpr int AG = NA * 4 / (R / 32);
