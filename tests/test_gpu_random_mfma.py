@@ -85,13 +85,17 @@ def test_mfma_forward_random_descriptor(seed):
     print(c, assert_close(got[:, :, rows], want, "bf16", "mfma forward %s" % c))
 
 
-@pytest.mark.parametrize("seed", range(6000, 6008))
+@pytest.mark.parametrize("seed", list(range(6000, 6008)) + list(range(6100, 6112)))
 def test_mfma_backward_random_descriptor(seed):
     rng = np.random.default_rng(seed)
     c = dict(batch=1, heads=int(rng.integers(1, 3)), b=int(rng.choice([256, 512])), d=64, p=4,
              r=int(rng.choice([32, 64])), per_head=bool(rng.integers(0, 2)), learned=False)
     c["n"] = c["b"] * int(rng.integers(1, 4))
     c["local"] = int(rng.choice([psf.LOCAL_EXACT, psf.LOCAL_SKETCH])) if c["r"] == 64 else psf.LOCAL_EXACT
+    if seed >= 6100:                              # head width 128 and degree 8 (exact in-block weights)
+        c["d"], c["p"] = int(rng.choice([64, 128, 128])), int(rng.choice([4, 8, 8]))
+        if (c["d"], c["p"]) != (64, 4):
+            c["local"] = psf.LOCAL_EXACT
     q, k, v, G, desc = draw_inputs(c, seed)
     assert psf.bwd_kernel_path(desc) == 3, c
     dO = inputs.make_dout(c["batch"], c["heads"], c["n"], c["d"], seed=seed, dtype="bf16")
