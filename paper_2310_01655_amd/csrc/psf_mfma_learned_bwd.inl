@@ -799,10 +799,20 @@ __global__ __launch_bounds__(kWg) void k_learned_bwd_reduce(const float *__restr
     if (idx >= blob_len) return;
     const int step = per_head ? heads : 1;
     float sum = 0.f;
+    // (the additions keep their order; the loads of up to eight slices are in flight together)
     for (int side = 0; side < 2; ++side)
-        for (int u = per_head ? set : 0; u < units; u += step)
-            for (int k = 0; k < per_unit; ++k)
-                sum += part[(((size_t)side * units + u) * per_unit + k) * blob_len + idx];
+        for (int u = per_head ? set : 0; u < units; u += step) {
+            const float *src = part + (((size_t)side * units + u) * per_unit) * blob_len + idx;
+            int k = 0;
+            for (; k + 8 <= per_unit; k += 8) {
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = src[(size_t)(k + j) * blob_len];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) sum += v[j];
+            }
+            for (; k < per_unit; ++k) sum += src[(size_t)k * blob_len];
+        }
     dG[(size_t)set * blob_len + idx] = sum;
 }
 
