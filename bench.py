@@ -149,6 +149,20 @@ def bwd_stage_flops_mfma(cfg, learned=False):
     return f
 
 
+# HBM bytes per step and stage of the MFMA backward pass (Gaussian sketches, exact in-block weights),
+# from rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 summed over the stage's kernels
+# (profiles/config3_backward_mfma_kernel_trace.md, profiles/config5_backward_mfma_kernel_trace.md)
+MIB = 1048576
+BWD_MEASURED_TRAFFIC_BYTES = {
+    ("config3", "forward_again"): 2722 * MIB, ("config3", "g_c_and_layouts"): 1638 * MIB,
+    ("config3", "mirror_states"): 2398 * MIB, ("config3", "in_block_and_dv"): 2675 * MIB,
+    ("config3", "cross_block_and_sketch_gradient"): 2042 * MIB,
+    ("config5", "forward_again"): 1695 * MIB, ("config5", "g_c_and_layouts"): 1088 * MIB,
+    ("config5", "mirror_states"): 2551 * MIB, ("config5", "in_block_and_dv"): 1905 * MIB,
+    ("config5", "cross_block_and_sketch_gradient"): 1999 * MIB,
+}
+
+
 def cpu_baseline_bwd(cfg, q, k, v, G, dO):
     """The float64 gradient oracle (O(n^2) pair loop) on `cores` units; sequences longer than
     8192 are cut to their first 8192 tokens (a prefix of a causal sequence is a smaller instance
@@ -218,7 +232,9 @@ def run_backward(args, cfg, psf, inputs, torch, q, k, v, G, idx):
         "stage_ms": {nm: round(ms, 4) for nm, ms in acc.items()},
         "tflops": fl["total"] / (ms_per_step * 1e-3) / 1e12,
         "roofline": {"kernel": dom, "bound": "mfma" if mfma else "alu", "achieved": achieved, "peak": peak,
-                     "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                     "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": (BWD_MEASURED_TRAFFIC_BYTES.get((args.workload, dom))
+                                 if mfma and not args.learned and not args.local_sketch else None),
                      "per_stage_tflops": {nm: fl[nm] / (acc[nm] * 1e-3) / 1e12 for nm in acc}},
     }
     if args.learned:
