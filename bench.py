@@ -251,9 +251,10 @@ def run_train(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     dev = torch.device("cuda:0")
     dO = inputs.make_dout(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], seed=1000 + idx, dtype=cfg["dtype"])
     desc = psf.make_desc(cfg["batch"], cfg["heads"], cfg["n"], cfg["d"], cfg["p"], cfg["r"], cfg["b"],
-                         cfg["dtype"], per_head=cfg["per_head"])
+                         cfg["dtype"], per_head=cfg["per_head"], learned=args.learned)
     if psf.bwd_kernel_path(desc) != 3:
-        sys.exit("--pass train needs a workload the MFMA backward kernels cover (config2, config3, d = 64 sweep points)")
+        sys.exit("--pass train needs a workload the MFMA backward kernels cover (config2, config3, config5, the sweep points; "
+                 "with --learned: d = 64, p = 4)")
     qd, kd, vd, Gd, dOd = (x.to(dev) for x in (q, k, v, G, dO))
     ws = psf.alloc_bwd_workspace(desc, dev)
     save = torch.empty(psf.fwd_save_bytes(desc), dtype=torch.uint8, device=dev)
@@ -261,9 +262,12 @@ def run_train(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     grads = (torch.empty_like(qd), torch.empty_like(kd), torch.empty_like(vd))
     stream = torch.cuda.current_stream()
 
+    # learned sketches: the call that also returns the gradient of the networks' parameters
+    bwd = psf.psf_causal_attn_bwd_saved_learned if args.learned else psf.psf_causal_attn_bwd_saved
+
     def step():
         psf.psf_causal_attn_fwd_save(desc, qd, kd, vd, Gd, O=O, save=save, stream=stream)
-        psf.psf_causal_attn_bwd_saved(desc, qd, kd, vd, Gd, O, dOd, save, workspace=ws, stream=stream, out=grads)
+        bwd(desc, qd, kd, vd, Gd, O, dOd, save, workspace=ws, stream=stream, out=grads)
 
     ramp_steps = ramp(step, args.ramp_ms, torch)
     for _ in range(args.warmup):
@@ -275,7 +279,7 @@ def run_train(args, cfg, psf, inputs, torch, q, k, v, G, idx):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
-    fb = bwd_stage_flops_mfma(cfg)
+    fb = bwd_stage_flops_mfma(cfg, learned=args.learned)
     total = fb["total"]                                     # forward once + the backward stages
     tfl = total / (ms_per_step * 1e-3) / 1e12
     out = {
@@ -286,12 +290,13 @@ def run_train(args, cfg, psf, inputs, torch, q, k, v, G, idx):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": args.workload, "pass": "train (forward with saved states + backward)",
                    "batch": cfg["batch"], "heads": cfg["heads"], "n": cfg["n"], "d": cfg["d"], "p": cfg["p"],
-                   "r": cfg["r"], "b": cfg["b"], "kernel_path": "mfma_bf16"},
+                   "r": cfg["r"], "b": cfg["b"], "sketch": "learned" if args.learned else "gaussian",
+                   "kernel_path": "mfma_bf16"},
         "tflops": tfl,
         "roofline": {"kernel": "whole step", "bound": "mfma", "achieved": tfl, "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": tfl / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.learned:
         out["cpu_baseline"] = cpu_baseline_bwd(cfg, q, k, v, G, dO)
         out["cpu_baseline"]["sample"] += "; gradient only, the oracle's forward is inside it"
     print(json.dumps(out))

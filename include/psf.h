@@ -266,9 +266,11 @@ psf_status psf_causal_attn_bwd_learned(const psf_desc *desc, const void *Q, cons
  * psf_causal_attn_bwd_saved takes that buffer untouched since, the same Q, K, V, G and the O the
  * forward call wrote, and returns the same gradients as psf_causal_attn_bwd (bit for bit).
  * workspace: psf_bwd_workspace_bytes(desc) as for psf_causal_attn_bwd.  Available where
- * psf_bwd_kernel_path(desc) == 3 with random sketches; elsewhere (learned sketches included)
- * psf_fwd_save_bytes is 0 and both calls return PSF_ERR_UNSUPPORTED (use psf_causal_attn_fwd /
- * psf_causal_attn_bwd there).
+ * psf_bwd_kernel_path(desc) == 3; elsewhere psf_fwd_save_bytes is 0 and the calls return
+ * PSF_ERR_UNSUPPORTED (use psf_causal_attn_fwd / psf_causal_attn_bwd there).
+ * psf_causal_attn_bwd_saved_learned: the same for desc->learned = 1 with the gradient of the
+ * networks' parameters as one more output (dG as for psf_causal_attn_bwd_learned, whose result it
+ * equals bit for bit); psf_causal_attn_bwd_saved itself treats the parameters as constants.
  */
 size_t psf_fwd_save_bytes(const psf_desc *desc);
 psf_status psf_causal_attn_fwd_save(const psf_desc *desc, const void *Q, const void *K, const void *V,
@@ -278,6 +280,10 @@ psf_status psf_causal_attn_bwd_saved(const psf_desc *desc, const void *Q, const 
                                      const void *G, const void *O, const void *dO, void *dQ, void *dK,
                                      void *dV, void *save, size_t save_bytes, void *workspace,
                                      size_t workspace_bytes, void *hip_stream);
+psf_status psf_causal_attn_bwd_saved_learned(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                             const void *G, const void *O, const void *dO, void *dQ, void *dK,
+                                             void *dV, float *dG, void *save, size_t save_bytes, void *workspace,
+                                             size_t workspace_bytes, void *hip_stream);
 
 /*
  * Token-by-token evaluation (the recurrent form behind the paper's remark, Section 5, that the

@@ -5,8 +5,8 @@ the forward state for the backward pass (psf_fwd_save_bytes(desc) > 0), psf_caus
 elsewhere; the backward is psf_causal_attn_bwd_saved / psf_causal_attn_bwd.  The Gaussian
 sketch matrices G are constants of the layer (Algorithm 1 draws them once): they receive no
 gradient.  With learned sketches (Algorithm 2) G holds the networks' parameters, which are
-trained with the model: when G requires a gradient the backward is psf_causal_attn_bwd_learned
-and G receives the parameter gradient (accumulated in fp32 by the library, returned in G's dtype).
+trained with the model: when G requires a gradient the backward is
+psf_causal_attn_bwd_saved_learned / psf_causal_attn_bwd_learned and G receives the parameter gradient (accumulated in fp32 by the library, returned in G's dtype).
 """
 import torch
 
@@ -34,7 +34,11 @@ class _CausalPolysketchAttention(torch.autograd.Function):
         dO = dO.contiguous()
         stream = torch.cuda.current_stream(Q.device)
         if ctx.g_grad:
-            dQ, dK, dV, dG = psf.psf_causal_attn_bwd_learned(ctx.desc, Q, K, V, G, dO, stream=stream)
+            if ctx.save is not None:
+                dQ, dK, dV, dG = psf.psf_causal_attn_bwd_saved_learned(ctx.desc, Q, K, V, G, O, dO, ctx.save,
+                                                                       stream=stream)
+            else:
+                dQ, dK, dV, dG = psf.psf_causal_attn_bwd_learned(ctx.desc, Q, K, V, G, dO, stream=stream)
             return dQ, dK, dV, dG.to(G.dtype), None
         if ctx.save is not None:
             dQ, dK, dV = psf.psf_causal_attn_bwd_saved(ctx.desc, Q, K, V, G, O, dO, ctx.save, stream=stream)

@@ -22,7 +22,7 @@ EXPORTS = ("psf_check_desc", "psf_kernel_path", "psf_fwd_beside_states", "psf_wo
            "psf_causal_attn_fwd", "psf_causal_attn_fwd_static", "psf_causal_attn_fwd_timed", "psf_stage_name",
            "psf_status_string", "psf_noncausal_workspace_bytes", "psf_noncausal_attn_fwd",
            "psf_noncausal_attn_fwd_timed", "psf_fwd_save_bytes", "psf_causal_attn_fwd_save",
-           "psf_causal_attn_bwd_saved", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
+           "psf_causal_attn_bwd_saved", "psf_causal_attn_bwd_saved_learned", "psf_bwd_kernel_path", "psf_bwd_workspace_bytes", "psf_causal_attn_bwd",
            "psf_causal_attn_bwd_learned",
            "psf_causal_attn_bwd_timed", "psf_decode_state_bytes", "psf_decode_reset",
            "psf_decode_step", "psf_decode_prefill_workspace_bytes", "psf_decode_prefill", "psf_probe_mfma_loop")
@@ -88,6 +88,8 @@ def lib():
         L.psf_causal_attn_fwd_save.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         L.psf_causal_attn_bwd_saved.restype = ctypes.c_int
         L.psf_causal_attn_bwd_saved.argtypes = [dp] + [vp] * 9 + [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
+        L.psf_causal_attn_bwd_saved_learned.restype = ctypes.c_int
+        L.psf_causal_attn_bwd_saved_learned.argtypes = [dp] + [vp] * 10 + [vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
         L.psf_bwd_kernel_path.restype = ctypes.c_int
         L.psf_bwd_kernel_path.argtypes = [dp]
         L.psf_bwd_workspace_bytes.restype = ctypes.c_size_t
@@ -333,23 +335,40 @@ def psf_causal_attn_fwd_save(desc, Q, K, V, G, O=None, save=None, stream=None):
     return O, save
 
 
-def psf_causal_attn_bwd_saved(desc, Q, K, V, G, O, dO, save, workspace=None, stream=None, out=None):
-    """Backward pass from the buffer psf_causal_attn_fwd_save left; returns (dQ, dK, dV)."""
+def _bwd_saved(desc, Q, K, V, G, O, dO, save, workspace, stream, out, learned):
     B, H, n, d, dv = desc.batch, desc.heads, desc.n, desc.d, desc.dv
     if workspace is None:
         workspace = alloc_bwd_workspace(desc, Q.device)
     dQ, dK, dV = out if out is not None else (torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V))
     gs = _g_shape(desc)
-    st = lib().psf_causal_attn_bwd_saved(
-        ctypes.byref(desc), _dev_ptr(Q, desc, (B, H, n, d), "Q"), _dev_ptr(K, desc, (B, H, n, d), "K"),
-        _dev_ptr(V, desc, (B, H, n, dv), "V"), _dev_ptr(G, desc, gs, "G") if gs else None,
-        _dev_ptr(O, desc, (B, H, n, dv), "O"), _dev_ptr(dO, desc, (B, H, n, dv), "dO"),
-        _dev_ptr(dQ, desc, (B, H, n, d), "dQ"), _dev_ptr(dK, desc, (B, H, n, d), "dK"),
-        _dev_ptr(dV, desc, (B, H, n, dv), "dV"), ctypes.c_void_p(save.data_ptr()), ctypes.c_size_t(save.numel()),
-        ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel()), _stream_ptr(stream))
+    ptrs = [_dev_ptr(Q, desc, (B, H, n, d), "Q"), _dev_ptr(K, desc, (B, H, n, d), "K"),
+            _dev_ptr(V, desc, (B, H, n, dv), "V"), _dev_ptr(G, desc, gs, "G") if gs else None,
+            _dev_ptr(O, desc, (B, H, n, dv), "O"), _dev_ptr(dO, desc, (B, H, n, dv), "dO"),
+            _dev_ptr(dQ, desc, (B, H, n, d), "dQ"), _dev_ptr(dK, desc, (B, H, n, d), "dK"),
+            _dev_ptr(dV, desc, (B, H, n, dv), "dV")]
+    tail = [ctypes.c_void_p(save.data_ptr()), ctypes.c_size_t(save.numel()),
+            ctypes.c_void_p(workspace.data_ptr()), ctypes.c_size_t(workspace.numel()), _stream_ptr(stream)]
+    if not learned:
+        st = lib().psf_causal_attn_bwd_saved(ctypes.byref(desc), *ptrs, *tail)
+        if st != PSF_OK:
+            raise PsfError(st, "psf_causal_attn_bwd_saved")
+        return dQ, dK, dV
+    dG = torch.empty(gs if gs else (1,), dtype=torch.float32, device=Q.device)
+    st = lib().psf_causal_attn_bwd_saved_learned(ctypes.byref(desc), *ptrs, ctypes.c_void_p(dG.data_ptr()), *tail)
     if st != PSF_OK:
-        raise PsfError(st, "psf_causal_attn_bwd_saved")
-    return dQ, dK, dV
+        raise PsfError(st, "psf_causal_attn_bwd_saved_learned")
+    return dQ, dK, dV, dG
+
+
+def psf_causal_attn_bwd_saved(desc, Q, K, V, G, O, dO, save, workspace=None, stream=None, out=None):
+    """Backward pass from the buffer psf_causal_attn_fwd_save left; returns (dQ, dK, dV)."""
+    return _bwd_saved(desc, Q, K, V, G, O, dO, save, workspace, stream, out, False)
+
+
+def psf_causal_attn_bwd_saved_learned(desc, Q, K, V, G, O, dO, save, workspace=None, stream=None, out=None):
+    """The same with learned sketches and the gradient of the networks' parameters; returns
+    (dQ, dK, dV, dG) with dG fp32 of G's shape."""
+    return _bwd_saved(desc, Q, K, V, G, O, dO, save, workspace, stream, out, True)
 
 
 def bwd_kernel_path(desc):

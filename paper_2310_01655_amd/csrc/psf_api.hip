@@ -356,7 +356,7 @@ psf_status psf_noncausal_attn_fwd_timed(const psf_desc *desc, const void *Q, con
 size_t psf_fwd_save_bytes(const psf_desc *desc)
 {
     Problem pb;
-    if (make_problem(desc, &pb) != PSF_OK || !general_bwd_supported(pb) || !bwd_on_mfma(pb) || pb.learned) return 0;
+    if (make_problem(desc, &pb) != PSF_OK || !general_bwd_supported(pb) || !bwd_on_mfma(pb)) return 0;
     return mfma_fwd_save_bytes(pb);
 }
 
@@ -366,7 +366,7 @@ psf_status psf_causal_attn_fwd_save(const psf_desc *desc, const void *Q, const v
     Problem pb;
     psf_status st = make_problem(desc, &pb);
     if (st != PSF_OK) return st;
-    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb) || pb.learned) return PSF_ERR_UNSUPPORTED;
+    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb)) return PSF_ERR_UNSUPPORTED;
     if (!Q || !K || !V || !O || !save) return PSF_ERR_NULL;
     if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
     if (save_bytes < mfma_fwd_save_bytes(pb) || ((uintptr_t)save & 255u) != 0) return PSF_ERR_WORKSPACE;
@@ -374,21 +374,40 @@ psf_status psf_causal_attn_fwd_save(const psf_desc *desc, const void *Q, const v
     return mfma_attn_fwd_save(pb, Q, K, V, G, O, save, (hipStream_t)hip_stream, nullptr);
 }
 
-psf_status psf_causal_attn_bwd_saved(const psf_desc *desc, const void *Q, const void *K, const void *V,
-                                     const void *G, const void *O, const void *dO, void *dQ, void *dK,
-                                     void *dV, void *save, size_t save_bytes, void *workspace,
-                                     size_t workspace_bytes, void *hip_stream)
+static psf_status run_bwd_saved(const psf_desc *desc, const void *Q, const void *K, const void *V, const void *G,
+                                const void *O, const void *dO, void *dQ, void *dK, void *dV, float *dG, void *save,
+                                size_t save_bytes, void *workspace, size_t workspace_bytes, void *hip_stream)
 {
     Problem pb;
     psf_status st = make_problem(desc, &pb);
     if (st != PSF_OK) return st;
-    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb) || pb.learned) return PSF_ERR_UNSUPPORTED;
+    if (!general_bwd_supported(pb) || !bwd_on_mfma(pb)) return PSF_ERR_UNSUPPORTED;
+    if (dG && !pb.learned) return PSF_ERR_UNSUPPORTED;
     if (!Q || !K || !V || !O || !dO || !dQ || !dK || !dV || !save || !workspace) return PSF_ERR_NULL;
     if (pb.g_len > 0 && !G) return PSF_ERR_NULL;
     if (save_bytes < mfma_fwd_save_bytes(pb) || ((uintptr_t)save & 255u) != 0) return PSF_ERR_WORKSPACE;
     if (workspace_bytes < mfma_bwd_workspace_bytes(pb) || ((uintptr_t)workspace & 255u) != 0) return PSF_ERR_WORKSPACE;
     if (!aligned16({Q, K, V, G, O, dO, dQ, dK, dV})) return PSF_ERR_ALIGNMENT;
-    return mfma_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, workspace, (hipStream_t)hip_stream, nullptr, save, O);
+    return mfma_attn_bwd(pb, Q, K, V, G, dO, dQ, dK, dV, workspace, (hipStream_t)hip_stream, nullptr, save, O, dG);
+}
+
+psf_status psf_causal_attn_bwd_saved(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                     const void *G, const void *O, const void *dO, void *dQ, void *dK,
+                                     void *dV, void *save, size_t save_bytes, void *workspace,
+                                     size_t workspace_bytes, void *hip_stream)
+{
+    return run_bwd_saved(desc, Q, K, V, G, O, dO, dQ, dK, dV, nullptr, save, save_bytes, workspace, workspace_bytes,
+                         hip_stream);
+}
+
+psf_status psf_causal_attn_bwd_saved_learned(const psf_desc *desc, const void *Q, const void *K, const void *V,
+                                             const void *G, const void *O, const void *dO, void *dQ, void *dK,
+                                             void *dV, float *dG, void *save, size_t save_bytes, void *workspace,
+                                             size_t workspace_bytes, void *hip_stream)
+{
+    if (!dG) return PSF_ERR_NULL;
+    return run_bwd_saved(desc, Q, K, V, G, O, dO, dQ, dK, dV, dG, save, save_bytes, workspace, workspace_bytes,
+                         hip_stream);
 }
 
 int psf_bwd_kernel_path(const psf_desc *desc)

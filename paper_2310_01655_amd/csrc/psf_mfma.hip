@@ -2953,11 +2953,28 @@ psf_status mfma_attn_bwd(const Problem &pb, const void *Q, const void *K, const 
 
 size_t mfma_fwd_save_bytes(const Problem &pb) { return carve_saved(pb, nullptr).total; }
 
+namespace {
+template <int D, int R, int P>
+psf_status fwd_save_impl(const Problem &pb, const void *Q, const void *K, const void *V, const void *G, void *O,
+                         const MfmaSaved &sv, hipStream_t s, StageTimer *tm)
+{
+    psf_status st = attn_impl<D, R, P>(pb, Q, K, V, G, O, sv.fwd, s, tm, sv.Den, sv.MK);
+    if (st != PSF_OK || !pb.learned) return st;
+    // (the learned key-side sketch kernel writes the state kernel's octets only)
+    if (!learned_on_mfma(pb)) return PSF_ERR_UNSUPPORTED;
+    const size_t count4 = (size_t)pb.units * pb.n * R / 4;
+    hipLaunchKernelGGL((k_octets_to_rows<R>), dim3((unsigned)((count4 + kWg - 1) / kWg)), dim3(kWg), 0, s,
+                       carve(pb, sv.fwd).MK8, sv.MK, count4);
+    PSF_LAUNCH_CHECK();
+    return PSF_OK;
+}
+}  // namespace
+
 psf_status mfma_attn_fwd_save(const Problem &pb, const void *Q, const void *K, const void *V, const void *G,
                               void *O, void *saved, hipStream_t s, StageTimer *tm)
 {
     const MfmaSaved sv = carve_saved(pb, saved);
-#define PSF_AT(D_, R_, P_) (attn_impl<D_, R_, P_>(pb, Q, K, V, G, O, sv.fwd, s, tm, sv.Den, sv.MK))
+#define PSF_AT(D_, R_, P_) (fwd_save_impl<D_, R_, P_>(pb, Q, K, V, G, O, sv, s, tm))
     PSF_BWD_DISPATCH(PSF_AT);
 #undef PSF_AT
 }

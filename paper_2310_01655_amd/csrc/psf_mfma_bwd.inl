@@ -1078,7 +1078,7 @@ psf_status attn_bwd_impl(const Problem &pb, const void *Q, const void *K, const 
     const bool ls = !pb.local_exact;
     if (ls && !(R == D && P == 4)) return PSF_ERR_UNSUPPORTED;
     if (pb.learned && !(D == 64 && P == 4)) return PSF_ERR_UNSUPPORTED;
-    if (pb.learned && (ls || saved)) return PSF_ERR_UNSUPPORTED;
+    if (pb.learned && ls) return PSF_ERR_UNSUPPORTED;
     psf_status st;
     if (saved) {
         const MfmaSaved sv = carve_saved(pb, saved);

@@ -110,6 +110,26 @@ def test_learned_backward_mfma_eight_units():
     run_case(4, 2, 256, 64, 64, 4, 32, 256, "bf16", per_head=True, path=3)
 
 
+def test_learned_backward_mfma_from_the_saved_forward():
+    """psf_causal_attn_fwd_save + psf_causal_attn_bwd_saved_learned: the same bits as the recomputing
+    call (the saving forward runs the launches the recomputation runs); psf_causal_attn_bwd_saved
+    treats the parameters as constants."""
+    desc, args, (dQ, dK, dV, dG) = run_case(2, 2, 512, 64, 64, 4, 32, 256, "bf16", path=3)
+    q, k, v, P, dO = args
+    assert psf.fwd_save_bytes(desc) > 0
+    O, save = psf.psf_causal_attn_fwd_save(desc, q, k, v, P)
+    got = psf.psf_causal_attn_bwd_saved_learned(desc, q, k, v, P, O, dO, save)
+    rows = psf.psf_causal_attn_bwd_saved(desc, q, k, v, P, O, dO, save)
+    O_plain = psf.psf_causal_attn_fwd(desc, q, k, v, P)
+    torch.cuda.synchronize()
+    for a, c in zip(got, (dQ, dK, dV, dG)):
+        assert torch.equal(a, c)
+    for a, c in zip(rows, (dQ, dK, dV)):
+        assert torch.equal(a, c)
+    from parity import assert_close
+    assert_close(O.float().cpu().numpy(), O_plain.float().cpu().numpy(), "bf16", "saving forward against plain forward")
+
+
 def test_learned_backward_mfma_rows_only_and_repeat():
     desc, args, (dQ, dK, dV, dG) = run_case(1, 2, 512, 64, 64, 4, 64, 256, "bf16", path=3)
     rQ, rK, rV = psf.psf_causal_attn_bwd(desc, *args)
