@@ -105,6 +105,12 @@ def test_learned_backward_mfma(batch, heads, n, r, b, per_head):
     run_case(batch, heads, n, 64, 64, 4, r, b, "bf16", per_head=per_head, path=3)
 
 
+def test_learned_backward_mfma_several_slices_per_unit():
+    # 2048 rows per unit: the parameter kernel works on four slices of 512 rows per unit, every
+    # one with its own part of the sums (all rows carry a gradient here)
+    run_case(1, 2, 2048, 64, 64, 4, 64, 512, "bf16", per_head=True, path=3)
+
+
 def test_learned_backward_mfma_eight_units():
     # eight units: the parameter kernel's XCD-aware workgroup order
     run_case(4, 2, 256, 64, 64, 4, 32, 256, "bf16", per_head=True, path=3)
