@@ -220,7 +220,7 @@ __global__ __launch_bounds__(512, 1) void k_learned_bwd_rows(const bf16_t *__res
             for (int s = 0; s < KS; ++s) acc = OpA::mfma(*(const a8 *)(sl + ((s * 32 + x) * 2 + h) * 16), xfr[s], acc);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const float hv = gelu_fast(acc[v]);
+                const float hv = gelu_poly(acc[v]);
                 sh += hv;
                 sqh += hv * hv;
                 acc[v] = hv;
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(512, 1) void k_learned_bwd_rows(const bf16_t *__res
 #pragma unroll
             for (int t = 0; t < RS; ++t) acc = OpA::mfma(*(const a8 *)(sl + ((t * 32 + x) * 2 + h) * 16), h2f[net][t], acc);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = gelu_fast(acc[v]);
+            for (int v = 0; v < 16; ++v) acc[v] = gelu_poly(acc[v]);
             const a8 hf0 = ls_cvt_from16<OpA>(acc, 0), hf1 = ls_cvt_from16<OpA>(acc, 8);
 #pragma unroll
             for (int ot = 0; ot < OT; ++ot) {
