@@ -108,3 +108,33 @@ def test_mfma_backward_random_descriptor(seed):
     for name, got, want in (("dQ", dQ, wQ), ("dK", dK, wK), ("dV", dV, wV)):
         assert_close_scaled(got.float().cpu().numpy(), want, "bf16", "%s %s" % (name, c))
     print(c)
+
+
+@pytest.mark.parametrize("seed", range(6200, 6208))
+def test_mfma_learned_backward_random_descriptor(seed):
+    """Learned sketches of degree 4 on the MFMA kernels: gradients with respect to Q, K, V in full
+    and the parameter gradient of every set (summed over the units that share it)."""
+    rng = np.random.default_rng(seed)
+    c = dict(batch=int(rng.integers(1, 3)), heads=int(rng.integers(1, 4)), b=int(rng.choice([256, 512])), d=64, p=4,
+             r=32 if seed % 2 else 64, per_head=bool((seed // 2) % 2), learned=True, local=psf.LOCAL_EXACT)
+    c["n"] = c["b"] * int(rng.integers(2, 5))       # at least two blocks: the sketches carry a gradient
+    q, k, v, G, desc = draw_inputs(c, seed)
+    assert psf.bwd_kernel_path(desc) == 3, c
+    dO = inputs.make_dout(c["batch"], c["heads"], c["n"], c["d"], seed=seed, dtype="bf16")
+    dev = torch.device("cuda:0")
+    dQ, dK, dV, dG = psf.psf_causal_attn_bwd_learned(desc, *[t.to(dev) for t in (q, k, v, G, dO)])
+    torch.cuda.synchronize()
+    wQ, wK, wV = (np.empty(tuple(t.shape)) for t in (q, k, v))
+    wG = np.zeros(tuple(G.shape))
+    for bi in range(c["batch"]):
+        for h in range(c["heads"]):
+            s = h if G.shape[0] > 1 else 0
+            wQ[bi, h], wK[bi, h], wV[bi, h], dp = oracle.attn_bwd_learned(
+                as_f64(q[bi, h]), as_f64(k[bi, h]), as_f64(v[bi, h]), as_f64(G[s]), as_f64(dO[bi, h]), c["p"], c["r"],
+                c["b"], local=oracle.LOCAL_EXACT)
+            wG[s] += dp
+    for name, got, want in (("dQ", dQ, wQ), ("dK", dK, wK), ("dV", dV, wV)):
+        assert_close_scaled(got.float().cpu().numpy(), want, "bf16", "%s %s" % (name, c))
+    for s in range(G.shape[0]):
+        assert_close_scaled(dG[s].cpu().numpy(), wG[s], "bf16", "dG set %d %s" % (s, c))
+    print(c)
