@@ -315,6 +315,8 @@ __global__ __launch_bounds__(512, 1) void k_learned_bwd_rows(const bf16_t *__res
             for (int g2 = 0; g2 < 2; ++g2) {
                 const bf16x4 p4 = {f[t][4 * g2], f[t][4 * g2 + 1], f[t][4 * g2 + 2], f[t][4 * g2 + 3]};
                 *(bf16x4 *)&rows_out[row * R + 16 * t + 8 * g2 + 4 * h] = p4;
+                // (the 16-bit pieces are cut from the 32-bit words: a bit cast of single vector elements
+                // stored the first element of every group of four for all four)
                 const uint2 bits = __builtin_bit_cast(uint2, p4);
                 bf16_t *col = tile_out + (tile * R + 16 * t + 8 * g2 + 4 * h) * 32 + x;
                 col[0] = (bf16_t)(bits.x & 0xffffu);
