@@ -96,8 +96,12 @@ __global__ __launch_bounds__(kWg) void k_learned_bwd_prep(const bf16_t *__restri
 }
 
 // What k_learned_bwd_rows leaves for k_learned_bwd_params, per side.  rows = units * n.
-//   XnR [rows][64]            normalised rows x^ (bf16)
-//   XnT [rows/32][64][32]     the same, one tile of 32 rows transposed
+//   XnR [rows/32][64/16][2][32][8]      normalised rows x^ (bf16): tile, k-step, half, row, 8 features
+//                                       16 step + 8 half + e -- what a lane (row, half) feeds an MFMA as a row operand
+//   XnT [rows/32][64/32][2][2][32][8]   the same transposed: tile, feature tile, k-step s2, half, feature, 8 rows
+//                                       16 s2 + 8 (e / 4) + 4 half + e % 4 -- the operand of a lane (feature, half)
+//   (either way a wave's load instruction takes 1 KB in one piece: with plain row-major arrays every
+//   lane touched a cache line of its own and the parameter kernel was bound by the vector L1's line rate)
 //   per network (stride rows * R): A2R / A2T (a2), DOR / DOT (df), DAR / DAT (da2), laid out alike with R features
 //   ST  [net][4][rows] fp32   mean of h1, 1 / sigma2, m1, m2
 struct LbStage {
@@ -307,22 +311,26 @@ __global__ __launch_bounds__(512, 1) void k_learned_bwd_rows(const bf16_t *__res
             dof[1][2 * ot + 1] = cvt8_from16(d1, 8);
         }
     }
-    // bf16 fragments (k-step t, entries e: feature 16 t + 8 (e / 4) + 4 h + e % 4) as rows and as a transposed tile
+    // bf16 fragments (k-step t, entries e: feature 16 t + 8 (e / 4) + 4 h + e % 4) go out twice, both in
+    // the order the parameter kernel's lanes load them, 1 KB per load instruction in one piece:
+    //   rows   [tile][k-step][half][row 0..31][8]       : feature 16 step + 8 half + e of the row
+    //   tiles  [tile][feature / 32][k-step s2][half][feature % 32][8] : row 16 s2 + 8 (e / 4) + 4 half + e % 4
+    const int tslot = ((x >> 4) * 2 + ((x >> 2) & 1)) * 256 + 4 * ((x >> 3) & 1) + (x & 3);
     auto stage_vec = [&](const bf16x8 (&f)[RS], bf16_t *rows_out, bf16_t *tile_out) {
 #pragma unroll
         for (int t = 0; t < RS; ++t)
 #pragma unroll
             for (int g2 = 0; g2 < 2; ++g2) {
                 const bf16x4 p4 = {f[t][4 * g2], f[t][4 * g2 + 1], f[t][4 * g2 + 2], f[t][4 * g2 + 3]};
-                *(bf16x4 *)&rows_out[row * R + 16 * t + 8 * g2 + 4 * h] = p4;
+                *(bf16x4 *)&rows_out[((tile * RS + t) * 2 + g2) * 256 + x * 8 + 4 * h] = p4;
                 // (the 16-bit pieces are cut from the 32-bit words: a bit cast of single vector elements
                 // stored the first element of every group of four for all four)
                 const uint2 bits = __builtin_bit_cast(uint2, p4);
-                bf16_t *col = tile_out + (tile * R + 16 * t + 8 * g2 + 4 * h) * 32 + x;
+                bf16_t *col = tile_out + (tile * OT + t / 2) * 1024 + tslot + (16 * (t % 2) + 8 * g2 + 4 * h) * 8;
                 col[0] = (bf16_t)(bits.x & 0xffffu);
-                col[32] = (bf16_t)(bits.x >> 16);
-                col[64] = (bf16_t)(bits.y & 0xffffu);
-                col[96] = (bf16_t)(bits.y >> 16);
+                col[8] = (bf16_t)(bits.x >> 16);
+                col[16] = (bf16_t)(bits.y & 0xffffu);
+                col[24] = (bf16_t)(bits.y >> 16);
             }
     };
     if constexpr (STAGE) {
@@ -331,12 +339,12 @@ __global__ __launch_bounds__(512, 1) void k_learned_bwd_rows(const bf16_t *__res
             bf16x8 xb;
 #pragma unroll
             for (int e = 0; e < 8; ++e) xb[e] = (__bf16)(float)xfr[s][e];
-            *(bf16x8 *)&sg.XnR[row * D + 16 * s + 8 * h] = xb;
+            *(bf16x8 *)&sg.XnR[((tile * KS + s) * 2 + h) * 256 + x * 8] = xb;
             const uint4 bits = __builtin_bit_cast(uint4, xb);
             const uint32_t wd[4] = {bits.x, bits.y, bits.z, bits.w};
-            bf16_t *col = sg.XnT + (tile * D + 16 * s + 8 * h) * 32 + x;
+            bf16_t *col = sg.XnT + (tile * DT + s / 2) * 1024 + tslot + (16 * (s % 2) + 8 * h) * 8;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) col[32 * e] = (bf16_t)((wd[e / 2] >> (16 * (e % 2))) & 0xffffu);
+            for (int e = 0; e < 8; ++e) col[8 * e] = (bf16_t)((wd[e / 2] >> (16 * (e % 2))) & 0xffffu);
         }
 #pragma unroll
         for (int net = 0; net < NETS; ++net) {
@@ -595,14 +603,13 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
     const bf16_t *DOR = sg.DOR + (size_t)net * sg.rows * R, *DOT = sg.DOT + (size_t)net * sg.rows * R;
     const bf16_t *DAR = sg.DAR + (size_t)net * sg.rows * R, *DAT = sg.DAT + (size_t)net * sg.rows * R;
     const float *ST = sg.ST + (size_t)net * 4 * sg.rows;
-    // 8 rows of a transposed tile in the accumulator order of k-step s2: 16 s2 + 4 h + {0..3}, + 8
-    auto frag_t = [&](const bf16_t *T, size_t tile, int width, int feature, int s2) {
-        const bf16_t *p = T + (tile * width + feature) * 32 + 16 * s2 + 4 * h;
-        const bf16x4 lo = *(const bf16x4 *)p, hi = *(const bf16x4 *)(p + 8);
-        bf16x8 f;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { f[e] = lo[e]; f[4 + e] = hi[e]; }
-        return f;
+    // 8 rows of a transposed tile in the accumulator order of k-step s2 (16 s2 + 4 h + {0..3}, + 8) of
+    // feature 32 ft + x: one 16-byte piece per lane, the wave's 1 KB in one run
+    auto frag_t = [&](const bf16_t *T, size_t tile, int tiles_wide, int ft, int s2) {
+        return *(const bf16x8 *)&T[((tile * tiles_wide + ft) * 2 + s2) * 512 + (h * 32 + x) * 8];
+    };
+    auto frag_r = [&](const bf16_t *Rw, size_t tile, int steps, int s) {
+        return *(const bf16x8 *)&Rw[((tile * steps + s) * 2 + h) * 256 + x * 8];
     };
 
     // operands of one tile of 32 rows: row fragments (lane = row) of two staged vectors and the
@@ -615,34 +622,34 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
     // wait for, come a tile ahead; the transposed tiles are asked for at the top of their own tile
     // and used at its end)
     auto load_tile = [&](int tl, Tile &o, bool rows_part, bool tiles_part) {
-        const size_t r0 = first + 32 * (size_t)tl, tile = r0 / 32, rw = r0 + x;
+        const size_t tile = (first + 32 * (size_t)tl) / 32;
         if constexpr (HALF == 0) {
             if (rows_part) {
 #pragma unroll
-                for (int s = 0; s < KS; ++s) o.ra[s] = *(const bf16x8 *)&sg.XnR[rw * D + 16 * s + 8 * h];
+                for (int s = 0; s < KS; ++s) o.ra[s] = frag_r(sg.XnR, tile, KS, s);
 #pragma unroll
-                for (int t = 0; t < RS; ++t) o.rb[t] = *(const bf16x8 *)&DAR[rw * R + 16 * t + 8 * h];
+                for (int t = 0; t < RS; ++t) o.rb[t] = frag_r(DAR, tile, RS, t);
             }
             if (tiles_part)
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) {
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) o.ta[dt][s2] = frag_t(sg.XnT, tile, D, 32 * dt + x, s2);
+                for (int dt = 0; dt < DT; ++dt) o.ta[dt][s2] = frag_t(sg.XnT, tile, DT, dt, s2);
 #pragma unroll
-                for (int ot = 0; ot < OT; ++ot) o.tb[ot][s2] = frag_t(DAT, tile, R, 32 * ot + x, s2);
+                for (int ot = 0; ot < OT; ++ot) o.tb[ot][s2] = frag_t(DAT, tile, OT, ot, s2);
             }
         } else {
 #pragma unroll
             for (int t = 0; t < RS; ++t) {
-                o.ra[t] = *(const bf16x8 *)&A2R[rw * R + 16 * t + 8 * h];
-                o.rb[t] = *(const bf16x8 *)&DOR[rw * R + 16 * t + 8 * h];
+                o.ra[t] = frag_r(A2R, tile, RS, t);
+                o.rb[t] = frag_r(DOR, tile, RS, t);
             }
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
                 for (int ot = 0; ot < OT; ++ot) {
-                    o.ta[ot][s2] = frag_t(A2T, tile, R, 32 * ot + x, s2);
-                    o.tb[ot][s2] = frag_t(DOT, tile, R, 32 * ot + x, s2);
+                    o.ta[ot][s2] = frag_t(A2T, tile, OT, ot, s2);
+                    o.tb[ot][s2] = frag_t(DOT, tile, OT, ot, s2);
                 }
         }
     };
