@@ -562,6 +562,10 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
     const int set = per_head ? u % heads : 0;
     const Net nt(P + (size_t)set * p_len + Net::offset_of(net, 4), 64);
 
+    // HALF 0: the four statistics of a tile's 32 rows, per wave (every lane needs those of the
+    // rows of its accumulator registers, the same for 32 lanes: as global loads those cost a
+    // cache access per lane, through workgroup memory one broadcast read)
+    __shared__ __attribute__((aligned(16))) float stl[HALF == 0 ? 4 : 1][128];
     // this chunk's weights as B operands (lane = hidden unit, 8 consecutive contraction indices)
     bf16x8 wa[HALF == 0 ? KS : RS], wb[RS];                // HALF 0: g1 . W1, W2;  HALF 1: W3, W4
     if constexpr (HALF == 0) {
@@ -617,6 +621,7 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
     struct Tile {
         bf16x8 ra[HALF == 0 ? KS : RS], rb[RS];            // HALF 0: x^, da2;  HALF 1: a2, df
         bf16x8 ta[NA][2], tb[OT][2];                       // HALF 0: x^ tiles, da2 tiles;  HALF 1: a2 tiles, df tiles
+        float st[2];                                       // HALF 0: statistics h and 2 + h of row x
     };
     // (HALF 0 is short of registers: there only the row fragments, which the tile's first products
     // wait for, come a tile ahead; the transposed tiles are asked for at the top of their own tile
@@ -629,6 +634,8 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
                 for (int s = 0; s < KS; ++s) o.ra[s] = frag_r(sg.XnR, tile, KS, s);
 #pragma unroll
                 for (int t = 0; t < RS; ++t) o.rb[t] = frag_r(DAR, tile, RS, t);
+                o.st[0] = ST[(size_t)h * sg.rows + tile * 32 + x];
+                o.st[1] = ST[(size_t)(2 + h) * sg.rows + tile * 32 + x];
             }
             if (tiles_part)
 #pragma unroll
@@ -658,7 +665,6 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
     load_tile(0, cur, true, HALF == 1);
 #pragma unroll 1
     for (int tl = 0; tl < n_tiles; ++tl) {
-        const size_t r0 = first + 32 * (size_t)tl;
         if constexpr (HALF == 0) load_tile(tl, cur, false, true);
         if (tl + 1 < n_tiles) load_tile(tl + 1, nxt, true, HALF == 1);
         // register v of a "[row][hidden]" accumulator: row 8 (v / 4) + 4 h + v % 4 of the tile
@@ -671,12 +677,17 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
 #pragma unroll
             for (int t = 0; t < RS; ++t) du2 = mfma32(cur.rb[t], wb[t], du2);
             f32x16 hh;
+            // (one wave writes and reads its own part: the wave's LDS instructions complete in order)
+            float *my = stl[wave];
+            my[h * 32 + x] = cur.st[0];
+            my[(2 + h) * 32 + x] = cur.st[1];
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int g4 = 0; g4 < 4; ++g4) {
-                const f32x4 mu = *(const f32x4 *)&ST[0 * sg.rows + r0 + 8 * g4 + 4 * h];
-                const f32x4 iv = *(const f32x4 *)&ST[1 * sg.rows + r0 + 8 * g4 + 4 * h];
-                const f32x4 m1 = *(const f32x4 *)&ST[2 * sg.rows + r0 + 8 * g4 + 4 * h];
-                const f32x4 m2 = *(const f32x4 *)&ST[3 * sg.rows + r0 + 8 * g4 + 4 * h];
+                const f32x4 mu = *(const f32x4 *)&my[0 * 32 + 8 * g4 + 4 * h];
+                const f32x4 iv = *(const f32x4 *)&my[1 * 32 + 8 * g4 + 4 * h];
+                const f32x4 m1 = *(const f32x4 *)&my[2 * 32 + 8 * g4 + 4 * h];
+                const f32x4 m2 = *(const f32x4 *)&my[3 * 32 + 8 * g4 + 4 * h];
 #pragma unroll
                 for (int j2 = 0; j2 < 4; ++j2) {
                     const int v = 4 * g4 + j2;
@@ -732,6 +743,8 @@ __global__ __launch_bounds__(kWg, 2) void k_learned_bwd_params(LbStage sg, const
             for (int s = 0; s < KS; ++s) cur.ra[s] = nxt.ra[s];
 #pragma unroll
             for (int t = 0; t < RS; ++t) cur.rb[t] = nxt.rb[t];
+            cur.st[0] = nxt.st[0];
+            cur.st[1] = nxt.st[1];
         } else {
             cur = nxt;
         }
