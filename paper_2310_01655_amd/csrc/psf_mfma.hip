@@ -1361,7 +1361,7 @@ constexpr int out_lds_bytes()
     constexpr int KD = LS ? R : D, TOK_WAVE = 32 * TT, TOK_WG = 4 * TOK_WAVE;
     constexpr int KV = TOK_WAVE * KD * 2 + TOK_WAVE * D * 2;
     constexpr int ZA = 16384 / (R * D);
-    constexpr int CROSS = 2 * (ZA * R * D * 2 + ZA * TOK_WG * 4);
+    constexpr int CROSS = 2 * (ZA * R * D * 2) + 16 * TOK_WG * 2;
     constexpr int INB = kKeyTilesInFlight * KV;
     return PART == 1 ? INB : (PART == 2 ? CROSS : (CROSS > INB ? CROSS : INB));
 }
@@ -1390,7 +1390,7 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
     constexpr int ZA = 16384 / (R * D);                   // sketch rows a per staged Z chunk
     constexpr int Z_PER_A = R * D;                        // bf16 elements of Z for one a
     constexpr int Z_CHUNK_BYTES = ZA * Z_PER_A * 2;       // 32 KB
-    constexpr int MQ_CHUNK_BYTES = ZA * TOK_WG * 4;       // m_i[a] of the chunk, fp32 [ZA][TOK_WG]
+    constexpr int MQ_STEP_BYTES = 16 * TOK_WG * 2;        // m_i[a] of one 16-wide step of a, bf16 [16][TOK_WG]
     static_assert(K_BYTES % (16 * kWg) == 0 && V_BYTES % (16 * kWg) == 0, "whole copies");
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -1651,14 +1651,17 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
         const bf16_t *zsrc = Zg + ((size_t)u * (t - 1) + (NONCAUSAL ? 0 : l - 1)) * R * R * D;
         const uint32_t stage0 = lds_address(stage);
         constexpr int NCHUNK = R / ZA;
-        constexpr int BUF_BYTES = Z_CHUNK_BYTES + MQ_CHUNK_BYTES;
-        // m_i[a] of the chunk as fp32 [ZA][TOK_WG]: each thread converts MQ_PER consecutive a of
-        // MQ_TOKS tokens; loaded early into registers, written to LDS after the chunk's MFMAs
-        constexpr int MQ_TOKS = TOK_WG > kWg ? TOK_WG / kWg : 1;
-        constexpr int MQ_PER = ZA * TOK_WG / kWg / MQ_TOKS;
-        typedef __bf16 mqvec __attribute__((ext_vector_type(MQ_PER)));
-        const int mq_tok = tid % TOK_WG, mq_grp = tid / TOK_WG;
-        mqvec mqv[MQ_TOKS];
+        constexpr int BUF_BYTES = Z_CHUNK_BYTES;
+        static_assert(PART == 1 || 2 * BUF_BYTES + MQ_STEP_BYTES <= out_lds_bytes<R, D, TT, LS, PART>(), "stage size");
+        // m_i[a] for the 16 sketch rows a of one 16-wide step, bf16 [16][TOK_WG] behind the two Z
+        // buffers, written from the fp32 copies of the B operands when the chunks reach the step:
+        // lane (x, h) holds entries a % 16 = 8 h + e of its tokens.  Every wave writes and reads
+        // only its own tokens, in program order: no barrier is involved.  (A second read of
+        // m(Q) from memory, 8 bytes of every row per chunk, cost an L1 access per lane and chunk:
+        // a tenth of this kernel's time.)
+        constexpr int PER = 16 / ZA;                         // chunks per step
+        static_assert(16 % ZA == 0, "whole chunks per step");
+        uint16_t *mq_step = (uint16_t *)(stage + 2 * BUF_BYTES);
         // Z is stored with the symmetry weights baked in (see k_state): for sketch row a only
         // b' >= 16 * (a / 16) contributes, i.e. 16-wide steps s >= s0 = a / 16 and octets >= 2 s0.
         // All rows of a chunk share s0.
@@ -1677,18 +1680,16 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
             dma16_sbase(zsrc + (size_t)chunk * ZA * Z_PER_A + (size_t)off * 8, (uint32_t)lane * 16,
                         stage0 + buf * BUF_BYTES + off * 16);
         };
-        auto load_mq = [&](int chunk) {
+        auto store_mq = [&](auto s_tag) {
+            constexpr int S = decltype(s_tag)::value;
+            if constexpr (S < RS) {
 #pragma unroll
-            for (int k = 0; k < MQ_TOKS; ++k)
-                mqv[k] = *(const mqvec *)&MQ[(urow + i0 + mq_tok + k * kWg) * R + chunk * ZA + mq_grp * MQ_PER];
-        };
-        auto store_mq = [&](int buf) {
-            float *dst = (float *)(stage + buf * BUF_BYTES + Z_CHUNK_BYTES);      // [ZA][TOK_WG]
+                for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-            for (int k = 0; k < MQ_TOKS; ++k)
-#pragma unroll
-                for (int e = 0; e < MQ_PER; ++e)
-                    dst[(mq_grp * MQ_PER + e) * TOK_WG + mq_tok + k * kWg] = (float)mqv[k][e];
+                    for (int e = 0; e < 8; ++e)
+                        mq_step[(8 * h + e) * TOK_WG + wave * TOK_WAVE + 32 * tt + x] =
+                            (uint16_t)(__float_as_uint(mb[tt][S][e]) >> 16);      // exact: mb holds bf16 values
+            }
         };
         auto gen = [&](float ma, const f32x8 &mbv) {
             f32x8 pr;
@@ -1697,7 +1698,6 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
             return cvt8(pr);
         };
         for (int k = 0; k < z_ncopy(0); ++k) stage_z_k(0, 0, k);
-        load_mq(0);
         // denominator: m_i^T S m_i with S = prefix of m_j m_j^T, hi + lo operands
         {
             const size_t sbase = ((size_t)u * (t - 1) + (NONCAUSAL ? 0 : l - 1)) * R * R;
@@ -1740,18 +1740,16 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
             }
         }
 
-        store_mq(0);
+        store_mq(std::integral_constant<int, 0>{});
         wait_all_memory();
         __syncthreads();
-#pragma unroll 1
-        for (int chunk = 0; chunk < NCHUNK; ++chunk) {
+        auto chunk_iter = [&](auto s0_tag, int chunk) {
             const int buf = chunk & 1;
             // the next chunk's copies are issued a few per row a inside the loop below: issued
             // back to back they stall this wave on the memory pipeline's queue
             const int n_copies = chunk + 1 < NCHUNK ? z_ncopy(chunk + 1) : 0;
-            if (chunk + 1 < NCHUNK) load_mq(chunk + 1);
             const bf16_t *zc = (const bf16_t *)(stage + buf * BUF_BYTES);
-            const float *mqs = (const float *)(stage + buf * BUF_BYTES + Z_CHUNK_BYTES);
+            const uint16_t *mqs = mq_step + (chunk % PER) * ZA * TOK_WG;
             auto run_chunk = [&](auto s0_tag) {
                 constexpr int S0 = decltype(s0_tag)::value;  // first 16-wide step with b' >= a
                 constexpr int NS = RS - S0;
@@ -1766,7 +1764,8 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
                             zf[ai & 1][ct][s] = *(const bf16x8 *)&za[((2 * s + h) * D + 32 * ct + x) * 8];
 #pragma unroll
                     for (int tt = 0; tt < TT; ++tt)
-                        ma[ai & 1][tt] = mqs[ai * TOK_WG + wave * TOK_WAVE + 32 * tt + x];
+                        ma[ai & 1][tt] =
+                            __uint_as_float((uint32_t)mqs[ai * TOK_WG + wave * TOK_WAVE + 32 * tt + x] << 16);
                 };
                 load_a(0);
                 bf16x8 frag = gen(ma[0][0], mb[0][S0]);
@@ -1795,17 +1794,20 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
                     }
                 }
             };
-            static_assert(RS <= 4, "step variants");
-            switch (chunk * ZA / 16) {
-            case 0: run_chunk(std::integral_constant<int, 0>{}); break;
-            case 1: run_chunk(std::integral_constant<int, RS >= 2 ? 1 : 0>{}); break;
-            case 2: run_chunk(std::integral_constant<int, RS >= 3 ? 2 : 0>{}); break;
-            default: run_chunk(std::integral_constant<int, RS >= 4 ? 3 : 0>{}); break;
-            }
-            if (chunk + 1 < NCHUNK) store_mq(buf ^ 1);
+            run_chunk(s0_tag);
             wait_all_memory();
             __syncthreads();
-        }
+        };
+        // one loop per step (the chunks come in the order of their first step s0), each with a
+        // single body, so that the accumulators are carried by simple loops; between two of them
+        // the next step's m_i[a] go to the table
+        static_assert(NCHUNK == RS * PER, "chunks per step");
+        static_for<RS>([&](auto s0_tag) {
+            constexpr int S0 = decltype(s0_tag)::value;
+#pragma unroll 1
+            for (int chunk = S0 * PER; chunk < (S0 + 1) * PER; ++chunk) chunk_iter(s0_tag, chunk);
+            store_mq(std::integral_constant<int, S0 + 1>{});
+        });
     }
 
     if constexpr (PART == 2) {
