@@ -27,8 +27,8 @@ HBM_PEAK_GBS = 8000.0
 # runs summarised in profiles/ (scaled by the copy calibration described there).  bench.py
 # cannot collect counters itself; workloads without a committed counter run report null.
 MEASURED_TRAFFIC_BYTES = {
-    ("config3", "output"): 0.707e9,                 # k_out, cross-block part: 606 MB read + 101 MB written
-    ("config3", "block_states_scan"): 1.562e9,      # k_state_and_in_block: 998 MB read + 564 MB written
+    ("config3", "output"): 0.802e9,                 # k_out, cross-block part: 631 MB read + 171 MB written
+    ("config3", "block_states_scan"): 1.529e9,      # k_state_and_in_block: 965 MB read + 564 MB written
 }
 
 
