@@ -1439,14 +1439,21 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
             for (int s = 0; s < KS; ++s)
                 qfr[tt][s] = *(const bf16x8 *)&Q[(urow + tok_w0 + 32 * tt + x) * KD + 16 * s + 8 * h];
 
-        // K tile in LDS as [D/8][KEYT keys][8] (A fragments are then contiguous 16-byte reads),
-        // V tile as [KEYT/8 octets][D][8], both filled by direct global->LDS copies.
+        // K tile in LDS row by row as in memory, [KEYT keys][KD/8 pieces of 8], so that a copy
+        // instruction reads whole rows (a lane per 16-byte piece: 16 cache lines per instruction;
+        // one key row per lane would be 64), with the pieces of key j stored at piece ^ swz(j): the
+        // A fragments of 8 consecutive keys then fall into different banks.  V tile as
+        // [KEYT/8 octets][D][8].  Both filled by direct global->LDS copies.
+        constexpr int P8 = KD / 8;                               // 16-byte pieces per key row
+        static_assert(P8 == 4 || P8 == 8 || P8 == 16, "swizzle");
+        auto swz = [](int key) { return P8 >= 8 ? (key & 7) : ((key >> 1) & 3); };
         const int ntiles_wg = (i0 + TOK_WG - jb) / KEYT;         // tiles staged by the workgroup
         const int ntiles_w = (tok_w0 + TOK_WAVE - jb) / KEYT;    // tiles this wave has keys in
         // (copies: wave-uniform base address in scalar registers + a fixed per-lane offset)
-        static_assert(kWg % KEYT == 0, "key index of a copy slot");
+        static_assert(kWg % P8 == 0 && (kWg / P8) % 8 == 0, "key index of a copy slot");
         const uint32_t stage0 = lds_address(stage);
-        const uint32_t k_lane = (uint32_t)(((tid % KEYT) * KD + 8 * (tid / KEYT)) * 2);
+        // copy slot q * kWg + tid = (key q * kWg / P8 + tid / P8, piece tid % P8)
+        const uint32_t k_lane = (uint32_t)(((tid / P8) * KD + 8 * ((tid % P8) ^ swz(tid / P8))) * 2);
         const uint32_t v_lane = (uint32_t)tid * 16;
         auto stage_kv = [&](int kt) {
             const int ktc = min(kt, ntiles_wg - 1);              // clamped: keeps the copy count uniform
@@ -1454,8 +1461,8 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
             const size_t j0 = urow + jb + (size_t)ktc * KEYT;
             const bf16_t *ksrc = K + j0 * KD, *vsrc = V8 + j0 * D;
 #pragma unroll
-            for (int q = 0; q < K_BYTES / 16 / kWg; ++q)          // copy slot q * kWg + tid = (d-octet, key)
-                dma16_sbase(ksrc + q * 8 * (kWg / KEYT), k_lane, dst + q * 4096);
+            for (int q = 0; q < K_BYTES / 16 / kWg; ++q)
+                dma16_sbase(ksrc + q * (kWg / P8) * KD, k_lane, dst + q * 4096);
 #pragma unroll
             for (int q = 0; q < V_BYTES / 16 / kWg; ++q)
                 dma16_sbase(vsrc + q * kWg * 8, v_lane, dst + K_BYTES + q * 4096);
@@ -1481,7 +1488,7 @@ __device__ __forceinline__ void out_workgroup(const bf16_t *__restrict__ Q, cons
             if (jtt == 0) {
 #pragma unroll
                 for (int s = 0; s < KS; ++s)
-                    kfr[s] = *(const bf16x8 *)&ks[((2 * s + h) * KEYT + 32 * jsub + x) * 8];
+                    kfr[s] = *(const bf16x8 *)&ks[(32 * jsub + x) * KD + 8 * ((2 * s + h) ^ swz(x))];
             }
             f32x16 acc = {0};
 #pragma unroll
