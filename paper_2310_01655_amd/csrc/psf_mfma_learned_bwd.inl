@@ -24,8 +24,10 @@
 //                         chain df -> da2 -> du1 -> dx with the hidden units walked in chunks of 32
 //                         (pre-activations recomputed per chunk); writes dX = bf16(direct term + dx),
 //                         the sums for dg1 / db1 per workgroup, and, for the parameter kernel, the
-//                         r-wide vectors of every row (x^, a2, df, da2 as bf16 rows and as
-//                         [tile of 32 rows][feature][32] tiles, mean / 1/sigma of h1, m1, m2).
+//                         r-wide vectors of every row (x^, a2, df, da2 as bf16, once as row
+//                         operands and once as transposed operands of the parameter kernel's
+//                         MFMAs, both in the order its lanes load them: see LbStage; mean and
+//                         1/sigma of h1, m1, m2).
 //   k_learned_bwd_params  workgroup = 4 waves = 4 hidden chunks of one network for a slice of the rows
 //                         of one unit, lane = hidden unit: recomputes a1 (or a3) of its 32 hidden units
 //                         with the operand roles swapped ("[row][hidden]" accumulators), forms h1, h^,
